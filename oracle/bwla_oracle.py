@@ -1,0 +1,247 @@
+"""CPU oracle of the BWLA W1A6 quantized linear-layer forward.
+
+THIS IS TEST INFRASTRUCTURE, NOT THE PRODUCT.  It is a plain, slow, fp64 / exact-integer
+NumPy implementation of what the HIP path computes.  Only the tests, the smoke check and
+the benchmark's CPU-baseline leg may import it.  It shares no code with the HIP library and
+imports nothing from the GPU package.
+
+The method approximates Y = X W^T (it quantizes), so this oracle is the algorithm taken
+step by step, not the dense product:
+
+  1. rotate       X~ = X (R1 (x) R2)                       (paper Sec. 3.1, "OKT"; App. A.2.2,
+                                                            "Matrix Formulation and Kronecker Structure")
+  2. quantize     per-token symmetric INT6 of X~            (paper Sec. 4.1 "Implementation Details" names
+                                                            per-token activation quantization; the symmetric
+                                                            6-bit form [-31, 31] is this build's reading)
+  3. binary GEMM  acc = q . Sign(W)^T  (exact integers)     (paper Sec. 3 "Discussion", Eq. 2-3)
+  4. PSP branch   L = (X U) V^T                             (paper Sec. 3.2 "PSP": W_res = W - M, M = A B)
+  5. dequantize   Y = s_t * alpha_n * acc + L               (paper Sec. 3 "Discussion", Eq. 4; App. A.2.4)
+
+Pins (tests/test_oracle_pins.py, no GPU): every function below is checked against something
+other than itself -- the dense Kronecker product, norm preservation and forward invariance,
+hand-derived worked values, the closed-form optimal scale and its residual, brute-force loops,
+and the exact end-to-end case.  The accuracy of the approximation itself (Y against the
+unquantized X W^T on synthetic data) is *parity unpinned*: the paper only reports it through
+perplexities of pretrained models.
+"""
+from __future__ import annotations
+
+import math
+
+import numpy as np
+
+QMAX = 31  # symmetric INT6: codes in [-31, 31]; -32 is never produced
+
+
+# --------------------------------------------------------------------------- Alg. 1
+def kron_factor(n: int) -> tuple[int, int]:
+    """Kronecker dimension factorization (paper App. A.1, Algorithm 1).
+
+    Start at floor(sqrt(n)) and walk down to the closest divisor; that divisor is n2 and
+    n1 = n / n2, so n1 >= n2.  A prime n gives (n, 1).
+    """
+    if n < 1:
+        raise ValueError("n must be >= 1")
+    a = math.isqrt(n)
+    while a > 1 and n % a != 0:
+        a -= 1
+    n2 = a
+    n1 = n // n2
+    return n1, n2
+
+
+# --------------------------------------------------------------------------- step 1
+def kron_rotate(X: np.ndarray, R1: np.ndarray, R2: np.ndarray) -> np.ndarray:
+    """X (M, K) times the Kronecker product R1 (x) R2, in fp64, without forming it.
+
+    With the standard Kronecker product, (R1 (x) R2)[a*n2+b, c*n2+d] = R1[a,c] * R2[b,d].
+    Reshaping a token row-major to V (n1, n2), the product is R1^T V R2 reshaped back
+    (paper Sec. 3.1 OKT and App. A.2.2 write the same object with a column-major vec).
+    """
+    X = np.asarray(X, dtype=np.float64)
+    R1 = np.asarray(R1, dtype=np.float64)
+    R2 = np.asarray(R2, dtype=np.float64)
+    n1, n2 = R1.shape[0], R2.shape[0]
+    M, K = X.shape
+    if R1.shape != (n1, n1) or R2.shape != (n2, n2) or n1 * n2 != K:
+        raise ValueError("factor shapes do not match K")
+    V = X.reshape(M, n1, n2)
+    Z = np.matmul(V, R2)                 # Z[t,a,d] = sum_b V[t,a,b] R2[b,d]
+    Y = np.matmul(R1.T, Z)               # Y[t,c,d] = sum_a R1[a,c] Z[t,a,d]
+    return Y.reshape(M, K)
+
+
+def kron_dense(R1: np.ndarray, R2: np.ndarray) -> np.ndarray:
+    """The dense K x K rotation, entry by entry from the definition (small K only)."""
+    R1 = np.asarray(R1, dtype=np.float64)
+    R2 = np.asarray(R2, dtype=np.float64)
+    n1, n2 = R1.shape[0], R2.shape[0]
+    Q = np.empty((n1 * n2, n1 * n2), dtype=np.float64)
+    for a in range(n1):
+        for b in range(n2):
+            for c in range(n1):
+                Q[a * n2 + b, c * n2: (c + 1) * n2] = R1[a, c] * R2[b, :]
+    return Q
+
+
+# --------------------------------------------------------------------------- step 2
+def quantize_int6(Xr: np.ndarray):
+    """Per-token symmetric INT6 (this build's reading of paper Sec. 4.1).
+
+    amax_t = max_k |X~[t,k]|;  v = 31 X~ / amax_t;  q = clip(rint(v), -31, 31) with ties to
+    even;  s_t = amax_t / 31.  A token that is all zero gets q = 0 and s = 0.
+    Returns (q int8 (M,K), s fp64 (M,), v fp64 (M,K)); v is the pre-rounding value the parity
+    test needs for its rounding-boundary mask.
+    """
+    Xr = np.asarray(Xr, dtype=np.float64)
+    amax = np.max(np.abs(Xr), axis=1)
+    safe = np.where(amax > 0, amax, 1.0)
+    v = Xr * (QMAX / safe)[:, None]
+    v[amax == 0] = 0.0
+    q = np.clip(np.rint(v), -QMAX, QMAX).astype(np.int8)
+    s = amax / QMAX
+    return q, s, v
+
+
+# --------------------------------------------------------------------------- step 3 (offline part)
+def binarize_rows(W: np.ndarray):
+    """Row-wise binarization without shift (paper Sec. 3 Eq. 2-3; App. A.2.4).
+
+    Sign(x) = +1 for x > 0 and -1 for x <= 0 (Eq. 3).  The per-output-channel scale is the
+    mean magnitude of the row, the minimizer of sum_j (w_j - alpha sign(w_j))^2 (App. A.2.4).
+    Returns (sgn int8 (N,K) in {-1,+1}, alpha fp64 (N,)).
+    """
+    W = np.asarray(W, dtype=np.float64)
+    sgn = np.where(W > 0, 1, -1).astype(np.int8)
+    alpha = np.mean(np.abs(W), axis=1)
+    return sgn, alpha
+
+
+def to_fp16(a: np.ndarray) -> np.ndarray:
+    """Round to the fp16 storage grid (nearest even) and return as fp64."""
+    return np.asarray(a, dtype=np.float64).astype(np.float16).astype(np.float64)
+
+
+# --------------------------------------------------------------------------- step 3 (online part)
+def binary_gemm(q: np.ndarray, sgn: np.ndarray) -> np.ndarray:
+    """acc[t,n] = sum_k q[t,k] * sgn[n,k], exact.
+
+    |acc| <= 31 K is far below 2^53, so the fp64 matrix product of the integer-valued
+    operands is exact in any summation order; it is returned as int64.
+    """
+    q = np.asarray(q)
+    sgn = np.asarray(sgn)
+    acc = np.matmul(q.astype(np.float64), sgn.astype(np.float64).T)
+    return np.rint(acc).astype(np.int64)
+
+
+def binary_gemm_loops(q, sgn):
+    """The same contraction as a literal triple loop over Python ints (tiny sizes only)."""
+    M, K = len(q), len(q[0])
+    N = len(sgn)
+    out = [[0] * N for _ in range(M)]
+    for t in range(M):
+        for n in range(N):
+            a = 0
+            for k in range(K):
+                a += int(q[t][k]) * int(sgn[n][k])
+            out[t][n] = a
+    return np.array(out, dtype=np.int64)
+
+
+# --------------------------------------------------------------------------- step 4
+def psp_project(X: np.ndarray, U: np.ndarray) -> np.ndarray:
+    """T = X U (M, r): the low-rank branch reads the original, un-rotated, un-quantized input
+    (paper Sec. 3.2: the residual M = A B lives in the un-rotated coordinates)."""
+    return np.asarray(X, dtype=np.float64) @ np.asarray(U, dtype=np.float64)
+
+
+# --------------------------------------------------------------------------- step 5
+def dequant_output(acc, s, alpha, T=None, V=None) -> np.ndarray:
+    """Y[t,n] = s_t * alpha_n * acc[t,n] + sum_j T[t,j] V[n,j]   (paper Eq. 4 without shift;
+    Sec. 3.2 for the added low-rank term)."""
+    Y = np.asarray(s, dtype=np.float64)[:, None] * np.asarray(alpha, dtype=np.float64)[None, :] \
+        * np.asarray(acc, dtype=np.float64)
+    if T is not None and V is not None and np.asarray(T).shape[1] > 0:
+        Y = Y + np.asarray(T, dtype=np.float64) @ np.asarray(V, dtype=np.float64).T
+    return Y
+
+
+# --------------------------------------------------------------------------- whole path
+def forward(X, R1, R2, W_rot, U=None, V=None) -> dict:
+    """The whole hot path on stored parameter values.
+
+    X      (M,K)  activations as stored (already on the bf16 or fp32 grid)
+    R1,R2  fp32 orthogonal factors
+    W_rot  (N,K)  the weight matrix in rotated (and PSP-corrected) coordinates, fp32
+    U (K,r), V (N,r): PSP factors on the fp16 grid, or None / r = 0
+    The scale alpha is rounded to fp16 because that is how the layer stores it.
+    """
+    Xr = kron_rotate(X, R1, R2)
+    q, s, v = quantize_int6(Xr)
+    sgn, alpha = binarize_rows(W_rot)
+    alpha16 = to_fp16(alpha)
+    acc = binary_gemm(q, sgn)
+    if U is not None and np.asarray(U).size > 0:
+        T = psp_project(X, U)
+    else:
+        T = np.zeros((np.asarray(X).shape[0], 0))
+        V = np.zeros((np.asarray(W_rot).shape[0], 0))
+    Y = dequant_output(acc, s, alpha16, T, V)
+    return dict(Xr=Xr, q=q, s=s, v=v, sgn=sgn, alpha=alpha, alpha16=alpha16,
+                acc=acc, T=T, Y=Y, qsum=q.astype(np.int64).sum(axis=1))
+
+
+def forward_rows(X, R1, R2, sgn, alpha16, U, V, rows) -> dict:
+    """The path for a subset of token rows (tokens are independent: per-token scale,
+    row-wise products).  Used where the full M would take minutes on the CPU."""
+    Xs = np.asarray(X)[rows]
+    Xr = kron_rotate(Xs, R1, R2)
+    q, s, v = quantize_int6(Xr)
+    acc = binary_gemm(q, sgn)
+    if U is not None and np.asarray(U).size > 0:
+        T = psp_project(Xs, U)
+    else:
+        T = np.zeros((Xs.shape[0], 0))
+        V = np.zeros((np.asarray(sgn).shape[0], 0))
+    Y = dequant_output(acc, s, alpha16, T, V)
+    return dict(Xr=Xr, q=q, s=s, v=v, acc=acc, T=T, Y=Y,
+                qsum=q.astype(np.int64).sum(axis=1))
+
+
+def forward_loops(X, R1, R2, W_rot, U, V) -> np.ndarray:
+    """Everything as scalar Python loops on the dense definition (tiny sizes only):
+    dense Kronecker matrix, per-token max, round-half-even, sign, mean magnitude, sums."""
+    X = [[float(x) for x in row] for row in np.asarray(X, dtype=np.float64)]
+    Q = kron_dense(R1, R2).tolist()
+    W = np.asarray(W_rot, dtype=np.float64).tolist()
+    U = np.asarray(U, dtype=np.float64).tolist() if U is not None else []
+    V = np.asarray(V, dtype=np.float64).tolist() if V is not None else []
+    M, K, N = len(X), len(X[0]), len(W)
+    r = len(U[0]) if U else 0
+    Y = np.zeros((M, N))
+    for t in range(M):
+        xr = [math.fsum(X[t][i] * Q[i][k] for i in range(K)) for k in range(K)]
+        amax = max(abs(z) for z in xr)
+        qs = [0] * K
+        if amax > 0:
+            for k in range(K):
+                c = round(31.0 * xr[k] / amax)       # Python's round is half-to-even
+                qs[k] = max(-31, min(31, c))
+        st = amax / 31.0
+        Tt = [math.fsum(X[t][k] * U[k][j] for k in range(K)) for j in range(r)]
+        for n in range(N):
+            alpha = float(np.float16(math.fsum(abs(w) for w in W[n]) / K))
+            acc = 0
+            for k in range(K):
+                acc += qs[k] if W[n][k] > 0 else -qs[k]
+            low = math.fsum(Tt[j] * V[n][j] for j in range(r))
+            Y[t, n] = st * alpha * acc + low
+    return Y
+
+
+# --------------------------------------------------------------------------- accounting
+def effective_weight_bits(N: int, K: int, n1: int, n2: int, r: int) -> float:
+    """Stored bits per weight of one packed layer: 1 sign bit, fp16 scale per row, fp16 PSP
+    factors U (K,r) and V (N,r), fp32 Kronecker factors (paper Table 1 reports 1.15-1.19)."""
+    return 1.0 + (16.0 * (r * (K + N) + N) + 32.0 * (n1 * n1 + n2 * n2)) / (N * K)

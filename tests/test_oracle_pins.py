@@ -1,0 +1,322 @@
+"""Pins of the CPU oracle against what the paper and the mathematics fix (no GPU).
+
+Each test names the passage it rests on.  None of them re-types the oracle's own formula:
+they use the dense Kronecker product, invariants, hand-derived values, closed forms,
+brute force, and exact special cases.
+"""
+import math
+import os
+
+import numpy as np
+import pytest
+
+from oracle import bwla_oracle as orc
+from paper_2605_00422_amd import inputs as syn
+
+GOLDEN = os.path.join(os.path.dirname(__file__), "golden")
+
+
+def _read_golden(name):
+    rows = {}
+    with open(os.path.join(GOLDEN, name)) as f:
+        for line in f:
+            line = line.strip()
+            if not line or line.startswith("#"):
+                continue
+            parts = line.split()
+            rows[parts[0]] = [float(p) for p in parts[1:]]
+    return rows
+
+
+def _orth(rng, n):
+    return syn.random_orthogonal(rng, n)
+
+
+# ------------------------------------------------------------------ Alg. 1 (paper App. A.1)
+def test_kron_factor_hand_pairs():
+    with open(os.path.join(GOLDEN, "kron_pairs.txt")) as f:
+        for line in f:
+            if line.startswith("#") or not line.strip():
+                continue
+            n, n1, n2 = (int(v) for v in line.split())
+            assert orc.kron_factor(n) == (n1, n2), n
+
+
+def test_kron_factor_properties_bruteforce():
+    for n in range(1, 600):
+        n1, n2 = orc.kron_factor(n)
+        assert n1 * n2 == n and n2 <= n1
+        # n2 is the largest divisor not above sqrt(n)
+        best = max(d for d in range(1, n + 1) if n % d == 0 and d * d <= n)
+        assert n2 == best
+
+
+# ------------------------------------------------------------------ rotation (paper Sec. 3.1; App. A.2.2)
+def test_kron_orthogonal_fp32():
+    """R1 (x) R2 is orthogonal: max |Q^T Q - I| < 1e-5 with fp32 factors."""
+    rng = np.random.default_rng(1)
+    R1, R2 = _orth(rng, 16), _orth(rng, 32)
+    Q = np.kron(R1, R2).astype(np.float32)
+    assert np.max(np.abs(Q.T @ Q - np.eye(512, dtype=np.float32))) < 1e-5
+    # factor-wise for a large K (the dense matrix is never formed there)
+    R1, R2 = _orth(rng, 160), _orth(rng, 160)
+    for R in (R1, R2):
+        assert np.max(np.abs(R.T @ R - np.eye(R.shape[0], dtype=np.float32))) < 1e-5
+
+
+@pytest.mark.parametrize("n1,n2", [(16, 32), (32, 16), (8, 10), (3, 5), (1, 7), (7, 1)])
+def test_rotation_equals_dense_kronecker(n1, n2):
+    """The two-small-products form equals X @ kron(R1, R2) (library Kronecker product);
+    non-square and n1 != n2 cases catch a swapped factor order or a transposed factor."""
+    rng = np.random.default_rng(2)
+    R1, R2 = _orth(rng, n1), _orth(rng, n2)
+    X = rng.standard_normal((5, n1 * n2))
+    ref = X @ np.kron(R1.astype(np.float64), R2.astype(np.float64))
+    got = orc.kron_rotate(X, R1, R2)
+    assert np.max(np.abs(got - ref)) < 1e-12
+    # and the entry-by-entry dense construction agrees with the library one
+    assert np.max(np.abs(orc.kron_dense(R1, R2) - np.kron(R1.astype(np.float64), R2.astype(np.float64)))) == 0.0
+
+
+def test_rotation_not_symmetric_in_factors():
+    """Guard for the guard: with n1 != n2 the swapped order really differs."""
+    rng = np.random.default_rng(3)
+    R1, R2 = _orth(rng, 4), _orth(rng, 6)
+    X = rng.standard_normal((2, 24))
+    a = X @ np.kron(R1, R2)
+    b = X @ np.kron(R2, R1)
+    assert np.max(np.abs(a - b)) > 1e-3
+
+
+def test_rotation_preserves_norm_and_forward_invariance():
+    """Orthogonality: ||x R|| = ||x||, and (X R)(W R)^T = X W^T (paper Sec. 1 and 3.1:
+    R^-1 = R^T keeps the forward pass unchanged).  Using R^T instead of R on one side
+    breaks the second identity."""
+    rng = np.random.default_rng(4)
+    n1, n2 = 12, 20
+    R1, R2 = _orth(rng, n1), _orth(rng, n2)
+    X = rng.standard_t(3.0, size=(7, n1 * n2))
+    W = rng.standard_normal((9, n1 * n2))
+    Xr = orc.kron_rotate(X, R1, R2)
+    Wr = orc.kron_rotate(W, R1, R2)
+    assert np.allclose(np.linalg.norm(Xr, axis=1), np.linalg.norm(X, axis=1), rtol=1e-6)
+    assert np.max(np.abs(Xr @ Wr.T - X @ W.T)) < 1e-4 * np.max(np.abs(X @ W.T))
+    # fp32 factors are orthogonal only to ~1e-7, hence the relative bound above; with the
+    # wrong direction the mismatch is of order one
+    Wbad = orc.kron_rotate(W, R1.T, R2.T)
+    assert np.max(np.abs(Xr @ Wbad.T - X @ W.T)) > 1e-2 * np.max(np.abs(X @ W.T))
+
+
+def test_rotation_identity_factors():
+    rng = np.random.default_rng(5)
+    X = rng.standard_normal((3, 48))
+    assert np.array_equal(orc.kron_rotate(X, np.eye(6), np.eye(8)), X)
+
+
+# ------------------------------------------------------------------ quantizer (symmetric INT6)
+def test_quantizer_range_and_max_maps_to_31():
+    rng = np.random.default_rng(6)
+    Xr = rng.standard_t(3.0, size=(64, 512))
+    q, s, v = orc.quantize_int6(Xr)
+    assert q.dtype == np.int8 and q.min() >= -31 and q.max() <= 31
+    for t in range(Xr.shape[0]):
+        k = int(np.argmax(np.abs(Xr[t])))
+        assert abs(int(q[t, k])) == 31 and np.sign(q[t, k]) == np.sign(Xr[t, k])
+        assert np.max(np.abs(q[t])) == 31
+    # reconstruction error is at most half a step everywhere
+    assert np.max(np.abs(q * s[:, None] - Xr) / s[:, None]) <= 0.5 + 1e-12
+
+
+def test_quantizer_integer_input_is_reproduced():
+    """Integer-valued X~ with amax 31 gives q = X~ and s = 1 exactly."""
+    rng = np.random.default_rng(7)
+    Xr = rng.integers(-31, 32, size=(8, 96)).astype(np.float64)
+    Xr[:, 0] = 31.0
+    q, s, _ = orc.quantize_int6(Xr)
+    assert np.array_equal(q.astype(np.float64), Xr) and np.all(s == 1.0)
+
+
+def test_quantizer_ties_to_even_zero_token_and_scale_equivariance():
+    # amax = 31 so v = x: ties at .5 go to the even neighbour
+    Xr = np.array([[31.0, 0.5, 1.5, 2.5, -0.5, -1.5, -2.5, 30.5]])
+    q, s, v = orc.quantize_int6(Xr)
+    assert q.tolist() == [[31, 0, 2, 2, 0, -2, -2, 30]]
+    q0, s0, v0 = orc.quantize_int6(np.zeros((2, 8)))
+    assert not q0.any() and not s0.any() and not v0.any()
+    # scaling a token by a power of two changes s, not q
+    rng = np.random.default_rng(8)
+    A = rng.standard_normal((4, 64))
+    qa, sa, _ = orc.quantize_int6(A)
+    qb, sb, _ = orc.quantize_int6(A * 8.0)
+    assert np.array_equal(qa, qb) and np.allclose(sb, 8.0 * sa, rtol=0, atol=0)
+    # negation flips the codes
+    qc, _, _ = orc.quantize_int6(-A)
+    assert np.array_equal(qc, -qa)
+
+
+# ------------------------------------------------------------------ binarization (paper Eq. 1-4; App. A.2.4)
+def test_sign_convention_zero_is_minus_one():
+    sgn, alpha = orc.binarize_rows(np.array([[0.0, 1e-30, -1e-30, 2.0]]))
+    assert sgn.tolist() == [[-1, 1, -1, 1]]
+
+
+def test_alpha_is_the_least_squares_scale_with_variance_residual():
+    """alpha* = mean |w| minimizes sum (w - alpha sign(w))^2 and the minimum is
+    K Var(|w|) (paper App. A.2.4)."""
+    rng = np.random.default_rng(9)
+    W = rng.standard_normal((6, 200)) * 0.02
+    sgn, alpha = orc.binarize_rows(W)
+    for i in range(W.shape[0]):
+        err = lambda a: float(np.sum((W[i] - a * sgn[i]) ** 2))
+        e0 = err(alpha[i])
+        assert e0 <= err(alpha[i] * 1.001) and e0 <= err(alpha[i] * 0.999)
+        grid = np.linspace(0, 0.1, 2001)
+        assert abs(grid[np.argmin([err(a) for a in grid])] - alpha[i]) <= 1e-4
+        assert math.isclose(e0, W.shape[1] * np.var(np.abs(W[i])), rel_tol=1e-10)
+
+
+def test_two_point_rows_are_recovered_exactly():
+    """A row with values in {+c, -c} is reproduced exactly by sign * alpha (App. A.2.4)."""
+    rng = np.random.default_rng(10)
+    c = np.array([0.5, 0.03125, 2.0])
+    S = np.where(rng.random((3, 64)) > 0.5, 1.0, -1.0)
+    W = S * c[:, None]
+    sgn, alpha = orc.binarize_rows(W)
+    assert np.array_equal(sgn * alpha[:, None], W)
+
+
+def test_binarized_layer_bruteforce_tiny():
+    """Brute force: y[n] = sum_k x[k] * (w[n,k] > 0 ? +alpha_n : -alpha_n) by scalar loops."""
+    rng = np.random.default_rng(11)
+    W = rng.standard_normal((5, 12))
+    q = rng.integers(-31, 32, size=(3, 12)).astype(np.int8)
+    sgn, alpha = orc.binarize_rows(W)
+    acc = orc.binary_gemm(q, sgn)
+    for t in range(3):
+        for n in range(5):
+            a = sum(abs(W[n, k]) for k in range(12)) / 12
+            ref = sum(int(q[t, k]) * (a if W[n, k] > 0 else -a) for k in range(12))
+            assert math.isclose(alpha[n] * acc[t, n], ref, rel_tol=1e-12, abs_tol=1e-12)
+
+
+# ------------------------------------------------------------------ integer GEMM
+def test_binary_gemm_matches_triple_loop_and_bound():
+    rng = np.random.default_rng(12)
+    q = rng.integers(-31, 32, size=(16, 512)).astype(np.int8)
+    sgn = np.where(rng.random((40, 512)) > 0.5, 1, -1).astype(np.int8)
+    a = orc.binary_gemm(q, sgn)
+    b = orc.binary_gemm_loops(q.tolist(), sgn.tolist())
+    assert a.dtype == np.int64 and np.array_equal(a, b)
+    assert np.max(np.abs(a)) <= 31 * 512
+    # extreme: all codes 31, all signs +1 reaches the bound exactly
+    assert orc.binary_gemm(np.full((1, 64), 31, np.int8), np.ones((1, 64), np.int8))[0, 0] == 31 * 64
+
+
+# ------------------------------------------------------------------ PSP branch (paper Sec. 3.2)
+def test_low_rank_split_is_function_preserving():
+    """x (W - V U^T)^T + (x U) V^T = x W^T: adding the branch restores the layer."""
+    rng = np.random.default_rng(13)
+    X = rng.standard_normal((4, 30))
+    W = rng.standard_normal((7, 30))
+    U = rng.standard_normal((30, 3))
+    V = rng.standard_normal((7, 3))
+    T = orc.psp_project(X, U)
+    lhs = X @ (W - V @ U.T).T + orc.dequant_output(np.zeros((4, 7)), np.ones(4), np.ones(7), T, V)
+    assert np.max(np.abs(lhs - X @ W.T)) < 1e-12
+    assert T.shape == (4, 3)
+    # a transposed or swapped factor cannot satisfy this with these shapes (7 != 30 != 3)
+
+
+# ------------------------------------------------------------------ end to end
+def test_hand_example_2x2():
+    g = _read_golden("hand_example_2x2.txt")
+    X = np.array([g["x"]])
+    R1 = np.array(g["R1"]).reshape(2, 2)
+    R2 = np.array(g["R2"]).reshape(2, 2)
+    W = np.array([g["w0"], g["w1"]])
+    out = orc.forward(X, R1, R2, W)
+    assert np.allclose(out["Xr"][0], g["xr"], atol=1e-14)
+    assert out["q"][0].tolist() == [int(v) for v in g["q"]]
+    assert math.isclose(out["s"][0], g["s"][0], rel_tol=1e-15)
+    assert out["sgn"].tolist() == [[int(v) for v in g["sgn0"]], [int(v) for v in g["sgn1"]]]
+    assert out["alpha"].tolist() == g["alpha"]
+    assert out["acc"][0].tolist() == [int(v) for v in g["acc"]]
+    assert np.allclose(out["Y"][0], g["y"], rtol=1e-14)
+    assert out["qsum"][0] == sum(int(v) for v in g["q"])
+
+
+def test_exact_case_identity_rotation_rank0():
+    """R = I, r = 0, integer X with amax 31, W in {+c,-c} with c on the fp16 grid:
+    the quantized path equals the plain product X W^T exactly, which is also the plain
+    sign-weight GEMM."""
+    rng = np.random.default_rng(14)
+    n1, n2, N = 4, 8, 10
+    X = rng.integers(-31, 32, size=(6, n1 * n2)).astype(np.float64)
+    X[:, 3] = -31.0
+    c = 2.0 ** rng.integers(-6, 2, size=N)
+    W = np.where(rng.random((N, n1 * n2)) > 0.5, 1.0, -1.0) * c[:, None]
+    out = orc.forward(X, np.eye(n1), np.eye(n2), W)
+    assert np.array_equal(out["Y"], X @ W.T)
+    assert np.array_equal(out["acc"], (X @ np.sign(W).T).astype(np.int64))
+
+
+def test_full_path_equals_scalar_loops_tiny():
+    """The vectorized oracle equals the all-scalar dense-definition loops."""
+    cfg = syn.LayerConfig("t", 3, 24, 4, 6, 5, 2, "f32", 2, 20.0, seed=3)
+    d = syn.make_layer(cfg)
+    out = orc.forward(d.X, d.R1, d.R2, d.W, d.U, d.V)
+    ref = orc.forward_loops(d.X, d.R1, d.R2, d.W, d.U, d.V)
+    assert np.max(np.abs(out["Y"] - ref)) <= 1e-12 * np.max(np.abs(ref))
+
+
+def test_forward_rows_matches_forward():
+    cfg = syn.LayerConfig("t", 9, 64, 8, 8, 12, 4, "bf16", 2, 20.0, seed=5)
+    d = syn.make_layer(cfg)
+    full = orc.forward(d.X, d.R1, d.R2, d.W, d.U, d.V)
+    rows = np.array([0, 4, 8])
+    sub = orc.forward_rows(d.X, d.R1, d.R2, full["sgn"], full["alpha16"], d.U, d.V, rows)
+    assert np.array_equal(sub["q"], full["q"][rows])
+    assert np.array_equal(sub["acc"], full["acc"][rows])
+    assert np.array_equal(sub["Y"], full["Y"][rows])
+
+
+def test_quantized_path_tracks_the_unquantized_layer():
+    """Sanity of the approximation (not a pin of its accuracy): with R = identity the output
+    correlates strongly with x (sign(W) alpha)^T."""
+    cfg = syn.LayerConfig("t", 8, 512, 16, 32, 64, 8, "f32", 0, 1.0, seed=7)
+    d = syn.make_layer(cfg)
+    out = orc.forward(d.X, d.R1, d.R2, d.W, d.U, d.V)
+    Xr = orc.kron_rotate(d.X, d.R1, d.R2)
+    ref = Xr @ (out["sgn"] * out["alpha16"][:, None]).T + (d.X.astype(np.float64) @ d.U) @ d.V.T
+    rel = np.linalg.norm(out["Y"] - ref) / np.linalg.norm(ref)
+    assert rel < 0.05
+
+
+# ------------------------------------------------------------------ storage accounting (paper Table 1)
+def test_effective_bits_in_paper_band():
+    lo, hi = (float(v) for v in open(os.path.join(GOLDEN, "effective_bits.txt")).read().split("\n")[-2].split())
+    b = orc.effective_weight_bits(11008, 4096, 64, 64, 32)
+    assert lo <= b <= hi
+    # independent count of the same storage in bytes
+    bytes_ = 11008 * 4096 / 8 + 2 * 11008 + 2 * 32 * (4096 + 11008) + 4 * 2 * 64 * 64
+    assert math.isclose(b, 8 * bytes_ / (11008 * 4096), rel_tol=1e-12)
+
+
+# ------------------------------------------------------------------ input generator (storage grids only)
+def test_inputs_are_on_their_storage_grids():
+    import torch
+    d = syn.make_layer(syn.CONFIGS["cfg0_tiny"])
+    assert d.X.dtype == np.float32 and d.X.shape == (16, 512)
+    cfg = syn.LayerConfig("t", 4, 64, 8, 8, 16, 4, "bf16", 2, 20.0, seed=1)
+    e = syn.make_layer(cfg)
+    xt = torch.from_numpy(e.X)
+    assert torch.equal(xt.to(torch.bfloat16).to(torch.float32), xt)
+    raw = np.random.default_rng(0).standard_normal(1000).astype(np.float32)
+    assert torch.equal(torch.from_numpy(syn.round_to_bf16(raw)),
+                       torch.from_numpy(raw).to(torch.bfloat16).to(torch.float32))
+    assert np.array_equal(e.U.astype(np.float16).astype(np.float32), e.U)
+    assert np.array_equal(e.V.astype(np.float16).astype(np.float32), e.V)
+    # seeded: same config twice gives the same tensors
+    f = syn.make_layer(cfg)
+    assert np.array_equal(e.X, f.X) and np.array_equal(e.W, f.W)
+    assert len(e.outlier_idx) == 2
