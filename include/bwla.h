@@ -1,0 +1,159 @@
+/*
+ * bwla.h -- C ABI of the MI355X (gfx950) W1A6 quantized linear forward of BWLA.
+ *
+ * The layer computes, for activations X (M tokens x K features) and a layer quantized
+ * offline by the paper's method,
+ *
+ *     Y = dequant( INT6( X (R1 (x) R2) ) . Sign(W_rot)^T ) + (X U) V^T
+ *
+ * i.e. the Orthogonal-Kronecker rotation applied online to the activations (paper Sec. 3.1
+ * "Orthogonal-Kronecker Transformation"), per-token low-bit activation quantization (Sec. 4.1
+ * "Implementation Details"; here symmetric INT6, codes in [-31, 31]), the product with the
+ * binarized weights and their per-output-channel scales (Sec. 3 "Discussion", Eq. 1-4, without
+ * the shift), and the rank-r Proximal-SVD-Projection branch added back (Sec. 3.2: the binarized
+ * matrix is W - M with M = A B; here V = A (N x r) and U = B^T (K x r)).
+ *
+ * Conventions for every call
+ *   - All `d_*` pointers are DEVICE pointers on the current HIP device, owned by the caller,
+ *     at least 16-byte aligned.  The library never allocates or frees device memory and keeps
+ *     no global state.
+ *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).  Calls enqueue
+ *     work and return; they do not synchronize.
+ *   - Return value is a bwla_status_t.  Arguments are validated on the host before anything is
+ *     enqueued; a failed check enqueues nothing.  A failed launch returns BWLA_ERR_HIP.
+ *   - Matrices are dense row-major.
+ */
+#ifndef BWLA_H
+#define BWLA_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    BWLA_OK = 0,
+    BWLA_ERR_NULL = 1,         /* a required pointer is NULL */
+    BWLA_ERR_SHAPE = 2,        /* inconsistent or non-positive dimensions */
+    BWLA_ERR_ALIGN = 3,        /* a device pointer is not 16-byte aligned */
+    BWLA_ERR_BUFSIZE = 4,      /* a caller buffer is too small */
+    BWLA_ERR_UNSUPPORTED = 5,  /* valid but outside what the kernels cover */
+    BWLA_ERR_HIP = 6           /* the HIP runtime reported an error */
+} bwla_status_t;
+
+typedef enum {
+    BWLA_X_F32 = 0,            /* activations are float */
+    BWLA_X_BF16 = 1            /* activations are bfloat16 (raw uint16 storage) */
+} bwla_xdtype_t;
+
+/* Limits of the kernels (checked; violations give BWLA_ERR_UNSUPPORTED). */
+#define BWLA_MAX_RANK 128      /* PSP rank r */
+#define BWLA_MAX_K 32768       /* in-features; also requires K % 32 == 0 */
+#define BWLA_MAX_FACTOR 256    /* n1, n2 */
+
+/*
+ * Descriptor of one packed layer: plain data, may be copied freely.  Filled by
+ * bwla_pack_weights; offsets are byte offsets into the caller-owned device blob.
+ * Layout of the blob (each section 256-byte aligned):
+ *   bits   sign bits of W_rot, tiled for the kernels (see bwla_unpack_signs for the
+ *          interchange view); 16-row tiles x 512-column chunks, 1 KiB each
+ *   alpha  N fp16, alpha_n = mean_k |W_rot[n,k]|            (paper App. A.2.4)
+ *   V      N x r fp16 row-major
+ *   U      K x r fp16 row-major
+ *   R1     n1 x n1 fp32 row-major;  R2  n2 x n2 fp32 row-major
+ */
+typedef struct bwla_layer {
+    int64_t N, K;
+    int32_t n1, n2, r, reserved;
+    uint64_t off_bits, off_alpha, off_V, off_U, off_R1, off_R2;
+    uint64_t blob_bytes;
+    const void* d_blob;
+} bwla_layer_t;
+
+const char* bwla_status_string(int status);
+
+/* Library ABI version (integer, bumped on incompatible change). */
+int bwla_version(void);
+
+/*
+ * Kronecker dimension factorization, paper App. A.1 Algorithm 1: n2 is the largest divisor of
+ * K not above sqrt(K), n1 = K / n2 (so n1 >= n2).  Host only.
+ */
+bwla_status_t bwla_kron_factor(int64_t K, int32_t* n1, int32_t* n2);
+
+/* Size in bytes of the packed blob for a layer of this shape.  Host only. */
+bwla_status_t bwla_packed_size(int64_t N, int64_t K, int32_t n1, int32_t n2, int32_t r,
+                               size_t* bytes);
+
+/*
+ * Pack one layer (offline step; paper Algorithm 2, "Final binarization", restricted to sign
+ * and scale: bit = (W_rot[n,k] > 0), so Sign(0) = -1 as in Eq. 3; alpha_n = mean_k |W_rot[n,k]|
+ * accumulated in fp64 and rounded once to fp16).
+ *   d_W_rot  N x K fp32, the weight in rotated, PSP-corrected coordinates
+ *   d_R1, d_R2  fp32 orthogonal factors, n1 x n1 and n2 x n2, n1 * n2 == K
+ *   d_U  K x r fp32, d_V  N x r fp32 (values are rounded to fp16); both may be NULL iff r == 0
+ *   d_blob   output, blob_bytes >= bwla_packed_size(...)
+ *   out      host descriptor to fill
+ * Runs as kernels on `stream`; the inputs may be released once the stream has drained.
+ */
+bwla_status_t bwla_pack_weights(const float* d_W_rot, const float* d_R1, const float* d_R2,
+                                const float* d_U, const float* d_V,
+                                int64_t N, int64_t K, int32_t n1, int32_t n2, int32_t r,
+                                void* d_blob, size_t blob_bytes, void* stream,
+                                bwla_layer_t* out);
+
+/*
+ * Inspection helper: expand the packed sign bits to the interchange view, an N x K int8
+ * matrix of +1 / -1 (bit 1 <-> +1), and copy alpha as fp32.  d_alpha may be NULL.
+ */
+bwla_status_t bwla_unpack_signs(const bwla_layer_t* layer, int8_t* d_sgn, float* d_alpha,
+                                void* stream);
+
+/*
+ * Bytes of scratch bwla_rotate_quant wants for M tokens (split-K partial sums of X U and
+ * their arrival counters).  Returns 0 bytes when no split is used (r == 0 or M large).
+ * The scratch must be zero-filled once when it is allocated; every call leaves it zeroed
+ * again.  Two calls that overlap in time must not share one scratch buffer.
+ */
+bwla_status_t bwla_psp_workspace_size(const bwla_layer_t* layer, int64_t M, size_t* bytes);
+
+/*
+ * Steps 1, 2 and the first half of 4 of the forward:
+ *   X~ = X (R1 (x) R2) evaluated as R1^T V R2 on each token reshaped row-major to n1 x n2
+ *        (paper Sec. 3.1; App. A.2.2), fp32 accumulation;
+ *   amax_t = max_k |X~[t,k]|, scale_t = amax_t / 31, q = clamp(rint(X~ * 31 / amax_t), -31, 31)
+ *        with ties to even; an all-zero token gives q = 0 and scale 0;
+ *   qsum_t = sum_k q[t,k];
+ *   T = X U (M x r, fp32 accumulation, from the un-rotated un-quantized X; Sec. 3.2).
+ *   d_X      M x K, float or bf16 according to xdtype
+ *   d_q      out, M x K int8;  d_scale out, M fp32;  d_qsum out, M int32
+ *   d_T      out, M x r fp32 (NULL iff r == 0)
+ *   d_ws     scratch of ws_bytes >= bwla_psp_workspace_size(layer, M) (NULL allowed when that is 0)
+ */
+bwla_status_t bwla_rotate_quant(const bwla_layer_t* layer, const void* d_X, int xdtype, int64_t M,
+                                int8_t* d_q, float* d_scale, int32_t* d_qsum, float* d_T,
+                                void* d_ws, size_t ws_bytes, void* stream);
+
+/* qsum_t = sum_k q[t,k] for codes that did not come from bwla_rotate_quant. */
+bwla_status_t bwla_code_sums(const int8_t* d_q, int64_t M, int64_t K, int32_t* d_qsum, void* stream);
+
+/*
+ * Steps 3, 4 (second half) and 5:
+ *   acc[t,n] = sum_k q[t,k] * Sign(W_rot[n,k])   exact int32 on INT8 MFMA.  The sign bits are
+ *              expanded in registers to 0/1-valued int8 digits b, and the +-1 product is
+ *              recovered exactly as 2 * sum_k q b - qsum_t;
+ *   Y[t,n]   = scale_t * alpha_n * acc[t,n] + sum_j T[t,j] V[n,j]      (paper Eq. 4; Sec. 3.2)
+ *   d_q, d_scale, d_qsum, d_T  as produced by bwla_rotate_quant (d_T NULL iff r == 0)
+ *   d_Y      out, M x N fp32
+ *   d_acc    optional out, M x N int32 raw accumulators (NULL to skip)
+ */
+bwla_status_t bwla_linear_forward(const bwla_layer_t* layer, const int8_t* d_q, const float* d_scale,
+                                  const int32_t* d_qsum, const float* d_T, int64_t M,
+                                  float* d_Y, int32_t* d_acc, void* stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* BWLA_H */

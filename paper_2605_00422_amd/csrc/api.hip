@@ -1,0 +1,191 @@
+// C ABI of libbwla: argument validation on the host, then kernel launches on the caller's
+// stream.  Nothing here allocates device memory or synchronizes.
+#include <math.h>
+
+#include "bwla_internal.h"
+
+size_t bwla_rotate_lds_bytes(int n1, int n2);
+int bwla_rotate_tiles(int n1, int n2);
+int bwla_rotate_max_tiles();
+size_t bwla_gemm_decode_lds(int64_t M, int64_t K);
+
+namespace {
+
+constexpr size_t LDS_LIMIT = 160 * 1024;          // per-workgroup LDS on gfx950
+constexpr size_t DECODE_LDS_LIMIT = 128 * 1024;   // code tile of the decode kernel
+
+inline bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+bwla_status_t check_shape(int64_t N, int64_t K, int32_t n1, int32_t n2, int32_t r) {
+    if (N <= 0 || K <= 0 || n1 <= 0 || n2 <= 0 || r < 0) return BWLA_ERR_SHAPE;
+    if ((int64_t)n1 * (int64_t)n2 != K) return BWLA_ERR_SHAPE;
+    if (K % 32 != 0 || K > BWLA_MAX_K || r > BWLA_MAX_RANK) return BWLA_ERR_UNSUPPORTED;
+    if (n1 > BWLA_MAX_FACTOR || n2 > BWLA_MAX_FACTOR) return BWLA_ERR_UNSUPPORTED;
+    if (N > (int64_t)1 << 24) return BWLA_ERR_UNSUPPORTED;
+    if (bwla_rotate_tiles(n1, n2) > bwla_rotate_max_tiles()) return BWLA_ERR_UNSUPPORTED;
+    if (bwla_rotate_lds_bytes(n1, n2) > LDS_LIMIT) return BWLA_ERR_UNSUPPORTED;
+    return BWLA_OK;
+}
+
+void fill_layout(bwla_layer_t* L, int64_t N, int64_t K, int32_t n1, int32_t n2, int32_t r) {
+    const uint64_t rp = (uint64_t)((r + 15) & ~15);
+    uint64_t off = 0;
+    L->N = N; L->K = K; L->n1 = n1; L->n2 = n2; L->r = r; L->reserved = 0;
+    L->off_bits = off;  off = bwla_align256(off + (uint64_t)bwla_row_tiles(N) * bwla_chunks(K) * BWLA_UNIT_BYTES);
+    L->off_alpha = off; off = bwla_align256(off + (uint64_t)N * 2);
+    L->off_V = off;     off = bwla_align256(off + (uint64_t)N * rp * 2);
+    L->off_U = off;     off = bwla_align256(off + (uint64_t)K * rp * 2);
+    L->off_R1 = off;    off = bwla_align256(off + (uint64_t)n1 * n1 * 4);
+    L->off_R2 = off;    off = bwla_align256(off + (uint64_t)n2 * n2 * 4);
+    L->blob_bytes = off;
+}
+
+bwla_status_t check_layer(const bwla_layer_t* L) {
+    if (!L) return BWLA_ERR_NULL;
+    if (!L->d_blob) return BWLA_ERR_NULL;
+    bwla_status_t s = check_shape(L->N, L->K, L->n1, L->n2, L->r);
+    if (s != BWLA_OK) return s;
+    bwla_layer_t ref;
+    fill_layout(&ref, L->N, L->K, L->n1, L->n2, L->r);
+    if (ref.off_bits != L->off_bits || ref.off_alpha != L->off_alpha || ref.off_V != L->off_V ||
+        ref.off_U != L->off_U || ref.off_R1 != L->off_R1 || ref.off_R2 != L->off_R2 ||
+        ref.blob_bytes != L->blob_bytes)
+        return BWLA_ERR_SHAPE;
+    if (!aligned16(L->d_blob)) return BWLA_ERR_ALIGN;
+    return BWLA_OK;
+}
+
+size_t psp_ws_bytes(const bwla_psp_plan& p, int r) {
+    if (r <= 0 || p.splits <= 1) return 0;
+    const uint64_t rp = (uint64_t)((r + 15) & ~15);
+    return (size_t)(bwla_align256((uint64_t)p.token_tiles * sizeof(int)) +
+                    (uint64_t)p.token_tiles * p.splits * 16 * rp * sizeof(float));
+}
+
+}  // namespace
+
+extern "C" {
+
+const char* bwla_status_string(int status) {
+    switch (status) {
+        case BWLA_OK: return "ok";
+        case BWLA_ERR_NULL: return "null pointer";
+        case BWLA_ERR_SHAPE: return "inconsistent shape";
+        case BWLA_ERR_ALIGN: return "pointer not 16-byte aligned";
+        case BWLA_ERR_BUFSIZE: return "buffer too small";
+        case BWLA_ERR_UNSUPPORTED: return "shape outside the supported range";
+        case BWLA_ERR_HIP: return "HIP runtime error";
+        default: return "unknown status";
+    }
+}
+
+int bwla_version(void) { return 1; }
+
+bwla_status_t bwla_kron_factor(int64_t K, int32_t* n1, int32_t* n2) {
+    if (!n1 || !n2) return BWLA_ERR_NULL;
+    if (K < 1) return BWLA_ERR_SHAPE;
+    int64_t a = (int64_t)floor(sqrt((double)K));
+    while (a * a > K) --a;                 // guard the floating-point square root
+    while ((a + 1) * (a + 1) <= K) ++a;
+    while (a > 1 && K % a != 0) --a;
+    if (K / a > INT32_MAX) return BWLA_ERR_UNSUPPORTED;
+    *n2 = (int32_t)a;
+    *n1 = (int32_t)(K / a);
+    return BWLA_OK;
+}
+
+bwla_status_t bwla_packed_size(int64_t N, int64_t K, int32_t n1, int32_t n2, int32_t r, size_t* bytes) {
+    if (!bytes) return BWLA_ERR_NULL;
+    bwla_status_t s = check_shape(N, K, n1, n2, r);
+    if (s != BWLA_OK) return s;
+    bwla_layer_t L;
+    fill_layout(&L, N, K, n1, n2, r);
+    *bytes = (size_t)L.blob_bytes;
+    return BWLA_OK;
+}
+
+bwla_status_t bwla_pack_weights(const float* d_W_rot, const float* d_R1, const float* d_R2,
+                                const float* d_U, const float* d_V, int64_t N, int64_t K, int32_t n1,
+                                int32_t n2, int32_t r, void* d_blob, size_t blob_bytes, void* stream,
+                                bwla_layer_t* out) {
+    if (!d_W_rot || !d_R1 || !d_R2 || !d_blob || !out) return BWLA_ERR_NULL;
+    bwla_status_t s = check_shape(N, K, n1, n2, r);
+    if (s != BWLA_OK) return s;
+    if (r > 0 && (!d_U || !d_V)) return BWLA_ERR_NULL;
+    if (!aligned16(d_W_rot) || !aligned16(d_blob) || !aligned16(d_R1) || !aligned16(d_R2)) return BWLA_ERR_ALIGN;
+    bwla_layer_t L;
+    fill_layout(&L, N, K, n1, n2, r);
+    if (blob_bytes < L.blob_bytes) return BWLA_ERR_BUFSIZE;
+    L.d_blob = d_blob;
+    hipError_t e = bwla_launch_pack(d_W_rot, d_R1, d_R2, d_U, d_V, N, K, n1, n2, r, &L, (hipStream_t)stream);
+    if (e != hipSuccess) return BWLA_ERR_HIP;
+    *out = L;
+    return BWLA_OK;
+}
+
+bwla_status_t bwla_unpack_signs(const bwla_layer_t* layer, int8_t* d_sgn, float* d_alpha, void* stream) {
+    bwla_status_t s = check_layer(layer);
+    if (s != BWLA_OK) return s;
+    if (!d_sgn) return BWLA_ERR_NULL;
+    return bwla_launch_unpack(layer, d_sgn, d_alpha, (hipStream_t)stream) == hipSuccess ? BWLA_OK : BWLA_ERR_HIP;
+}
+
+bwla_status_t bwla_psp_workspace_size(const bwla_layer_t* layer, int64_t M, size_t* bytes) {
+    if (!bytes) return BWLA_ERR_NULL;
+    bwla_status_t s = check_layer(layer);
+    if (s != BWLA_OK) return s;
+    if (M <= 0) return BWLA_ERR_SHAPE;
+    *bytes = psp_ws_bytes(bwla_make_psp_plan(M, layer->K, layer->r), layer->r);
+    return BWLA_OK;
+}
+
+bwla_status_t bwla_rotate_quant(const bwla_layer_t* layer, const void* d_X, int xdtype, int64_t M,
+                                int8_t* d_q, float* d_scale, int32_t* d_qsum, float* d_T, void* d_ws,
+                                size_t ws_bytes, void* stream) {
+    bwla_status_t s = check_layer(layer);
+    if (s != BWLA_OK) return s;
+    if (!d_X || !d_q || !d_scale || !d_qsum) return BWLA_ERR_NULL;
+    if (layer->r > 0 && !d_T) return BWLA_ERR_NULL;
+    if (M <= 0 || M > (int64_t)1 << 24) return BWLA_ERR_SHAPE;
+    if (xdtype != BWLA_X_F32 && xdtype != BWLA_X_BF16) return BWLA_ERR_UNSUPPORTED;
+    if (!aligned16(d_X) || !aligned16(d_q) || (d_T && !aligned16(d_T)) || (d_ws && !aligned16(d_ws)))
+        return BWLA_ERR_ALIGN;
+    const bwla_psp_plan plan = bwla_make_psp_plan(M, layer->K, layer->r);
+    const size_t need = psp_ws_bytes(plan, layer->r);
+    if (need > 0 && (!d_ws || ws_bytes < need)) return d_ws ? BWLA_ERR_BUFSIZE : BWLA_ERR_NULL;
+    hipStream_t st = (hipStream_t)stream;
+    if (layer->r > 0) {
+        if (bwla_launch_psp_project(layer, d_X, xdtype, M, d_T, d_ws, plan, st) != hipSuccess) return BWLA_ERR_HIP;
+    }
+    if (bwla_launch_rotate_quant(layer, d_X, xdtype, M, d_q, d_scale, d_qsum, st) != hipSuccess) return BWLA_ERR_HIP;
+    return BWLA_OK;
+}
+
+bwla_status_t bwla_code_sums(const int8_t* d_q, int64_t M, int64_t K, int32_t* d_qsum, void* stream) {
+    if (!d_q || !d_qsum) return BWLA_ERR_NULL;
+    if (M <= 0 || K <= 0 || M > (int64_t)1 << 24) return BWLA_ERR_SHAPE;
+    if (K % 32 != 0 || K > BWLA_MAX_K) return BWLA_ERR_UNSUPPORTED;
+    if (!aligned16(d_q)) return BWLA_ERR_ALIGN;
+    return bwla_launch_code_sums(d_q, M, K, d_qsum, (hipStream_t)stream) == hipSuccess ? BWLA_OK : BWLA_ERR_HIP;
+}
+
+bwla_status_t bwla_linear_forward(const bwla_layer_t* layer, const int8_t* d_q, const float* d_scale,
+                                  const int32_t* d_qsum, const float* d_T, int64_t M, float* d_Y,
+                                  int32_t* d_acc, void* stream) {
+    bwla_status_t s = check_layer(layer);
+    if (s != BWLA_OK) return s;
+    if (!d_q || !d_scale || !d_qsum || !d_Y) return BWLA_ERR_NULL;
+    if (layer->r > 0 && !d_T) return BWLA_ERR_NULL;
+    if (M <= 0 || M > (int64_t)1 << 24) return BWLA_ERR_SHAPE;
+    if (!aligned16(d_q) || !aligned16(d_Y) || (d_T && !aligned16(d_T)) || (d_acc && !aligned16(d_acc)))
+        return BWLA_ERR_ALIGN;
+    hipStream_t st = (hipStream_t)stream;
+    hipError_t e;
+    if (M <= 16 && bwla_gemm_decode_lds(M, layer->K) <= DECODE_LDS_LIMIT)
+        e = bwla_launch_gemm_decode(layer, d_q, d_scale, d_qsum, d_T, M, d_Y, d_acc, st);
+    else
+        e = bwla_launch_gemm_prefill(layer, d_q, d_scale, d_qsum, d_T, M, d_Y, d_acc, st);
+    return e == hipSuccess ? BWLA_OK : BWLA_ERR_HIP;
+}
+
+}  // extern "C"

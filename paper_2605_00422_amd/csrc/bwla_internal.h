@@ -1,0 +1,74 @@
+// Internal declarations shared by the translation units of libbwla (not installed).
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <hip/hip_fp16.h>
+#include <stdint.h>
+
+#include "bwla.h"
+
+// ---------------------------------------------------------------- packed sign-bit tiling
+// A "unit" is 16 output rows x 512 input columns = 1 KiB = 64 lanes x 16 bytes, exactly one
+// wavefront-wide 128-bit load.  Lane l of a unit holds row (l & 15), column group g = l >> 4
+// (128 columns).  Its four 32-bit words w[0..3] hold
+//     bit (8*b + j) of w[d]  <->  column 512*chunk + 128*g + 16*j + 4*d + b
+// so that, for a fixed j, (w[d] >> j) & 0x01010101 (d = 0..3) is a 16-byte run of 0/1 bytes for
+// 16 consecutive columns: one INT8 MFMA operand, with no cross-lane traffic.
+// Units are stored [row tile][chunk], i.e. a row tile's chunks are contiguous.
+#define BWLA_TILE_ROWS 16
+#define BWLA_CHUNK_COLS 512
+#define BWLA_UNIT_BYTES 1024
+
+static inline int64_t bwla_row_tiles(int64_t N) { return (N + BWLA_TILE_ROWS - 1) / BWLA_TILE_ROWS; }
+static inline int64_t bwla_chunks(int64_t K) { return (K + BWLA_CHUNK_COLS - 1) / BWLA_CHUNK_COLS; }
+static inline uint64_t bwla_align256(uint64_t x) { return (x + 255u) & ~uint64_t(255); }
+
+// PSP projection (T = X U) launch plan: token tiles of 16, S splits of K.
+struct bwla_psp_plan {
+    int token_tiles;
+    int splits;        // S
+    int k_per_split;   // multiple of 64
+};
+bwla_psp_plan bwla_make_psp_plan(int64_t M, int64_t K, int r);
+
+// ---------------------------------------------------------------- launchers (one per .hip file)
+hipError_t bwla_launch_pack(const float* dW, const float* dR1, const float* dR2, const float* dU,
+                            const float* dV, int64_t N, int64_t K, int n1, int n2, int r,
+                            const bwla_layer_t* L, hipStream_t st);
+hipError_t bwla_launch_unpack(const bwla_layer_t* L, int8_t* d_sgn, float* d_alpha, hipStream_t st);
+
+hipError_t bwla_launch_rotate_quant(const bwla_layer_t* L, const void* dX, int xdtype, int64_t M,
+                                    int8_t* dq, float* dscale, int32_t* dqsum, hipStream_t st);
+hipError_t bwla_launch_psp_project(const bwla_layer_t* L, const void* dX, int xdtype, int64_t M,
+                                   float* dT, void* dws, const bwla_psp_plan& plan, hipStream_t st);
+hipError_t bwla_launch_code_sums(const int8_t* dq, int64_t M, int64_t K, int32_t* dqsum, hipStream_t st);
+
+hipError_t bwla_launch_gemm_decode(const bwla_layer_t* L, const int8_t* dq, const float* dscale,
+                                   const int32_t* dqsum, const float* dT, int64_t M, float* dY,
+                                   int32_t* dacc, hipStream_t st);
+hipError_t bwla_launch_gemm_prefill(const bwla_layer_t* L, const int8_t* dq, const float* dscale,
+                                    const int32_t* dqsum, const float* dT, int64_t M, float* dY,
+                                    int32_t* dacc, hipStream_t st);
+
+// ---------------------------------------------------------------- device helpers
+#ifdef __HIPCC__
+typedef int v4i __attribute__((ext_vector_type(4)));
+typedef int v16i __attribute__((ext_vector_type(16)));
+typedef float v4f __attribute__((ext_vector_type(4)));
+typedef float v16f __attribute__((ext_vector_type(16)));
+
+__device__ __forceinline__ float bwla_bf16_to_f32(uint16_t h) {
+    return __uint_as_float(((uint32_t)h) << 16);
+}
+
+__device__ __forceinline__ float bwla_wave_max(float v) {
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) v = fmaxf(v, __shfl_xor(v, off, 64));
+    return v;
+}
+__device__ __forceinline__ int bwla_wave_sum_i32(int v) {
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) v += __shfl_xor(v, off, 64);
+    return v;
+}
+#endif

@@ -1,0 +1,122 @@
+// Offline packing of one layer: sign bits into the tiled layout, per-row scale, fp16 PSP
+// factors, fp32 Kronecker factors.  (Paper Algorithm 2 "Final binarization" restricted to sign
+// and scale; Sign(x) = +1 iff x > 0, paper Eq. 3; alpha = mean |w|, paper App. A.2.4.)
+#include "bwla_internal.h"
+
+namespace {
+
+// One wavefront builds one 1 KiB unit (16 rows x 512 columns).
+__global__ __launch_bounds__(64) void pack_bits_kernel(const float* __restrict__ W, int64_t N, int64_t K,
+                                                       int64_t chunks, uint32_t* __restrict__ bits) {
+    const int64_t unit = blockIdx.x;
+    const int64_t rt = unit / chunks, kc = unit % chunks;
+    const int lane = threadIdx.x;
+    const int i = lane & 15, g = lane >> 4;
+    const int64_t n = rt * BWLA_TILE_ROWS + i;
+    const int64_t kbase = kc * BWLA_CHUNK_COLS + g * 128;
+    uint32_t w[4] = {0u, 0u, 0u, 0u};
+    if (n < N) {
+        const float* row = W + n * K;
+#pragma unroll 4
+        for (int kk = 0; kk < 128; ++kk) {
+            const int64_t k = kbase + kk;
+            const float v = (k < K) ? row[k] : 0.0f;
+            const int j = kk >> 4, d = (kk >> 2) & 3, b = kk & 3;
+            if (v > 0.0f) w[d] |= 1u << (8 * b + j);
+        }
+    }
+    uint4 out = make_uint4(w[0], w[1], w[2], w[3]);
+    reinterpret_cast<uint4*>(bits)[unit * 64 + lane] = out;
+}
+
+// Exact round-to-nearest-even of a non-negative double to IEEE binary16 bits (a double ->
+// float -> half chain can round twice).
+__device__ uint16_t double_to_half_bits(double x) {
+    if (!(x > 0.0)) return 0;
+    if (x >= 65520.0) return 0x7C00;                     // rounds to infinity
+    if (x < 6.103515625e-05) {                           // below 2^-14: subnormal grid 2^-24
+        const double m = rint(ldexp(x, 24));             // 0..1024 (1024 encodes the least normal)
+        return (uint16_t)(int)m;
+    }
+    int e;
+    (void)frexp(x, &e);                                  // x = f * 2^e, f in [0.5, 1)
+    e -= 1;                                              // x = (1.f) * 2^e
+    double m = rint(ldexp(x, 10 - e));                   // in [1024, 2048]
+    if (m >= 2048.0) { m = 1024.0; e += 1; }
+    return (uint16_t)(((e + 15) << 10) | ((int)m - 1024));
+}
+
+// One wavefront per row: fp64 sum of magnitudes, rounded once to fp16.
+__global__ __launch_bounds__(64) void row_scale_kernel(const float* __restrict__ W, int64_t N, int64_t K,
+                                                       uint16_t* __restrict__ alpha) {
+    const int64_t n = blockIdx.x;
+    if (n >= N) return;
+    const float* row = W + n * K;
+    double s = 0.0;
+    for (int64_t k = threadIdx.x; k < K; k += 64) s += (double)fabsf(row[k]);
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) s += __shfl_xor(s, off, 64);
+    if (threadIdx.x == 0) alpha[n] = double_to_half_bits(s / (double)K);
+}
+
+// rows x r fp32 -> rows x rp fp16 (rp = r rounded up to 16, zero padded)
+__global__ void f32_to_f16_rows_kernel(const float* __restrict__ src, int64_t rows, int r, int rp,
+                                       __half* __restrict__ dst) {
+    const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i >= rows * rp) return;
+    const int64_t row = i / rp;
+    const int col = (int)(i - row * rp);
+    dst[i] = col < r ? __float2half_rn(src[row * r + col]) : __float2half_rn(0.0f);
+}
+
+__global__ void copy_f32_kernel(const float* __restrict__ src, int64_t n, float* __restrict__ dst) {
+    const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < n) dst[i] = src[i];
+}
+
+__global__ void unpack_kernel(const uint32_t* __restrict__ bits, const __half* __restrict__ alpha16,
+                              int64_t N, int64_t K, int64_t chunks, int8_t* __restrict__ sgn,
+                              float* __restrict__ alpha) {
+    const int64_t idx = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (idx < N && alpha != nullptr) alpha[idx] = __half2float(alpha16[idx]);
+    if (idx >= N * K) return;
+    const int64_t n = idx / K, k = idx % K;
+    const int64_t rt = n / BWLA_TILE_ROWS, kc = k / BWLA_CHUNK_COLS;
+    const int i = (int)(n % BWLA_TILE_ROWS);
+    const int kk = (int)(k % BWLA_CHUNK_COLS);
+    const int g = kk >> 7, j = (kk >> 4) & 7, d = (kk >> 2) & 3, b = kk & 3;
+    const int lane = g * 16 + i;
+    const uint32_t w = bits[((rt * chunks + kc) * 64 + lane) * 4 + d];
+    sgn[idx] = ((w >> (8 * b + j)) & 1u) ? 1 : -1;
+}
+
+}  // namespace
+
+hipError_t bwla_launch_pack(const float* dW, const float* dR1, const float* dR2, const float* dU,
+                            const float* dV, int64_t N, int64_t K, int n1, int n2, int r,
+                            const bwla_layer_t* L, hipStream_t st) {
+    char* blob = (char*)L->d_blob;
+    const int64_t chunks = bwla_chunks(K), rts = bwla_row_tiles(N);
+    pack_bits_kernel<<<dim3((unsigned)(rts * chunks)), dim3(64), 0, st>>>(
+        dW, N, K, chunks, (uint32_t*)(blob + L->off_bits));
+    row_scale_kernel<<<dim3((unsigned)N), dim3(64), 0, st>>>(dW, N, K, (uint16_t*)(blob + L->off_alpha));
+    if (r > 0) {
+        const int rp = (r + 15) & ~15;
+        const int64_t nv = N * rp, nu = K * rp;
+        f32_to_f16_rows_kernel<<<dim3((unsigned)((nv + 255) / 256)), dim3(256), 0, st>>>(dV, N, r, rp, (__half*)(blob + L->off_V));
+        f32_to_f16_rows_kernel<<<dim3((unsigned)((nu + 255) / 256)), dim3(256), 0, st>>>(dU, K, r, rp, (__half*)(blob + L->off_U));
+    }
+    const int64_t e1 = (int64_t)n1 * n1, e2 = (int64_t)n2 * n2;
+    copy_f32_kernel<<<dim3((unsigned)((e1 + 255) / 256)), dim3(256), 0, st>>>(dR1, e1, (float*)(blob + L->off_R1));
+    copy_f32_kernel<<<dim3((unsigned)((e2 + 255) / 256)), dim3(256), 0, st>>>(dR2, e2, (float*)(blob + L->off_R2));
+    return hipGetLastError();
+}
+
+hipError_t bwla_launch_unpack(const bwla_layer_t* L, int8_t* d_sgn, float* d_alpha, hipStream_t st) {
+    const char* blob = (const char*)L->d_blob;
+    const int64_t total = L->N * L->K;
+    unpack_kernel<<<dim3((unsigned)((total + 255) / 256)), dim3(256), 0, st>>>(
+        (const uint32_t*)(blob + L->off_bits), (const __half*)(blob + L->off_alpha), L->N, L->K,
+        bwla_chunks(L->K), d_sgn, d_alpha);
+    return hipGetLastError();
+}

@@ -1,0 +1,125 @@
+"""Shared helpers of the GPU parity tests: run the HIP path through the C-ABI binding and the
+CPU oracle on the same seeded inputs, and compare by the three criteria:
+
+  1. INT6 codes identical except where the oracle's pre-rounding value lies within 1e-4 of a
+     rounding boundary; there they may differ by one.
+  2. int32 accumulators on identical codes are bit-exact.
+  3. final fp32 output: relative Frobenius error <= 1e-3 and max relative error <= 1e-2
+     (relative to the largest |y| of the same token).
+"""
+from __future__ import annotations
+
+import numpy as np
+import torch
+
+from oracle import bwla_oracle as orc
+from paper_2605_00422_amd import binding as B
+from paper_2605_00422_amd import inputs as syn
+
+DEV = "cuda:0"
+
+
+def to_dev(a, dtype=None):
+    t = torch.from_numpy(np.ascontiguousarray(a)).to(DEV)
+    return t if dtype is None else t.to(dtype)
+
+
+def pack_on_gpu(d: syn.LayerData) -> B.PackedLayer:
+    U = to_dev(d.U) if d.cfg.r > 0 else None
+    V = to_dev(d.V) if d.cfg.r > 0 else None
+    layer = B.pack_weights(to_dev(d.W), to_dev(d.R1), to_dev(d.R2), U, V, d.cfg.n1, d.cfg.n2)
+    torch.cuda.synchronize()
+    return layer
+
+
+def x_on_gpu(d: syn.LayerData):
+    X = to_dev(d.X)
+    return X.to(torch.bfloat16) if d.cfg.x_dtype == "bf16" else X
+
+
+def check_codes(q_gpu: np.ndarray, ref: dict) -> dict:
+    """Criterion 1."""
+    q_ref, v = ref["q"], ref["v"]
+    diff = q_gpu.astype(np.int32) - q_ref.astype(np.int32)
+    near = np.abs(np.abs(v - np.floor(v)) - 0.5) < 1e-4
+    bad_far = np.count_nonzero((diff != 0) & ~near)
+    bad_near = np.count_nonzero(np.abs(diff) > 1)
+    assert bad_far == 0, f"{bad_far} codes differ away from a rounding boundary"
+    assert bad_near == 0, f"{bad_near} codes differ by more than 1"
+    assert q_gpu.min() >= -31 and q_gpu.max() <= 31
+    return dict(mismatch=int(np.count_nonzero(diff)), near=int(np.count_nonzero(near)), total=int(diff.size))
+
+
+def check_output(Y_gpu: np.ndarray, Y_ref: np.ndarray) -> dict:
+    """Criterion 3."""
+    Y_gpu = Y_gpu.astype(np.float64)
+    err = Y_gpu - Y_ref
+    fro = np.linalg.norm(err) / max(np.linalg.norm(Y_ref), 1e-300)
+    denom = np.maximum(np.max(np.abs(Y_ref), axis=1, keepdims=True), 1e-300)
+    mx = float(np.max(np.abs(err) / denom))
+    assert np.all(np.isfinite(Y_gpu))
+    assert fro <= 1e-3, f"relative Frobenius error {fro:.3e}"
+    assert mx <= 1e-2, f"max relative error {mx:.3e}"
+    return dict(fro=float(fro), max_rel=mx)
+
+
+def run_case(cfg: syn.LayerConfig, rows=None) -> dict:
+    """Whole path on the GPU for all M tokens; the oracle on all of them, or on `rows`."""
+    d = syn.make_layer(cfg)
+    sgn, alpha = orc.binarize_rows(d.W)
+    alpha16 = orc.to_fp16(alpha)
+    U = d.U if cfg.r > 0 else None
+    V = d.V if cfg.r > 0 else None
+    sel = np.arange(cfg.M) if rows is None else np.asarray(rows)
+    ref = orc.forward_rows(d.X, d.R1, d.R2, sgn, alpha16, U, V, sel)
+
+    layer = pack_on_gpu(d)
+    # packed weights: interchange view equals the oracle's binarization, bit for bit
+    sgn_gpu, alpha_gpu = B.unpack_signs(layer)
+    assert torch.equal(sgn_gpu.cpu(), torch.from_numpy(sgn)), "sign bits differ"
+    assert np.array_equal(alpha_gpu.cpu().numpy().astype(np.float64), alpha16), "alpha differs"
+    del sgn_gpu
+
+    X = x_on_gpu(d)
+    act = B.Activations(layer, cfg.M)
+    B.rotate_quant(layer, X, act)
+    Y = torch.empty((cfg.M, cfg.N), dtype=torch.float32, device=DEV)
+    acc = torch.empty((cfg.M, cfg.N), dtype=torch.int32, device=DEV)
+    B.linear_forward(layer, act, Y, acc)
+    torch.cuda.synchronize()
+    assert int(torch.count_nonzero(act.ws)) == 0, "scratch not left zeroed"
+
+    sel_t = torch.from_numpy(sel).to(DEV)
+    q_gpu = act.q[sel_t].cpu().numpy()
+    out = dict(cfg=cfg.name)
+    out["codes"] = check_codes(q_gpu, ref)
+    s_gpu = act.scale[sel_t].cpu().numpy().astype(np.float64)
+    assert np.allclose(s_gpu, ref["s"], rtol=2e-6, atol=0), "per-token scales differ"
+    assert np.array_equal(act.qsum[sel_t].cpu().numpy().astype(np.int64), q_gpu.astype(np.int64).sum(axis=1))
+    if cfg.r > 0:
+        T_gpu = act.T[sel_t].cpu().numpy().astype(np.float64)
+        tden = np.maximum(np.max(np.abs(ref["T"]), axis=1, keepdims=True), 1e-30)
+        assert np.max(np.abs(T_gpu - ref["T"]) / tden) < 2e-5, "PSP projection differs"
+    # the GPU's own accumulators are consistent with the GPU's own codes (exact)
+    acc_own = orc.binary_gemm(q_gpu, sgn)
+    assert np.array_equal(acc[sel_t].cpu().numpy().astype(np.int64), acc_own), "int32 accumulators differ"
+
+    # criterion 2: identical codes (the oracle's) in, bit-exact accumulators out
+    act2 = B.Activations(layer, len(sel))
+    act2.q.copy_(torch.from_numpy(ref["q"]))
+    act2.scale.copy_(torch.from_numpy(ref["s"].astype(np.float32)))
+    if cfg.r > 0:
+        act2.T.copy_(torch.from_numpy(ref["T"].astype(np.float32)))
+    B.code_sums(act2.q, act2.qsum)
+    Y2 = torch.empty((len(sel), cfg.N), dtype=torch.float32, device=DEV)
+    acc2 = torch.empty((len(sel), cfg.N), dtype=torch.int32, device=DEV)
+    B.linear_forward(layer, act2, Y2, acc2)
+    torch.cuda.synchronize()
+    assert np.array_equal(act2.qsum.cpu().numpy().astype(np.int64), ref["qsum"])
+    assert np.array_equal(acc2.cpu().numpy().astype(np.int64), ref["acc"]), "criterion 2: accumulators not bit-exact"
+    out["same_codes"] = check_output(Y2.cpu().numpy(), ref["Y"])
+    assert out["same_codes"]["fro"] < 1e-5
+
+    # criterion 3: end to end
+    out["end_to_end"] = check_output(Y[sel_t].cpu().numpy(), ref["Y"])
+    return out

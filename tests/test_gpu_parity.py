@@ -1,0 +1,111 @@
+"""GPU parity of the HIP path against the CPU oracle, through the C ABI (run with -m gpu)."""
+import numpy as np
+import pytest
+
+torch = pytest.importorskip("torch")
+
+from paper_2605_00422_amd import inputs as syn  # noqa: E402
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module", autouse=True)
+def _need_gpu():
+    if not torch.cuda.is_available():
+        pytest.skip("no GPU")
+    from paper_2605_00422_amd import binding as B
+    B.load()   # raises when the HIP library is missing: there is no fallback path
+
+
+def _sample_rows(M, n=64, seed=0):
+    rng = np.random.default_rng(seed)
+    rows = set(rng.choice(M, size=min(n, M), replace=False).tolist()) | {0, M - 1}
+    return np.array(sorted(rows))
+
+
+def test_cfg0_tiny():
+    from parity_util import run_case
+    print(run_case(syn.CONFIGS["cfg0_tiny"]), flush=True)
+
+
+def test_cfg1_decode7b():
+    from parity_util import run_case
+    print(run_case(syn.CONFIGS["cfg1_decode7b"]), flush=True)
+
+
+def test_cfg2_qwen32b_up_m16():
+    from parity_util import run_case
+    print(run_case(syn.CONFIGS["cfg2_qwen32b_up_m16"]), flush=True)
+
+
+def test_cfg3_qwen32b_down_prefill_sampled_rows():
+    """Full M = 2048 on the GPU in the benchmarked launch configuration; the oracle checks 64
+    seeded token rows plus the first and the last (tokens are independent)."""
+    from parity_util import run_case
+    cfg = syn.CONFIGS["cfg3_qwen32b_down_m2048"]
+    print(run_case(cfg, rows=_sample_rows(cfg.M)), flush=True)
+
+
+@pytest.mark.parametrize("M", [1, 64])
+@pytest.mark.parametrize("which", ["k", "o", "down"])
+def test_cfg4_70b_block_small_m(which, M):
+    from parity_util import run_case
+    cfg = {c.name.split("_")[2]: c for c in syn.block70b_configs(M)}[which]
+    print(run_case(cfg), flush=True)
+
+
+def test_cfg4_70b_gate_m4096_sampled_rows():
+    from parity_util import run_case
+    cfg = {c.name.split("_")[2]: c for c in syn.block70b_configs(4096)}["gate"]
+    print(run_case(cfg, rows=_sample_rows(cfg.M, 32)), flush=True)
+
+
+@pytest.mark.parametrize("M,K,n1,n2,N,r,xd", [
+    (1, 96, 12, 8, 40, 0, "f32"),        # rank 0, ragged N, single partly filled chunk
+    (5, 96, 8, 12, 33, 8, "bf16"),       # factors not multiples of 16
+    (16, 1024, 32, 32, 100, 20, "bf16"), # rank not a multiple of 16, N not a multiple of 4... of 16
+    (17, 512, 16, 32, 130, 8, "f32"),    # just past the decode batch: tiled kernel with a ragged tile
+    (33, 640, 20, 32, 257, 64, "bf16"),  # ragged in every dimension
+    (200, 2048, 32, 64, 300, 32, "bf16"),
+    (3, 11008, 128, 86, 64, 16, "bf16"), # 7B down-projection width: n2 = 86, K not a multiple of 512
+])
+def test_ragged_and_degenerate_shapes(M, K, n1, n2, N, r, xd):
+    from parity_util import run_case
+    cfg = syn.LayerConfig(f"edge_{M}_{K}_{N}_{r}", M, K, n1, n2, N, r, xd, max(1, K // 100), 20.0, seed=11)
+    print(run_case(cfg), flush=True)
+
+
+def test_zero_token_gives_zero_codes_and_scale():
+    from parity_util import pack_on_gpu, DEV
+    from paper_2605_00422_amd import binding as B
+    cfg = syn.LayerConfig("zero_tok", 4, 512, 16, 32, 64, 8, "f32", 0, 1.0, seed=2)
+    d = syn.make_layer(cfg)
+    d.X[2] = 0.0
+    layer = pack_on_gpu(d)
+    act = B.Activations(layer, 4)
+    B.rotate_quant(layer, torch.from_numpy(d.X).to(DEV), act)
+    Y = torch.empty((4, 64), dtype=torch.float32, device=DEV)
+    B.linear_forward(layer, act, Y)
+    torch.cuda.synchronize()
+    assert int(act.q[2].abs().max()) == 0 and float(act.scale[2]) == 0.0 and int(act.qsum[2]) == 0
+    assert float(Y[2].abs().max()) == 0.0
+    assert int(act.q[1].abs().max()) == 31
+
+
+def test_repeated_calls_are_deterministic():
+    from parity_util import pack_on_gpu, x_on_gpu, DEV
+    from paper_2605_00422_amd import binding as B
+    cfg = syn.CONFIGS["cfg1_decode7b"]
+    d = syn.make_layer(cfg)
+    layer = pack_on_gpu(d)
+    X = x_on_gpu(d)
+    act = B.Activations(layer, cfg.M)
+    outs = []
+    for _ in range(3):
+        B.rotate_quant(layer, X, act)
+        Y = torch.empty((cfg.M, cfg.N), dtype=torch.float32, device=DEV)
+        B.linear_forward(layer, act, Y)
+        torch.cuda.synchronize()
+        outs.append((Y.clone(), act.T.clone(), act.q.clone()))
+    for o in outs[1:]:
+        assert all(torch.equal(a, b) for a, b in zip(o, outs[0]))

@@ -1,0 +1,117 @@
+"""Host-side checks of the C-ABI library (no GPU): it loads, exports every symbol the header
+declares, and rejects bad arguments before enqueueing anything."""
+import ctypes
+import math
+import os
+import re
+from ctypes import byref, c_int32, c_size_t, c_void_p
+
+import pytest
+
+from paper_2605_00422_amd import binding as B
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+GOLDEN = os.path.join(os.path.dirname(__file__), "golden")
+
+
+@pytest.fixture(scope="module")
+def lib():
+    if not os.path.exists(B.LIB_PATH):
+        from paper_2605_00422_amd.build import build_library
+        build_library()
+    return B.load()
+
+
+def test_exports_match_header(lib):
+    text = open(os.path.join(ROOT, "include", "bwla.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    declared = set(re.findall(r"\b(bwla_[a-z_0-9]+)\s*\(", text))
+    assert declared == set(B.EXPORTS)
+    for name in declared:
+        assert hasattr(lib, name), name
+
+
+def test_status_strings_and_version(lib):
+    assert B.status_string(0) == "ok"
+    seen = {B.status_string(s) for s in range(0, 7)}
+    assert len(seen) == 7 and "unknown status" not in seen
+    assert B.status_string(99) == "unknown status"
+    assert B.version() >= 1
+
+
+def test_kron_factor_matches_hand_pairs(lib):
+    with open(os.path.join(GOLDEN, "kron_pairs.txt")) as f:
+        for line in f:
+            if line.startswith("#") or not line.strip():
+                continue
+            n, n1, n2 = (int(v) for v in line.split())
+            assert B.kron_factor(n) == (n1, n2), n
+    for n in range(1, 400):
+        n1, n2 = B.kron_factor(n)
+        assert n1 * n2 == n and n2 <= n1
+        assert n2 == max(d for d in range(1, n + 1) if n % d == 0 and d * d <= n)
+    a, b = c_int32(), c_int32()
+    assert lib.bwla_kron_factor(0, byref(a), byref(b)) == B.BWLA_ERR_SHAPE
+    assert lib.bwla_kron_factor(16, None, byref(b)) == B.BWLA_ERR_NULL
+
+
+def test_packed_size_accounting(lib):
+    """Blob = 1 bit per weight in 16 x 512 tiles + fp16 alpha + fp16 U, V (rows padded to 16)
+    + fp32 factors; at the 7B-like shape this is ~1.18 bits per weight, inside the band the
+    paper reports (Table 1: 1.15-1.19)."""
+    N, K, n1, n2, r = 11008, 4096, 64, 64, 32
+    size = B.packed_size(N, K, n1, n2, r)
+    exact = N * K // 8 + 2 * N + 2 * r * (N + K) + 4 * (n1 * n1 + n2 * n2)
+    assert exact <= size <= exact + 6 * 256
+    assert 1.15 <= 8 * size / (N * K) <= 1.19
+    # ragged shapes pad rows to 16 and columns to 512
+    size2 = B.packed_size(100, 96, 12, 8, 8)
+    assert size2 >= 7 * 1 * 1024 + 200 + 2 * 16 * (100 + 96) + 4 * (144 + 64)
+
+
+@pytest.mark.parametrize("args,status", [
+    ((0, 512, 16, 32, 8), B.BWLA_ERR_SHAPE),
+    ((512, 512, 16, 16, 8), B.BWLA_ERR_SHAPE),        # n1 * n2 != K
+    ((512, 512, 16, 32, -1), B.BWLA_ERR_SHAPE),
+    ((512, 48, 6, 8, 8), B.BWLA_ERR_UNSUPPORTED),     # K % 32 != 0
+    ((512, 512, 16, 32, 129), B.BWLA_ERR_UNSUPPORTED),
+    ((512, 65536, 256, 256, 8), B.BWLA_ERR_UNSUPPORTED),
+    ((512, 8192, 512, 16, 8), B.BWLA_ERR_UNSUPPORTED),
+])
+def test_shape_validation(lib, args, status):
+    out = c_size_t()
+    assert lib.bwla_packed_size(*args, byref(out)) == status
+
+
+def test_null_and_alignment_checks_happen_before_any_launch(lib):
+    desc = B.BwlaLayer()
+    fake = c_void_p(0x1000)
+    odd = c_void_p(0x1008)
+    # pack: null pointers, misalignment, small buffer
+    assert lib.bwla_pack_weights(None, fake, fake, fake, fake, 512, 512, 16, 32, 8, fake, 1 << 20, None,
+                                 byref(desc)) == B.BWLA_ERR_NULL
+    assert lib.bwla_pack_weights(fake, fake, fake, None, fake, 512, 512, 16, 32, 8, fake, 1 << 20, None,
+                                 byref(desc)) == B.BWLA_ERR_NULL
+    assert lib.bwla_pack_weights(odd, fake, fake, fake, fake, 512, 512, 16, 32, 8, fake, 1 << 20, None,
+                                 byref(desc)) == B.BWLA_ERR_ALIGN
+    assert lib.bwla_pack_weights(fake, fake, fake, fake, fake, 512, 512, 16, 32, 8, fake, 16, None,
+                                 byref(desc)) == B.BWLA_ERR_BUFSIZE
+    assert lib.bwla_pack_weights(fake, fake, fake, fake, fake, 512, 512, 16, 16, 8, fake, 1 << 20, None,
+                                 byref(desc)) == B.BWLA_ERR_SHAPE
+    # forward calls: null layer, zeroed descriptor, inconsistent descriptor
+    assert lib.bwla_rotate_quant(None, fake, 0, 1, fake, fake, fake, fake, None, 0, None) == B.BWLA_ERR_NULL
+    assert lib.bwla_linear_forward(byref(desc), fake, fake, fake, fake, 1, fake, None, None) == B.BWLA_ERR_NULL
+    desc.N, desc.K, desc.n1, desc.n2, desc.r = 512, 512, 16, 32, 8
+    desc.d_blob = 0x1000
+    assert lib.bwla_linear_forward(byref(desc), fake, fake, fake, fake, 1, fake, None, None) == B.BWLA_ERR_SHAPE
+    assert lib.bwla_code_sums(None, 1, 512, fake, None) == B.BWLA_ERR_NULL
+    assert lib.bwla_code_sums(fake, 0, 512, fake, None) == B.BWLA_ERR_SHAPE
+    assert lib.bwla_code_sums(fake, 1, 48, fake, None) == B.BWLA_ERR_UNSUPPORTED
+    out = c_size_t()
+    assert lib.bwla_psp_workspace_size(byref(desc), 1, byref(out)) == B.BWLA_ERR_SHAPE
+
+
+def test_binding_raises_on_error(lib):
+    with pytest.raises(B.BwlaError) as e:
+        B.packed_size(512, 512, 16, 16, 8)
+    assert e.value.status == B.BWLA_ERR_SHAPE
