@@ -1,0 +1,276 @@
+#!/usr/bin/env python3
+"""Benchmark of the W1A6 linear forward (rotate+quantize, then binary GEMM + PSP + dequant).
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload NAME] [--no-extra]
+
+A step is one pass of the whole hot path over one batch of synthetic activations: one
+bwla_rotate_quant call and one bwla_linear_forward call.  Successive steps use different
+packed copies of the layer (enough copies to exceed the 256 MB last-level cache), as the layers
+of a model are all distinct, so the sign bits always stream from HBM.  Prints one JSON line.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import math
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBPS = 8000.0        # MI355X HBM3E
+INT8_PEAK_TOPS = 5000.0       # dense INT8 MFMA
+CACHE_DEFEAT_BYTES = 512 << 20
+
+
+def linear_forward_bytes(cfg) -> int:
+    """Algorithmic HBM bytes of one bwla_linear_forward launch: sign bits, alpha, V (fp16),
+    codes, per-token scale and code sum, T, and the fp32 output."""
+    M, K, N, r = cfg.M, cfg.K, cfg.N, cfg.r
+    return N * K // 8 + 2 * N + 2 * N * r + M * K + 8 * M + 4 * M * r + 4 * M * N
+
+
+def rotate_quant_bytes(cfg) -> int:
+    """Algorithmic bytes of one bwla_rotate_quant call: X, the factors, U (fp16), codes,
+    scale, code sum and T."""
+    xb = 2 if cfg.x_dtype == "bf16" else 4
+    return cfg.M * cfg.K * xb + 4 * (cfg.n1 ** 2 + cfg.n2 ** 2) + 2 * cfg.K * cfg.r + cfg.M * cfg.K \
+        + 8 * cfg.M + 4 * cfg.M * cfg.r
+
+
+def gemm_ops(cfg) -> int:
+    return 2 * cfg.M * cfg.N * cfg.K
+
+
+class Workload:
+    """One layer on the GPU with `copies` packed replicas and preallocated outputs."""
+
+    def __init__(self, cfg, copies=None):
+        import numpy as np
+        import torch
+        from paper_2605_00422_amd import binding as B
+        from paper_2605_00422_amd import inputs as syn
+        self.cfg, self.B, self.torch = cfg, B, torch
+        dev = "cuda:0"
+        d = syn.make_layer(cfg)
+        self.data = d
+        t = lambda a: torch.from_numpy(np.ascontiguousarray(a)).to(dev)
+        U = t(d.U) if cfg.r > 0 else None
+        V = t(d.V) if cfg.r > 0 else None
+        first = B.pack_weights(t(d.W), t(d.R1), t(d.R2), U, V, cfg.n1, cfg.n2)
+        torch.cuda.synchronize()
+        nbytes = first.blob.numel()
+        if copies is None:
+            copies = max(2, min(96, math.ceil(CACHE_DEFEAT_BYTES / nbytes)))
+        self.layers = [first]
+        for _ in range(copies - 1):
+            blob = first.blob.clone()
+            desc = B.BwlaLayer.from_buffer_copy(first.desc)
+            desc.d_blob = blob.data_ptr()
+            self.layers.append(B.PackedLayer(desc, blob))
+        X = t(d.X)
+        self.X = X.to(torch.bfloat16) if cfg.x_dtype == "bf16" else X
+        self.act = B.Activations(first, cfg.M)
+        self.Y = torch.empty((cfg.M, cfg.N), dtype=torch.float32, device=dev)
+        torch.cuda.synchronize()
+
+    def step(self, i):
+        L = self.layers[i % len(self.layers)]
+        self.B.rotate_quant(L, self.X, self.act)
+        self.B.linear_forward(L, self.act, self.Y)
+
+    def only_rotate(self, i):
+        self.B.rotate_quant(self.layers[i % len(self.layers)], self.X, self.act)
+
+    def only_forward(self, i):
+        self.B.linear_forward(self.layers[i % len(self.layers)], self.act, self.Y)
+
+    def time_loop(self, fn, steps, warmup):
+        """Average milliseconds per call of fn over `steps` back-to-back calls, bracketed by
+        events on the stream the kernels are launched on (torch's current stream)."""
+        torch = self.torch
+        for i in range(warmup):
+            fn(i)
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for i in range(steps):
+            fn(warmup + i)
+        e1.record()
+        torch.cuda.synchronize()
+        return e0.elapsed_time(e1) / steps
+
+    def time_graph(self, fn, steps, warmup):
+        """The same K calls captured once into a HIP graph and replayed: per-call milliseconds
+        without host launch overhead (how a decode loop would be deployed)."""
+        torch = self.torch
+        for i in range(max(warmup, 3)):
+            fn(i)
+        torch.cuda.synchronize()
+        g = torch.cuda.CUDAGraph()
+        s = torch.cuda.Stream()
+        with torch.cuda.stream(s):
+            with torch.cuda.graph(g, stream=s):
+                for i in range(steps):
+                    fn(warmup + i)
+        torch.cuda.synchronize()
+        g.replay()
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        g.replay()
+        e1.record()
+        torch.cuda.synchronize()
+        return e0.elapsed_time(e1) / steps
+
+
+def measure(cfg, steps, warmup, use_graph=True):
+    w = Workload(cfg)
+    out = {"workload": cfg.name, "M": cfg.M, "K": cfg.K, "N": cfg.N, "r": cfg.r,
+           "kron": f"{cfg.n1}x{cfg.n2}", "layer_copies": len(w.layers)}
+    ms_step = w.time_loop(w.step, steps, warmup)
+    ms_fwd = w.time_loop(w.only_forward, steps, warmup)
+    ms_rot = w.time_loop(w.only_rotate, steps, warmup)
+    out["stream"] = {"us_per_layer": ms_step * 1e3, "us_linear_forward": ms_fwd * 1e3,
+                     "us_rotate_quant": ms_rot * 1e3}
+    if use_graph:
+        try:
+            gs = w.time_graph(w.step, steps, warmup)
+            gf = w.time_graph(w.only_forward, steps, warmup)
+            gr = w.time_graph(w.only_rotate, steps, warmup)
+            out["graph"] = {"us_per_layer": gs * 1e3, "us_linear_forward": gf * 1e3, "us_rotate_quant": gr * 1e3}
+        except Exception as ex:  # graph capture is an optimisation of the launch path only
+            out["graph"] = {"error": repr(ex)[:200]}
+    return w, out
+
+
+def roofline_for(cfg, us_forward):
+    """Roofline of the dominant kernel (the binary GEMM inside bwla_linear_forward)."""
+    hbm_t = linear_forward_bytes(cfg) / (HBM_PEAK_GBPS * 1e9)
+    mfma_t = gemm_ops(cfg) / (INT8_PEAK_TOPS * 1e12)
+    t = us_forward * 1e-6
+    if hbm_t >= mfma_t:
+        a = linear_forward_bytes(cfg) / t / 1e9
+        return {"bound": "hbm", "achieved": a, "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": a / HBM_PEAK_GBPS,
+                "traffic": None, "kernel": "bwla_linear_forward", "bytes_per_launch": linear_forward_bytes(cfg)}
+    a = gemm_ops(cfg) / t / 1e12
+    return {"bound": "mfma", "achieved": a, "peak": INT8_PEAK_TOPS, "unit": "TOP/s", "frac": a / INT8_PEAK_TOPS,
+            "traffic": None, "kernel": "bwla_linear_forward", "ops_per_launch": gemm_ops(cfg)}
+
+
+def cpu_baseline(w, budget_s=12.0):
+    """The CPU oracle (as it stands) on the same workload: online path only (the binarized
+    matrix is prepared once, like the packed layer on the GPU)."""
+    import numpy as np
+    from oracle import bwla_oracle as orc
+    cfg, d = w.cfg, w.data
+    sgn, alpha = orc.binarize_rows(d.W)
+    alpha16 = orc.to_fp16(alpha)
+    rows_n = cfg.M if cfg.M <= 64 else 64
+    rows = np.arange(rows_n)
+    U = d.U if cfg.r > 0 else None
+    V = d.V if cfg.r > 0 else None
+    orc.forward_rows(d.X, d.R1, d.R2, sgn, alpha16, U, V, rows)       # warm-up
+    n, t0 = 0, time.perf_counter()
+    while True:
+        orc.forward_rows(d.X, d.R1, d.R2, sgn, alpha16, U, V, rows)
+        n += 1
+        el = time.perf_counter() - t0
+        if el > budget_s or n >= 200:
+            break
+    per_call = el / n
+    us_layer = per_call * (cfg.M / rows_n) * 1e6
+    try:
+        from threadpoolctl import threadpool_info
+        cores = max([p.get("num_threads", 1) for p in threadpool_info()] or [1])
+    except Exception:
+        cores = os.cpu_count() or 1
+    sample = (f"{n} repeats of the oracle's online path on {rows_n} of {cfg.M} token rows of {cfg.name}"
+              + ("" if rows_n == cfg.M else f", scaled by {cfg.M}/{rows_n}"))
+    return {"value": us_layer, "unit": "us/layer", "cores": int(cores), "kind": "oracle", "sample": sample,
+            "host_cpus": os.cpu_count()}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=400)
+    ap.add_argument("--warmup", type=int, default=50)
+    ap.add_argument("--workload", default="cfg1_decode7b")
+    ap.add_argument("--no-extra", action="store_true", help="skip the other configurations")
+    ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle baseline")
+    ap.add_argument("--no-graph", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on one GPU only (no sharding or collectives); use --gpus 1",
+              file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    from paper_2605_00422_amd import binding as B
+    from paper_2605_00422_amd import inputs as syn
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        sys.exit(1)
+    B.load()          # raises if the HIP library has not been built: there is no fallback
+
+    all_cfgs = dict(syn.CONFIGS)
+    for M in (1, 64, 4096):
+        for c in syn.block70b_configs(M):
+            all_cfgs[c.name] = c
+    cfg = all_cfgs[args.workload]
+
+    w, res = measure(cfg, args.steps, args.warmup, not args.no_graph)
+    best = res["stream"]
+    mode = "stream"
+    if "graph" in res and "us_per_layer" in res["graph"] and res["graph"]["us_per_layer"] < best["us_per_layer"]:
+        best, mode = res["graph"], "graph"
+    us_layer = best["us_per_layer"]
+    us_fwd = best["us_linear_forward"]
+    roof = roofline_for(cfg, us_fwd)
+    line = {
+        "metric": "us/layer, W1A6 linear forward (rotate+quant, binary GEMM + PSP + dequant)",
+        "value": us_layer, "unit": "us/layer", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": us_layer / 1e3, "higher_is_better": False, "scaling": "weak", "vs_baseline": None,
+        "dtype": "int8 codes x 1-bit weights -> int32 (INT8 MFMA); fp32 rotation and epilogue",
+        "data": "synthetic",
+        "config": {"workload": cfg.name, "M": cfg.M, "K": cfg.K, "N": cfg.N, "r": cfg.r,
+                   "kron": f"{cfg.n1}x{cfg.n2}", "x_dtype": cfg.x_dtype, "launch_mode": mode,
+                   "layer_copies": res["layer_copies"]},
+        "effective_tops": gemm_ops(cfg) / (us_layer * 1e-6) / 1e12,
+        "hbm_gbps_layer": (linear_forward_bytes(cfg) + rotate_quant_bytes(cfg)) / (us_layer * 1e-6) / 1e9,
+        "us_linear_forward": us_fwd, "us_rotate_quant": best["us_rotate_quant"],
+        "timings": {k: res[k] for k in ("stream", "graph") if k in res},
+        "roofline": roof,
+    }
+    if not args.no_cpu:
+        line["cpu_baseline"] = cpu_baseline(w)
+    del w
+    torch.cuda.empty_cache()
+
+    if not args.no_extra:
+        extra = []
+        names = ["cfg2_qwen32b_up_m16", "cfg3_qwen32b_down_m2048", "cfg4_70b_gate_m1", "cfg4_70b_down_m1"]
+        for nm in names:
+            if nm == cfg.name:
+                continue
+            c = all_cfgs[nm]
+            st = max(20, min(args.steps, 200 if c.M <= 64 else 20))
+            ww, r = measure(c, st, max(3, min(args.warmup, st // 4)), not args.no_graph)
+            b = r["stream"]
+            if "graph" in r and "us_per_layer" in r["graph"] and r["graph"]["us_per_layer"] < b["us_per_layer"]:
+                b = r["graph"]
+            r["roofline"] = roofline_for(c, b["us_linear_forward"])
+            r["effective_tops"] = gemm_ops(c) / (b["us_per_layer"] * 1e-6) / 1e12
+            extra.append(r)
+            del ww
+            torch.cuda.empty_cache()
+        line["other_workloads"] = extra
+    print(json.dumps(line))
+
+
+if __name__ == "__main__":
+    main()

@@ -60,8 +60,8 @@ typedef enum {
  *   bits   sign bits of W_rot, tiled for the kernels (see bwla_unpack_signs for the
  *          interchange view); 16-row tiles x 512-column chunks, 1 KiB each
  *   alpha  N fp16, alpha_n = mean_k |W_rot[n,k]|            (paper App. A.2.4)
- *   V      N x r fp16 row-major
- *   U      K x r fp16 row-major
+ *   V      N x rp fp16 row-major, rp = r rounded up to a multiple of 16, zero padded
+ *   U      K x rp fp16 row-major, zero padded
  *   R1     n1 x n1 fp32 row-major;  R2  n2 x n2 fp32 row-major
  */
 typedef struct bwla_layer {
@@ -114,8 +114,9 @@ bwla_status_t bwla_unpack_signs(const bwla_layer_t* layer, int8_t* d_sgn, float*
 /*
  * Bytes of scratch bwla_rotate_quant wants for M tokens (split-K partial sums of X U and
  * their arrival counters).  Returns 0 bytes when no split is used (r == 0 or M large).
- * The scratch must be zero-filled once when it is allocated; every call leaves it zeroed
- * again.  Two calls that overlap in time must not share one scratch buffer.
+ * The scratch must be zero-filled once when it is allocated: it starts with one arrival counter
+ * per 16-token tile, which every call returns to zero; the partial sums behind them are
+ * overwritten by each call.  Two calls that overlap in time must not share one scratch buffer.
  */
 bwla_status_t bwla_psp_workspace_size(const bwla_layer_t* layer, int64_t M, size_t* bytes);
 

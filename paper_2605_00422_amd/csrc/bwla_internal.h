@@ -31,6 +31,23 @@ struct bwla_psp_plan {
 };
 bwla_psp_plan bwla_make_psp_plan(int64_t M, int64_t K, int r);
 
+// Raises a kernel's dynamic-LDS limit once per process and size class (per device 0..15), so
+// that steady-state launches, also under stream capture, issue no attribute calls.
+struct bwla_lds_attr {
+    size_t granted[16] = {0};
+    hipError_t ensure(const void* fn, size_t bytes) {
+        if (bytes <= 64 * 1024) return hipSuccess;      // default limit, nothing to raise
+        int dev = 0;
+        hipError_t e = hipGetDevice(&dev);
+        if (e != hipSuccess) return e;
+        if (dev < 0 || dev >= 16) dev = 0, granted[0] = 0;
+        if (bytes <= granted[dev]) return hipSuccess;
+        e = hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)bytes);
+        if (e == hipSuccess) granted[dev] = bytes;
+        return e;
+    }
+};
+
 // ---------------------------------------------------------------- launchers (one per .hip file)
 hipError_t bwla_launch_pack(const float* dW, const float* dR1, const float* dR2, const float* dU,
                             const float* dV, int64_t N, int64_t K, int n1, int n2, int r,

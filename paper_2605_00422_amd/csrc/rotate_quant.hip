@@ -251,14 +251,14 @@ hipError_t bwla_launch_rotate_quant(const bwla_layer_t* L, const void* dX, int x
     const RqShape sh = rq_shape(L->n1, L->n2);
     hipError_t e;
     if (xdtype == BWLA_X_BF16) {
-        e = hipFuncSetAttribute((const void*)rotate_quant_kernel<true>, hipFuncAttributeMaxDynamicSharedMemorySize,
-                                (int)sh.lds_bytes);
+        static bwla_lds_attr attr;
+        e = attr.ensure((const void*)rotate_quant_kernel<true>, sh.lds_bytes);
         if (e != hipSuccess) return e;
         rotate_quant_kernel<true><<<dim3((unsigned)M), dim3(RQ_THREADS), sh.lds_bytes, st>>>(
             dX, L->K, L->n1, L->n2, R1, R2, dq, dscale, dqsum);
     } else {
-        e = hipFuncSetAttribute((const void*)rotate_quant_kernel<false>, hipFuncAttributeMaxDynamicSharedMemorySize,
-                                (int)sh.lds_bytes);
+        static bwla_lds_attr attr;
+        e = attr.ensure((const void*)rotate_quant_kernel<false>, sh.lds_bytes);
         if (e != hipSuccess) return e;
         rotate_quant_kernel<false><<<dim3((unsigned)M), dim3(RQ_THREADS), sh.lds_bytes, st>>>(
             dX, L->K, L->n1, L->n2, R1, R2, dq, dscale, dqsum);
