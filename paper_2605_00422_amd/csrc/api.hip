@@ -181,7 +181,9 @@ bwla_status_t bwla_linear_forward(const bwla_layer_t* layer, const int8_t* d_q, 
         return BWLA_ERR_ALIGN;
     hipStream_t st = (hipStream_t)stream;
     hipError_t e;
-    if (M <= 16 && bwla_gemm_decode_lds(M, layer->K) <= DECODE_LDS_LIMIT)
+    if (bwla_gemm_decode_bs_supported(M, layer->K, layer->r))
+        e = bwla_launch_gemm_decode_bs(layer, d_q, d_scale, d_qsum, d_T, M, d_Y, d_acc, st);
+    else if (M <= 16 && bwla_gemm_decode_lds(M, layer->K) <= DECODE_LDS_LIMIT)
         e = bwla_launch_gemm_decode(layer, d_q, d_scale, d_qsum, d_T, M, d_Y, d_acc, st);
     else
         e = bwla_launch_gemm_prefill(layer, d_q, d_scale, d_qsum, d_T, M, d_Y, d_acc, st);

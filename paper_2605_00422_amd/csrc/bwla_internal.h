@@ -63,6 +63,14 @@ hipError_t bwla_launch_code_sums(const int8_t* dq, int64_t M, int64_t K, int32_t
 hipError_t bwla_launch_gemm_decode(const bwla_layer_t* L, const int8_t* dq, const float* dscale,
                                    const int32_t* dqsum, const float* dT, int64_t M, float* dY,
                                    int32_t* dacc, hipStream_t st);
+bool bwla_gemm_decode_bs_supported(int64_t M, int64_t K, int r);
+hipError_t bwla_launch_gemm_decode_bs(const bwla_layer_t* L, const int8_t* dq, const float* dscale,
+                                      const int32_t* dqsum, const float* dT, int64_t M, float* dY,
+                                      int32_t* dacc, hipStream_t st);
+// explicit launch shape (tiles per step 1/2, grid size, prefetch depth 2/4)
+hipError_t bwla_launch_gemm_decode_bs_cfg(const bwla_layer_t* L, const int8_t* dq, const float* dscale,
+                                          const int32_t* dqsum, const float* dT, int64_t M, float* dY,
+                                          int32_t* dacc, hipStream_t st, int nt, int grid, int depth);
 hipError_t bwla_launch_gemm_prefill(const bwla_layer_t* L, const int8_t* dq, const float* dscale,
                                     const int32_t* dqsum, const float* dT, int64_t M, float* dY,
                                     int32_t* dacc, hipStream_t st);
@@ -73,6 +81,15 @@ typedef int v4i __attribute__((ext_vector_type(4)));
 typedef int v16i __attribute__((ext_vector_type(16)));
 typedef float v4f __attribute__((ext_vector_type(4)));
 typedef float v16f __attribute__((ext_vector_type(16)));
+
+// Workgroup barrier that orders LDS traffic only.  __syncthreads() also waits for every
+// outstanding global load and store (vmcnt(0)), which would drain the HBM prefetch queue of a
+// software-pipelined loop at each barrier.
+__device__ __forceinline__ void bwla_lds_barrier() {
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup", "local");
+    __builtin_amdgcn_s_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup", "local");
+}
 
 __device__ __forceinline__ float bwla_bf16_to_f32(uint16_t h) {
     return __uint_as_float(((uint32_t)h) << 16);
