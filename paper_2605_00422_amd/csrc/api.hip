@@ -154,10 +154,8 @@ bwla_status_t bwla_rotate_quant(const bwla_layer_t* layer, const void* d_X, int 
     const size_t need = psp_ws_bytes(plan, layer->r);
     if (need > 0 && (!d_ws || ws_bytes < need)) return d_ws ? BWLA_ERR_BUFSIZE : BWLA_ERR_NULL;
     hipStream_t st = (hipStream_t)stream;
-    if (layer->r > 0) {
-        if (bwla_launch_psp_project(layer, d_X, xdtype, M, d_T, d_ws, plan, st) != hipSuccess) return BWLA_ERR_HIP;
-    }
-    if (bwla_launch_rotate_quant(layer, d_X, xdtype, M, d_q, d_scale, d_qsum, st) != hipSuccess) return BWLA_ERR_HIP;
+    if (bwla_launch_rotate_quant(layer, d_X, xdtype, M, d_q, d_scale, d_qsum, d_T, d_ws, plan, st) != hipSuccess)
+        return BWLA_ERR_HIP;
     return BWLA_OK;
 }
 

@@ -23,11 +23,11 @@ static inline int64_t bwla_row_tiles(int64_t N) { return (N + BWLA_TILE_ROWS - 1
 static inline int64_t bwla_chunks(int64_t K) { return (K + BWLA_CHUNK_COLS - 1) / BWLA_CHUNK_COLS; }
 static inline uint64_t bwla_align256(uint64_t x) { return (x + 255u) & ~uint64_t(255); }
 
-// PSP projection (T = X U) launch plan: token tiles of 16, S splits of K.
+// PSP projection (T = X U) launch plan: token tiles of 16, S slices of K.
 struct bwla_psp_plan {
     int token_tiles;
     int splits;        // S
-    int k_per_split;   // multiple of 64
+    int k_per_split;   // columns of K per slice
 };
 bwla_psp_plan bwla_make_psp_plan(int64_t M, int64_t K, int r);
 
@@ -54,10 +54,10 @@ hipError_t bwla_launch_pack(const float* dW, const float* dR1, const float* dR2,
                             const bwla_layer_t* L, hipStream_t st);
 hipError_t bwla_launch_unpack(const bwla_layer_t* L, int8_t* d_sgn, float* d_alpha, hipStream_t st);
 
-hipError_t bwla_launch_rotate_quant(const bwla_layer_t* L, const void* dX, int xdtype, int64_t M,
-                                    int8_t* dq, float* dscale, int32_t* dqsum, hipStream_t st);
-hipError_t bwla_launch_psp_project(const bwla_layer_t* L, const void* dX, int xdtype, int64_t M,
-                                   float* dT, void* dws, const bwla_psp_plan& plan, hipStream_t st);
+// one launch: rotation + quantization workgroups, then the PSP projection workgroups
+hipError_t bwla_launch_rotate_quant(const bwla_layer_t* L, const void* dX, int xdtype, int64_t M, int8_t* dq,
+                                    float* dscale, int32_t* dqsum, float* dT, void* dws, const bwla_psp_plan& plan,
+                                    hipStream_t st);
 hipError_t bwla_launch_code_sums(const int8_t* dq, int64_t M, int64_t K, int32_t* dqsum, hipStream_t st);
 
 hipError_t bwla_launch_gemm_decode(const bwla_layer_t* L, const int8_t* dq, const float* dscale,
