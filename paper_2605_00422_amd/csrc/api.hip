@@ -5,6 +5,7 @@
 #include "bwla_internal.h"
 
 size_t bwla_rotate_lds_bytes(int n1, int n2);
+bool bwla_rotate_supported(int n1, int n2);
 int bwla_rotate_tiles(int n1, int n2);
 int bwla_rotate_max_tiles();
 size_t bwla_gemm_decode_lds(int64_t M, int64_t K);
@@ -23,7 +24,7 @@ bwla_status_t check_shape(int64_t N, int64_t K, int32_t n1, int32_t n2, int32_t 
     if (n1 > BWLA_MAX_FACTOR || n2 > BWLA_MAX_FACTOR) return BWLA_ERR_UNSUPPORTED;
     if (N > (int64_t)1 << 24) return BWLA_ERR_UNSUPPORTED;
     if (bwla_rotate_tiles(n1, n2) > bwla_rotate_max_tiles()) return BWLA_ERR_UNSUPPORTED;
-    if (bwla_rotate_lds_bytes(n1, n2) > LDS_LIMIT) return BWLA_ERR_UNSUPPORTED;
+    if (!bwla_rotate_supported(n1, n2)) return BWLA_ERR_UNSUPPORTED;
     return BWLA_OK;
 }
 

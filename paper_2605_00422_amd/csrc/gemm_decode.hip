@@ -27,7 +27,7 @@ __global__ __launch_bounds__(64 * GD_MAX_WAVES) void gemm_decode_kernel(
     const float* __restrict__ scale, const int32_t* __restrict__ qsum, const __half* __restrict__ alpha,
     const __half* __restrict__ V, const float* __restrict__ T, int r, float* __restrict__ Y, int N,
     int32_t* __restrict__ acc_out, int ksplit, int wn_count) {
-    extern __shared__ char smem[];
+    extern __shared__ __align__(16) char smem[];
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int li = lane & 15, lg = lane >> 4;
     const int Kp = chunks * BWLA_CHUNK_COLS;

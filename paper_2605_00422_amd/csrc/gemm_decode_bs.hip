@@ -337,7 +337,7 @@ __device__ __forceinline__ void epilogue_wave(const BsArgs& a, char* smem, int f
 // FAST: N % 4 == 0 and no accumulator dump, which allows float4 stores.
 template <int CPW, int DEPTH, int NT, int JTT, bool FAST>
 __global__ __launch_bounds__(BS_MAX_THREADS) void gemm_decode_bs_kernel(BsArgs a) {
-    extern __shared__ char smem[];
+    extern __shared__ __align__(16) char smem[];
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int stride = gridDim.x, first = blockIdx.x;
     const int units = (a.row_tiles + NT - 1) / NT;

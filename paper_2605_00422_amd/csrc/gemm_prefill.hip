@@ -25,7 +25,7 @@ __global__ __launch_bounds__(64 * WM * WN) void gemm_prefill_kernel(
     constexpr int BN = WN * NTL * 32;
     constexpr int PIECES = BM * (GP_BK / 16) / THREADS;     // 16-byte granules of the A tile per thread
     static_assert(BM * (GP_BK / 16) % THREADS == 0, "tile fill must divide evenly");
-    extern __shared__ char smem[];
+    extern __shared__ __align__(16) char smem[];
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int l32 = lane & 31, lg = lane >> 5;

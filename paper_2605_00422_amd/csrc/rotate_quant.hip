@@ -20,42 +20,53 @@
 namespace {
 
 #ifdef BWLA_TRACE
+// Development aid (off in the product build): cycle stamps are kept in registers and written
+// once at the end of the workgroup, so that taking them adds no memory waits.
 __device__ long long bwla_rq_trace_buf[16 * 8 * 16];
-#define RQTRACE(slot) do { if ((threadIdx.x & 63) == 0 && blockIdx.x < 16) bwla_rq_trace_buf[(blockIdx.x * 8 + (threadIdx.x >> 6)) * 16 + (slot)] = __builtin_readcyclecounter(); } while (0)
+#define RQTRACE_DECL long long rq_tr[10] = {0, 0, 0, 0, 0, 0, 0, 0, 0, 0}
+#define RQTRACE(slot) do { rq_tr[slot] = __builtin_readcyclecounter(); } while (0)
+#define RQTRACE_FLUSH do { if ((threadIdx.x & 63) == 0 && blockIdx.x < 16) { _Pragma("unroll") for (int i_ = 0; i_ < 10; ++i_) bwla_rq_trace_buf[(blockIdx.x * 8 + (threadIdx.x >> 6)) * 16 + i_] = rq_tr[i_]; } } while (0)
 #else
+#define RQTRACE_DECL do { } while (0)
 #define RQTRACE(slot) do { } while (0)
+#define RQTRACE_FLUSH do { } while (0)
 #endif
 
 constexpr int RQ_THREADS = 512;
 constexpr int RQ_WAVES = RQ_THREADS / 64;
 constexpr int RQ_MAXT = 16;          // 16x16 output tiles per wavefront
-constexpr int RQ_KC = 8;             // factor rows per chunk in streaming mode
+constexpr int RQ_CK = 16;            // contraction indices per streamed factor chunk
+constexpr int RQ_CLD = RQ_CK + 4;    // LDS pitch of a streamed chunk row
+constexpr int RQ_RING = 3;           // streamed chunks in flight (registers)
 constexpr int PP_SLICE = 512;        // columns of K per projection workgroup
 constexpr int PP_MAXJT = BWLA_MAX_RANK / 16;
 constexpr size_t RQ_LDS_LIMIT = 160 * 1024 - 256;   // leaves room for the few static bytes
 
 __host__ __device__ inline int rq_pad16(int n) { return (n + 15) & ~15; }
-// leading dimension with ld % 32 == 17: both the "16 rows x 4 columns" and the
-// "4 rows x 16 columns" access patterns of the two stages then spread over the LDS banks
-__host__ __device__ inline int rq_ld(int np16) { return np16 + ((np16 & 31) == 16 ? 1 : 17); }
 
+// LDS layout of a rotation workgroup (floats).  Every matrix is stored so that the MFMA
+// contraction index runs along a row with a pitch of (multiple of 16) + 4: a lane then fetches
+// four consecutive contraction values of its operand row with one 128-bit read, and the 16 rows
+// of a lane group fall into disjoint banks.
+//   region  V  [a][b]  pitch ldv   (token, stage-1 A)   later  ZT [d][a]  pitch ldzt (stage-2 A)
+//   R2T [d][b] pitch ld2t (stage-1 B),  R1T [c][a] pitch ld1t (stage-2 B)      -- resident mode
+//   two chunk buffers [row][16] pitch RQ_CLD                                   -- streaming mode
 struct RqShape {
-    int n1, n2, n1p, n2p, ldz, ldr, ld1, ld2;
+    int n1, n2, n1p, n2p, ldv, ldzt, ld2t, ld1t, region, nmaxp;
     bool resident;
-    size_t lds_bytes;      // rotation workgroups
+    size_t lds_bytes;
 };
 
 __host__ __device__ inline RqShape rq_shape(int n1, int n2) {
     RqShape s;
     s.n1 = n1; s.n2 = n2;
     s.n1p = rq_pad16(n1); s.n2p = rq_pad16(n2);
-    s.ldz = rq_ld(s.n2p);
-    const int nmax = s.n1p > s.n2p ? s.n1p : s.n2p;
-    s.ldr = rq_ld(nmax);                 // streaming mode: one pitch for both factors
-    s.ld2 = rq_ld(s.n2p);                // resident mode: R2 is n2p rows x ld2, R1 is n1p rows x ld1
-    s.ld1 = rq_ld(s.n1p);
-    const size_t res = ((size_t)s.n1p * s.ldz + (size_t)s.n2p * s.ld2 + (size_t)s.n1p * s.ld1 + 64) * sizeof(float);
-    const size_t str = ((size_t)s.n1p * s.ldz + 2 * RQ_KC * s.ldr + 64) * sizeof(float);
+    s.ldv = s.n2p + 4; s.ldzt = s.n1p + 4; s.ld2t = s.n2p + 4; s.ld1t = s.n1p + 4;
+    const int rv = s.n1p * s.ldv, rz = s.n2p * s.ldzt;
+    s.region = rv > rz ? rv : rz;
+    s.nmaxp = s.n1p > s.n2p ? s.n1p : s.n2p;
+    const size_t res = ((size_t)s.region + (size_t)s.n2p * s.ld2t + (size_t)s.n1p * s.ld1t + 64) * sizeof(float);
+    const size_t str = ((size_t)s.region + (size_t)2 * s.nmaxp * RQ_CLD + 64) * sizeof(float);
     s.resident = res <= RQ_LDS_LIMIT;
     s.lds_bytes = s.resident ? res : str;
     return s;
@@ -68,169 +79,176 @@ __host__ __device__ inline size_t pp_lds_bytes(int r) {
     return (us > red ? us : red) + 16;
 }
 
+// Exact n / d for n * d < 2^32 with one multiply-high; index arithmetic on run-time factor
+// sizes would otherwise cost a ~30-instruction division sequence per use.
+struct FastDiv {
+    uint32_t d, m;
+    __device__ explicit FastDiv(uint32_t dd) : d(dd), m(dd > 1 ? 0xFFFFFFFFu / dd + 1u : 0u) {}
+    __device__ __forceinline__ int div(int n) const { return d > 1 ? (int)__umulhi((uint32_t)n, m) : n; }
+};
+
 // ================================================================== rotation of one token
-// Stage a chunk of RQ_KC rows of an n x n factor (rows k0.., all columns) into registers.
-__device__ __forceinline__ void chunk_fetch(const float* __restrict__ R, int n, int np, int k0, float (&reg)[4]) {
-#pragma unroll
-    for (int e = 0; e < 4; ++e) {
-        const int idx = threadIdx.x + e * RQ_THREADS;
-        const int rr = idx / np, cc = idx - rr * np;
-        const int k = k0 + rr;
-        reg[e] = (rr < RQ_KC && k < n && cc < n) ? R[(int64_t)k * n + cc] : 0.0f;
-    }
-}
-__device__ __forceinline__ void chunk_store(float* __restrict__ dst, int np, int ldr, const float (&reg)[4]) {
-#pragma unroll
-    for (int e = 0; e < 4; ++e) {
-        const int idx = threadIdx.x + e * RQ_THREADS;
-        const int rr = idx / np, cc = idx - rr * np;
-        if (rr < RQ_KC) dst[rr * ldr + cc] = reg[e];
-    }
-}
-
-// whole factor -> LDS, zero padded to np rows x np columns (pitch ld)
-__device__ __forceinline__ void factor_to_lds(const float* __restrict__ R, int n, int np, int ld, float* dst) {
-    if ((n & 3) == 0) {
-        const int q4 = np >> 2;                                    // float4 per padded row
-        for (int idx = threadIdx.x; idx < np * q4; idx += RQ_THREADS) {
-            const int rr = idx / q4, c4 = (idx - rr * q4) << 2;
-            float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
-            if (rr < n && c4 < n) v = *reinterpret_cast<const float4*>(R + (int64_t)rr * n + c4);
-            float* d = dst + rr * ld + c4;
-            d[0] = v.x; d[1] = v.y; d[2] = v.z; d[3] = v.w;
-        }
-    } else {
-        for (int idx = threadIdx.x; idx < np * np; idx += RQ_THREADS) {
-            const int rr = idx / np, cc = idx - rr * np;
-            dst[rr * ld + cc] = (rr < n && cc < n) ? R[(int64_t)rr * n + cc] : 0.0f;
-        }
-    }
-}
-
 template <bool BF16>
-__device__ __forceinline__ void token_to_lds(const void* __restrict__ X, int64_t row_off, int n1, int n2,
-                                             const RqShape& sh, float* buf) {
-    constexpr int VEC = BF16 ? 8 : 4;                              // elements per 16-byte load
-    if (n2 % VEC == 0) {
-        const int vpr = n2 / VEC;
-        for (int idx = threadIdx.x; idx < n1 * vpr; idx += RQ_THREADS) {
-            const int a = idx / vpr, b0 = (idx - a * vpr) * VEC;
-            float* d = buf + a * sh.ldz + b0;
-            if (BF16) {
-                const uint4 raw = *reinterpret_cast<const uint4*>(reinterpret_cast<const uint16_t*>(X) + row_off +
-                                                                  (int64_t)a * n2 + b0);
-                d[0] = __uint_as_float(raw.x << 16); d[1] = __uint_as_float(raw.x & 0xffff0000u);
-                d[2] = __uint_as_float(raw.y << 16); d[3] = __uint_as_float(raw.y & 0xffff0000u);
-                d[4] = __uint_as_float(raw.z << 16); d[5] = __uint_as_float(raw.z & 0xffff0000u);
-                d[6] = __uint_as_float(raw.w << 16); d[7] = __uint_as_float(raw.w & 0xffff0000u);
-            } else {
-                const float4 raw = *reinterpret_cast<const float4*>(reinterpret_cast<const float*>(X) + row_off +
-                                                                    (int64_t)a * n2 + b0);
-                d[0] = raw.x; d[1] = raw.y; d[2] = raw.z; d[3] = raw.w;
-            }
-        }
-        // zero padding: columns [n2, n2p) of the real rows, then the rows [n1, n1p)
-        const int padc = sh.n2p - n2;
-        for (int idx = threadIdx.x; idx < n1 * padc; idx += RQ_THREADS) {
-            const int a = idx / padc, b = n2 + (idx - a * padc);
-            buf[a * sh.ldz + b] = 0.0f;
-        }
-        for (int idx = threadIdx.x; idx < (sh.n1p - n1) * sh.n2p; idx += RQ_THREADS) {
-            const int a = n1 + idx / sh.n2p, b = idx % sh.n2p;
-            buf[a * sh.ldz + b] = 0.0f;
-        }
+__device__ __forceinline__ void store_token_vec(float* d, const uint4& v) {
+    // d is 16-byte aligned (pitches and column offsets are multiples of four floats)
+    float4* d4 = reinterpret_cast<float4*>(d);
+    if (BF16) {
+        d4[0] = make_float4(__uint_as_float(v.x << 16), __uint_as_float(v.x & 0xffff0000u),
+                            __uint_as_float(v.y << 16), __uint_as_float(v.y & 0xffff0000u));
+        d4[1] = make_float4(__uint_as_float(v.z << 16), __uint_as_float(v.z & 0xffff0000u),
+                            __uint_as_float(v.w << 16), __uint_as_float(v.w & 0xffff0000u));
     } else {
+        d4[0] = make_float4(__uint_as_float(v.x), __uint_as_float(v.y), __uint_as_float(v.z), __uint_as_float(v.w));
+    }
+}
+
+// Token (and, in resident mode, R2 and R1 transposed) into LDS.  Every global load of a batch is
+// issued before the first use, so that a decode token pays one memory round trip.  Items are
+// 16-byte vectors [token | R2 | R1] when the shapes allow it; odd shapes take scalar loops.
+template <bool BF16>
+__device__ __forceinline__ void fill_lds(const void* __restrict__ X, int64_t row_off, int n1, int n2,
+                                         const float* __restrict__ R1, const float* __restrict__ R2,
+                                         const RqShape& sh, float* V, float* r2t, float* r1t) {
+    constexpr int VEC = BF16 ? 8 : 4;
+    const bool with_factors = sh.resident;
+    // zero the padding first (disjoint from everything written below)
+    if (n2 != sh.n2p || n1 != sh.n1p) {
         for (int idx = threadIdx.x; idx < sh.n1p * sh.n2p; idx += RQ_THREADS) {
             const int a = idx / sh.n2p, b = idx - a * sh.n2p;
-            float v = 0.0f;
-            if (a < n1 && b < n2) {
-                const int64_t i = row_off + (int64_t)a * n2 + b;
-                v = BF16 ? bwla_bf16_to_f32(reinterpret_cast<const uint16_t*>(X)[i])
-                         : reinterpret_cast<const float*>(X)[i];
+            if (a >= n1 || b >= n2) V[a * sh.ldv + b] = 0.0f;
+        }
+        if (with_factors) {
+            for (int idx = threadIdx.x; idx < sh.n2p * sh.n2p; idx += RQ_THREADS) {
+                const int d = idx / sh.n2p, b = idx - d * sh.n2p;
+                if (d >= n2 || b >= n2) r2t[d * sh.ld2t + b] = 0.0f;
             }
-            buf[a * sh.ldz + b] = v;
+            for (int idx = threadIdx.x; idx < sh.n1p * sh.n1p; idx += RQ_THREADS) {
+                const int c = idx / sh.n1p, a = idx - c * sh.n1p;
+                if (c >= n1 || a >= n1) r1t[c * sh.ld1t + a] = 0.0f;
+            }
+        }
+    }
+    if ((n2 % VEC) == 0 && (n1 & 3) == 0 && (n2 & 3) == 0) {
+        const int vpr = n2 / VEC, nx = n1 * vpr;
+        // A factor is cut into blocks of 16 rows k x 4 vectors (16 columns x): lane l of an item
+        // group takes row (l & 15), vector (l >> 4).  A wave then loads 64-byte row pieces and its
+        // four transposed scalar stores each hit 64 distinct LDS banks.
+        const int q2 = n2 >> 2, kg2 = (n2 + 15) >> 4, nr2 = with_factors ? 64 * kg2 * ((q2 + 3) >> 2) : 0;
+        const int q1 = n1 >> 2, kg1 = (n1 + 15) >> 4, nr1 = with_factors ? 64 * kg1 * ((q1 + 3) >> 2) : 0;
+        const int total = nx + nr2 + nr1;
+        const FastDiv dvpr(vpr), dkg1(kg1), dkg2(kg2);
+        auto factor_item = [&](int it, bool& second, int& k, int& x4) -> bool {
+            second = it >= nx + nr2;
+            const int j = second ? it - nx - nr2 : it - nx;
+            const int l = j & 63, blk = j >> 6;
+            const int kg = second ? kg1 : kg2;
+            const int xgi = (second ? dkg1 : dkg2).div(blk), kgi = blk - xgi * kg;
+            k = 16 * kgi + (l & 15);
+            x4 = 4 * xgi + (l >> 4);
+            return k < (second ? n1 : n2) && x4 < (second ? q1 : q2);
+        };
+        for (int base = 0; base < total; base += 8 * RQ_THREADS) {
+            uint4 v[8];
+#pragma unroll
+            for (int e = 0; e < 8; ++e) {
+                const int it = base + e * RQ_THREADS + threadIdx.x;
+                v[e] = make_uint4(0, 0, 0, 0);
+                if (it < nx) {
+                    const int a = dvpr.div(it), b0 = (it - a * vpr) * VEC;
+                    const int64_t off = row_off + (int64_t)a * n2 + b0;
+                    v[e] = BF16 ? *reinterpret_cast<const uint4*>(reinterpret_cast<const uint16_t*>(X) + off)
+                                : *reinterpret_cast<const uint4*>(reinterpret_cast<const float*>(X) + off);
+                } else if (it < total) {
+                    bool second; int k, x4;
+                    if (factor_item(it, second, k, x4))
+                        v[e] = *reinterpret_cast<const uint4*>((second ? R1 : R2) + (int64_t)k * (second ? n1 : n2) + 4 * x4);
+                }
+            }
+#pragma unroll
+            for (int e = 0; e < 8; ++e) {
+                const int it = base + e * RQ_THREADS + threadIdx.x;
+                if (it < nx) {
+                    const int a = dvpr.div(it), b0 = (it - a * vpr) * VEC;
+                    store_token_vec<BF16>(V + a * sh.ldv + b0, v[e]);
+                } else if (it < total) {
+                    // R[k][x0..x0+3] -> transposed rows x0..x0+3, column k
+                    bool second; int k, x4;
+                    if (factor_item(it, second, k, x4)) {
+                        const int ld = second ? sh.ld1t : sh.ld2t;
+                        float* d = (second ? r1t : r2t) + 4 * x4 * ld + k;
+                        d[0] = __uint_as_float(v[e].x); d[ld] = __uint_as_float(v[e].y);
+                        d[2 * ld] = __uint_as_float(v[e].z); d[3 * ld] = __uint_as_float(v[e].w);
+                    }
+                }
+            }
+        }
+    } else {
+        for (int idx = threadIdx.x; idx < n1 * n2; idx += RQ_THREADS) {
+            const int a = idx / n2, b = idx - a * n2;
+            const int64_t i = row_off + idx;
+            V[a * sh.ldv + b] = BF16 ? bwla_bf16_to_f32(reinterpret_cast<const uint16_t*>(X)[i])
+                                     : reinterpret_cast<const float*>(X)[i];
+        }
+        if (with_factors) {
+            for (int idx = threadIdx.x; idx < n2 * n2; idx += RQ_THREADS) {
+                const int b = idx / n2, d = idx - b * n2;
+                r2t[d * sh.ld2t + b] = R2[idx];
+            }
+            for (int idx = threadIdx.x; idx < n1 * n1; idx += RQ_THREADS) {
+                const int a = idx / n1, c = idx - a * n1;
+                r1t[c * sh.ld1t + a] = R1[idx];
+            }
         }
     }
 }
 
-// Token, R2 and R1 into LDS with every global load of a batch issued before the first use, so
-// that a decode token pays one memory round trip instead of one per array.  Items are 16-byte
-// vectors: [token | R2 | R1]; a thread takes items tid, tid + 512, ... in batches of 8.
-template <bool BF16>
-__device__ __forceinline__ void resident_fill(const void* __restrict__ X, int64_t row_off, int n1, int n2,
-                                              const float* __restrict__ R1, const float* __restrict__ R2,
-                                              const RqShape& sh, float* buf, float* r2s, float* r1s) {
-    constexpr int VEC = BF16 ? 8 : 4;
-    if ((n2 % VEC) != 0 || (n1 & 3) != 0 || (n2 & 3) != 0) {       // odd shapes: plain loops
-        token_to_lds<BF16>(X, row_off, n1, n2, sh, buf);
-        factor_to_lds(R2, n2, sh.n2p, sh.ld2, r2s);
-        factor_to_lds(R1, n1, sh.n1p, sh.ld1, r1s);
-        return;
-    }
-    const int vpr = n2 / VEC;                      // token vectors per row
-    const int nx = n1 * vpr;
-    const int q2 = n2 >> 2, nr2 = n2 * q2;         // float4 per R2 row, R2 vectors
-    const int q1 = n1 >> 2, nr1 = n1 * q1;
-    const int total = nx + nr2 + nr1;
-    for (int base = 0; base < total; base += 8 * RQ_THREADS) {
-        uint4 v[8];
+// one 16-wide contraction group: four MFMA steps fed by one 128-bit LDS read per operand
+__device__ __forceinline__ v4f mfma16(const float* ap, const float* bp, v4f acc) {
+    const float4 a4 = *reinterpret_cast<const float4*>(ap);
+    const float4 b4 = *reinterpret_cast<const float4*>(bp);
+    acc = __builtin_amdgcn_mfma_f32_16x16x4f32(a4.x, b4.x, acc, 0, 0, 0);
+    acc = __builtin_amdgcn_mfma_f32_16x16x4f32(a4.y, b4.y, acc, 0, 0, 0);
+    acc = __builtin_amdgcn_mfma_f32_16x16x4f32(a4.z, b4.z, acc, 0, 0, 0);
+    acc = __builtin_amdgcn_mfma_f32_16x16x4f32(a4.w, b4.w, acc, 0, 0, 0);
+    return acc;
+}
+
+// Streamed factor chunks (n % 4 == 0): chunk c holds R[16c .. 16c+15][all x]; a thread carries
+// two 16-byte vectors of it (slot e: local row kk[e], columns x0[e]..x0[e]+3).  They are stored
+// transposed, [x][k_local] with pitch RQ_CLD.
+struct ChunkRegs { float4 v[2]; };
+struct ChunkSlots { int kk[2], x0[2]; };
+// lane l of a 64-item group takes local row (l & 15) and vector (l >> 4) of the group's 16
+// columns: 64-byte row pieces from global memory, conflict-free transposed stores (pitch 20
+// floats puts the four column groups 16 banks apart)
+__device__ __forceinline__ ChunkSlots chunk_slots(int n) {
+    ChunkSlots cs;
 #pragma unroll
-        for (int e = 0; e < 8; ++e) {
-            const int it = base + e * RQ_THREADS + threadIdx.x;
-            v[e] = make_uint4(0, 0, 0, 0);
-            if (it < nx) {
-                const int a = it / vpr, b0 = (it - a * vpr) * VEC;
-                const int64_t off = row_off + (int64_t)a * n2 + b0;
-                v[e] = BF16 ? *reinterpret_cast<const uint4*>(reinterpret_cast<const uint16_t*>(X) + off)
-                            : *reinterpret_cast<const uint4*>(reinterpret_cast<const float*>(X) + off);
-            } else if (it < nx + nr2) {
-                v[e] = *reinterpret_cast<const uint4*>(R2 + (int64_t)(it - nx) * 4);
-            } else if (it < total) {
-                v[e] = *reinterpret_cast<const uint4*>(R1 + (int64_t)(it - nx - nr2) * 4);
-            }
-        }
+    for (int e = 0; e < 2; ++e) {
+        const int idx = threadIdx.x + e * RQ_THREADS;
+        const int l = idx & 63, grp = idx >> 6;
+        cs.x0[e] = (4 * grp + (l >> 4)) << 2;
+        cs.kk[e] = cs.x0[e] < n ? (l & 15) : RQ_CK;      // RQ_CK marks an unused slot
+    }
+    return cs;
+}
+__device__ __forceinline__ ChunkRegs chunk_fetch(const float* __restrict__ R, int n, int c, const ChunkSlots& cs) {
+    ChunkRegs cr;
 #pragma unroll
-        for (int e = 0; e < 8; ++e) {
-            const int it = base + e * RQ_THREADS + threadIdx.x;
-            if (it < nx) {
-                const int a = it / vpr, b0 = (it - a * vpr) * VEC;
-                float* d = buf + a * sh.ldz + b0;
-                if (BF16) {
-                    d[0] = __uint_as_float(v[e].x << 16); d[1] = __uint_as_float(v[e].x & 0xffff0000u);
-                    d[2] = __uint_as_float(v[e].y << 16); d[3] = __uint_as_float(v[e].y & 0xffff0000u);
-                    d[4] = __uint_as_float(v[e].z << 16); d[5] = __uint_as_float(v[e].z & 0xffff0000u);
-                    d[6] = __uint_as_float(v[e].w << 16); d[7] = __uint_as_float(v[e].w & 0xffff0000u);
-                } else {
-                    d[0] = __uint_as_float(v[e].x); d[1] = __uint_as_float(v[e].y);
-                    d[2] = __uint_as_float(v[e].z); d[3] = __uint_as_float(v[e].w);
-                }
-            } else if (it < total) {
-                const bool second = it >= nx + nr2;
-                const int j = second ? it - nx - nr2 : it - nx;
-                const int q = second ? q1 : q2;
-                const int rr = j / q, c4 = (j - rr * q) << 2;
-                float* d = (second ? r1s + rr * sh.ld1 : r2s + rr * sh.ld2) + c4;
-                d[0] = __uint_as_float(v[e].x); d[1] = __uint_as_float(v[e].y);
-                d[2] = __uint_as_float(v[e].z); d[3] = __uint_as_float(v[e].w);
-            }
+    for (int e = 0; e < 2; ++e) {
+        const int k = c * RQ_CK + cs.kk[e];
+        cr.v[e] = make_float4(0.f, 0.f, 0.f, 0.f);
+        if (cs.kk[e] < RQ_CK && k < n) cr.v[e] = *reinterpret_cast<const float4*>(R + (int64_t)k * n + cs.x0[e]);
+    }
+    return cr;
+}
+__device__ __forceinline__ void chunk_store(float* dst, const ChunkSlots& cs, const ChunkRegs& cr) {
+#pragma unroll
+    for (int e = 0; e < 2; ++e) {
+        if (cs.kk[e] < RQ_CK) {
+            float* d = dst + cs.x0[e] * RQ_CLD + cs.kk[e];
+            d[0] = cr.v[e].x; d[RQ_CLD] = cr.v[e].y; d[2 * RQ_CLD] = cr.v[e].z; d[3 * RQ_CLD] = cr.v[e].w;
         }
-    }
-    // zero padding of the token tile and of the factors (rows and columns up to the next 16)
-    if (n1 == sh.n1p && n2 == sh.n2p) return;
-    const int padc = sh.n2p - n2;
-    for (int idx = threadIdx.x; idx < n1 * padc; idx += RQ_THREADS) {
-        const int a = idx / padc, b = n2 + (idx - a * padc);
-        buf[a * sh.ldz + b] = 0.0f;
-    }
-    for (int idx = threadIdx.x; idx < (sh.n1p - n1) * sh.n2p; idx += RQ_THREADS)
-        buf[(n1 + idx / sh.n2p) * sh.ldz + idx % sh.n2p] = 0.0f;
-    for (int idx = threadIdx.x; idx < sh.n2p * sh.n2p; idx += RQ_THREADS) {
-        const int rr = idx / sh.n2p, cc = idx - rr * sh.n2p;
-        if (rr >= n2 || cc >= n2) r2s[rr * sh.ld2 + cc] = 0.0f;
-    }
-    for (int idx = threadIdx.x; idx < sh.n1p * sh.n1p; idx += RQ_THREADS) {
-        const int rr = idx / sh.n1p, cc = idx - rr * sh.n1p;
-        if (rr >= n1 || cc >= n1) r1s[rr * sh.ld1 + cc] = 0.0f;
     }
 }
 
@@ -240,133 +258,149 @@ __device__ __forceinline__ void rotate_token(float* lds, const void* __restrict_
                                              int8_t* __restrict__ q, float* __restrict__ scale,
                                              int32_t* __restrict__ qsum) {
     const RqShape sh = rq_shape(n1, n2);
-    float* buf = lds;                                              // n1p x ldz
-    float* fac = lds + (size_t)sh.n1p * sh.ldz;                    // factors (resident) or chunk ring (streaming)
-    float* red = fac + (sh.resident ? (size_t)sh.n2p * sh.ld2 + (size_t)sh.n1p * sh.ld1 : (size_t)2 * RQ_KC * sh.ldr);
+    float* reg = lds;                                              // V, later ZT
+    float* fac = lds + sh.region;                                  // R2T | R1T (resident) or two chunk buffers
+    float* red = fac + (sh.resident ? sh.n2p * sh.ld2t + sh.n1p * sh.ld1t : 2 * sh.nmaxp * RQ_CLD);
 
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);     // wave-uniform: tile indices stay scalar
     const int li = lane & 15, lg = lane >> 4;
-    const int tilesN = sh.n2p >> 4;
-    const int tiles = (sh.n1p >> 4) * tilesN;
+    const int tiles1 = sh.n1p >> 4, tiles2 = sh.n2p >> 4;         // 16-row tiles along a/c and along b/d
+    const int tiles = tiles1 * tiles2;
     const int my_tiles = (tiles - wave + RQ_WAVES - 1) / RQ_WAVES;      // tiles wave, wave+8, ...
+    const FastDiv dt1(tiles1), dt2(tiles2);
+    // Tiles are processed in pairs so that two independent read->MFMA chains overlap; an odd
+    // last tile is paired with a copy of itself whose result is never used.
+#define RQ_PAIR_SLOTS(g) const int s0 = 2 * (g), s1 = (2 * (g) + 1 < my_tiles) ? 2 * (g) + 1 : 2 * (g)
 
     v4f acc[RQ_MAXT];
 #pragma unroll
     for (int s = 0; s < RQ_MAXT; ++s) acc[s] = v4f{0.f, 0.f, 0.f, 0.f};
 
+    RQTRACE_DECL;
+    RQTRACE(0);
+    fill_lds<BF16>(X, t * K, n1, n2, R1, R2, sh, reg, fac, fac + sh.n2p * sh.ld2t);
+
     if (sh.resident) {
-        // ---------------- everything the token needs in one round trip
-        float* r2s = fac;
-        float* r1s = fac + (size_t)sh.n2p * sh.ld2;
-        RQTRACE(0);
-        resident_fill<BF16>(X, t * K, n1, n2, R1, R2, sh, buf, r2s, r1s);
+        const float* r2t = fac;
+        const float* r1t = fac + sh.n2p * sh.ld2t;
         RQTRACE(1);
         __syncthreads();
         RQTRACE(2);
-        // stage 1: Z = V R2 (contraction over b)
+        // stage 1: Z[a][d] = sum_b V[a][b] R2[b][d];   tile (ti over a, tj over d)
 #pragma unroll
-        for (int s = 0; s < RQ_MAXT; ++s) {
-            if (s < my_tiles) {
-                const int tau = wave + s * RQ_WAVES;
-                const int ti = tau / tilesN, tj = tau - ti * tilesN;
-                const float* ap = buf + (ti * 16 + li) * sh.ldz + lg;
-                const float* bp = r2s + lg * sh.ld2 + tj * 16 + li;
-#pragma unroll 4
-                for (int k = 0; k < sh.n2p; k += 4)
-                    acc[s] = __builtin_amdgcn_mfma_f32_16x16x4f32(ap[k], bp[k * sh.ld2], acc[s], 0, 0, 0);
+        for (int g = 0; g < RQ_MAXT / 2; ++g) {
+            if (2 * g < my_tiles) {
+                RQ_PAIR_SLOTS(g);
+                const int tau0 = wave + s0 * RQ_WAVES, tau1 = wave + s1 * RQ_WAVES;
+                const int ti0 = dt2.div(tau0), tj0 = tau0 - ti0 * tiles2;
+                const int ti1 = dt2.div(tau1), tj1 = tau1 - ti1 * tiles2;
+                const float* ap0 = reg + (ti0 * 16 + li) * sh.ldv + 4 * lg;
+                const float* bp0 = r2t + (tj0 * 16 + li) * sh.ld2t + 4 * lg;
+                const float* ap1 = reg + (ti1 * 16 + li) * sh.ldv + 4 * lg;
+                const float* bp1 = r2t + (tj1 * 16 + li) * sh.ld2t + 4 * lg;
+#pragma unroll 2
+                for (int k = 0; k < sh.n2p; k += 16) {
+                    acc[2 * g] = mfma16(ap0 + k, bp0 + k, acc[2 * g]);
+                    acc[2 * g + 1] = mfma16(ap1 + k, bp1 + k, acc[2 * g + 1]);
+                }
             }
         }
         RQTRACE(3);
         bwla_lds_barrier();                                        // every wave is done reading V
+        // lane holds Z[a = ti*16 + 4*lg + v][d = tj*16 + li]: one 128-bit store into ZT[d][a..a+3]
 #pragma unroll
         for (int s = 0; s < RQ_MAXT; ++s) {
             if (s < my_tiles) {
                 const int tau = wave + s * RQ_WAVES;
-                const int ti = tau / tilesN, tj = tau - ti * tilesN;
-#pragma unroll
-                for (int v = 0; v < 4; ++v) buf[(ti * 16 + 4 * lg + v) * sh.ldz + tj * 16 + li] = acc[s][v];
+                const int ti = dt2.div(tau), tj = tau - ti * tiles2;
+                *reinterpret_cast<float4*>(reg + (tj * 16 + li) * sh.ldzt + ti * 16 + 4 * lg) =
+                    make_float4(acc[s][0], acc[s][1], acc[s][2], acc[s][3]);
                 acc[s] = v4f{0.f, 0.f, 0.f, 0.f};
             }
         }
-        bwla_lds_barrier();                                        // Z is published
+        bwla_lds_barrier();                                        // ZT is published
         RQTRACE(4);
-        // stage 2: Y = R1^T Z (contraction over a):  A[c][a] = R1[a][c],  B[a][d] = Z[a][d]
+        // stage 2: Yt[d][c] = sum_a ZT[d][a] R1[a][c];   tile (ti over d, tj over c)
 #pragma unroll
-        for (int s = 0; s < RQ_MAXT; ++s) {
-            if (s < my_tiles) {
-                const int tau = wave + s * RQ_WAVES;
-                const int ti = tau / tilesN, tj = tau - ti * tilesN;
-                const float* ap = r1s + lg * sh.ld1 + ti * 16 + li;
-                const float* bp = buf + lg * sh.ldz + tj * 16 + li;
-#pragma unroll 4
-                for (int k = 0; k < sh.n1p; k += 4)
-                    acc[s] = __builtin_amdgcn_mfma_f32_16x16x4f32(ap[k * sh.ld1], bp[k * sh.ldz], acc[s], 0, 0, 0);
+        for (int g = 0; g < RQ_MAXT / 2; ++g) {
+            if (2 * g < my_tiles) {
+                RQ_PAIR_SLOTS(g);
+                const int tau0 = wave + s0 * RQ_WAVES, tau1 = wave + s1 * RQ_WAVES;
+                const int ti0 = dt1.div(tau0), tj0 = tau0 - ti0 * tiles1;
+                const int ti1 = dt1.div(tau1), tj1 = tau1 - ti1 * tiles1;
+                const float* ap0 = reg + (ti0 * 16 + li) * sh.ldzt + 4 * lg;
+                const float* bp0 = r1t + (tj0 * 16 + li) * sh.ld1t + 4 * lg;
+                const float* ap1 = reg + (ti1 * 16 + li) * sh.ldzt + 4 * lg;
+                const float* bp1 = r1t + (tj1 * 16 + li) * sh.ld1t + 4 * lg;
+#pragma unroll 2
+                for (int k = 0; k < sh.n1p; k += 16) {
+                    acc[2 * g] = mfma16(ap0 + k, bp0 + k, acc[2 * g]);
+                    acc[2 * g + 1] = mfma16(ap1 + k, bp1 + k, acc[2 * g + 1]);
+                }
             }
         }
     } else {
-        // ---------------- factors streamed in RQ_KC-row chunks through a double buffer
-        float* rch = fac;
-        float creg[4];
-        token_to_lds<BF16>(X, t * K, n1, n2, sh, buf);
-        {
-            const int nchunks = (n2 + RQ_KC - 1) / RQ_KC;
-            chunk_fetch(R2, n2, sh.n2p, 0, creg);
-            chunk_store(rch, sh.n2p, sh.ldr, creg);
-            __syncthreads();
-            for (int c = 0; c < nchunks; ++c) {
-                const float* cur = rch + (c & 1) * RQ_KC * sh.ldr;
-                if (c + 1 < nchunks) chunk_fetch(R2, n2, sh.n2p, (c + 1) * RQ_KC, creg);
+        // ---------------- factors streamed in 16-index chunks: RQ_RING chunks in flight in
+        // registers, two chunk buffers in LDS, one LDS-only barrier per chunk
+        float* cb = fac;
+        const int cbs = sh.nmaxp * RQ_CLD;                         // floats per chunk buffer
+        for (int idx = tid; idx < 2 * cbs; idx += RQ_THREADS) cb[idx] = 0.0f;    // padded rows stay zero
+        __syncthreads();
+        for (int stage = 0; stage < 2; ++stage) {
+            const float* R = stage == 0 ? R2 : R1;
+            const int n = stage == 0 ? n2 : n1;
+            const int nchunks = (n + RQ_CK - 1) / RQ_CK;
+            const int lda = stage == 0 ? sh.ldv : sh.ldzt;
+            const int tdiv = stage == 0 ? tiles2 : tiles1;         // tiles along the operand-B rows
+            const FastDiv dtd = stage == 0 ? dt2 : dt1;
+            const ChunkSlots cs = chunk_slots(n);
+            ChunkRegs ring[RQ_RING];
+#pragma unroll
+            for (int d = 0; d < RQ_RING; ++d) ring[d] = chunk_fetch(R, n, d, cs);
+            chunk_store(cb, cs, ring[0]);
+            bwla_lds_barrier();                                    // chunk 0 (and V / ZT) published
+            for (int c0 = 0; c0 < nchunks; c0 += RQ_RING) {
+#pragma unroll
+                for (int d = 0; d < RQ_RING; ++d) {
+                    const int c = c0 + d;
+                    if (c < nchunks) {
+                        const float* cur = cb + (c & 1) * cbs;
+#pragma unroll
+                        for (int g = 0; g < RQ_MAXT / 2; ++g) {
+                            if (2 * g < my_tiles) {
+                                RQ_PAIR_SLOTS(g);
+                                const int tau0 = wave + s0 * RQ_WAVES, tau1 = wave + s1 * RQ_WAVES;
+                                const int ti0 = dtd.div(tau0), tj0 = tau0 - ti0 * tdiv;
+                                const int ti1 = dtd.div(tau1), tj1 = tau1 - ti1 * tdiv;
+                                acc[2 * g] = mfma16(reg + (ti0 * 16 + li) * lda + c * RQ_CK + 4 * lg,
+                                                    cur + (tj0 * 16 + li) * RQ_CLD + 4 * lg, acc[2 * g]);
+                                acc[2 * g + 1] = mfma16(reg + (ti1 * 16 + li) * lda + c * RQ_CK + 4 * lg,
+                                                        cur + (tj1 * 16 + li) * RQ_CLD + 4 * lg, acc[2 * g + 1]);
+                            }
+                        }
+                    }
+                    // chunk c+1 (requested RQ_RING - 1 chunks ago) into the other buffer, whose last
+                    // readers passed the previous barrier; then refill this ring slot
+                    chunk_store(cb + ((c + 1) & 1) * cbs, cs, ring[(d + 1) % RQ_RING]);
+                    ring[d] = chunk_fetch(R, n, c + RQ_RING, cs);
+                    bwla_lds_barrier();
+                }
+            }
+            if (stage == 0) RQTRACE(3); else RQTRACE(9);
+            if (stage == 0) {
+                // lane holds Z[a = ti*16 + 4*lg + v][d = tj*16 + li] -> ZT[d][a..a+3]; V is dead
+                // (every wave passed the last barrier of the loop)
 #pragma unroll
                 for (int s = 0; s < RQ_MAXT; ++s) {
                     if (s < my_tiles) {
                         const int tau = wave + s * RQ_WAVES;
-                        const int ti = tau / tilesN, tj = tau - ti * tilesN;
-#pragma unroll
-                        for (int ks = 0; ks < RQ_KC; ks += 4) {
-                            const float a = buf[(ti * 16 + li) * sh.ldz + c * RQ_KC + ks + lg];
-                            const float b = cur[(ks + lg) * sh.ldr + tj * 16 + li];
-                            acc[s] = __builtin_amdgcn_mfma_f32_16x16x4f32(a, b, acc[s], 0, 0, 0);
-                        }
+                        const int ti = dt2.div(tau), tj = tau - ti * tiles2;
+                        *reinterpret_cast<float4*>(reg + (tj * 16 + li) * sh.ldzt + ti * 16 + 4 * lg) =
+                            make_float4(acc[s][0], acc[s][1], acc[s][2], acc[s][3]);
+                        acc[s] = v4f{0.f, 0.f, 0.f, 0.f};
                     }
                 }
-                if (c + 1 < nchunks) chunk_store(rch + ((c + 1) & 1) * RQ_KC * sh.ldr, sh.n2p, sh.ldr, creg);
-                __syncthreads();
-            }
-        }
-        // Z replaces V (every wave is past its last read of V after the loop's final barrier)
-#pragma unroll
-        for (int s = 0; s < RQ_MAXT; ++s) {
-            if (s < my_tiles) {
-                const int tau = wave + s * RQ_WAVES;
-                const int ti = tau / tilesN, tj = tau - ti * tilesN;
-#pragma unroll
-                for (int v = 0; v < 4; ++v) buf[(ti * 16 + 4 * lg + v) * sh.ldz + tj * 16 + li] = acc[s][v];
-                acc[s] = v4f{0.f, 0.f, 0.f, 0.f};
-            }
-        }
-        {
-            const int nchunks = (n1 + RQ_KC - 1) / RQ_KC;
-            chunk_fetch(R1, n1, sh.n1p, 0, creg);
-            chunk_store(rch, sh.n1p, sh.ldr, creg);       // last stage-1 reads of rch ended at its final barrier
-            __syncthreads();                              // also publishes Z
-            for (int c = 0; c < nchunks; ++c) {
-                const float* cur = rch + (c & 1) * RQ_KC * sh.ldr;
-                if (c + 1 < nchunks) chunk_fetch(R1, n1, sh.n1p, (c + 1) * RQ_KC, creg);
-#pragma unroll
-                for (int s = 0; s < RQ_MAXT; ++s) {
-                    if (s < my_tiles) {
-                        const int tau = wave + s * RQ_WAVES;
-                        const int ti = tau / tilesN, tj = tau - ti * tilesN;
-#pragma unroll
-                        for (int ks = 0; ks < RQ_KC; ks += 4) {
-                            const float a = cur[(ks + lg) * sh.ldr + ti * 16 + li];
-                            const float b = buf[(c * RQ_KC + ks + lg) * sh.ldz + tj * 16 + li];
-                            acc[s] = __builtin_amdgcn_mfma_f32_16x16x4f32(a, b, acc[s], 0, 0, 0);
-                        }
-                    }
-                }
-                if (c + 1 < nchunks) chunk_store(rch + ((c + 1) & 1) * RQ_KC * sh.ldr, sh.n1p, sh.ldr, creg);
-                __syncthreads();
             }
         }
     }
@@ -382,31 +416,44 @@ __device__ __forceinline__ void rotate_token(float* lds, const void* __restrict_
         }
     m = bwla_wave_max(m);
     if (lane == 0) red[wave] = m;
-    bwla_lds_barrier();                                // also: every wave is done reading Z
+    bwla_lds_barrier();                                // also: every wave is done reading ZT
     float amax = red[0];
 #pragma unroll
     for (int w = 1; w < RQ_WAVES; ++w) amax = fmaxf(amax, red[w]);
     const float inv = amax > 0.0f ? 31.0f / amax : 0.0f;
     RQTRACE(6);
 
-    // ================= quantize from registers into an LDS byte image of the token's codes
-    int8_t* codes = reinterpret_cast<int8_t*>(buf);
+    // ================= quantize from registers into an LDS byte image of the token's codes:
+    // lane holds Yt[d = ti*16 + 4*lg + v][c = tj*16 + li], i.e. four consecutive d of one c
+    int8_t* codes = reinterpret_cast<int8_t*>(reg);
     int lsum = 0;
 #pragma unroll
     for (int s = 0; s < RQ_MAXT; ++s) {
         if (s < my_tiles) {
             const int tau = wave + s * RQ_WAVES;
-            const int ti = tau / tilesN, tj = tau - ti * tilesN;
-            const int d = tj * 16 + li;
+            const int ti = dt1.div(tau), tj = tau - ti * tiles1;
+            const int c = tj * 16 + li, d0 = ti * 16 + 4 * lg;
+            int code[4];
 #pragma unroll
             for (int v = 0; v < 4; ++v) {
-                const int c = ti * 16 + 4 * lg + v;
                 float r = rintf(acc[s][v] * inv);
                 r = fminf(fmaxf(r, -31.0f), 31.0f);
-                const int code = (int)r;
-                if (c < n1 && d < n2) {
-                    codes[c * n2 + d] = (int8_t)code;
-                    lsum += code;
+                code[v] = (int)r;
+            }
+            if (c < n1) {
+                if ((n2 & 3) == 0) {
+                    if (d0 < n2) {
+                        *reinterpret_cast<int*>(codes + c * n2 + d0) = (code[0] & 0xff) | ((code[1] & 0xff) << 8) |
+                                                                        ((code[2] & 0xff) << 16) | (code[3] << 24);
+                        lsum += code[0] + code[1] + code[2] + code[3];
+                    }
+                } else {
+#pragma unroll
+                    for (int v = 0; v < 4; ++v)
+                        if (d0 + v < n2) {
+                            codes[c * n2 + d0 + v] = (int8_t)code[v];
+                            lsum += code[v];
+                        }
                 }
             }
         }
@@ -431,6 +478,8 @@ __device__ __forceinline__ void rotate_token(float* lds, const void* __restrict_
         scale[t] = amax / 31.0f;
     }
     RQTRACE(8);
+    RQTRACE_FLUSH;
+#undef RQ_PAIR_SLOTS
 }
 
 // ================================================================== PSP projection T = X U
@@ -551,15 +600,16 @@ struct RqArgs {
     const float* R1; const float* R2; const __half* U;
     int8_t* q; float* scale; int32_t* qsum; float* T;
     int* counters; float* partials; int S;
+    int64_t rot_blocks;      // workgroups below this index rotate token blockIdx.x, the rest project
 };
 
 template <bool BF16>
 __global__ __launch_bounds__(RQ_THREADS) void rotate_quant_kernel(RqArgs a) {
-    extern __shared__ float lds[];
-    if ((int64_t)blockIdx.x < a.M) {
+    extern __shared__ __align__(16) float lds[];
+    if ((int64_t)blockIdx.x < a.rot_blocks) {
         rotate_token<BF16>(lds, a.X, blockIdx.x, a.K, a.n1, a.n2, a.R1, a.R2, a.q, a.scale, a.qsum);
     } else {
-        const int pb = (int)(blockIdx.x - a.M);
+        const int pb = (int)(blockIdx.x - a.rot_blocks);
         psp_block<BF16>(reinterpret_cast<char*>(lds), a.X, a.M, a.K, a.r, a.U, a.T, a.counters, a.partials, a.S,
                         pb / a.S, pb % a.S);
     }
@@ -590,6 +640,11 @@ extern "C" int bwla_rq_trace_dump(long long* host, int n) {
 #endif
 
 size_t bwla_rotate_lds_bytes(int n1, int n2) { return rq_shape(n1, n2).lds_bytes; }
+// factors that do not fit into LDS are streamed with 16-byte loads, which needs n % 4 == 0
+bool bwla_rotate_supported(int n1, int n2) {
+    const RqShape sh = rq_shape(n1, n2);
+    return sh.lds_bytes <= RQ_LDS_LIMIT && (sh.resident || ((n1 & 3) == 0 && (n2 & 3) == 0));
+}
 int bwla_rotate_tiles(int n1, int n2) { return (rq_pad16(n1) / 16) * (rq_pad16(n2) / 16); }
 int bwla_rotate_max_tiles() { return RQ_MAXT * RQ_WAVES; }
 
@@ -606,13 +661,6 @@ hipError_t bwla_launch_rotate_quant(const bwla_layer_t* L, const void* dX, int x
                                     hipStream_t st) {
     const char* blob = (const char*)L->d_blob;
     const RqShape sh = rq_shape(L->n1, L->n2);
-    size_t lds = sh.lds_bytes;
-    int64_t blocks = M;
-    if (L->r > 0) {
-        const size_t pl = pp_lds_bytes(L->r);
-        if (pl > lds) lds = pl;
-        blocks += (int64_t)plan.token_tiles * plan.splits;
-    }
     RqArgs a;
     a.X = dX; a.M = M; a.K = L->K; a.n1 = L->n1; a.n2 = L->n2; a.r = L->r;
     a.R1 = (const float*)(blob + L->off_R1); a.R2 = (const float*)(blob + L->off_R2);
@@ -621,19 +669,38 @@ hipError_t bwla_launch_rotate_quant(const bwla_layer_t* L, const void* dX, int x
     a.counters = (int*)dws;
     a.partials = dws ? (float*)((char*)dws + bwla_align256((uint64_t)plan.token_tiles * sizeof(int))) : nullptr;
     a.S = plan.splits;
-    hipError_t e;
-    if (xdtype == BWLA_X_BF16) {
-        static bwla_lds_attr attr;
-        e = attr.ensure((const void*)rotate_quant_kernel<true>, lds);
-        if (e != hipSuccess) return e;
-        rotate_quant_kernel<true><<<dim3((unsigned)blocks), dim3(RQ_THREADS), lds, st>>>(a);
+    const int64_t pblocks = L->r > 0 ? (int64_t)plan.token_tiles * plan.splits : 0;
+    const size_t plds = L->r > 0 ? pp_lds_bytes(L->r) : 0;
+    // Few tokens: one launch holds rotation and projection workgroups (a second launch would
+    // cost more than it saves).  Many tokens: two launches, so that the projection workgroups
+    // are not limited to one per CU by the rotation's LDS size.
+    struct Launch { int64_t blocks, rot; size_t lds; } launches[2];
+    int nl = 0;
+    if (M <= 16 || pblocks == 0) {
+        launches[nl++] = {M + pblocks, M, plds > sh.lds_bytes ? plds : sh.lds_bytes};
     } else {
-        static bwla_lds_attr attr;
-        e = attr.ensure((const void*)rotate_quant_kernel<false>, lds);
-        if (e != hipSuccess) return e;
-        rotate_quant_kernel<false><<<dim3((unsigned)blocks), dim3(RQ_THREADS), lds, st>>>(a);
+        launches[nl++] = {M, M, sh.lds_bytes};
+        launches[nl++] = {pblocks, 0, plds};
     }
-    return hipGetLastError();
+    for (int i = 0; i < nl; ++i) {
+        a.rot_blocks = launches[i].rot;
+        const size_t lds = launches[i].lds;
+        hipError_t e;
+        if (xdtype == BWLA_X_BF16) {
+            static bwla_lds_attr attr;
+            e = attr.ensure((const void*)rotate_quant_kernel<true>, lds);
+            if (e != hipSuccess) return e;
+            rotate_quant_kernel<true><<<dim3((unsigned)launches[i].blocks), dim3(RQ_THREADS), lds, st>>>(a);
+        } else {
+            static bwla_lds_attr attr;
+            e = attr.ensure((const void*)rotate_quant_kernel<false>, lds);
+            if (e != hipSuccess) return e;
+            rotate_quant_kernel<false><<<dim3((unsigned)launches[i].blocks), dim3(RQ_THREADS), lds, st>>>(a);
+        }
+        e = hipGetLastError();
+        if (e != hipSuccess) return e;
+    }
+    return hipSuccess;
 }
 
 hipError_t bwla_launch_code_sums(const int8_t* dq, int64_t M, int64_t K, int32_t* dqsum, hipStream_t st) {
