@@ -61,7 +61,7 @@ typedef enum {
  *          interchange view); 16-row tiles x 512-column chunks, 1 KiB each
  *   alpha  N fp16, alpha_n = mean_k |W_rot[n,k]|            (paper App. A.2.4)
  *   V      N x rp fp16 row-major, rp = r rounded up to a multiple of 16, zero padded
- *   U      K x rp fp16 row-major, zero padded
+ *   U      rp x K fp16: U transposed (row j holds column j of U), rows r..rp-1 zero
  *   R1     n1 x n1 fp32 row-major;  R2  n2 x n2 fp32 row-major
  */
 typedef struct bwla_layer {

@@ -23,13 +23,23 @@ static inline int64_t bwla_row_tiles(int64_t N) { return (N + BWLA_TILE_ROWS - 1
 static inline int64_t bwla_chunks(int64_t K) { return (K + BWLA_CHUNK_COLS - 1) / BWLA_CHUNK_COLS; }
 static inline uint64_t bwla_align256(uint64_t x) { return (x + 255u) & ~uint64_t(255); }
 
-// PSP projection (T = X U) launch plan: token tiles of 16, S slices of K.
+// PSP projection (T = X U) launch plan: token tiles x column groups x S slices of K.  Up to 16
+// tokens the projection rides in the rotation launch (tiles of 16 tokens x rp columns); above,
+// a kernel of its own takes tiles of 64 tokens x up to 64 columns.
 struct bwla_psp_plan {
     int token_tiles;
     int splits;        // S
     int k_per_split;   // columns of K per slice
+    int tile_rows;     // tokens per tile (16 or 64)
+    int tile_cols;     // columns per tile
+    int col_groups;    // tiles across the rank
 };
 bwla_psp_plan bwla_make_psp_plan(int64_t M, int64_t K, int r);
+// scratch starts with one arrival counter per 16 tokens (whatever the plan), padded to 256 bytes
+inline uint64_t bwla_psp_counter_bytes(int64_t M) { return bwla_align256((uint64_t)((M + 15) / 16) * sizeof(int)); }
+int bwla_psp_prefill_tile_cols(int rp);
+hipError_t bwla_launch_psp_prefill(const bwla_layer_t* L, const void* dX, int xdtype, int64_t M, float* dT,
+                                   void* dws, const bwla_psp_plan& plan, hipStream_t st);
 
 // Raises a kernel's dynamic-LDS limit once per process and size class (per device 0..15), so
 // that steady-state launches, also under stream capture, issue no attribute calls.
@@ -58,6 +68,30 @@ hipError_t bwla_launch_unpack(const bwla_layer_t* L, int8_t* d_sgn, float* d_alp
 hipError_t bwla_launch_rotate_quant(const bwla_layer_t* L, const void* dX, int xdtype, int64_t M, int8_t* dq,
                                     float* dscale, int32_t* dqsum, float* dT, void* dws, const bwla_psp_plan& plan,
                                     hipStream_t st);
+#if defined(__HIPCC__)
+// Split-K hand-over between workgroups of one launch.  The GPU has one L2 per XCD, and a
+// device-scope fence is paid with a write-back / invalidate of that whole cache.  Instead the
+// partial sums themselves are moved with device-scope accesses (they bypass the non-coherent
+// levels), and ordering comes from waiting for those stores before the arrival counter is
+// bumped: publish = stores + bwla_partials_arrive(), consume = loads after it returned true.
+__device__ __forceinline__ void bwla_store_agent(float* p, float v) {
+    __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ float bwla_load_agent(const float* p) {
+    return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+// Called by every thread of the workgroup after its partial stores; true in the workgroup that
+// arrives last of `expected`.  `flag` is one int of LDS.
+__device__ __forceinline__ bool bwla_partials_arrive(int* counter, int expected, int* flag) {
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");     // my stores have completed
+    __syncthreads();
+    if (threadIdx.x == 0)
+        *flag = __hip_atomic_fetch_add(counter, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) == expected - 1;
+    __syncthreads();
+    return *flag != 0;
+}
+#endif
+
 hipError_t bwla_launch_code_sums(const int8_t* dq, int64_t M, int64_t K, int32_t* dqsum, hipStream_t st);
 
 hipError_t bwla_launch_gemm_decode(const bwla_layer_t* L, const int8_t* dq, const float* dscale,

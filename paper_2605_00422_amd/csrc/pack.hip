@@ -69,6 +69,15 @@ __global__ void f32_to_f16_rows_kernel(const float* __restrict__ src, int64_t ro
     dst[i] = col < r ? __float2half_rn(src[row * r + col]) : __float2half_rn(0.0f);
 }
 
+// K x r fp32 -> rp x K fp16, transposed (rows r..rp-1 zero)
+__global__ void u_transpose_f16_kernel(const float* __restrict__ U, int64_t K, int r, int rp,
+                                       __half* __restrict__ Ut) {
+    const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i >= (int64_t)rp * K) return;
+    const int64_t j = i / K, k = i - j * K;
+    Ut[i] = j < r ? __float2half_rn(U[k * r + j]) : __float2half_rn(0.0f);
+}
+
 __global__ void copy_f32_kernel(const float* __restrict__ src, int64_t n, float* __restrict__ dst) {
     const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
     if (i < n) dst[i] = src[i];
@@ -104,7 +113,7 @@ hipError_t bwla_launch_pack(const float* dW, const float* dR1, const float* dR2,
         const int rp = (r + 15) & ~15;
         const int64_t nv = N * rp, nu = K * rp;
         f32_to_f16_rows_kernel<<<dim3((unsigned)((nv + 255) / 256)), dim3(256), 0, st>>>(dV, N, r, rp, (__half*)(blob + L->off_V));
-        f32_to_f16_rows_kernel<<<dim3((unsigned)((nu + 255) / 256)), dim3(256), 0, st>>>(dU, K, r, rp, (__half*)(blob + L->off_U));
+        u_transpose_f16_kernel<<<dim3((unsigned)((nu + 255) / 256)), dim3(256), 0, st>>>(dU, K, r, rp, (__half*)(blob + L->off_U));
     }
     const int64_t e1 = (int64_t)n1 * n1, e2 = (int64_t)n2 * n2;
     copy_f32_kernel<<<dim3((unsigned)((e1 + 255) / 256)), dim3(256), 0, st>>>(dR1, e1, (float*)(blob + L->off_R1));

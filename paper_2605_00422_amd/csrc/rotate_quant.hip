@@ -1,20 +1,23 @@
-// bwla_rotate_quant in one launch: workgroups [0, M) rotate and quantize one token each,
-// the workgroups behind them compute the PSP projection T = X U.
+// bwla_rotate_quant: workgroups [0, M) rotate and quantize one token each; for up to 16
+// tokens the workgroups behind them compute the PSP projection T = X U in the same launch.
 //
 // Rotation (paper Sec. 3.1; App. A.2.2), per token on the row-major n1 x n2 reshape V:
 //   X~[t, c*n2 + d] = sum_{a,b} X[t, a*n2 + b] R1[a,c] R2[b,d]   =   (R1^T (V R2))[c,d]
-//   stage 1  Z = V R2      stage 2  Y = R1^T Z          (fp32 MFMA 16x16x4)
-// The token tile lives in LDS, Z replaces V in place (through the accumulators), and Y never
+//   stage 1  Z = V R2      stage 2  Y^T = Z^T R1        (fp32 MFMA 16x16x4)
+// The token tile lives in LDS, Z^T replaces V in place (through the accumulators), and Y never
 // leaves registers before it is quantized:
 //   amax = max |Y|, scale = amax / 31, q = clamp(rint(Y * 31 / amax)), qsum = sum q.
-// When both factors fit into LDS next to the token they are loaded once, together with the
-// token ("resident" mode: one global round trip, four barriers in total -- the decode case);
-// otherwise they are streamed in 8-row chunks through a double buffer.
+// All LDS operands are laid out with the contraction index along the row, so a lane fetches the
+// four contraction values of four MFMA steps with one 128-bit read.  When both factors fit into
+// LDS next to the token they are loaded once, together with the token ("resident" mode: one
+// global round trip, four barriers -- the decode case); otherwise they are streamed in chunks
+// of 16 contraction indices through a register ring and an LDS double buffer.
 //
-// PSP projection (paper Sec. 3.2), T = X U from the un-rotated, un-quantized activations:
-// a workgroup takes 16 tokens x 512 columns of K, stages its slice of U (fp16) in LDS with
-// 16-byte loads and multiplies on fp32 MFMA.  With several slices, every workgroup writes its
-// partial tile to scratch and the one that arrives last adds them in slice order.
+// PSP projection (paper Sec. 3.2), T = X U from the un-rotated, un-quantized activations, few
+// tokens: a workgroup takes 16 tokens x 512 columns of K, reads its operands (activations and
+// the transposed fp16 U) straight from global memory and multiplies on fp32 MFMA.  With several
+// slices, every workgroup writes its partial tile to scratch and the one that arrives last adds
+// them in slice order.
 #include "bwla_internal.h"
 
 namespace {
@@ -74,9 +77,7 @@ __host__ __device__ inline RqShape rq_shape(int n1, int n2) {
 
 __host__ __device__ inline size_t pp_lds_bytes(int r) {
     const int rp = ((r + 15) >> 4) * 16;
-    const size_t us = (size_t)PP_SLICE * (rp + 8) * 2;                 // U slice, fp16, padded pitch
-    const size_t red = (size_t)RQ_WAVES * (rp / 16) * 64 * 16;         // cross-wave reduction (reuses the slice)
-    return (us > red ? us : red) + 16;
+    return (size_t)RQ_WAVES * (rp / 16) * 64 * 16 + 16;                // cross-wave reduction
 }
 
 // Exact n / d for n * d < 2^32 with one multiply-high; index arithmetic on run-time factor
@@ -491,64 +492,53 @@ __device__ __forceinline__ void psp_block(char* smem, const void* __restrict__ X
     __shared__ int is_last;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int li = lane & 15, lg = lane >> 4;
-    const int JT = (r + 15) >> 4, rp = JT * 16, pitch = rp + 8;
-    __half* Us = reinterpret_cast<__half*>(smem);
+    const int JT = (r + 15) >> 4, rp = JT * 16;
     const int64_t kbase = (int64_t)s * PP_SLICE;
 
-    // activations of my 64 columns first (they do not depend on LDS): 4 groups of 16 columns,
-    // lane (li, lg) owns columns 16*g + 4*lg + e, e = 0..3, of token li in MFMA step e
+    // wave w takes columns [64w, 64w+64) of the slice in 4 groups of 16: lane (li, lg) owns
+    // k = 16*g + 4*lg + e, e = 0..3 -- of token li as MFMA operand A, of column jt*16 + li of U as
+    // operand B (8 contiguous bytes of the transposed U).  All loads are issued before the first use.
     int64_t trow = (int64_t)tt * 16 + li;
     if (trow > M - 1) trow = M - 1;                    // padded token rows are never stored
     float x[4][4];
+    uint2 u[4][PP_MAXJT];
 #pragma unroll
     for (int g = 0; g < 4; ++g) {
         const int64_t kx = kbase + wave * 64 + g * 16 + 4 * lg;
-        if (kx < K) {
-            if (BF16) {
-                const uint2 raw = *reinterpret_cast<const uint2*>(reinterpret_cast<const uint16_t*>(X) + trow * K + kx);
-                x[g][0] = __uint_as_float(raw.x << 16); x[g][1] = __uint_as_float(raw.x & 0xffff0000u);
-                x[g][2] = __uint_as_float(raw.y << 16); x[g][3] = __uint_as_float(raw.y & 0xffff0000u);
-            } else {
-                const float4 raw = *reinterpret_cast<const float4*>(reinterpret_cast<const float*>(X) + trow * K + kx);
-                x[g][0] = raw.x; x[g][1] = raw.y; x[g][2] = raw.z; x[g][3] = raw.w;
-            }
+        const bool in = kx < K;
+        const int64_t kc = in ? kx : K - 4;            // keep the address valid, zero the value
+        if (BF16) {
+            const uint2 raw = *reinterpret_cast<const uint2*>(reinterpret_cast<const uint16_t*>(X) + trow * K + kc);
+            x[g][0] = __uint_as_float(raw.x << 16); x[g][1] = __uint_as_float(raw.x & 0xffff0000u);
+            x[g][2] = __uint_as_float(raw.y << 16); x[g][3] = __uint_as_float(raw.y & 0xffff0000u);
         } else {
-            x[g][0] = x[g][1] = x[g][2] = x[g][3] = 0.0f;
+            const float4 raw = *reinterpret_cast<const float4*>(reinterpret_cast<const float*>(X) + trow * K + kc);
+            x[g][0] = raw.x; x[g][1] = raw.y; x[g][2] = raw.z; x[g][3] = raw.w;
         }
+        if (!in) x[g][0] = x[g][1] = x[g][2] = x[g][3] = 0.0f;
+#pragma unroll
+        for (int jt = 0; jt < PP_MAXJT; ++jt)
+            if (jt < JT) u[g][jt] = *reinterpret_cast<const uint2*>(U + (int64_t)(jt * 16 + li) * K + kc);
     }
-    // U slice -> LDS with 16-byte loads (rows past K are zero)
-    {
-        const int gpr = rp >> 3;                           // 16-byte granules per row
-        for (int idx = tid; idx < PP_SLICE * gpr; idx += RQ_THREADS) {
-            const int row = idx / gpr, g = idx - row * gpr;
-            uint4 v = make_uint4(0, 0, 0, 0);
-            if (kbase + row < K) v = *reinterpret_cast<const uint4*>(U + (kbase + row) * rp + g * 8);
-            *reinterpret_cast<uint4*>(Us + row * pitch + g * 8) = v;
-        }
-    }
-    __syncthreads();
 
     v4f acc[PP_MAXJT];
 #pragma unroll
     for (int jt = 0; jt < PP_MAXJT; ++jt) acc[jt] = v4f{0.f, 0.f, 0.f, 0.f};
-#pragma unroll 1
+#pragma unroll
     for (int g = 0; g < 4; ++g) {
-        const __half* up = Us + (wave * 64 + g * 16 + 4 * lg) * pitch + li;
-        const float xg[4] = {g == 0 ? x[0][0] : g == 1 ? x[1][0] : g == 2 ? x[2][0] : x[3][0],
-                             g == 0 ? x[0][1] : g == 1 ? x[1][1] : g == 2 ? x[2][1] : x[3][1],
-                             g == 0 ? x[0][2] : g == 1 ? x[1][2] : g == 2 ? x[2][2] : x[3][2],
-                             g == 0 ? x[0][3] : g == 1 ? x[1][3] : g == 2 ? x[2][3] : x[3][3]};
 #pragma unroll
         for (int jt = 0; jt < PP_MAXJT; ++jt) {
             if (jt < JT) {
-#pragma unroll
-                for (int e = 0; e < 4; ++e)
-                    acc[jt] = __builtin_amdgcn_mfma_f32_16x16x4f32(xg[e], __half2float(up[e * pitch + jt * 16]),
-                                                                  acc[jt], 0, 0, 0);
+                const __half2 h01 = *reinterpret_cast<const __half2*>(&u[g][jt].x);
+                const __half2 h23 = *reinterpret_cast<const __half2*>(&u[g][jt].y);
+                const float2 f01 = __half22float2(h01), f23 = __half22float2(h23);
+                acc[jt] = __builtin_amdgcn_mfma_f32_16x16x4f32(x[g][0], f01.x, acc[jt], 0, 0, 0);
+                acc[jt] = __builtin_amdgcn_mfma_f32_16x16x4f32(x[g][1], f01.y, acc[jt], 0, 0, 0);
+                acc[jt] = __builtin_amdgcn_mfma_f32_16x16x4f32(x[g][2], f23.x, acc[jt], 0, 0, 0);
+                acc[jt] = __builtin_amdgcn_mfma_f32_16x16x4f32(x[g][3], f23.y, acc[jt], 0, 0, 0);
             }
         }
     }
-    __syncthreads();                                   // the U slice is dead: reuse it for the reduction
     v4f* red = reinterpret_cast<v4f*>(smem);           // [wave][jt][lane]
 #pragma unroll
     for (int jt = 0; jt < PP_MAXJT; ++jt)
@@ -566,29 +556,30 @@ __device__ __forceinline__ void psp_block(char* smem, const void* __restrict__ X
             if (S == 1) {
                 if (tok < M && col < r) T[tok * r + col] = sum[v];
             } else {
-                partials[(((int64_t)tt * S + s) * 16 + row) * rp + col] = sum[v];
+                bwla_store_agent(&partials[(((int64_t)tt * S + s) * 16 + row) * rp + col], sum[v]);
             }
         }
     }
     if (S == 1) return;
 
-    __threadfence();
-    __syncthreads();
-    if (tid == 0) {
-        const int old = atomicAdd(&counters[tt], 1);
-        is_last = (old == S - 1);
-    }
-    __syncthreads();
-    if (!is_last) return;
-    __threadfence();
+    if (!bwla_partials_arrive(&counters[tt], S, &is_last)) return;
     // last workgroup of this token tile: add the S partial tiles in slice order
     for (int idx = tid; idx < 16 * rp; idx += RQ_THREADS) {
         const int row = idx / rp, col = idx - row * rp;
         const int64_t tok = (int64_t)tt * 16 + row;
         if (tok < M && col < r) {
+            // batches of eight loads in flight; slices past S re-read the last one and add zero
             float sum = 0.0f;
-            for (int ss = 0; ss < S; ++ss)
-                sum += __builtin_nontemporal_load(&partials[(((int64_t)tt * S + ss) * 16 + row) * rp + col]);
+            for (int ss = 0; ss < S; ss += 8) {
+                float v[8];
+#pragma unroll
+                for (int u = 0; u < 8; ++u) {
+                    const int sc = ss + u < S ? ss + u : S - 1;
+                    v[u] = bwla_load_agent(&partials[(((int64_t)tt * S + sc) * 16 + row) * rp + col]);
+                }
+#pragma unroll
+                for (int u = 0; u < 8; ++u) sum += ss + u < S ? v[u] : 0.0f;
+            }
             T[tok * r + col] = sum;
         }
     }
@@ -650,9 +641,27 @@ int bwla_rotate_max_tiles() { return RQ_MAXT * RQ_WAVES; }
 
 bwla_psp_plan bwla_make_psp_plan(int64_t M, int64_t K, int r) {
     bwla_psp_plan p;
-    p.token_tiles = (int)((M + 15) / 16);
-    p.k_per_split = PP_SLICE;
-    p.splits = r > 0 ? (int)((K + PP_SLICE - 1) / PP_SLICE) : 1;
+    const int rp = (r + 15) & ~15;
+    if (M <= 16 || r <= 0) {
+        p.token_tiles = (int)((M + 15) / 16);
+        p.k_per_split = PP_SLICE;
+        p.splits = r > 0 ? (int)((K + PP_SLICE - 1) / PP_SLICE) : 1;
+        p.tile_rows = 16; p.tile_cols = rp; p.col_groups = 1;
+        return p;
+    }
+    // many tokens: about three workgroups per CU, slices a multiple of 128 (4 wavefronts x 32)
+    p.tile_rows = 64;
+    p.tile_cols = bwla_psp_prefill_tile_cols(rp);
+    p.col_groups = (rp + 63) / 64;
+    p.token_tiles = (int)((M + 63) / 64);
+    const int64_t units = (int64_t)p.token_tiles * p.col_groups;
+    int64_t S = (768 + units - 1) / units;
+    const int64_t smax = K / 512 > 1 ? K / 512 : 1;
+    if (S > smax) S = smax;
+    if (S < 1) S = 1;
+    const int64_t per = (K + S - 1) / S;
+    p.k_per_split = (int)(((per + 127) / 128) * 128);
+    p.splits = (int)((K + p.k_per_split - 1) / p.k_per_split);
     return p;
 }
 
@@ -667,39 +676,30 @@ hipError_t bwla_launch_rotate_quant(const bwla_layer_t* L, const void* dX, int x
     a.U = (const __half*)(blob + L->off_U);
     a.q = dq; a.scale = dscale; a.qsum = dqsum; a.T = dT;
     a.counters = (int*)dws;
-    a.partials = dws ? (float*)((char*)dws + bwla_align256((uint64_t)plan.token_tiles * sizeof(int))) : nullptr;
+    a.partials = dws ? (float*)((char*)dws + bwla_psp_counter_bytes(M)) : nullptr;
     a.S = plan.splits;
-    const int64_t pblocks = L->r > 0 ? (int64_t)plan.token_tiles * plan.splits : 0;
-    const size_t plds = L->r > 0 ? pp_lds_bytes(L->r) : 0;
     // Few tokens: one launch holds rotation and projection workgroups (a second launch would
-    // cost more than it saves).  Many tokens: two launches, so that the projection workgroups
-    // are not limited to one per CU by the rotation's LDS size.
-    struct Launch { int64_t blocks, rot; size_t lds; } launches[2];
-    int nl = 0;
-    if (M <= 16 || pblocks == 0) {
-        launches[nl++] = {M + pblocks, M, plds > sh.lds_bytes ? plds : sh.lds_bytes};
-    } else {
-        launches[nl++] = {M, M, sh.lds_bytes};
-        launches[nl++] = {pblocks, 0, plds};
-    }
-    for (int i = 0; i < nl; ++i) {
-        a.rot_blocks = launches[i].rot;
-        const size_t lds = launches[i].lds;
-        hipError_t e;
-        if (xdtype == BWLA_X_BF16) {
-            static bwla_lds_attr attr;
-            e = attr.ensure((const void*)rotate_quant_kernel<true>, lds);
-            if (e != hipSuccess) return e;
-            rotate_quant_kernel<true><<<dim3((unsigned)launches[i].blocks), dim3(RQ_THREADS), lds, st>>>(a);
-        } else {
-            static bwla_lds_attr attr;
-            e = attr.ensure((const void*)rotate_quant_kernel<false>, lds);
-            if (e != hipSuccess) return e;
-            rotate_quant_kernel<false><<<dim3((unsigned)launches[i].blocks), dim3(RQ_THREADS), lds, st>>>(a);
-        }
-        e = hipGetLastError();
+    // cost more than it saves).  Many tokens: the projection has a kernel of its own.
+    const bool merged = L->r > 0 && plan.tile_rows == 16;
+    const int64_t pblocks = merged ? (int64_t)plan.token_tiles * plan.splits : 0;
+    const size_t plds = merged ? pp_lds_bytes(L->r) : 0;
+    const size_t lds = plds > sh.lds_bytes ? plds : sh.lds_bytes;
+    a.rot_blocks = M;
+    hipError_t e;
+    if (xdtype == BWLA_X_BF16) {
+        static bwla_lds_attr attr;
+        e = attr.ensure((const void*)rotate_quant_kernel<true>, lds);
         if (e != hipSuccess) return e;
+        rotate_quant_kernel<true><<<dim3((unsigned)(M + pblocks)), dim3(RQ_THREADS), lds, st>>>(a);
+    } else {
+        static bwla_lds_attr attr;
+        e = attr.ensure((const void*)rotate_quant_kernel<false>, lds);
+        if (e != hipSuccess) return e;
+        rotate_quant_kernel<false><<<dim3((unsigned)(M + pblocks)), dim3(RQ_THREADS), lds, st>>>(a);
     }
+    e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    if (L->r > 0 && !merged) return bwla_launch_psp_prefill(L, dX, xdtype, M, dT, dws, plan, st);
     return hipSuccess;
 }
 
