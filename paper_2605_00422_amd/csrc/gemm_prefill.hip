@@ -179,6 +179,329 @@ hipError_t launch_cfg(const bwla_layer_t* L, const int8_t* dq, const float* dsca
     return hipGetLastError();
 }
 
+// ------------------------------------------------------------------------------------------
+// Large token batches: every wavefront streams its own operands and synchronizes with nobody --
+// no workgroup barriers.  A wavefront owns 64 token rows x NTL*32 output channels.  Per
+// 128-column slice of K
+//   * its 64 code rows travel global -> LDS asynchronously (16 bytes per lane, 8 lanes per
+//     128-byte row segment, no registers involved) into a private ring of four swizzled 8 KiB
+//     tiles, four slices ahead of their use; the MFMA operand layout is read back from there:
+//     lane (row l32, half lg) gets columns [64*lg, 64*lg + 64) of the slice, 16 per step;
+//   * the 16-byte bit slice of each of its NTL weight rows goes straight into a register ring,
+//     three slices ahead.
+// Step s of a slice contracts the 16-column group 4*lg + s on both operands.  The four
+// wavefronts of a workgroup share the weight rows (L1 hits) and take different token rows.
+//
+// The compiler cannot tell which ring tile an LDS read touches and would wait for every
+// outstanding asynchronous copy before each read.  The operand reads are therefore issued as
+// inline assembly, paired with explicit waits: `s_waitcnt vmcnt(GD_YOUNGER)` for the copy that
+// must have landed (the count of younger vector-memory operations is fixed by the issue order
+// documented at the loop) and `s_waitcnt lgkmcnt(0)` before a read's registers are consumed.
+constexpr int GD_MT = 2;
+constexpr int GD_ROWS = GD_MT * 32;                 // token rows per wavefront
+constexpr int GD_TILE = GD_ROWS * 128;              // bytes of one private code tile
+constexpr int GD_BUFS = 4;                          // private code tiles per wavefront
+
+typedef __attribute__((ext_vector_type(8))) __bf16 v8bf;
+
+// x = h1 + h2 + h3 exactly, each a bf16
+__device__ __forceinline__ void gd_split3(float x, __bf16& h1, __bf16& h2, __bf16& h3) {
+    h1 = (__bf16)x;
+    const float r1 = x - (float)h1;
+    h2 = (__bf16)r1;
+    h3 = (__bf16)(r1 - (float)h2);
+}
+
+// 16-byte position of piece `c16` of row `row` inside its 128-byte LDS row; the XOR key makes
+// the column-wise operand reads conflict free
+__device__ __forceinline__ int gd_key(int row) { return (row ^ (row >> 3)) & 7; }
+
+__device__ __forceinline__ v4i gd_lds_read(uint32_t addr) {
+    v4i r;
+    asm volatile("ds_read_b128 %0, %1" : "=v"(r) : "v"(addr));
+    return r;
+}
+// s_waitcnt immediate for vmcnt(n) alone on gfx9 encodings: vmcnt = bits 3:0 and 15:14,
+// expcnt (6:4) and lgkmcnt (11:8) left at "no wait"
+constexpr int gd_vmcnt_imm(int n) { return (n & 15) | ((n >> 4) << 14) | (7 << 4) | (15 << 8); }
+
+template <int NTL>
+__global__ __launch_bounds__(256) void gemm_prefill_direct_kernel(
+    const uint4* __restrict__ bits, int chunks, int row_tiles, const int8_t* __restrict__ q, int M, int K,
+    const float* __restrict__ scale, const int32_t* __restrict__ qsum, const __half* __restrict__ alpha,
+    const __half* __restrict__ V, const float* __restrict__ T, int r, float* __restrict__ Y, int N,
+    int32_t* __restrict__ acc_out, int tiles_m, int tiles_n) {
+    constexpr int MT = GD_MT;
+    constexpr int BM = 4 * GD_ROWS, BN = NTL * 32;
+    // vector-memory operations per slice and wavefront: 8 code copies, then NTL weight loads
+    constexpr int GD_YOUNGER = NTL + 2 * (8 + NTL);
+    extern __shared__ __align__(16) char smem[];
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wm = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int l32 = lane & 31, lg = lane >> 5;
+    char* mytile = smem + wm * (GD_BUFS * GD_TILE);
+    const uint32_t mytile_lds = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) char*)mytile;
+
+    // XCD-aware tile order (workgroups are dealt round-robin to the 8 XCDs): one XCD works on
+    // runs of tiles with the same token rows, so the codes are fetched once per XCD
+    int pid = blockIdx.x;
+    const int nblocks = gridDim.x;
+    if ((nblocks & 7) == 0) pid = (pid & 7) * (nblocks >> 3) + (pid >> 3);
+    const int tm = pid / tiles_n, tn = pid - tm * tiles_n;
+    const int m_base = tm * BM + wm * GD_ROWS, n_base = tn * BN;
+    const int nslices = K >> 7;                                  // K % 128 == 0 (checked by the launcher)
+
+    // asynchronous copies: instruction j moves rows 8j .. 8j+7; lane i lands at row i/8,
+    // position i%8 and therefore fetches piece (i%8) ^ key(row).  Row groups past the matrix
+    // re-read its last eight rows (their results are not stored).
+    const int8_t* abase[8];
+    int avofs[8];
+#pragma unroll
+    for (int j = 0; j < 8; ++j) {
+        int m0 = m_base + 8 * j;
+        if (m0 > M - 8) m0 = M - 8;                              // M >= 256 here
+        abase[j] = q + (int64_t)m0 * K;
+        const int row = 8 * j + (lane >> 3);
+        avofs[j] = (lane >> 3) * K + (((lane & 7) ^ gd_key(row)) << 4);
+    }
+    // operand reads: row mt*32 + l32, piece 4*lg + s
+    uint32_t rofs[MT][4];
+#pragma unroll
+    for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+        for (int s = 0; s < 4; ++s) {
+            const int row = mt * 32 + l32;
+            rofs[mt][s] = mytile_lds + row * 128 + ((((4 * lg + s) ^ gd_key(row)) & 7) << 4);
+        }
+    // weight rows nt*32 + l32: 16-row tile 2*nt + l32/16 of this workgroup's columns (tile pairs
+    // past the matrix re-read its last two tiles), row l32 % 16 inside it
+    const uint4* wbase[NTL];
+#pragma unroll
+    for (int nt = 0; nt < NTL; ++nt) {
+        int rt0 = (n_base >> 4) + 2 * nt;
+        if (rt0 > row_tiles - 2) rt0 = row_tiles - 2;            // N >= 32 here
+        wbase[nt] = bits + (int64_t)rt0 * chunks * 64;
+    }
+    const int wvofs = (l32 >> 4) * chunks * 64 + (l32 & 15);     // in 16-byte units
+    const int shamt = 4 * lg;
+
+    auto copy_codes = [&](int ks) {                              // 8 vector-memory operations
+        const int kc = ks < nslices ? ks : nslices - 1;          // past the end: any valid slice
+        char* dst = mytile + (ks & (GD_BUFS - 1)) * GD_TILE;
+#pragma unroll
+        for (int j = 0; j < 8; ++j)
+            __builtin_amdgcn_global_load_lds(
+                (const __attribute__((address_space(1))) void*)(abase[j] + (int64_t)kc * 128 + avofs[j]),
+                (__attribute__((address_space(3))) void*)(dst + j * 1024), 16, 0, 0);
+    };
+    struct Wslot { v4i w[NTL]; };                                // vector values: they stay in registers
+    auto fetch_w = [&](Wslot& sl, int ks) {                      // NTL vector-memory operations
+        const int kc = ks < nslices ? ks : nslices - 1;
+        const int so = (kc >> 2) * 64 + (kc & 3) * 16;
+#pragma unroll
+        for (int nt = 0; nt < NTL; ++nt) sl.w[nt] = *reinterpret_cast<const v4i*>(wbase[nt] + so + wvofs);
+    };
+
+    v16i acc[MT][NTL];
+#pragma unroll
+    for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+        for (int nt = 0; nt < NTL; ++nt)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) acc[mt][nt][v] = 0;
+
+    // Operands of one contraction step: code rows from LDS (asynchronous read, to be followed
+    // by settle()), expanded weight bits.
+    struct Ops { v4i av[MT]; v4i b[NTL]; };
+    auto prepare = [&](Ops& o, const Wslot& sl, int ks, int s) {
+        const uint32_t bo = (uint32_t)((ks & (GD_BUFS - 1)) * GD_TILE);
+#pragma unroll
+        for (int mt = 0; mt < MT; ++mt) o.av[mt] = gd_lds_read(rofs[mt][s] + bo);
+        // slices past the end (the trip count is padded to a multiple of three) contract zeros
+        const int mask = ks < nslices ? 0x01010101 : 0;
+#pragma unroll
+        for (int nt = 0; nt < NTL; ++nt) o.b[nt] = (sl.w[nt] >> (shamt + s)) & mask;
+    };
+    auto settle = [&](Ops& o) {
+        static_assert(MT == 2, "operand list of the wait below");
+        asm volatile("s_waitcnt lgkmcnt(0)" : "+v"(o.av[0]), "+v"(o.av[1]));
+    };
+    auto contract = [&](const Ops& o) {
+#pragma unroll
+        for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+            for (int nt = 0; nt < NTL; ++nt)
+                acc[mt][nt] = __builtin_amdgcn_mfma_i32_32x32x32_i8(o.av[mt], o.b[nt], acc[mt][nt], 0, 0, 0);
+    };
+
+    // Issue order of the vector-memory operations (it fixes GD_YOUNGER):
+    //   prologue  codes(0) codes(1) w(0) codes(2) w(1) codes(3) w(2)
+    //   step ks   ... codes(ks + 4) w(ks + 3)
+    // so at the top of step ks the operations younger than codes(ks + 1) are
+    // w(ks), codes(ks + 2), w(ks + 1), codes(ks + 3), w(ks + 2).  Step ks reads slice ks from
+    // tile ks % 4 (its first step's operands were prepared by step ks - 1) and prepares the
+    // first operands of slice ks + 1; when it is done the tile is free for slice ks + 4 and the
+    // weight slot for slice ks + 3.  Steps past the end copy a valid slice that nobody reads.
+    Wslot w0, w1, w2;
+    Ops ops;
+    auto step = [&](Wslot& cur, Wslot& nxt, int ks) {
+        __builtin_amdgcn_s_waitcnt(gd_vmcnt_imm(GD_YOUNGER));    // codes(ks + 1) have landed
+#pragma unroll
+        for (int s = 0; s < 4; ++s) {
+            Ops following;
+            if (s < 3) prepare(following, cur, ks, s + 1);
+            else prepare(following, nxt, ks + 1, 0);
+            contract(ops);
+            __builtin_amdgcn_sched_barrier(0);
+            settle(following);
+            ops = following;
+        }
+        copy_codes(ks + 4);
+        fetch_w(cur, ks + 3);
+        __builtin_amdgcn_sched_barrier(0);
+    };
+    copy_codes(0);
+    copy_codes(1);
+    fetch_w(w0, 0);
+    __builtin_amdgcn_sched_barrier(0);
+    copy_codes(2);
+    fetch_w(w1, 1);
+    __builtin_amdgcn_sched_barrier(0);
+    copy_codes(3);
+    fetch_w(w2, 2);
+    __builtin_amdgcn_sched_barrier(0);
+    __builtin_amdgcn_s_waitcnt(gd_vmcnt_imm(GD_YOUNGER + 8));    // codes(0) have landed
+    prepare(ops, w0, 0, 0);
+    settle(ops);
+    for (int ks0 = 0; ks0 < nslices; ks0 += 3) {
+        step(w0, w1, ks0);
+        step(w1, w2, ks0 + 1);
+        step(w2, w0, ks0 + 2);
+    }
+    __builtin_amdgcn_s_waitcnt(gd_vmcnt_imm(0));                 // drain the copies nobody reads
+
+    // ---- epilogue.  Accumulator element v of lane (l32, lg): row 8*(v/4) + 4*lg + v%4, column l32.
+    // Low-rank term on bf16 MFMA 32x32x16 with exact operand splits (T: three terms, V: two):
+    // per 16 ranks one T fragment and NTL V fragments are loaded one step ahead of their use.
+    const int JT = (r + 15) >> 4, rp = JT * 16;
+    int ncol[NTL];
+    float al[NTL];
+#pragma unroll
+    for (int nt = 0; nt < NTL; ++nt) {
+        const int n = n_base + nt * 32 + l32;
+        ncol[nt] = n < N ? n : N - 1;
+        al[nt] = __half2float(alpha[ncol[nt]]);
+    }
+    struct Raw { float4 t[2]; uint4 v[NTL]; };
+#pragma unroll
+    for (int mt = 0; mt < MT; ++mt) {
+        const int mrow0 = m_base + mt * 32;
+        if (mrow0 >= M) continue;
+        int tmr = mrow0 + l32;
+        if (tmr > M - 1) tmr = M - 1;
+        auto load_raw = [&](Raw& rw, int kk) {
+            const int j0 = kk * 16 + 8 * lg;
+            const float* tp = T + (int64_t)tmr * r + j0;
+            if ((r & 3) == 0) {
+                // whole groups of four are inside or outside the row; clamp the address, zero the value
+                const float4 z = make_float4(0.f, 0.f, 0.f, 0.f);
+                const float4 t0 = *reinterpret_cast<const float4*>(j0 < r ? tp : T);
+                const float4 t1 = *reinterpret_cast<const float4*>(j0 + 4 < r ? tp + 4 : T);
+                rw.t[0] = j0 < r ? t0 : z;
+                rw.t[1] = j0 + 4 < r ? t1 : z;
+            } else {
+                float e[8];
+#pragma unroll
+                for (int i = 0; i < 8; ++i) e[i] = j0 + i < r ? tp[i] : 0.0f;
+                rw.t[0] = make_float4(e[0], e[1], e[2], e[3]);
+                rw.t[1] = make_float4(e[4], e[5], e[6], e[7]);
+            }
+#pragma unroll
+            for (int nt = 0; nt < NTL; ++nt)
+                rw.v[nt] = *reinterpret_cast<const uint4*>(V + (int64_t)ncol[nt] * rp + j0);
+        };
+        v16f low[NTL];
+#pragma unroll
+        for (int nt = 0; nt < NTL; ++nt)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) low[nt][v] = 0.0f;
+        if (JT > 0) {
+            Raw cur, nxt;
+            load_raw(cur, 0);
+            for (int kk = 0; kk < JT; ++kk) {
+                load_raw(nxt, kk + 1 < JT ? kk + 1 : JT - 1);
+                const float tv[8] = {cur.t[0].x, cur.t[0].y, cur.t[0].z, cur.t[0].w,
+                                     cur.t[1].x, cur.t[1].y, cur.t[1].z, cur.t[1].w};
+                v8bf t1, t2, t3;
+#pragma unroll
+                for (int e = 0; e < 8; ++e) {
+                    __bf16 h1, h2, h3;
+                    gd_split3(tv[e], h1, h2, h3);
+                    t1[e] = h1; t2[e] = h2; t3[e] = h3;
+                }
+#pragma unroll
+                for (int nt = 0; nt < NTL; ++nt) {
+                    v8bf vh, vl;
+                    const __half2* h2p = reinterpret_cast<const __half2*>(&cur.v[nt]);
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) {
+                        const float2 f = __half22float2(h2p[e]);
+                        const __bf16 a0 = (__bf16)f.x, a1 = (__bf16)f.y;
+                        vh[2 * e] = a0; vh[2 * e + 1] = a1;
+                        vl[2 * e] = (__bf16)(f.x - (float)a0); vl[2 * e + 1] = (__bf16)(f.y - (float)a1);
+                    }
+                    low[nt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(t3, vl, low[nt], 0, 0, 0);
+                    low[nt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(t2, vl, low[nt], 0, 0, 0);
+                    low[nt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(t3, vh, low[nt], 0, 0, 0);
+                    low[nt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(t1, vl, low[nt], 0, 0, 0);
+                    low[nt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(t2, vh, low[nt], 0, 0, 0);
+                    low[nt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(t1, vh, low[nt], 0, 0, 0);
+                }
+                cur = nxt;
+            }
+        }
+        float sc[16];
+        int qs[16];
+#pragma unroll
+        for (int v = 0; v < 16; ++v) {
+            int m = mrow0 + 8 * (v >> 2) + 4 * lg + (v & 3);
+            if (m > M - 1) m = M - 1;
+            sc[v] = scale[m];
+            qs[v] = qsum[m];
+        }
+#pragma unroll
+        for (int nt = 0; nt < NTL; ++nt) {
+            const int n = n_base + nt * 32 + l32;
+#pragma unroll
+            for (int v = 0; v < 16; ++v) {
+                const int m = mrow0 + 8 * (v >> 2) + 4 * lg + (v & 3);
+                if (m < M && n < N) {
+                    const int a = 2 * acc[mt][nt][v] - qs[v];
+                    Y[(int64_t)m * N + n] = sc[v] * al[nt] * (float)a + low[nt][v];
+                    if (acc_out) acc_out[(int64_t)m * N + n] = a;
+                }
+            }
+        }
+    }
+}
+
+template <int NTL>
+hipError_t launch_direct(const bwla_layer_t* L, const int8_t* dq, const float* dscale, const int32_t* dqsum,
+                         const float* dT, int64_t M, float* dY, int32_t* dacc, hipStream_t st) {
+    constexpr int BM = 4 * GD_ROWS, BN = NTL * 32;
+    const char* blob = (const char*)L->d_blob;
+    const int tiles_m = (int)((M + BM - 1) / BM), tiles_n = (int)((L->N + BN - 1) / BN);
+    const size_t lds = (size_t)4 * GD_BUFS * GD_TILE;
+    static bwla_lds_attr attr;
+    hipError_t e = attr.ensure((const void*)gemm_prefill_direct_kernel<NTL>, lds);
+    if (e != hipSuccess) return e;
+    gemm_prefill_direct_kernel<NTL><<<dim3((unsigned)(tiles_m * tiles_n)), dim3(256), lds, st>>>(
+        (const uint4*)(blob + L->off_bits), (int)bwla_chunks(L->K), (int)bwla_row_tiles(L->N), dq, (int)M,
+        (int)L->K, dscale, dqsum, (const __half*)(blob + L->off_alpha), (const __half*)(blob + L->off_V), dT,
+        L->r, dY, (int)L->N, dacc, tiles_m, tiles_n);
+    return hipGetLastError();
+}
+
 inline int64_t tiles_for(int64_t M, int64_t N, int BM, int BN) { return ((M + BM - 1) / BM) * ((N + BN - 1) / BN); }
 
 // fraction of the chip kept busy by `tiles` equal workgroups on 256 CUs (last round may be ragged)
@@ -194,6 +517,12 @@ hipError_t bwla_launch_gemm_prefill(const bwla_layer_t* L, const int8_t* dq, con
                                     int32_t* dacc, hipStream_t st) {
     const int64_t N = L->N;
     if (M <= 64) return launch_cfg<1, 2, 2, 2>(L, dq, dscale, dqsum, dT, M, dY, dacc, st);          // 64 x 128
+    if (M >= 256 && N >= 32 && (L->K & 127) == 0) {
+        // register-streaming kernel, 256 x 160 or 256 x 128 tiles, whichever fills the chip better
+        const double d160 = wave_eff(tiles_for(M, N, 256, 160)), d128 = wave_eff(tiles_for(M, N, 256, 128));
+        if (d160 >= d128) return launch_direct<5>(L, dq, dscale, dqsum, dT, M, dY, dacc, st);
+        return launch_direct<4>(L, dq, dscale, dqsum, dT, M, dY, dacc, st);
+    }
     // pick the largest tile that still fills the chip reasonably
     const double e256 = wave_eff(tiles_for(M, N, 256, 256));
     const double e160 = wave_eff(tiles_for(M, N, 256, 160));
