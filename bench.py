@@ -25,6 +25,15 @@ HBM_PEAK_GBPS = 8000.0        # MI355X HBM3E
 INT8_PEAK_TOPS = 5000.0       # dense INT8 MFMA
 CACHE_DEFEAT_BYTES = 512 << 20
 
+# HBM bytes per bwla_linear_forward launch measured with rocprofv3 --pmc (FETCH_SIZE and
+# WRITE_SIZE in separate runs, each scaled by what the same counter reads for a plain device
+# copy of known size in the same run); the runs and their figures are summarised in
+# profiles/pmc_hbm_traffic_linear_forward.txt.  None = not measured for that workload.
+MEASURED_TRAFFIC_BYTES = {
+    "cfg1_decode7b": 6685964,                 # fetch 6.64 MB + write 0.04 MB (algorithmic 6.41 MB)
+    "cfg3_qwen32b_down_m2048": 231902860,     # fetch 190.0 MB (8 XCDs x bits + codes) + write 41.9 MB
+}
+
 
 def linear_forward_bytes(cfg) -> int:
     """Algorithmic HBM bytes of one bwla_linear_forward launch: sign bits, alpha, V (fp16),
@@ -155,10 +164,23 @@ def roofline_for(cfg, us_forward):
     if hbm_t >= mfma_t:
         a = linear_forward_bytes(cfg) / t / 1e9
         return {"bound": "hbm", "achieved": a, "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": a / HBM_PEAK_GBPS,
-                "traffic": None, "kernel": "bwla_linear_forward", "bytes_per_launch": linear_forward_bytes(cfg)}
+                "traffic": MEASURED_TRAFFIC_BYTES.get(cfg.name), "kernel": "bwla_linear_forward",
+                "bytes_per_launch": linear_forward_bytes(cfg), "us_per_launch": us_forward}
     a = gemm_ops(cfg) / t / 1e12
     return {"bound": "mfma", "achieved": a, "peak": INT8_PEAK_TOPS, "unit": "TOP/s", "frac": a / INT8_PEAK_TOPS,
-            "traffic": None, "kernel": "bwla_linear_forward", "ops_per_launch": gemm_ops(cfg)}
+            "traffic": MEASURED_TRAFFIC_BYTES.get(cfg.name), "kernel": "bwla_linear_forward",
+            "ops_per_launch": gemm_ops(cfg), "us_per_launch": us_forward}
+
+
+def side_kernel_report(cfg, us_rotate):
+    """bwla_rotate_quant beside the GEMM: its algorithmic bytes and flops against the same
+    peaks.  With one token it is a single workgroup and latency bound; it is reported so that
+    the share of the layer time it takes is visible."""
+    t = us_rotate * 1e-6
+    flops = 2 * cfg.M * cfg.K * (cfg.n1 + cfg.n2) + 2 * cfg.M * cfg.K * cfg.r
+    return {"kernel": "bwla_rotate_quant", "us_per_launch": us_rotate,
+            "bytes_per_launch": rotate_quant_bytes(cfg), "gbps": rotate_quant_bytes(cfg) / t / 1e9,
+            "flops_per_launch": flops, "tflops": flops / t / 1e12}
 
 
 def cpu_baseline(w, budget_s=12.0):
@@ -203,6 +225,8 @@ def main():
     ap.add_argument("--no-extra", action="store_true", help="skip the other configurations")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle baseline")
     ap.add_argument("--no-graph", action="store_true")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="also run three plain 256 MiB device copies (counter calibration under rocprofv3 --pmc)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only (no sharding or collectives); use --gpus 1",
@@ -223,6 +247,15 @@ def main():
             all_cfgs[c.name] = c
     cfg = all_cfgs[args.workload]
 
+    if args.calibrate_copy:
+        src = torch.empty(256 << 20, dtype=torch.uint8, device="cuda:0").fill_(1)
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
+        torch.cuda.empty_cache()
+
     w, res = measure(cfg, args.steps, args.warmup, not args.no_graph)
     best = res["stream"]
     mode = "stream"
@@ -235,7 +268,8 @@ def main():
         "metric": "us/layer, W1A6 linear forward (rotate+quant, binary GEMM + PSP + dequant)",
         "value": us_layer, "unit": "us/layer", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": us_layer / 1e3, "higher_is_better": False, "scaling": "weak", "vs_baseline": None,
-        "dtype": "int8 codes x 1-bit weights -> int32 (INT8 MFMA); fp32 rotation and epilogue",
+        "dtype": "int8",
+        "dtype_detail": "int8 codes x 1-bit weights -> int32 on INT8 MFMA; fp32 rotation, bf16/fp16-split MFMA side products, fp32 epilogue",
         "data": "synthetic",
         "config": {"workload": cfg.name, "M": cfg.M, "K": cfg.K, "N": cfg.N, "r": cfg.r,
                    "kron": f"{cfg.n1}x{cfg.n2}", "x_dtype": cfg.x_dtype, "launch_mode": mode,
@@ -245,6 +279,7 @@ def main():
         "us_linear_forward": us_fwd, "us_rotate_quant": best["us_rotate_quant"],
         "timings": {k: res[k] for k in ("stream", "graph") if k in res},
         "roofline": roof,
+        "side_kernels": [side_kernel_report(cfg, best["us_rotate_quant"])],
     }
     if not args.no_cpu:
         line["cpu_baseline"] = cpu_baseline(w)
@@ -264,6 +299,7 @@ def main():
             if "graph" in r and "us_per_layer" in r["graph"] and r["graph"]["us_per_layer"] < b["us_per_layer"]:
                 b = r["graph"]
             r["roofline"] = roofline_for(c, b["us_linear_forward"])
+            r["side_kernels"] = [side_kernel_report(c, b["us_rotate_quant"])]
             r["effective_tops"] = gemm_ops(c) / (b["us_per_layer"] * 1e-6) / 1e12
             extra.append(r)
             del ww

@@ -1,5 +1,5 @@
-// PSP projection T = X U for many tokens (the rank-r side branch of the forward, paper
-// Sec. 3.3 / Eq. 11, first factor).
+// PSP projection T = X U for many tokens: first factor of the rank-r side branch
+// (X U) V^T that carries the low-rank part of the weight (paper Sec. 3.2).
 //
 // The product is tall and thin (M x K times K x r with r <= 128), so it is bound by streaming X
 // once.  Both MFMA operands come straight from global memory as 16-byte vectors along K:
