@@ -187,16 +187,18 @@ hipError_t launch_cfg(const bwla_layer_t* L, const int8_t* dq, const float* dsca
 //     128-byte row segment, no registers involved) into a private ring of four swizzled 8 KiB
 //     tiles, four slices ahead of their use; the MFMA operand layout is read back from there:
 //     lane (row l32, half lg) gets columns [64*lg, 64*lg + 64) of the slice, 16 per step;
-//   * the 16-byte bit slice of each of its NTL weight rows goes straight into a register ring,
-//     three slices ahead.
+//   * the 16-byte bit slice of each of its NTL weight rows goes straight into a ring of four
+//     register slots, four slices ahead.
 // Step s of a slice contracts the 16-column group 4*lg + s on both operands.  The four
 // wavefronts of a workgroup share the weight rows (L1 hits) and take different token rows.
 //
-// The compiler cannot tell which ring tile an LDS read touches and would wait for every
-// outstanding asynchronous copy before each read.  The operand reads are therefore issued as
-// inline assembly, paired with explicit waits: `s_waitcnt vmcnt(GD_YOUNGER)` for the copy that
-// must have landed (the count of younger vector-memory operations is fixed by the issue order
-// documented at the loop) and `s_waitcnt lgkmcnt(0)` before a read's registers are consumed.
+// The compiler cannot tell which ring tile an LDS read touches, and with an asynchronous copy
+// in flight it turns every wait for a vector-memory result into a wait for all of them.  The
+// loop therefore issues its operand reads (LDS) and its weight loads (global) as inline
+// assembly and waits explicitly: `s_waitcnt vmcnt(GD_YOUNGER)` for the slice that must have
+// landed (the count of younger vector-memory operations is fixed by the issue order documented
+// at the loop) and `s_waitcnt lgkmcnt(0)` before an LDS read's registers are consumed.  A
+// register written by such a load is not touched between the load and its wait.
 constexpr int GD_MT = 2;
 constexpr int GD_ROWS = GD_MT * 32;                 // token rows per wavefront
 constexpr int GD_TILE = GD_ROWS * 128;              // bytes of one private code tile
@@ -233,8 +235,10 @@ __global__ __launch_bounds__(256) void gemm_prefill_direct_kernel(
     int32_t* __restrict__ acc_out, int tiles_m, int tiles_n) {
     constexpr int MT = GD_MT;
     constexpr int BM = 4 * GD_ROWS, BN = NTL * 32;
-    // vector-memory operations per slice and wavefront: 8 code copies, then NTL weight loads
-    constexpr int GD_YOUNGER = NTL + 2 * (8 + NTL);
+    // vector-memory operations per slice and wavefront: NTL weight loads, then 8 code copies;
+    // when slice j + 1 is needed, the operations of slices j + 2 and j + 3 may still be in flight
+    constexpr int GD_PER_SLICE = NTL + 8;
+    constexpr int GD_YOUNGER = 2 * GD_PER_SLICE;
     extern __shared__ __align__(16) char smem[];
     const int tid = threadIdx.x, lane = tid & 63;
     const int wm = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -299,7 +303,15 @@ __global__ __launch_bounds__(256) void gemm_prefill_direct_kernel(
         const int kc = ks < nslices ? ks : nslices - 1;
         const int so = (kc >> 2) * 64 + (kc & 3) * 16;
 #pragma unroll
-        for (int nt = 0; nt < NTL; ++nt) sl.w[nt] = *reinterpret_cast<const v4i*>(wbase[nt] + so + wvofs);
+        for (int nt = 0; nt < NTL; ++nt) {
+            const uint4* p = wbase[nt] + so + wvofs;
+            asm volatile("global_load_dwordx4 %0, %1, off" : "=v"(sl.w[nt]) : "v"(p) : "memory");
+        }
+    };
+    // marks the point after which a slot's registers hold their data (placed behind the wait)
+    auto landed = [&](Wslot& sl) {
+#pragma unroll
+        for (int nt = 0; nt < NTL; ++nt) asm volatile("" : "+v"(sl.w[nt]));
     };
 
     v16i acc[MT][NTL];
@@ -335,50 +347,62 @@ __global__ __launch_bounds__(256) void gemm_prefill_direct_kernel(
     };
 
     // Issue order of the vector-memory operations (it fixes GD_YOUNGER):
-    //   prologue  codes(0) codes(1) w(0) codes(2) w(1) codes(3) w(2)
-    //   step ks   ... codes(ks + 4) w(ks + 3)
-    // so at the top of step ks the operations younger than codes(ks + 1) are
-    // w(ks), codes(ks + 2), w(ks + 1), codes(ks + 3), w(ks + 2).  Step ks reads slice ks from
-    // tile ks % 4 (its first step's operands were prepared by step ks - 1) and prepares the
-    // first operands of slice ks + 1; when it is done the tile is free for slice ks + 4 and the
-    // weight slot for slice ks + 3.  Steps past the end copy a valid slice that nobody reads.
-    Wslot w0, w1, w2;
+    //   prologue  w(0) codes(0) w(1) codes(1) w(2) codes(2) w(3) codes(3)
+    //   step ks   ... w(ks + 4) codes(ks + 4)
+    // Step ks reads slice ks from tile ks % 4 and weight slot ks % 4 (its first step's operands
+    // were prepared by step ks - 1).  Before its last contraction step it needs slice ks + 1 for
+    // the first operands of the next slice: at that point the operations younger than
+    // codes(ks + 1) are those of slices ks + 2 and ks + 3.  When step ks is done, its tile and
+    // slot are free for slice ks + 4.  Slices past the end (the trip count is padded to a multiple
+    // of four) re-read a valid slice and contract zeros.
+    Wslot w0, w1, w2, w3;
     Ops ops;
     auto step = [&](Wslot& cur, Wslot& nxt, int ks) {
-        __builtin_amdgcn_s_waitcnt(gd_vmcnt_imm(GD_YOUNGER));    // codes(ks + 1) have landed
 #pragma unroll
         for (int s = 0; s < 4; ++s) {
             Ops following;
-            if (s < 3) prepare(following, cur, ks, s + 1);
-            else prepare(following, nxt, ks + 1, 0);
+            if (s < 3) {
+                prepare(following, cur, ks, s + 1);
+            } else {
+                __builtin_amdgcn_s_waitcnt(gd_vmcnt_imm(GD_YOUNGER));    // slice ks + 1 has landed
+                landed(nxt);
+                prepare(following, nxt, ks + 1, 0);
+            }
             contract(ops);
             __builtin_amdgcn_sched_barrier(0);
             settle(following);
             ops = following;
         }
+        fetch_w(cur, ks + 4);
         copy_codes(ks + 4);
-        fetch_w(cur, ks + 3);
         __builtin_amdgcn_sched_barrier(0);
     };
-    copy_codes(0);
-    copy_codes(1);
-    fetch_w(w0, 0);
+    fetch_w(w0, 0); copy_codes(0);
+    fetch_w(w1, 1); copy_codes(1);
+    fetch_w(w2, 2); copy_codes(2);
+    fetch_w(w3, 3); copy_codes(3);
     __builtin_amdgcn_sched_barrier(0);
-    copy_codes(2);
-    fetch_w(w1, 1);
-    __builtin_amdgcn_sched_barrier(0);
-    copy_codes(3);
-    fetch_w(w2, 2);
-    __builtin_amdgcn_sched_barrier(0);
-    __builtin_amdgcn_s_waitcnt(gd_vmcnt_imm(GD_YOUNGER + 8));    // codes(0) have landed
+    __builtin_amdgcn_s_waitcnt(gd_vmcnt_imm(3 * GD_PER_SLICE));  // slice 0 has landed
+    landed(w0);
     prepare(ops, w0, 0, 0);
     settle(ops);
-    for (int ks0 = 0; ks0 < nslices; ks0 += 3) {
+    for (int ks0 = 0; ks0 < nslices; ks0 += 4) {
         step(w0, w1, ks0);
         step(w1, w2, ks0 + 1);
-        step(w2, w0, ks0 + 2);
+        step(w2, w3, ks0 + 2);
+        step(w3, w0, ks0 + 3);
     }
-    __builtin_amdgcn_s_waitcnt(gd_vmcnt_imm(0));                 // drain the copies nobody reads
+    // Drain the loads nobody reads.  Their destination registers must stay reserved until they
+    // have landed, so the wait names all four slots as operands: without that the code behind
+    // the loop may reuse a register that a load still in flight is about to overwrite.
+    static_assert(NTL == 4 || NTL == 5, "operand lists of the drain below");
+    asm volatile("s_waitcnt vmcnt(0)"
+                 : "+v"(w0.w[0]), "+v"(w0.w[1]), "+v"(w0.w[2]), "+v"(w0.w[3]),
+                   "+v"(w1.w[0]), "+v"(w1.w[1]), "+v"(w1.w[2]), "+v"(w1.w[3]),
+                   "+v"(w2.w[0]), "+v"(w2.w[1]), "+v"(w2.w[2]), "+v"(w2.w[3]),
+                   "+v"(w3.w[0]), "+v"(w3.w[1]), "+v"(w3.w[2]), "+v"(w3.w[3]));
+    if constexpr (NTL == 5)      // used after the wait, hence reserved across it
+        asm volatile("" : "+v"(w0.w[4]), "+v"(w1.w[4]), "+v"(w2.w[4]), "+v"(w3.w[4]));
 
     // ---- epilogue.  Accumulator element v of lane (l32, lg): row 8*(v/4) + 4*lg + v%4, column l32.
     // Low-rank term on bf16 MFMA 32x32x16 with exact operand splits (T: three terms, V: two):
