@@ -256,17 +256,18 @@ __global__ __launch_bounds__(256) void gemm_prefill_direct_kernel(
     const int nslices = K >> 7;                                  // K % 128 == 0 (checked by the launcher)
 
     // asynchronous copies: instruction j moves rows 8j .. 8j+7; lane i lands at row i/8,
-    // position i%8 and therefore fetches piece (i%8) ^ key(row).  Row groups past the matrix
-    // re-read its last eight rows (their results are not stored).
-    const int8_t* abase[8];
+    // position i%8 and therefore fetches piece (i%8) ^ key(row).  Rows past the matrix re-read
+    // its last row (their results are not stored).  Addresses are a wave-uniform base plus a
+    // 32-bit lane offset (at most 64 rows apart).
+    const int m_first = m_base < M ? m_base : M - 1;
+    const int8_t* abase = q + (int64_t)m_first * K;
     int avofs[8];
 #pragma unroll
     for (int j = 0; j < 8; ++j) {
-        int m0 = m_base + 8 * j;
-        if (m0 > M - 8) m0 = M - 8;                              // M >= 256 here
-        abase[j] = q + (int64_t)m0 * K;
         const int row = 8 * j + (lane >> 3);
-        avofs[j] = (lane >> 3) * K + (((lane & 7) ^ gd_key(row)) << 4);
+        int m = m_base + row;
+        if (m > M - 1) m = M - 1;
+        avofs[j] = (m - m_first) * K + (((lane & 7) ^ gd_key(row)) << 4);
     }
     // operand reads: row mt*32 + l32, piece 4*lg + s
     uint32_t rofs[MT][4];
@@ -277,16 +278,19 @@ __global__ __launch_bounds__(256) void gemm_prefill_direct_kernel(
             const int row = mt * 32 + l32;
             rofs[mt][s] = mytile_lds + row * 128 + ((((4 * lg + s) ^ gd_key(row)) & 7) << 4);
         }
-    // weight rows nt*32 + l32: 16-row tile 2*nt + l32/16 of this workgroup's columns (tile pairs
-    // past the matrix re-read its last two tiles), row l32 % 16 inside it
-    const uint4* wbase[NTL];
+    // weight rows nt*32 + l32 of this workgroup's columns: 16-row tile, row inside it (tiles past
+    // the matrix re-read its last tile); offsets in 16-byte units from a uniform base
+    int rt_first = n_base >> 4;
+    if (rt_first > row_tiles - 1) rt_first = row_tiles - 1;
+    const uint4* wbase = bits + (int64_t)rt_first * chunks * 64;
+    int wvofs[NTL];
 #pragma unroll
     for (int nt = 0; nt < NTL; ++nt) {
-        int rt0 = (n_base >> 4) + 2 * nt;
-        if (rt0 > row_tiles - 2) rt0 = row_tiles - 2;            // N >= 32 here
-        wbase[nt] = bits + (int64_t)rt0 * chunks * 64;
+        const int row = n_base + nt * 32 + l32;
+        int rt = row >> 4;
+        if (rt > row_tiles - 1) rt = row_tiles - 1;
+        wvofs[nt] = (rt - rt_first) * chunks * 64 + (row & 15);
     }
-    const int wvofs = (l32 >> 4) * chunks * 64 + (l32 & 15);     // in 16-byte units
     const int shamt = 4 * lg;
 
     auto copy_codes = [&](int ks) {                              // 8 vector-memory operations
@@ -295,7 +299,7 @@ __global__ __launch_bounds__(256) void gemm_prefill_direct_kernel(
 #pragma unroll
         for (int j = 0; j < 8; ++j)
             __builtin_amdgcn_global_load_lds(
-                (const __attribute__((address_space(1))) void*)(abase[j] + (int64_t)kc * 128 + avofs[j]),
+                (const __attribute__((address_space(1))) void*)(abase + (int64_t)kc * 128 + avofs[j]),
                 (__attribute__((address_space(3))) void*)(dst + j * 1024), 16, 0, 0);
     };
     struct Wslot { v4i w[NTL]; };                                // vector values: they stay in registers
@@ -304,7 +308,7 @@ __global__ __launch_bounds__(256) void gemm_prefill_direct_kernel(
         const int so = (kc >> 2) * 64 + (kc & 3) * 16;
 #pragma unroll
         for (int nt = 0; nt < NTL; ++nt) {
-            const uint4* p = wbase[nt] + so + wvofs;
+            const uint4* p = wbase + so + wvofs[nt];
             asm volatile("global_load_dwordx4 %0, %1, off" : "=v"(sl.w[nt]) : "v"(p) : "memory");
         }
     };

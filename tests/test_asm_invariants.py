@@ -1,0 +1,84 @@
+"""Structural checks of the compiled streaming GEMM (no GPU needed).
+
+The kernel issues its ring loads as inline assembly and waits for them with hand-counted
+`s_waitcnt vmcnt(N)`.  That is only correct while the compiler (a) adds no vector-memory
+operation of its own to the loop, (b) never copies a ring register between its load and its
+wait, and (c) does not hand a register of a load still in flight to other code behind the loop.
+These properties are read off the generated assembly."""
+import os
+import re
+import subprocess
+import tempfile
+
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+CSRC = os.path.join(ROOT, "paper_2605_00422_amd", "csrc")
+HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
+
+
+@pytest.fixture(scope="module")
+def kernels():
+    if not os.path.exists(HIPCC):
+        pytest.skip("hipcc not available")
+    with tempfile.TemporaryDirectory() as tmp:
+        out = os.path.join(tmp, "gemm_prefill.s")
+        cmd = [HIPCC, "--offload-arch=gfx950", "-O3", "-std=c++17", "-w", "-Xclang", "-target-feature", "-Xclang",
+               "-packed-fp32-ops", "-I", os.path.join(ROOT, "include"), "-I", CSRC, "-S", "--cuda-device-only",
+               "-o", out, os.path.join(CSRC, "gemm_prefill.hip")]
+        subprocess.run(cmd, check=True, capture_output=True)
+        text = open(out).read().split("\n")
+    found = {}
+    for ntl in (4, 5):
+        pat = re.compile(rf"^_ZN.*gemm_prefill_direct_kernelILi{ntl}E.*:")
+        start = next(i for i, l in enumerate(text) if pat.match(l))
+        end = next(i for i in range(start, len(text)) if "s_endpgm" in text[i])
+        found[ntl] = text[start:end + 1]
+    return found
+
+
+def _main_loop(lines):
+    start = next(i for i, l in enumerate(lines) if "Loop Header" in l)
+    label = lines[start].split(":")[0].strip()
+    end = next(i for i in range(start + 1, len(lines)) if re.search(rf"s_cbranch\S*\s+{re.escape(label)}$", lines[i]))
+    return start, end
+
+
+@pytest.mark.parametrize("ntl", [4, 5])
+def test_streaming_gemm_loop_structure(kernels, ntl):
+    lines = kernels[ntl]
+    start, end = _main_loop(lines)
+    loop = lines[start:end + 1]
+    code = [l.strip() for l in loop if l.strip() and not l.strip().startswith((";", "."))]
+    # four slices per trip: 4 x (NTL weight loads + 8 asynchronous code copies), 4 x 40 MFMAs
+    assert sum(l.startswith("global_load_lds_dwordx4") for l in code) == 32
+    assert sum(l.startswith("global_load_dwordx4") for l in code) == 4 * ntl
+    assert sum(l.startswith("v_mfma_i32_32x32x32_i8") for l in code) == 4 * 4 * 2 * ntl
+    # the only vector-memory waits are the four hand-counted ones, with the documented count
+    waits = [l for l in code if l.startswith("s_waitcnt") and "vmcnt" in l]
+    assert waits == [f"s_waitcnt vmcnt({2 * (ntl + 8)})"] * 4
+    # no other memory traffic and no register shuffling of ring or accumulator registers
+    assert not any(l.startswith(("scratch_", "global_store", "buffer_", "flat_")) for l in code)
+    assert not any(l.startswith(("v_mov_b32", "v_accvgpr")) for l in code)
+
+
+@pytest.mark.parametrize("ntl", [4, 5])
+def test_registers_of_loads_in_flight_stay_reserved(kernels, ntl):
+    lines = kernels[ntl]
+    start, end = _main_loop(lines)
+    dest = set()
+    for l in lines[start:end]:
+        m = re.match(r"\s*global_load_dwordx4 v\[(\d+):(\d+)\]", l)
+        if m:
+            dest.update(range(int(m.group(1)), int(m.group(2)) + 1))
+    assert len(dest) == 16 * ntl
+    drain = next(i for i in range(end, len(lines)) if "s_waitcnt vmcnt(0)" in lines[i])
+    for l in lines[end + 1:drain]:
+        l = l.strip()
+        if not l or l.startswith((";", ".", "s_", "global_store", "ds_write", "scratch_store")):
+            continue
+        m = re.match(r"\S+\s+v\[(\d+):(\d+)\]", l) or re.match(r"\S+\s+v(\d+)()", l)
+        if m:
+            lo = int(m.group(1))
+            hi = int(m.group(2)) if m.group(2) else lo
+            assert not any(r in dest for r in range(lo, hi + 1)), f"writes a register of a load in flight: {l}"

@@ -68,6 +68,9 @@ def test_cfg4_70b_gate_m4096_sampled_rows():
     (33, 640, 20, 32, 257, 64, "bf16"),  # ragged in every dimension
     (200, 2048, 32, 64, 300, 32, "bf16"),
     (3, 11008, 128, 86, 64, 16, "bf16"), # 7B down-projection width: n2 = 86, K not a multiple of 512
+    (300, 1152, 36, 32, 200, 20, "bf16"),  # streaming GEMM: ragged token and channel tiles, 9 slices
+    (257, 256, 16, 16, 48, 5, "f32"),      # streaming GEMM: two slices, odd rank, N < one tile, fp32 input
+    (520, 640, 20, 32, 330, 0, "bf16"),    # streaming GEMM without a low-rank branch
 ])
 def test_ragged_and_degenerate_shapes(M, K, n1, n2, N, r, xd):
     from parity_util import run_case
