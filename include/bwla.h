@@ -63,11 +63,13 @@ typedef enum {
  *   V      N x rp fp16 row-major, rp = r rounded up to a multiple of 16, zero padded
  *   U      rp x K fp16: U transposed (row j holds column j of U), rows r..rp-1 zero
  *   R1     n1 x n1 fp32 row-major;  R2  n2 x n2 fp32 row-major
+ *   R1p, R2p  the same factors transposed and split into three bfloat16 terms each (their sum is
+ *          the fp32 value exactly), zero padded: operand layout of the bf16-MFMA rotation
  */
 typedef struct bwla_layer {
     int64_t N, K;
     int32_t n1, n2, r, reserved;
-    uint64_t off_bits, off_alpha, off_V, off_U, off_R1, off_R2;
+    uint64_t off_bits, off_alpha, off_V, off_U, off_R1, off_R2, off_R1p, off_R2p;
     uint64_t blob_bytes;
     const void* d_blob;
 } bwla_layer_t;

@@ -38,6 +38,8 @@ void fill_layout(bwla_layer_t* L, int64_t N, int64_t K, int32_t n1, int32_t n2, 
     L->off_U = off;     off = bwla_align256(off + (uint64_t)K * rp * 2);
     L->off_R1 = off;    off = bwla_align256(off + (uint64_t)n1 * n1 * 4);
     L->off_R2 = off;    off = bwla_align256(off + (uint64_t)n2 * n2 * 4);
+    L->off_R1p = off;   off = bwla_align256(off + bwla_factor_planes_bytes(n1));
+    L->off_R2p = off;   off = bwla_align256(off + bwla_factor_planes_bytes(n2));
     L->blob_bytes = off;
 }
 
@@ -50,7 +52,7 @@ bwla_status_t check_layer(const bwla_layer_t* L) {
     fill_layout(&ref, L->N, L->K, L->n1, L->n2, L->r);
     if (ref.off_bits != L->off_bits || ref.off_alpha != L->off_alpha || ref.off_V != L->off_V ||
         ref.off_U != L->off_U || ref.off_R1 != L->off_R1 || ref.off_R2 != L->off_R2 ||
-        ref.blob_bytes != L->blob_bytes)
+        ref.off_R1p != L->off_R1p || ref.off_R2p != L->off_R2p || ref.blob_bytes != L->blob_bytes)
         return BWLA_ERR_SHAPE;
     if (!aligned16(L->d_blob)) return BWLA_ERR_ALIGN;
     return BWLA_OK;

@@ -23,6 +23,11 @@ static inline int64_t bwla_row_tiles(int64_t N) { return (N + BWLA_TILE_ROWS - 1
 static inline int64_t bwla_chunks(int64_t K) { return (K + BWLA_CHUNK_COLS - 1) / BWLA_CHUNK_COLS; }
 static inline uint64_t bwla_align256(uint64_t x) { return (x + 255u) & ~uint64_t(255); }
 
+// three bf16 term planes of an n x n factor, rows padded to 16 and columns to 32
+inline uint64_t bwla_factor_planes_bytes(int n) {
+    return (uint64_t)3 * ((n + 15) & ~15) * ((n + 31) & ~31) * 2;
+}
+
 // PSP projection (T = X U) launch plan: token tiles x column groups x S slices of K.  Up to 16
 // tokens the projection rides in the rotation launch (tiles of 16 tokens x rp columns); above,
 // a kernel of its own takes tiles of 64 tokens x up to 64 columns.

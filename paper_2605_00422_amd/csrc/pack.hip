@@ -78,6 +78,37 @@ __global__ void u_transpose_f16_kernel(const float* __restrict__ U, int64_t K, i
     Ut[i] = j < r ? __float2half_rn(U[k * r + j]) : __float2half_rn(0.0f);
 }
 
+// n x n fp32 factor R -> three bf16 term planes P[term][x][k], x < np16, k < np32, of R transposed:
+// P[.][x][pos] = terms of R[k][x] (zero outside n x n), where pos = k, or -- `permute` -- inside
+// every block of 32 the position 8 g + e holds k = 32 blk + (e < 4 ? 4 g + e : 16 + 4 g + e - 4):
+// the order in which two stacked 16-row MFMA accumulator tiles present their rows to a lane group.
+__global__ void factor_planes_kernel(const float* __restrict__ R, int n, int permute, uint16_t* __restrict__ P) {
+    const int np16 = (n + 15) & ~15, np32 = (n + 31) & ~31;
+    const int i = blockIdx.x * blockDim.x + threadIdx.x;
+    if (i >= np16 * np32) return;
+    const int x = i / np32, pos = i - x * np32;
+    int k = pos;
+    if (permute) {
+        const int blk = pos >> 5, g = (pos >> 3) & 3, e = pos & 7;
+        k = 32 * blk + (e < 4 ? 4 * g + e : 16 + 4 * g + e - 4);
+    }
+    const float v = (x < n && k < n) ? R[(int64_t)k * n + x] : 0.0f;
+    // round to nearest even on the upper 16 bits; the remainders are exact in fp32
+    auto bf = [](float f) -> uint32_t {
+        const uint32_t u = __float_as_uint(f);
+        return (u + 0x7fffu + ((u >> 16) & 1u)) & 0xffff0000u;
+    };
+    const uint32_t h1 = bf(v);
+    const float r1 = v - __uint_as_float(h1);
+    const uint32_t h2 = bf(r1);
+    const float r2 = r1 - __uint_as_float(h2);
+    const uint32_t h3 = bf(r2);
+    const int64_t plane = (int64_t)np16 * np32;
+    P[i] = (uint16_t)(h1 >> 16);
+    P[plane + i] = (uint16_t)(h2 >> 16);
+    P[2 * plane + i] = (uint16_t)(h3 >> 16);
+}
+
 __global__ void copy_f32_kernel(const float* __restrict__ src, int64_t n, float* __restrict__ dst) {
     const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
     if (i < n) dst[i] = src[i];
@@ -118,6 +149,9 @@ hipError_t bwla_launch_pack(const float* dW, const float* dR1, const float* dR2,
     const int64_t e1 = (int64_t)n1 * n1, e2 = (int64_t)n2 * n2;
     copy_f32_kernel<<<dim3((unsigned)((e1 + 255) / 256)), dim3(256), 0, st>>>(dR1, e1, (float*)(blob + L->off_R1));
     copy_f32_kernel<<<dim3((unsigned)((e2 + 255) / 256)), dim3(256), 0, st>>>(dR2, e2, (float*)(blob + L->off_R2));
+    const int p1 = ((n1 + 15) & ~15) * ((n1 + 31) & ~31), p2 = ((n2 + 15) & ~15) * ((n2 + 31) & ~31);
+    factor_planes_kernel<<<dim3((unsigned)((p1 + 255) / 256)), dim3(256), 0, st>>>(dR1, n1, 1, (uint16_t*)(blob + L->off_R1p));
+    factor_planes_kernel<<<dim3((unsigned)((p2 + 255) / 256)), dim3(256), 0, st>>>(dR2, n2, 0, (uint16_t*)(blob + L->off_R2p));
     return hipGetLastError();
 }
 

@@ -75,9 +75,9 @@ __host__ __device__ inline RqShape rq_shape(int n1, int n2) {
     return s;
 }
 
-__host__ __device__ inline size_t pp_lds_bytes(int r) {
+__host__ __device__ inline size_t pp_lds_bytes(int r, int waves = RQ_WAVES) {
     const int rp = ((r + 15) >> 4) * 16;
-    return (size_t)RQ_WAVES * (rp / 16) * 64 * 16 + 16;                // cross-wave reduction
+    return (size_t)waves * (rp / 16) * 64 * 16 + 16;                   // cross-wave reduction
 }
 
 // Exact n / d for n * d < 2^32 with one multiply-high; index arithmetic on run-time factor
@@ -483,6 +483,331 @@ __device__ __forceinline__ void rotate_token(float* lds, const void* __restrict_
 #undef RQ_PAIR_SLOTS
 }
 
+// ================================================================== rotation on bf16 MFMA
+// bf16 activations, second form of the rotation: every product is exact (bf16 x bf16 in fp32)
+// and only the fp32 accumulation rounds, because the fp32 factors are stored as three bf16
+// terms (8 + 8 + 8 mantissa bits) and the intermediate Z is split the same way in registers.
+//   stage 1  Z[a,d]  = sum_b V[a,b] R2[b,d]       MFMA 16x16x32: A = V rows (LDS), B = R2 terms
+//   stage 2  Yt[d,c] = sum_a Z[a,d] R1[a,c]       A = Z terms, B = R1 terms (LDS)
+// Wavefront w owns the 16 columns d of strip w.  The accumulator tile of stage 1 (lane (li, lg)
+// holds Z[a = 4*lg + v][d = li]) already is an A operand of stage 2 (row d = li, contraction
+// indices a = 4*lg + v): two stacked tiles give the eight indices of one 32-deep step, in the
+// order for which the packed R1 terms were permuted.  Z therefore never leaves registers, and
+// between the two stages there is neither an LDS round trip nor a barrier.  The R2 terms of a
+// strip are read once, from global memory, by the one wavefront that uses them.
+constexpr int R3_MAXA = 16;          // 16-row tiles along n1 (a and c); kernels are built for 4, 8, 12, 16
+constexpr int R3_MAXK1 = 5;          // 32-deep steps along n2 in stage 1: n2 <= 160
+constexpr int R3_MAXW = 10;          // wavefronts = 16-column strips along n2
+constexpr int R3_CPITCH = 80;        // bytes of one chunk row in LDS: 32 bf16 + 16 bytes of padding
+constexpr int R3_ITEMS = 6;          // 16-byte pieces of a streamed chunk per thread
+
+typedef __attribute__((ext_vector_type(8))) __bf16 v8bf;
+
+struct R3Shape {
+    int n1, n2, at, strips, k1, ch2, vpitch, vbytes, cbytes, nbuf;
+    bool ok, resident;
+    size_t lds_bytes;
+};
+
+__host__ __device__ inline R3Shape r3_shape(int n1, int n2) {
+    R3Shape s;
+    s.n1 = n1; s.n2 = n2;
+    s.at = (n1 + 15) >> 4; s.strips = (n2 + 15) >> 4;
+    s.k1 = (n2 + 31) >> 5; s.ch2 = (n1 + 31) >> 5;
+    s.vpitch = s.k1 * 64 + 16;                                   // bytes per token row: n2 padded to 32, + 16
+    s.vbytes = s.at * 16 * s.vpitch;
+    s.cbytes = 3 * s.at * 16 * R3_CPITCH;                        // one chunk: three terms x n1p16 rows
+    const size_t res = (size_t)s.vbytes + (size_t)s.ch2 * s.cbytes + 256;
+    s.resident = res <= RQ_LDS_LIMIT;
+    s.nbuf = s.resident ? s.ch2 : 2;
+    s.lds_bytes = (size_t)s.vbytes + (size_t)s.nbuf * s.cbytes + 256;
+    // streamed chunks: 12 * n1p16 pieces over 64 * strips threads, at most R3_ITEMS each
+    const bool stream_ok = 12 * s.at * 16 <= R3_ITEMS * 64 * s.strips;
+    // more than 12 tiles along n1 need more registers than a 10-wavefront workgroup can have
+    s.ok = s.at <= R3_MAXA && s.k1 <= R3_MAXK1 && s.strips <= (s.at > 12 ? 8 : R3_MAXW) &&
+           s.lds_bytes <= RQ_LDS_LIMIT && (s.resident || stream_ok);
+    return s;
+}
+
+__device__ __forceinline__ void r3_split3(const float (&f)[8], v8bf& h1, v8bf& h2, v8bf& h3) {
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+        const __bf16 a = (__bf16)f[e];
+        const float r1 = f[e] - (float)a;
+        const __bf16 b = (__bf16)r1;
+        h1[e] = a; h2[e] = b; h3[e] = (__bf16)(r1 - (float)b);
+    }
+}
+
+template <int ATM>
+__device__ __forceinline__ void rotate3_token(char* lds, const uint16_t* __restrict__ X, int64_t t, int64_t K, int n1,
+                                              int n2, const uint16_t* __restrict__ R1p,
+                                              const uint16_t* __restrict__ R2p, int8_t* __restrict__ q,
+                                              float* __restrict__ scale, int32_t* __restrict__ qsum) {
+    const R3Shape sh = r3_shape(n1, n2);
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);         // = strip
+    // the workgroup may have more wavefronts than strips (the projection workgroups of the same
+    // launch use them); those leave before the first barrier
+    if (wave >= sh.strips) return;
+    const int nthreads = 64 * sh.strips;
+    const int li = lane & 15, lg = lane >> 4;
+    const int n1p16 = sh.at * 16, n1p32 = sh.ch2 * 32, n2p32 = sh.k1 * 32;
+    char* vt = lds;                                                    // token rows, later the code image
+    char* cb = lds + sh.vbytes;                                        // chunk buffers
+    float* red = reinterpret_cast<float*>(lds + sh.vbytes + (size_t)sh.nbuf * sh.cbytes);
+
+    // ---- R2 terms of my strip: rows d = 16*strip + li of the packed [term][n2p16][n2p32] planes
+    v4i bfr[R3_MAXK1][3];
+#pragma unroll
+    for (int kb = 0; kb < R3_MAXK1; ++kb)
+#pragma unroll
+        for (int p = 0; p < 3; ++p) {
+            bfr[kb][p] = v4i{0, 0, 0, 0};
+            if (kb < sh.k1)
+                bfr[kb][p] = *reinterpret_cast<const v4i*>(R2p + ((int64_t)(p * sh.strips * 16 + wave * 16 + li)) * n2p32 +
+                                                           kb * 32 + 8 * lg);
+        }
+
+    // ---- token rows into LDS (bf16 as stored; zero padding), 8 elements per item, eight loads
+    // in flight per thread
+    {
+        const int per_row = n2p32 >> 3, items = n1p16 * per_row;
+        const uint16_t* xrow = X + t * K;
+        const FastDiv dpr(per_row);
+        if ((n2 & 7) == 0) {
+            for (int base = 0; base < items; base += 8 * nthreads) {
+                v4i tmp[8];
+#pragma unroll
+                for (int e = 0; e < 8; ++e) {
+                    const int it = base + e * nthreads + tid;
+                    const int a = dpr.div(it), b0 = (it - a * per_row) << 3;
+                    const bool in = it < items && a < n1 && b0 < n2;
+                    const v4i v = *reinterpret_cast<const v4i*>(xrow + (in ? (int64_t)a * n2 + b0 : 0));
+                    tmp[e] = in ? v : v4i{0, 0, 0, 0};
+                }
+#pragma unroll
+                for (int e = 0; e < 8; ++e) {
+                    const int it = base + e * nthreads + tid;
+                    if (it < items) {
+                        const int a = dpr.div(it), b0 = (it - a * per_row) << 3;
+                        *reinterpret_cast<v4i*>(vt + a * sh.vpitch + b0 * 2) = tmp[e];
+                    }
+                }
+            }
+        } else {
+            for (int it = tid; it < items; it += nthreads) {
+                const int a = dpr.div(it), b0 = (it - a * per_row) << 3;
+                uint32_t w[4] = {0u, 0u, 0u, 0u};
+                if (a < n1) {
+#pragma unroll
+                    for (int e = 0; e < 8; ++e)
+                        if (b0 + e < n2) w[e >> 1] |= (uint32_t)xrow[(int64_t)a * n2 + b0 + e] << (16 * (e & 1));
+                }
+                *reinterpret_cast<v4i*>(vt + a * sh.vpitch + b0 * 2) = v4i{(int)w[0], (int)w[1], (int)w[2], (int)w[3]};
+            }
+        }
+    }
+    // ---- packed R1 terms [term][n1p16][n1p32]: chunk ch = columns [32 ch, 32 ch + 32) of every row
+    const int crow_items = 3 * n1p16 * 4;                              // 16-byte pieces per chunk
+    auto chunk_src = [&](int ch, int item) -> const v4i* {
+        const int row = item >> 2, piece = item & 3;                   // row = term * n1p16 + c
+        return reinterpret_cast<const v4i*>(R1p + (int64_t)row * n1p32 + ch * 32 + piece * 8);
+    };
+    auto chunk_dst = [&](int buf, int item) -> v4i* {
+        return reinterpret_cast<v4i*>(cb + buf * sh.cbytes + (item >> 2) * R3_CPITCH + (item & 3) * 16);
+    };
+    v4i ring[R3_ITEMS];
+    if (sh.resident) {
+        // all chunks at once, eight loads in flight per thread
+        const int total = sh.ch2 * crow_items;
+        for (int base = 0; base < total; base += 8 * nthreads) {
+            v4i tmp[8];
+#pragma unroll
+            for (int e = 0; e < 8; ++e) {
+                const int g = base + e * nthreads + tid;
+                const int gc = g < total ? g : total - 1;
+                const int ch = gc / crow_items;
+                tmp[e] = *chunk_src(ch, gc - ch * crow_items);
+            }
+#pragma unroll
+            for (int e = 0; e < 8; ++e) {
+                const int g = base + e * nthreads + tid;
+                if (g < total) {
+                    const int ch = g / crow_items;
+                    *chunk_dst(ch, g - ch * crow_items) = tmp[e];
+                }
+            }
+        }
+    } else {
+#pragma unroll
+        for (int e = 0; e < R3_ITEMS; ++e) {
+            const int it = tid + e * nthreads;
+            if (it < crow_items) *chunk_dst(0, it) = *chunk_src(0, it);
+        }
+#pragma unroll
+        for (int e = 0; e < R3_ITEMS; ++e) {
+            const int it = tid + e * nthreads;
+            ring[e] = v4i{0, 0, 0, 0};
+            if (it < crow_items && sh.ch2 > 1) ring[e] = *chunk_src(1, it);
+        }
+    }
+    __syncthreads();
+
+    // ---- stage 1
+    v4f z[ATM];
+#pragma unroll
+    for (int ta = 0; ta < ATM; ++ta) z[ta] = v4f{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+    for (int g = 0; g < ATM / 2; ++g) {
+        if (2 * g < sh.at) {
+            const int t0 = 2 * g, t1 = 2 * g + 1 < sh.at ? 2 * g + 1 : 2 * g;      // an odd last tile is done twice
+            const char* a0p = vt + (t0 * 16 + li) * sh.vpitch + lg * 16;
+            const char* a1p = vt + (t1 * 16 + li) * sh.vpitch + lg * 16;
+#pragma unroll
+            for (int kb = 0; kb < R3_MAXK1; ++kb) {
+                if (kb < sh.k1) {
+                    const v8bf a0 = __builtin_bit_cast(v8bf, *reinterpret_cast<const v4i*>(a0p + kb * 64));
+                    const v8bf a1 = __builtin_bit_cast(v8bf, *reinterpret_cast<const v4i*>(a1p + kb * 64));
+#pragma unroll
+                    for (int p = 2; p >= 0; --p) {                     // small terms first
+                        const v8bf b = __builtin_bit_cast(v8bf, bfr[kb][p]);
+                        z[2 * g] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a0, b, z[2 * g], 0, 0, 0);
+                        z[2 * g + 1] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a1, b, z[2 * g + 1], 0, 0, 0);
+                    }
+                }
+            }
+        }
+    }
+    if ((sh.at & 1) != 0) {                                            // the duplicate of an odd last tile
+#pragma unroll
+        for (int ta = 1; ta < ATM; ta += 2)
+            if (ta == sh.at) z[ta] = v4f{0.f, 0.f, 0.f, 0.f};
+    }
+
+    // ---- stage 2: chunk ch contracts a in [32 ch, 32 ch + 32) = accumulator tiles 2 ch, 2 ch + 1
+    v4f y[ATM];
+#pragma unroll
+    for (int tc = 0; tc < ATM; ++tc) y[tc] = v4f{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+    for (int ch = 0; ch < ATM / 2; ++ch) {
+        if (ch < sh.ch2) {
+            int buf = ch;
+            if (!sh.resident) {
+                buf = ch & 1;
+                // chunk ch + 1 from the registers into the other buffer (its readers passed the
+                // barrier that closed chunk ch - 1), then chunk ch + 2 into the registers
+#pragma unroll
+                for (int e = 0; e < R3_ITEMS; ++e) {
+                    const int it = tid + e * nthreads;
+                    if (it < crow_items && ch + 1 < sh.ch2) *chunk_dst((ch + 1) & 1, it) = ring[e];
+                }
+#pragma unroll
+                for (int e = 0; e < R3_ITEMS; ++e) {
+                    const int it = tid + e * nthreads;
+                    if (it < crow_items && ch + 2 < sh.ch2) ring[e] = *chunk_src(ch + 2, it);
+                }
+            }
+            const float f[8] = {z[2 * ch][0], z[2 * ch][1], z[2 * ch][2], z[2 * ch][3],
+                                z[2 * ch + 1][0], z[2 * ch + 1][1], z[2 * ch + 1][2], z[2 * ch + 1][3]};
+            v8bf a1, a2, a3;
+            r3_split3(f, a1, a2, a3);
+            const char* cbase = cb + buf * sh.cbytes + li * R3_CPITCH + lg * 16;
+#pragma unroll
+            for (int g = 0; g < ATM / 2; ++g) {
+                if (2 * g < sh.at) {
+                    const int c0 = 2 * g, c1 = 2 * g + 1 < sh.at ? 2 * g + 1 : 2 * g;
+                    v8bf b0[3], b1[3];
+#pragma unroll
+                    for (int p = 0; p < 3; ++p) {
+                        b0[p] = __builtin_bit_cast(v8bf, *reinterpret_cast<const v4i*>(cbase + (p * n1p16 + c0 * 16) * R3_CPITCH));
+                        b1[p] = __builtin_bit_cast(v8bf, *reinterpret_cast<const v4i*>(cbase + (p * n1p16 + c1 * 16) * R3_CPITCH));
+                    }
+                    // the six products whose error is below fp32 rounding, small ones first
+                    y[2 * g] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a3, b0[0], y[2 * g], 0, 0, 0);
+                    y[2 * g + 1] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a3, b1[0], y[2 * g + 1], 0, 0, 0);
+                    y[2 * g] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a1, b0[2], y[2 * g], 0, 0, 0);
+                    y[2 * g + 1] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a1, b1[2], y[2 * g + 1], 0, 0, 0);
+                    y[2 * g] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a2, b0[1], y[2 * g], 0, 0, 0);
+                    y[2 * g + 1] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a2, b1[1], y[2 * g + 1], 0, 0, 0);
+                    y[2 * g] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a2, b0[0], y[2 * g], 0, 0, 0);
+                    y[2 * g + 1] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a2, b1[0], y[2 * g + 1], 0, 0, 0);
+                    y[2 * g] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a1, b0[1], y[2 * g], 0, 0, 0);
+                    y[2 * g + 1] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a1, b1[1], y[2 * g + 1], 0, 0, 0);
+                    y[2 * g] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a1, b0[0], y[2 * g], 0, 0, 0);
+                    y[2 * g + 1] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a1, b1[0], y[2 * g + 1], 0, 0, 0);
+                }
+            }
+            if (!sh.resident) __syncthreads();                         // chunk ch + 1 is published, chunk ch is free
+        }
+    }
+
+    // ---- per-token max magnitude (padded rows and columns are exact zeros)
+    float m = 0.0f;
+#pragma unroll
+    for (int tc = 0; tc < ATM; ++tc)
+        if (tc < sh.at) {
+#pragma unroll
+            for (int v = 0; v < 4; ++v) m = fmaxf(m, fabsf(y[tc][v]));
+        }
+    m = bwla_wave_max(m);
+    if (lane == 0) red[wave] = m;
+    __syncthreads();                                   // also: every wave is done with the token rows
+    float amax = red[0];
+    for (int w = 1; w < sh.strips; ++w) amax = fmaxf(amax, red[w]);
+    const float inv = amax > 0.0f ? 31.0f / amax : 0.0f;
+
+    // ---- quantize: lane holds Yt[d = 16*strip + 4*lg + v][c = 16*tc + li], four consecutive d of one c
+    int8_t* codes = reinterpret_cast<int8_t*>(vt);
+    int lsum = 0;
+    const int d0 = wave * 16 + 4 * lg;
+#pragma unroll
+    for (int tc = 0; tc < ATM; ++tc) {
+        if (tc < sh.at) {
+            const int c = tc * 16 + li;
+            int code[4];
+#pragma unroll
+            for (int v = 0; v < 4; ++v) {
+                float r = rintf(y[tc][v] * inv);
+                r = fminf(fmaxf(r, -31.0f), 31.0f);
+                code[v] = (int)r;
+            }
+            if (c < n1) {
+                if ((n2 & 3) == 0) {
+                    if (d0 < n2) {
+                        *reinterpret_cast<int*>(codes + c * n2 + d0) = (code[0] & 0xff) | ((code[1] & 0xff) << 8) |
+                                                                        ((code[2] & 0xff) << 16) | (code[3] << 24);
+                        lsum += code[0] + code[1] + code[2] + code[3];
+                    }
+                } else {
+#pragma unroll
+                    for (int v = 0; v < 4; ++v)
+                        if (d0 + v < n2) {
+                            codes[c * n2 + d0 + v] = (int8_t)code[v];
+                            lsum += code[v];
+                        }
+                }
+            }
+        }
+    }
+    lsum = bwla_wave_sum_i32(lsum);
+    int* redi = reinterpret_cast<int*>(red) + 16;
+    if (lane == 0) redi[wave] = lsum;
+    __syncthreads();
+    {
+        const uint4* src = reinterpret_cast<const uint4*>(codes);
+        uint4* dst = reinterpret_cast<uint4*>(q + t * K);
+        const int n16 = (int)(K >> 4);
+        for (int idx = tid; idx < n16; idx += nthreads) dst[idx] = src[idx];
+    }
+    if (tid == 0) {
+        int tot = 0;
+        for (int w = 0; w < sh.strips; ++w) tot += redi[w];
+        qsum[t] = tot;
+        scale[t] = amax / 31.0f;
+    }
+}
+
 // ================================================================== PSP projection T = X U
 template <bool BF16>
 __device__ __forceinline__ void psp_block(char* smem, const void* __restrict__ X, int64_t M, int64_t K, int r,
@@ -491,6 +816,7 @@ __device__ __forceinline__ void psp_block(char* smem, const void* __restrict__ X
                                           int s) {
     __shared__ int is_last;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int nw = (int)(blockDim.x >> 6);             // the eight 64-column parts of a slice are dealt to nw waves
     const int li = lane & 15, lg = lane >> 4;
     const int JT = (r + 15) >> 4, rp = JT * 16;
     const int64_t kbase = (int64_t)s * PP_SLICE;
@@ -500,11 +826,15 @@ __device__ __forceinline__ void psp_block(char* smem, const void* __restrict__ X
     // operand B (8 contiguous bytes of the transposed U).  All loads are issued before the first use.
     int64_t trow = (int64_t)tt * 16 + li;
     if (trow > M - 1) trow = M - 1;                    // padded token rows are never stored
+    v4f acc[PP_MAXJT];
+#pragma unroll
+    for (int jt = 0; jt < PP_MAXJT; ++jt) acc[jt] = v4f{0.f, 0.f, 0.f, 0.f};
+    for (int part = wave; part < 8; part += nw) {
     float x[4][4];
     uint2 u[4][PP_MAXJT];
 #pragma unroll
     for (int g = 0; g < 4; ++g) {
-        const int64_t kx = kbase + wave * 64 + g * 16 + 4 * lg;
+        const int64_t kx = kbase + part * 64 + g * 16 + 4 * lg;
         const bool in = kx < K;
         const int64_t kc = in ? kx : K - 4;            // keep the address valid, zero the value
         if (BF16) {
@@ -521,9 +851,6 @@ __device__ __forceinline__ void psp_block(char* smem, const void* __restrict__ X
             if (jt < JT) u[g][jt] = *reinterpret_cast<const uint2*>(U + (int64_t)(jt * 16 + li) * K + kc);
     }
 
-    v4f acc[PP_MAXJT];
-#pragma unroll
-    for (int jt = 0; jt < PP_MAXJT; ++jt) acc[jt] = v4f{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
     for (int g = 0; g < 4; ++g) {
 #pragma unroll
@@ -539,15 +866,16 @@ __device__ __forceinline__ void psp_block(char* smem, const void* __restrict__ X
             }
         }
     }
+    }
     v4f* red = reinterpret_cast<v4f*>(smem);           // [wave][jt][lane]
 #pragma unroll
     for (int jt = 0; jt < PP_MAXJT; ++jt)
         if (jt < JT) red[(wave * JT + jt) * 64 + lane] = acc[jt];
     __syncthreads();
     // waves share the column tiles; lane holds tokens 4*lg + v, column jt*16 + li
-    for (int jt = wave; jt < JT; jt += RQ_WAVES) {
+    for (int jt = wave; jt < JT; jt += nw) {
         v4f sum = red[jt * 64 + lane];
-        for (int w = 1; w < RQ_WAVES; ++w) sum += red[(w * JT + jt) * 64 + lane];
+        for (int w = 1; w < nw; ++w) sum += red[(w * JT + jt) * 64 + lane];
         const int col = jt * 16 + li;
 #pragma unroll
         for (int v = 0; v < 4; ++v) {
@@ -564,7 +892,7 @@ __device__ __forceinline__ void psp_block(char* smem, const void* __restrict__ X
 
     if (!bwla_partials_arrive(&counters[tt], S, &is_last)) return;
     // last workgroup of this token tile: add the S partial tiles in slice order
-    for (int idx = tid; idx < 16 * rp; idx += RQ_THREADS) {
+    for (int idx = tid; idx < 16 * rp; idx += (int)blockDim.x) {
         const int row = idx / rp, col = idx - row * rp;
         const int64_t tok = (int64_t)tt * 16 + row;
         if (tok < M && col < r) {
@@ -592,6 +920,7 @@ struct RqArgs {
     int8_t* q; float* scale; int32_t* qsum; float* T;
     int* counters; float* partials; int S;
     int64_t rot_blocks;      // workgroups below this index rotate token blockIdx.x, the rest project
+    const uint16_t* R1p; const uint16_t* R2p;          // bf16 term planes of the factors
 };
 
 template <bool BF16>
@@ -604,6 +933,29 @@ __global__ __launch_bounds__(RQ_THREADS) void rotate_quant_kernel(RqArgs a) {
         psp_block<BF16>(reinterpret_cast<char*>(lds), a.X, a.M, a.K, a.r, a.U, a.T, a.counters, a.partials, a.S,
                         pb / a.S, pb % a.S);
     }
+}
+
+// rotation on bf16 MFMA (bf16 activations): 64 threads per 16-column strip of n2
+template <int ATM, int THREADS>
+__global__ __launch_bounds__(THREADS) void rotate_quant3_kernel(RqArgs a) {
+    extern __shared__ __align__(16) float lds[];
+    if ((int64_t)blockIdx.x < a.rot_blocks) {
+        rotate3_token<ATM>(reinterpret_cast<char*>(lds), reinterpret_cast<const uint16_t*>(a.X), blockIdx.x, a.K, a.n1,
+                           a.n2, a.R1p, a.R2p, a.q, a.scale, a.qsum);
+    } else {
+        const int pb = (int)(blockIdx.x - a.rot_blocks);
+        psp_block<true>(reinterpret_cast<char*>(lds), a.X, a.M, a.K, a.r, a.U, a.T, a.counters, a.partials, a.S,
+                        pb / a.S, pb % a.S);
+    }
+}
+
+template <int ATM, int THREADS>
+hipError_t launch_rotate3(const RqArgs& a, int64_t blocks, int threads, size_t lds, hipStream_t st) {
+    static bwla_lds_attr attr;
+    hipError_t e = attr.ensure((const void*)rotate_quant3_kernel<ATM, THREADS>, lds);
+    if (e != hipSuccess) return e;
+    rotate_quant3_kernel<ATM, THREADS><<<dim3((unsigned)blocks), dim3((unsigned)threads), lds, st>>>(a);
+    return hipGetLastError();
 }
 
 __global__ __launch_bounds__(256) void code_sums_kernel(const int8_t* __restrict__ q, int64_t K,
@@ -674,6 +1026,7 @@ hipError_t bwla_launch_rotate_quant(const bwla_layer_t* L, const void* dX, int x
     a.X = dX; a.M = M; a.K = L->K; a.n1 = L->n1; a.n2 = L->n2; a.r = L->r;
     a.R1 = (const float*)(blob + L->off_R1); a.R2 = (const float*)(blob + L->off_R2);
     a.U = (const __half*)(blob + L->off_U);
+    a.R1p = (const uint16_t*)(blob + L->off_R1p); a.R2p = (const uint16_t*)(blob + L->off_R2p);
     a.q = dq; a.scale = dscale; a.qsum = dqsum; a.T = dT;
     a.counters = (int*)dws;
     a.partials = dws ? (float*)((char*)dws + bwla_psp_counter_bytes(M)) : nullptr;
@@ -683,9 +1036,24 @@ hipError_t bwla_launch_rotate_quant(const bwla_layer_t* L, const void* dX, int x
     const bool merged = L->r > 0 && plan.tile_rows == 16;
     const int64_t pblocks = merged ? (int64_t)plan.token_tiles * plan.splits : 0;
     const size_t plds = merged ? pp_lds_bytes(L->r) : 0;
-    const size_t lds = plds > sh.lds_bytes ? plds : sh.lds_bytes;
     a.rot_blocks = M;
     hipError_t e;
+    const R3Shape s3 = r3_shape(L->n1, L->n2);
+    if (xdtype == BWLA_X_BF16 && s3.ok) {
+        // projection workgroups in the same launch want all eight wavefronts
+        const int threads = (merged && s3.strips < 8) ? 512 : 64 * s3.strips;
+        const size_t pl3 = merged ? pp_lds_bytes(L->r, threads / 64) : 0;
+        const size_t lds3 = pl3 > s3.lds_bytes ? pl3 : s3.lds_bytes;
+        // register budget: up to 8 wavefronts may use 256 VGPRs, 9 or 10 only 168
+        if (s3.strips <= 8 && s3.at <= 4) e = launch_rotate3<4, 512>(a, M + pblocks, threads, lds3, st);
+        else if (s3.strips <= 8 && s3.at <= 8) e = launch_rotate3<8, 512>(a, M + pblocks, threads, lds3, st);
+        else if (s3.at <= 12) e = launch_rotate3<12, 640>(a, M + pblocks, threads, lds3, st);
+        else e = launch_rotate3<16, 512>(a, M + pblocks, threads, lds3, st);
+        if (e != hipSuccess) return e;
+        if (L->r > 0 && !merged) return bwla_launch_psp_prefill(L, dX, xdtype, M, dT, dws, plan, st);
+        return hipSuccess;
+    }
+    const size_t lds = plds > sh.lds_bytes ? plds : sh.lds_bytes;
     if (xdtype == BWLA_X_BF16) {
         static bwla_lds_attr attr;
         e = attr.ensure((const void*)rotate_quant_kernel<true>, lds);
