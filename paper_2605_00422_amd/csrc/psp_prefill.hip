@@ -124,7 +124,13 @@ __global__ __launch_bounds__(PF_THREADS) void psp_prefill_kernel(PfArgs a) {
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int li = lane & 15, lg = lane >> 4;
-    const int s = (int)(blockIdx.x % (unsigned)a.S), unit = (int)(blockIdx.x / (unsigned)a.S);
+    // Workgroups are dealt round-robin to the 8 XCDs.  XCD x takes the slices x, x + 8, ... of every
+    // tile, so the rows of U it needs (a few hundred KB) stay in its L2 while the activations
+    // stream through; the grid is padded to 8 * ceil(S / 8) slices and the surplus leaves at once.
+    const int sx = (a.S + 7) >> 3;
+    const int xcd = (int)(blockIdx.x & 7u), j = (int)(blockIdx.x >> 3);
+    const int s = xcd + 8 * (j % sx), unit = j / sx;
+    if (s >= a.S) return;
     const int jg = unit % a.JG, tile = unit / a.JG;
     const int64_t K = a.K;
 
@@ -273,7 +279,7 @@ hipError_t bwla_launch_psp_prefill(const bwla_layer_t* L, const void* dX, int xd
     a.counters = (int*)dws;
     a.partials = dws ? (float*)((char*)dws + bwla_psp_counter_bytes(M)) : nullptr;
     a.S = plan.splits; a.JG = plan.col_groups; a.kslice = plan.k_per_split;
-    const int blocks = plan.token_tiles * plan.col_groups * plan.splits;
+    const int blocks = plan.token_tiles * plan.col_groups * 8 * ((plan.splits + 7) / 8);
     const bool bf = xdtype == BWLA_X_BF16;
     switch (plan.tile_cols) {
         case 16: return bf ? launch<true, 1>(a, blocks, st) : launch<false, 1>(a, blocks, st);

@@ -504,8 +504,8 @@ constexpr int R3_ITEMS = 6;          // 16-byte pieces of a streamed chunk per t
 typedef __attribute__((ext_vector_type(8))) __bf16 v8bf;
 
 struct R3Shape {
-    int n1, n2, at, strips, k1, ch2, vpitch, vbytes, cbytes, nbuf;
-    bool ok, resident;
+    int n1, n2, at, strips, k1, ch2, vpitch, vbytes, cbytes, nbuf, r0bytes;
+    bool ok, resident, alias;
     size_t lds_bytes;
 };
 
@@ -520,7 +520,11 @@ __host__ __device__ inline R3Shape r3_shape(int n1, int n2) {
     const size_t res = (size_t)s.vbytes + (size_t)s.ch2 * s.cbytes + 256;
     s.resident = res <= RQ_LDS_LIMIT;
     s.nbuf = s.resident ? s.ch2 : 2;
-    s.lds_bytes = (size_t)s.vbytes + (size_t)s.nbuf * s.cbytes + 256;
+    // streaming with two chunk buffers; if they do not fit next to the token rows, the second one
+    // takes the place of the token rows, which are dead once stage 1 is done
+    s.alias = !s.resident && (size_t)s.vbytes + 2 * (size_t)s.cbytes + 256 > RQ_LDS_LIMIT;
+    s.r0bytes = s.alias && s.cbytes > s.vbytes ? s.cbytes : s.vbytes;
+    s.lds_bytes = (size_t)s.r0bytes + (size_t)(s.alias ? 1 : s.nbuf) * s.cbytes + 256;
     // streamed chunks: 12 * n1p16 pieces over 64 * strips threads, at most R3_ITEMS each
     const bool stream_ok = 12 * s.at * 16 <= R3_ITEMS * 64 * s.strips;
     // more than 12 tiles along n1 need more registers than a 10-wavefront workgroup can have
@@ -551,11 +555,13 @@ __device__ __forceinline__ void rotate3_token(char* lds, const uint16_t* __restr
     // launch use them); those leave before the first barrier
     if (wave >= sh.strips) return;
     const int nthreads = 64 * sh.strips;
+    RQTRACE_DECL;
+    RQTRACE(0);
     const int li = lane & 15, lg = lane >> 4;
     const int n1p16 = sh.at * 16, n1p32 = sh.ch2 * 32, n2p32 = sh.k1 * 32;
     char* vt = lds;                                                    // token rows, later the code image
-    char* cb = lds + sh.vbytes;                                        // chunk buffers
-    float* red = reinterpret_cast<float*>(lds + sh.vbytes + (size_t)sh.nbuf * sh.cbytes);
+    char* cb = lds + sh.r0bytes;                                       // chunk buffers
+    float* red = reinterpret_cast<float*>(lds + sh.r0bytes + (size_t)(sh.alias ? 1 : sh.nbuf) * sh.cbytes);
 
     // ---- R2 terms of my strip: rows d = 16*strip + li of the packed [term][n2p16][n2p32] planes
     v4i bfr[R3_MAXK1][3];
@@ -569,6 +575,28 @@ __device__ __forceinline__ void rotate3_token(char* lds, const uint16_t* __restr
                                                            kb * 32 + 8 * lg);
         }
 
+    // ---- packed R1 terms [term][n1p16][n1p32]: chunk ch = columns [32 ch, 32 ch + 32) of every row
+    const int crow_items = 3 * n1p16 * 4;                              // 16-byte pieces per chunk
+    auto chunk_src = [&](int ch, int item) -> const v4i* {
+        const int row = item >> 2, piece = item & 3;                   // row = term * n1p16 + c
+        return reinterpret_cast<const v4i*>(R1p + (int64_t)row * n1p32 + ch * 32 + piece * 8);
+    };
+    auto buf_base = [&](int buf) -> char* { return (sh.alias && buf == 1) ? lds : cb + buf * sh.cbytes; };
+    auto chunk_dst = [&](int buf, int item) -> v4i* {
+        return reinterpret_cast<v4i*>(buf_base(buf) + (item >> 2) * R3_CPITCH + (item & 3) * 16);
+    };
+    // streaming: the loads of chunks 0 and 1 are issued before the token rows are filled, so that
+    // all of them share one memory round trip
+    v4i ring[R3_ITEMS], first[R3_ITEMS];
+    if (!sh.resident) {
+#pragma unroll
+        for (int e = 0; e < R3_ITEMS; ++e) {
+            const int it = tid + e * nthreads;
+            const int ic = it < crow_items ? it : crow_items - 1;
+            first[e] = *chunk_src(0, ic);
+            ring[e] = *chunk_src(sh.ch2 > 1 ? 1 : 0, ic);
+        }
+    }
     // ---- token rows into LDS (bf16 as stored; zero padding), 8 elements per item, eight loads
     // in flight per thread
     {
@@ -608,16 +636,6 @@ __device__ __forceinline__ void rotate3_token(char* lds, const uint16_t* __restr
             }
         }
     }
-    // ---- packed R1 terms [term][n1p16][n1p32]: chunk ch = columns [32 ch, 32 ch + 32) of every row
-    const int crow_items = 3 * n1p16 * 4;                              // 16-byte pieces per chunk
-    auto chunk_src = [&](int ch, int item) -> const v4i* {
-        const int row = item >> 2, piece = item & 3;                   // row = term * n1p16 + c
-        return reinterpret_cast<const v4i*>(R1p + (int64_t)row * n1p32 + ch * 32 + piece * 8);
-    };
-    auto chunk_dst = [&](int buf, int item) -> v4i* {
-        return reinterpret_cast<v4i*>(cb + buf * sh.cbytes + (item >> 2) * R3_CPITCH + (item & 3) * 16);
-    };
-    v4i ring[R3_ITEMS];
     if (sh.resident) {
         // all chunks at once, eight loads in flight per thread
         const int total = sh.ch2 * crow_items;
@@ -643,16 +661,12 @@ __device__ __forceinline__ void rotate3_token(char* lds, const uint16_t* __restr
 #pragma unroll
         for (int e = 0; e < R3_ITEMS; ++e) {
             const int it = tid + e * nthreads;
-            if (it < crow_items) *chunk_dst(0, it) = *chunk_src(0, it);
-        }
-#pragma unroll
-        for (int e = 0; e < R3_ITEMS; ++e) {
-            const int it = tid + e * nthreads;
-            ring[e] = v4i{0, 0, 0, 0};
-            if (it < crow_items && sh.ch2 > 1) ring[e] = *chunk_src(1, it);
+            if (it < crow_items) *chunk_dst(0, it) = first[e];
         }
     }
+    RQTRACE(1);
     __syncthreads();
+    RQTRACE(2);
 
     // ---- stage 1
     v4f z[ATM];
@@ -686,6 +700,8 @@ __device__ __forceinline__ void rotate3_token(char* lds, const uint16_t* __restr
     }
 
     // ---- stage 2: chunk ch contracts a in [32 ch, 32 ch + 32) = accumulator tiles 2 ch, 2 ch + 1
+    RQTRACE(3);
+    if (sh.alias) __syncthreads();                     // the token rows make room for a chunk buffer
     v4f y[ATM];
 #pragma unroll
     for (int tc = 0; tc < ATM; ++tc) y[tc] = v4f{0.f, 0.f, 0.f, 0.f};
@@ -712,7 +728,7 @@ __device__ __forceinline__ void rotate3_token(char* lds, const uint16_t* __restr
                                 z[2 * ch + 1][0], z[2 * ch + 1][1], z[2 * ch + 1][2], z[2 * ch + 1][3]};
             v8bf a1, a2, a3;
             r3_split3(f, a1, a2, a3);
-            const char* cbase = cb + buf * sh.cbytes + li * R3_CPITCH + lg * 16;
+            const char* cbase = buf_base(buf) + li * R3_CPITCH + lg * 16;
 #pragma unroll
             for (int g = 0; g < ATM / 2; ++g) {
                 if (2 * g < sh.at) {
@@ -742,6 +758,7 @@ __device__ __forceinline__ void rotate3_token(char* lds, const uint16_t* __restr
         }
     }
 
+    RQTRACE(4);
     // ---- per-token max magnitude (padded rows and columns are exact zeros)
     float m = 0.0f;
 #pragma unroll
@@ -756,6 +773,7 @@ __device__ __forceinline__ void rotate3_token(char* lds, const uint16_t* __restr
     float amax = red[0];
     for (int w = 1; w < sh.strips; ++w) amax = fmaxf(amax, red[w]);
     const float inv = amax > 0.0f ? 31.0f / amax : 0.0f;
+    RQTRACE(5);
 
     // ---- quantize: lane holds Yt[d = 16*strip + 4*lg + v][c = 16*tc + li], four consecutive d of one c
     int8_t* codes = reinterpret_cast<int8_t*>(vt);
@@ -806,6 +824,8 @@ __device__ __forceinline__ void rotate3_token(char* lds, const uint16_t* __restr
         qsum[t] = tot;
         scale[t] = amax / 31.0f;
     }
+    RQTRACE(6);
+    RQTRACE_FLUSH;
 }
 
 // ================================================================== PSP projection T = X U
