@@ -227,23 +227,28 @@ __device__ __forceinline__ v4i gd_lds_read(uint32_t addr) {
 // expcnt (6:4) and lgkmcnt (11:8) left at "no wait"
 constexpr int gd_vmcnt_imm(int n) { return (n & 15) | ((n >> 4) << 14) | (7 << 4) | (15 << 8); }
 
-template <int NTL>
-__global__ __launch_bounds__(256) void gemm_prefill_direct_kernel(
+template <int NTL, int WM, int WK, int NB>
+__global__ __launch_bounds__(64 * WM * WK) void gemm_prefill_direct_kernel(
     const uint4* __restrict__ bits, int chunks, int row_tiles, const int8_t* __restrict__ q, int M, int K,
     const float* __restrict__ scale, const int32_t* __restrict__ qsum, const __half* __restrict__ alpha,
     const __half* __restrict__ V, const float* __restrict__ T, int r, float* __restrict__ Y, int N,
     int32_t* __restrict__ acc_out, int tiles_m, int tiles_n) {
     constexpr int MT = GD_MT;
-    constexpr int BM = 4 * GD_ROWS, BN = NTL * 32;
+    // WM wavefronts stacked along the tokens; WK wavefronts share one tile and split its slices of K
+    // (small batches: more wavefronts in flight), their accumulators are added through LDS
+    constexpr int BM = WM * GD_ROWS, BN = NTL * 32;
     // vector-memory operations per slice and wavefront: NTL weight loads, then 8 code copies;
     // when slice j + 1 is needed, the operations of slices j + 2 and j + 3 may still be in flight
+    // (NB = ring depth, 4 or 2: code tiles in LDS and weight slots in registers)
+    static_assert(NB == 4 || NB == 2, "ring depth");
     constexpr int GD_PER_SLICE = NTL + 8;
-    constexpr int GD_YOUNGER = 2 * GD_PER_SLICE;
+    constexpr int GD_YOUNGER = (NB - 2) * GD_PER_SLICE;
     extern __shared__ __align__(16) char smem[];
     const int tid = threadIdx.x, lane = tid & 63;
-    const int wm = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int wm = wave % WM, wk = wave / WM;
     const int l32 = lane & 31, lg = lane >> 5;
-    char* mytile = smem + wm * (GD_BUFS * GD_TILE);
+    char* mytile = smem + wave * (NB * GD_TILE);
     const uint32_t mytile_lds = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) char*)mytile;
 
     // XCD-aware tile order (workgroups are dealt round-robin to the 8 XCDs): one XCD works on
@@ -253,7 +258,16 @@ __global__ __launch_bounds__(256) void gemm_prefill_direct_kernel(
     if ((nblocks & 7) == 0) pid = (pid & 7) * (nblocks >> 3) + (pid >> 3);
     const int tm = pid / tiles_n, tn = pid - tm * tiles_n;
     const int m_base = tm * BM + wm * GD_ROWS, n_base = tn * BN;
-    const int nslices = K >> 7;                                  // K % 128 == 0 (checked by the launcher)
+    // my slices of K: [s_begin, s_begin + nslices) of K / 128 (K % 128 == 0, checked by the launcher)
+    const int ns_all = K >> 7;
+    const int ns_per = (ns_all + WK - 1) / WK;
+    const int s_begin = wk * ns_per;
+    const int nslices = ns_all - s_begin < ns_per ? (ns_all - s_begin > 0 ? ns_all - s_begin : 0) : ns_per;
+    // local slice index -> a slice that exists (indices past my range re-read a valid slice)
+    auto slice_of = [&](int ks) -> int {
+        const int g = s_begin + (ks < nslices ? ks : nslices - 1);
+        return g < 0 ? 0 : (g < ns_all ? g : ns_all - 1);
+    };
 
     // asynchronous copies: instruction j moves rows 8j .. 8j+7; lane i lands at row i/8,
     // position i%8 and therefore fetches piece (i%8) ^ key(row).  Rows past the matrix re-read
@@ -294,8 +308,8 @@ __global__ __launch_bounds__(256) void gemm_prefill_direct_kernel(
     const int shamt = 4 * lg;
 
     auto copy_codes = [&](int ks) {                              // 8 vector-memory operations
-        const int kc = ks < nslices ? ks : nslices - 1;          // past the end: any valid slice
-        char* dst = mytile + (ks & (GD_BUFS - 1)) * GD_TILE;
+        const int kc = slice_of(ks);
+        char* dst = mytile + (ks & (NB - 1)) * GD_TILE;
 #pragma unroll
         for (int j = 0; j < 8; ++j)
             __builtin_amdgcn_global_load_lds(
@@ -304,7 +318,7 @@ __global__ __launch_bounds__(256) void gemm_prefill_direct_kernel(
     };
     struct Wslot { v4i w[NTL]; };                                // vector values: they stay in registers
     auto fetch_w = [&](Wslot& sl, int ks) {                      // NTL vector-memory operations
-        const int kc = ks < nslices ? ks : nslices - 1;
+        const int kc = slice_of(ks);
         const int so = (kc >> 2) * 64 + (kc & 3) * 16;
 #pragma unroll
         for (int nt = 0; nt < NTL; ++nt) {
@@ -330,7 +344,7 @@ __global__ __launch_bounds__(256) void gemm_prefill_direct_kernel(
     // by settle()), expanded weight bits.
     struct Ops { v4i av[MT]; v4i b[NTL]; };
     auto prepare = [&](Ops& o, const Wslot& sl, int ks, int s) {
-        const uint32_t bo = (uint32_t)((ks & (GD_BUFS - 1)) * GD_TILE);
+        const uint32_t bo = (uint32_t)((ks & (NB - 1)) * GD_TILE);
 #pragma unroll
         for (int mt = 0; mt < MT; ++mt) o.av[mt] = gd_lds_read(rofs[mt][s] + bo);
         // slices past the end (the trip count is padded to a multiple of three) contract zeros
@@ -377,36 +391,78 @@ __global__ __launch_bounds__(256) void gemm_prefill_direct_kernel(
             settle(following);
             ops = following;
         }
-        fetch_w(cur, ks + 4);
-        copy_codes(ks + 4);
+        fetch_w(cur, ks + NB);
+        copy_codes(ks + NB);
         __builtin_amdgcn_sched_barrier(0);
     };
     fetch_w(w0, 0); copy_codes(0);
     fetch_w(w1, 1); copy_codes(1);
-    fetch_w(w2, 2); copy_codes(2);
-    fetch_w(w3, 3); copy_codes(3);
+    if constexpr (NB == 4) {
+        fetch_w(w2, 2); copy_codes(2);
+        fetch_w(w3, 3); copy_codes(3);
+    }
     __builtin_amdgcn_sched_barrier(0);
-    __builtin_amdgcn_s_waitcnt(gd_vmcnt_imm(3 * GD_PER_SLICE));  // slice 0 has landed
+    __builtin_amdgcn_s_waitcnt(gd_vmcnt_imm((NB - 1) * GD_PER_SLICE));  // slice 0 has landed
     landed(w0);
     prepare(ops, w0, 0, 0);
     settle(ops);
-    for (int ks0 = 0; ks0 < nslices; ks0 += 4) {
-        step(w0, w1, ks0);
-        step(w1, w2, ks0 + 1);
-        step(w2, w3, ks0 + 2);
-        step(w3, w0, ks0 + 3);
+    if constexpr (NB == 4) {
+        for (int ks0 = 0; ks0 < nslices; ks0 += 4) {
+            step(w0, w1, ks0);
+            step(w1, w2, ks0 + 1);
+            step(w2, w3, ks0 + 2);
+            step(w3, w0, ks0 + 3);
+        }
+    } else {
+        for (int ks0 = 0; ks0 < nslices; ks0 += 2) {
+            step(w0, w1, ks0);
+            step(w1, w0, ks0 + 1);
+        }
     }
     // Drain the loads nobody reads.  Their destination registers must stay reserved until they
     // have landed, so the wait names all four slots as operands: without that the code behind
     // the loop may reuse a register that a load still in flight is about to overwrite.
-    static_assert(NTL == 4 || NTL == 5, "operand lists of the drain below");
-    asm volatile("s_waitcnt vmcnt(0)"
-                 : "+v"(w0.w[0]), "+v"(w0.w[1]), "+v"(w0.w[2]), "+v"(w0.w[3]),
-                   "+v"(w1.w[0]), "+v"(w1.w[1]), "+v"(w1.w[2]), "+v"(w1.w[3]),
-                   "+v"(w2.w[0]), "+v"(w2.w[1]), "+v"(w2.w[2]), "+v"(w2.w[3]),
-                   "+v"(w3.w[0]), "+v"(w3.w[1]), "+v"(w3.w[2]), "+v"(w3.w[3]));
-    if constexpr (NTL == 5)      // used after the wait, hence reserved across it
-        asm volatile("" : "+v"(w0.w[4]), "+v"(w1.w[4]), "+v"(w2.w[4]), "+v"(w3.w[4]));
+    static_assert(NTL == 1 || NTL == 2 || NTL == 4 || NTL == 5, "operand lists of the drain below");
+    asm volatile("s_waitcnt vmcnt(0)" : "+v"(w0.w[0]), "+v"(w1.w[0]));
+    // the remaining slot registers are used after the wait, hence reserved across it
+    if constexpr (NB == 4) asm volatile("" : "+v"(w2.w[0]), "+v"(w3.w[0]));
+    if constexpr (NTL >= 2) {
+        asm volatile("" : "+v"(w0.w[1]), "+v"(w1.w[1]));
+        if constexpr (NB == 4) asm volatile("" : "+v"(w2.w[1]), "+v"(w3.w[1]));
+    }
+    if constexpr (NTL >= 4) {
+        static_assert(NTL < 4 || NB == 4, "wide tiles use the deep ring");
+        asm volatile("" : "+v"(w0.w[2]), "+v"(w1.w[2]), "+v"(w2.w[2]), "+v"(w3.w[2]),
+                          "+v"(w0.w[3]), "+v"(w1.w[3]), "+v"(w2.w[3]), "+v"(w3.w[3]));
+    }
+    if constexpr (NTL == 5) asm volatile("" : "+v"(w0.w[4]), "+v"(w1.w[4]), "+v"(w2.w[4]), "+v"(w3.w[4]));
+
+    if constexpr (WK > 1) {
+        // every wavefront has drained its copies: the tiles are dead, LDS carries the partial sums
+        __syncthreads();
+        int* red = reinterpret_cast<int*>(smem);
+        constexpr int PER_WAVE = MT * NTL * 16 * 64;
+        if (wk > 0) {
+#pragma unroll
+            for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+                for (int nt = 0; nt < NTL; ++nt)
+#pragma unroll
+                    for (int v = 0; v < 16; ++v)
+                        red[((wk - 1) * WM + wm) * PER_WAVE + ((mt * NTL + nt) * 16 + v) * 64 + lane] = acc[mt][nt][v];
+        }
+        __syncthreads();
+        if (wk > 0) return;
+#pragma unroll
+        for (int w = 1; w < WK; ++w)
+#pragma unroll
+            for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+                for (int nt = 0; nt < NTL; ++nt)
+#pragma unroll
+                    for (int v = 0; v < 16; ++v)
+                        acc[mt][nt][v] += red[((w - 1) * WM + wm) * PER_WAVE + ((mt * NTL + nt) * 16 + v) * 64 + lane];
+    }
 
     // ---- epilogue.  Accumulator element v of lane (l32, lg): row 8*(v/4) + 4*lg + v%4, column l32.
     // Low-rank term on bf16 MFMA 32x32x16 with exact operand splits (T: three terms, V: two):
@@ -513,17 +569,19 @@ __global__ __launch_bounds__(256) void gemm_prefill_direct_kernel(
     }
 }
 
-template <int NTL>
+template <int NTL, int WM, int WK, int NB>
 hipError_t launch_direct(const bwla_layer_t* L, const int8_t* dq, const float* dscale, const int32_t* dqsum,
                          const float* dT, int64_t M, float* dY, int32_t* dacc, hipStream_t st) {
-    constexpr int BM = 4 * GD_ROWS, BN = NTL * 32;
+    constexpr int BM = WM * GD_ROWS, BN = NTL * 32;
     const char* blob = (const char*)L->d_blob;
     const int tiles_m = (int)((M + BM - 1) / BM), tiles_n = (int)((L->N + BN - 1) / BN);
-    const size_t lds = (size_t)4 * GD_BUFS * GD_TILE;
+    const size_t lds = (size_t)WM * WK * NB * GD_TILE;
+    static_assert((size_t)(WK - 1) * WM * GD_MT * NTL * 16 * 64 * 4 <= (size_t)WM * WK * NB * GD_TILE,
+                  "the partial sums must fit into the tile rings");
     static bwla_lds_attr attr;
-    hipError_t e = attr.ensure((const void*)gemm_prefill_direct_kernel<NTL>, lds);
+    hipError_t e = attr.ensure((const void*)gemm_prefill_direct_kernel<NTL, WM, WK, NB>, lds);
     if (e != hipSuccess) return e;
-    gemm_prefill_direct_kernel<NTL><<<dim3((unsigned)(tiles_m * tiles_n)), dim3(256), lds, st>>>(
+    gemm_prefill_direct_kernel<NTL, WM, WK, NB><<<dim3((unsigned)(tiles_m * tiles_n)), dim3(64 * WM * WK), lds, st>>>(
         (const uint4*)(blob + L->off_bits), (int)bwla_chunks(L->K), (int)bwla_row_tiles(L->N), dq, (int)M,
         (int)L->K, dscale, dqsum, (const __half*)(blob + L->off_alpha), (const __half*)(blob + L->off_V), dT,
         L->r, dY, (int)L->N, dacc, tiles_m, tiles_n);
@@ -544,13 +602,22 @@ hipError_t bwla_launch_gemm_prefill(const bwla_layer_t* L, const int8_t* dq, con
                                     const int32_t* dqsum, const float* dT, int64_t M, float* dY,
                                     int32_t* dacc, hipStream_t st) {
     const int64_t N = L->N;
-    if (M <= 64) return launch_cfg<1, 2, 2, 2>(L, dq, dscale, dqsum, dT, M, dY, dacc, st);          // 64 x 128
-    if (M >= 256 && N >= 32 && (L->K & 127) == 0) {
-        // register-streaming kernel, 256 x 160 or 256 x 128 tiles, whichever fills the chip better
-        const double d160 = wave_eff(tiles_for(M, N, 256, 160)), d128 = wave_eff(tiles_for(M, N, 256, 128));
-        if (d160 >= d128) return launch_direct<5>(L, dq, dscale, dqsum, dT, M, dY, dacc, st);
-        return launch_direct<4>(L, dq, dscale, dqsum, dT, M, dY, dacc, st);
+    if (N >= 32 && (L->K & 127) == 0) {
+        // register-streaming kernel.  Large batches: four wavefronts stacked along the tokens,
+        // 256 x 160 or 256 x 128 tiles, whichever fills the chip better.  Up to 128 tokens: one or
+        // two wavefronts per workgroup and narrow channel tiles, so that enough workgroups exist.
+        if (M > 128) {
+            const double d160 = wave_eff(tiles_for(M, N, 256, 160)), d128 = wave_eff(tiles_for(M, N, 256, 128));
+            if (d160 >= d128) return launch_direct<5, 4, 1, 4>(L, dq, dscale, dqsum, dT, M, dY, dacc, st);
+            return launch_direct<4, 4, 1, 4>(L, dq, dscale, dqsum, dT, M, dY, dacc, st);
+        }
+        // 64 x 32 tiles: one wavefront per workgroup when there are many tiles, else four
+        // wavefronts that share a tile and split K (measured on the 70B block at 64 tokens)
+        const int64_t tiles = ((M + 63) / 64) * ((N + 31) / 32);
+        if (tiles >= 768) return launch_direct<1, 1, 1, 4>(L, dq, dscale, dqsum, dT, M, dY, dacc, st);
+        return launch_direct<1, 1, 4, 4>(L, dq, dscale, dqsum, dT, M, dY, dacc, st);
     }
+    if (M <= 64) return launch_cfg<1, 2, 2, 2>(L, dq, dscale, dqsum, dT, M, dY, dacc, st);          // 64 x 128
     // pick the largest tile that still fills the chip reasonably
     const double e256 = wave_eff(tiles_for(M, N, 256, 256));
     const double e160 = wave_eff(tiles_for(M, N, 256, 160));
