@@ -1014,7 +1014,10 @@ int bwla_rotate_max_tiles() { return RQ_MAXT * RQ_WAVES; }
 bwla_psp_plan bwla_make_psp_plan(int64_t M, int64_t K, int r) {
     bwla_psp_plan p;
     const int rp = (r + 15) & ~15;
-    if (M <= 16 || r <= 0) {
+    // The projection rides in the rotation launch while that launch stays within about two
+    // workgroups per CU: its short workgroups then finish in the shadow of the rotation.
+    const int64_t ride = M + ((M + 15) / 16) * ((K + PP_SLICE - 1) / PP_SLICE);
+    if (M <= 16 || r <= 0 || ride <= 512) {
         p.token_tiles = (int)((M + 15) / 16);
         p.k_per_split = PP_SLICE;
         p.splits = r > 0 ? (int)((K + PP_SLICE - 1) / PP_SLICE) : 1;
