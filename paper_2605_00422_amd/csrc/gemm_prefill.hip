@@ -4,9 +4,13 @@
 //   acc[t,n] = sum_k q[t,k] Sign(W[n,k]) = 2 * sum_k q[t,k] b[n,k] - qsum_t
 //   Y[t,n]   = scale_t * alpha_n * acc[t,n] + sum_j T[t,j] V[n,j]       (paper Eq. 4; Sec. 3.2)
 //
-// The activation codes are tiled through LDS (double buffered); the 1-bit weights never touch
-// LDS: each lane keeps the 128-column bit slice of its own output channel in four registers and
-// expands a 16-column run with (w >> j) & 0x01010101 right before the MFMA that consumes it.
+// In both kernels of this file the 1-bit weights never touch LDS: each lane keeps the
+// 128-column bit slice of its own output channel in four registers and expands a 16-column run
+// with (w >> j) & 0x01010101 right before the MFMA that consumes it.
+//   gemm_prefill_direct_kernel  the main path (K % 128 == 0, N >= 32): every wavefront streams
+//                               its own operands, no workgroup barriers (described further down)
+//   gemm_prefill_kernel         the remaining shapes: code tiles shared through LDS, double
+//                               buffered, one barrier per 128 columns
 #include "bwla_internal.h"
 
 namespace {
@@ -617,12 +621,8 @@ hipError_t bwla_launch_gemm_prefill(const bwla_layer_t* L, const int8_t* dq, con
         if (tiles >= 768) return launch_direct<1, 1, 1, 4>(L, dq, dscale, dqsum, dT, M, dY, dacc, st);
         return launch_direct<1, 1, 4, 4>(L, dq, dscale, dqsum, dT, M, dY, dacc, st);
     }
-    if (M <= 64) return launch_cfg<1, 2, 2, 2>(L, dq, dscale, dqsum, dT, M, dY, dacc, st);          // 64 x 128
-    // pick the largest tile that still fills the chip reasonably
-    const double e256 = wave_eff(tiles_for(M, N, 256, 256));
-    const double e160 = wave_eff(tiles_for(M, N, 256, 160));
-    const double e128 = wave_eff(tiles_for(M, N, 128, 128)) * 0.85;   // smaller tile: more LDS traffic per MFMA
-    if (e256 >= e160 && e256 >= e128) return launch_cfg<4, 4, 2, 2>(L, dq, dscale, dqsum, dT, M, dY, dacc, st);
-    if (e160 >= e128) return launch_cfg<2, 5, 4, 1>(L, dq, dscale, dqsum, dT, M, dY, dacc, st);      // 256 x 160
-    return launch_cfg<2, 2, 2, 2>(L, dq, dscale, dqsum, dT, M, dY, dacc, st);                        // 128 x 128
+    // shapes the streaming kernel does not take (K not a multiple of 128, fewer than 32 channels):
+    // LDS-tiled kernel, 64 x 128 or 128 x 128 tiles
+    if (M <= 64) return launch_cfg<1, 2, 2, 2>(L, dq, dscale, dqsum, dT, M, dY, dacc, st);
+    return launch_cfg<2, 2, 2, 2>(L, dq, dscale, dqsum, dT, M, dY, dacc, st);
 }

@@ -71,6 +71,8 @@ def test_cfg4_70b_gate_m4096_sampled_rows():
     (300, 1152, 36, 32, 200, 20, "bf16"),  # streaming GEMM: ragged token and channel tiles, 9 slices
     (257, 256, 16, 16, 48, 5, "f32"),      # streaming GEMM: two slices, odd rank, N < one tile, fp32 input
     (520, 640, 20, 32, 330, 0, "bf16"),    # streaming GEMM without a low-rank branch
+    (40, 480, 20, 24, 70, 8, "bf16"),      # K not a multiple of 128: LDS-tiled GEMM, 64 x 128 tiles
+    (150, 160, 16, 10, 24, 4, "f32"),      # fewer than 32 channels: LDS-tiled GEMM, 128 x 128 tiles
 ])
 def test_ragged_and_degenerate_shapes(M, K, n1, n2, N, r, xd):
     from parity_util import run_case
