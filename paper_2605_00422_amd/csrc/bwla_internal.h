@@ -23,6 +23,9 @@ static inline int64_t bwla_row_tiles(int64_t N) { return (N + BWLA_TILE_ROWS - 1
 static inline int64_t bwla_chunks(int64_t K) { return (K + BWLA_CHUNK_COLS - 1) / BWLA_CHUNK_COLS; }
 static inline uint64_t bwla_align256(uint64_t x) { return (x + 255u) & ~uint64_t(255); }
 
+// compute units of the current device (cached; 256 if the query fails)
+int bwla_device_cus();
+
 // three bf16 term planes of an n x n factor, rows padded to 16 and columns to 32
 inline uint64_t bwla_factor_planes_bytes(int n) {
     return (uint64_t)3 * ((n + 15) & ~15) * ((n + 31) & ~31) * 2;

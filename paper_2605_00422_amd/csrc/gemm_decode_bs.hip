@@ -349,18 +349,6 @@ __global__ __launch_bounds__(BS_MAX_THREADS) void gemm_decode_bs_kernel(BsArgs a
     else compute_wave<CPW, DEPTH, NT, false>(a, smem, first, stride, n_iter, wave, lane);
 }
 
-int device_cus() {
-    static int cus = 0;
-    if (cus == 0) {
-        int dev = 0, n = 0;
-        if (hipGetDevice(&dev) == hipSuccess &&
-            hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess && n > 0)
-            cus = n;
-        else
-            cus = 256;
-    }
-    return cus;
-}
 
 constexpr int BS_CPW = 2;   // two chunks per compute wave amortize the class recombination
 
@@ -429,7 +417,7 @@ hipError_t bwla_launch_gemm_decode_bs(const bwla_layer_t* L, const int8_t* dq, c
                                       const int32_t* dqsum, const float* dT, int64_t M, float* dY,
                                       int32_t* dacc, hipStream_t st) {
     const int chunks = (int)bwla_chunks(L->K), row_tiles = (int)bwla_row_tiles(L->N);
-    const int cus = device_cus();
+    const int cus = bwla_device_cus();
     // Measured on MI355X: one tile per step and one workgroup per CU is the best shape for all
     // decode layers tried (two tiles per step run the steady state ~30% faster but pay more at
     // start-up, which dominates at these sizes).
@@ -438,4 +426,17 @@ hipError_t bwla_launch_gemm_decode_bs(const bwla_layer_t* L, const int8_t* dq, c
     const int grid = units < cus ? units : cus;
     (void)chunks;
     return bwla_launch_gemm_decode_bs_cfg(L, dq, dscale, dqsum, dT, M, dY, dacc, st, nt, grid, 2);
+}
+
+int bwla_device_cus() {
+    static int cus = 0;
+    if (cus == 0) {
+        int dev = 0, n = 0;
+        if (hipGetDevice(&dev) == hipSuccess &&
+            hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess && n > 0)
+            cus = n;
+        else
+            cus = 256;
+    }
+    return cus;
 }

@@ -543,9 +543,10 @@ __device__ __forceinline__ void r3_split3(const float (&f)[8], v8bf& h1, v8bf& h
     }
 }
 
-template <int ATM>
-__device__ __forceinline__ void rotate3_token(char* lds, const uint16_t* __restrict__ X, int64_t t, int64_t K, int n1,
-                                              int n2, const uint16_t* __restrict__ R1p,
+template <int ATM, bool LOOP>
+__device__ __forceinline__ void rotate3_token(char* lds, const uint16_t* __restrict__ X, int64_t t_first,
+                                              int64_t t_stride, int64_t M, int64_t K, int n1, int n2,
+                                              const uint16_t* __restrict__ R1p,
                                               const uint16_t* __restrict__ R2p, int8_t* __restrict__ q,
                                               float* __restrict__ scale, int32_t* __restrict__ qsum) {
     const R3Shape sh = r3_shape(n1, n2);
@@ -563,18 +564,6 @@ __device__ __forceinline__ void rotate3_token(char* lds, const uint16_t* __restr
     char* cb = lds + sh.r0bytes;                                       // chunk buffers
     float* red = reinterpret_cast<float*>(lds + sh.r0bytes + (size_t)(sh.alias ? 1 : sh.nbuf) * sh.cbytes);
 
-    // ---- R2 terms of my strip: rows d = 16*strip + li of the packed [term][n2p16][n2p32] planes
-    v4i bfr[R3_MAXK1][3];
-#pragma unroll
-    for (int kb = 0; kb < R3_MAXK1; ++kb)
-#pragma unroll
-        for (int p = 0; p < 3; ++p) {
-            bfr[kb][p] = v4i{0, 0, 0, 0};
-            if (kb < sh.k1)
-                bfr[kb][p] = *reinterpret_cast<const v4i*>(R2p + ((int64_t)(p * sh.strips * 16 + wave * 16 + li)) * n2p32 +
-                                                           kb * 32 + 8 * lg);
-        }
-
     // ---- packed R1 terms [term][n1p16][n1p32]: chunk ch = columns [32 ch, 32 ch + 32) of every row
     const int crow_items = 3 * n1p16 * 4;                              // 16-byte pieces per chunk
     auto chunk_src = [&](int ch, int item) -> const v4i* {
@@ -585,6 +574,55 @@ __device__ __forceinline__ void rotate3_token(char* lds, const uint16_t* __restr
     auto chunk_dst = [&](int buf, int item) -> v4i* {
         return reinterpret_cast<v4i*>(buf_base(buf) + (item >> 2) * R3_CPITCH + (item & 3) * 16);
     };
+    if (sh.resident) {
+        // all chunks at once, eight loads in flight per thread
+        const int total = sh.ch2 * crow_items;
+        for (int base = 0; base < total; base += 8 * nthreads) {
+            v4i tmp[8];
+#pragma unroll
+            for (int e = 0; e < 8; ++e) {
+                const int g = base + e * nthreads + tid;
+                const int gc = g < total ? g : total - 1;
+                const int ch = gc / crow_items;
+                tmp[e] = *chunk_src(ch, gc - ch * crow_items);
+            }
+#pragma unroll
+            for (int e = 0; e < 8; ++e) {
+                const int g = base + e * nthreads + tid;
+                if (g < total) {
+                    const int ch = g / crow_items;
+                    *chunk_dst(ch, g - ch * crow_items) = tmp[e];
+                }
+            }
+        }
+    }
+    // LOOP: resident factors and many tokens -- the workgroup keeps the factors and walks over
+    // tokens t_first, t_first + t_stride, ...  Otherwise one token per workgroup (the body below is
+    // then straight-line code).
+    int64_t t = t_first;
+#pragma nounroll
+    do {
+    // In a loop, lane-derived values are recomputed per token from an opaque copy of the thread
+    // index: otherwise every address of the body is hoisted out of the loop and kept in registers.
+    int tid_opaque = threadIdx.x;
+    if constexpr (LOOP) asm volatile("" : "+v"(tid_opaque));
+    const int tid = tid_opaque, lane = tid & 63, li = lane & 15, lg = lane >> 4;
+    // ---- R2 terms of my strip: rows d = 16*strip + li of the packed [term][n2p16][n2p32] planes
+    // (read again for every token: kept across the token loop they would not fit the register
+    // budget; the opaque zero keeps the loads inside the loop)
+    int opaque_zero = 0;
+    if constexpr (LOOP) asm volatile("" : "+s"(opaque_zero));
+    v4i bfr[R3_MAXK1][3];
+#pragma unroll
+    for (int kb = 0; kb < R3_MAXK1; ++kb)
+#pragma unroll
+        for (int p = 0; p < 3; ++p) {
+            bfr[kb][p] = v4i{0, 0, 0, 0};
+            if (kb < sh.k1)
+                bfr[kb][p] = *reinterpret_cast<const v4i*>(R2p + ((int64_t)(p * sh.strips * 16 + wave * 16 + li)) * n2p32 +
+                                                           kb * 32 + 8 * lg + opaque_zero);
+        }
+
     // streaming: the loads of chunks 0 and 1 are issued before the token rows are filled, so that
     // all of them share one memory round trip
     v4i ring[R3_ITEMS], first[R3_ITEMS];
@@ -636,28 +674,7 @@ __device__ __forceinline__ void rotate3_token(char* lds, const uint16_t* __restr
             }
         }
     }
-    if (sh.resident) {
-        // all chunks at once, eight loads in flight per thread
-        const int total = sh.ch2 * crow_items;
-        for (int base = 0; base < total; base += 8 * nthreads) {
-            v4i tmp[8];
-#pragma unroll
-            for (int e = 0; e < 8; ++e) {
-                const int g = base + e * nthreads + tid;
-                const int gc = g < total ? g : total - 1;
-                const int ch = gc / crow_items;
-                tmp[e] = *chunk_src(ch, gc - ch * crow_items);
-            }
-#pragma unroll
-            for (int e = 0; e < 8; ++e) {
-                const int g = base + e * nthreads + tid;
-                if (g < total) {
-                    const int ch = g / crow_items;
-                    *chunk_dst(ch, g - ch * crow_items) = tmp[e];
-                }
-            }
-        }
-    } else {
+    if (!sh.resident) {
 #pragma unroll
         for (int e = 0; e < R3_ITEMS; ++e) {
             const int it = tid + e * nthreads;
@@ -825,6 +842,9 @@ __device__ __forceinline__ void rotate3_token(char* lds, const uint16_t* __restr
         scale[t] = amax / 31.0f;
     }
     RQTRACE(6);
+    if constexpr (LOOP) __syncthreads();               // the code image and the reduction words are free again
+    t += t_stride;
+    } while (LOOP && t < M);
     RQTRACE_FLUSH;
 }
 
@@ -956,12 +976,12 @@ __global__ __launch_bounds__(RQ_THREADS) void rotate_quant_kernel(RqArgs a) {
 }
 
 // rotation on bf16 MFMA (bf16 activations): 64 threads per 16-column strip of n2
-template <int ATM, int THREADS>
+template <int ATM, int THREADS, bool LOOP>
 __global__ __launch_bounds__(THREADS) void rotate_quant3_kernel(RqArgs a) {
     extern __shared__ __align__(16) float lds[];
     if ((int64_t)blockIdx.x < a.rot_blocks) {
-        rotate3_token<ATM>(reinterpret_cast<char*>(lds), reinterpret_cast<const uint16_t*>(a.X), blockIdx.x, a.K, a.n1,
-                           a.n2, a.R1p, a.R2p, a.q, a.scale, a.qsum);
+        rotate3_token<ATM, LOOP>(reinterpret_cast<char*>(lds), reinterpret_cast<const uint16_t*>(a.X), blockIdx.x,
+                           a.rot_blocks, a.M, a.K, a.n1, a.n2, a.R1p, a.R2p, a.q, a.scale, a.qsum);
     } else {
         const int pb = (int)(blockIdx.x - a.rot_blocks);
         psp_block<true>(reinterpret_cast<char*>(lds), a.X, a.M, a.K, a.r, a.U, a.T, a.counters, a.partials, a.S,
@@ -969,13 +989,19 @@ __global__ __launch_bounds__(THREADS) void rotate_quant3_kernel(RqArgs a) {
     }
 }
 
+template <int ATM, int THREADS, bool LOOP>
+hipError_t launch_rotate3_v(const RqArgs& a, int64_t blocks, int threads, size_t lds, hipStream_t st) {
+    static bwla_lds_attr attr;
+    hipError_t e = attr.ensure((const void*)rotate_quant3_kernel<ATM, THREADS, LOOP>, lds);
+    if (e != hipSuccess) return e;
+    rotate_quant3_kernel<ATM, THREADS, LOOP><<<dim3((unsigned)blocks), dim3((unsigned)threads), lds, st>>>(a);
+    return hipGetLastError();
+}
+// the looping variant only when a workgroup really has more than one token
 template <int ATM, int THREADS>
 hipError_t launch_rotate3(const RqArgs& a, int64_t blocks, int threads, size_t lds, hipStream_t st) {
-    static bwla_lds_attr attr;
-    hipError_t e = attr.ensure((const void*)rotate_quant3_kernel<ATM, THREADS>, lds);
-    if (e != hipSuccess) return e;
-    rotate_quant3_kernel<ATM, THREADS><<<dim3((unsigned)blocks), dim3((unsigned)threads), lds, st>>>(a);
-    return hipGetLastError();
+    if (a.rot_blocks < a.M) return launch_rotate3_v<ATM, THREADS, true>(a, blocks, threads, lds, st);
+    return launch_rotate3_v<ATM, THREADS, false>(a, blocks, threads, lds, st);
 }
 
 __global__ __launch_bounds__(256) void code_sums_kernel(const int8_t* __restrict__ q, int64_t K,
@@ -1067,11 +1093,22 @@ hipError_t bwla_launch_rotate_quant(const bwla_layer_t* L, const void* dX, int x
         const int threads = (merged && s3.strips < 8) ? 512 : 64 * s3.strips;
         const size_t pl3 = merged ? pp_lds_bytes(L->r, threads / 64) : 0;
         const size_t lds3 = pl3 > s3.lds_bytes ? pl3 : s3.lds_bytes;
+        // resident factors and many tokens: as many workgroups as fit the chip at once, each
+        // walking over its share of the tokens with the factors loaded once
+        if (s3.resident && !merged) {
+            int64_t per_cu = (int64_t)(RQ_LDS_LIMIT / lds3);
+            const int64_t by_waves = 32 / (threads / 64);              // at most 32 wavefronts per CU
+            if (per_cu > by_waves) per_cu = by_waves;
+            if (per_cu < 1) per_cu = 1;
+            const int64_t cap = per_cu * bwla_device_cus();
+            if (M > cap) a.rot_blocks = cap;
+        }
         // register budget: up to 8 wavefronts may use 256 VGPRs, 9 or 10 only 168
-        if (s3.strips <= 8 && s3.at <= 4) e = launch_rotate3<4, 512>(a, M + pblocks, threads, lds3, st);
-        else if (s3.strips <= 8 && s3.at <= 8) e = launch_rotate3<8, 512>(a, M + pblocks, threads, lds3, st);
-        else if (s3.at <= 12) e = launch_rotate3<12, 640>(a, M + pblocks, threads, lds3, st);
-        else e = launch_rotate3<16, 512>(a, M + pblocks, threads, lds3, st);
+        const int64_t grid = a.rot_blocks + pblocks;
+        if (s3.strips <= 8 && s3.at <= 4) e = launch_rotate3<4, 512>(a, grid, threads, lds3, st);
+        else if (s3.strips <= 8 && s3.at <= 8) e = launch_rotate3<8, 512>(a, grid, threads, lds3, st);
+        else if (s3.at <= 12) e = launch_rotate3<12, 640>(a, grid, threads, lds3, st);
+        else e = launch_rotate3<16, 512>(a, grid, threads, lds3, st);
         if (e != hipSuccess) return e;
         if (L->r > 0 && !merged) return bwla_launch_psp_prefill(L, dX, xdtype, M, dT, dws, plan, st);
         return hipSuccess;
