@@ -288,7 +288,8 @@ def main():
 
     if not args.no_extra:
         extra = []
-        names = ["cfg2_qwen32b_up_m16", "cfg3_qwen32b_down_m2048", "cfg4_70b_gate_m1", "cfg4_70b_down_m1"]
+        names = ["cfg2_qwen32b_up_m16", "cfg3_qwen32b_down_m2048", "cfg4_70b_gate_m1", "cfg4_70b_down_m1",
+                 "cfg4_70b_q_m64", "cfg4_70b_q_m4096"]
         for nm in names:
             if nm == cfg.name:
                 continue
