@@ -156,6 +156,20 @@ bwla_status_t bwla_linear_forward(const bwla_layer_t* layer, const int8_t* d_q, 
                                   const int32_t* d_qsum, const float* d_T, int64_t M,
                                   float* d_Y, int32_t* d_acc, void* stream);
 
+/*
+ * The whole forward of one layer, steps 1-5 above (paper Sec. 3.1, Sec. 4.1, Eq. 3-4, Sec. 3.2), in
+ * one call: same results as bwla_rotate_quant followed by bwla_linear_forward with the same
+ * buffers (d_q, d_scale, d_qsum, d_T are still written; same arguments, same errors).  For a single
+ * bf16 token of a layer without low-rank part (r == 0) on the common decode shapes (K = 4096 with
+ * n2 = 64, for one) everything runs in ONE kernel launch: every GEMM workgroup rotates and
+ * quantizes the token itself while its first weights are in flight, and nothing crosses
+ * workgroups.  All other cases run the two launches back to back.
+ */
+bwla_status_t bwla_decode_forward(const bwla_layer_t* layer, const void* d_X, int xdtype, int64_t M,
+                                  int8_t* d_q, float* d_scale, int32_t* d_qsum, float* d_T,
+                                  void* d_ws, size_t ws_bytes, float* d_Y, int32_t* d_acc,
+                                  void* stream);
+
 #ifdef __cplusplus
 }
 #endif

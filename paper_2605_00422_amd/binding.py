@@ -16,7 +16,7 @@ BWLA_X_F32, BWLA_X_BF16 = 0, 1
 
 EXPORTS = ["bwla_status_string", "bwla_version", "bwla_kron_factor", "bwla_packed_size", "bwla_pack_weights",
            "bwla_unpack_signs", "bwla_psp_workspace_size", "bwla_rotate_quant", "bwla_code_sums",
-           "bwla_linear_forward"]
+           "bwla_linear_forward", "bwla_decode_forward"]
 
 
 class BwlaLayer(Structure):
@@ -59,6 +59,8 @@ def load() -> ctypes.CDLL:
     lib.bwla_code_sums.argtypes = [c_void_p, c_int64, c_int64, c_void_p, c_void_p]
     lib.bwla_linear_forward.argtypes = [POINTER(BwlaLayer), c_void_p, c_void_p, c_void_p, c_void_p, c_int64,
                                         c_void_p, c_void_p, c_void_p]
+    lib.bwla_decode_forward.argtypes = [POINTER(BwlaLayer), c_void_p, c_int, c_int64, c_void_p, c_void_p, c_void_p,
+                                        c_void_p, c_void_p, c_size_t, c_void_p, c_void_p, c_void_p]
     for name in EXPORTS:
         if name not in ("bwla_status_string", "bwla_version"):
             getattr(lib, name).restype = c_int
@@ -170,6 +172,18 @@ def rotate_quant(layer: PackedLayer, X, act: Activations) -> Activations:
                                     _ptr(act.qsum), _ptr(act.T), _ptr(act.ws), act.ws_bytes, _stream()),
            "bwla_rotate_quant")
     return act
+
+
+def decode_forward(layer: PackedLayer, X, act: Activations, Y, acc=None):
+    """bwla_rotate_quant + bwla_linear_forward in one call (one kernel launch where possible)."""
+    import torch
+    if X.dtype not in (torch.bfloat16, torch.float32):
+        raise TypeError("X must be float32 or bfloat16")
+    xd = BWLA_X_BF16 if X.dtype == torch.bfloat16 else BWLA_X_F32
+    _check(load().bwla_decode_forward(byref(layer.desc), _ptr(X), xd, X.shape[0], _ptr(act.q), _ptr(act.scale),
+                                      _ptr(act.qsum), _ptr(act.T), _ptr(act.ws), act.ws_bytes, _ptr(Y), _ptr(acc),
+                                      _stream()), "bwla_decode_forward")
+    return Y
 
 
 def code_sums(q, qsum) -> None:

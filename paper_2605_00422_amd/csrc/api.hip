@@ -161,6 +161,32 @@ bwla_status_t bwla_rotate_quant(const bwla_layer_t* layer, const void* d_X, int 
     return BWLA_OK;
 }
 
+bwla_status_t bwla_decode_forward(const bwla_layer_t* layer, const void* d_X, int xdtype, int64_t M,
+                                  int8_t* d_q, float* d_scale, int32_t* d_qsum, float* d_T, void* d_ws,
+                                  size_t ws_bytes, float* d_Y, int32_t* d_acc, void* stream) {
+    bwla_status_t s = check_layer(layer);
+    if (s != BWLA_OK) return s;
+    if (!d_X || !d_q || !d_scale || !d_qsum || !d_Y) return BWLA_ERR_NULL;
+    if (layer->r > 0 && !d_T) return BWLA_ERR_NULL;
+    if (M <= 0 || M > (int64_t)1 << 24) return BWLA_ERR_SHAPE;
+    if (xdtype != BWLA_X_F32 && xdtype != BWLA_X_BF16) return BWLA_ERR_UNSUPPORTED;
+    if (!aligned16(d_X) || !aligned16(d_q) || !aligned16(d_Y) || (d_T && !aligned16(d_T)) ||
+        (d_ws && !aligned16(d_ws)) || (d_acc && !aligned16(d_acc)))
+        return BWLA_ERR_ALIGN;
+    const bwla_psp_plan plan = bwla_make_psp_plan(M, layer->K, layer->r);
+    const size_t need = psp_ws_bytes(plan, M, layer->r);
+    if (need > 0 && (!d_ws || ws_bytes < need)) return d_ws ? BWLA_ERR_BUFSIZE : BWLA_ERR_NULL;
+    hipStream_t st = (hipStream_t)stream;
+    // one launch when the shape allows it
+    bool done = false;
+    if (bwla_launch_decode_fused(layer, d_X, xdtype, M, d_q, d_scale, d_qsum, d_Y, d_acc, st, &done) != hipSuccess)
+        return BWLA_ERR_HIP;
+    if (done) return BWLA_OK;
+    s = bwla_rotate_quant(layer, d_X, xdtype, M, d_q, d_scale, d_qsum, d_T, d_ws, ws_bytes, stream);
+    if (s != BWLA_OK) return s;
+    return bwla_linear_forward(layer, d_q, d_scale, d_qsum, d_T, M, d_Y, d_acc, stream);
+}
+
 bwla_status_t bwla_code_sums(const int8_t* d_q, int64_t M, int64_t K, int32_t* d_qsum, void* stream) {
     if (!d_q || !d_qsum) return BWLA_ERR_NULL;
     if (M <= 0 || K <= 0 || M > (int64_t)1 << 24) return BWLA_ERR_SHAPE;

@@ -101,6 +101,9 @@ __device__ __forceinline__ bool bwla_partials_arrive(int* counter, int expected,
 #endif
 
 hipError_t bwla_launch_code_sums(const int8_t* dq, int64_t M, int64_t K, int32_t* dqsum, hipStream_t st);
+hipError_t bwla_launch_decode_fused(const bwla_layer_t* L, const void* dX, int xdtype, int64_t M, int8_t* dq,
+                                    float* dscale, int32_t* dqsum, float* dY, int32_t* dacc, hipStream_t st,
+                                    bool* done);
 
 hipError_t bwla_launch_gemm_decode(const bwla_layer_t* L, const int8_t* dq, const float* dscale,
                                    const int32_t* dqsum, const float* dT, int64_t M, float* dY,

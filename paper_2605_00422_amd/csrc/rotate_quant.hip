@@ -19,6 +19,7 @@
 // slices, every workgroup writes its partial tile to scratch and the one that arrives last adds
 // them in slice order.
 #include "bwla_internal.h"
+#include "gemm_decode_bs_device.h"
 
 namespace {
 
@@ -543,12 +544,17 @@ __device__ __forceinline__ void r3_split3(const float (&f)[8], v8bf& h1, v8bf& h
     }
 }
 
-template <int ATM, bool LOOP>
+// LOCAL (fused single-launch decode): the codes, the per-strip maxima and the per-strip code sums
+// stay in LDS for the rest of the workgroup (see r3_local); only if `store_out` are they also
+// written out.  The body then has exactly three barriers, which the workgroup's other wavefronts
+// match.
+template <int ATM, bool LOOP, bool LOCAL = false>
 __device__ __forceinline__ void rotate3_token(char* lds, const uint16_t* __restrict__ X, int64_t t_first,
                                               int64_t t_stride, int64_t M, int64_t K, int n1, int n2,
                                               const uint16_t* __restrict__ R1p,
                                               const uint16_t* __restrict__ R2p, int8_t* __restrict__ q,
-                                              float* __restrict__ scale, int32_t* __restrict__ qsum) {
+                                              float* __restrict__ scale, int32_t* __restrict__ qsum,
+                                              bool store_out = true) {
     const R3Shape sh = r3_shape(n1, n2);
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);         // = strip
@@ -829,23 +835,32 @@ __device__ __forceinline__ void rotate3_token(char* lds, const uint16_t* __restr
     int* redi = reinterpret_cast<int*>(red) + 16;
     if (lane == 0) redi[wave] = lsum;
     __syncthreads();
-    {
-        const uint4* src = reinterpret_cast<const uint4*>(codes);
-        uint4* dst = reinterpret_cast<uint4*>(q + t * K);
-        const int n16 = (int)(K >> 4);
-        for (int idx = tid; idx < n16; idx += nthreads) dst[idx] = src[idx];
-    }
-    if (tid == 0) {
-        int tot = 0;
-        for (int w = 0; w < sh.strips; ++w) tot += redi[w];
-        qsum[t] = tot;
-        scale[t] = amax / 31.0f;
+    if (!LOCAL || store_out) {
+        {
+            const uint4* src = reinterpret_cast<const uint4*>(codes);
+            uint4* dst = reinterpret_cast<uint4*>(q + t * K);
+            const int n16 = (int)(K >> 4);
+            for (int idx = tid; idx < n16; idx += nthreads) dst[idx] = src[idx];
+        }
+        if (tid == 0) {
+            int tot = 0;
+            for (int w = 0; w < sh.strips; ++w) tot += redi[w];
+            qsum[t] = tot;
+            scale[t] = amax / 31.0f;
+        }
     }
     RQTRACE(6);
     if constexpr (LOOP) __syncthreads();               // the code image and the reduction words are free again
     t += t_stride;
     } while (LOOP && t < M);
     RQTRACE_FLUSH;
+}
+
+// where rotate3_token<.., LOCAL> leaves its results (resident shapes only)
+__device__ __forceinline__ FusedLocal r3_local(const char* lds, const R3Shape& sh) {
+    // words [0, 16) maxima, [16, 32) sums (of the 64 words behind the chunk buffers)
+    const float* red = reinterpret_cast<const float*>(lds + sh.r0bytes + (size_t)sh.nbuf * sh.cbytes);
+    return FusedLocal{lds, red, reinterpret_cast<const int*>(red) + 16, sh.strips};
 }
 
 // ================================================================== PSP projection T = X U
@@ -1004,6 +1019,50 @@ hipError_t launch_rotate3(const RqArgs& a, int64_t blocks, int threads, size_t l
     return launch_rotate3_v<ATM, THREADS, false>(a, blocks, threads, lds, st);
 }
 
+// ---------------------------------------------------------------------------------------------
+// One launch for a whole decode layer with a single token and no low-rank part (r = 0).  Every
+// workgroup is a workgroup of the activation-stationary GEMM that first rotates and quantizes the
+// token itself: the rotation of one token is a few hundred kFLOP fed from L2, cheaper to repeat
+// per workgroup than to hand its result from one workgroup to all the others through memory, and
+// nothing crosses workgroups.  Wavefronts [0, strips) rotate while wavefronts
+// [strips, strips + KS), the GEMM's compute wavefronts, already have their first weights in
+// flight; then wavefront 0 goes on as the GEMM's epilogue wavefront and the other rotation
+// wavefronts end.  The first workgroup also writes codes, scale and code sum out.
+// (With r > 0 the projection T = x U would have to reach every workgroup inside the launch; the
+// arrival counting and the wait that this takes cost more than the second launch saves.)
+constexpr int FD_THREADS = 512;
+#ifdef BWLA_TRACE
+#define FDTRACE(slot) do { if ((threadIdx.x & 63) == 0 && (blockIdx.x & 3) == 0 && blockIdx.x < 256) bwla_trace_buf[((blockIdx.x >> 2) * 16 + 8 + (threadIdx.x >> 6)) * 40 + (slot)] = wall_clock64(); } while (0)
+#else
+#define FDTRACE(slot) do { } while (0)
+#endif
+template <int ATM, bool FAST>
+__global__ __launch_bounds__(FD_THREADS) void decode_fused_kernel(RqArgs ra, BsArgs ba) {
+    extern __shared__ __align__(16) float lds[];
+    const R3Shape sh = r3_shape(ra.n1, ra.n2);
+    char* rot = reinterpret_cast<char*>(lds);
+    char* smem = rot + ((sh.lds_bytes + 255) & ~(size_t)255);
+    const FusedLocal fl = r3_local(rot, sh);
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int first = (int)blockIdx.x, stride = (int)gridDim.x;
+    const int n_iter = (ba.row_tiles - first + stride - 1) / stride;
+    if (wave < sh.strips) {
+        FDTRACE(0);
+        rotate3_token<ATM, false, true>(rot, reinterpret_cast<const uint16_t*>(ra.X), 0, 1, 1, ra.K, ra.n1, ra.n2,
+                                        ra.R1p, ra.R2p, ra.q, ra.scale, ra.qsum, first == 0);
+        FDTRACE(1);
+        if (wave != 0) return;
+        epilogue_wave<2, 1, 0, FAST, true>(ba, smem, first, stride, n_iter, ba.KS, lane, fl);
+    } else {
+        const int cw = wave - sh.strips;
+        if (cw >= ba.KS) return;                                   // surplus wavefronts
+        // r = 0: only the wavefront that fetches the output scales has a side piece
+        if (cw == 0) compute_wave<BS_CPW, 2, 1, true, true>(ba, smem, first, stride, n_iter, cw, lane, fl);
+        else compute_wave<BS_CPW, 2, 1, false, true>(ba, smem, first, stride, n_iter, cw, lane, fl);
+    }
+}
+
 __global__ __launch_bounds__(256) void code_sums_kernel(const int8_t* __restrict__ q, int64_t K,
                                                         int32_t* __restrict__ qsum) {
     __shared__ int red[4];
@@ -1023,6 +1082,9 @@ __global__ __launch_bounds__(256) void code_sums_kernel(const int8_t* __restrict
 }  // namespace
 
 #ifdef BWLA_TRACE
+extern "C" int bwla_fd_trace_dump(long long* host, int n) {
+    return (int)hipMemcpyFromSymbol(host, HIP_SYMBOL(bwla_trace_buf), (size_t)n * sizeof(long long));
+}
 extern "C" int bwla_rq_trace_dump(long long* host, int n) {
     return (int)hipMemcpyFromSymbol(host, HIP_SYMBOL(bwla_rq_trace_buf), (size_t)n * sizeof(long long));
 }
@@ -1129,6 +1191,48 @@ hipError_t bwla_launch_rotate_quant(const bwla_layer_t* L, const void* dX, int x
     if (e != hipSuccess) return e;
     if (L->r > 0 && !merged) return bwla_launch_psp_prefill(L, dX, xdtype, M, dT, dws, plan, st);
     return hipSuccess;
+}
+
+// Single-launch decode layer.  *done = false (and nothing launched) when the shape is outside what
+// the fused kernel takes: one bf16 token, r = 0, factors resident in LDS with at most 8 tiles
+// along n1, rotation strips and GEMM compute wavefronts together within the 512-thread workgroup
+// (K = 4096 with n2 = 64: 4 + 4), and LDS for both roles side by side.
+hipError_t bwla_launch_decode_fused(const bwla_layer_t* L, const void* dX, int xdtype, int64_t M, int8_t* dq,
+                                    float* dscale, int32_t* dqsum, float* dY, int32_t* dacc, hipStream_t st,
+                                    bool* done) {
+    *done = false;
+    const R3Shape s3 = r3_shape(L->n1, L->n2);
+    const int chunks = (int)bwla_chunks(L->K), row_tiles = (int)bwla_row_tiles(L->N);
+    const int KS = (chunks + BS_CPW - 1) / BS_CPW;
+    if (M != 1 || L->r != 0 || xdtype != BWLA_X_BF16 || !s3.ok || !s3.resident || s3.at > 8 || (L->K & 15) != 0)
+        return hipSuccess;
+    if (chunks < 2 || s3.strips + KS > FD_THREADS / 64 || !bs_fits(M, chunks, 0, 1)) return hipSuccess;
+    const size_t lds = ((s3.lds_bytes + 255) & ~(size_t)255) + bs_lds_bytes(M, chunks, 0, 1);
+    if (lds > 160 * 1024) return hipSuccess;
+    const char* blob = (const char*)L->d_blob;
+    RqArgs ra{};
+    ra.X = dX; ra.M = M; ra.K = L->K; ra.n1 = L->n1; ra.n2 = L->n2; ra.r = 0;
+    ra.R1p = (const uint16_t*)(blob + L->off_R1p); ra.R2p = (const uint16_t*)(blob + L->off_R2p);
+    ra.q = dq; ra.scale = dscale; ra.qsum = dqsum;
+    BsArgs ba{(const uint4*)(blob + L->off_bits), chunks, row_tiles, dq, (int)M, (int)L->K, dscale, dqsum,
+              (const __half*)(blob + L->off_alpha), (const __half*)(blob + L->off_V), nullptr, 0, dY, (int)L->N,
+              dacc, KS};
+    // one workgroup per CU fits (registers)
+    const int cus = bwla_device_cus();
+    const int G = row_tiles < cus ? row_tiles : cus;
+    const bool fast = (L->N % 4 == 0) && dacc == nullptr;
+    auto launch = [&](auto kern) -> hipError_t {
+        static bwla_lds_attr attr;
+        hipError_t e = attr.ensure((const void*)kern, lds);
+        if (e != hipSuccess) return e;
+        kern<<<dim3((unsigned)G), dim3(FD_THREADS), lds, st>>>(ra, ba);
+        return hipGetLastError();
+    };
+    hipError_t e;
+    if (s3.at <= 4) e = fast ? launch(decode_fused_kernel<4, true>) : launch(decode_fused_kernel<4, false>);
+    else e = fast ? launch(decode_fused_kernel<8, true>) : launch(decode_fused_kernel<8, false>);
+    if (e == hipSuccess) *done = true;
+    return e;
 }
 
 hipError_t bwla_launch_code_sums(const int8_t* dq, int64_t M, int64_t K, int32_t* dqsum, hipStream_t st) {

@@ -73,6 +73,12 @@ def test_cfg4_70b_gate_m4096_sampled_rows():
     (520, 640, 20, 32, 330, 0, "bf16"),    # streaming GEMM without a low-rank branch
     (40, 480, 20, 24, 70, 8, "bf16"),      # K not a multiple of 128: LDS-tiled GEMM, 64 x 128 tiles
     (150, 160, 16, 10, 24, 4, "f32"),      # fewer than 32 channels: LDS-tiled GEMM, 128 x 128 tiles
+    # one token without low-rank part: bwla_decode_forward runs its single-launch kernel
+    (1, 4096, 64, 64, 4096, 0, "bf16"),    # 7B attention projection shape, one channel tile per workgroup
+    (1, 4096, 64, 64, 11008, 0, "bf16"),   # 7B gate/up shape: up to three channel tiles per workgroup
+    (1, 2048, 32, 64, 333, 0, "bf16"),     # ragged N (scalar stores), two compute wavefronts
+    (1, 1536, 48, 32, 1000, 0, "bf16"),    # two rotation strips, odd chunk count, last tile ragged
+    (1, 4096, 128, 32, 520, 0, "bf16"),    # eight tiles along n1
 ])
 def test_ragged_and_degenerate_shapes(M, K, n1, n2, N, r, xd):
     from parity_util import run_case
