@@ -98,7 +98,8 @@ __device__ __forceinline__ void stage_codes(const BsArgs& a, char* qt, int wave,
 // ------------------------------------------------------------------ compute wave
 template <int CPW, int DEPTH, int NT, bool SIDE, bool FUSED = false>
 __device__ __forceinline__ void compute_wave(const BsArgs& a, char* smem, int first, int stride, int n_iter,
-                                             int wave, int lane, const FusedLocal& fl = FusedLocal{}) {
+                                             int wave, int lane, const FusedLocal& fl = FusedLocal{},
+                                             int rotation_barriers = 0) {
     const int li = lane & 15, lg = lane >> 4;
     const int KS = a.KS, chunks = a.chunks;
     const int JT = (a.r + 15) >> 4, rp = JT * 16;
@@ -165,12 +166,11 @@ __device__ __forceinline__ void compute_wave(const BsArgs& a, char* smem, int fi
     const int brow = li < a.M ? li : a.M - 1;             // padded token columns repeat the last row; never stored
     if constexpr (FUSED) {
         // the weights are on their way; meanwhile the rotation wavefronts of this workgroup work
-        // through their three barriers, after the last of which the token's codes are in LDS
+        // through their barriers, after the last of which the token's codes are in LDS
         TRACE(0);
         if (wave == 0) bs_zero_fill<NT>(a, qt, red, lane);
-        bwla_lds_barrier();
-        bwla_lds_barrier();
-        bwla_lds_barrier();
+#pragma unroll
+        for (int i = 0; i < rotation_barriers; ++i) bwla_lds_barrier();
         TRACE(39);
         bs_local_stage_codes(a, qt, fl, wave, lane);
     } else {

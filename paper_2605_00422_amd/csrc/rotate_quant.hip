@@ -544,10 +544,17 @@ __device__ __forceinline__ void r3_split3(const float (&f)[8], v8bf& h1, v8bf& h
     }
 }
 
+// One token per workgroup with resident factors (!LOOP): everything the token needs is requested
+// in one go -- its R2 terms, the token itself, and last the R1 terms, which stay in flight (in
+// registers) through stage 1 and go to LDS just before stage 2.  Wavefronts beyond the strips, if
+// the workgroup has any (and they are not somebody else's, see LOCAL), carry their share of the R1
+// terms and end once it is in LDS.
 // LOCAL (fused single-launch decode): the codes, the per-strip maxima and the per-strip code sums
 // stay in LDS for the rest of the workgroup (see r3_local); only if `store_out` are they also
-// written out.  The body then has exactly three barriers, which the workgroup's other wavefronts
-// match.
+// written out.  The body then has exactly R3_LOCAL_BARRIERS barriers, which the workgroup's other
+// wavefronts match.
+constexpr int R3_FILLR = 12;         // 16-byte pieces of the R1 terms a thread keeps in flight
+constexpr int R3_LOCAL_BARRIERS = 4;
 template <int ATM, bool LOOP, bool LOCAL = false>
 __device__ __forceinline__ void rotate3_token(char* lds, const uint16_t* __restrict__ X, int64_t t_first,
                                               int64_t t_stride, int64_t M, int64_t K, int n1, int n2,
@@ -559,9 +566,13 @@ __device__ __forceinline__ void rotate3_token(char* lds, const uint16_t* __restr
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);         // = strip
     // the workgroup may have more wavefronts than strips (the projection workgroups of the same
-    // launch use them); those leave before the first barrier
-    if (wave >= sh.strips) return;
+    // launch use them): those only help to fetch the R1 terms, or leave at once
+    // (more than 8 tiles along n1 never fit LDS whole: no code for them)
+    const bool early = !LOOP && ATM <= 8 && sh.resident;
+    const bool helper = wave >= sh.strips;
+    if (helper && !(early && !LOCAL)) return;
     const int nthreads = 64 * sh.strips;
+    const int nfill = (early && !LOCAL) ? (int)blockDim.x : nthreads;
     RQTRACE_DECL;
     RQTRACE(0);
     const int li = lane & 15, lg = lane >> 4;
@@ -580,9 +591,55 @@ __device__ __forceinline__ void rotate3_token(char* lds, const uint16_t* __restr
     auto chunk_dst = [&](int buf, int item) -> v4i* {
         return reinterpret_cast<v4i*>(buf_base(buf) + (item >> 2) * R3_CPITCH + (item & 3) * 16);
     };
-    if (sh.resident) {
+    const int total = sh.ch2 * crow_items;
+    const FastDiv dci(crow_items);
+    v4i rp[R3_FILLR];
+    auto rp_issue = [&]() {
+#pragma unroll
+        for (int e = 0; e < R3_FILLR; ++e) {
+            const int g = tid + e * nfill;
+            const int gc = g < total ? g : total - 1;
+            const int ch = dci.div(gc);
+            rp[e] = *chunk_src(ch, gc - ch * crow_items);
+        }
+    };
+    auto rp_store = [&]() {
+#pragma unroll
+        for (int e = 0; e < R3_FILLR; ++e) {
+            const int g = tid + e * nfill;
+            if (g < total) {
+                const int ch = dci.div(g);
+                *chunk_dst(ch, g - ch * crow_items) = rp[e];
+            }
+        }
+        // what did not fit the first round
+        for (int base = R3_FILLR * nfill; base < total; base += 8 * nfill) {
+            v4i tmp[8];
+#pragma unroll
+            for (int e = 0; e < 8; ++e) {
+                const int g = base + e * nfill + tid;
+                const int gc = g < total ? g : total - 1;
+                const int ch = dci.div(gc);
+                tmp[e] = *chunk_src(ch, gc - ch * crow_items);
+            }
+#pragma unroll
+            for (int e = 0; e < 8; ++e) {
+                const int g = base + e * nfill + tid;
+                if (g < total) {
+                    const int ch = dci.div(g);
+                    *chunk_dst(ch, g - ch * crow_items) = tmp[e];
+                }
+            }
+        }
+    };
+    if (early && helper) {
+        rp_issue();
+        bwla_lds_barrier();                            // the barrier behind the token rows
+        rp_store();
+        return;                                        // (a wavefront ends only when its LDS writes have)
+    }
+    if (sh.resident && !early) {
         // all chunks at once, eight loads in flight per thread
-        const int total = sh.ch2 * crow_items;
         for (int base = 0; base < total; base += 8 * nthreads) {
             v4i tmp[8];
 #pragma unroll
@@ -658,6 +715,9 @@ __device__ __forceinline__ void rotate3_token(char* lds, const uint16_t* __restr
                     const v4i v = *reinterpret_cast<const v4i*>(xrow + (in ? (int64_t)a * n2 + b0 : 0));
                     tmp[e] = in ? v : v4i{0, 0, 0, 0};
                 }
+                // the R1 terms behind the first token loads: those are then waited for with
+                // these still in flight
+                if (early && base == 0) rp_issue();
 #pragma unroll
                 for (int e = 0; e < 8; ++e) {
                     const int it = base + e * nthreads + tid;
@@ -668,6 +728,7 @@ __device__ __forceinline__ void rotate3_token(char* lds, const uint16_t* __restr
                 }
             }
         } else {
+            if (early) rp_issue();
             for (int it = tid; it < items; it += nthreads) {
                 const int a = dpr.div(it), b0 = (it - a * per_row) << 3;
                 uint32_t w[4] = {0u, 0u, 0u, 0u};
@@ -688,7 +749,8 @@ __device__ __forceinline__ void rotate3_token(char* lds, const uint16_t* __restr
         }
     }
     RQTRACE(1);
-    __syncthreads();
+    // (one token per workgroup: a barrier that leaves the loads of later stages in flight)
+    if constexpr (LOOP) __syncthreads(); else bwla_lds_barrier();
     RQTRACE(2);
 
     // ---- stage 1
@@ -724,6 +786,11 @@ __device__ __forceinline__ void rotate3_token(char* lds, const uint16_t* __restr
 
     // ---- stage 2: chunk ch contracts a in [32 ch, 32 ch + 32) = accumulator tiles 2 ch, 2 ch + 1
     RQTRACE(3);
+    if (early) {
+        rp_store();
+        bwla_lds_barrier();
+        RQTRACE(7);
+    }
     if (sh.alias) __syncthreads();                     // the token rows make room for a chunk buffer
     v4f y[ATM];
 #pragma unroll
@@ -1058,8 +1125,10 @@ __global__ __launch_bounds__(FD_THREADS) void decode_fused_kernel(RqArgs ra, BsA
         const int cw = wave - sh.strips;
         if (cw >= ba.KS) return;                                   // surplus wavefronts
         // r = 0: only the wavefront that fetches the output scales has a side piece
-        if (cw == 0) compute_wave<BS_CPW, 2, 1, true, true>(ba, smem, first, stride, n_iter, cw, lane, fl);
-        else compute_wave<BS_CPW, 2, 1, false, true>(ba, smem, first, stride, n_iter, cw, lane, fl);
+        if (cw == 0)
+            compute_wave<BS_CPW, 2, 1, true, true>(ba, smem, first, stride, n_iter, cw, lane, fl, R3_LOCAL_BARRIERS);
+        else
+            compute_wave<BS_CPW, 2, 1, false, true>(ba, smem, first, stride, n_iter, cw, lane, fl, R3_LOCAL_BARRIERS);
     }
 }
 
@@ -1151,8 +1220,9 @@ hipError_t bwla_launch_rotate_quant(const bwla_layer_t* L, const void* dX, int x
     hipError_t e;
     const R3Shape s3 = r3_shape(L->n1, L->n2);
     if (xdtype == BWLA_X_BF16 && s3.ok) {
-        // projection workgroups in the same launch want all eight wavefronts
-        const int threads = (merged && s3.strips < 8) ? 512 : 64 * s3.strips;
+        // projection workgroups in the same launch want all eight wavefronts; so does a rotation
+        // workgroup with one token and resident factors (the extra wavefronts help to fetch them)
+        int threads = (merged && s3.strips < 8) ? 512 : 64 * s3.strips;
         const size_t pl3 = merged ? pp_lds_bytes(L->r, threads / 64) : 0;
         const size_t lds3 = pl3 > s3.lds_bytes ? pl3 : s3.lds_bytes;
         // resident factors and many tokens: as many workgroups as fit the chip at once, each
@@ -1165,6 +1235,7 @@ hipError_t bwla_launch_rotate_quant(const bwla_layer_t* L, const void* dX, int x
             const int64_t cap = per_cu * bwla_device_cus();
             if (M > cap) a.rot_blocks = cap;
         }
+        if (s3.resident && a.rot_blocks == M && s3.strips < 8) threads = 512;
         // register budget: up to 8 wavefronts may use 256 VGPRs, 9 or 10 only 168
         const int64_t grid = a.rot_blocks + pblocks;
         if (s3.strips <= 8 && s3.at <= 4) e = launch_rotate3<4, 512>(a, grid, threads, lds3, st);
