@@ -58,10 +58,11 @@ bwla_status_t check_layer(const bwla_layer_t* L) {
     return BWLA_OK;
 }
 
-size_t psp_ws_bytes(const bwla_psp_plan& p, int64_t M, int r) {
-    if (r <= 0 || p.splits <= 1) return 0;
-    return (size_t)(bwla_psp_counter_bytes(M) + (uint64_t)p.token_tiles * p.col_groups * p.splits *
-                                                    p.tile_rows * p.tile_cols * sizeof(float));
+// scratch of bwla_rotate_quant: the projection's part, then (256-byte aligned) the split rotation's
+size_t rq_ws_bytes(const bwla_layer_t* L, const bwla_psp_plan& p, int64_t M) {
+    const size_t split = bwla_split_rotation_bytes(L, p, M);
+    const size_t psp = bwla_psp_ws_bytes(p, M, L->r);
+    return split ? (size_t)bwla_align256(psp) + split : psp;
 }
 
 }  // namespace
@@ -137,7 +138,7 @@ bwla_status_t bwla_psp_workspace_size(const bwla_layer_t* layer, int64_t M, size
     bwla_status_t s = check_layer(layer);
     if (s != BWLA_OK) return s;
     if (M <= 0) return BWLA_ERR_SHAPE;
-    *bytes = psp_ws_bytes(bwla_make_psp_plan(M, layer->K, layer->r), M, layer->r);
+    *bytes = rq_ws_bytes(layer, bwla_make_psp_plan(M, layer->K, layer->r), M);
     return BWLA_OK;
 }
 
@@ -153,7 +154,7 @@ bwla_status_t bwla_rotate_quant(const bwla_layer_t* layer, const void* d_X, int 
     if (!aligned16(d_X) || !aligned16(d_q) || (d_T && !aligned16(d_T)) || (d_ws && !aligned16(d_ws)))
         return BWLA_ERR_ALIGN;
     const bwla_psp_plan plan = bwla_make_psp_plan(M, layer->K, layer->r);
-    const size_t need = psp_ws_bytes(plan, M, layer->r);
+    const size_t need = rq_ws_bytes(layer, plan, M);
     if (need > 0 && (!d_ws || ws_bytes < need)) return d_ws ? BWLA_ERR_BUFSIZE : BWLA_ERR_NULL;
     hipStream_t st = (hipStream_t)stream;
     if (bwla_launch_rotate_quant(layer, d_X, xdtype, M, d_q, d_scale, d_qsum, d_T, d_ws, plan, st) != hipSuccess)
@@ -174,7 +175,7 @@ bwla_status_t bwla_decode_forward(const bwla_layer_t* layer, const void* d_X, in
         (d_ws && !aligned16(d_ws)) || (d_acc && !aligned16(d_acc)))
         return BWLA_ERR_ALIGN;
     const bwla_psp_plan plan = bwla_make_psp_plan(M, layer->K, layer->r);
-    const size_t need = psp_ws_bytes(plan, M, layer->r);
+    const size_t need = rq_ws_bytes(layer, plan, M);
     if (need > 0 && (!d_ws || ws_bytes < need)) return d_ws ? BWLA_ERR_BUFSIZE : BWLA_ERR_NULL;
     hipStream_t st = (hipStream_t)stream;
     // one launch when the shape allows it

@@ -45,6 +45,14 @@ struct bwla_psp_plan {
 bwla_psp_plan bwla_make_psp_plan(int64_t M, int64_t K, int r);
 // scratch starts with one arrival counter per 16 tokens (whatever the plan), padded to 256 bytes
 inline uint64_t bwla_psp_counter_bytes(int64_t M) { return bwla_align256((uint64_t)((M + 15) / 16) * sizeof(int)); }
+inline size_t bwla_psp_ws_bytes(const bwla_psp_plan& p, int64_t M, int r) {
+    if (r <= 0 || p.splits <= 1) return 0;
+    return (size_t)(bwla_psp_counter_bytes(M) + (uint64_t)p.token_tiles * p.col_groups * p.splits *
+                                                    p.tile_rows * p.tile_cols * sizeof(float));
+}
+// Bytes the rotation wants behind the projection's scratch when it is split over several
+// workgroups per token and a second launch (few bf16 tokens, R1 too large for LDS); else 0.
+size_t bwla_split_rotation_bytes(const bwla_layer_t* L, const bwla_psp_plan& plan, int64_t M);
 int bwla_psp_prefill_tile_cols(int rp);
 hipError_t bwla_launch_psp_prefill(const bwla_layer_t* L, const void* dX, int xdtype, int64_t M, float* dT,
                                    void* dws, const bwla_psp_plan& plan, hipStream_t st);
