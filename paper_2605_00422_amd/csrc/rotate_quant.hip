@@ -1283,21 +1283,22 @@ __device__ __forceinline__ void psp_block(char* smem, const void* __restrict__ X
 
     if (!bwla_partials_arrive(&counters[tt], S, &is_last)) return;
     // last workgroup of this token tile: add the S partial tiles in slice order
-    for (int idx = tid; idx < 16 * rp; idx += (int)blockDim.x) {
+    const int rows = M - (int64_t)tt * 16 < 16 ? (int)(M - (int64_t)tt * 16) : 16;
+    for (int idx = tid; idx < rows * rp; idx += (int)blockDim.x) {
         const int row = idx / rp, col = idx - row * rp;
         const int64_t tok = (int64_t)tt * 16 + row;
-        if (tok < M && col < r) {
-            // batches of eight loads in flight; slices past S re-read the last one and add zero
+        if (col < r) {
+            // batches of sixteen loads in flight; slices past S re-read the last one and add zero
             float sum = 0.0f;
-            for (int ss = 0; ss < S; ss += 8) {
-                float v[8];
+            for (int ss = 0; ss < S; ss += 16) {
+                float v[16];
 #pragma unroll
-                for (int u = 0; u < 8; ++u) {
+                for (int u = 0; u < 16; ++u) {
                     const int sc = ss + u < S ? ss + u : S - 1;
                     v[u] = bwla_load_agent(&partials[(((int64_t)tt * S + sc) * 16 + row) * rp + col]);
                 }
 #pragma unroll
-                for (int u = 0; u < 8; ++u) sum += ss + u < S ? v[u] : 0.0f;
+                for (int u = 0; u < 16; ++u) sum += ss + u < S ? v[u] : 0.0f;
             }
             T[tok * r + col] = sum;
         }
