@@ -597,17 +597,19 @@ __device__ __forceinline__ void rotate3_token(char* lds, const uint16_t* __restr
     auto rp_issue = [&]() {
 #pragma unroll
         for (int e = 0; e < R3_FILLR; ++e) {
-            const int g = tid + e * nfill;
-            const int gc = g < total ? g : total - 1;
-            const int ch = dci.div(gc);
-            rp[e] = *chunk_src(ch, gc - ch * crow_items);
+            if (e * nfill < total) {                   // (uniform: small factors need few rounds)
+                const int g = tid + e * nfill;
+                const int gc = g < total ? g : total - 1;
+                const int ch = dci.div(gc);
+                rp[e] = *chunk_src(ch, gc - ch * crow_items);
+            }
         }
     };
     auto rp_store = [&]() {
 #pragma unroll
         for (int e = 0; e < R3_FILLR; ++e) {
             const int g = tid + e * nfill;
-            if (g < total) {
+            if (e * nfill < total && g < total) {
                 const int ch = dci.div(g);
                 *chunk_dst(ch, g - ch * crow_items) = rp[e];
             }
@@ -638,6 +640,7 @@ __device__ __forceinline__ void rotate3_token(char* lds, const uint16_t* __restr
         rp_store();
         return;                                        // (a wavefront ends only when its LDS writes have)
     }
+    if (early) rp_issue();                             // first of all: the largest request of the token
     if (sh.resident && !early) {
         // all chunks at once, eight loads in flight per thread
         for (int base = 0; base < total; base += 8 * nthreads) {
@@ -715,9 +718,6 @@ __device__ __forceinline__ void rotate3_token(char* lds, const uint16_t* __restr
                     const v4i v = *reinterpret_cast<const v4i*>(xrow + (in ? (int64_t)a * n2 + b0 : 0));
                     tmp[e] = in ? v : v4i{0, 0, 0, 0};
                 }
-                // the R1 terms behind the first token loads: those are then waited for with
-                // these still in flight
-                if (early && base == 0) rp_issue();
 #pragma unroll
                 for (int e = 0; e < 8; ++e) {
                     const int it = base + e * nthreads + tid;
@@ -728,7 +728,6 @@ __device__ __forceinline__ void rotate3_token(char* lds, const uint16_t* __restr
                 }
             }
         } else {
-            if (early) rp_issue();
             for (int it = tid; it < items; it += nthreads) {
                 const int a = dpr.div(it), b0 = (it - a * per_row) << 3;
                 uint32_t w[4] = {0u, 0u, 0u, 0u};
