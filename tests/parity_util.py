@@ -87,7 +87,8 @@ def run_case(cfg: syn.LayerConfig, rows=None) -> dict:
     acc = torch.empty((cfg.M, cfg.N), dtype=torch.int32, device=DEV)
     B.linear_forward(layer, act, Y, acc)
     torch.cuda.synchronize()
-    ncnt = (((cfg.M + 15) // 16) * 4 + 255) // 256 * 256
+    # the scratch starts with the projection's arrival counters (if there is a projection)
+    ncnt = (((cfg.M + 15) // 16) * 4 + 255) // 256 * 256 if cfg.r > 0 else 0
     assert int(torch.count_nonzero(act.ws[:ncnt])) == 0, "arrival counters not restored to zero"
 
     # the one-call entry point (a single launch for one bf16 token) gives the same bits, also when

@@ -79,6 +79,9 @@ def test_cfg4_70b_gate_m4096_sampled_rows():
     (1, 2048, 32, 64, 333, 0, "bf16"),     # ragged N (scalar stores), two compute wavefronts
     (1, 1536, 48, 32, 1000, 0, "bf16"),    # two rotation strips, odd chunk count, last tile ragged
     (1, 4096, 128, 32, 520, 0, "bf16"),    # eight tiles along n1
+    # few tokens, R1 too large for LDS: rotation split over several workgroups + quantizing launch
+    (3, 16896, 176, 96, 80, 8, "bf16"),    # odd number of tiles along n1: the last slice has one tile
+    (2, 20000, 200, 100, 48, 0, "bf16"),   # ragged n1 and n2 (strips and tiles partly filled), r = 0
 ])
 def test_ragged_and_degenerate_shapes(M, K, n1, n2, N, r, xd):
     from parity_util import run_case
