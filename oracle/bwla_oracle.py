@@ -17,6 +17,12 @@ step by step, not the dense product:
   4. PSP branch   L = (X U) V^T                             (paper Sec. 3.2 "PSP": W_res = W - M, M = A B)
   5. dequantize   Y = s_t * alpha_n * acc + L               (paper Sec. 3 "Discussion", Eq. 4; App. A.2.4)
 
+Variant with row-wise centering (paper Sec. 3 "Discussion", Eq. 1-2 and 4 in full): the shift
+mu_n = mean_k W[n,k] is taken out before the sign and the scale are computed, and comes back at
+dequantization: W_deq = delta_n Sign(W - mu_n) + mu_n, so Y = s_t (delta_n acc + mu_n qsum_t) + L
+with qsum_t the sum of the token's codes (binarize_rows_centered, dequant_output_centered,
+forward(..., centered=True)).
+
 Pins (tests/test_oracle_pins.py, no GPU): every function below is checked against something
 other than itself -- the dense Kronecker product, norm preservation and forward invariance,
 hand-derived worked values, the closed-form optimal scale and its residual, brute-force loops,
@@ -117,6 +123,18 @@ def binarize_rows(W: np.ndarray):
     return sgn, alpha
 
 
+def binarize_rows_centered(W: np.ndarray):
+    """Row-wise binarization with the shift (paper Sec. 3 "Discussion", Eq. 1-2):
+    mu_n = mean_k W[n,k], delta_n = mean_k |W[n,k] - mu_n|, sign of the centered weight, with
+    Sign(0) = -1 (Eq. 3).  Returns (sgn int8 (N,K) in {-1,+1}, delta fp64 (N,), mu fp64 (N,))."""
+    W = np.asarray(W, dtype=np.float64)
+    mu = np.mean(W, axis=1)
+    C = W - mu[:, None]
+    sgn = np.where(C > 0, 1, -1).astype(np.int8)
+    delta = np.mean(np.abs(C), axis=1)
+    return sgn, delta, mu
+
+
 def to_fp16(a: np.ndarray) -> np.ndarray:
     """Round to the fp16 storage grid (nearest even) and return as fp64."""
     return np.asarray(a, dtype=np.float64).astype(np.float16).astype(np.float64)
@@ -167,19 +185,38 @@ def dequant_output(acc, s, alpha, T=None, V=None) -> np.ndarray:
     return Y
 
 
+def dequant_output_centered(acc, s, delta, mu, qsum, T=None, V=None) -> np.ndarray:
+    """Dequantization with the shift (paper Sec. 3 "Discussion", Eq. 4: W_deq = W~ delta + mu):
+    the dequantized token s_t q[t,:] times W_deq[n,:] = delta_n sgn[n,:] + mu_n gives
+    Y[t,n] = s_t * (delta_n * acc[t,n] + mu_n * qsum_t) + sum_j T[t,j] V[n,j],  qsum_t = sum_k q[t,k]."""
+    s = np.asarray(s, dtype=np.float64)[:, None]
+    Y = s * (np.asarray(delta, dtype=np.float64)[None, :] * np.asarray(acc, dtype=np.float64)
+             + np.asarray(mu, dtype=np.float64)[None, :] * np.asarray(qsum, dtype=np.float64)[:, None])
+    if T is not None and V is not None and np.asarray(T).shape[1] > 0:
+        Y = Y + np.asarray(T, dtype=np.float64) @ np.asarray(V, dtype=np.float64).T
+    return Y
+
+
 # --------------------------------------------------------------------------- whole path
-def forward(X, R1, R2, W_rot, U=None, V=None) -> dict:
+def forward(X, R1, R2, W_rot, U=None, V=None, centered: bool = False) -> dict:
     """The whole hot path on stored parameter values.
 
     X      (M,K)  activations as stored (already on the bf16 or fp32 grid)
     R1,R2  fp32 orthogonal factors
     W_rot  (N,K)  the weight matrix in rotated (and PSP-corrected) coordinates, fp32
     U (K,r), V (N,r): PSP factors on the fp16 grid, or None / r = 0
-    The scale alpha is rounded to fp16 because that is how the layer stores it.
+    The scale alpha (and, with centered=True, the shift mu) is rounded to fp16 because that is
+    how the layer stores it.  centered=True: binarization with the row shift (Eq. 1-2, 4).
     """
     Xr = kron_rotate(X, R1, R2)
     q, s, v = quantize_int6(Xr)
-    sgn, alpha = binarize_rows(W_rot)
+    qsum = q.astype(np.int64).sum(axis=1)
+    if centered:
+        sgn, alpha, mu = binarize_rows_centered(W_rot)
+        mu16 = to_fp16(mu)
+    else:
+        sgn, alpha = binarize_rows(W_rot)
+        mu = mu16 = None
     alpha16 = to_fp16(alpha)
     acc = binary_gemm(q, sgn)
     if U is not None and np.asarray(U).size > 0:
@@ -187,14 +224,18 @@ def forward(X, R1, R2, W_rot, U=None, V=None) -> dict:
     else:
         T = np.zeros((np.asarray(X).shape[0], 0))
         V = np.zeros((np.asarray(W_rot).shape[0], 0))
-    Y = dequant_output(acc, s, alpha16, T, V)
-    return dict(Xr=Xr, q=q, s=s, v=v, sgn=sgn, alpha=alpha, alpha16=alpha16,
-                acc=acc, T=T, Y=Y, qsum=q.astype(np.int64).sum(axis=1))
+    if centered:
+        Y = dequant_output_centered(acc, s, alpha16, mu16, qsum, T, V)
+    else:
+        Y = dequant_output(acc, s, alpha16, T, V)
+    return dict(Xr=Xr, q=q, s=s, v=v, sgn=sgn, alpha=alpha, alpha16=alpha16, mu=mu, mu16=mu16,
+                acc=acc, T=T, Y=Y, qsum=qsum)
 
 
-def forward_rows(X, R1, R2, sgn, alpha16, U, V, rows) -> dict:
+def forward_rows(X, R1, R2, sgn, alpha16, U, V, rows, mu16=None) -> dict:
     """The path for a subset of token rows (tokens are independent: per-token scale,
-    row-wise products).  Used where the full M would take minutes on the CPU."""
+    row-wise products).  Used where the full M would take minutes on the CPU.  With mu16 the
+    layer is one with row shifts (sgn, alpha16 from binarize_rows_centered)."""
     Xs = np.asarray(X)[rows]
     Xr = kron_rotate(Xs, R1, R2)
     q, s, v = quantize_int6(Xr)
@@ -204,9 +245,12 @@ def forward_rows(X, R1, R2, sgn, alpha16, U, V, rows) -> dict:
     else:
         T = np.zeros((Xs.shape[0], 0))
         V = np.zeros((np.asarray(sgn).shape[0], 0))
-    Y = dequant_output(acc, s, alpha16, T, V)
-    return dict(Xr=Xr, q=q, s=s, v=v, acc=acc, T=T, Y=Y,
-                qsum=q.astype(np.int64).sum(axis=1))
+    qsum = q.astype(np.int64).sum(axis=1)
+    if mu16 is not None:
+        Y = dequant_output_centered(acc, s, alpha16, mu16, qsum, T, V)
+    else:
+        Y = dequant_output(acc, s, alpha16, T, V)
+    return dict(Xr=Xr, q=q, s=s, v=v, acc=acc, T=T, Y=Y, qsum=qsum)
 
 
 def forward_loops(X, R1, R2, W_rot, U, V) -> np.ndarray:

@@ -227,6 +227,107 @@ def test_low_rank_split_is_function_preserving():
     # a transposed or swapped factor cannot satisfy this with these shapes (7 != 30 != 3)
 
 
+# ------------------------------------------------------------------ binarization with the row shift
+def test_centered_binarization_matches_scalar_loops_and_sign_of_zero():
+    rng = np.random.default_rng(21)
+    W = rng.normal(0.3, 1.0, size=(5, 12))
+    W[2, :] = [1.0, 3.0, 1.0, 3.0, 2.0, 2.0, 1.0, 3.0, 2.0, 2.0, 1.0, 3.0]   # mean 2: four exact zeros after centering
+    sgn, delta, mu = orc.binarize_rows_centered(W)
+    for n in range(5):
+        m = math.fsum(W[n]) / 12
+        assert math.isclose(mu[n], m, rel_tol=1e-15, abs_tol=1e-16)
+        assert math.isclose(delta[n], math.fsum(abs(w - m) for w in W[n]) / 12, rel_tol=1e-14)
+    assert mu[2] == 2.0 and math.isclose(delta[2], 2.0 / 3.0, rel_tol=1e-15)
+    assert sgn[2].tolist() == [-1, 1, -1, 1, -1, -1, -1, 1, -1, -1, -1, 1]    # Sign(0) = -1
+    assert np.array_equal(sgn[[0, 1, 3, 4]], np.where(W[[0, 1, 3, 4]] - mu[[0, 1, 3, 4], None] > 0, 1, -1))
+
+
+def test_centered_scale_is_least_squares_and_shifted_two_point_rows_are_exact():
+    rng = np.random.default_rng(22)
+    W = rng.normal(-0.2, 0.5, size=(4, 64))
+    sgn, delta, mu = orc.binarize_rows_centered(W)
+    C = W - mu[:, None]
+    loss = lambda d: np.sum((C - d[:, None] * sgn) ** 2, axis=1)
+    base = loss(delta)
+    assert np.allclose(base, 64 * np.var(np.abs(C), axis=1), rtol=1e-12)      # K * Var|w - mu|
+    for eps in (1e-3, -1e-3):
+        assert np.all(loss(delta + eps) > base)
+    # rows that take the two values mu +- c equally often are reproduced exactly
+    c = np.array([0.5, 0.125, 2.0]); m = np.array([1.0, -0.25, 4.0])
+    pat = np.tile([1.0, -1.0], 8)
+    W2 = m[:, None] + c[:, None] * np.stack([pat, np.roll(pat, 1), pat])
+    sgn2, delta2, mu2 = orc.binarize_rows_centered(W2)
+    assert np.array_equal(mu2, m) and np.array_equal(delta2, c)
+    assert np.array_equal(delta2[:, None] * sgn2 + mu2[:, None], W2)
+
+
+def test_centered_dequantization_is_the_product_with_the_dequantized_weights():
+    """Y = s (delta acc + mu qsum) + T V^T against the dense route: dequantized activations
+    times W_deq = delta sgn + mu (paper Eq. 4), plus the low-rank product."""
+    rng = np.random.default_rng(23)
+    M, K, N, r = 7, 48, 9, 3
+    q = rng.integers(-31, 32, size=(M, K)).astype(np.int8)
+    s = rng.uniform(0.01, 0.2, size=M)
+    W = rng.normal(0.1, 0.3, size=(N, K))
+    sgn, delta, mu = orc.binarize_rows_centered(W)
+    T = rng.normal(size=(M, r)); V = rng.normal(size=(N, r))
+    acc = orc.binary_gemm(q, sgn)
+    Y = orc.dequant_output_centered(acc, s, delta, mu, q.astype(np.int64).sum(axis=1), T, V)
+    Wdeq = delta[:, None] * sgn + mu[:, None]
+    Yd = (s[:, None] * q.astype(np.float64)) @ Wdeq.T + T @ V.T
+    assert np.allclose(Y, Yd, rtol=1e-12, atol=1e-12)
+    # dropping the shift term is a different result (the term is really there)
+    assert not np.allclose(orc.dequant_output(acc, s, delta, T, V), Yd, rtol=1e-3)
+
+
+def test_centered_equals_uncentered_when_row_means_vanish():
+    rng = np.random.default_rng(24)
+    n1, n2, N = 4, 8, 6
+    half = rng.integers(-60, 61, size=(N, 16)) / 1024.0       # dyadic grid: every partial sum is exact
+    W = np.concatenate([half, -half], axis=1)                 # every row sums to zero exactly
+    W = W[:, rng.permutation(32)]
+    X = rng.standard_t(3, size=(5, 32))
+    R1, R2 = _orth(rng, n1), _orth(rng, n2)
+    a = orc.forward(X, R1, R2, W)
+    b = orc.forward(X, R1, R2, W, centered=True)
+    assert np.array_equal(b["mu"], np.zeros(N))
+    assert np.array_equal(a["sgn"], b["sgn"]) and np.array_equal(a["alpha16"], b["alpha16"])
+    assert np.allclose(a["Y"], b["Y"], rtol=1e-14, atol=0.0)  # (same value, products taken in another order)
+
+
+def test_hand_example_centered():
+    g = _read_golden("hand_example_centered.txt")
+    X = np.array([g["x"]])
+    R1 = np.array(g["R1"]).reshape(2, 2)
+    R2 = np.array(g["R2"]).reshape(2, 2)
+    W = np.array([g["w0"], g["w1"]])
+    out = orc.forward(X, R1, R2, W, centered=True)
+    assert out["q"][0].tolist() == [int(v) for v in g["q"]]
+    assert math.isclose(out["s"][0], g["s"][0], rel_tol=1e-15)
+    assert out["mu"].tolist() == g["mu"] and out["alpha"].tolist() == g["delta"]
+    assert out["sgn"].tolist() == [[int(v) for v in g["sgn0"]], [int(v) for v in g["sgn1"]]]
+    Wdeq = out["alpha"][:, None] * out["sgn"] + out["mu"][:, None]
+    assert Wdeq.tolist() == [g["wdeq0"], g["wdeq1"]]
+    assert out["acc"][0].tolist() == [int(v) for v in g["acc"]]
+    assert out["qsum"][0] == int(g["qsum"][0])
+    assert np.allclose(out["Y"][0], g["y"], rtol=1e-14)
+
+
+def test_centered_forward_rows_matches_forward():
+    rng = np.random.default_rng(25)
+    cfg = syn.CONFIGS["cfg0_tiny"]
+    d = syn.make_layer(cfg)
+    W = d.W + rng.normal(0.0, 0.01, size=(cfg.N, 1)).astype(np.float32)
+    full = orc.forward(d.X, d.R1, d.R2, W, d.U, d.V, centered=True)
+    sgn, delta, mu = orc.binarize_rows_centered(W)
+    rows = np.array([0, 5, 15])
+    part = orc.forward_rows(d.X, d.R1, d.R2, sgn, orc.to_fp16(delta), d.U, d.V, rows, mu16=orc.to_fp16(mu))
+    assert np.array_equal(part["Y"], full["Y"][rows]) and np.array_equal(part["q"], full["q"][rows])
+    # and the shift matters at this size: without it the output moves by more than the tolerance
+    plain = orc.forward_rows(d.X, d.R1, d.R2, sgn, orc.to_fp16(delta), d.U, d.V, rows)
+    assert np.linalg.norm(plain["Y"] - part["Y"]) > 1e-2 * np.linalg.norm(part["Y"])
+
+
 # ------------------------------------------------------------------ end to end
 def test_hand_example_2x2():
     g = _read_golden("hand_example_2x2.txt")
