@@ -65,10 +65,14 @@ typedef enum {
  *   R1     n1 x n1 fp32 row-major;  R2  n2 x n2 fp32 row-major
  *   R1p, R2p  the same factors transposed and split into three bfloat16 terms each (their sum is
  *          the fp32 value exactly), zero padded: operand layout of the bf16-MFMA rotation
+ * A layer packed with the row shift (bwla_pack_weights_centered) has centered == 1 and r one
+ * larger than its PSP rank: column r-1 of V holds the shifts mu_n, U keeps r-1 columns, and
+ * column r-1 of T is scale_t * qsum_t (see bwla_rotate_quant), so that the shift term of the
+ * dequantization is one more term of the low-rank sum.
  */
 typedef struct bwla_layer {
     int64_t N, K;
-    int32_t n1, n2, r, reserved;
+    int32_t n1, n2, r, centered;
     uint64_t off_bits, off_alpha, off_V, off_U, off_R1, off_R2, off_R1p, off_R2p;
     uint64_t blob_bytes;
     const void* d_blob;
@@ -105,6 +109,23 @@ bwla_status_t bwla_pack_weights(const float* d_W_rot, const float* d_R1, const f
                                 int64_t N, int64_t K, int32_t n1, int32_t n2, int32_t r,
                                 void* d_blob, size_t blob_bytes, void* stream,
                                 bwla_layer_t* out);
+
+/*
+ * The same with the row shift of the paper's binarization (Sec. 3 "Discussion", Eq. 1-2 and 4):
+ *   mu_n = mean_k W_rot[n,k] (fp64 accumulation), bit = (W_rot[n,k] - mu_n > 0),
+ *   delta_n = mean_k |W_rot[n,k] - mu_n| (stored where alpha is), W_deq = delta_n Sign(.) + mu_n,
+ * so that Y[t,n] = scale_t * (delta_n * acc[t,n] + mu_n * qsum_t) + sum_j T[t,j] V[n,j].
+ * mu_n is stored in fp16 as one more column of V; the layer's r becomes r + 1 (at most
+ * BWLA_MAX_RANK), centered = 1.  Arguments as for bwla_pack_weights / bwla_packed_size, with r
+ * the PSP rank (columns of d_U and d_V).
+ */
+bwla_status_t bwla_packed_size_centered(int64_t N, int64_t K, int32_t n1, int32_t n2, int32_t r,
+                                        size_t* bytes);
+bwla_status_t bwla_pack_weights_centered(const float* d_W_rot, const float* d_R1, const float* d_R2,
+                                         const float* d_U, const float* d_V,
+                                         int64_t N, int64_t K, int32_t n1, int32_t n2, int32_t r,
+                                         void* d_blob, size_t blob_bytes, void* stream,
+                                         bwla_layer_t* out);
 
 /*
  * Inspection helper: expand the packed sign bits to the interchange view, an N x K int8

@@ -16,12 +16,12 @@ BWLA_X_F32, BWLA_X_BF16 = 0, 1
 
 EXPORTS = ["bwla_status_string", "bwla_version", "bwla_kron_factor", "bwla_packed_size", "bwla_pack_weights",
            "bwla_unpack_signs", "bwla_psp_workspace_size", "bwla_rotate_quant", "bwla_code_sums",
-           "bwla_linear_forward", "bwla_decode_forward"]
+           "bwla_linear_forward", "bwla_decode_forward", "bwla_packed_size_centered", "bwla_pack_weights_centered"]
 
 
 class BwlaLayer(Structure):
     _fields_ = [("N", c_int64), ("K", c_int64), ("n1", c_int32), ("n2", c_int32), ("r", c_int32),
-                ("reserved", c_int32), ("off_bits", c_uint64), ("off_alpha", c_uint64), ("off_V", c_uint64),
+                ("centered", c_int32), ("off_bits", c_uint64), ("off_alpha", c_uint64), ("off_V", c_uint64),
                 ("off_U", c_uint64), ("off_R1", c_uint64), ("off_R2", c_uint64), ("off_R1p", c_uint64), ("off_R2p", c_uint64),
                 ("blob_bytes", c_uint64),
                 ("d_blob", c_void_p)]
@@ -52,6 +52,8 @@ def load() -> ctypes.CDLL:
     lib.bwla_packed_size.argtypes = [c_int64, c_int64, c_int32, c_int32, c_int32, POINTER(c_size_t)]
     lib.bwla_pack_weights.argtypes = [c_void_p] * 5 + [c_int64, c_int64, c_int32, c_int32, c_int32, c_void_p,
                                                        c_size_t, c_void_p, POINTER(BwlaLayer)]
+    lib.bwla_packed_size_centered.argtypes = lib.bwla_packed_size.argtypes
+    lib.bwla_pack_weights_centered.argtypes = lib.bwla_pack_weights.argtypes
     lib.bwla_unpack_signs.argtypes = [POINTER(BwlaLayer), c_void_p, c_void_p, c_void_p]
     lib.bwla_psp_workspace_size.argtypes = [POINTER(BwlaLayer), c_int64, POINTER(c_size_t)]
     lib.bwla_rotate_quant.argtypes = [POINTER(BwlaLayer), c_void_p, c_int, c_int64, c_void_p, c_void_p, c_void_p,
@@ -97,9 +99,10 @@ def kron_factor(K: int) -> tuple[int, int]:
     return n1.value, n2.value
 
 
-def packed_size(N: int, K: int, n1: int, n2: int, r: int) -> int:
+def packed_size(N: int, K: int, n1: int, n2: int, r: int, centered: bool = False) -> int:
     out = c_size_t()
-    _check(load().bwla_packed_size(N, K, n1, n2, r, byref(out)), "bwla_packed_size")
+    name = "bwla_packed_size_centered" if centered else "bwla_packed_size"
+    _check(getattr(load(), name)(N, K, n1, n2, r, byref(out)), name)
     return out.value
 
 
@@ -117,16 +120,18 @@ class PackedLayer:
         return d.N, d.K, d.n1, d.n2, d.r
 
 
-def pack_weights(W_rot, R1, R2, U, V, n1: int, n2: int) -> PackedLayer:
-    """W_rot (N,K), R1, R2, U (K,r), V (N,r): fp32 CUDA tensors (U, V may be None for r = 0)."""
+def pack_weights(W_rot, R1, R2, U, V, n1: int, n2: int, centered: bool = False) -> PackedLayer:
+    """W_rot (N,K), R1, R2, U (K,r), V (N,r): fp32 CUDA tensors (U, V may be None for r = 0).
+    centered: binarize with the row shift (bwla_pack_weights_centered)."""
     import torch
     N, K = W_rot.shape
     r = 0 if U is None else U.shape[1]
-    nbytes = packed_size(N, K, n1, n2, r)
+    nbytes = packed_size(N, K, n1, n2, r, centered)
     blob = torch.zeros(nbytes, dtype=torch.uint8, device=W_rot.device)
     desc = BwlaLayer()
-    _check(load().bwla_pack_weights(_ptr(W_rot), _ptr(R1), _ptr(R2), _ptr(U), _ptr(V), N, K, n1, n2, r,
-                                    _ptr(blob), nbytes, _stream(), byref(desc)), "bwla_pack_weights")
+    name = "bwla_pack_weights_centered" if centered else "bwla_pack_weights"
+    _check(getattr(load(), name)(_ptr(W_rot), _ptr(R1), _ptr(R2), _ptr(U), _ptr(V), N, K, n1, n2, r,
+                                 _ptr(blob), nbytes, _stream(), byref(desc)), name)
     return PackedLayer(desc, blob)
 
 

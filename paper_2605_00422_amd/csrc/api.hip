@@ -28,14 +28,16 @@ bwla_status_t check_shape(int64_t N, int64_t K, int32_t n1, int32_t n2, int32_t 
     return BWLA_OK;
 }
 
-void fill_layout(bwla_layer_t* L, int64_t N, int64_t K, int32_t n1, int32_t n2, int32_t r) {
+// r counts the columns of V and T; a layer with row shifts keeps one column fewer in U
+void fill_layout(bwla_layer_t* L, int64_t N, int64_t K, int32_t n1, int32_t n2, int32_t r, int32_t centered) {
     const uint64_t rp = (uint64_t)((r + 15) & ~15);
+    const uint64_t rpu = (uint64_t)((r - centered + 15) & ~15);
     uint64_t off = 0;
-    L->N = N; L->K = K; L->n1 = n1; L->n2 = n2; L->r = r; L->reserved = 0;
+    L->N = N; L->K = K; L->n1 = n1; L->n2 = n2; L->r = r; L->centered = centered;
     L->off_bits = off;  off = bwla_align256(off + (uint64_t)bwla_row_tiles(N) * bwla_chunks(K) * BWLA_UNIT_BYTES);
     L->off_alpha = off; off = bwla_align256(off + (uint64_t)N * 2);
     L->off_V = off;     off = bwla_align256(off + (uint64_t)N * rp * 2);
-    L->off_U = off;     off = bwla_align256(off + (uint64_t)K * rp * 2);
+    L->off_U = off;     off = bwla_align256(off + (uint64_t)K * rpu * 2);
     L->off_R1 = off;    off = bwla_align256(off + (uint64_t)n1 * n1 * 4);
     L->off_R2 = off;    off = bwla_align256(off + (uint64_t)n2 * n2 * 4);
     L->off_R1p = off;   off = bwla_align256(off + bwla_factor_planes_bytes(n1));
@@ -48,8 +50,9 @@ bwla_status_t check_layer(const bwla_layer_t* L) {
     if (!L->d_blob) return BWLA_ERR_NULL;
     bwla_status_t s = check_shape(L->N, L->K, L->n1, L->n2, L->r);
     if (s != BWLA_OK) return s;
+    if ((L->centered != 0 && L->centered != 1) || L->r < L->centered) return BWLA_ERR_SHAPE;
     bwla_layer_t ref;
-    fill_layout(&ref, L->N, L->K, L->n1, L->n2, L->r);
+    fill_layout(&ref, L->N, L->K, L->n1, L->n2, L->r, L->centered);
     if (ref.off_bits != L->off_bits || ref.off_alpha != L->off_alpha || ref.off_V != L->off_V ||
         ref.off_U != L->off_U || ref.off_R1 != L->off_R1 || ref.off_R2 != L->off_R2 ||
         ref.off_R1p != L->off_R1p || ref.off_R2p != L->off_R2p || ref.blob_bytes != L->blob_bytes)
@@ -61,7 +64,7 @@ bwla_status_t check_layer(const bwla_layer_t* L) {
 // scratch of bwla_rotate_quant: the projection's part, then (256-byte aligned) the split rotation's
 size_t rq_ws_bytes(const bwla_layer_t* L, const bwla_psp_plan& p, int64_t M) {
     const size_t split = bwla_split_rotation_bytes(L, p, M);
-    const size_t psp = bwla_psp_ws_bytes(p, M, L->r);
+    const size_t psp = bwla_psp_ws_bytes(p, M, bwla_rank_u(L));
     return split ? (size_t)bwla_align256(psp) + split : psp;
 }
 
@@ -97,13 +100,44 @@ bwla_status_t bwla_kron_factor(int64_t K, int32_t* n1, int32_t* n2) {
     return BWLA_OK;
 }
 
-bwla_status_t bwla_packed_size(int64_t N, int64_t K, int32_t n1, int32_t n2, int32_t r, size_t* bytes) {
+static bwla_status_t packed_size(int64_t N, int64_t K, int32_t n1, int32_t n2, int32_t r, int32_t centered,
+                                 size_t* bytes) {
     if (!bytes) return BWLA_ERR_NULL;
-    bwla_status_t s = check_shape(N, K, n1, n2, r);
+    if (r < 0) return BWLA_ERR_SHAPE;
+    bwla_status_t s = check_shape(N, K, n1, n2, r + centered);
     if (s != BWLA_OK) return s;
     bwla_layer_t L;
-    fill_layout(&L, N, K, n1, n2, r);
+    fill_layout(&L, N, K, n1, n2, r + centered, centered);
     *bytes = (size_t)L.blob_bytes;
+    return BWLA_OK;
+}
+
+bwla_status_t bwla_packed_size(int64_t N, int64_t K, int32_t n1, int32_t n2, int32_t r, size_t* bytes) {
+    return packed_size(N, K, n1, n2, r, 0, bytes);
+}
+
+bwla_status_t bwla_packed_size_centered(int64_t N, int64_t K, int32_t n1, int32_t n2, int32_t r, size_t* bytes) {
+    return packed_size(N, K, n1, n2, r, 1, bytes);
+}
+
+// r is the PSP rank (columns of d_U and d_V); the layer's r is r + centered
+static bwla_status_t pack_weights(const float* d_W_rot, const float* d_R1, const float* d_R2, const float* d_U,
+                                  const float* d_V, int64_t N, int64_t K, int32_t n1, int32_t n2, int32_t r,
+                                  int32_t centered, void* d_blob, size_t blob_bytes, void* stream,
+                                  bwla_layer_t* out) {
+    if (!d_W_rot || !d_R1 || !d_R2 || !d_blob || !out) return BWLA_ERR_NULL;
+    if (r < 0) return BWLA_ERR_SHAPE;
+    bwla_status_t s = check_shape(N, K, n1, n2, r + centered);
+    if (s != BWLA_OK) return s;
+    if (r > 0 && (!d_U || !d_V)) return BWLA_ERR_NULL;
+    if (!aligned16(d_W_rot) || !aligned16(d_blob) || !aligned16(d_R1) || !aligned16(d_R2)) return BWLA_ERR_ALIGN;
+    bwla_layer_t L;
+    fill_layout(&L, N, K, n1, n2, r + centered, centered);
+    if (blob_bytes < L.blob_bytes) return BWLA_ERR_BUFSIZE;
+    L.d_blob = d_blob;
+    hipError_t e = bwla_launch_pack(d_W_rot, d_R1, d_R2, d_U, d_V, N, K, n1, n2, r, &L, (hipStream_t)stream);
+    if (e != hipSuccess) return BWLA_ERR_HIP;
+    *out = L;
     return BWLA_OK;
 }
 
@@ -111,19 +145,14 @@ bwla_status_t bwla_pack_weights(const float* d_W_rot, const float* d_R1, const f
                                 const float* d_U, const float* d_V, int64_t N, int64_t K, int32_t n1,
                                 int32_t n2, int32_t r, void* d_blob, size_t blob_bytes, void* stream,
                                 bwla_layer_t* out) {
-    if (!d_W_rot || !d_R1 || !d_R2 || !d_blob || !out) return BWLA_ERR_NULL;
-    bwla_status_t s = check_shape(N, K, n1, n2, r);
-    if (s != BWLA_OK) return s;
-    if (r > 0 && (!d_U || !d_V)) return BWLA_ERR_NULL;
-    if (!aligned16(d_W_rot) || !aligned16(d_blob) || !aligned16(d_R1) || !aligned16(d_R2)) return BWLA_ERR_ALIGN;
-    bwla_layer_t L;
-    fill_layout(&L, N, K, n1, n2, r);
-    if (blob_bytes < L.blob_bytes) return BWLA_ERR_BUFSIZE;
-    L.d_blob = d_blob;
-    hipError_t e = bwla_launch_pack(d_W_rot, d_R1, d_R2, d_U, d_V, N, K, n1, n2, r, &L, (hipStream_t)stream);
-    if (e != hipSuccess) return BWLA_ERR_HIP;
-    *out = L;
-    return BWLA_OK;
+    return pack_weights(d_W_rot, d_R1, d_R2, d_U, d_V, N, K, n1, n2, r, 0, d_blob, blob_bytes, stream, out);
+}
+
+bwla_status_t bwla_pack_weights_centered(const float* d_W_rot, const float* d_R1, const float* d_R2,
+                                         const float* d_U, const float* d_V, int64_t N, int64_t K, int32_t n1,
+                                         int32_t n2, int32_t r, void* d_blob, size_t blob_bytes, void* stream,
+                                         bwla_layer_t* out) {
+    return pack_weights(d_W_rot, d_R1, d_R2, d_U, d_V, N, K, n1, n2, r, 1, d_blob, blob_bytes, stream, out);
 }
 
 bwla_status_t bwla_unpack_signs(const bwla_layer_t* layer, int8_t* d_sgn, float* d_alpha, void* stream) {
@@ -138,7 +167,7 @@ bwla_status_t bwla_psp_workspace_size(const bwla_layer_t* layer, int64_t M, size
     bwla_status_t s = check_layer(layer);
     if (s != BWLA_OK) return s;
     if (M <= 0) return BWLA_ERR_SHAPE;
-    *bytes = rq_ws_bytes(layer, bwla_make_psp_plan(M, layer->K, layer->r), M);
+    *bytes = rq_ws_bytes(layer, bwla_make_psp_plan(M, layer->K, bwla_rank_u(layer)), M);
     return BWLA_OK;
 }
 
@@ -153,7 +182,7 @@ bwla_status_t bwla_rotate_quant(const bwla_layer_t* layer, const void* d_X, int 
     if (xdtype != BWLA_X_F32 && xdtype != BWLA_X_BF16) return BWLA_ERR_UNSUPPORTED;
     if (!aligned16(d_X) || !aligned16(d_q) || (d_T && !aligned16(d_T)) || (d_ws && !aligned16(d_ws)))
         return BWLA_ERR_ALIGN;
-    const bwla_psp_plan plan = bwla_make_psp_plan(M, layer->K, layer->r);
+    const bwla_psp_plan plan = bwla_make_psp_plan(M, layer->K, bwla_rank_u(layer));
     const size_t need = rq_ws_bytes(layer, plan, M);
     if (need > 0 && (!d_ws || ws_bytes < need)) return d_ws ? BWLA_ERR_BUFSIZE : BWLA_ERR_NULL;
     hipStream_t st = (hipStream_t)stream;
@@ -174,7 +203,7 @@ bwla_status_t bwla_decode_forward(const bwla_layer_t* layer, const void* d_X, in
     if (!aligned16(d_X) || !aligned16(d_q) || !aligned16(d_Y) || (d_T && !aligned16(d_T)) ||
         (d_ws && !aligned16(d_ws)) || (d_acc && !aligned16(d_acc)))
         return BWLA_ERR_ALIGN;
-    const bwla_psp_plan plan = bwla_make_psp_plan(M, layer->K, layer->r);
+    const bwla_psp_plan plan = bwla_make_psp_plan(M, layer->K, bwla_rank_u(layer));
     const size_t need = rq_ws_bytes(layer, plan, M);
     if (need > 0 && (!d_ws || ws_bytes < need)) return d_ws ? BWLA_ERR_BUFSIZE : BWLA_ERR_NULL;
     hipStream_t st = (hipStream_t)stream;

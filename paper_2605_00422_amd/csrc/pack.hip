@@ -59,6 +59,65 @@ __global__ __launch_bounds__(64) void row_scale_kernel(const float* __restrict__
     if (threadIdx.x == 0) alpha[n] = double_to_half_bits(s / (double)K);
 }
 
+// Binarization with the row shift (paper Sec. 3 "Discussion", Eq. 1-2): one workgroup per tile of
+// 16 rows.  First the fp64 row means mu; then, chunk by chunk, the bits of (w - mu > 0) in the
+// tiled layout (padding columns stay 0) and the fp64 sums of |w - mu|, added up in a fixed order;
+// delta goes where alpha is, mu (fp16) into column `mu_col` of V.
+__global__ __launch_bounds__(256) void pack_rows_centered_kernel(const float* __restrict__ W, int64_t N, int64_t K,
+                                                                 int64_t chunks, uint32_t* __restrict__ bits,
+                                                                 uint16_t* __restrict__ alpha,
+                                                                 uint16_t* __restrict__ V16, int rp, int mu_col) {
+    __shared__ double mu[16];
+    __shared__ double part[4][64];
+    const int64_t rt = blockIdx.x;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    for (int rr = 0; rr < 4; ++rr) {                     // wave w: rows 4w .. 4w+3 of the tile
+        const int64_t n = rt * BWLA_TILE_ROWS + wave * 4 + rr;
+        double s = 0.0;
+        if (n < N) {
+            const float* row = W + n * K;
+            for (int64_t k = lane; k < K; k += 64) s += (double)row[k];
+        }
+#pragma unroll
+        for (int off = 32; off > 0; off >>= 1) s += __shfl_xor(s, off, 64);
+        if (lane == 0) mu[wave * 4 + rr] = s / (double)K;
+    }
+    __syncthreads();
+    const int i = lane & 15, g = lane >> 4;
+    const int64_t n = rt * BWLA_TILE_ROWS + i;
+    const double m = mu[i];
+    double dsum = 0.0;
+    for (int64_t kc = wave; kc < chunks; kc += 4) {
+        const int64_t kbase = kc * BWLA_CHUNK_COLS + g * 128;
+        uint32_t w[4] = {0u, 0u, 0u, 0u};
+        if (n < N) {
+            const float* row = W + n * K;
+#pragma unroll 4
+            for (int kk = 0; kk < 128; ++kk) {
+                const int64_t k = kbase + kk;
+                if (k < K) {
+                    const double c = (double)row[k] - m;
+                    const int j = kk >> 4, d = (kk >> 2) & 3, b = kk & 3;
+                    if (c > 0.0) w[d] |= 1u << (8 * b + j);
+                    dsum += fabs(c);
+                }
+            }
+        }
+        reinterpret_cast<uint4*>(bits)[(rt * chunks + kc) * 64 + lane] = make_uint4(w[0], w[1], w[2], w[3]);
+    }
+    part[wave][lane] = dsum;
+    __syncthreads();
+    if (tid < 16 && rt * BWLA_TILE_ROWS + tid < N) {
+        double s = 0.0;
+        for (int w2 = 0; w2 < 4; ++w2)
+            for (int g2 = 0; g2 < 4; ++g2) s += part[w2][g2 * 16 + tid];
+        const int64_t row = rt * BWLA_TILE_ROWS + tid;
+        alpha[row] = double_to_half_bits(s / (double)K);
+        const double mm = mu[tid];
+        V16[row * rp + mu_col] = (uint16_t)((mm < 0.0 ? 0x8000u : 0u) | double_to_half_bits(fabs(mm)));
+    }
+}
+
 // rows x r fp32 -> rows x rp fp16 (rp = r rounded up to 16, zero padded)
 __global__ void f32_to_f16_rows_kernel(const float* __restrict__ src, int64_t rows, int r, int rp,
                                        __half* __restrict__ dst) {
@@ -135,16 +194,26 @@ __global__ void unpack_kernel(const uint32_t* __restrict__ bits, const __half* _
 hipError_t bwla_launch_pack(const float* dW, const float* dR1, const float* dR2, const float* dU,
                             const float* dV, int64_t N, int64_t K, int n1, int n2, int r,
                             const bwla_layer_t* L, hipStream_t st) {
+    // r = columns of dU and dV (the PSP rank); V has L->r columns (one more with row shifts)
     char* blob = (char*)L->d_blob;
     const int64_t chunks = bwla_chunks(K), rts = bwla_row_tiles(N);
-    pack_bits_kernel<<<dim3((unsigned)(rts * chunks)), dim3(64), 0, st>>>(
-        dW, N, K, chunks, (uint32_t*)(blob + L->off_bits));
-    row_scale_kernel<<<dim3((unsigned)N), dim3(64), 0, st>>>(dW, N, K, (uint16_t*)(blob + L->off_alpha));
+    const int rpv = (L->r + 15) & ~15, rpu = (r + 15) & ~15;
+    if (L->r > 0) {
+        const int64_t nv = N * rpv;
+        f32_to_f16_rows_kernel<<<dim3((unsigned)((nv + 255) / 256)), dim3(256), 0, st>>>(dV, N, r, rpv, (__half*)(blob + L->off_V));
+    }
     if (r > 0) {
-        const int rp = (r + 15) & ~15;
-        const int64_t nv = N * rp, nu = K * rp;
-        f32_to_f16_rows_kernel<<<dim3((unsigned)((nv + 255) / 256)), dim3(256), 0, st>>>(dV, N, r, rp, (__half*)(blob + L->off_V));
-        u_transpose_f16_kernel<<<dim3((unsigned)((nu + 255) / 256)), dim3(256), 0, st>>>(dU, K, r, rp, (__half*)(blob + L->off_U));
+        const int64_t nu = K * rpu;
+        u_transpose_f16_kernel<<<dim3((unsigned)((nu + 255) / 256)), dim3(256), 0, st>>>(dU, K, r, rpu, (__half*)(blob + L->off_U));
+    }
+    if (L->centered) {
+        pack_rows_centered_kernel<<<dim3((unsigned)rts), dim3(256), 0, st>>>(
+            dW, N, K, chunks, (uint32_t*)(blob + L->off_bits), (uint16_t*)(blob + L->off_alpha),
+            (uint16_t*)(blob + L->off_V), rpv, r);
+    } else {
+        pack_bits_kernel<<<dim3((unsigned)(rts * chunks)), dim3(64), 0, st>>>(
+            dW, N, K, chunks, (uint32_t*)(blob + L->off_bits));
+        row_scale_kernel<<<dim3((unsigned)N), dim3(64), 0, st>>>(dW, N, K, (uint16_t*)(blob + L->off_alpha));
     }
     const int64_t e1 = (int64_t)n1 * n1, e2 = (int64_t)n2 * n2;
     copy_f32_kernel<<<dim3((unsigned)((e1 + 255) / 256)), dim3(256), 0, st>>>(dR1, e1, (float*)(blob + L->off_R1));

@@ -24,7 +24,8 @@ constexpr int PF_KSTEP = 32;              // K per bf16 MFMA
 typedef __attribute__((ext_vector_type(8))) __bf16 v8bf;
 
 struct PfArgs {
-    const void* X; int64_t M, K; int r, rp;
+    const void* X; int64_t M, K; int r, rp;   // r = rank of the projection (columns of U)
+    int tp;                               // row pitch of T (r, or r + 1 for a layer with row shifts)
     const __half* Ut;                     // [rp][K] fp16
     float* T; int* counters; float* partials;
     int S, JG, kslice;
@@ -204,7 +205,7 @@ __global__ __launch_bounds__(PF_THREADS) void psp_prefill_kernel(PfArgs a) {
             const float vv[4] = {v.x, v.y, v.z, v.w};
 #pragma unroll
             for (int c = 0; c < 4; ++c)
-                if (col0 + col + c < a.r) a.T[tok * a.r + col0 + col + c] = vv[c];
+                if (col0 + col + c < a.r) a.T[tok * a.tp + col0 + col + c] = vv[c];
         }
     };
     // a partial tile is stored as four planes (one per vector component), so that the scalar
@@ -273,7 +274,7 @@ hipError_t bwla_launch_psp_prefill(const bwla_layer_t* L, const void* dX, int xd
                                    void* dws, const bwla_psp_plan& plan, hipStream_t st) {
     const char* blob = (const char*)L->d_blob;
     PfArgs a;
-    a.X = dX; a.M = M; a.K = L->K; a.r = L->r; a.rp = (L->r + 15) & ~15;
+    a.X = dX; a.M = M; a.K = L->K; a.r = bwla_rank_u(L); a.rp = (a.r + 15) & ~15; a.tp = L->r;
     a.Ut = (const __half*)(blob + L->off_U);
     a.T = dT;
     a.counters = (int*)dws;

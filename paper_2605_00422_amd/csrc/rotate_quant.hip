@@ -258,7 +258,7 @@ template <bool BF16>
 __device__ __forceinline__ void rotate_token(float* lds, const void* __restrict__ X, int64_t t, int64_t K, int n1,
                                              int n2, const float* __restrict__ R1, const float* __restrict__ R2,
                                              int8_t* __restrict__ q, float* __restrict__ scale,
-                                             int32_t* __restrict__ qsum) {
+                                             int32_t* __restrict__ qsum, float* __restrict__ tshift, int tp) {
     const RqShape sh = rq_shape(n1, n2);
     float* reg = lds;                                              // V, later ZT
     float* fac = lds + sh.region;                                  // R2T | R1T (resident) or two chunk buffers
@@ -478,6 +478,7 @@ __device__ __forceinline__ void rotate_token(float* lds, const void* __restrict_
         for (int w = 0; w < RQ_WAVES; ++w) tot += redi[w];
         qsum[t] = tot;
         scale[t] = amax / 31.0f;
+        if (tshift) tshift[t * tp] = (amax / 31.0f) * (float)tot;      // the shift term's entry of T
     }
     RQTRACE(8);
     RQTRACE_FLUSH;
@@ -561,7 +562,8 @@ __device__ __forceinline__ void rotate3_token(char* lds, const uint16_t* __restr
                                               const uint16_t* __restrict__ R1p,
                                               const uint16_t* __restrict__ R2p, int8_t* __restrict__ q,
                                               float* __restrict__ scale, int32_t* __restrict__ qsum,
-                                              bool store_out = true) {
+                                              bool store_out = true, float* __restrict__ tshift = nullptr,
+                                              int tp = 0) {
     const R3Shape sh = r3_shape(n1, n2);
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);         // = strip
@@ -913,6 +915,7 @@ __device__ __forceinline__ void rotate3_token(char* lds, const uint16_t* __restr
             for (int w = 0; w < sh.strips; ++w) tot += redi[w];
             qsum[t] = tot;
             scale[t] = amax / 31.0f;
+            if (tshift) tshift[t * tp] = (amax / 31.0f) * (float)tot;  // the shift term's entry of T
         }
     }
     RQTRACE(6);
@@ -1191,6 +1194,13 @@ __global__ __launch_bounds__(512) void quantize_rows_kernel(const float* __restr
     }
 }
 
+// layers with row shifts, after the split rotation: T[t, last] = scale_t * qsum_t
+__global__ void shift_column_kernel(const float* __restrict__ scale, const int32_t* __restrict__ qsum, int64_t M,
+                                    float* __restrict__ tshift, int tp) {
+    const int64_t t = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (t < M) tshift[t * tp] = scale[t] * (float)qsum[t];
+}
+
 // where rotate3_token<.., LOCAL> leaves its results (resident shapes only)
 __device__ __forceinline__ FusedLocal r3_local(const char* lds, const R3Shape& sh) {
     // words [0, 16) maxima, [16, 32) sums (of the 64 words behind the chunk buffers)
@@ -1203,7 +1213,7 @@ template <bool BF16>
 __device__ __forceinline__ void psp_block(char* smem, const void* __restrict__ X, int64_t M, int64_t K, int r,
                                           const __half* __restrict__ U, float* __restrict__ T,
                                           int* __restrict__ counters, float* __restrict__ partials, int S, int tt,
-                                          int s) {
+                                          int s, int tp) {
     __shared__ int is_last;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int nw = (int)(blockDim.x >> 6);             // the eight 64-column parts of a slice are dealt to nw waves
@@ -1272,7 +1282,7 @@ __device__ __forceinline__ void psp_block(char* smem, const void* __restrict__ X
             const int row = 4 * lg + v;
             const int64_t tok = (int64_t)tt * 16 + row;
             if (S == 1) {
-                if (tok < M && col < r) T[tok * r + col] = sum[v];
+                if (tok < M && col < r) T[tok * tp + col] = sum[v];
             } else {
                 bwla_store_agent(&partials[(((int64_t)tt * S + s) * 16 + row) * rp + col], sum[v]);
             }
@@ -1299,7 +1309,7 @@ __device__ __forceinline__ void psp_block(char* smem, const void* __restrict__ X
 #pragma unroll
                 for (int u = 0; u < 16; ++u) sum += ss + u < S ? v[u] : 0.0f;
             }
-            T[tok * r + col] = sum;
+            T[tok * tp + col] = sum;
         }
     }
     if (tid == 0) counters[tt] = 0;                    // leave the scratch as it was found
@@ -1311,6 +1321,8 @@ struct RqArgs {
     int8_t* q; float* scale; int32_t* qsum; float* T;
     int* counters; float* partials; int S;
     float* xs; float* pmax;  // split rotation: rotated values (M x K) and per-workgroup maxima (M x G)
+    int tp;                  // row pitch of T (= r, or r + 1 for a layer with row shifts)
+    float* tshift;           // T + r for such a layer (entry scale_t * qsum_t of each row), else NULL
     int64_t rot_blocks;      // workgroups below this index rotate token blockIdx.x, the rest project
     const uint16_t* R1p; const uint16_t* R2p;          // bf16 term planes of the factors
 };
@@ -1319,11 +1331,11 @@ template <bool BF16>
 __global__ __launch_bounds__(RQ_THREADS) void rotate_quant_kernel(RqArgs a) {
     extern __shared__ __align__(16) float lds[];
     if ((int64_t)blockIdx.x < a.rot_blocks) {
-        rotate_token<BF16>(lds, a.X, blockIdx.x, a.K, a.n1, a.n2, a.R1, a.R2, a.q, a.scale, a.qsum);
+        rotate_token<BF16>(lds, a.X, blockIdx.x, a.K, a.n1, a.n2, a.R1, a.R2, a.q, a.scale, a.qsum, a.tshift, a.tp);
     } else {
         const int pb = (int)(blockIdx.x - a.rot_blocks);
         psp_block<BF16>(reinterpret_cast<char*>(lds), a.X, a.M, a.K, a.r, a.U, a.T, a.counters, a.partials, a.S,
-                        pb / a.S, pb % a.S);
+                        pb / a.S, pb % a.S, a.tp);
     }
 }
 
@@ -1333,11 +1345,12 @@ __global__ __launch_bounds__(THREADS) void rotate_quant3_kernel(RqArgs a) {
     extern __shared__ __align__(16) float lds[];
     if ((int64_t)blockIdx.x < a.rot_blocks) {
         rotate3_token<ATM, LOOP>(reinterpret_cast<char*>(lds), reinterpret_cast<const uint16_t*>(a.X), blockIdx.x,
-                           a.rot_blocks, a.M, a.K, a.n1, a.n2, a.R1p, a.R2p, a.q, a.scale, a.qsum);
+                           a.rot_blocks, a.M, a.K, a.n1, a.n2, a.R1p, a.R2p, a.q, a.scale, a.qsum, true, a.tshift,
+                           a.tp);
     } else {
         const int pb = (int)(blockIdx.x - a.rot_blocks);
         psp_block<true>(reinterpret_cast<char*>(lds), a.X, a.M, a.K, a.r, a.U, a.T, a.counters, a.partials, a.S,
-                        pb / a.S, pb % a.S);
+                        pb / a.S, pb % a.S, a.tp);
     }
 }
 
@@ -1352,7 +1365,7 @@ __global__ __launch_bounds__(512) void rotate_split_kernel(RqArgs a) {
     } else {
         const int pb = (int)(blockIdx.x - a.rot_blocks);
         psp_block<true>(reinterpret_cast<char*>(lds), a.X, a.M, a.K, a.r, a.U, a.T, a.counters, a.partials, a.S,
-                        pb / a.S, pb % a.S);
+                        pb / a.S, pb % a.S, a.tp);
     }
 }
 
@@ -1488,7 +1501,9 @@ hipError_t bwla_launch_rotate_quant(const bwla_layer_t* L, const void* dX, int x
     const char* blob = (const char*)L->d_blob;
     const RqShape sh = rq_shape(L->n1, L->n2);
     RqArgs a;
-    a.X = dX; a.M = M; a.K = L->K; a.n1 = L->n1; a.n2 = L->n2; a.r = L->r;
+    const int ru = bwla_rank_u(L);                     // the projection's rank; T has L->r columns
+    a.X = dX; a.M = M; a.K = L->K; a.n1 = L->n1; a.n2 = L->n2; a.r = ru;
+    a.tp = L->r; a.tshift = L->centered ? dT + ru : nullptr;
     a.R1 = (const float*)(blob + L->off_R1); a.R2 = (const float*)(blob + L->off_R2);
     a.U = (const __half*)(blob + L->off_U);
     a.R1p = (const uint16_t*)(blob + L->off_R1p); a.R2p = (const uint16_t*)(blob + L->off_R2p);
@@ -1499,9 +1514,9 @@ hipError_t bwla_launch_rotate_quant(const bwla_layer_t* L, const void* dX, int x
     a.xs = nullptr; a.pmax = nullptr;
     // Few tokens: one launch holds rotation and projection workgroups (a second launch would
     // cost more than it saves).  Many tokens: the projection has a kernel of its own.
-    const bool merged = L->r > 0 && plan.tile_rows == 16;
+    const bool merged = ru > 0 && plan.tile_rows == 16;
     const int64_t pblocks = merged ? (int64_t)plan.token_tiles * plan.splits : 0;
-    const size_t plds = merged ? pp_lds_bytes(L->r) : 0;
+    const size_t plds = merged ? pp_lds_bytes(ru) : 0;
     a.rot_blocks = M;
     hipError_t e;
     const R3Shape s3 = r3_shape(L->n1, L->n2);
@@ -1509,10 +1524,10 @@ hipError_t bwla_launch_rotate_quant(const bwla_layer_t* L, const void* dX, int x
     if (split_bytes > 0 && dws != nullptr) {
         // few tokens, R1 too large for LDS: several workgroups per token, then a launch that quantizes
         const RsShape rs = rs_shape(s3);
-        a.xs = (float*)((char*)dws + bwla_align256(bwla_psp_ws_bytes(plan, M, L->r)));
+        a.xs = (float*)((char*)dws + bwla_align256(bwla_psp_ws_bytes(plan, M, ru)));
         a.pmax = a.xs + M * L->K;
         a.rot_blocks = M * rs.G;
-        const size_t pl3 = merged ? pp_lds_bytes(L->r, 8) : 0;
+        const size_t pl3 = merged ? pp_lds_bytes(ru, 8) : 0;
         const size_t lds3 = pl3 > rs.lds_bytes ? pl3 : rs.lds_bytes;
         static bwla_lds_attr attr;
         e = attr.ensure((const void*)rotate_split_kernel, lds3);
@@ -1524,14 +1539,19 @@ hipError_t bwla_launch_rotate_quant(const bwla_layer_t* L, const void* dX, int x
                                                                                  dqsum);
         e = hipGetLastError();
         if (e != hipSuccess) return e;
-        if (L->r > 0 && !merged) return bwla_launch_psp_prefill(L, dX, xdtype, M, dT, dws, plan, st);
+        if (a.tshift) {
+            shift_column_kernel<<<dim3((unsigned)((M + 255) / 256)), dim3(256), 0, st>>>(dscale, dqsum, M, a.tshift, a.tp);
+            e = hipGetLastError();
+            if (e != hipSuccess) return e;
+        }
+        if (ru > 0 && !merged) return bwla_launch_psp_prefill(L, dX, xdtype, M, dT, dws, plan, st);
         return hipSuccess;
     }
     if (xdtype == BWLA_X_BF16 && s3.ok) {
         // projection workgroups in the same launch want all eight wavefronts; so does a rotation
         // workgroup with one token and resident factors (the extra wavefronts help to fetch them)
         int threads = (merged && s3.strips < 8) ? 512 : 64 * s3.strips;
-        const size_t pl3 = merged ? pp_lds_bytes(L->r, threads / 64) : 0;
+        const size_t pl3 = merged ? pp_lds_bytes(ru, threads / 64) : 0;
         const size_t lds3 = pl3 > s3.lds_bytes ? pl3 : s3.lds_bytes;
         // resident factors and many tokens: as many workgroups as fit the chip at once, each
         // walking over its share of the tokens with the factors loaded once
@@ -1551,7 +1571,7 @@ hipError_t bwla_launch_rotate_quant(const bwla_layer_t* L, const void* dX, int x
         else if (s3.at <= 12) e = launch_rotate3<12, 640>(a, grid, threads, lds3, st);
         else e = launch_rotate3<16, 512>(a, grid, threads, lds3, st);
         if (e != hipSuccess) return e;
-        if (L->r > 0 && !merged) return bwla_launch_psp_prefill(L, dX, xdtype, M, dT, dws, plan, st);
+        if (ru > 0 && !merged) return bwla_launch_psp_prefill(L, dX, xdtype, M, dT, dws, plan, st);
         return hipSuccess;
     }
     const size_t lds = plds > sh.lds_bytes ? plds : sh.lds_bytes;
@@ -1568,7 +1588,7 @@ hipError_t bwla_launch_rotate_quant(const bwla_layer_t* L, const void* dX, int x
     }
     e = hipGetLastError();
     if (e != hipSuccess) return e;
-    if (L->r > 0 && !merged) return bwla_launch_psp_prefill(L, dX, xdtype, M, dT, dws, plan, st);
+    if (ru > 0 && !merged) return bwla_launch_psp_prefill(L, dX, xdtype, M, dT, dws, plan, st);
     return hipSuccess;
 }
 
@@ -1577,7 +1597,7 @@ size_t bwla_split_rotation_bytes(const bwla_layer_t* L, const bwla_psp_plan& pla
     if (!s3.ok || s3.resident || (L->n2 & 3) != 0 || L->K > (int64_t)RS_QB * 512 * RS_QI * 4) return 0;
     const RsShape rs = rs_shape(s3);
     if (!rs.ok) return 0;
-    const bool merged = L->r > 0 && plan.tile_rows == 16;
+    const bool merged = bwla_rank_u(L) > 0 && plan.tile_rows == 16;
     const int64_t pblocks = merged ? (int64_t)plan.token_tiles * plan.splits : 0;
     // every workgroup of the launch gets a CU of its own at once; with more tokens than that the
     // one-workgroup-per-token kernel keeps the chip busy anyway

@@ -24,12 +24,20 @@ def to_dev(a, dtype=None):
     return t if dtype is None else t.to(dtype)
 
 
-def pack_on_gpu(d: syn.LayerData) -> B.PackedLayer:
+def pack_on_gpu(d: syn.LayerData, W=None, centered: bool = False) -> B.PackedLayer:
     U = to_dev(d.U) if d.cfg.r > 0 else None
     V = to_dev(d.V) if d.cfg.r > 0 else None
-    layer = B.pack_weights(to_dev(d.W), to_dev(d.R1), to_dev(d.R2), U, V, d.cfg.n1, d.cfg.n2)
+    layer = B.pack_weights(to_dev(d.W if W is None else W), to_dev(d.R1), to_dev(d.R2), U, V, d.cfg.n1, d.cfg.n2,
+                           centered=centered)
     torch.cuda.synchronize()
     return layer
+
+
+def shifted_weights(d: syn.LayerData) -> np.ndarray:
+    """The layer's weights with a seeded offset per output channel (N(0, 0.01^2), about half a
+    standard deviation of the weights), so that the row shift of the centered binarization matters."""
+    rng = np.random.default_rng(1000 + d.cfg.seed)
+    return (d.W + rng.normal(0.0, 0.01, size=(d.cfg.N, 1))).astype(np.float32)
 
 
 def x_on_gpu(d: syn.LayerData):
@@ -63,22 +71,39 @@ def check_output(Y_gpu: np.ndarray, Y_ref: np.ndarray) -> dict:
     return dict(fro=float(fro), max_rel=mx)
 
 
-def run_case(cfg: syn.LayerConfig, rows=None) -> dict:
-    """Whole path on the GPU for all M tokens; the oracle on all of them, or on `rows`."""
+def run_case(cfg: syn.LayerConfig, rows=None, centered: bool = False) -> dict:
+    """Whole path on the GPU for all M tokens; the oracle on all of them, or on `rows`.
+    centered: the layer is binarized with the row shift (weights get a per-channel offset first)."""
     d = syn.make_layer(cfg)
-    sgn, alpha = orc.binarize_rows(d.W)
-    alpha16 = orc.to_fp16(alpha)
     U = d.U if cfg.r > 0 else None
     V = d.V if cfg.r > 0 else None
     sel = np.arange(cfg.M) if rows is None else np.asarray(rows)
-    ref = orc.forward_rows(d.X, d.R1, d.R2, sgn, alpha16, U, V, sel)
+    rt = cfg.r + (1 if centered else 0)                # columns of T and V on the GPU
+    if centered:
+        W = shifted_weights(d)
+        sgn, alpha, mu = orc.binarize_rows_centered(W)
+        alpha16, mu16 = orc.to_fp16(alpha), orc.to_fp16(mu)
+        ref = orc.forward_rows(d.X, d.R1, d.R2, sgn, alpha16, U, V, sel, mu16=mu16)
+        # the GPU carries the shift term as one more column of T: scale_t * qsum_t
+        ref_T = np.concatenate([ref["T"], (ref["s"] * ref["qsum"])[:, None]], axis=1)
+    else:
+        W = d.W
+        sgn, alpha = orc.binarize_rows(W)
+        alpha16 = orc.to_fp16(alpha)
+        ref = orc.forward_rows(d.X, d.R1, d.R2, sgn, alpha16, U, V, sel)
+        ref_T = ref["T"]
 
-    layer = pack_on_gpu(d)
+    layer = pack_on_gpu(d, W, centered)
+    assert layer.desc.r == rt and layer.desc.centered == int(centered)
     # packed weights: interchange view equals the oracle's binarization, bit for bit
     sgn_gpu, alpha_gpu = B.unpack_signs(layer)
     assert torch.equal(sgn_gpu.cpu(), torch.from_numpy(sgn)), "sign bits differ"
     assert np.array_equal(alpha_gpu.cpu().numpy().astype(np.float64), alpha16), "alpha differs"
     del sgn_gpu
+    if centered:
+        rp = (rt + 15) // 16 * 16
+        v16 = layer.blob[layer.desc.off_V:layer.desc.off_V + cfg.N * rp * 2].view(torch.float16).reshape(cfg.N, rp)
+        assert np.array_equal(v16[:, rt - 1].cpu().numpy().astype(np.float64), mu16), "stored row shifts differ"
 
     X = x_on_gpu(d)
     act = B.Activations(layer, cfg.M)
@@ -88,7 +113,7 @@ def run_case(cfg: syn.LayerConfig, rows=None) -> dict:
     B.linear_forward(layer, act, Y, acc)
     torch.cuda.synchronize()
     # the scratch starts with the projection's arrival counters (if there is a projection)
-    ncnt = (((cfg.M + 15) // 16) * 4 + 255) // 256 * 256 if cfg.r > 0 else 0
+    ncnt = (((cfg.M + 15) // 16) * 4 + 255) // 256 * 256 if cfg.r > 0 else 0   # (cfg.r: the projection's rank)
     assert int(torch.count_nonzero(act.ws[:ncnt])) == 0, "arrival counters not restored to zero"
 
     # the one-call entry point (a single launch for one bf16 token) gives the same bits, also when
@@ -103,7 +128,7 @@ def run_case(cfg: syn.LayerConfig, rows=None) -> dict:
             torch.cuda.synchronize()
             assert int(torch.count_nonzero(act1.ws[:ncnt])) == 0, f"call {rep}: counters not restored to zero"
         assert torch.equal(act1.q, act.q) and torch.equal(act1.scale, act.scale) and torch.equal(act1.qsum, act.qsum)
-        if cfg.r > 0:
+        if rt > 0:
             assert torch.equal(act1.T, act.T), "one-call T differs"
         assert torch.equal(Y1, Y), "one-call output differs from the two-call output"
         assert torch.equal(acc1, acc), "one-call accumulators differ"
@@ -124,10 +149,15 @@ def run_case(cfg: syn.LayerConfig, rows=None) -> dict:
     s_gpu = act.scale[sel_t].cpu().numpy().astype(np.float64)
     assert np.allclose(s_gpu, ref["s"], rtol=2e-6, atol=0), "per-token scales differ"
     assert np.array_equal(act.qsum[sel_t].cpu().numpy().astype(np.int64), q_gpu.astype(np.int64).sum(axis=1))
-    if cfg.r > 0:
+    if rt > 0:
         T_gpu = act.T[sel_t].cpu().numpy().astype(np.float64)
-        tden = np.maximum(np.max(np.abs(ref["T"]), axis=1, keepdims=True), 1e-30)
-        assert np.max(np.abs(T_gpu - ref["T"]) / tden) < 2e-5, "PSP projection differs"
+        if cfg.r > 0:
+            tden = np.maximum(np.max(np.abs(ref["T"]), axis=1, keepdims=True), 1e-30)
+            assert np.max(np.abs(T_gpu[:, :cfg.r] - ref["T"]) / tden) < 2e-5, "PSP projection differs"
+        if centered:
+            # the GPU's shift entry is its own scale times its own code sum (fp32)
+            own = s_gpu * q_gpu.astype(np.int64).sum(axis=1)
+            assert np.allclose(T_gpu[:, cfg.r], own, rtol=1e-6, atol=1e-30), "shift entries of T differ"
     # the GPU's own accumulators are consistent with the GPU's own codes (exact)
     acc_own = orc.binary_gemm(q_gpu, sgn)
     assert np.array_equal(acc[sel_t].cpu().numpy().astype(np.int64), acc_own), "int32 accumulators differ"
@@ -136,8 +166,8 @@ def run_case(cfg: syn.LayerConfig, rows=None) -> dict:
     act2 = B.Activations(layer, len(sel))
     act2.q.copy_(torch.from_numpy(ref["q"]))
     act2.scale.copy_(torch.from_numpy(ref["s"].astype(np.float32)))
-    if cfg.r > 0:
-        act2.T.copy_(torch.from_numpy(ref["T"].astype(np.float32)))
+    if rt > 0:
+        act2.T.copy_(torch.from_numpy(ref_T.astype(np.float32)))
     B.code_sums(act2.q, act2.qsum)
     Y2 = torch.empty((len(sel), cfg.N), dtype=torch.float32, device=DEV)
     acc2 = torch.empty((len(sel), cfg.N), dtype=torch.int32, device=DEV)

@@ -89,6 +89,22 @@ def test_ragged_and_degenerate_shapes(M, K, n1, n2, N, r, xd):
     print(run_case(cfg), flush=True)
 
 
+@pytest.mark.parametrize("M,K,n1,n2,N,r,xd", [
+    (16, 512, 16, 32, 512, 8, "f32"),        # fp32 activations (old rotation kernel), decode GEMM
+    (1, 4096, 64, 64, 1000, 32, "bf16"),     # one token: merged projection, shift entry from the bf16 rotation
+    (1, 4096, 64, 64, 528, 0, "bf16"),       # no PSP at all: the shift is the only column of T and V
+    (16, 5120, 64, 80, 640, 15, "bf16"),     # r + 1 = 16 fills the padded rank exactly
+    (40, 1024, 32, 32, 200, 16, "bf16"),     # r + 1 = 17 crosses into the next 16-column group; streaming GEMM, 4 waves split K
+    (300, 1152, 36, 32, 200, 20, "bf16"),    # prefill: separate projection kernel writes T with the wider pitch
+    (2, 20000, 200, 100, 48, 4, "bf16"),     # split rotation: shift entries from the extra small launch
+])
+def test_row_shift_binarization(M, K, n1, n2, N, r, xd):
+    """Layers packed with bwla_pack_weights_centered (paper Sec. 3 "Discussion", Eq. 1-2, 4)."""
+    from parity_util import run_case
+    cfg = syn.LayerConfig(f"shift_{M}_{K}_{N}_{r}", M, K, n1, n2, N, r, xd, max(1, K // 100), 20.0, seed=12)
+    print(run_case(cfg, centered=True), flush=True)
+
+
 def test_zero_token_gives_zero_codes_and_scale():
     from parity_util import pack_on_gpu, DEV
     from paper_2605_00422_amd import binding as B

@@ -71,6 +71,21 @@ def test_packed_size_accounting(lib):
     assert size2 >= 7 * 1 * 1024 + 200 + 2 * 16 * (100 + 96) + 4 * (144 + 64)
 
 
+def test_packed_size_with_row_shifts(lib):
+    """A layer with row shifts stores them as one more fp16 column of V (U keeps r columns): the blob
+    grows only where the padded rank of V grows."""
+    N, K, n1, n2 = 11008, 4096, 64, 64
+    pad16 = lambda n: (n + 15) // 16 * 16
+    for r in (0, 15, 16, 32):
+        grow = B.packed_size(N, K, n1, n2, r, centered=True) - B.packed_size(N, K, n1, n2, r)
+        expect = 2 * N * (pad16(r + 1) - pad16(r))
+        assert expect <= grow <= expect + 2 * 256
+    out = c_size_t()
+    assert lib.bwla_packed_size_centered(512, 512, 16, 32, 128, byref(out)) == B.BWLA_ERR_UNSUPPORTED   # r + 1 > 128
+    assert lib.bwla_packed_size_centered(512, 512, 16, 32, -1, byref(out)) == B.BWLA_ERR_SHAPE
+    assert lib.bwla_packed_size_centered(512, 512, 16, 32, 127, byref(out)) == B.BWLA_OK
+
+
 @pytest.mark.parametrize("args,status", [
     ((0, 512, 16, 32, 8), B.BWLA_ERR_SHAPE),
     ((512, 512, 16, 16, 8), B.BWLA_ERR_SHAPE),        # n1 * n2 != K
