@@ -11,6 +11,7 @@ of a model are all distinct, so the sign bits always stream from HBM.  Prints on
 from __future__ import annotations
 
 import argparse
+import dataclasses
 import json
 import math
 import os
@@ -57,7 +58,7 @@ def gemm_ops(cfg) -> int:
 class Workload:
     """One layer on the GPU with `copies` packed replicas and preallocated outputs."""
 
-    def __init__(self, cfg, copies=None):
+    def __init__(self, cfg, copies=None, centered=False):
         import numpy as np
         import torch
         from paper_2605_00422_amd import binding as B
@@ -69,7 +70,9 @@ class Workload:
         t = lambda a: torch.from_numpy(np.ascontiguousarray(a)).to(dev)
         U = t(d.U) if cfg.r > 0 else None
         V = t(d.V) if cfg.r > 0 else None
-        first = B.pack_weights(t(d.W), t(d.R1), t(d.R2), U, V, cfg.n1, cfg.n2)
+        # centered: binarization with the row shift, on weights with a per-channel offset
+        W = syn.shifted_weights(d) if centered else d.W
+        first = B.pack_weights(t(W), t(d.R1), t(d.R2), U, V, cfg.n1, cfg.n2, centered=centered)
         torch.cuda.synchronize()
         nbytes = first.blob.numel()
         if copies is None:
@@ -136,9 +139,9 @@ class Workload:
         return e0.elapsed_time(e1) / steps
 
 
-def measure(cfg, steps, warmup, use_graph=True):
-    w = Workload(cfg)
-    out = {"workload": cfg.name, "M": cfg.M, "K": cfg.K, "N": cfg.N, "r": cfg.r,
+def measure(cfg, steps, warmup, use_graph=True, centered=False):
+    w = Workload(cfg, centered=centered)
+    out = {"workload": cfg.name + ("+row_shift" if centered else ""), "M": cfg.M, "K": cfg.K, "N": cfg.N, "r": cfg.r,
            "kron": f"{cfg.n1}x{cfg.n2}", "layer_copies": len(w.layers)}
     ms_step = w.time_loop(w.step, steps, warmup)
     ms_fwd = w.time_loop(w.only_forward, steps, warmup)
@@ -290,12 +293,15 @@ def main():
         extra = []
         names = ["cfg2_qwen32b_up_m16", "cfg3_qwen32b_down_m2048", "cfg4_70b_gate_m1", "cfg4_70b_down_m1",
                  "cfg4_70b_q_m64", "cfg4_70b_q_m4096"]
-        for nm in names:
-            if nm == cfg.name:
+        # (name, layer binarized with the row shift: the shift term rides as one more low-rank column)
+        for nm, shift in [(n, False) for n in names] + [("cfg1_decode7b", True)]:
+            if nm == cfg.name and not shift:
                 continue
             c = all_cfgs[nm]
             st = max(20, min(args.steps, 200 if c.M <= 64 else 20))
-            ww, r = measure(c, st, max(3, min(args.warmup, st // 4)), not args.no_graph)
+            ww, r = measure(c, st, max(3, min(args.warmup, st // 4)), not args.no_graph, centered=shift)
+            if shift:
+                c = dataclasses.replace(c, r=c.r + 1)          # bytes of the extra column of V and T
             b = r["stream"]
             if "graph" in r and "us_per_layer" in r["graph"] and r["graph"]["us_per_layer"] < b["us_per_layer"]:
                 b = r["graph"]

@@ -155,7 +155,8 @@ bwla_status_t bwla_psp_workspace_size(const bwla_layer_t* layer, int64_t M, size
  *   T = X U (M x r, fp32 accumulation, from the un-rotated un-quantized X; Sec. 3.2).
  *   d_X      M x K, float or bf16 according to xdtype
  *   d_q      out, M x K int8;  d_scale out, M fp32;  d_qsum out, M int32
- *   d_T      out, M x r fp32 (NULL iff r == 0)
+ *   d_T      out, M x r fp32 (NULL iff r == 0); for a layer with row shifts (centered == 1) the
+ *            first r-1 columns are X U and column r-1 is scale_t * qsum_t
  *   d_ws     scratch of ws_bytes >= bwla_psp_workspace_size(layer, M) (NULL allowed when that is 0)
  */
 bwla_status_t bwla_rotate_quant(const bwla_layer_t* layer, const void* d_X, int xdtype, int64_t M,

@@ -123,3 +123,12 @@ def make_layer(cfg: LayerConfig, with_activations: bool = True) -> LayerData:
     else:
         X, idx = np.zeros((0, cfg.K), dtype=np.float32), np.zeros(0, dtype=np.int64)
     return LayerData(cfg, X, R1, R2, W, U, V, idx)
+
+
+def shifted_weights(d: LayerData) -> np.ndarray:
+    """The layer's weights with a seeded offset per output channel (N(0, 0.01^2), half a standard
+    deviation of the weights): input of the binarization with the row shift, which a zero-mean
+    Gaussian matrix would not exercise.  A generator of its own, so that the draws of make_layer
+    stay as they are."""
+    rng = np.random.default_rng(1000 + d.cfg.seed)
+    return (d.W + rng.normal(0.0, 0.01, size=(d.cfg.N, 1))).astype(np.float32)

@@ -33,13 +33,6 @@ def pack_on_gpu(d: syn.LayerData, W=None, centered: bool = False) -> B.PackedLay
     return layer
 
 
-def shifted_weights(d: syn.LayerData) -> np.ndarray:
-    """The layer's weights with a seeded offset per output channel (N(0, 0.01^2), about half a
-    standard deviation of the weights), so that the row shift of the centered binarization matters."""
-    rng = np.random.default_rng(1000 + d.cfg.seed)
-    return (d.W + rng.normal(0.0, 0.01, size=(d.cfg.N, 1))).astype(np.float32)
-
-
 def x_on_gpu(d: syn.LayerData):
     X = to_dev(d.X)
     return X.to(torch.bfloat16) if d.cfg.x_dtype == "bf16" else X
@@ -80,7 +73,7 @@ def run_case(cfg: syn.LayerConfig, rows=None, centered: bool = False) -> dict:
     sel = np.arange(cfg.M) if rows is None else np.asarray(rows)
     rt = cfg.r + (1 if centered else 0)                # columns of T and V on the GPU
     if centered:
-        W = shifted_weights(d)
+        W = syn.shifted_weights(d)
         sgn, alpha, mu = orc.binarize_rows_centered(W)
         alpha16, mu16 = orc.to_fp16(alpha), orc.to_fp16(mu)
         ref = orc.forward_rows(d.X, d.R1, d.R2, sgn, alpha16, U, V, sel, mu16=mu16)
