@@ -91,22 +91,32 @@ def kron_dense(R1: np.ndarray, R2: np.ndarray) -> np.ndarray:
 
 
 # --------------------------------------------------------------------------- step 2
-def quantize_int6(Xr: np.ndarray):
-    """Per-token symmetric INT6 (this build's reading of paper Sec. 4.1).
+def quantize_sym(Xr: np.ndarray, bits: int = 6):
+    """Per-token symmetric quantization to `bits` bits (this build's reading of paper Sec. 4.1;
+    the paper evaluates 6- and 4-bit activations, Tables 1-3, and times W1A8, Sec. 4.4).
 
-    amax_t = max_k |X~[t,k]|;  v = 31 X~ / amax_t;  q = clip(rint(v), -31, 31) with ties to
-    even;  s_t = amax_t / 31.  A token that is all zero gets q = 0 and s = 0.
+    With qmax = 2^(bits-1) - 1 (31 for INT6, 127 for INT8, 7 for INT4): amax_t = max_k |X~[t,k]|;
+    v = qmax X~ / amax_t;  q = clip(rint(v), -qmax, qmax) with ties to even;  s_t = amax_t / qmax.
+    A token that is all zero gets q = 0 and s = 0.
     Returns (q int8 (M,K), s fp64 (M,), v fp64 (M,K)); v is the pre-rounding value the parity
     test needs for its rounding-boundary mask.
     """
+    if bits < 2 or bits > 8:
+        raise ValueError("bits must be in 2..8 (codes are kept in int8)")
+    qmax = (1 << (bits - 1)) - 1
     Xr = np.asarray(Xr, dtype=np.float64)
     amax = np.max(np.abs(Xr), axis=1)
     safe = np.where(amax > 0, amax, 1.0)
-    v = Xr * (QMAX / safe)[:, None]
+    v = Xr * (qmax / safe)[:, None]
     v[amax == 0] = 0.0
-    q = np.clip(np.rint(v), -QMAX, QMAX).astype(np.int8)
-    s = amax / QMAX
+    q = np.clip(np.rint(v), -qmax, qmax).astype(np.int8)
+    s = amax / qmax
     return q, s, v
+
+
+def quantize_int6(Xr: np.ndarray):
+    """Per-token symmetric INT6: quantize_sym with 6 bits (codes in [-31, 31])."""
+    return quantize_sym(Xr, 6)
 
 
 # --------------------------------------------------------------------------- step 3 (offline part)
@@ -198,7 +208,7 @@ def dequant_output_centered(acc, s, delta, mu, qsum, T=None, V=None) -> np.ndarr
 
 
 # --------------------------------------------------------------------------- whole path
-def forward(X, R1, R2, W_rot, U=None, V=None, centered: bool = False) -> dict:
+def forward(X, R1, R2, W_rot, U=None, V=None, centered: bool = False, act_bits: int = 6) -> dict:
     """The whole hot path on stored parameter values.
 
     X      (M,K)  activations as stored (already on the bf16 or fp32 grid)
@@ -209,7 +219,7 @@ def forward(X, R1, R2, W_rot, U=None, V=None, centered: bool = False) -> dict:
     how the layer stores it.  centered=True: binarization with the row shift (Eq. 1-2, 4).
     """
     Xr = kron_rotate(X, R1, R2)
-    q, s, v = quantize_int6(Xr)
+    q, s, v = quantize_sym(Xr, act_bits)
     qsum = q.astype(np.int64).sum(axis=1)
     if centered:
         sgn, alpha, mu = binarize_rows_centered(W_rot)
@@ -232,13 +242,13 @@ def forward(X, R1, R2, W_rot, U=None, V=None, centered: bool = False) -> dict:
                 acc=acc, T=T, Y=Y, qsum=qsum)
 
 
-def forward_rows(X, R1, R2, sgn, alpha16, U, V, rows, mu16=None) -> dict:
+def forward_rows(X, R1, R2, sgn, alpha16, U, V, rows, mu16=None, act_bits: int = 6) -> dict:
     """The path for a subset of token rows (tokens are independent: per-token scale,
     row-wise products).  Used where the full M would take minutes on the CPU.  With mu16 the
     layer is one with row shifts (sgn, alpha16 from binarize_rows_centered)."""
     Xs = np.asarray(X)[rows]
     Xr = kron_rotate(Xs, R1, R2)
-    q, s, v = quantize_int6(Xr)
+    q, s, v = quantize_sym(Xr, act_bits)
     acc = binary_gemm(q, sgn)
     if U is not None and np.asarray(U).size > 0:
         T = psp_project(Xs, U)

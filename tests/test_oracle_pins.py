@@ -154,6 +154,46 @@ def test_quantizer_ties_to_even_zero_token_and_scale_equivariance():
     assert np.array_equal(qc, -qa)
 
 
+@pytest.mark.parametrize("bits,qmax", [(4, 7), (6, 31), (8, 127)])
+def test_quantizer_other_widths(bits, qmax):
+    """The same quantizer at 4, 6 and 8 bits: range, the maximum maps to +-qmax with its sign,
+    half-step reconstruction bound, integer inputs reproduced, ties to even, and agreement with a
+    scalar loop (Python's round is half-to-even)."""
+    rng = np.random.default_rng(30 + bits)
+    Xr = rng.standard_t(3.0, size=(16, 96))
+    q, s, v = orc.quantize_sym(Xr, bits)
+    assert q.dtype == np.int8 and q.min() >= -qmax and q.max() <= qmax
+    for t in range(Xr.shape[0]):
+        k = int(np.argmax(np.abs(Xr[t])))
+        assert int(q[t, k]) == qmax * int(np.sign(Xr[t, k]))
+        amax = max(abs(float(x)) for x in Xr[t])
+        assert math.isclose(s[t], amax / qmax, rel_tol=1e-15)
+        assert q[t].tolist() == [max(-qmax, min(qmax, round(qmax * float(x) / amax))) for x in Xr[t]]
+    assert np.max(np.abs(q * s[:, None] - Xr) / s[:, None]) <= 0.5 + 1e-12
+    Xi = rng.integers(-qmax, qmax + 1, size=(4, 40)).astype(np.float64)
+    Xi[:, 1] = -qmax
+    qi, si, _ = orc.quantize_sym(Xi, bits)
+    assert np.array_equal(qi.astype(np.float64), Xi) and np.all(si == 1.0)
+    tie = np.array([[float(qmax), 0.5, 1.5, 2.5, -0.5, -1.5, -2.5]])
+    assert orc.quantize_sym(tie, bits)[0].tolist() == [[qmax, 0, 2, 2, 0, -2, -2]]
+    if bits == 6:
+        a, b = orc.quantize_int6(Xr), (q, s, v)
+        assert all(np.array_equal(x, y) for x, y in zip(a, b))
+    with pytest.raises(ValueError):
+        orc.quantize_sym(Xr, 9)
+
+
+def test_forward_with_eight_bit_codes_is_closer_to_the_unquantized_layer():
+    """Finer activation codes can only help: the same layer at 4, 6 and 8 bits against the
+    rotated, binarized layer applied to unquantized activations."""
+    cfg = syn.CONFIGS["cfg0_tiny"]
+    d = syn.make_layer(cfg)
+    sgn, alpha = orc.binarize_rows(d.W)
+    exact = orc.kron_rotate(d.X, d.R1, d.R2) @ (orc.to_fp16(alpha)[:, None] * sgn).T + orc.psp_project(d.X, d.U) @ d.V.astype(np.float64).T
+    err = [np.linalg.norm(orc.forward(d.X, d.R1, d.R2, d.W, d.U, d.V, act_bits=b)["Y"] - exact) for b in (4, 6, 8)]
+    assert err[0] > 2.5 * err[1] > 2.5 * 2.5 * err[2] > 0
+
+
 # ------------------------------------------------------------------ binarization (paper Eq. 1-4; App. A.2.4)
 def test_sign_convention_zero_is_minus_one():
     sgn, alpha = orc.binarize_rows(np.array([[0.0, 1e-30, -1e-30, 2.0]]))
