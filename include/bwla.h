@@ -163,6 +163,16 @@ bwla_status_t bwla_rotate_quant(const bwla_layer_t* layer, const void* d_X, int 
                                 int8_t* d_q, float* d_scale, int32_t* d_qsum, float* d_T,
                                 void* d_ws, size_t ws_bytes, void* stream);
 
+/*
+ * The same with another activation code width (the paper evaluates A6 and A4, Tables 1-3, and times
+ * W1A8, Sec. 4.4): symmetric codes in [-qmax, qmax], qmax = 2^(act_bits-1) - 1, scale = amax / qmax,
+ * act_bits in 2..8 (else BWLA_ERR_UNSUPPORTED), still one code per int8.  bwla_rotate_quant is
+ * act_bits = 6.  bwla_linear_forward takes the codes of any width; bwla_decode_forward is 6-bit.
+ */
+bwla_status_t bwla_rotate_quant_bits(const bwla_layer_t* layer, const void* d_X, int xdtype, int act_bits,
+                                     int64_t M, int8_t* d_q, float* d_scale, int32_t* d_qsum, float* d_T,
+                                     void* d_ws, size_t ws_bytes, void* stream);
+
 /* qsum_t = sum_k q[t,k] for codes that did not come from bwla_rotate_quant. */
 bwla_status_t bwla_code_sums(const int8_t* d_q, int64_t M, int64_t K, int32_t* d_qsum, void* stream);
 

@@ -16,7 +16,7 @@ BWLA_X_F32, BWLA_X_BF16 = 0, 1
 
 EXPORTS = ["bwla_status_string", "bwla_version", "bwla_kron_factor", "bwla_packed_size", "bwla_pack_weights",
            "bwla_unpack_signs", "bwla_psp_workspace_size", "bwla_rotate_quant", "bwla_code_sums",
-           "bwla_linear_forward", "bwla_decode_forward", "bwla_packed_size_centered", "bwla_pack_weights_centered"]
+           "bwla_linear_forward", "bwla_decode_forward", "bwla_packed_size_centered", "bwla_pack_weights_centered", "bwla_rotate_quant_bits"]
 
 
 class BwlaLayer(Structure):
@@ -58,6 +58,8 @@ def load() -> ctypes.CDLL:
     lib.bwla_psp_workspace_size.argtypes = [POINTER(BwlaLayer), c_int64, POINTER(c_size_t)]
     lib.bwla_rotate_quant.argtypes = [POINTER(BwlaLayer), c_void_p, c_int, c_int64, c_void_p, c_void_p, c_void_p,
                                       c_void_p, c_void_p, c_size_t, c_void_p]
+    lib.bwla_rotate_quant_bits.argtypes = [POINTER(BwlaLayer), c_void_p, c_int, c_int, c_int64, c_void_p, c_void_p,
+                                           c_void_p, c_void_p, c_void_p, c_size_t, c_void_p]
     lib.bwla_code_sums.argtypes = [c_void_p, c_int64, c_int64, c_void_p, c_void_p]
     lib.bwla_linear_forward.argtypes = [POINTER(BwlaLayer), c_void_p, c_void_p, c_void_p, c_void_p, c_int64,
                                         c_void_p, c_void_p, c_void_p]
@@ -167,15 +169,20 @@ class Activations:
         self.ws = torch.zeros(max(ws, 16), dtype=torch.uint8, device=dev)   # zero-filled once, as the ABI asks
 
 
-def rotate_quant(layer: PackedLayer, X, act: Activations) -> Activations:
-    """X: (M,K) CUDA tensor, float32 or bfloat16."""
+def rotate_quant(layer: PackedLayer, X, act: Activations, act_bits: int = 6) -> Activations:
+    """X: (M,K) CUDA tensor, float32 or bfloat16.  act_bits other than 6: bwla_rotate_quant_bits."""
     import torch
     xd = BWLA_X_BF16 if X.dtype == torch.bfloat16 else BWLA_X_F32
     if X.dtype not in (torch.bfloat16, torch.float32):
         raise TypeError("X must be float32 or bfloat16")
-    _check(load().bwla_rotate_quant(byref(layer.desc), _ptr(X), xd, X.shape[0], _ptr(act.q), _ptr(act.scale),
-                                    _ptr(act.qsum), _ptr(act.T), _ptr(act.ws), act.ws_bytes, _stream()),
-           "bwla_rotate_quant")
+    if act_bits == 6:
+        _check(load().bwla_rotate_quant(byref(layer.desc), _ptr(X), xd, X.shape[0], _ptr(act.q), _ptr(act.scale),
+                                        _ptr(act.qsum), _ptr(act.T), _ptr(act.ws), act.ws_bytes, _stream()),
+               "bwla_rotate_quant")
+    else:
+        _check(load().bwla_rotate_quant_bits(byref(layer.desc), _ptr(X), xd, act_bits, X.shape[0], _ptr(act.q),
+                                             _ptr(act.scale), _ptr(act.qsum), _ptr(act.T), _ptr(act.ws),
+                                             act.ws_bytes, _stream()), "bwla_rotate_quant_bits")
     return act
 
 

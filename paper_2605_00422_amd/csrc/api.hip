@@ -174,6 +174,13 @@ bwla_status_t bwla_psp_workspace_size(const bwla_layer_t* layer, int64_t M, size
 bwla_status_t bwla_rotate_quant(const bwla_layer_t* layer, const void* d_X, int xdtype, int64_t M,
                                 int8_t* d_q, float* d_scale, int32_t* d_qsum, float* d_T, void* d_ws,
                                 size_t ws_bytes, void* stream) {
+    return bwla_rotate_quant_bits(layer, d_X, xdtype, 6, M, d_q, d_scale, d_qsum, d_T, d_ws, ws_bytes, stream);
+}
+
+bwla_status_t bwla_rotate_quant_bits(const bwla_layer_t* layer, const void* d_X, int xdtype, int act_bits,
+                                     int64_t M, int8_t* d_q, float* d_scale, int32_t* d_qsum, float* d_T,
+                                     void* d_ws, size_t ws_bytes, void* stream) {
+    if (act_bits < 2 || act_bits > 8) return BWLA_ERR_UNSUPPORTED;
     bwla_status_t s = check_layer(layer);
     if (s != BWLA_OK) return s;
     if (!d_X || !d_q || !d_scale || !d_qsum) return BWLA_ERR_NULL;
@@ -186,7 +193,8 @@ bwla_status_t bwla_rotate_quant(const bwla_layer_t* layer, const void* d_X, int 
     const size_t need = rq_ws_bytes(layer, plan, M);
     if (need > 0 && (!d_ws || ws_bytes < need)) return d_ws ? BWLA_ERR_BUFSIZE : BWLA_ERR_NULL;
     hipStream_t st = (hipStream_t)stream;
-    if (bwla_launch_rotate_quant(layer, d_X, xdtype, M, d_q, d_scale, d_qsum, d_T, d_ws, plan, st) != hipSuccess)
+    if (bwla_launch_rotate_quant(layer, d_X, xdtype, M, d_q, d_scale, d_qsum, d_T, d_ws, plan, st, act_bits) !=
+        hipSuccess)
         return BWLA_ERR_HIP;
     return BWLA_OK;
 }

@@ -85,7 +85,7 @@ hipError_t bwla_launch_unpack(const bwla_layer_t* L, int8_t* d_sgn, float* d_alp
 // one launch: rotation + quantization workgroups, then the PSP projection workgroups
 hipError_t bwla_launch_rotate_quant(const bwla_layer_t* L, const void* dX, int xdtype, int64_t M, int8_t* dq,
                                     float* dscale, int32_t* dqsum, float* dT, void* dws, const bwla_psp_plan& plan,
-                                    hipStream_t st);
+                                    hipStream_t st, int act_bits);
 #if defined(__HIPCC__)
 // Split-K hand-over between workgroups of one launch.  The GPU has one L2 per XCD, and a
 // device-scope fence is paid with a write-back / invalidate of that whole cache.  Instead the

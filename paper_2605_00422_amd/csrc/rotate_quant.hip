@@ -258,7 +258,8 @@ template <bool BF16>
 __device__ __forceinline__ void rotate_token(float* lds, const void* __restrict__ X, int64_t t, int64_t K, int n1,
                                              int n2, const float* __restrict__ R1, const float* __restrict__ R2,
                                              int8_t* __restrict__ q, float* __restrict__ scale,
-                                             int32_t* __restrict__ qsum, float* __restrict__ tshift, int tp) {
+                                             int32_t* __restrict__ qsum, float* __restrict__ tshift, int tp,
+                                             float qmax) {
     const RqShape sh = rq_shape(n1, n2);
     float* reg = lds;                                              // V, later ZT
     float* fac = lds + sh.region;                                  // R2T | R1T (resident) or two chunk buffers
@@ -422,7 +423,7 @@ __device__ __forceinline__ void rotate_token(float* lds, const void* __restrict_
     float amax = red[0];
 #pragma unroll
     for (int w = 1; w < RQ_WAVES; ++w) amax = fmaxf(amax, red[w]);
-    const float inv = amax > 0.0f ? 31.0f / amax : 0.0f;
+    const float inv = amax > 0.0f ? qmax / amax : 0.0f;
     RQTRACE(6);
 
     // ================= quantize from registers into an LDS byte image of the token's codes:
@@ -439,7 +440,7 @@ __device__ __forceinline__ void rotate_token(float* lds, const void* __restrict_
 #pragma unroll
             for (int v = 0; v < 4; ++v) {
                 float r = rintf(acc[s][v] * inv);
-                r = fminf(fmaxf(r, -31.0f), 31.0f);
+                r = fminf(fmaxf(r, -qmax), qmax);
                 code[v] = (int)r;
             }
             if (c < n1) {
@@ -477,8 +478,8 @@ __device__ __forceinline__ void rotate_token(float* lds, const void* __restrict_
 #pragma unroll
         for (int w = 0; w < RQ_WAVES; ++w) tot += redi[w];
         qsum[t] = tot;
-        scale[t] = amax / 31.0f;
-        if (tshift) tshift[t * tp] = (amax / 31.0f) * (float)tot;      // the shift term's entry of T
+        scale[t] = amax / qmax;
+        if (tshift) tshift[t * tp] = (amax / qmax) * (float)tot;      // the shift term's entry of T
     }
     RQTRACE(8);
     RQTRACE_FLUSH;
@@ -563,7 +564,7 @@ __device__ __forceinline__ void rotate3_token(char* lds, const uint16_t* __restr
                                               const uint16_t* __restrict__ R2p, int8_t* __restrict__ q,
                                               float* __restrict__ scale, int32_t* __restrict__ qsum,
                                               bool store_out = true, float* __restrict__ tshift = nullptr,
-                                              int tp = 0) {
+                                              int tp = 0, float qmax = 31.0f) {
     const R3Shape sh = r3_shape(n1, n2);
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);         // = strip
@@ -863,7 +864,7 @@ __device__ __forceinline__ void rotate3_token(char* lds, const uint16_t* __restr
     __syncthreads();                                   // also: every wave is done with the token rows
     float amax = red[0];
     for (int w = 1; w < sh.strips; ++w) amax = fmaxf(amax, red[w]);
-    const float inv = amax > 0.0f ? 31.0f / amax : 0.0f;
+    const float inv = amax > 0.0f ? qmax / amax : 0.0f;
     RQTRACE(5);
 
     // ---- quantize: lane holds Yt[d = 16*strip + 4*lg + v][c = 16*tc + li], four consecutive d of one c
@@ -878,7 +879,7 @@ __device__ __forceinline__ void rotate3_token(char* lds, const uint16_t* __restr
 #pragma unroll
             for (int v = 0; v < 4; ++v) {
                 float r = rintf(y[tc][v] * inv);
-                r = fminf(fmaxf(r, -31.0f), 31.0f);
+                r = fminf(fmaxf(r, -qmax), qmax);
                 code[v] = (int)r;
             }
             if (c < n1) {
@@ -914,8 +915,8 @@ __device__ __forceinline__ void rotate3_token(char* lds, const uint16_t* __restr
             int tot = 0;
             for (int w = 0; w < sh.strips; ++w) tot += redi[w];
             qsum[t] = tot;
-            scale[t] = amax / 31.0f;
-            if (tshift) tshift[t * tp] = (amax / 31.0f) * (float)tot;  // the shift term's entry of T
+            scale[t] = amax / qmax;
+            if (tshift) tshift[t * tp] = (amax / qmax) * (float)tot;  // the shift term's entry of T
         }
     }
     RQTRACE(6);
@@ -1149,7 +1150,8 @@ constexpr int RS_QB = 8;
 constexpr int RS_QI = 4;             // float4 per thread: K <= RS_QB * 512 * RS_QI * 4
 __global__ __launch_bounds__(512) void quantize_rows_kernel(const float* __restrict__ xs, const float* __restrict__ pmax,
                                                             int G, int64_t K, int8_t* __restrict__ q,
-                                                            float* __restrict__ scale, int32_t* __restrict__ qsum) {
+                                                            float* __restrict__ scale, int32_t* __restrict__ qsum,
+                                                            float qmax) {
     __shared__ int redi[8];
     const int64_t t = blockIdx.x / RS_QB;
     const int part = (int)(blockIdx.x - t * RS_QB);
@@ -1164,7 +1166,7 @@ __global__ __launch_bounds__(512) void quantize_rows_kernel(const float* __restr
     }
     float amax = pmax[t * G];
     for (int j = 1; j < G; ++j) amax = fmaxf(amax, pmax[t * G + j]);
-    const float inv = amax > 0.0f ? 31.0f / amax : 0.0f;
+    const float inv = amax > 0.0f ? qmax / amax : 0.0f;
     int* dst = reinterpret_cast<int*>(q + t * K);
     int lsum = 0;
 #pragma unroll
@@ -1176,7 +1178,7 @@ __global__ __launch_bounds__(512) void quantize_rows_kernel(const float* __restr
 #pragma unroll
             for (int v = 0; v < 4; ++v) {
                 float r = rintf(f[v] * inv);
-                r = fminf(fmaxf(r, -31.0f), 31.0f);
+                r = fminf(fmaxf(r, -qmax), qmax);
                 code[v] = (int)r;
                 lsum += code[v];
             }
@@ -1190,7 +1192,7 @@ __global__ __launch_bounds__(512) void quantize_rows_kernel(const float* __restr
         int tot = 0;
         for (int w = 0; w < 8; ++w) tot += redi[w];
         atomicAdd(qsum + t, tot);
-        if (part == 0) scale[t] = amax / 31.0f;
+        if (part == 0) scale[t] = amax / qmax;
     }
 }
 
@@ -1321,6 +1323,7 @@ struct RqArgs {
     int8_t* q; float* scale; int32_t* qsum; float* T;
     int* counters; float* partials; int S;
     float* xs; float* pmax;  // split rotation: rotated values (M x K) and per-workgroup maxima (M x G)
+    float qmax;              // largest code: 2^(bits-1) - 1
     int tp;                  // row pitch of T (= r, or r + 1 for a layer with row shifts)
     float* tshift;           // T + r for such a layer (entry scale_t * qsum_t of each row), else NULL
     int64_t rot_blocks;      // workgroups below this index rotate token blockIdx.x, the rest project
@@ -1331,7 +1334,7 @@ template <bool BF16>
 __global__ __launch_bounds__(RQ_THREADS) void rotate_quant_kernel(RqArgs a) {
     extern __shared__ __align__(16) float lds[];
     if ((int64_t)blockIdx.x < a.rot_blocks) {
-        rotate_token<BF16>(lds, a.X, blockIdx.x, a.K, a.n1, a.n2, a.R1, a.R2, a.q, a.scale, a.qsum, a.tshift, a.tp);
+        rotate_token<BF16>(lds, a.X, blockIdx.x, a.K, a.n1, a.n2, a.R1, a.R2, a.q, a.scale, a.qsum, a.tshift, a.tp, a.qmax);
     } else {
         const int pb = (int)(blockIdx.x - a.rot_blocks);
         psp_block<BF16>(reinterpret_cast<char*>(lds), a.X, a.M, a.K, a.r, a.U, a.T, a.counters, a.partials, a.S,
@@ -1346,7 +1349,7 @@ __global__ __launch_bounds__(THREADS) void rotate_quant3_kernel(RqArgs a) {
     if ((int64_t)blockIdx.x < a.rot_blocks) {
         rotate3_token<ATM, LOOP>(reinterpret_cast<char*>(lds), reinterpret_cast<const uint16_t*>(a.X), blockIdx.x,
                            a.rot_blocks, a.M, a.K, a.n1, a.n2, a.R1p, a.R2p, a.q, a.scale, a.qsum, true, a.tshift,
-                           a.tp);
+                           a.tp, a.qmax);
     } else {
         const int pb = (int)(blockIdx.x - a.rot_blocks);
         psp_block<true>(reinterpret_cast<char*>(lds), a.X, a.M, a.K, a.r, a.U, a.T, a.counters, a.partials, a.S,
@@ -1497,13 +1500,14 @@ bwla_psp_plan bwla_make_psp_plan(int64_t M, int64_t K, int r) {
 
 hipError_t bwla_launch_rotate_quant(const bwla_layer_t* L, const void* dX, int xdtype, int64_t M, int8_t* dq,
                                     float* dscale, int32_t* dqsum, float* dT, void* dws, const bwla_psp_plan& plan,
-                                    hipStream_t st) {
+                                    hipStream_t st, int act_bits) {
     const char* blob = (const char*)L->d_blob;
     const RqShape sh = rq_shape(L->n1, L->n2);
     RqArgs a;
     const int ru = bwla_rank_u(L);                     // the projection's rank; T has L->r columns
     a.X = dX; a.M = M; a.K = L->K; a.n1 = L->n1; a.n2 = L->n2; a.r = ru;
     a.tp = L->r; a.tshift = L->centered ? dT + ru : nullptr;
+    a.qmax = (float)((1 << (act_bits - 1)) - 1);
     a.R1 = (const float*)(blob + L->off_R1); a.R2 = (const float*)(blob + L->off_R2);
     a.U = (const __half*)(blob + L->off_U);
     a.R1p = (const uint16_t*)(blob + L->off_R1p); a.R2p = (const uint16_t*)(blob + L->off_R2p);
@@ -1536,7 +1540,7 @@ hipError_t bwla_launch_rotate_quant(const bwla_layer_t* L, const void* dX, int x
         e = hipGetLastError();
         if (e != hipSuccess) return e;
         quantize_rows_kernel<<<dim3((unsigned)(M * RS_QB)), dim3(512), 0, st>>>(a.xs, a.pmax, rs.G, L->K, dq, dscale,
-                                                                                 dqsum);
+                                                                                 dqsum, a.qmax);
         e = hipGetLastError();
         if (e != hipSuccess) return e;
         if (a.tshift) {

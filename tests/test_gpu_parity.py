@@ -105,6 +105,29 @@ def test_row_shift_binarization(M, K, n1, n2, N, r, xd):
     print(run_case(cfg, centered=True), flush=True)
 
 
+@pytest.mark.parametrize("bits,M,K,n1,n2,N,r,xd", [
+    (8, 1, 4096, 64, 64, 1000, 32, "bf16"),    # W1A8, the width of the paper's speed run: decode
+    (8, 16, 512, 16, 32, 512, 8, "f32"),       # fp32 activations (old rotation kernel)
+    (8, 300, 1152, 36, 32, 200, 20, "bf16"),   # prefill: accumulators up to 127 K through the streaming GEMM
+    (8, 2, 20000, 200, 100, 48, 4, "bf16"),    # split rotation: the quantizing launch
+    (4, 16, 5120, 64, 80, 640, 16, "bf16"),    # A4 codes (in int8 containers)
+    (4, 40, 1024, 32, 32, 200, 16, "bf16"),
+    (2, 5, 96, 8, 12, 33, 8, "bf16"),          # the narrowest width: codes in {-1, 0, 1}
+])
+def test_other_activation_widths(bits, M, K, n1, n2, N, r, xd):
+    """bwla_rotate_quant_bits: the same quantizer at other code widths (paper Tables 1-3: A6, A4;
+    Sec. 4.4: W1A8); bwla_linear_forward takes the codes as they are."""
+    from parity_util import run_case
+    cfg = syn.LayerConfig(f"a{bits}_{M}_{K}_{N}_{r}", M, K, n1, n2, N, r, xd, max(1, K // 100), 20.0, seed=13)
+    print(run_case(cfg, act_bits=bits), flush=True)
+
+
+def test_row_shift_with_eight_bit_codes():
+    from parity_util import run_case
+    cfg = syn.LayerConfig("shift_a8", 3, 2048, 32, 64, 300, 16, "bf16", 20, 20.0, seed=14)
+    print(run_case(cfg, centered=True, act_bits=8), flush=True)
+
+
 def test_zero_token_gives_zero_codes_and_scale():
     from parity_util import pack_on_gpu, DEV
     from paper_2605_00422_amd import binding as B

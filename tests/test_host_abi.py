@@ -132,3 +132,13 @@ def test_binding_raises_on_error(lib):
     with pytest.raises(B.BwlaError) as e:
         B.packed_size(512, 512, 16, 16, 8)
     assert e.value.status == B.BWLA_ERR_SHAPE
+
+
+def test_rotate_quant_bits_rejects_widths_outside_int8(lib):
+    """The code width is checked on the host before anything else."""
+    for bits in (1, 9, 16, -6):
+        assert lib.bwla_rotate_quant_bits(None, None, 1, bits, 1, None, None, None, None, None, 0, None) == \
+            B.BWLA_ERR_UNSUPPORTED
+    for bits in (2, 4, 6, 8):                           # accepted: the next check (the layer) reports
+        assert lib.bwla_rotate_quant_bits(None, None, 1, bits, 1, None, None, None, None, None, 0, None) == \
+            B.BWLA_ERR_NULL
