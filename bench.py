@@ -58,12 +58,13 @@ def gemm_ops(cfg) -> int:
 class Workload:
     """One layer on the GPU with `copies` packed replicas and preallocated outputs."""
 
-    def __init__(self, cfg, copies=None, centered=False):
+    def __init__(self, cfg, copies=None, centered=False, act_bits=6):
         import numpy as np
         import torch
         from paper_2605_00422_amd import binding as B
         from paper_2605_00422_amd import inputs as syn
         self.cfg, self.B, self.torch = cfg, B, torch
+        self.act_bits = act_bits
         dev = "cuda:0"
         d = syn.make_layer(cfg)
         self.data = d
@@ -91,11 +92,11 @@ class Workload:
 
     def step(self, i):
         L = self.layers[i % len(self.layers)]
-        self.B.rotate_quant(L, self.X, self.act)
+        self.B.rotate_quant(L, self.X, self.act, self.act_bits)
         self.B.linear_forward(L, self.act, self.Y)
 
     def only_rotate(self, i):
-        self.B.rotate_quant(self.layers[i % len(self.layers)], self.X, self.act)
+        self.B.rotate_quant(self.layers[i % len(self.layers)], self.X, self.act, self.act_bits)
 
     def only_forward(self, i):
         self.B.linear_forward(self.layers[i % len(self.layers)], self.act, self.Y)
@@ -139,9 +140,10 @@ class Workload:
         return e0.elapsed_time(e1) / steps
 
 
-def measure(cfg, steps, warmup, use_graph=True, centered=False):
-    w = Workload(cfg, centered=centered)
-    out = {"workload": cfg.name + ("+row_shift" if centered else ""), "M": cfg.M, "K": cfg.K, "N": cfg.N, "r": cfg.r,
+def measure(cfg, steps, warmup, use_graph=True, centered=False, act_bits=6):
+    w = Workload(cfg, centered=centered, act_bits=act_bits)
+    out = {"workload": cfg.name + ("+row_shift" if centered else "") + (f"+a{act_bits}" if act_bits != 6 else ""),
+           "M": cfg.M, "K": cfg.K, "N": cfg.N, "r": cfg.r,
            "kron": f"{cfg.n1}x{cfg.n2}", "layer_copies": len(w.layers)}
     ms_step = w.time_loop(w.step, steps, warmup)
     ms_fwd = w.time_loop(w.only_forward, steps, warmup)
@@ -294,12 +296,14 @@ def main():
         names = ["cfg2_qwen32b_up_m16", "cfg3_qwen32b_down_m2048", "cfg4_70b_gate_m1", "cfg4_70b_down_m1",
                  "cfg4_70b_q_m64", "cfg4_70b_q_m4096"]
         # (name, layer binarized with the row shift: the shift term rides as one more low-rank column)
-        for nm, shift in [(n, False) for n in names] + [("cfg1_decode7b", True)]:
-            if nm == cfg.name and not shift:
+        # and 8-bit activation codes, the width of the paper's speed run: same kernels, same bytes)
+        for nm, shift, bits in [(n, False, 6) for n in names] + [("cfg1_decode7b", True, 6), ("cfg1_decode7b", False, 8)]:
+            if nm == cfg.name and not shift and bits == 6:
                 continue
             c = all_cfgs[nm]
             st = max(20, min(args.steps, 200 if c.M <= 64 else 20))
-            ww, r = measure(c, st, max(3, min(args.warmup, st // 4)), not args.no_graph, centered=shift)
+            ww, r = measure(c, st, max(3, min(args.warmup, st // 4)), not args.no_graph, centered=shift,
+                            act_bits=bits)
             if shift:
                 c = dataclasses.replace(c, r=c.r + 1)          # bytes of the extra column of V and T
             b = r["stream"]
