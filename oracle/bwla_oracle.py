@@ -17,6 +17,9 @@ step by step, not the dense product:
   4. PSP branch   L = (X U) V^T                             (paper Sec. 3.2 "PSP": W_res = W - M, M = A B)
   5. dequantize   Y = s_t * alpha_n * acc + L               (paper Sec. 3 "Discussion", Eq. 4; App. A.2.4)
 
+Variant with per-token asymmetric activation codes (paper Sec. 4.1 says "per-token asymmetric
+quantization for activations", no formula): quantize_asym, forward_asym.
+
 Variant with row-wise centering (paper Sec. 3 "Discussion", Eq. 1-2 and 4 in full): the shift
 mu_n = mean_k W[n,k] is taken out before the sign and the scale are computed, and comes back at
 dequantization: W_deq = delta_n Sign(W - mu_n) + mu_n, so Y = s_t (delta_n acc + mu_n qsum_t) + L
@@ -114,6 +117,32 @@ def quantize_sym(Xr: np.ndarray, bits: int = 6):
     return q, s, v
 
 
+def quantize_asym(Xr: np.ndarray, bits: int = 6):
+    """Per-token asymmetric quantization (paper Sec. 4.1 names it, without a formula; this is the
+    usual min-max affine form, this build's reading): with L = 2^bits - 1 levels above zero,
+        lo_t = min(min_k X~[t,k], 0),  hi_t = max(max_k X~[t,k], 0)      (zero is representable)
+        s_t = (hi_t - lo_t) / L,   z_t = rint(-lo_t / s_t)  in [0, L]     (the zero point)
+        q = clip(rint(X~ / s_t) + z_t, 0, L),  dequantized value s_t (q - z_t);
+    ties to even; an all-zero token gets q = z = 0 and s = 0.
+    Returns (q int16 (M,K) in [0, L], s fp64 (M,), z int64 (M,), v fp64 (M,K) = X~ / s_t, the
+    pre-rounding value, and u fp64 (M,) = -lo_t / s_t, the pre-rounding zero point)."""
+    if bits < 2 or bits > 8:
+        raise ValueError("bits must be in 2..8")
+    L = (1 << bits) - 1
+    Xr = np.asarray(Xr, dtype=np.float64)
+    lo = np.minimum(Xr.min(axis=1), 0.0)
+    hi = np.maximum(Xr.max(axis=1), 0.0)
+    span = hi - lo
+    s = span / L
+    safe = np.where(span > 0, s, 1.0)
+    u = np.where(span > 0, -lo / safe, 0.0)
+    z = np.rint(u).astype(np.int64)
+    v = Xr / safe[:, None]
+    v[span == 0] = 0.0
+    q = np.clip(np.rint(v) + z[:, None], 0, L).astype(np.int16)
+    return q, s, z, v, u
+
+
 def quantize_int6(Xr: np.ndarray):
     """Per-token symmetric INT6: quantize_sym with 6 bits (codes in [-31, 31])."""
     return quantize_sym(Xr, 6)
@@ -208,6 +237,34 @@ def dequant_output_centered(acc, s, delta, mu, qsum, T=None, V=None) -> np.ndarr
 
 
 # --------------------------------------------------------------------------- whole path
+def forward_asym(X, R1, R2, W_rot, U=None, V=None, centered: bool = False, act_bits: int = 6) -> dict:
+    """The path with per-token asymmetric activation codes (quantize_asym): the dequantized token
+    s_t (q - z_t) meets the dequantized weights, alpha_n sgn (+ mu_n with centered=True):
+        Y[t,n] = s_t * (alpha_n * sum_k (q[t,k] - z_t) sgn[n,k] + mu_n * sum_k (q[t,k] - z_t)) + L[t,n].
+    The contraction runs on the centered codes q - z, exact integers."""
+    Xr = kron_rotate(X, R1, R2)
+    q, s, z, v, u = quantize_asym(Xr, act_bits)
+    c = q.astype(np.int64) - z[:, None]                   # centered codes, |c| <= 2^bits - 1
+    if centered:
+        sgn, alpha, mu = binarize_rows_centered(W_rot)
+        mu16 = to_fp16(mu)
+    else:
+        sgn, alpha = binarize_rows(W_rot)
+        mu = None
+        mu16 = np.zeros(np.asarray(W_rot).shape[0])
+    alpha16 = to_fp16(alpha)
+    acc_c = c.astype(np.float64) @ sgn.astype(np.float64).T   # exact: |acc| <= 255 K < 2^53
+    acc_c = np.rint(acc_c).astype(np.int64)
+    if U is not None and np.asarray(U).size > 0:
+        T = psp_project(X, U)
+    else:
+        T = np.zeros((np.asarray(X).shape[0], 0))
+        V = np.zeros((np.asarray(W_rot).shape[0], 0))
+    Y = dequant_output_centered(acc_c, s, alpha16, mu16, c.sum(axis=1), T, V)
+    return dict(Xr=Xr, q=q, s=s, z=z, v=v, u=u, c=c, sgn=sgn, alpha=alpha, alpha16=alpha16, mu=mu,
+                acc_c=acc_c, T=T, Y=Y)
+
+
 def forward(X, R1, R2, W_rot, U=None, V=None, centered: bool = False, act_bits: int = 6) -> dict:
     """The whole hot path on stored parameter values.
 

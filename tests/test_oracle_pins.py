@@ -194,6 +194,98 @@ def test_forward_with_eight_bit_codes_is_closer_to_the_unquantized_layer():
     assert err[0] > 2.5 * err[1] > 2.5 * 2.5 * err[2] > 0
 
 
+# ------------------------------------------------------------------ asymmetric activation codes
+@pytest.mark.parametrize("bits", [4, 6, 8])
+def test_asymmetric_quantizer_against_scalar_loop_and_invariants(bits):
+    L = (1 << bits) - 1
+    rng = np.random.default_rng(40 + bits)
+    Xr = rng.standard_t(3.0, size=(12, 80)) + rng.normal(0.0, 2.0, size=(12, 1))     # skewed tokens
+    Xr[3] = np.abs(Xr[3])                                   # a token without negative values: lo = 0
+    Xr[4] = -np.abs(Xr[4])                                  # and one without positive values: hi = 0
+    q, s, z, v, u = orc.quantize_asym(Xr, bits)
+    assert q.min() >= 0 and q.max() <= L and z.min() >= 0 and z.max() <= L
+    for t in range(Xr.shape[0]):
+        lo = min(min(float(x) for x in Xr[t]), 0.0)
+        hi = max(max(float(x) for x in Xr[t]), 0.0)
+        st = (hi - lo) / L
+        zt = round(-lo / st)                                # Python's round: half to even
+        assert math.isclose(s[t], st, rel_tol=1e-15) and z[t] == zt
+        assert q[t].tolist() == [max(0, min(L, round(float(x) / st) + zt)) for x in Xr[t]]
+        # the ends of the range land on the ends of the code range (up to the rounding of z), zero is exact
+        assert q[t, int(np.argmin(Xr[t]))] <= 1 or lo == 0.0
+        assert q[t, int(np.argmax(Xr[t]))] >= L - 1 or hi == 0.0
+    assert z[3] == 0 and z[4] == L
+    # reconstruction: half a step inside the range; one step more where the rounding of z moved the range
+    rec = s[:, None] * (q - z[:, None])
+    assert np.max(np.abs(rec - Xr) / s[:, None]) <= 1.0 + 1e-9
+    inner = (q > 0) & (q < L)
+    assert np.max((np.abs(rec - Xr) / s[:, None])[inner]) <= 0.5 + 1e-9
+    zero = orc.quantize_asym(np.zeros((2, 8)), bits)
+    assert not zero[0].any() and not zero[1].any() and not zero[2].any()
+    # a token that is symmetric about zero has its zero point in the middle
+    sym = np.array([[-3.0, -1.0, 0.0, 1.0, 3.0]])
+    assert orc.quantize_asym(sym, bits)[2][0] in ((L - 1) // 2, (L + 1) // 2)
+
+
+def test_asymmetric_codes_integer_case_is_exact():
+    """Tokens whose values are integers spanning exactly [lo, lo + 63]: s = 1, z = -lo, q - z = X~."""
+    rng = np.random.default_rng(44)
+    Xr = rng.integers(-20, 44, size=(5, 64)).astype(np.float64)
+    Xr[:, 0], Xr[:, 1] = -20.0, 43.0
+    q, s, z, v, u = orc.quantize_asym(Xr, 6)
+    assert np.all(s == 1.0) and np.all(z == 20)
+    assert np.array_equal(q - z[:, None], Xr.astype(np.int64))
+
+
+def test_asymmetric_forward_equals_dense_dequantized_product_and_loops():
+    rng = np.random.default_rng(45)
+    n1, n2, N, r, M = 4, 8, 7, 3, 5
+    K = n1 * n2
+    X = rng.standard_t(3.0, size=(M, K)) + 0.7
+    R1, R2 = _orth(rng, n1), _orth(rng, n2)
+    W = rng.normal(0.05, 0.3, size=(N, K))
+    U = orc.to_fp16(rng.normal(size=(K, r)) * 0.1); V = orc.to_fp16(rng.normal(size=(N, r)) * 0.1)
+    for centered in (False, True):
+        out = orc.forward_asym(X, R1, R2, W, U, V, centered=centered)
+        # dense route: dequantized activations times dequantized weights
+        xhat = out["s"][:, None] * (out["q"] - out["z"][:, None])
+        Wdeq = out["alpha16"][:, None] * out["sgn"] + (orc.to_fp16(out["mu"])[:, None] if centered else 0.0)
+        Yd = xhat @ Wdeq.T + (X @ U) @ V.T
+        assert np.allclose(out["Y"], Yd, rtol=1e-12, atol=1e-12)
+        # the contraction as a literal loop over Python ints
+        for t in range(M):
+            for n in range(N):
+                a = sum(int(out["c"][t, k]) * int(out["sgn"][n, k]) for k in range(K))
+                assert a == out["acc_c"][t, n]
+    # what the GPU uses: codes stored with an offset, q' = q - 32, z' = z - 32, and the zero point
+    # taken out of the accumulator as a rank-one term  sum_k (q - z) sgn = sum_k q' sgn - z' rowsum
+    out = orc.forward_asym(X, R1, R2, W, U, V)
+    qp = out["q"].astype(np.int64) - 32
+    zp = out["z"] - 32
+    rowsum = out["sgn"].astype(np.int64).sum(axis=1)
+    assert np.array_equal(orc.binary_gemm(qp.astype(np.int8), out["sgn"]) - zp[:, None] * rowsum[None, :], out["acc_c"])
+
+
+def test_asymmetric_beats_symmetric_on_skewed_tokens_and_matches_it_in_accuracy_on_symmetric_ones():
+    rng = np.random.default_rng(46)
+    cfg = syn.CONFIGS["cfg0_tiny"]
+    d = syn.make_layer(cfg)
+    sgn, alpha = orc.binarize_rows(d.W)
+    Wb = orc.to_fp16(alpha)[:, None] * sgn
+    low = orc.psp_project(d.X, d.U) @ d.V.astype(np.float64).T
+    exact = orc.kron_rotate(d.X, d.R1, d.R2) @ Wb.T + low
+    e_sym = np.linalg.norm(orc.forward(d.X, d.R1, d.R2, d.W, d.U, d.V)["Y"] - exact)
+    e_asym = np.linalg.norm(orc.forward_asym(d.X, d.R1, d.R2, d.W, d.U, d.V)["Y"] - exact)
+    assert 0.3 * e_sym < e_asym < 1.2 * e_sym               # same step size up to the spare level: same accuracy class
+    # a rotated token with a large offset: the symmetric range wastes half of its codes
+    Xr = rng.normal(5.0, 1.0, size=(8, 256))
+    qs, ss, _ = orc.quantize_sym(Xr, 6)
+    qa, sa, za, _, _ = orc.quantize_asym(Xr, 6)
+    err_s = np.linalg.norm(qs * ss[:, None] - Xr)
+    err_a = np.linalg.norm(sa[:, None] * (qa - za[:, None]) - Xr)
+    assert err_a < 0.6 * err_s
+
+
 # ------------------------------------------------------------------ binarization (paper Eq. 1-4; App. A.2.4)
 def test_sign_convention_zero_is_minus_one():
     sgn, alpha = orc.binarize_rows(np.array([[0.0, 1e-30, -1e-30, 2.0]]))
