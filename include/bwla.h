@@ -65,14 +65,18 @@ typedef enum {
  *   R1     n1 x n1 fp32 row-major;  R2  n2 x n2 fp32 row-major
  *   R1p, R2p  the same factors transposed and split into three bfloat16 terms each (their sum is
  *          the fp32 value exactly), zero padded: operand layout of the bf16-MFMA rotation
- * A layer packed with the row shift (bwla_pack_weights_centered) has centered == 1 and r one
- * larger than its PSP rank: column r-1 of V holds the shifts mu_n, U keeps r-1 columns, and
- * column r-1 of T is scale_t * qsum_t (see bwla_rotate_quant), so that the shift term of the
- * dequantization is one more term of the low-rank sum.
+ * `mode` is a set of BWLA_MODE_* bits; each adds rank-one terms of the dequantization as extra
+ * columns of V (written at pack time) and T (written by bwla_rotate_quant) behind the PSP columns,
+ * and r counts them: U keeps r - extra columns.
+ *   BWLA_MODE_ASYM_ACT   two columns: V = delta_n * rowsum_n split into two fp16 (rowsum_n = sum_k
+ *                        Sign), T = -scale_t * z_t twice (z_t: the token's zero point)
+ *   BWLA_MODE_ROW_SHIFT  one column, the last: V = mu_n, T = scale_t * sum_k (q[t,k] - z_t)
  */
+#define BWLA_MODE_ROW_SHIFT 1   /* binarization with the row shift (bwla_pack_weights_centered) */
+#define BWLA_MODE_ASYM_ACT 2    /* the layer's activations get per-token asymmetric codes */
 typedef struct bwla_layer {
     int64_t N, K;
-    int32_t n1, n2, r, centered;
+    int32_t n1, n2, r, mode;
     uint64_t off_bits, off_alpha, off_V, off_U, off_R1, off_R2, off_R1p, off_R2p;
     uint64_t blob_bytes;
     const void* d_blob;
@@ -116,7 +120,7 @@ bwla_status_t bwla_pack_weights(const float* d_W_rot, const float* d_R1, const f
  *   delta_n = mean_k |W_rot[n,k] - mu_n| (stored where alpha is), W_deq = delta_n Sign(.) + mu_n,
  * so that Y[t,n] = scale_t * (delta_n * acc[t,n] + mu_n * qsum_t) + sum_j T[t,j] V[n,j].
  * mu_n is stored in fp16 as one more column of V; the layer's r becomes r + 1 (at most
- * BWLA_MAX_RANK), centered = 1.  Arguments as for bwla_pack_weights / bwla_packed_size, with r
+ * BWLA_MAX_RANK), mode = BWLA_MODE_ROW_SHIFT.  Arguments as for bwla_pack_weights / bwla_packed_size, with r
  * the PSP rank (columns of d_U and d_V).
  */
 bwla_status_t bwla_packed_size_centered(int64_t N, int64_t K, int32_t n1, int32_t n2, int32_t r,
@@ -126,6 +130,25 @@ bwla_status_t bwla_pack_weights_centered(const float* d_W_rot, const float* d_R1
                                          int64_t N, int64_t K, int32_t n1, int32_t n2, int32_t r,
                                          void* d_blob, size_t blob_bytes, void* stream,
                                          bwla_layer_t* out);
+
+/*
+ * The general form: `mode` is any set of BWLA_MODE_* bits (0: bwla_pack_weights; ROW_SHIFT:
+ * bwla_pack_weights_centered).  BWLA_MODE_ASYM_ACT prepares the layer for per-token asymmetric
+ * activation codes (paper Sec. 4.1 names them; the min-max affine form is this library's reading):
+ * bwla_rotate_quant then quantizes each token over [lo, hi] = [min(min_k x, 0), max(max_k x, 0)] with
+ * step scale_t = (hi - lo) / (2^b - 1) and zero point z_t = rint(-lo / scale_t), stores the codes
+ * with an offset so that they fit int8 (q - 2^(b-1); b <= 7), and the zero point leaves the
+ * accumulator as the rank-one term  sum_k (q - z) Sign = sum_k q Sign - z * rowsum_n:
+ *   Y[t,n] = scale_t * (delta_n * (acc - z rowsum_n) + mu_n * sum_k (q - z)) + sum_j T[t,j] V[n,j].
+ * The layer's r becomes r + (2 if ASYM_ACT) + (1 if ROW_SHIFT), at most BWLA_MAX_RANK.
+ */
+bwla_status_t bwla_packed_size_mode(int64_t N, int64_t K, int32_t n1, int32_t n2, int32_t r, int32_t mode,
+                                    size_t* bytes);
+bwla_status_t bwla_pack_weights_mode(const float* d_W_rot, const float* d_R1, const float* d_R2,
+                                     const float* d_U, const float* d_V,
+                                     int64_t N, int64_t K, int32_t n1, int32_t n2, int32_t r, int32_t mode,
+                                     void* d_blob, size_t blob_bytes, void* stream,
+                                     bwla_layer_t* out);
 
 /*
  * Inspection helper: expand the packed sign bits to the interchange view, an N x K int8
@@ -155,8 +178,10 @@ bwla_status_t bwla_psp_workspace_size(const bwla_layer_t* layer, int64_t M, size
  *   T = X U (M x r, fp32 accumulation, from the un-rotated un-quantized X; Sec. 3.2).
  *   d_X      M x K, float or bf16 according to xdtype
  *   d_q      out, M x K int8;  d_scale out, M fp32;  d_qsum out, M int32
- *   d_T      out, M x r fp32 (NULL iff r == 0); for a layer with row shifts (centered == 1) the
- *            first r-1 columns are X U and column r-1 is scale_t * qsum_t
+ *   d_T      out, M x r fp32 (NULL iff r == 0); the leading columns are X U, the columns that the
+ *            layer's mode adds follow (see bwla_layer_t)
+ * For a layer with BWLA_MODE_ASYM_ACT the codes are the asymmetric ones (see bwla_pack_weights_mode):
+ * d_q holds q - 2^(b-1), d_qsum their sums, d_scale the step (hi - lo) / (2^b - 1).
  *   d_ws     scratch of ws_bytes >= bwla_psp_workspace_size(layer, M) (NULL allowed when that is 0)
  */
 bwla_status_t bwla_rotate_quant(const bwla_layer_t* layer, const void* d_X, int xdtype, int64_t M,

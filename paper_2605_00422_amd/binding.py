@@ -13,15 +13,17 @@ LIB_PATH = os.path.join(HERE, "libbwla.so")
 BWLA_OK = 0
 BWLA_ERR_NULL, BWLA_ERR_SHAPE, BWLA_ERR_ALIGN, BWLA_ERR_BUFSIZE, BWLA_ERR_UNSUPPORTED, BWLA_ERR_HIP = 1, 2, 3, 4, 5, 6
 BWLA_X_F32, BWLA_X_BF16 = 0, 1
+BWLA_MODE_ROW_SHIFT, BWLA_MODE_ASYM_ACT = 1, 2
 
 EXPORTS = ["bwla_status_string", "bwla_version", "bwla_kron_factor", "bwla_packed_size", "bwla_pack_weights",
            "bwla_unpack_signs", "bwla_psp_workspace_size", "bwla_rotate_quant", "bwla_code_sums",
-           "bwla_linear_forward", "bwla_decode_forward", "bwla_packed_size_centered", "bwla_pack_weights_centered", "bwla_rotate_quant_bits"]
+           "bwla_linear_forward", "bwla_decode_forward", "bwla_packed_size_centered", "bwla_pack_weights_centered", "bwla_rotate_quant_bits",
+           "bwla_packed_size_mode", "bwla_pack_weights_mode"]
 
 
 class BwlaLayer(Structure):
     _fields_ = [("N", c_int64), ("K", c_int64), ("n1", c_int32), ("n2", c_int32), ("r", c_int32),
-                ("centered", c_int32), ("off_bits", c_uint64), ("off_alpha", c_uint64), ("off_V", c_uint64),
+                ("mode", c_int32), ("off_bits", c_uint64), ("off_alpha", c_uint64), ("off_V", c_uint64),
                 ("off_U", c_uint64), ("off_R1", c_uint64), ("off_R2", c_uint64), ("off_R1p", c_uint64), ("off_R2p", c_uint64),
                 ("blob_bytes", c_uint64),
                 ("d_blob", c_void_p)]
@@ -54,6 +56,9 @@ def load() -> ctypes.CDLL:
                                                        c_size_t, c_void_p, POINTER(BwlaLayer)]
     lib.bwla_packed_size_centered.argtypes = lib.bwla_packed_size.argtypes
     lib.bwla_pack_weights_centered.argtypes = lib.bwla_pack_weights.argtypes
+    lib.bwla_packed_size_mode.argtypes = [c_int64, c_int64, c_int32, c_int32, c_int32, c_int32, POINTER(c_size_t)]
+    lib.bwla_pack_weights_mode.argtypes = [c_void_p] * 5 + [c_int64, c_int64, c_int32, c_int32, c_int32, c_int32,
+                                                            c_void_p, c_size_t, c_void_p, POINTER(BwlaLayer)]
     lib.bwla_unpack_signs.argtypes = [POINTER(BwlaLayer), c_void_p, c_void_p, c_void_p]
     lib.bwla_psp_workspace_size.argtypes = [POINTER(BwlaLayer), c_int64, POINTER(c_size_t)]
     lib.bwla_rotate_quant.argtypes = [POINTER(BwlaLayer), c_void_p, c_int, c_int64, c_void_p, c_void_p, c_void_p,
@@ -101,8 +106,12 @@ def kron_factor(K: int) -> tuple[int, int]:
     return n1.value, n2.value
 
 
-def packed_size(N: int, K: int, n1: int, n2: int, r: int, centered: bool = False) -> int:
+def packed_size(N: int, K: int, n1: int, n2: int, r: int, centered: bool = False, asym: bool = False) -> int:
     out = c_size_t()
+    if asym:
+        mode = BWLA_MODE_ASYM_ACT | (BWLA_MODE_ROW_SHIFT if centered else 0)
+        _check(load().bwla_packed_size_mode(N, K, n1, n2, r, mode, byref(out)), "bwla_packed_size_mode")
+        return out.value
     name = "bwla_packed_size_centered" if centered else "bwla_packed_size"
     _check(getattr(load(), name)(N, K, n1, n2, r, byref(out)), name)
     return out.value
@@ -122,15 +131,21 @@ class PackedLayer:
         return d.N, d.K, d.n1, d.n2, d.r
 
 
-def pack_weights(W_rot, R1, R2, U, V, n1: int, n2: int, centered: bool = False) -> PackedLayer:
+def pack_weights(W_rot, R1, R2, U, V, n1: int, n2: int, centered: bool = False, asym: bool = False) -> PackedLayer:
     """W_rot (N,K), R1, R2, U (K,r), V (N,r): fp32 CUDA tensors (U, V may be None for r = 0).
-    centered: binarize with the row shift (bwla_pack_weights_centered)."""
+    centered: binarize with the row shift (bwla_pack_weights_centered); asym: the layer's
+    activations get per-token asymmetric codes (bwla_pack_weights_mode)."""
     import torch
     N, K = W_rot.shape
     r = 0 if U is None else U.shape[1]
-    nbytes = packed_size(N, K, n1, n2, r, centered)
+    nbytes = packed_size(N, K, n1, n2, r, centered, asym)
     blob = torch.zeros(nbytes, dtype=torch.uint8, device=W_rot.device)
     desc = BwlaLayer()
+    if asym:
+        mode = BWLA_MODE_ASYM_ACT | (BWLA_MODE_ROW_SHIFT if centered else 0)
+        _check(load().bwla_pack_weights_mode(_ptr(W_rot), _ptr(R1), _ptr(R2), _ptr(U), _ptr(V), N, K, n1, n2, r, mode,
+                                             _ptr(blob), nbytes, _stream(), byref(desc)), "bwla_pack_weights_mode")
+        return PackedLayer(desc, blob)
     name = "bwla_pack_weights_centered" if centered else "bwla_pack_weights"
     _check(getattr(load(), name)(_ptr(W_rot), _ptr(R1), _ptr(R2), _ptr(U), _ptr(V), N, K, n1, n2, r,
                                  _ptr(blob), nbytes, _stream(), byref(desc)), name)

@@ -28,12 +28,12 @@ bwla_status_t check_shape(int64_t N, int64_t K, int32_t n1, int32_t n2, int32_t 
     return BWLA_OK;
 }
 
-// r counts the columns of V and T; a layer with row shifts keeps one column fewer in U
-void fill_layout(bwla_layer_t* L, int64_t N, int64_t K, int32_t n1, int32_t n2, int32_t r, int32_t centered) {
+// r counts the columns of V and T; U keeps the PSP columns only
+void fill_layout(bwla_layer_t* L, int64_t N, int64_t K, int32_t n1, int32_t n2, int32_t r, int32_t mode) {
     const uint64_t rp = (uint64_t)((r + 15) & ~15);
-    const uint64_t rpu = (uint64_t)((r - centered + 15) & ~15);
+    const uint64_t rpu = (uint64_t)((r - bwla_extra_cols(mode) + 15) & ~15);
     uint64_t off = 0;
-    L->N = N; L->K = K; L->n1 = n1; L->n2 = n2; L->r = r; L->centered = centered;
+    L->N = N; L->K = K; L->n1 = n1; L->n2 = n2; L->r = r; L->mode = mode;
     L->off_bits = off;  off = bwla_align256(off + (uint64_t)bwla_row_tiles(N) * bwla_chunks(K) * BWLA_UNIT_BYTES);
     L->off_alpha = off; off = bwla_align256(off + (uint64_t)N * 2);
     L->off_V = off;     off = bwla_align256(off + (uint64_t)N * rp * 2);
@@ -50,9 +50,10 @@ bwla_status_t check_layer(const bwla_layer_t* L) {
     if (!L->d_blob) return BWLA_ERR_NULL;
     bwla_status_t s = check_shape(L->N, L->K, L->n1, L->n2, L->r);
     if (s != BWLA_OK) return s;
-    if ((L->centered != 0 && L->centered != 1) || L->r < L->centered) return BWLA_ERR_SHAPE;
+    if ((L->mode & ~(BWLA_MODE_ROW_SHIFT | BWLA_MODE_ASYM_ACT)) != 0 || L->r < bwla_extra_cols(L->mode))
+        return BWLA_ERR_SHAPE;
     bwla_layer_t ref;
-    fill_layout(&ref, L->N, L->K, L->n1, L->n2, L->r, L->centered);
+    fill_layout(&ref, L->N, L->K, L->n1, L->n2, L->r, L->mode);
     if (ref.off_bits != L->off_bits || ref.off_alpha != L->off_alpha || ref.off_V != L->off_V ||
         ref.off_U != L->off_U || ref.off_R1 != L->off_R1 || ref.off_R2 != L->off_R2 ||
         ref.off_R1p != L->off_R1p || ref.off_R2p != L->off_R2p || ref.blob_bytes != L->blob_bytes)
@@ -100,39 +101,42 @@ bwla_status_t bwla_kron_factor(int64_t K, int32_t* n1, int32_t* n2) {
     return BWLA_OK;
 }
 
-static bwla_status_t packed_size(int64_t N, int64_t K, int32_t n1, int32_t n2, int32_t r, int32_t centered,
-                                 size_t* bytes) {
+bwla_status_t bwla_packed_size_mode(int64_t N, int64_t K, int32_t n1, int32_t n2, int32_t r, int32_t mode,
+                                    size_t* bytes) {
     if (!bytes) return BWLA_ERR_NULL;
     if (r < 0) return BWLA_ERR_SHAPE;
-    bwla_status_t s = check_shape(N, K, n1, n2, r + centered);
+    if ((mode & ~(BWLA_MODE_ROW_SHIFT | BWLA_MODE_ASYM_ACT)) != 0) return BWLA_ERR_UNSUPPORTED;
+    bwla_status_t s = check_shape(N, K, n1, n2, r + bwla_extra_cols(mode));
     if (s != BWLA_OK) return s;
     bwla_layer_t L;
-    fill_layout(&L, N, K, n1, n2, r + centered, centered);
+    fill_layout(&L, N, K, n1, n2, r + bwla_extra_cols(mode), mode);
     *bytes = (size_t)L.blob_bytes;
     return BWLA_OK;
 }
 
 bwla_status_t bwla_packed_size(int64_t N, int64_t K, int32_t n1, int32_t n2, int32_t r, size_t* bytes) {
-    return packed_size(N, K, n1, n2, r, 0, bytes);
+    return bwla_packed_size_mode(N, K, n1, n2, r, 0, bytes);
 }
 
 bwla_status_t bwla_packed_size_centered(int64_t N, int64_t K, int32_t n1, int32_t n2, int32_t r, size_t* bytes) {
-    return packed_size(N, K, n1, n2, r, 1, bytes);
+    return bwla_packed_size_mode(N, K, n1, n2, r, BWLA_MODE_ROW_SHIFT, bytes);
 }
 
-// r is the PSP rank (columns of d_U and d_V); the layer's r is r + centered
-static bwla_status_t pack_weights(const float* d_W_rot, const float* d_R1, const float* d_R2, const float* d_U,
-                                  const float* d_V, int64_t N, int64_t K, int32_t n1, int32_t n2, int32_t r,
-                                  int32_t centered, void* d_blob, size_t blob_bytes, void* stream,
-                                  bwla_layer_t* out) {
+// r is the PSP rank (columns of d_U and d_V); the layer's r also counts the columns of its mode
+bwla_status_t bwla_pack_weights_mode(const float* d_W_rot, const float* d_R1, const float* d_R2, const float* d_U,
+                                     const float* d_V, int64_t N, int64_t K, int32_t n1, int32_t n2, int32_t r,
+                                     int32_t mode, void* d_blob, size_t blob_bytes, void* stream,
+                                     bwla_layer_t* out) {
     if (!d_W_rot || !d_R1 || !d_R2 || !d_blob || !out) return BWLA_ERR_NULL;
     if (r < 0) return BWLA_ERR_SHAPE;
-    bwla_status_t s = check_shape(N, K, n1, n2, r + centered);
+    if ((mode & ~(BWLA_MODE_ROW_SHIFT | BWLA_MODE_ASYM_ACT)) != 0) return BWLA_ERR_UNSUPPORTED;
+    const int32_t rt = r + bwla_extra_cols(mode);
+    bwla_status_t s = check_shape(N, K, n1, n2, rt);
     if (s != BWLA_OK) return s;
     if (r > 0 && (!d_U || !d_V)) return BWLA_ERR_NULL;
     if (!aligned16(d_W_rot) || !aligned16(d_blob) || !aligned16(d_R1) || !aligned16(d_R2)) return BWLA_ERR_ALIGN;
     bwla_layer_t L;
-    fill_layout(&L, N, K, n1, n2, r + centered, centered);
+    fill_layout(&L, N, K, n1, n2, rt, mode);
     if (blob_bytes < L.blob_bytes) return BWLA_ERR_BUFSIZE;
     L.d_blob = d_blob;
     hipError_t e = bwla_launch_pack(d_W_rot, d_R1, d_R2, d_U, d_V, N, K, n1, n2, r, &L, (hipStream_t)stream);
@@ -145,14 +149,15 @@ bwla_status_t bwla_pack_weights(const float* d_W_rot, const float* d_R1, const f
                                 const float* d_U, const float* d_V, int64_t N, int64_t K, int32_t n1,
                                 int32_t n2, int32_t r, void* d_blob, size_t blob_bytes, void* stream,
                                 bwla_layer_t* out) {
-    return pack_weights(d_W_rot, d_R1, d_R2, d_U, d_V, N, K, n1, n2, r, 0, d_blob, blob_bytes, stream, out);
+    return bwla_pack_weights_mode(d_W_rot, d_R1, d_R2, d_U, d_V, N, K, n1, n2, r, 0, d_blob, blob_bytes, stream, out);
 }
 
 bwla_status_t bwla_pack_weights_centered(const float* d_W_rot, const float* d_R1, const float* d_R2,
                                          const float* d_U, const float* d_V, int64_t N, int64_t K, int32_t n1,
                                          int32_t n2, int32_t r, void* d_blob, size_t blob_bytes, void* stream,
                                          bwla_layer_t* out) {
-    return pack_weights(d_W_rot, d_R1, d_R2, d_U, d_V, N, K, n1, n2, r, 1, d_blob, blob_bytes, stream, out);
+    return bwla_pack_weights_mode(d_W_rot, d_R1, d_R2, d_U, d_V, N, K, n1, n2, r, BWLA_MODE_ROW_SHIFT, d_blob,
+                                  blob_bytes, stream, out);
 }
 
 bwla_status_t bwla_unpack_signs(const bwla_layer_t* layer, int8_t* d_sgn, float* d_alpha, void* stream) {
@@ -183,6 +188,8 @@ bwla_status_t bwla_rotate_quant_bits(const bwla_layer_t* layer, const void* d_X,
     if (act_bits < 2 || act_bits > 8) return BWLA_ERR_UNSUPPORTED;
     bwla_status_t s = check_layer(layer);
     if (s != BWLA_OK) return s;
+    // asymmetric codes are stored as q - 2^(b-1): with b = 8 that would use -128, which the GEMMs exclude
+    if ((layer->mode & BWLA_MODE_ASYM_ACT) && act_bits > 7) return BWLA_ERR_UNSUPPORTED;
     if (!d_X || !d_q || !d_scale || !d_qsum) return BWLA_ERR_NULL;
     if (layer->r > 0 && !d_T) return BWLA_ERR_NULL;
     if (M <= 0 || M > (int64_t)1 << 24) return BWLA_ERR_SHAPE;

@@ -45,8 +45,10 @@ struct bwla_psp_plan {
 bwla_psp_plan bwla_make_psp_plan(int64_t M, int64_t K, int r);
 // scratch starts with one arrival counter per 16 tokens (whatever the plan), padded to 256 bytes
 inline uint64_t bwla_psp_counter_bytes(int64_t M) { return bwla_align256((uint64_t)((M + 15) / 16) * sizeof(int)); }
-// columns of U = rank of the projection T = X U (a layer with row shifts has one more column in V, T)
-inline int bwla_rank_u(const bwla_layer_t* L) { return L->r - L->centered; }
+// columns that a layer's mode adds to V and T behind the PSP columns
+inline int bwla_extra_cols(int mode) { return ((mode & BWLA_MODE_ASYM_ACT) ? 2 : 0) + ((mode & BWLA_MODE_ROW_SHIFT) ? 1 : 0); }
+// columns of U = rank of the projection T = X U
+inline int bwla_rank_u(const bwla_layer_t* L) { return L->r - bwla_extra_cols(L->mode); }
 inline size_t bwla_psp_ws_bytes(const bwla_psp_plan& p, int64_t M, int r) {
     if (r <= 0 || p.splits <= 1) return 0;
     return (size_t)(bwla_psp_counter_bytes(M) + (uint64_t)p.token_tiles * p.col_groups * p.splits *

@@ -33,7 +33,7 @@ struct BsArgs {
 // itself, so the codes, the scale and the code sum come from its own LDS.
 struct FusedLocal {
     const char* codes;       // K code bytes of the token, in k order
-    const float* amax;       // per-strip maxima of |rotated x|
+    const float* amax;       // per-strip largest rotated value; 32 words further on: the smallest
     const int* sums;         // per-strip sums of the codes
     int strips;
 };
@@ -262,9 +262,12 @@ __device__ __forceinline__ void epilogue_wave(const BsArgs& a, char* smem, int f
         // this wavefront comes from the rotation: the codes are in LDS, and so are the per-strip
         // maxima and sums (same expressions as where the rotation writes scale and sum out)
         TRACE(39);
-        float amax = fl.amax[0];
+        float amax = fmaxf(fl.amax[0], -fl.amax[32]);
         int tot = fl.sums[0];
-        for (int w = 1; w < fl.strips; ++w) { amax = fmaxf(amax, fl.amax[w]); tot += fl.sums[w]; }
+        for (int w = 1; w < fl.strips; ++w) {
+            amax = fmaxf(amax, fmaxf(fl.amax[w], -fl.amax[32 + w]));
+            tot += fl.sums[w];
+        }
         st = tok_ok ? amax / 31.0f : 0.0f;
         qs = tok_ok ? tot : 0;
         bs_local_stage_codes(a, qt, fl, wave, lane);

@@ -59,22 +59,27 @@ __global__ __launch_bounds__(64) void row_scale_kernel(const float* __restrict__
     if (threadIdx.x == 0) alpha[n] = double_to_half_bits(s / (double)K);
 }
 
-// Binarization with the row shift (paper Sec. 3 "Discussion", Eq. 1-2): one workgroup per tile of
-// 16 rows.  First the fp64 row means mu; then, chunk by chunk, the bits of (w - mu > 0) in the
-// tiled layout (padding columns stay 0) and the fp64 sums of |w - mu|, added up in a fixed order;
-// delta goes where alpha is, mu (fp16) into column `mu_col` of V.
-__global__ __launch_bounds__(256) void pack_rows_centered_kernel(const float* __restrict__ W, int64_t N, int64_t K,
-                                                                 int64_t chunks, uint32_t* __restrict__ bits,
-                                                                 uint16_t* __restrict__ alpha,
-                                                                 uint16_t* __restrict__ V16, int rp, int mu_col) {
+// Layers whose mode adds columns to V: one workgroup per tile of 16 rows.
+// Row shift (paper Sec. 3 "Discussion", Eq. 1-2; mu_col >= 0): first the fp64 row means mu; else
+// mu = 0.  Then, chunk by chunk, the bits of (w - mu > 0) in the tiled layout (padding columns
+// stay 0), the fp64 sums of |w - mu| and the counts of positive signs, added up in a fixed order.
+// delta goes where alpha is, mu (fp16) into column mu_col of V; for asymmetric activation codes
+// (asym_col >= 0) delta_n * rowsum_n, with delta as stored and rowsum_n = sum_k Sign = 2 pos - K,
+// goes into columns asym_col, asym_col + 1 as two fp16 terms.
+__global__ __launch_bounds__(256) void pack_rows_mode_kernel(const float* __restrict__ W, int64_t N, int64_t K,
+                                                             int64_t chunks, uint32_t* __restrict__ bits,
+                                                             uint16_t* __restrict__ alpha,
+                                                             uint16_t* __restrict__ V16, int rp, int mu_col,
+                                                             int asym_col) {
     __shared__ double mu[16];
     __shared__ double part[4][64];
+    __shared__ int pos[4][64];
     const int64_t rt = blockIdx.x;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     for (int rr = 0; rr < 4; ++rr) {                     // wave w: rows 4w .. 4w+3 of the tile
         const int64_t n = rt * BWLA_TILE_ROWS + wave * 4 + rr;
         double s = 0.0;
-        if (n < N) {
+        if (n < N && mu_col >= 0) {
             const float* row = W + n * K;
             for (int64_t k = lane; k < K; k += 64) s += (double)row[k];
         }
@@ -87,6 +92,7 @@ __global__ __launch_bounds__(256) void pack_rows_centered_kernel(const float* __
     const int64_t n = rt * BWLA_TILE_ROWS + i;
     const double m = mu[i];
     double dsum = 0.0;
+    int npos = 0;
     for (int64_t kc = wave; kc < chunks; kc += 4) {
         const int64_t kbase = kc * BWLA_CHUNK_COLS + g * 128;
         uint32_t w[4] = {0u, 0u, 0u, 0u};
@@ -98,7 +104,7 @@ __global__ __launch_bounds__(256) void pack_rows_centered_kernel(const float* __
                 if (k < K) {
                     const double c = (double)row[k] - m;
                     const int j = kk >> 4, d = (kk >> 2) & 3, b = kk & 3;
-                    if (c > 0.0) w[d] |= 1u << (8 * b + j);
+                    if (c > 0.0) { w[d] |= 1u << (8 * b + j); ++npos; }
                     dsum += fabs(c);
                 }
             }
@@ -106,15 +112,27 @@ __global__ __launch_bounds__(256) void pack_rows_centered_kernel(const float* __
         reinterpret_cast<uint4*>(bits)[(rt * chunks + kc) * 64 + lane] = make_uint4(w[0], w[1], w[2], w[3]);
     }
     part[wave][lane] = dsum;
+    pos[wave][lane] = npos;
     __syncthreads();
     if (tid < 16 && rt * BWLA_TILE_ROWS + tid < N) {
         double s = 0.0;
+        int p = 0;
         for (int w2 = 0; w2 < 4; ++w2)
-            for (int g2 = 0; g2 < 4; ++g2) s += part[w2][g2 * 16 + tid];
+            for (int g2 = 0; g2 < 4; ++g2) { s += part[w2][g2 * 16 + tid]; p += pos[w2][g2 * 16 + tid]; }
         const int64_t row = rt * BWLA_TILE_ROWS + tid;
-        alpha[row] = double_to_half_bits(s / (double)K);
-        const double mm = mu[tid];
-        V16[row * rp + mu_col] = (uint16_t)((mm < 0.0 ? 0x8000u : 0u) | double_to_half_bits(fabs(mm)));
+        const uint16_t d16 = double_to_half_bits(s / (double)K);
+        alpha[row] = d16;
+        if (mu_col >= 0) {
+            const double mm = mu[tid];
+            V16[row * rp + mu_col] = (uint16_t)((mm < 0.0 ? 0x8000u : 0u) | double_to_half_bits(fabs(mm)));
+        }
+        if (asym_col >= 0) {
+            const float c = __half2float(__ushort_as_half(d16)) * (float)(2 * p - (int)K);
+            const __half hi = __float2half_rn(c);
+            const __half lo = __float2half_rn(c - __half2float(hi));
+            V16[row * rp + asym_col] = __half_as_ushort(hi);
+            V16[row * rp + asym_col + 1] = __half_as_ushort(lo);
+        }
     }
 }
 
@@ -194,7 +212,7 @@ __global__ void unpack_kernel(const uint32_t* __restrict__ bits, const __half* _
 hipError_t bwla_launch_pack(const float* dW, const float* dR1, const float* dR2, const float* dU,
                             const float* dV, int64_t N, int64_t K, int n1, int n2, int r,
                             const bwla_layer_t* L, hipStream_t st) {
-    // r = columns of dU and dV (the PSP rank); V has L->r columns (one more with row shifts)
+    // r = columns of dU and dV (the PSP rank); V has L->r columns (the layer's mode may add some)
     char* blob = (char*)L->d_blob;
     const int64_t chunks = bwla_chunks(K), rts = bwla_row_tiles(N);
     const int rpv = (L->r + 15) & ~15, rpu = (r + 15) & ~15;
@@ -206,10 +224,13 @@ hipError_t bwla_launch_pack(const float* dW, const float* dR1, const float* dR2,
         const int64_t nu = K * rpu;
         u_transpose_f16_kernel<<<dim3((unsigned)((nu + 255) / 256)), dim3(256), 0, st>>>(dU, K, r, rpu, (__half*)(blob + L->off_U));
     }
-    if (L->centered) {
-        pack_rows_centered_kernel<<<dim3((unsigned)rts), dim3(256), 0, st>>>(
+    if (L->mode != 0) {
+        // columns behind the PSP ones: [asymmetric codes: 2][row shift: 1]
+        const int asym_col = (L->mode & BWLA_MODE_ASYM_ACT) ? r : -1;
+        const int mu_col = (L->mode & BWLA_MODE_ROW_SHIFT) ? L->r - 1 : -1;
+        pack_rows_mode_kernel<<<dim3((unsigned)rts), dim3(256), 0, st>>>(
             dW, N, K, chunks, (uint32_t*)(blob + L->off_bits), (uint16_t*)(blob + L->off_alpha),
-            (uint16_t*)(blob + L->off_V), rpv, r);
+            (uint16_t*)(blob + L->off_V), rpv, mu_col, asym_col);
     } else {
         pack_bits_kernel<<<dim3((unsigned)(rts * chunks)), dim3(64), 0, st>>>(
             dW, N, K, chunks, (uint32_t*)(blob + L->off_bits));

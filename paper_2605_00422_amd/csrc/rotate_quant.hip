@@ -36,6 +36,49 @@ __device__ long long bwla_rq_trace_buf[16 * 8 * 16];
 #define RQTRACE_FLUSH do { } while (0)
 #endif
 
+// How a token is quantized, from its largest and smallest rotated value (hi >= 0 >= lo: the
+// reductions start at zero, which also covers the zero padding).
+//   symmetric:   codes rint(x * qmax / amax) in [-qmax, qmax], scale = amax / qmax
+//   asymmetric:  L = 2 qmax + 1 steps over [lo, hi], scale = (hi - lo) / L, zero point
+//                z = rint(-lo / scale); the code q = rint(x / scale) + z in [0, L] is stored as
+//                q - (qmax + 1), so zc = z - (qmax + 1) is what the stored code has to lose
+struct QuantPlan {
+    float inv, zc, cmin, cmax, scale;
+};
+__device__ __forceinline__ QuantPlan quant_plan(float hi, float lo, float qmax, bool asym) {
+    QuantPlan p;
+    if (asym) {
+        const float L = 2.0f * qmax + 1.0f, span = hi - lo;
+        p.inv = span > 0.0f ? L / span : 0.0f;
+        p.scale = span / L;
+        p.zc = rintf(-lo * p.inv) - (qmax + 1.0f);
+        if (!(span > 0.0f)) p.zc = -(qmax + 1.0f);      // all-zero token: q = z = 0
+        p.cmin = -(qmax + 1.0f);
+        p.cmax = qmax;
+    } else {
+        const float amax = fmaxf(hi, -lo);
+        p.inv = amax > 0.0f ? qmax / amax : 0.0f;
+        p.scale = amax / qmax;
+        p.zc = 0.0f;
+        p.cmin = -qmax;
+        p.cmax = qmax;
+    }
+    return p;
+}
+__device__ __forceinline__ int quant_code(float x, const QuantPlan& p) {
+    return (int)fminf(fmaxf(rintf(x * p.inv) + p.zc, p.cmin), p.cmax);
+}
+// The entries of T that the layer's mode adds for token t (tmode points at the first of them in
+// row 0, or is NULL): asymmetric codes: -scale * zc, twice; row shift: scale * sum_k (q - z).
+__device__ __forceinline__ void quant_extras(float* tmode, int tp, int64_t t, bool asym, bool shift,
+                                             const QuantPlan& p, int tot, int64_t K) {
+    if (!tmode) return;
+    float* row = tmode + t * tp;
+    int c = 0;
+    if (asym) { row[0] = row[1] = -(p.scale * p.zc); c = 2; }
+    if (shift) row[c] = p.scale * ((float)tot - (float)K * p.zc);
+}
+
 constexpr int RQ_THREADS = 512;
 constexpr int RQ_WAVES = RQ_THREADS / 64;
 constexpr int RQ_MAXT = 16;          // 16x16 output tiles per wavefront
@@ -258,8 +301,8 @@ template <bool BF16>
 __device__ __forceinline__ void rotate_token(float* lds, const void* __restrict__ X, int64_t t, int64_t K, int n1,
                                              int n2, const float* __restrict__ R1, const float* __restrict__ R2,
                                              int8_t* __restrict__ q, float* __restrict__ scale,
-                                             int32_t* __restrict__ qsum, float* __restrict__ tshift, int tp,
-                                             float qmax) {
+                                             int32_t* __restrict__ qsum, float* __restrict__ tmode, int tp,
+                                             float qmax, bool asym, bool shift) {
     const RqShape sh = rq_shape(n1, n2);
     float* reg = lds;                                              // V, later ZT
     float* fac = lds + sh.region;                                  // R2T | R1T (resident) or two chunk buffers
@@ -410,20 +453,21 @@ __device__ __forceinline__ void rotate_token(float* lds, const void* __restrict_
 
     RQTRACE(5);
     // ================= per-token max magnitude
-    float m = 0.0f;
+    float mx = 0.0f, mn = 0.0f;
 #pragma unroll
     for (int s = 0; s < RQ_MAXT; ++s)
         if (s < my_tiles) {
 #pragma unroll
-            for (int v = 0; v < 4; ++v) m = fmaxf(m, fabsf(acc[s][v]));
+            for (int v = 0; v < 4; ++v) { mx = fmaxf(mx, acc[s][v]); mn = fminf(mn, acc[s][v]); }
         }
-    m = bwla_wave_max(m);
-    if (lane == 0) red[wave] = m;
+    mx = bwla_wave_max(mx);
+    mn = -bwla_wave_max(-mn);
+    if (lane == 0) { red[wave] = mx; red[32 + wave] = mn; }
     bwla_lds_barrier();                                // also: every wave is done reading ZT
-    float amax = red[0];
+    float hi = red[0], lo = red[32];
 #pragma unroll
-    for (int w = 1; w < RQ_WAVES; ++w) amax = fmaxf(amax, red[w]);
-    const float inv = amax > 0.0f ? qmax / amax : 0.0f;
+    for (int w = 1; w < RQ_WAVES; ++w) { hi = fmaxf(hi, red[w]); lo = fminf(lo, red[32 + w]); }
+    const QuantPlan qp = quant_plan(hi, lo, qmax, asym);
     RQTRACE(6);
 
     // ================= quantize from registers into an LDS byte image of the token's codes:
@@ -438,11 +482,7 @@ __device__ __forceinline__ void rotate_token(float* lds, const void* __restrict_
             const int c = tj * 16 + li, d0 = ti * 16 + 4 * lg;
             int code[4];
 #pragma unroll
-            for (int v = 0; v < 4; ++v) {
-                float r = rintf(acc[s][v] * inv);
-                r = fminf(fmaxf(r, -qmax), qmax);
-                code[v] = (int)r;
-            }
+            for (int v = 0; v < 4; ++v) code[v] = quant_code(acc[s][v], qp);
             if (c < n1) {
                 if ((n2 & 3) == 0) {
                     if (d0 < n2) {
@@ -478,8 +518,8 @@ __device__ __forceinline__ void rotate_token(float* lds, const void* __restrict_
 #pragma unroll
         for (int w = 0; w < RQ_WAVES; ++w) tot += redi[w];
         qsum[t] = tot;
-        scale[t] = amax / qmax;
-        if (tshift) tshift[t * tp] = (amax / qmax) * (float)tot;      // the shift term's entry of T
+        scale[t] = qp.scale;
+        quant_extras(tmode, tp, t, asym, shift, qp, tot, K);
     }
     RQTRACE(8);
     RQTRACE_FLUSH;
@@ -563,8 +603,9 @@ __device__ __forceinline__ void rotate3_token(char* lds, const uint16_t* __restr
                                               const uint16_t* __restrict__ R1p,
                                               const uint16_t* __restrict__ R2p, int8_t* __restrict__ q,
                                               float* __restrict__ scale, int32_t* __restrict__ qsum,
-                                              bool store_out = true, float* __restrict__ tshift = nullptr,
-                                              int tp = 0, float qmax = 31.0f) {
+                                              bool store_out = true, float* __restrict__ tmode = nullptr,
+                                              int tp = 0, float qmax = 31.0f, bool asym = false,
+                                              bool shift = false) {
     const R3Shape sh = r3_shape(n1, n2);
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);         // = strip
@@ -852,19 +893,20 @@ __device__ __forceinline__ void rotate3_token(char* lds, const uint16_t* __restr
 
     RQTRACE(4);
     // ---- per-token max magnitude (padded rows and columns are exact zeros)
-    float m = 0.0f;
+    float mx = 0.0f, mn = 0.0f;
 #pragma unroll
     for (int tc = 0; tc < ATM; ++tc)
         if (tc < sh.at) {
 #pragma unroll
-            for (int v = 0; v < 4; ++v) m = fmaxf(m, fabsf(y[tc][v]));
+            for (int v = 0; v < 4; ++v) { mx = fmaxf(mx, y[tc][v]); mn = fminf(mn, y[tc][v]); }
         }
-    m = bwla_wave_max(m);
-    if (lane == 0) red[wave] = m;
+    mx = bwla_wave_max(mx);
+    mn = -bwla_wave_max(-mn);
+    if (lane == 0) { red[wave] = mx; red[32 + wave] = mn; }
     __syncthreads();                                   // also: every wave is done with the token rows
-    float amax = red[0];
-    for (int w = 1; w < sh.strips; ++w) amax = fmaxf(amax, red[w]);
-    const float inv = amax > 0.0f ? qmax / amax : 0.0f;
+    float hi = red[0], lo = red[32];
+    for (int w = 1; w < sh.strips; ++w) { hi = fmaxf(hi, red[w]); lo = fminf(lo, red[32 + w]); }
+    const QuantPlan qp = quant_plan(hi, lo, qmax, asym);
     RQTRACE(5);
 
     // ---- quantize: lane holds Yt[d = 16*strip + 4*lg + v][c = 16*tc + li], four consecutive d of one c
@@ -877,11 +919,7 @@ __device__ __forceinline__ void rotate3_token(char* lds, const uint16_t* __restr
             const int c = tc * 16 + li;
             int code[4];
 #pragma unroll
-            for (int v = 0; v < 4; ++v) {
-                float r = rintf(y[tc][v] * inv);
-                r = fminf(fmaxf(r, -qmax), qmax);
-                code[v] = (int)r;
-            }
+            for (int v = 0; v < 4; ++v) code[v] = quant_code(y[tc][v], qp);
             if (c < n1) {
                 if ((n2 & 3) == 0) {
                     if (d0 < n2) {
@@ -915,8 +953,8 @@ __device__ __forceinline__ void rotate3_token(char* lds, const uint16_t* __restr
             int tot = 0;
             for (int w = 0; w < sh.strips; ++w) tot += redi[w];
             qsum[t] = tot;
-            scale[t] = amax / qmax;
-            if (tshift) tshift[t * tp] = (amax / qmax) * (float)tot;  // the shift term's entry of T
+            scale[t] = qp.scale;
+            quant_extras(tmode, tp, t, asym, shift, qp, tot, K);
         }
     }
     RQTRACE(6);
@@ -1115,8 +1153,8 @@ __device__ __forceinline__ void rotate_split_block(char* lds, const uint16_t* __
         }
     }
 
-    // ---- rotated values out (lane: d = 16*strip + 4*lg + v, c = 16*tile + li), and my maximum
-    float m = 0.0f;
+    // ---- rotated values out (lane: d = 16*strip + 4*lg + v, c = 16*tile + li), and my extremes
+    float mx = 0.0f, mn = 0.0f;
     const int d0 = wave * 16 + 4 * lg;
     float* xt = xs + t * K;
 #pragma unroll
@@ -1128,17 +1166,20 @@ __device__ __forceinline__ void rotate_split_block(char* lds, const uint16_t* __
             for (int v = 0; v < 4; ++v)
                 if (d0 + v < n2) {
                     xt[(int64_t)c * n2 + d0 + v] = y[v];
-                    m = fmaxf(m, fabsf(y[v]));
+                    mx = fmaxf(mx, y[v]);
+                    mn = fminf(mn, y[v]);
                 }
         }
     }
-    m = bwla_wave_max(m);
-    if (lane == 0) red[wave] = m;
+    mx = bwla_wave_max(mx);
+    mn = -bwla_wave_max(-mn);
+    if (lane == 0) { red[wave] = mx; red[32 + wave] = mn; }
     bwla_lds_barrier();
     if (tid == 0) {
-        float mm = red[0];
-        for (int w = 1; w < sh.strips; ++w) mm = fmaxf(mm, red[w]);
-        pmax[t * rs.G + j] = mm;
+        float hi = red[0], lo = red[32];
+        for (int w = 1; w < sh.strips; ++w) { hi = fmaxf(hi, red[w]); lo = fminf(lo, red[32 + w]); }
+        pmax[(t * rs.G + j) * 2] = hi;                 // largest and smallest value of my slice (0 included)
+        pmax[(t * rs.G + j) * 2 + 1] = lo;
         if (j == 0) qsum[t] = 0;                       // the quantizing launch adds its sums up here
     }
 }
@@ -1151,7 +1192,8 @@ constexpr int RS_QI = 4;             // float4 per thread: K <= RS_QB * 512 * RS
 __global__ __launch_bounds__(512) void quantize_rows_kernel(const float* __restrict__ xs, const float* __restrict__ pmax,
                                                             int G, int64_t K, int8_t* __restrict__ q,
                                                             float* __restrict__ scale, int32_t* __restrict__ qsum,
-                                                            float qmax) {
+                                                            float qmax, int asym, float* __restrict__ tmode, int tp,
+                                                            float* __restrict__ zcs) {
     __shared__ int redi[8];
     const int64_t t = blockIdx.x / RS_QB;
     const int part = (int)(blockIdx.x - t * RS_QB);
@@ -1164,9 +1206,9 @@ __global__ __launch_bounds__(512) void quantize_rows_kernel(const float* __restr
         const int i = (e * RS_QB + part) * 512 + tid;
         x[e] = src[i < n4 ? i : n4 - 1];
     }
-    float amax = pmax[t * G];
-    for (int j = 1; j < G; ++j) amax = fmaxf(amax, pmax[t * G + j]);
-    const float inv = amax > 0.0f ? qmax / amax : 0.0f;
+    float hi = pmax[t * G * 2], lo = pmax[t * G * 2 + 1];
+    for (int j = 1; j < G; ++j) { hi = fmaxf(hi, pmax[(t * G + j) * 2]); lo = fminf(lo, pmax[(t * G + j) * 2 + 1]); }
+    const QuantPlan qp = quant_plan(hi, lo, qmax, asym != 0);
     int* dst = reinterpret_cast<int*>(q + t * K);
     int lsum = 0;
 #pragma unroll
@@ -1177,9 +1219,7 @@ __global__ __launch_bounds__(512) void quantize_rows_kernel(const float* __restr
             int code[4];
 #pragma unroll
             for (int v = 0; v < 4; ++v) {
-                float r = rintf(f[v] * inv);
-                r = fminf(fmaxf(r, -qmax), qmax);
-                code[v] = (int)r;
+                code[v] = quant_code(f[v], qp);
                 lsum += code[v];
             }
             dst[i] = (code[0] & 0xff) | ((code[1] & 0xff) << 8) | ((code[2] & 0xff) << 16) | (code[3] << 24);
@@ -1192,20 +1232,27 @@ __global__ __launch_bounds__(512) void quantize_rows_kernel(const float* __restr
         int tot = 0;
         for (int w = 0; w < 8; ++w) tot += redi[w];
         atomicAdd(qsum + t, tot);
-        if (part == 0) scale[t] = amax / qmax;
+        if (part == 0) {
+            scale[t] = qp.scale;
+            zcs[t] = qp.zc;
+            if (asym && tmode) tmode[t * tp] = tmode[t * tp + 1] = -(qp.scale * qp.zc);
+        }
     }
 }
 
-// layers with row shifts, after the split rotation: T[t, last] = scale_t * qsum_t
-__global__ void shift_column_kernel(const float* __restrict__ scale, const int32_t* __restrict__ qsum, int64_t M,
+// layers with row shifts, after the split rotation (the code sum is complete only now):
+// T[t, last] = scale_t * sum_k (q - z) = scale_t * (qsum_t - K zc_t)
+__global__ void shift_column_kernel(const float* __restrict__ scale, const int32_t* __restrict__ qsum,
+                                    const float* __restrict__ zcs, int64_t M, int64_t K,
                                     float* __restrict__ tshift, int tp) {
     const int64_t t = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-    if (t < M) tshift[t * tp] = scale[t] * (float)qsum[t];
+    if (t < M) tshift[t * tp] = scale[t] * ((float)qsum[t] - (float)K * zcs[t]);
 }
 
 // where rotate3_token<.., LOCAL> leaves its results (resident shapes only)
 __device__ __forceinline__ FusedLocal r3_local(const char* lds, const R3Shape& sh) {
-    // words [0, 16) maxima, [16, 32) sums (of the 64 words behind the chunk buffers)
+    // words [0, 16) largest values, [16, 32) code sums, [32, 48) smallest values (of the 64 words
+    // behind the chunk buffers)
     const float* red = reinterpret_cast<const float*>(lds + sh.r0bytes + (size_t)sh.nbuf * sh.cbytes);
     return FusedLocal{lds, red, reinterpret_cast<const int*>(red) + 16, sh.strips};
 }
@@ -1322,10 +1369,11 @@ struct RqArgs {
     const float* R1; const float* R2; const __half* U;
     int8_t* q; float* scale; int32_t* qsum; float* T;
     int* counters; float* partials; int S;
-    float* xs; float* pmax;  // split rotation: rotated values (M x K) and per-workgroup maxima (M x G)
+    float* xs; float* pmax;  // split rotation: rotated values (M x K) and per-workgroup extremes (M x G x 2)
     float qmax;              // largest code: 2^(bits-1) - 1
     int tp;                  // row pitch of T (= r, or r + 1 for a layer with row shifts)
-    float* tshift;           // T + r for such a layer (entry scale_t * qsum_t of each row), else NULL
+    float* tmode;            // T + (PSP rank): first of the entries the layer's mode adds to a row, or NULL
+    int asym, shift;         // the layer's mode: asymmetric activation codes, row shift
     int64_t rot_blocks;      // workgroups below this index rotate token blockIdx.x, the rest project
     const uint16_t* R1p; const uint16_t* R2p;          // bf16 term planes of the factors
 };
@@ -1334,7 +1382,8 @@ template <bool BF16>
 __global__ __launch_bounds__(RQ_THREADS) void rotate_quant_kernel(RqArgs a) {
     extern __shared__ __align__(16) float lds[];
     if ((int64_t)blockIdx.x < a.rot_blocks) {
-        rotate_token<BF16>(lds, a.X, blockIdx.x, a.K, a.n1, a.n2, a.R1, a.R2, a.q, a.scale, a.qsum, a.tshift, a.tp, a.qmax);
+        rotate_token<BF16>(lds, a.X, blockIdx.x, a.K, a.n1, a.n2, a.R1, a.R2, a.q, a.scale, a.qsum, a.tmode, a.tp, a.qmax,
+                           a.asym != 0, a.shift != 0);
     } else {
         const int pb = (int)(blockIdx.x - a.rot_blocks);
         psp_block<BF16>(reinterpret_cast<char*>(lds), a.X, a.M, a.K, a.r, a.U, a.T, a.counters, a.partials, a.S,
@@ -1348,8 +1397,8 @@ __global__ __launch_bounds__(THREADS) void rotate_quant3_kernel(RqArgs a) {
     extern __shared__ __align__(16) float lds[];
     if ((int64_t)blockIdx.x < a.rot_blocks) {
         rotate3_token<ATM, LOOP>(reinterpret_cast<char*>(lds), reinterpret_cast<const uint16_t*>(a.X), blockIdx.x,
-                           a.rot_blocks, a.M, a.K, a.n1, a.n2, a.R1p, a.R2p, a.q, a.scale, a.qsum, true, a.tshift,
-                           a.tp, a.qmax);
+                           a.rot_blocks, a.M, a.K, a.n1, a.n2, a.R1p, a.R2p, a.q, a.scale, a.qsum, true, a.tmode,
+                           a.tp, a.qmax, a.asym != 0, a.shift != 0);
     } else {
         const int pb = (int)(blockIdx.x - a.rot_blocks);
         psp_block<true>(reinterpret_cast<char*>(lds), a.X, a.M, a.K, a.r, a.U, a.T, a.counters, a.partials, a.S,
@@ -1506,7 +1555,8 @@ hipError_t bwla_launch_rotate_quant(const bwla_layer_t* L, const void* dX, int x
     RqArgs a;
     const int ru = bwla_rank_u(L);                     // the projection's rank; T has L->r columns
     a.X = dX; a.M = M; a.K = L->K; a.n1 = L->n1; a.n2 = L->n2; a.r = ru;
-    a.tp = L->r; a.tshift = L->centered ? dT + ru : nullptr;
+    a.tp = L->r; a.tmode = L->mode != 0 ? dT + ru : nullptr;
+    a.asym = (L->mode & BWLA_MODE_ASYM_ACT) ? 1 : 0; a.shift = (L->mode & BWLA_MODE_ROW_SHIFT) ? 1 : 0;
     a.qmax = (float)((1 << (act_bits - 1)) - 1);
     a.R1 = (const float*)(blob + L->off_R1); a.R2 = (const float*)(blob + L->off_R2);
     a.U = (const __half*)(blob + L->off_U);
@@ -1530,6 +1580,7 @@ hipError_t bwla_launch_rotate_quant(const bwla_layer_t* L, const void* dX, int x
         const RsShape rs = rs_shape(s3);
         a.xs = (float*)((char*)dws + bwla_align256(bwla_psp_ws_bytes(plan, M, ru)));
         a.pmax = a.xs + M * L->K;
+        float* zcs = a.pmax + 2 * M * rs.G;            // per token: what the stored codes have to lose
         a.rot_blocks = M * rs.G;
         const size_t pl3 = merged ? pp_lds_bytes(ru, 8) : 0;
         const size_t lds3 = pl3 > rs.lds_bytes ? pl3 : rs.lds_bytes;
@@ -1540,11 +1591,13 @@ hipError_t bwla_launch_rotate_quant(const bwla_layer_t* L, const void* dX, int x
         e = hipGetLastError();
         if (e != hipSuccess) return e;
         quantize_rows_kernel<<<dim3((unsigned)(M * RS_QB)), dim3(512), 0, st>>>(a.xs, a.pmax, rs.G, L->K, dq, dscale,
-                                                                                 dqsum, a.qmax);
+                                                                                 dqsum, a.qmax, a.asym, a.tmode,
+                                                                                 a.tp, zcs);
         e = hipGetLastError();
         if (e != hipSuccess) return e;
-        if (a.tshift) {
-            shift_column_kernel<<<dim3((unsigned)((M + 255) / 256)), dim3(256), 0, st>>>(dscale, dqsum, M, a.tshift, a.tp);
+        if (a.shift) {
+            shift_column_kernel<<<dim3((unsigned)((M + 255) / 256)), dim3(256), 0, st>>>(
+                dscale, dqsum, zcs, M, L->K, a.tmode + (a.asym ? 2 : 0), a.tp);
             e = hipGetLastError();
             if (e != hipSuccess) return e;
         }
@@ -1606,7 +1659,7 @@ size_t bwla_split_rotation_bytes(const bwla_layer_t* L, const bwla_psp_plan& pla
     // every workgroup of the launch gets a CU of its own at once; with more tokens than that the
     // one-workgroup-per-token kernel keeps the chip busy anyway
     if (M * rs.G + pblocks > bwla_device_cus()) return 0;
-    return (size_t)(M * L->K + M * rs.G) * sizeof(float);
+    return (size_t)(M * L->K + 2 * M * rs.G + M) * sizeof(float);     // values, extremes, per-token code offset
 }
 
 // Single-launch decode layer.  *done = false (and nothing launched) when the shape is outside what

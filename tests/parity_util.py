@@ -91,7 +91,7 @@ def run_case(cfg: syn.LayerConfig, rows=None, centered: bool = False, act_bits: 
         ref_T = ref["T"]
 
     layer = pack_on_gpu(d, W, centered)
-    assert layer.desc.r == rt and layer.desc.centered == int(centered)
+    assert layer.desc.r == rt and layer.desc.mode == int(centered)
     # packed weights: interchange view equals the oracle's binarization, bit for bit
     sgn_gpu, alpha_gpu = B.unpack_signs(layer)
     assert torch.equal(sgn_gpu.cpu(), torch.from_numpy(sgn)), "sign bits differ"
