@@ -58,7 +58,7 @@ def gemm_ops(cfg) -> int:
 class Workload:
     """One layer on the GPU with `copies` packed replicas and preallocated outputs."""
 
-    def __init__(self, cfg, copies=None, centered=False, act_bits=6):
+    def __init__(self, cfg, copies=None, centered=False, act_bits=6, asym=False):
         import numpy as np
         import torch
         from paper_2605_00422_amd import binding as B
@@ -73,7 +73,7 @@ class Workload:
         V = t(d.V) if cfg.r > 0 else None
         # centered: binarization with the row shift, on weights with a per-channel offset
         W = syn.shifted_weights(d) if centered else d.W
-        first = B.pack_weights(t(W), t(d.R1), t(d.R2), U, V, cfg.n1, cfg.n2, centered=centered)
+        first = B.pack_weights(t(W), t(d.R1), t(d.R2), U, V, cfg.n1, cfg.n2, centered=centered, asym=asym)
         torch.cuda.synchronize()
         nbytes = first.blob.numel()
         if copies is None:
@@ -140,9 +140,10 @@ class Workload:
         return e0.elapsed_time(e1) / steps
 
 
-def measure(cfg, steps, warmup, use_graph=True, centered=False, act_bits=6):
-    w = Workload(cfg, centered=centered, act_bits=act_bits)
-    out = {"workload": cfg.name + ("+row_shift" if centered else "") + (f"+a{act_bits}" if act_bits != 6 else ""),
+def measure(cfg, steps, warmup, use_graph=True, centered=False, act_bits=6, asym=False):
+    w = Workload(cfg, centered=centered, act_bits=act_bits, asym=asym)
+    out = {"workload": cfg.name + ("+row_shift" if centered else "") + (f"+a{act_bits}" if act_bits != 6 else "")
+           + ("+asym" if asym else ""),
            "M": cfg.M, "K": cfg.K, "N": cfg.N, "r": cfg.r,
            "kron": f"{cfg.n1}x{cfg.n2}", "layer_copies": len(w.layers)}
     ms_step = w.time_loop(w.step, steps, warmup)
@@ -297,15 +298,19 @@ def main():
                  "cfg4_70b_q_m64", "cfg4_70b_q_m4096"]
         # (name, layer binarized with the row shift: the shift term rides as one more low-rank column)
         # and 8-bit activation codes, the width of the paper's speed run: same kernels, same bytes)
-        for nm, shift, bits in [(n, False, 6) for n in names] + [("cfg1_decode7b", True, 6), ("cfg1_decode7b", False, 8)]:
-            if nm == cfg.name and not shift and bits == 6:
+        # and per-token asymmetric codes with the row shift, the paper's own setting: three more columns)
+        variants = [(n, False, 6, False) for n in names] + [("cfg1_decode7b", True, 6, False),
+                                                            ("cfg1_decode7b", False, 8, False),
+                                                            ("cfg1_decode7b", True, 6, True)]
+        for nm, shift, bits, asym in variants:
+            if nm == cfg.name and not shift and bits == 6 and not asym:
                 continue
             c = all_cfgs[nm]
             st = max(20, min(args.steps, 200 if c.M <= 64 else 20))
             ww, r = measure(c, st, max(3, min(args.warmup, st // 4)), not args.no_graph, centered=shift,
-                            act_bits=bits)
-            if shift:
-                c = dataclasses.replace(c, r=c.r + 1)          # bytes of the extra column of V and T
+                            act_bits=bits, asym=asym)
+            if shift or asym:
+                c = dataclasses.replace(c, r=c.r + int(shift) + 2 * int(asym))   # bytes of the extra columns of V and T
             b = r["stream"]
             if "graph" in r and "us_per_layer" in r["graph"] and r["graph"]["us_per_layer"] < b["us_per_layer"]:
                 b = r["graph"]

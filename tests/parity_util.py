@@ -178,3 +178,95 @@ def run_case(cfg: syn.LayerConfig, rows=None, centered: bool = False, act_bits: 
     # criterion 3: end to end
     out["end_to_end"] = check_output(Y[sel_t].cpu().numpy(), ref["Y"])
     return out
+
+
+def run_case_asym(cfg: syn.LayerConfig, centered: bool = False, act_bits: int = 6) -> dict:
+    """The path with per-token asymmetric activation codes (layer packed with BWLA_MODE_ASYM_ACT),
+    all M tokens against the oracle's forward_asym.  The GPU stores q - 2^(b-1) and carries the
+    zero point as two extra columns of T and V; what is compared is the zero point (equal, or off
+    by one where its pre-rounding value is within the window of a half), the codes (identical up
+    to the same window; shifted along with a zero point that moved), the raw accumulators on the
+    stored codes (exact), and the output."""
+    half, Lv = 1 << (act_bits - 1), (1 << act_bits) - 1
+    win = 1e-4 * Lv / 63
+    d = syn.make_layer(cfg)
+    W = syn.shifted_weights(d) if centered else d.W
+    U = d.U if cfg.r > 0 else None
+    V = d.V if cfg.r > 0 else None
+    ref = orc.forward_asym(d.X, d.R1, d.R2, W, U, V, centered=centered, act_bits=act_bits)
+    sgn, alpha16 = ref["sgn"], ref["alpha16"]
+    ru, rt = cfg.r, cfg.r + 2 + int(centered)
+
+    U_t = to_dev(d.U) if cfg.r > 0 else None
+    V_t = to_dev(d.V) if cfg.r > 0 else None
+    layer = B.pack_weights(to_dev(W), to_dev(d.R1), to_dev(d.R2), U_t, V_t, cfg.n1, cfg.n2, centered=centered, asym=True)
+    torch.cuda.synchronize()
+    assert layer.desc.r == rt and layer.desc.mode == 2 + int(centered)
+    sgn_gpu, alpha_gpu = B.unpack_signs(layer)
+    assert torch.equal(sgn_gpu.cpu(), torch.from_numpy(sgn)), "sign bits differ"
+    assert np.array_equal(alpha_gpu.cpu().numpy().astype(np.float64), alpha16), "alpha differs"
+    rp = (rt + 15) // 16 * 16
+    v16 = layer.blob[layer.desc.off_V:layer.desc.off_V + cfg.N * rp * 2].view(torch.float16).reshape(cfg.N, rp)
+    v16 = v16.cpu().numpy().astype(np.float64)
+    want = alpha16 * sgn.astype(np.int64).sum(axis=1)                    # delta (as stored) times rowsum
+    assert np.allclose(v16[:, ru] + v16[:, ru + 1], want, rtol=2.0 ** -20, atol=1e-12), "stored rowsum terms differ"
+    if centered:
+        assert np.array_equal(v16[:, rt - 1], orc.to_fp16(ref["mu"])), "stored row shifts differ"
+
+    X = x_on_gpu(d)
+    act = B.Activations(layer, cfg.M)
+    B.rotate_quant(layer, X, act, act_bits)
+    Y = torch.empty((cfg.M, cfg.N), dtype=torch.float32, device=DEV)
+    acc = torch.empty((cfg.M, cfg.N), dtype=torch.int32, device=DEV)
+    B.linear_forward(layer, act, Y, acc)
+    torch.cuda.synchronize()
+
+    q_gpu = act.q.cpu().numpy().astype(np.int64)
+    s_gpu = act.scale.cpu().numpy().astype(np.float64)
+    T_gpu = act.T.cpu().numpy().astype(np.float64)
+    assert q_gpu.min() >= -half and q_gpu.max() <= Lv - half
+    assert np.allclose(s_gpu, ref["s"], rtol=2e-6, atol=0), "per-token steps differ"
+    assert np.array_equal(T_gpu[:, ru], T_gpu[:, ru + 1])
+    zc_gpu = np.rint(np.where(s_gpu > 0, -T_gpu[:, ru] / np.where(s_gpu > 0, s_gpu, 1.0), -half)).astype(np.int64)
+    assert np.allclose(T_gpu[:, ru], -(s_gpu.astype(np.float32) * zc_gpu.astype(np.float32)), rtol=1e-6, atol=1e-30)
+    zc_ref = ref["z"] - half
+    dz = zc_gpu - zc_ref
+    near_z = np.abs(np.abs(ref["u"] - np.floor(ref["u"])) - 0.5) < win
+    assert np.all((dz == 0) | (near_z & (np.abs(dz) <= 1))), "zero points differ away from a rounding boundary"
+    diff = q_gpu - (ref["q"].astype(np.int64) - half)
+    near = np.abs(np.abs(ref["v"] - np.floor(ref["v"])) - 0.5) < win
+    same = dz == 0
+    assert not np.any((diff[same] != 0) & ~near[same]), "codes differ away from a rounding boundary"
+    assert np.all(np.abs(diff[same]) <= 1)
+    assert np.all(np.abs(diff[~same] - dz[~same, None]) <= 1), "codes did not move with their zero point"
+    qsum_gpu = act.qsum.cpu().numpy().astype(np.int64)
+    assert np.array_equal(qsum_gpu, q_gpu.sum(axis=1))
+    if cfg.r > 0:
+        tden = np.maximum(np.max(np.abs(ref["T"]), axis=1, keepdims=True), 1e-30)
+        assert np.max(np.abs(T_gpu[:, :ru] - ref["T"]) / tden) < 2e-5, "PSP projection differs"
+    if centered:
+        own = s_gpu * (qsum_gpu - cfg.K * zc_gpu)
+        assert np.allclose(T_gpu[:, rt - 1], own, rtol=2e-6, atol=1e-6 * np.max(np.abs(own)) + 1e-30), "shift entries differ"
+    # the raw accumulators belong to the stored codes, exactly
+    assert np.array_equal(acc.cpu().numpy().astype(np.int64), orc.binary_gemm(q_gpu.astype(np.int8), sgn))
+
+    # the oracle's codes through the ABI: exact accumulators, output to rounding
+    act2 = B.Activations(layer, cfg.M)
+    qp = (ref["q"].astype(np.int64) - half).astype(np.int8)
+    act2.q.copy_(torch.from_numpy(qp))
+    act2.scale.copy_(torch.from_numpy(ref["s"].astype(np.float32)))
+    cols = [ref["T"], (-ref["s"] * zc_ref)[:, None], (-ref["s"] * zc_ref)[:, None]]
+    if centered:
+        cols.append((ref["s"] * ref["c"].sum(axis=1))[:, None])
+    act2.T.copy_(torch.from_numpy(np.concatenate(cols, axis=1).astype(np.float32)))
+    B.code_sums(act2.q, act2.qsum)
+    Y2 = torch.empty_like(Y)
+    acc2 = torch.empty_like(acc)
+    B.linear_forward(layer, act2, Y2, acc2)
+    torch.cuda.synchronize()
+    assert np.array_equal(acc2.cpu().numpy().astype(np.int64), orc.binary_gemm(qp, sgn)), "accumulators not bit-exact"
+    out = dict(cfg=cfg.name, zero_point_moved=int(np.count_nonzero(dz)), code_mismatch=int(np.count_nonzero(diff[same])))
+    out["same_codes"] = check_output(Y2.cpu().numpy(), ref["Y"])
+    assert out["same_codes"]["fro"] < 1e-5
+    out["end_to_end"] = check_output(Y.cpu().numpy(), ref["Y"])
+    return out

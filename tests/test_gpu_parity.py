@@ -128,6 +128,24 @@ def test_row_shift_with_eight_bit_codes():
     print(run_case(cfg, centered=True, act_bits=8), flush=True)
 
 
+@pytest.mark.parametrize("bits,centered,M,K,n1,n2,N,r,xd", [
+    (6, False, 16, 512, 16, 32, 512, 8, "f32"),      # fp32 activations (old rotation kernel)
+    (6, False, 1, 4096, 64, 64, 1000, 32, "bf16"),   # decode, one token
+    (6, True, 16, 5120, 64, 80, 640, 13, "bf16"),    # with the row shift: 13 + 2 + 1 = 16 columns
+    (6, True, 300, 1152, 36, 32, 200, 20, "bf16"),   # prefill kernels
+    (6, False, 2, 20000, 200, 100, 48, 4, "bf16"),   # split rotation
+    (6, True, 3, 16896, 176, 96, 80, 0, "bf16"),     # split rotation, shift, no PSP: the three mode columns only
+    (4, False, 40, 1024, 32, 32, 200, 16, "bf16"),   # A4
+    (7, True, 5, 2048, 32, 64, 333, 8, "bf16"),      # the widest the offset form allows
+])
+def test_asymmetric_activation_codes(bits, centered, M, K, n1, n2, N, r, xd):
+    """Layers packed with BWLA_MODE_ASYM_ACT (paper Sec. 4.1: per-token asymmetric activation
+    quantization; min-max affine reading) against the oracle's forward_asym."""
+    from parity_util import run_case_asym
+    cfg = syn.LayerConfig(f"asym{bits}_{M}_{K}_{N}_{r}", M, K, n1, n2, N, r, xd, max(1, K // 100), 20.0, seed=15)
+    print(run_case_asym(cfg, centered=centered, act_bits=bits), flush=True)
+
+
 def test_zero_token_gives_zero_codes_and_scale():
     from parity_util import pack_on_gpu, DEV
     from paper_2605_00422_amd import binding as B

@@ -142,3 +142,20 @@ def test_rotate_quant_bits_rejects_widths_outside_int8(lib):
     for bits in (2, 4, 6, 8):                           # accepted: the next check (the layer) reports
         assert lib.bwla_rotate_quant_bits(None, None, 1, bits, 1, None, None, None, None, None, 0, None) == \
             B.BWLA_ERR_NULL
+
+
+def test_packed_size_mode(lib):
+    """Mode bits add columns to V only: asymmetric activation codes two, the row shift one."""
+    N, K, n1, n2, r = 1024, 512, 16, 32, 13
+    pad16 = lambda n: (n + 15) // 16 * 16
+    base = B.packed_size(N, K, n1, n2, r)
+    out = c_size_t()
+    for mode, extra in ((0, 0), (1, 1), (2, 2), (3, 3)):
+        assert lib.bwla_packed_size_mode(N, K, n1, n2, r, mode, byref(out)) == B.BWLA_OK
+        grow = 2 * N * (pad16(r + extra) - pad16(r))
+        assert grow <= out.value - base <= grow + 2 * 256
+    assert lib.bwla_packed_size_mode(N, K, n1, n2, r, 4, byref(out)) == B.BWLA_ERR_UNSUPPORTED
+    assert lib.bwla_packed_size_mode(N, K, n1, n2, 126, 3, byref(out)) == B.BWLA_ERR_UNSUPPORTED    # 126 + 3 > 128
+    assert lib.bwla_packed_size_mode(N, K, n1, n2, 125, 3, byref(out)) == B.BWLA_OK
+    assert B.packed_size(N, K, n1, n2, r, centered=True, asym=True) == \
+        (lib.bwla_packed_size_mode(N, K, n1, n2, r, 3, byref(out)), out.value)[1]
