@@ -43,14 +43,13 @@ __device__ long long bwla_rq_trace_buf[16 * 8 * 16];
 //                z = rint(-lo / scale); the code q = rint(x / scale) + z in [0, L] is stored as
 //                q - (qmax + 1), so zc = z - (qmax + 1) is what the stored code has to lose
 struct QuantPlan {
-    float inv, zc, cmin, cmax, scale;
+    float inv, zc, cmin, cmax;
 };
 __device__ __forceinline__ QuantPlan quant_plan(float hi, float lo, float qmax, bool asym) {
     QuantPlan p;
     if (asym) {
         const float L = 2.0f * qmax + 1.0f, span = hi - lo;
         p.inv = span > 0.0f ? L / span : 0.0f;
-        p.scale = span / L;
         p.zc = rintf(-lo * p.inv) - (qmax + 1.0f);
         if (!(span > 0.0f)) p.zc = -(qmax + 1.0f);      // all-zero token: q = z = 0
         p.cmin = -(qmax + 1.0f);
@@ -58,12 +57,15 @@ __device__ __forceinline__ QuantPlan quant_plan(float hi, float lo, float qmax, 
     } else {
         const float amax = fmaxf(hi, -lo);
         p.inv = amax > 0.0f ? qmax / amax : 0.0f;
-        p.scale = amax / qmax;
         p.zc = 0.0f;
         p.cmin = -qmax;
         p.cmax = qmax;
     }
     return p;
+}
+// the token's step (only the thread that writes it out needs it)
+__device__ __forceinline__ float quant_scale(float hi, float lo, float qmax, bool asym) {
+    return asym ? (hi - lo) / (2.0f * qmax + 1.0f) : fmaxf(hi, -lo) / qmax;
 }
 __device__ __forceinline__ int quant_code(float x, const QuantPlan& p) {
     return (int)fminf(fmaxf(rintf(x * p.inv) + p.zc, p.cmin), p.cmax);
@@ -71,12 +73,12 @@ __device__ __forceinline__ int quant_code(float x, const QuantPlan& p) {
 // The entries of T that the layer's mode adds for token t (tmode points at the first of them in
 // row 0, or is NULL): asymmetric codes: -scale * zc, twice; row shift: scale * sum_k (q - z).
 __device__ __forceinline__ void quant_extras(float* tmode, int tp, int64_t t, bool asym, bool shift,
-                                             const QuantPlan& p, int tot, int64_t K) {
+                                             const QuantPlan& p, float scale, int tot, int64_t K) {
     if (!tmode) return;
     float* row = tmode + t * tp;
     int c = 0;
-    if (asym) { row[0] = row[1] = -(p.scale * p.zc); c = 2; }
-    if (shift) row[c] = p.scale * ((float)tot - (float)K * p.zc);
+    if (asym) { row[0] = row[1] = -(scale * p.zc); c = 2; }
+    if (shift) row[c] = scale * ((float)tot - (float)K * p.zc);
 }
 
 constexpr int RQ_THREADS = 512;
@@ -518,8 +520,9 @@ __device__ __forceinline__ void rotate_token(float* lds, const void* __restrict_
 #pragma unroll
         for (int w = 0; w < RQ_WAVES; ++w) tot += redi[w];
         qsum[t] = tot;
-        scale[t] = qp.scale;
-        quant_extras(tmode, tp, t, asym, shift, qp, tot, K);
+        const float sc = quant_scale(hi, lo, qmax, asym);
+        scale[t] = sc;
+        quant_extras(tmode, tp, t, asym, shift, qp, sc, tot, K);
     }
     RQTRACE(8);
     RQTRACE_FLUSH;
@@ -893,19 +896,36 @@ __device__ __forceinline__ void rotate3_token(char* lds, const uint16_t* __restr
 
     RQTRACE(4);
     // ---- per-token max magnitude (padded rows and columns are exact zeros)
+    // (symmetric codes need the largest magnitude only: one reduction, stored as hi = -lo)
     float mx = 0.0f, mn = 0.0f;
+    if (asym) {
 #pragma unroll
-    for (int tc = 0; tc < ATM; ++tc)
-        if (tc < sh.at) {
+        for (int tc = 0; tc < ATM; ++tc)
+            if (tc < sh.at) {
 #pragma unroll
-            for (int v = 0; v < 4; ++v) { mx = fmaxf(mx, y[tc][v]); mn = fminf(mn, y[tc][v]); }
-        }
-    mx = bwla_wave_max(mx);
-    mn = -bwla_wave_max(-mn);
+                for (int v = 0; v < 4; ++v) { mx = fmaxf(mx, y[tc][v]); mn = fminf(mn, y[tc][v]); }
+            }
+        mx = bwla_wave_max(mx);
+        mn = -bwla_wave_max(-mn);
+    } else {
+#pragma unroll
+        for (int tc = 0; tc < ATM; ++tc)
+            if (tc < sh.at) {
+#pragma unroll
+                for (int v = 0; v < 4; ++v) mx = fmaxf(mx, fabsf(y[tc][v]));
+            }
+        mx = bwla_wave_max(mx);
+        mn = -mx;
+    }
     if (lane == 0) { red[wave] = mx; red[32 + wave] = mn; }
     __syncthreads();                                   // also: every wave is done with the token rows
-    float hi = red[0], lo = red[32];
-    for (int w = 1; w < sh.strips; ++w) { hi = fmaxf(hi, red[w]); lo = fminf(lo, red[32 + w]); }
+    float hi = red[0];
+    for (int w = 1; w < sh.strips; ++w) hi = fmaxf(hi, red[w]);
+    float lo = -hi;
+    if (asym) {
+        lo = red[32];
+        for (int w = 1; w < sh.strips; ++w) lo = fminf(lo, red[32 + w]);
+    }
     const QuantPlan qp = quant_plan(hi, lo, qmax, asym);
     RQTRACE(5);
 
@@ -953,8 +973,9 @@ __device__ __forceinline__ void rotate3_token(char* lds, const uint16_t* __restr
             int tot = 0;
             for (int w = 0; w < sh.strips; ++w) tot += redi[w];
             qsum[t] = tot;
-            scale[t] = qp.scale;
-            quant_extras(tmode, tp, t, asym, shift, qp, tot, K);
+            const float sc = quant_scale(hi, lo, qmax, asym);
+            scale[t] = sc;
+            quant_extras(tmode, tp, t, asym, shift, qp, sc, tot, K);
         }
     }
     RQTRACE(6);
@@ -1233,9 +1254,10 @@ __global__ __launch_bounds__(512) void quantize_rows_kernel(const float* __restr
         for (int w = 0; w < 8; ++w) tot += redi[w];
         atomicAdd(qsum + t, tot);
         if (part == 0) {
-            scale[t] = qp.scale;
+            const float sc = quant_scale(hi, lo, qmax, asym != 0);
+            scale[t] = sc;
             zcs[t] = qp.zc;
-            if (asym && tmode) tmode[t * tp] = tmode[t * tp + 1] = -(qp.scale * qp.zc);
+            if (asym && tmode) tmode[t * tp] = tmode[t * tp + 1] = -(sc * qp.zc);
         }
     }
 }
