@@ -180,3 +180,58 @@ def test_repeated_calls_are_deterministic():
         outs.append((Y.clone(), act.T.clone(), act.q.clone()))
     for o in outs[1:]:
         assert all(torch.equal(a, b) for a, b in zip(o, outs[0]))
+
+
+@pytest.mark.parametrize("name,M,K,n1,n2,N,r,one_call", [
+    ("decode", 1, 4096, 64, 64, 1024, 32, False),          # two launches per layer (the bench's default workload shape)
+    ("single_launch", 1, 4096, 64, 64, 1024, 0, True),     # bwla_decode_forward's single-launch kernel
+    ("batch16", 16, 5120, 64, 80, 640, 64, False),         # projection with ten slices and its arrival counters
+    ("split_rotation", 2, 20000, 200, 100, 48, 4, False),  # three launches; integer atomics on qsum
+    ("prefill", 300, 1152, 36, 32, 200, 20, False),        # separate projection kernel, streaming GEMM
+])
+def test_hip_graph_replays_match_eager(name, M, K, n1, n2, N, r, one_call):
+    """The benchmark times HIP graphs: a captured layer forward, replayed several times with other
+    activations in the same buffers and with eager work and synchronizations in between, gives
+    the eager results bit for bit on every replay."""
+    from parity_util import pack_on_gpu, x_on_gpu, DEV
+    from paper_2605_00422_amd import binding as B
+    cfg = syn.LayerConfig(f"graph_{name}", M, K, n1, n2, N, r, "bf16", max(1, K // 100), 20.0, seed=16)
+    d = syn.make_layer(cfg)
+    layer = pack_on_gpu(d)
+    X1 = x_on_gpu(d)
+    X2 = (X1.float() * 0.75 + torch.roll(X1.float(), 3, dims=1)).to(X1.dtype)
+
+    def forward(X, act, Y):
+        if one_call:
+            B.decode_forward(layer, X, act, Y)
+        else:
+            B.rotate_quant(layer, X, act)
+            B.linear_forward(layer, act, Y)
+
+    eager = {}
+    for key, X in (("x1", X1), ("x2", X2)):
+        act = B.Activations(layer, M)
+        Y = torch.empty((M, N), dtype=torch.float32, device=DEV)
+        forward(X, act, Y)
+        torch.cuda.synchronize()
+        eager[key] = (Y.clone(), act.q.clone(), act.scale.clone(), act.qsum.clone())
+
+    Xg = X1.clone()
+    actg = B.Activations(layer, M)
+    Yg = torch.empty((M, N), dtype=torch.float32, device=DEV)
+    forward(Xg, actg, Yg)                                   # warm-up outside the capture
+    torch.cuda.synchronize()
+    g = torch.cuda.CUDAGraph()
+    s = torch.cuda.Stream()
+    with torch.cuda.stream(s):
+        with torch.cuda.graph(g, stream=s):
+            forward(Xg, actg, Yg)
+    torch.cuda.synchronize()
+    for rep, key in enumerate(("x2", "x1", "x2", "x2")):
+        Xg.copy_(X2 if key == "x2" else X1)                 # eager work between the replays
+        Yg.fill_(float("nan"))
+        torch.cuda.synchronize()
+        g.replay()
+        torch.cuda.synchronize()
+        got = (Yg, actg.q, actg.scale, actg.qsum)
+        assert all(torch.equal(a, b) for a, b in zip(got, eager[key])), f"replay {rep} ({key}) differs from eager"
