@@ -67,7 +67,7 @@ hipError_t bwla_launch_gemm_decode_bs_cfg(const bwla_layer_t* L, const int8_t* d
     const int JT = (L->r + 15) >> 4, rp = JT * 16;
     const int units = (row_tiles + nt - 1) / nt;
     if (grid > units) grid = units;
-    const int jtt = JT == 0 ? 0 : JT == 1 ? 1 : JT == 2 ? 2 : JT <= 4 ? 4 : 8;
+    const int jtt = JT <= 3 ? JT : JT <= 4 ? 4 : 8;    // (3: ranks 33..48, e.g. rank 32 plus the columns a layer mode adds)
     const size_t lds = bs_lds_bytes(M, chunks, rp, nt);
     BsArgs a{(const uint4*)(blob + L->off_bits), chunks, row_tiles, dq, (int)M, (int)L->K, dscale, dqsum,
              (const __half*)(blob + L->off_alpha), (const __half*)(blob + L->off_V), dT, L->r, dY, (int)L->N,
@@ -85,7 +85,7 @@ hipError_t bwla_launch_gemm_decode_bs_cfg(const bwla_layer_t* L, const int8_t* d
         return fast ? launch(gemm_decode_bs_kernel<BS_CPW, D, T, J, true>)                                 \
                     : launch(gemm_decode_bs_kernel<BS_CPW, D, T, J, false>);
 #define BS_CASES(J) BS_CASE(2, 1, J) BS_CASE(4, 1, J) BS_CASE(2, 2, J) BS_CASE(4, 2, J)
-    BS_CASES(0) BS_CASES(1) BS_CASES(2) BS_CASES(4) BS_CASES(8)
+    BS_CASES(0) BS_CASES(1) BS_CASES(2) BS_CASES(3) BS_CASES(4) BS_CASES(8)
 #undef BS_CASES
 #undef BS_CASE
     return hipErrorInvalidValue;
