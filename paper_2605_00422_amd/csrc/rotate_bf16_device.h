@@ -249,6 +249,32 @@ __device__ __forceinline__ void rotate3_token(char* lds, const uint16_t* __restr
                     }
                 }
             }
+        } else if ((n2 & 1) == 0) {
+            // rows start on 4-byte boundaries only: four 4-byte loads per item, eight items in flight
+            const uint32_t* x32 = reinterpret_cast<const uint32_t*>(xrow);
+            for (int base = 0; base < items; base += 8 * nthreads) {
+                uint32_t tmp[8][4];
+#pragma unroll
+                for (int e = 0; e < 8; ++e) {
+                    const int it = base + e * nthreads + tid;
+                    const int a = dpr.div(it), b0 = (it - a * per_row) << 3;
+#pragma unroll
+                    for (int p = 0; p < 4; ++p) {
+                        const bool in = it < items && a < n1 && b0 + 2 * p < n2;
+                        const uint32_t v = x32[in ? ((a * n2 + b0) >> 1) + p : 0];
+                        tmp[e][p] = in ? v : 0u;
+                    }
+                }
+#pragma unroll
+                for (int e = 0; e < 8; ++e) {
+                    const int it = base + e * nthreads + tid;
+                    if (it < items) {
+                        const int a = dpr.div(it), b0 = (it - a * per_row) << 3;
+                        *reinterpret_cast<v4i*>(vt + a * sh.vpitch + b0 * 2) =
+                            v4i{(int)tmp[e][0], (int)tmp[e][1], (int)tmp[e][2], (int)tmp[e][3]};
+                    }
+                }
+            }
         } else {
             for (int it = tid; it < items; it += nthreads) {
                 const int a = dpr.div(it), b0 = (it - a * per_row) << 3;

@@ -1,14 +1,16 @@
-// Rotation of a token split over several workgroups (few tokens, R1 too large for LDS), the
-// launch that quantizes afterwards, and where the in-workgroup rotation leaves its results.
+// Rotation of a token split over several workgroups (few tokens and a large n1: R1 too large for
+// LDS, or a long stage 2), the launch that quantizes afterwards, and where the in-workgroup
+// rotation leaves its results.
 #pragma once
 #include "rotate_bf16_device.h"
 #include "gemm_decode_bs_device.h"
 
 namespace {
 
-// ================================================================== few tokens, factors too large for LDS
-// One workgroup per token has to stream all of the R1 terms through one CU, chunk by chunk, with
-// a memory round trip per chunk.  With only a few tokens most of the chip is idle meanwhile, so
+// ================================================================== few tokens, many tiles along n1
+// One workgroup per token has to do all of stage 2 on one CU's four MFMA pipes, and, when R1 does
+// not fit LDS, to stream all of its terms through that CU, chunk by chunk, with a memory round
+// trip per chunk.  With only a few tokens most of the chip is idle meanwhile, so
 // the rotation of a token is split over G workgroups: each does stage 1 for the whole token (it
 // is cheap) and stage 2 for RS_CT tiles along n1, for which its slice of the R1 terms fits LDS
 // whole and is requested at once.  The token's maximum is then not known inside the launch:
@@ -101,6 +103,33 @@ __device__ __forceinline__ void rotate_split_block(char* lds, const uint16_t* __
                     if (it < items) {
                         const int a = dpr.div(it), b0 = (it - a * per_row) << 3;
                         *reinterpret_cast<v4i*>(vt + a * sh.vpitch + b0 * 2) = tmp[e];
+                    }
+                }
+            }
+        } else if ((n2 & 1) == 0) {
+            // rows start on 4-byte boundaries only: four 4-byte loads per item, eight items in flight
+            const uint32_t* x32 = reinterpret_cast<const uint32_t*>(xrow);
+            for (int base = 0; base < items; base += 8 * nthreads) {
+                uint32_t tmp[8][4];
+#pragma unroll
+                for (int e = 0; e < 8; ++e) {
+                    const int it = base + e * nthreads + tid;
+                    const int a = dpr.div(it), b0 = (it - a * per_row) << 3;
+#pragma unroll
+                    for (int p = 0; p < 4; ++p) {
+                        const bool in = it < items && a < n1 && b0 + 2 * p < n2;
+                        const uint32_t v = x32[in ? ((a * n2 + b0) >> 1) + p : 0];
+                        tmp[e][p] = in ? v : 0u;
+                    }
+                }
+                if (base == 0) slice_issue();          // behind the first token loads
+#pragma unroll
+                for (int e = 0; e < 8; ++e) {
+                    const int it = base + e * nthreads + tid;
+                    if (it < items) {
+                        const int a = dpr.div(it), b0 = (it - a * per_row) << 3;
+                        *reinterpret_cast<v4i*>(vt + a * sh.vpitch + b0 * 2) =
+                            v4i{(int)tmp[e][0], (int)tmp[e][1], (int)tmp[e][2], (int)tmp[e][3]};
                     }
                 }
             }
