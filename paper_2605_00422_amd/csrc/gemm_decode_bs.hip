@@ -28,7 +28,8 @@ namespace {
 // NT: 16-row tiles per step.  JTT: compile-time number of 16-wide rank groups (>= ceil(r/16)).
 // FAST: N % 4 == 0 and no accumulator dump, which allows float4 stores.
 template <int CPW, int DEPTH, int NT, int JTT, bool FAST>
-__global__ __launch_bounds__(BS_MAX_THREADS) void gemm_decode_bs_kernel(BsArgs a) {
+__global__ __launch_bounds__(CPW == BS_CPW ? BS_MAX_THREADS : 64 * (BS_MAXKS_LONG + 1)) void gemm_decode_bs_kernel(
+    BsArgs a) {
     extern __shared__ __align__(16) char smem[];
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int stride = gridDim.x, first = blockIdx.x;
@@ -52,7 +53,7 @@ extern "C" int bwla_trace_dump(long long* host, int n) {
 
 bool bwla_gemm_decode_bs_supported(int64_t M, int64_t K, int r) {
     const int chunks = (int)bwla_chunks(K);
-    return M <= 16 && chunks >= 2 && bs_fits(M, chunks, r, 1);
+    return M <= 16 && chunks >= 2 && bs_fits(M, chunks, r, 1, bs_cpw_for(chunks));
 }
 
 // explicit launch shape: nt tiles per step (1 or 2), grid size, prefetch depth (2 or 4)
@@ -61,9 +62,10 @@ hipError_t bwla_launch_gemm_decode_bs_cfg(const bwla_layer_t* L, const int8_t* d
                                           int32_t* dacc, hipStream_t st, int nt, int grid, int depth) {
     const char* blob = (const char*)L->d_blob;
     const int chunks = (int)bwla_chunks(L->K), row_tiles = (int)bwla_row_tiles(L->N);
-    if ((nt != 1 && nt != 2) || grid < 1 || chunks < 2 || M > 16 || !bs_fits(M, chunks, L->r, nt))
+    const int cpw = bs_cpw_for(chunks);
+    if ((nt != 1 && nt != 2) || grid < 1 || chunks < 2 || M > 16 || !bs_fits(M, chunks, L->r, nt, cpw))
         return hipErrorInvalidValue;
-    const int KS = (chunks + BS_CPW - 1) / BS_CPW;
+    const int KS = (chunks + cpw - 1) / cpw;
     const int JT = (L->r + 15) >> 4, rp = JT * 16;
     const int units = (row_tiles + nt - 1) / nt;
     if (grid > units) grid = units;
@@ -80,6 +82,14 @@ hipError_t bwla_launch_gemm_decode_bs_cfg(const bwla_layer_t* L, const int8_t* d
         return hipGetLastError();
     };
     const bool fast = (L->N % 4 == 0) && dacc == nullptr;
+    // long rows: one launch shape (depth 2, one tile per step)
+#define BS_LONG(J)                                                                                         \
+    if (cpw == BS_CPW_LONG && jtt == J)                                                                    \
+        return fast ? launch(gemm_decode_bs_kernel<BS_CPW_LONG, 2, 1, J, true>)                            \
+                    : launch(gemm_decode_bs_kernel<BS_CPW_LONG, 2, 1, J, false>);
+    if (cpw == BS_CPW_LONG && nt != 1) return hipErrorInvalidValue;
+    BS_LONG(0) BS_LONG(1) BS_LONG(2) BS_LONG(3) BS_LONG(4) BS_LONG(8)
+#undef BS_LONG
 #define BS_CASE(D, T, J)                                                                                   \
     if (depth == D && nt == T && jtt == J)                                                                 \
         return fast ? launch(gemm_decode_bs_kernel<BS_CPW, D, T, J, true>)                                 \

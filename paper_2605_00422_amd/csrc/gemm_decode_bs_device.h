@@ -373,6 +373,16 @@ __device__ __forceinline__ void epilogue_wave(const BsArgs& a, char* smem, int f
 }
 
 constexpr int BS_CPW = 2;   // two chunks per compute wave amortize the class recombination
+// Longer rows (K up to 7 * 4 * 512 = 14336, e.g. the 7B down projection): four chunks per compute
+// wave, whose 32 operand registers per chunk then need the 256-register budget of a workgroup of
+// at most eight wavefronts (seven compute waves + the epilogue wave).
+constexpr int BS_CPW_LONG = 4;
+constexpr int BS_MAXKS_LONG = 7;
+inline int bs_cpw_for(int chunks) {
+    if ((chunks + BS_CPW - 1) / BS_CPW <= BS_MAXKS) return BS_CPW;
+    if ((chunks + BS_CPW_LONG - 1) / BS_CPW_LONG <= BS_MAXKS_LONG) return BS_CPW_LONG;
+    return 0;
+}
 
 inline size_t bs_lds_bytes(int64_t M, int chunks, int rp, int nt) {
     return (size_t)red_bytes(nt) + 2 * (size_t)side_bytes(rp, nt) +
@@ -380,10 +390,12 @@ inline size_t bs_lds_bytes(int64_t M, int chunks, int rp, int nt) {
 }
 
 // one compute wave per side piece (the unit's V rows in 1 KiB pieces + its scales), LDS fits
-inline bool bs_fits(int64_t M, int chunks, int r, int nt) {
-    const int KS = (chunks + BS_CPW - 1) / BS_CPW;
+inline bool bs_fits(int64_t M, int chunks, int r, int nt, int cpw = BS_CPW) {
+    if (cpw == 0) return false;
+    const int KS = (chunks + cpw - 1) / cpw;
     const int rp = ((r + 15) >> 4) * 16;
-    return KS <= BS_MAXKS && KS >= ((nt * rp + 31) >> 5) + 1 && bs_lds_bytes(M, chunks, rp, nt) <= 160 * 1024;
+    return KS <= (cpw == BS_CPW ? BS_MAXKS : BS_MAXKS_LONG) && KS >= ((nt * rp + 31) >> 5) + 1 &&
+           bs_lds_bytes(M, chunks, rp, nt) <= 160 * 1024;
 }
 
 }  // namespace

@@ -73,6 +73,10 @@ def test_cfg4_70b_gate_m4096_sampled_rows():
     (520, 640, 20, 32, 330, 0, "bf16"),    # streaming GEMM without a low-rank branch
     (40, 480, 20, 24, 70, 8, "bf16"),      # K not a multiple of 128: LDS-tiled GEMM, 64 x 128 tiles
     (150, 160, 16, 10, 24, 4, "f32"),      # fewer than 32 channels: LDS-tiled GEMM, 128 x 128 tiles
+    # rows longer than 8192 columns at decode: four chunks per compute wavefront
+    (1, 11008, 128, 86, 1000, 32, "bf16"),  # 7B down-projection shape: 22 chunks, six compute wavefronts
+    (8, 12288, 128, 96, 520, 0, "bf16"),    # 24 chunks, eight tokens, no low-rank part
+    (2, 14336, 128, 112, 200, 48, "bf16"),  # the longest row this variant takes: 28 chunks, seven compute wavefronts
     # one token without low-rank part: bwla_decode_forward runs its single-launch kernel
     (1, 4096, 64, 64, 4096, 0, "bf16"),    # 7B attention projection shape, one channel tile per workgroup
     (1, 4096, 64, 64, 11008, 0, "bf16"),   # 7B gate/up shape: up to three channel tiles per workgroup
