@@ -53,7 +53,7 @@ extern "C" int bwla_trace_dump(long long* host, int n) {
 
 bool bwla_gemm_decode_bs_supported(int64_t M, int64_t K, int r) {
     const int chunks = (int)bwla_chunks(K);
-    return M <= 16 && chunks >= 2 && bs_fits(M, chunks, r, 1, bs_cpw_for(chunks));
+    return M <= 16 && chunks >= 2 && bs_fits(0, chunks, r, 1, bs_cpw_for(chunks));
 }
 
 // explicit launch shape: nt tiles per step (1 or 2), grid size, prefetch depth (2 or 4)
@@ -63,17 +63,19 @@ hipError_t bwla_launch_gemm_decode_bs_cfg(const bwla_layer_t* L, const int8_t* d
     const char* blob = (const char*)L->d_blob;
     const int chunks = (int)bwla_chunks(L->K), row_tiles = (int)bwla_row_tiles(L->N);
     const int cpw = bs_cpw_for(chunks);
-    if ((nt != 1 && nt != 2) || grid < 1 || chunks < 2 || M > 16 || !bs_fits(M, chunks, L->r, nt, cpw))
+    if ((nt != 1 && nt != 2) || grid < 1 || chunks < 2 || M > 16 || !bs_fits(0, chunks, L->r, nt, cpw))
         return hipErrorInvalidValue;
+    // up to four tokens: code rows staged in LDS when they fit; else every wave loads its own
+    const int direct = (M > 4 || !bs_fits(M, chunks, L->r, nt, cpw)) ? 1 : 0;
     const int KS = (chunks + cpw - 1) / cpw;
     const int JT = (L->r + 15) >> 4, rp = JT * 16;
     const int units = (row_tiles + nt - 1) / nt;
     if (grid > units) grid = units;
     const int jtt = JT <= 3 ? JT : JT <= 4 ? 4 : 8;    // (3: ranks 33..48, e.g. rank 32 plus the columns a layer mode adds)
-    const size_t lds = bs_lds_bytes(M, chunks, rp, nt);
+    const size_t lds = bs_lds_bytes(direct ? 0 : M, chunks, rp, nt);
     BsArgs a{(const uint4*)(blob + L->off_bits), chunks, row_tiles, dq, (int)M, (int)L->K, dscale, dqsum,
              (const __half*)(blob + L->off_alpha), (const __half*)(blob + L->off_V), dT, L->r, dY, (int)L->N,
-             dacc, KS};
+             dacc, KS, direct};
     auto launch = [&](auto kern) -> hipError_t {
         static bwla_lds_attr attr;
         hipError_t e = attr.ensure((const void*)kern, lds);

@@ -27,6 +27,8 @@ struct BsArgs {
     const int8_t* q; int M, K;
     const float* scale; const int32_t* qsum; const __half* alpha; const __half* V; const float* T;
     int r; float* Y; int N; int32_t* acc_out; int KS;
+    int direct;      // stand-alone kernel: compute waves load their codes straight from global memory
+                     // (else the code rows are staged in LDS first)
 };
 
 // Fused single-launch decode (one token, r = 0): the workgroup has rotated and quantized the token
@@ -49,9 +51,9 @@ __device__ __forceinline__ void bs_local_stage_codes(const BsArgs& a, char* qt, 
 // the others belong to the copies, which may land at any time), and the partial-tile slots that
 // no compute wave writes (the epilogue wave is their only reader)
 template <int NT>
-__device__ __forceinline__ void bs_zero_fill(const BsArgs& a, char* qt, v4i* red, int lane) {
+__device__ __forceinline__ void bs_zero_fill(const BsArgs& a, char* qt, v4i* red, int lane, bool code_rows = true) {
     const int pitch = (a.chunks + 1) * BWLA_CHUNK_COLS;
-    const int rows = a.M < 16 ? a.M : 16;
+    const int rows = !code_rows ? 0 : (a.M < 16 ? a.M : 16);
     const int kgran = a.K >> 4;
     const int zbeg = (a.K / BWLA_CHUNK_COLS) * BWLA_CHUNK_COLS;
     for (int row = 0; row < rows; ++row)
@@ -173,20 +175,55 @@ __device__ __forceinline__ void compute_wave(const BsArgs& a, char* smem, int fi
         for (int i = 0; i < rotation_barriers; ++i) bwla_lds_barrier();
         TRACE(39);
         bs_local_stage_codes(a, qt, fl, wave, lane);
-    } else {
+        __builtin_amdgcn_s_waitcnt(0);                     // this wave's copies (and first units) landed
+        TRACE(1);
+        bwla_lds_barrier();
+    } else if (!a.direct) {
         stage_codes(a, qt, wave, lane);
+        __builtin_amdgcn_s_waitcnt(0);
+        TRACE(1);
+        bwla_lds_barrier();
     }
-    __builtin_amdgcn_s_waitcnt(0);                         // this wave's copies (and first units) landed
-    TRACE(1);
-    bwla_lds_barrier();
     v4i b[CPW][8];
+    if (FUSED || !a.direct) {
 #pragma unroll
-    for (int i = 0; i < CPW; ++i) {
-        const int c = wave + i * KS < chunks ? wave + i * KS : chunks;   // chunk `chunks` is a zero patch
+        for (int i = 0; i < CPW; ++i) {
+            const int c = wave + i * KS < chunks ? wave + i * KS : chunks;   // chunk `chunks` is a zero patch
 #pragma unroll
-        for (int j = 0; j < 8; ++j)
-            b[i][j] = *reinterpret_cast<const v4i*>(qt + brow * (Kp + BWLA_CHUNK_COLS) + c * BWLA_CHUNK_COLS +
-                                                    (((lg * 8 + j) ^ brow) << 4));
+            for (int j = 0; j < 8; ++j)
+                b[i][j] = *reinterpret_cast<const v4i*>(qt + brow * (Kp + BWLA_CHUNK_COLS) + c * BWLA_CHUNK_COLS +
+                                                        (((lg * 8 + j) ^ brow) << 4));
+        }
+    } else {
+        // Straight from global memory, once per workgroup: lane (li, lg) takes, for step j of a
+        // chunk, the 16 codes of token li at columns 128 lg + 16 j of the chunk (the column order
+        // of the packed bits).  Granules past K (the last chunk may be partial) and chunks this
+        // wave does not have are zero operands.  No LDS and no barrier are involved, so every
+        // token count up to 16 and every row length fit; with more than a few tokens it is also
+        // the faster way (16 tokens: 11.7 -> 9.7 us on the 32B up projection), with one token the
+        // address arithmetic of the 16 or 32 loads costs more than the staging (5.0 -> 5.1 us).
+        const int kgran = a.K >> 4;
+        const int8_t* qrow = a.q + (int64_t)brow * a.K;
+#pragma unroll
+        for (int i = 0; i < CPW; ++i)
+#pragma unroll
+            for (int j = 0; j < 8; ++j) b[i][j] = v4i{0, 0, 0, 0};
+        // (lanes of token columns past M stay out of the loads: their operands are never used,
+        // and an instruction costs the texture path as many cycles as it has active lanes)
+        if (li < a.M) {
+#pragma unroll
+            for (int i = 0; i < CPW; ++i) {
+                const int c = wave + i * KS;
+#pragma unroll
+                for (int j = 0; j < 8; ++j) {
+                    const int g = c * 32 + lg * 8 + j;
+                    const bool ok = c < chunks && g < kgran;
+                    const v4i v = *reinterpret_cast<const v4i*>(qrow + (ok ? g : 0) * 16);
+                    b[i][j] = ok ? v : v4i{0, 0, 0, 0};
+                }
+            }
+        }
+        TRACE(1);
     }
 #pragma unroll
     for (int i = 0; i < CPW; ++i)
@@ -289,11 +326,16 @@ __device__ __forceinline__ void epilogue_wave(const BsArgs& a, char* smem, int f
                 if (tok_ok && j < a.r) tv[uu][e] = a.T[(int64_t)t * a.r + j];
                 tmax = fmaxf(tmax, fabsf(tv[uu][e]));
             }
-        bs_zero_fill<NT>(a, qt, red, lane);
-        stage_codes(a, qt, wave, lane);
-        __builtin_amdgcn_s_waitcnt(0);                         // zeros written, this wave's copies landed
-        TRACE(1);
-        bwla_lds_barrier();
+        if (a.direct) {
+            bs_zero_fill<NT>(a, qt, red, lane, false);         // (the compute waves fetch their codes themselves)
+            TRACE(1);
+        } else {
+            bs_zero_fill<NT>(a, qt, red, lane);
+            stage_codes(a, qt, wave, lane);
+            __builtin_amdgcn_s_waitcnt(0);                     // zeros written, this wave's copies landed
+            TRACE(1);
+            bwla_lds_barrier();
+        }
     }
 
     // fp16 operands of T for the f16 MFMA: T * 2^k = hi + lo (both fp16, error 2^-22), with the
@@ -384,6 +426,7 @@ inline int bs_cpw_for(int chunks) {
     return 0;
 }
 
+// (M: token rows staged in LDS; 0 when the compute waves load their codes themselves)
 inline size_t bs_lds_bytes(int64_t M, int chunks, int rp, int nt) {
     return (size_t)red_bytes(nt) + 2 * (size_t)side_bytes(rp, nt) +
            (size_t)(M < 16 ? M : 16) * ((size_t)chunks + 1) * BWLA_CHUNK_COLS;
