@@ -251,6 +251,8 @@ def main():
     for M in (1, 64, 4096):
         for c in syn.block70b_configs(M):
             all_cfgs[c.name] = c
+    for c in syn.block7b_configs(1):
+        all_cfgs[c.name] = c
     cfg = all_cfgs[args.workload]
 
     if args.calibrate_copy:
@@ -294,8 +296,8 @@ def main():
 
     if not args.no_extra:
         extra = []
-        names = ["cfg2_qwen32b_up_m16", "cfg3_qwen32b_down_m2048", "cfg4_70b_gate_m1", "cfg4_70b_down_m1",
-                 "cfg4_70b_q_m64", "cfg4_70b_q_m4096"]
+        names = ["cfg1_7b_q_m1", "cfg1_7b_down_m1", "cfg2_qwen32b_up_m16", "cfg3_qwen32b_down_m2048",
+                 "cfg4_70b_gate_m1", "cfg4_70b_down_m1", "cfg4_70b_q_m64", "cfg4_70b_q_m4096"]
         # (name, layer binarized with the row shift: the shift term rides as one more low-rank column)
         # and 8-bit activation codes, the width of the paper's speed run: same kernels, same bytes)
         # and per-token asymmetric codes with the row shift, the paper's own setting: three more columns)

@@ -72,6 +72,17 @@ def block70b_configs(M: int) -> list[LayerConfig]:
     return out
 
 
+def block7b_configs(M: int) -> list[LayerConfig]:
+    """7B-shaped decoder block (the model of cfg1, whose layer is this block's gate/up projection):
+    hidden 4096, intermediate 11008; Kronecker pairs by Algorithm 1 (11008 = 128 x 86)."""
+    h, inter = 4096, 11008
+    out = []
+    for nm, K, N in (("q", h, h), ("gate", h, inter), ("down", inter, h)):
+        n1, n2 = _near_square(K)
+        out.append(LayerConfig(f"cfg1_7b_{nm}_m{M}", M, K, n1, n2, N, 32, "bf16", _pct(K, 0.01), 50.0))
+    return out
+
+
 def round_to_bf16(a: np.ndarray) -> np.ndarray:
     """Round fp32 values to the nearest bf16 (ties to even); result stays fp32."""
     u = np.ascontiguousarray(a, dtype=np.float32).view(np.uint32)
