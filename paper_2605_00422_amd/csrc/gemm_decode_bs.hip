@@ -27,7 +27,8 @@ namespace {
 
 // NT: 16-row tiles per step.  JTT: compile-time number of 16-wide rank groups (>= ceil(r/16)).
 // FAST: N % 4 == 0 and no accumulator dump, which allows float4 stores.
-template <int CPW, int DEPTH, int NT, int JTT, bool FAST>
+// MULTI: rows of more than one pass (long-row variant only).
+template <int CPW, int DEPTH, int NT, int JTT, bool FAST, bool MULTI = false>
 __global__ __launch_bounds__(CPW == BS_CPW ? BS_MAX_THREADS : 64 * (BS_MAXKS_LONG + 1)) void gemm_decode_bs_kernel(
     BsArgs a) {
     extern __shared__ __align__(16) char smem[];
@@ -37,9 +38,9 @@ __global__ __launch_bounds__(CPW == BS_CPW ? BS_MAX_THREADS : 64 * (BS_MAXKS_LON
     const int n_iter = (units - first + stride - 1) / stride;            // >= 1: grid <= units
     const int PV = (NT * (((a.r + 15) >> 4) * 16) + 31) >> 5;
     TRACE(0);
-    if (wave == a.KS) epilogue_wave<DEPTH, NT, JTT, FAST>(a, smem, first, stride, n_iter, wave, lane);
-    else if (wave <= PV) compute_wave<CPW, DEPTH, NT, true>(a, smem, first, stride, n_iter, wave, lane);
-    else compute_wave<CPW, DEPTH, NT, false>(a, smem, first, stride, n_iter, wave, lane);
+    if (wave == a.KS) epilogue_wave<DEPTH, NT, JTT, FAST, false, MULTI>(a, smem, first, stride, n_iter, wave, lane);
+    else if (wave <= PV) compute_wave<CPW, DEPTH, NT, true, false, MULTI>(a, smem, first, stride, n_iter, wave, lane);
+    else compute_wave<CPW, DEPTH, NT, false, false, MULTI>(a, smem, first, stride, n_iter, wave, lane);
 }
 
 
@@ -53,7 +54,8 @@ extern "C" int bwla_trace_dump(long long* host, int n) {
 
 bool bwla_gemm_decode_bs_supported(int64_t M, int64_t K, int r) {
     const int chunks = (int)bwla_chunks(K);
-    return M <= 16 && chunks >= 2 && bs_fits(0, chunks, r, 1, bs_cpw_for(chunks));
+    // (rows of more than one pass keep 1 KiB of sums per unit of a workgroup in LDS: at most 64 units)
+    return M <= 16 && chunks >= 2 && bs_fits(0, chunks, r, 1, bs_cpw_for(chunks), bs_passes_for(chunks) > 1 ? 64 : 0);
 }
 
 // explicit launch shape: nt tiles per step (1 or 2), grid size, prefetch depth (2 or 4)
@@ -62,20 +64,25 @@ hipError_t bwla_launch_gemm_decode_bs_cfg(const bwla_layer_t* L, const int8_t* d
                                           int32_t* dacc, hipStream_t st, int nt, int grid, int depth) {
     const char* blob = (const char*)L->d_blob;
     const int chunks = (int)bwla_chunks(L->K), row_tiles = (int)bwla_row_tiles(L->N);
-    const int cpw = bs_cpw_for(chunks);
-    if ((nt != 1 && nt != 2) || grid < 1 || chunks < 2 || M > 16 || !bs_fits(0, chunks, L->r, nt, cpw))
+    const int cpw = bs_cpw_for(chunks), passes = bs_passes_for(chunks);
+    const int units0 = (row_tiles + nt - 1) / nt;
+    if (grid > units0) grid = units0;
+    // with several passes the sums of earlier passes wait in LDS, 1 KiB per tile of the workgroup's units
+    const int pass_units = passes > 1 ? (units0 + grid - 1) / grid : 0;
+    if ((nt != 1 && nt != 2) || grid < 1 || chunks < 2 || M > 16 || pass_units > 64 ||
+        !bs_fits(0, chunks, L->r, nt, cpw, pass_units))
         return hipErrorInvalidValue;
     // up to four tokens: code rows staged in LDS when they fit; else every wave loads its own
-    const int direct = (M > 4 || !bs_fits(M, chunks, L->r, nt, cpw)) ? 1 : 0;
-    const int KS = (chunks + cpw - 1) / cpw;
+    const int direct = (M > 4 || !bs_fits(M, chunks, L->r, nt, cpw, pass_units)) ? 1 : 0;
+    const int KS = bs_ks_for(chunks);
     const int JT = (L->r + 15) >> 4, rp = JT * 16;
     const int units = (row_tiles + nt - 1) / nt;
     if (grid > units) grid = units;
     const int jtt = JT <= 3 ? JT : JT <= 4 ? 4 : 8;    // (3: ranks 33..48, e.g. rank 32 plus the columns a layer mode adds)
-    const size_t lds = bs_lds_bytes(direct ? 0 : M, chunks, rp, nt);
+    const size_t lds = bs_lds_bytes(direct ? 0 : M, chunks, rp, nt, pass_units);
     BsArgs a{(const uint4*)(blob + L->off_bits), chunks, row_tiles, dq, (int)M, (int)L->K, dscale, dqsum,
              (const __half*)(blob + L->off_alpha), (const __half*)(blob + L->off_V), dT, L->r, dY, (int)L->N,
-             dacc, KS, direct};
+             dacc, KS, direct, passes};
     auto launch = [&](auto kern) -> hipError_t {
         static bwla_lds_attr attr;
         hipError_t e = attr.ensure((const void*)kern, lds);
@@ -86,9 +93,12 @@ hipError_t bwla_launch_gemm_decode_bs_cfg(const bwla_layer_t* L, const int8_t* d
     const bool fast = (L->N % 4 == 0) && dacc == nullptr;
     // long rows: one launch shape (depth 2, one tile per step)
 #define BS_LONG(J)                                                                                         \
-    if (cpw == BS_CPW_LONG && jtt == J)                                                                    \
+    if (cpw == BS_CPW_LONG && jtt == J && passes == 1)                                                     \
         return fast ? launch(gemm_decode_bs_kernel<BS_CPW_LONG, 2, 1, J, true>)                            \
-                    : launch(gemm_decode_bs_kernel<BS_CPW_LONG, 2, 1, J, false>);
+                    : launch(gemm_decode_bs_kernel<BS_CPW_LONG, 2, 1, J, false>);                          \
+    if (cpw == BS_CPW_LONG && jtt == J)                                                                    \
+        return fast ? launch(gemm_decode_bs_kernel<BS_CPW_LONG, 2, 1, J, true, true>)                      \
+                    : launch(gemm_decode_bs_kernel<BS_CPW_LONG, 2, 1, J, false, true>);
     if (cpw == BS_CPW_LONG && nt != 1) return hipErrorInvalidValue;
     BS_LONG(0) BS_LONG(1) BS_LONG(2) BS_LONG(3) BS_LONG(4) BS_LONG(8)
 #undef BS_LONG

@@ -22,6 +22,13 @@ __device__ __forceinline__ int neg_bytes(int x) {
     return (int)(((nx & 0x7f7f7f7fu) + 0x01010101u) ^ (nx & 0x80808080u));
 }
 
+// n / d for small non-negative n (d >= 1)
+struct FastDivU {
+    uint32_t d, m;
+    __device__ explicit FastDivU(uint32_t dd) : d(dd), m(dd > 1 ? 0xFFFFFFFFu / dd + 1u : 0u) {}
+    __device__ __forceinline__ int div(int n) const { return d > 1 ? (int)__umulhi((uint32_t)n, m) : n; }
+};
+
 struct BsArgs {
     const uint4* bits; int chunks, row_tiles;
     const int8_t* q; int M, K;
@@ -29,6 +36,7 @@ struct BsArgs {
     int r; float* Y; int N; int32_t* acc_out; int KS;
     int direct;      // stand-alone kernel: compute waves load their codes straight from global memory
                      // (else the code rows are staged in LDS first)
+    int passes;      // rows longer than KS * CPW chunks are contracted in this many passes (else 1)
 };
 
 // Fused single-launch decode (one token, r = 0): the workgroup has rotated and quantized the token
@@ -98,7 +106,7 @@ __device__ __forceinline__ void stage_codes(const BsArgs& a, char* qt, int wave,
 }
 
 // ------------------------------------------------------------------ compute wave
-template <int CPW, int DEPTH, int NT, bool SIDE, bool FUSED = false>
+template <int CPW, int DEPTH, int NT, bool SIDE, bool FUSED = false, bool MULTI = false>
 __device__ __forceinline__ void compute_wave(const BsArgs& a, char* smem, int first, int stride, int n_iter,
                                              int wave, int lane, const FusedLocal& fl = FusedLocal{},
                                              int rotation_barriers = 0) {
@@ -108,24 +116,39 @@ __device__ __forceinline__ void compute_wave(const BsArgs& a, char* smem, int fi
     v4i* red = reinterpret_cast<v4i*>(smem);
     char* side = smem + red_bytes(NT);
     char* qt = side + 2 * side_bytes(rp, NT);
-    const int last_it = n_iter - 1;
+    // A row longer than KS * CPW chunks is contracted in several passes: step s of the loop is
+    // unit s % n_iter in pass s / n_iter (all units of a pass, then the next pass, whose operand
+    // codes are loaded when it begins); the weight prefetch runs on across the pass boundaries.
+    // (MULTI is a compile-time choice: the one-pass kernels keep their precomputed addresses)
+    const int H = MULTI ? a.passes : 1;
+    const int last_it = n_iter * H - 1;                   // last step
     const int last_tile = a.row_tiles - 1;
-
-    // Loads in the loop are unconditional (addresses clamped to valid tiles, chunks and rows).  A
-    // chunk past the end of K pairs with all-zero activation operands; a unit past this
-    // workgroup's last one is fetched again and dropped.
+    const FastDivU dni((uint32_t)n_iter);
     const uint4* wp[CPW];
 #pragma unroll
     for (int i = 0; i < CPW; ++i) {
         const int c = wave + i * KS;
         wp[i] = a.bits + (c < chunks ? c : 0) * 64 + lane;
     }
+
+    // Loads in the loop are unconditional (addresses clamped to valid tiles, chunks and rows).  A
+    // chunk past the end of K pairs with all-zero activation operands; a step past this
+    // workgroup's last one is fetched again and dropped.
     auto w_load = [&](int it_ahead, int nt, int i) -> v4i {
-        const int ia = it_ahead < last_it ? it_ahead : last_it;
-        int tile = (first + ia * stride) * NT + nt;
-        tile = tile < last_tile ? tile : last_tile;
-        const uint4 x = wp[i][(int64_t)tile * chunks * 64];
-        return v4i{(int)x.x, (int)x.y, (int)x.z, (int)x.w};
+        const int sa = it_ahead < last_it ? it_ahead : last_it;
+        if constexpr (MULTI) {
+            const int hp = dni.div(sa), ia = sa - hp * n_iter;
+            const int c = hp * KS * CPW + wave + i * KS;
+            int tile = (first + ia * stride) * NT + nt;
+            tile = tile < last_tile ? tile : last_tile;
+            const uint4 x = a.bits[((int64_t)tile * chunks + (c < chunks ? c : 0)) * 64 + lane];
+            return v4i{(int)x.x, (int)x.y, (int)x.z, (int)x.w};
+        } else {
+            int tile = (first + sa * stride) * NT + nt;
+            tile = tile < last_tile ? tile : last_tile;
+            const uint4 x = wp[i][(int64_t)tile * chunks * 64];
+            return v4i{(int)x.x, (int)x.y, (int)x.z, (int)x.w};
+        }
     };
     // side piece of this wave: piece p < PV is 1 KiB of the unit's V rows, piece PV its scales
     const int PV = (NT * rp + 31) >> 5;
@@ -135,7 +158,8 @@ __device__ __forceinline__ void compute_wave(const BsArgs& a, char* smem, int fi
     const bool side_ok = is_alpha ? lane < 2 * NT : vr < 16 * NT;
     const int side_dst = is_alpha ? NT * 16 * side_pitch(rp) * 2 + lane * 16 : (vr * side_pitch(rp) + vc) * 2;
     auto s_load = [&](int it_ahead) -> v4i {
-        const int ia = it_ahead < last_it ? it_ahead : last_it;
+        const int sa = it_ahead < last_it ? it_ahead : last_it;
+        const int ia = MULTI ? sa - dni.div(sa) * n_iter : sa;
         const int n0 = (first + ia * stride) * NT * 16;
         const __half* src;
         if (is_alpha) {
@@ -185,56 +209,66 @@ __device__ __forceinline__ void compute_wave(const BsArgs& a, char* smem, int fi
         bwla_lds_barrier();
     }
     v4i b[CPW][8];
-    if (FUSED || !a.direct) {
-#pragma unroll
-        for (int i = 0; i < CPW; ++i) {
-            const int c = wave + i * KS < chunks ? wave + i * KS : chunks;   // chunk `chunks` is a zero patch
-#pragma unroll
-            for (int j = 0; j < 8; ++j)
-                b[i][j] = *reinterpret_cast<const v4i*>(qt + brow * (Kp + BWLA_CHUNK_COLS) + c * BWLA_CHUNK_COLS +
-                                                        (((lg * 8 + j) ^ brow) << 4));
-        }
-    } else {
-        // Straight from global memory, once per workgroup: lane (li, lg) takes, for step j of a
-        // chunk, the 16 codes of token li at columns 128 lg + 16 j of the chunk (the column order
-        // of the packed bits).  Granules past K (the last chunk may be partial) and chunks this
-        // wave does not have are zero operands.  No LDS and no barrier are involved, so every
-        // token count up to 16 and every row length fit; with more than a few tokens it is also
-        // the faster way (16 tokens: 11.7 -> 9.7 us on the 32B up projection), with one token the
-        // address arithmetic of the 16 or 32 loads costs more than the staging (5.0 -> 5.1 us).
-        const int kgran = a.K >> 4;
-        const int8_t* qrow = a.q + (int64_t)brow * a.K;
-#pragma unroll
-        for (int i = 0; i < CPW; ++i)
-#pragma unroll
-            for (int j = 0; j < 8; ++j) b[i][j] = v4i{0, 0, 0, 0};
-        // (lanes of token columns past M stay out of the loads: their operands are never used,
-        // and an instruction costs the texture path as many cycles as it has active lanes)
-        if (li < a.M) {
+    // operand codes of pass hp: chunks hp * KS * CPW + wave + i * KS
+    auto load_b = [&](int hp) {
+        const int cbase = hp * KS * CPW + wave;
+        if (FUSED || !a.direct) {
 #pragma unroll
             for (int i = 0; i < CPW; ++i) {
-                const int c = wave + i * KS;
+                const int c = cbase + i * KS < chunks ? cbase + i * KS : chunks;   // chunk `chunks` is a zero patch
 #pragma unroll
-                for (int j = 0; j < 8; ++j) {
-                    const int g = c * 32 + lg * 8 + j;
-                    const bool ok = c < chunks && g < kgran;
-                    const v4i v = *reinterpret_cast<const v4i*>(qrow + (ok ? g : 0) * 16);
-                    b[i][j] = ok ? v : v4i{0, 0, 0, 0};
+                for (int j = 0; j < 8; ++j)
+                    b[i][j] = *reinterpret_cast<const v4i*>(qt + brow * (Kp + BWLA_CHUNK_COLS) + c * BWLA_CHUNK_COLS +
+                                                            (((lg * 8 + j) ^ brow) << 4));
+            }
+        } else {
+            // Straight from global memory, once per workgroup and pass: lane (li, lg) takes, for
+            // step j of a chunk, the 16 codes of token li at columns 128 lg + 16 j of the chunk
+            // (the column order of the packed bits).  Granules past K (the last chunk may be
+            // partial) and chunks this wave does not have are zero operands.  No LDS and no
+            // barrier are involved, so every token count up to 16 and every row length fit; with
+            // more than a few tokens it is also the faster way (16 tokens: 11.7 -> 9.7 us on the
+            // 32B up projection), with one token the address arithmetic of the 16 or 32 loads
+            // costs more than the staging (5.0 -> 5.1 us).
+            const int kgran = a.K >> 4;
+            const int8_t* qrow = a.q + (int64_t)brow * a.K;
+#pragma unroll
+            for (int i = 0; i < CPW; ++i)
+#pragma unroll
+                for (int j = 0; j < 8; ++j) b[i][j] = v4i{0, 0, 0, 0};
+            // (lanes of token columns past M stay out of the loads: their operands are never used,
+            // and an instruction costs the texture path as many cycles as it has active lanes)
+            if (li < a.M) {
+#pragma unroll
+                for (int i = 0; i < CPW; ++i) {
+                    const int c = cbase + i * KS;
+#pragma unroll
+                    for (int j = 0; j < 8; ++j) {
+                        const int g = c * 32 + lg * 8 + j;
+                        const bool ok = c < chunks && g < kgran;
+                        const v4i v = *reinterpret_cast<const v4i*>(qrow + (ok ? g : 0) * 16);
+                        b[i][j] = ok ? v : v4i{0, 0, 0, 0};
+                    }
                 }
             }
         }
-        TRACE(1);
-    }
 #pragma unroll
-    for (int i = 0; i < CPW; ++i)
-        b[i][7] = v4i{neg_bytes(b[i][7].x), neg_bytes(b[i][7].y), neg_bytes(b[i][7].z), neg_bytes(b[i][7].w)};
+        for (int i = 0; i < CPW; ++i)
+            b[i][7] = v4i{neg_bytes(b[i][7].x), neg_bytes(b[i][7].y), neg_bytes(b[i][7].z), neg_bytes(b[i][7].w)};
+    };
+    load_b(0);
     TRACE(2);
+    int cur_pass = 0;
 
-    // The trip count is rounded up to a multiple of DEPTH: surplus steps redo the last unit.
-    for (int it0 = 0; it0 < n_iter; it0 += DEPTH) {
+    // The trip count is rounded up to a multiple of DEPTH: surplus steps redo the last step.
+    for (int it0 = 0; it0 < n_iter * H; it0 += DEPTH) {
 #pragma unroll
         for (int d = 0; d < DEPTH; ++d) {
             const int it = it0 + d;
+            if constexpr (MULTI) {                         // a new pass begins: its operand codes
+                const int hp = dni.div(it < last_it ? it : last_it);
+                if (hp != cur_pass) { load_b(hp); cur_pass = hp; }
+            }
             // per tile two independent chains (odd and even classes, two bits apart):
             // e = S6+S4+S2+S0 exactly, o = 2*(S7+S5+S3+S1) exactly
             v4i acc_e[NT], acc_o[NT];
@@ -278,7 +312,7 @@ __device__ __forceinline__ void compute_wave(const BsArgs& a, char* smem, int fi
 }
 
 // ------------------------------------------------------------------ epilogue wave
-template <int DEPTH, int NT, int JTT, bool FAST, bool FUSED = false>
+template <int DEPTH, int NT, int JTT, bool FAST, bool FUSED = false, bool MULTI = false>
 __device__ __forceinline__ void epilogue_wave(const BsArgs& a, char* smem, int first, int stride, int n_iter,
                                               int wave, int lane, const FusedLocal& fl = FusedLocal{}) {
     const int li = lane & 15, lg = lane >> 4;
@@ -359,20 +393,33 @@ __device__ __forceinline__ void epilogue_wave(const BsArgs& a, char* smem, int f
         }
     TRACE(2);
 
-    const int n_steps = (n_iter + DEPTH - 1) / DEPTH * DEPTH;    // same barrier count as the compute waves
+    // Several passes over a long row (see compute_wave): step `it` is unit it % n_iter of pass
+    // it / n_iter; the sums of the earlier passes wait in LDS (this wavefront alone touches them)
+    // and the unit is finished in the last pass.
+    const int H = MULTI ? a.passes : 1;
+    const FastDivU dni((uint32_t)n_iter);
+    v4i* usum = reinterpret_cast<v4i*>(qt + (a.direct ? 0 : (size_t)(a.M < 16 ? a.M : 16) * (a.chunks + 1) * BWLA_CHUNK_COLS));
+    const int n_real = n_iter * H;
+    const int n_steps = (n_real + DEPTH - 1) / DEPTH * DEPTH;    // same barrier count as the compute waves
     for (int it = 0; it < n_steps; ++it) {
         if (it < 12) TRACE(3 + 3 * it);
         bwla_lds_barrier();                                // partial tiles and side pieces of `it` are in LDS
         if (it < 12) TRACE(4 + 3 * it);
         const char* sd = side + (it & 1) * side_bytes(rp, NT);
+        const int hp = MULTI ? dni.div(it < n_real ? it : 0) : 0, ui = it - hp * n_iter;
 #pragma unroll
         for (int nt = 0; nt < NT; ++nt) {
-            const int tile = (first + it * stride) * NT + nt;
-            if (it >= n_iter || tile >= a.row_tiles) continue;      // surplus step or ragged last unit
+            const int tile = (first + ui * stride) * NT + nt;
+            if (it >= n_real || tile >= a.row_tiles) continue;      // surplus step or ragged last unit
             v4i tot = v4i{0, 0, 0, 0};
 #pragma unroll
             for (int k2 = 0; k2 < BS_MAXKS; ++k2)
                 tot += red[(((it & 1) * NT + nt) * BS_MAXKS + k2) * 64 + lane];
+            if constexpr (MULTI) {
+                v4i* us = usum + (ui * NT + nt) * 64 + lane;
+                if (hp > 0) tot += *us;
+                if (hp < H - 1) { *us = tot; continue; }
+            }
 
             // low-rank term on f16 MFMA (fp32 accumulate): D[n][t] = sum_j V[n][j] T[t][j]; lane
             // (li, lg) feeds j = 16*uu + 4*lg + e, e = 0..3, of group uu for both operands
@@ -421,24 +468,32 @@ constexpr int BS_CPW = 2;   // two chunks per compute wave amortize the class re
 constexpr int BS_CPW_LONG = 4;
 constexpr int BS_MAXKS_LONG = 7;
 inline int bs_cpw_for(int chunks) {
-    if ((chunks + BS_CPW - 1) / BS_CPW <= BS_MAXKS) return BS_CPW;
-    if ((chunks + BS_CPW_LONG - 1) / BS_CPW_LONG <= BS_MAXKS_LONG) return BS_CPW_LONG;
-    return 0;
+    return (chunks + BS_CPW - 1) / BS_CPW <= BS_MAXKS ? BS_CPW : BS_CPW_LONG;
+}
+// still longer rows: passes of BS_MAXKS_LONG * BS_CPW_LONG = 28 chunks (70B down, K = 28672: two)
+inline int bs_passes_for(int chunks) {
+    const int per = BS_MAXKS_LONG * BS_CPW_LONG;
+    return bs_cpw_for(chunks) == BS_CPW ? 1 : (chunks + per - 1) / per;
+}
+inline int bs_ks_for(int chunks) {
+    const int cpw = bs_cpw_for(chunks);
+    const int ks = (chunks + cpw - 1) / cpw;
+    return cpw == BS_CPW ? ks : (ks < BS_MAXKS_LONG ? ks : BS_MAXKS_LONG);
 }
 
-// (M: token rows staged in LDS; 0 when the compute waves load their codes themselves)
-inline size_t bs_lds_bytes(int64_t M, int chunks, int rp, int nt) {
+// (M: token rows staged in LDS; 0 when the compute waves load their codes themselves.  With more
+// than one pass: 1 KiB per tile of the workgroup's units behind them, for the sums of earlier passes.)
+inline size_t bs_lds_bytes(int64_t M, int chunks, int rp, int nt, int pass_units = 0) {
     return (size_t)red_bytes(nt) + 2 * (size_t)side_bytes(rp, nt) +
-           (size_t)(M < 16 ? M : 16) * ((size_t)chunks + 1) * BWLA_CHUNK_COLS;
+           (size_t)(M < 16 ? M : 16) * ((size_t)chunks + 1) * BWLA_CHUNK_COLS + (size_t)pass_units * nt * 1024;
 }
 
 // one compute wave per side piece (the unit's V rows in 1 KiB pieces + its scales), LDS fits
-inline bool bs_fits(int64_t M, int chunks, int r, int nt, int cpw = BS_CPW) {
-    if (cpw == 0) return false;
-    const int KS = (chunks + cpw - 1) / cpw;
+inline bool bs_fits(int64_t M, int chunks, int r, int nt, int cpw = BS_CPW, int pass_units = 0) {
+    const int KS = cpw == BS_CPW ? (chunks + cpw - 1) / cpw : bs_ks_for(chunks);
     const int rp = ((r + 15) >> 4) * 16;
     return KS <= (cpw == BS_CPW ? BS_MAXKS : BS_MAXKS_LONG) && KS >= ((nt * rp + 31) >> 5) + 1 &&
-           bs_lds_bytes(M, chunks, rp, nt) <= 160 * 1024;
+           bs_lds_bytes(M, chunks, rp, nt, pass_units) <= 160 * 1024;
 }
 
 }  // namespace

@@ -356,7 +356,7 @@ hipError_t bwla_launch_decode_fused(const bwla_layer_t* L, const void* dX, int x
     ra.q = dq; ra.scale = dscale; ra.qsum = dqsum;
     BsArgs ba{(const uint4*)(blob + L->off_bits), chunks, row_tiles, dq, (int)M, (int)L->K, dscale, dqsum,
               (const __half*)(blob + L->off_alpha), (const __half*)(blob + L->off_V), nullptr, 0, dY, (int)L->N,
-              dacc, KS, 0};
+              dacc, KS, 0, 1};
     // one workgroup per CU fits (registers)
     const int cus = bwla_device_cus();
     const int G = row_tiles < cus ? row_tiles : cus;
