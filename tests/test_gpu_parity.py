@@ -77,6 +77,10 @@ def test_cfg4_70b_gate_m4096_sampled_rows():
     (1, 11008, 128, 86, 1000, 32, "bf16"),  # 7B down-projection shape: 22 chunks, six compute wavefronts
     (8, 12288, 128, 96, 520, 0, "bf16"),    # 24 chunks, eight tokens, no low-rank part
     (2, 14336, 128, 112, 200, 48, "bf16"),  # the longest row this variant takes: 28 chunks, seven compute wavefronts
+    # rows longer than 14336 columns at decode: several passes of 28 chunks in one launch
+    (1, 28672, 224, 128, 300, 32, "bf16"),  # 70B down-projection width: two full passes
+    (16, 27648, 216, 128, 200, 16, "bf16"), # 32B down-projection width, sixteen tokens: 54 chunks, 28 + 26
+    (4, 30976, 176, 176, 9000, 8, "bf16"),  # three passes (28, 28, 5 chunks, the last partly filled), three channel tiles per workgroup
     # one token without low-rank part: bwla_decode_forward runs its single-launch kernel
     (1, 4096, 64, 64, 4096, 0, "bf16"),    # 7B attention projection shape, one channel tile per workgroup
     (1, 4096, 64, 64, 11008, 0, "bf16"),   # 7B gate/up shape: up to three channel tiles per workgroup
