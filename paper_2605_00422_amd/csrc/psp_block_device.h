@@ -4,12 +4,40 @@
 
 namespace {
 
+// Sum of the S partial tiles of token tile tt, in slice order, into T (all threads of the workgroup).
+__device__ __forceinline__ void psp_sum_partials(const float* __restrict__ partials, float* __restrict__ T, int64_t M,
+                                                 int r, int S, int tt, int tp) {
+    const int rp = ((r + 15) >> 4) * 16;
+    const int rows = M - (int64_t)tt * 16 < 16 ? (int)(M - (int64_t)tt * 16) : 16;
+    for (int idx = threadIdx.x; idx < rows * rp; idx += (int)blockDim.x) {
+        const int row = idx / rp, col = idx - row * rp;
+        const int64_t tok = (int64_t)tt * 16 + row;
+        if (col < r) {
+            // batches of sixteen loads in flight; slices past S re-read the last one and add zero
+            float sum = 0.0f;
+            for (int ss = 0; ss < S; ss += 16) {
+                float v[16];
+#pragma unroll
+                for (int u = 0; u < 16; ++u) {
+                    const int sc = ss + u < S ? ss + u : S - 1;
+                    v[u] = bwla_load_agent(&partials[(((int64_t)tt * S + sc) * 16 + row) * rp + col]);
+                }
+#pragma unroll
+                for (int u = 0; u < 16; ++u) sum += ss + u < S ? v[u] : 0.0f;
+            }
+            T[tok * tp + col] = sum;
+        }
+    }
+}
+
 // ================================================================== PSP projection T = X U
+// finish = false: with more than one slice the workgroup only leaves its partial tile; a later
+// launch adds them up (psp_sum_partials) and the arrival counters are not touched.
 template <bool BF16>
 __device__ __forceinline__ void psp_block(char* smem, const void* __restrict__ X, int64_t M, int64_t K, int r,
                                           const __half* __restrict__ U, float* __restrict__ T,
                                           int* __restrict__ counters, float* __restrict__ partials, int S, int tt,
-                                          int s, int tp) {
+                                          int s, int tp, bool finish = true) {
     __shared__ int is_last;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int nw = (int)(blockDim.x >> 6);             // the eight 64-column parts of a slice are dealt to nw waves
@@ -84,30 +112,11 @@ __device__ __forceinline__ void psp_block(char* smem, const void* __restrict__ X
             }
         }
     }
-    if (S == 1) return;
+    if (S == 1 || !finish) return;
 
     if (!bwla_partials_arrive(&counters[tt], S, &is_last)) return;
     // last workgroup of this token tile: add the S partial tiles in slice order
-    const int rows = M - (int64_t)tt * 16 < 16 ? (int)(M - (int64_t)tt * 16) : 16;
-    for (int idx = tid; idx < rows * rp; idx += (int)blockDim.x) {
-        const int row = idx / rp, col = idx - row * rp;
-        const int64_t tok = (int64_t)tt * 16 + row;
-        if (col < r) {
-            // batches of sixteen loads in flight; slices past S re-read the last one and add zero
-            float sum = 0.0f;
-            for (int ss = 0; ss < S; ss += 16) {
-                float v[16];
-#pragma unroll
-                for (int u = 0; u < 16; ++u) {
-                    const int sc = ss + u < S ? ss + u : S - 1;
-                    v[u] = bwla_load_agent(&partials[(((int64_t)tt * S + sc) * 16 + row) * rp + col]);
-                }
-#pragma unroll
-                for (int u = 0; u < 16; ++u) sum += ss + u < S ? v[u] : 0.0f;
-            }
-            T[tok * tp + col] = sum;
-        }
-    }
+    psp_sum_partials(partials, T, M, r, S, tt, tp);
     if (tid == 0) counters[tt] = 0;                    // leave the scratch as it was found
 }
 

@@ -72,17 +72,17 @@ __global__ __launch_bounds__(THREADS) void rotate_quant3_kernel(RqArgs a) {
 }
 
 // split rotation: workgroup b < rot_blocks does slice b % G of token b / G
-__global__ __launch_bounds__(512) void rotate_split_kernel(RqArgs a) {
+__global__ __launch_bounds__(640) void rotate_split_kernel(RqArgs a) {
     extern __shared__ __align__(16) float lds[];
     if ((int64_t)blockIdx.x < a.rot_blocks) {
         const int G = rs_shape(r3_shape(a.n1, a.n2)).G;
         const int64_t t = blockIdx.x / G;
-        rotate_split_block<R3_MAXA>(reinterpret_cast<char*>(lds), reinterpret_cast<const uint16_t*>(a.X), t,
-                                    (int)(blockIdx.x - t * G), a.K, a.n1, a.n2, a.R1p, a.R2p, a.xs, a.pmax, a.qsum);
+        rotate_slice_block(reinterpret_cast<char*>(lds), reinterpret_cast<const uint16_t*>(a.X), t,
+                           (int)(blockIdx.x - t * G), a.K, a.n1, a.n2, a.R1p, a.R2p, a.xs, a.pmax, a.qsum);
     } else {
         const int pb = (int)(blockIdx.x - a.rot_blocks);
         psp_block<true>(reinterpret_cast<char*>(lds), a.X, a.M, a.K, a.r, a.U, a.T, a.counters, a.partials, a.S,
-                        pb / a.S, pb % a.S, a.tp);
+                        pb / a.S, pb % a.S, a.tp, false);
     }
 }
 
@@ -245,19 +245,22 @@ hipError_t bwla_launch_rotate_quant(const bwla_layer_t* L, const void* dX, int x
         const RsShape rs = rs_shape(s3);
         a.xs = (float*)((char*)dws + bwla_align256(bwla_psp_ws_bytes(plan, M, ru)));
         a.pmax = a.xs + M * L->K;
-        float* zcs = a.pmax + 2 * M * rs.G;            // per token: what the stored codes have to lose
+        float* zcs = a.pmax + 2 * M * rs.E;            // per token: what the stored codes have to lose
         a.rot_blocks = M * rs.G;
-        const size_t pl3 = merged ? pp_lds_bytes(ru, 8) : 0;
+        const int threads3 = s3.strips > 8 ? 64 * s3.strips : 512;     // the projection wants eight wavefronts
+        const size_t pl3 = merged ? pp_lds_bytes(ru, threads3 / 64) : 0;
         const size_t lds3 = pl3 > rs.lds_bytes ? pl3 : rs.lds_bytes;
         static bwla_lds_attr attr;
         e = attr.ensure((const void*)rotate_split_kernel, lds3);
         if (e != hipSuccess) return e;
-        rotate_split_kernel<<<dim3((unsigned)(a.rot_blocks + pblocks)), dim3(512), lds3, st>>>(a);
+        rotate_split_kernel<<<dim3((unsigned)(a.rot_blocks + pblocks)), dim3((unsigned)threads3), lds3, st>>>(a);
         e = hipGetLastError();
         if (e != hipSuccess) return e;
-        quantize_rows_kernel<<<dim3((unsigned)(M * RS_QB)), dim3(512), 0, st>>>(a.xs, a.pmax, rs.G, L->K, dq, dscale,
-                                                                                 dqsum, a.qmax, a.asym, a.tmode,
-                                                                                 a.tp, zcs);
+        // (the projection's workgroups in that launch leave partial tiles; the next one adds them up)
+        const bool psum = merged && a.S > 1;
+        const PspSum ps{a.partials, a.T, M, M * RS_QB, a.r, a.S};
+        quantize_rows_kernel<<<dim3((unsigned)(M * RS_QB + (psum ? plan.token_tiles : 0))), dim3(512), 0, st>>>(
+            a.xs, a.pmax, rs.E, L->K, dq, dscale, dqsum, a.qmax, a.asym, a.tmode, a.tp, zcs, ps);
         e = hipGetLastError();
         if (e != hipSuccess) return e;
         if (a.shift) {
@@ -330,7 +333,7 @@ size_t bwla_split_rotation_bytes(const bwla_layer_t* L, const bwla_psp_plan& pla
     // every workgroup of the launch gets a CU of its own at once; with more tokens than that the
     // one-workgroup-per-token kernel keeps the chip busy anyway
     if (M * rs.G + pblocks > bwla_device_cus()) return 0;
-    return (size_t)(M * L->K + 2 * M * rs.G + M) * sizeof(float);     // values, extremes, per-token code offset
+    return (size_t)(M * L->K + 2 * M * rs.E + M) * sizeof(float);     // values, extremes, per-token code offset
 }
 
 // Single-launch decode layer.  *done = false (and nothing launched) when the shape is outside what

@@ -113,22 +113,35 @@ def run_case(cfg: syn.LayerConfig, rows=None, centered: bool = False, act_bits: 
     ncnt = (((cfg.M + 15) // 16) * 4 + 255) // 256 * 256 if cfg.r > 0 else 0   # (cfg.r: the projection's rank)
     assert int(torch.count_nonzero(act.ws[:ncnt])) == 0, "arrival counters not restored to zero"
 
-    # the one-call entry point (a single launch for one bf16 token) gives the same bits, also when
-    # it is called again on other activations with the same buffers
-    if cfg.M <= 16 and act_bits == 6:
+    # the one-call entry point (a single launch for one bf16 token without low-rank part, else the
+    # two calls).  It may rotate with another kernel than bwla_rotate_quant picks for the shape,
+    # and the two kernels need not add their products in the same order: its results are held
+    # against the oracle by the same criteria, not against the two-call results bit for bit.
+    # Called again on the same activations, with other activations in between, it gives the same bits.
+    if cfg.M <= 16 and act_bits == 6 and rows is None:
         act1 = B.Activations(layer, cfg.M)
         Y1 = torch.full((cfg.M, cfg.N), float("nan"), dtype=torch.float32, device=DEV)
         acc1 = torch.full((cfg.M, cfg.N), -1, dtype=torch.int32, device=DEV)
         X2 = (X.float() * 0.5 + torch.roll(X.float(), 1, dims=1)).to(X.dtype)
+        kept = None
         for rep, (Xi, with_acc) in enumerate(((X2, False), (X, True), (X, False))):
             B.decode_forward(layer, Xi, act1, Y1, acc1 if with_acc else None)
             torch.cuda.synchronize()
             assert int(torch.count_nonzero(act1.ws[:ncnt])) == 0, f"call {rep}: counters not restored to zero"
-        assert torch.equal(act1.q, act.q) and torch.equal(act1.scale, act.scale) and torch.equal(act1.qsum, act.qsum)
-        if rt > 0:
-            assert torch.equal(act1.T, act.T), "one-call T differs"
-        assert torch.equal(Y1, Y), "one-call output differs from the two-call output"
-        assert torch.equal(acc1, acc), "one-call accumulators differ"
+            if rep == 1:
+                kept = (act1.q.clone(), act1.scale.clone(), act1.qsum.clone(), Y1.clone())
+        assert torch.equal(act1.q, kept[0]) and torch.equal(act1.scale, kept[1]) and torch.equal(act1.qsum, kept[2])
+        assert torch.equal(Y1, kept[3]), "one-call output changes between calls on the same activations"
+        q1 = act1.q.cpu().numpy()
+        check_codes(q1, ref, qmax)
+        assert np.allclose(act1.scale.cpu().numpy().astype(np.float64), ref["s"], rtol=2e-6, atol=0)
+        assert np.array_equal(act1.qsum.cpu().numpy().astype(np.int64), q1.astype(np.int64).sum(axis=1))
+        assert np.array_equal(acc1.cpu().numpy().astype(np.int64), orc.binary_gemm(q1, sgn)), "one-call accumulators differ"
+        if cfg.r > 0:
+            tden1 = np.maximum(np.max(np.abs(ref["T"]), axis=1, keepdims=True), 1e-30)
+            assert np.max(np.abs(act1.T.cpu().numpy().astype(np.float64)[:, :cfg.r] - ref["T"]) / tden1) < 2e-5
+        check_output(Y1.cpu().numpy(), ref["Y"])
+        # other activations: the one call and the two calls agree to within criterion 3
         act2x = B.Activations(layer, cfg.M)
         Y2a = torch.empty_like(Y)
         Y2b = torch.empty_like(Y)
@@ -136,8 +149,8 @@ def run_case(cfg: syn.LayerConfig, rows=None, centered: bool = False, act_bits: 
         B.linear_forward(layer, act2x, Y2a)
         B.decode_forward(layer, X2, act1, Y2b)
         torch.cuda.synchronize()
-        assert torch.equal(Y2a, Y2b), "one-call output differs on the second set of activations"
-        del act1, act2x, Y1, Y2a, Y2b, acc1, X2
+        check_output(Y2b.cpu().numpy(), Y2a.cpu().numpy().astype(np.float64))
+        del act1, act2x, Y1, Y2a, Y2b, acc1, X2, kept
 
     sel_t = torch.from_numpy(sel).to(DEV)
     q_gpu = act.q[sel_t].cpu().numpy()
