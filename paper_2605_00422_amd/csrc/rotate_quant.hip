@@ -320,12 +320,12 @@ hipError_t bwla_launch_rotate_quant(const bwla_layer_t* L, const void* dX, int x
 size_t bwla_split_rotation_bytes(const bwla_layer_t* L, const bwla_psp_plan& plan, int64_t M) {
     const R3Shape s3 = r3_shape(L->n1, L->n2);
     if (!s3.ok || L->K > (int64_t)RS_QB * 512 * RS_QI * 4) return 0;
-    // Factors that fit LDS: the split still pays when stage 2 is long (six or more tiles along n1)
-    // and either the strips do not spread evenly over the CU's four SIMDs (n2 = 86: six wavefronts,
-    // two SIMDs carry two) or there are at most two tokens, so that the extra workgroups are free
-    // (measured: 7B down 16.7 -> 11.7 us at one token, 17.1 -> 13.2 at sixteen; 128 x 64 at sixteen
-    // tokens 12.3 -> 14.4, hence not there).
-    if (s3.resident && !(s3.at >= 6 && ((s3.strips & 3) != 0 || M <= 2))) return 0;
+    // Factors that fit LDS: the split still pays when the second product is long (six or more
+    // tiles along n1) and either the strips do not spread evenly over the CU's four SIMDs (n2 = 86:
+    // six wavefronts, two SIMDs carry two) or there are at most eight tokens, so that the extra
+    // workgroups are free (measured, 128 x 64: 12.1 -> 11.1 us at four tokens, 12.2 -> 11.8 at
+    // eight, 12.3 -> 12.9 at sixteen; 128 x 86: 16.7 -> 10.9 at one token, 17.1 -> 12.2 at sixteen).
+    if (s3.resident && !(s3.at >= 6 && ((s3.strips & 3) != 0 || M <= 8))) return 0;
     const RsShape rs = rs_shape(s3);
     if (!rs.ok) return 0;
     const bool merged = bwla_rank_u(L) > 0 && plan.tile_rows == 16;
