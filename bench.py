@@ -296,7 +296,7 @@ def main():
 
     if not args.no_extra:
         extra = []
-        names = ["cfg1_7b_q_m1", "cfg1_7b_down_m1", "cfg2_qwen32b_up_m16", "cfg3_qwen32b_down_m2048",
+        names = ["cfg1_7b_q_m1", "cfg1_7b_down_m1", "cfg1_7b_qkv_m1", "cfg1_7b_gateup_m1", "cfg2_qwen32b_up_m16", "cfg3_qwen32b_down_m2048",
                  "cfg4_70b_gate_m1", "cfg4_70b_down_m1", "cfg4_70b_q_m64", "cfg4_70b_q_m4096"]
         # (name, layer binarized with the row shift: the shift term rides as one more low-rank column)
         # and 8-bit activation codes, the width of the paper's speed run: same kernels, same bytes)
@@ -323,6 +323,18 @@ def main():
             del ww
             torch.cuda.empty_cache()
         line["other_workloads"] = extra
+        # the seven linear layers of a 7B decoder block at one token: called one by one (q, k, v, o,
+        # gate, up, down), and with the projections that read the same activations packed as one
+        # layer (qkv, o, gate|up, down)
+        us = {e["workload"]: min(e[k]["us_per_layer"] for k in ("stream", "graph") if k in e and "us_per_layer" in e[k])
+              for e in extra}
+        us[cfg.name] = us_layer
+        need = ("cfg1_7b_q_m1", "cfg1_decode7b", "cfg1_7b_down_m1", "cfg1_7b_qkv_m1", "cfg1_7b_gateup_m1")
+        if all(k in us for k in need):
+            line["block7b_m1"] = {
+                "us_seven_layers": 4 * us["cfg1_7b_q_m1"] + 2 * us["cfg1_decode7b"] + us["cfg1_7b_down_m1"],
+                "us_four_merged_layers": us["cfg1_7b_qkv_m1"] + us["cfg1_7b_q_m1"] + us["cfg1_7b_gateup_m1"]
+                                         + us["cfg1_7b_down_m1"]}
     print(json.dumps(line))
 
 

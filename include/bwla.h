@@ -159,9 +159,9 @@ bwla_status_t bwla_unpack_signs(const bwla_layer_t* layer, int8_t* d_sgn, float*
 
 /*
  * Bytes of scratch bwla_rotate_quant wants for M tokens: split-K partial sums of X U with their
- * arrival counters, and, for a few tokens of a layer whose factor R1 does not fit on-chip memory
- * whole, the rotated values in fp32 between the two launches the rotation then takes.  Returns 0
- * bytes when neither is used.
+ * arrival counters, and, for a few tokens of a layer with a large factor R1 (six or more 16-row
+ * tiles), the rotated values in fp32 and their extremes between the two launches the rotation
+ * then takes.  Returns 0 bytes when neither is used.
  * The scratch must be zero-filled once when it is allocated: it starts with one arrival counter
  * per 16-token tile, which every call returns to zero; everything behind them is overwritten by
  * each call.  Two calls that overlap in time must not share one scratch buffer.

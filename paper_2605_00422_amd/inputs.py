@@ -74,12 +74,16 @@ def block70b_configs(M: int) -> list[LayerConfig]:
 
 def block7b_configs(M: int) -> list[LayerConfig]:
     """7B-shaped decoder block (the model of cfg1, whose layer is this block's gate/up projection):
-    hidden 4096, intermediate 11008; Kronecker pairs by Algorithm 1 (11008 = 128 x 86)."""
+    hidden 4096, intermediate 11008; Kronecker pairs by Algorithm 1 (11008 = 128 x 86).
+    "qkv" and "gateup" are the projections that read the same activations packed as one layer
+    (rows stacked, one rotation pair, the ranks of the parts added up): one rotation and one GEMM
+    launch serve all of them."""
     h, inter = 4096, 11008
     out = []
-    for nm, K, N in (("q", h, h), ("gate", h, inter), ("down", inter, h)):
+    for nm, K, N, r in (("q", h, h, 32), ("gate", h, inter, 32), ("down", inter, h, 32),
+                        ("qkv", h, 3 * h, 96), ("gateup", h, 2 * inter, 64)):
         n1, n2 = _near_square(K)
-        out.append(LayerConfig(f"cfg1_7b_{nm}_m{M}", M, K, n1, n2, N, 32, "bf16", _pct(K, 0.01), 50.0))
+        out.append(LayerConfig(f"cfg1_7b_{nm}_m{M}", M, K, n1, n2, N, r, "bf16", _pct(K, 0.01), 50.0))
     return out
 
 

@@ -54,6 +54,14 @@ def test_cfg4_70b_block_small_m(which, M):
     print(run_case(cfg), flush=True)
 
 
+@pytest.mark.parametrize("which", ["qkv", "gateup"])
+def test_cfg1_7b_merged_projections(which):
+    """Projections that read the same activations, packed as one layer (N = 12288, r = 96; N = 22016, r = 64)."""
+    from parity_util import run_case
+    cfg = {c.name.split("_")[2]: c for c in syn.block7b_configs(1)}[which]
+    print(run_case(cfg), flush=True)
+
+
 def test_cfg4_70b_gate_m4096_sampled_rows():
     from parity_util import run_case
     cfg = {c.name.split("_")[2]: c for c in syn.block70b_configs(4096)}["gate"]
