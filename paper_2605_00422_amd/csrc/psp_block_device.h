@@ -31,18 +31,23 @@ __device__ __forceinline__ void psp_sum_partials(const float* __restrict__ parti
 }
 
 // ================================================================== PSP projection T = X U
+// A workgroup takes 16 tokens, one 512-column slice of K and up to PP_GROUPJT 16-column tiles of
+// the rank (group jg of JG): the fp32 MFMAs of a wavefront grow with the tiles it carries (six
+// tiles: 96 of them, 1.3 us), so wide ranks are dealt to more workgroups.
 // finish = false: with more than one slice the workgroup only leaves its partial tile; a later
 // launch adds them up (psp_sum_partials) and the arrival counters are not touched.
 template <bool BF16>
 __device__ __forceinline__ void psp_block(char* smem, const void* __restrict__ X, int64_t M, int64_t K, int r,
                                           const __half* __restrict__ U, float* __restrict__ T,
                                           int* __restrict__ counters, float* __restrict__ partials, int S, int tt,
-                                          int s, int tp, bool finish = true) {
+                                          int s, int tp, bool finish = true, int jg = 0, int JG = 1) {
     __shared__ int is_last;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int nw = (int)(blockDim.x >> 6);             // the eight 64-column parts of a slice are dealt to nw waves
     const int li = lane & 15, lg = lane >> 4;
-    const int JT = (r + 15) >> 4, rp = JT * 16;
+    const int JTall = (r + 15) >> 4, rp = JTall * 16;
+    const int jt0 = JG > 1 ? jg * PP_GROUPJT : 0;                      // my tiles: jt0 .. jt0 + JT - 1
+    const int JT = JG > 1 ? (JTall - jt0 < PP_GROUPJT ? JTall - jt0 : PP_GROUPJT) : JTall;
     const int64_t kbase = (int64_t)s * PP_SLICE;
 
     // wave w takes columns [64w, 64w+64) of the slice in 4 groups of 16: lane (li, lg) owns
@@ -72,7 +77,7 @@ __device__ __forceinline__ void psp_block(char* smem, const void* __restrict__ X
         if (!in) x[g][0] = x[g][1] = x[g][2] = x[g][3] = 0.0f;
 #pragma unroll
         for (int jt = 0; jt < PP_MAXJT; ++jt)
-            if (jt < JT) u[g][jt] = *reinterpret_cast<const uint2*>(U + (int64_t)(jt * 16 + li) * K + kc);
+            if (jt < JT) u[g][jt] = *reinterpret_cast<const uint2*>(U + (int64_t)((jt0 + jt) * 16 + li) * K + kc);
     }
 
 #pragma unroll
@@ -100,7 +105,7 @@ __device__ __forceinline__ void psp_block(char* smem, const void* __restrict__ X
     for (int jt = wave; jt < JT; jt += nw) {
         v4f sum = red[jt * 64 + lane];
         for (int w = 1; w < nw; ++w) sum += red[(w * JT + jt) * 64 + lane];
-        const int col = jt * 16 + li;
+        const int col = (jt0 + jt) * 16 + li;
 #pragma unroll
         for (int v = 0; v < 4; ++v) {
             const int row = 4 * lg + v;
@@ -114,7 +119,7 @@ __device__ __forceinline__ void psp_block(char* smem, const void* __restrict__ X
     }
     if (S == 1 || !finish) return;
 
-    if (!bwla_partials_arrive(&counters[tt], S, &is_last)) return;
+    if (!bwla_partials_arrive(&counters[tt], S * JG, &is_last)) return;
     // last workgroup of this token tile: add the S partial tiles in slice order
     psp_sum_partials(partials, T, M, r, S, tt, tp);
     if (tid == 0) counters[tt] = 0;                    // leave the scratch as it was found

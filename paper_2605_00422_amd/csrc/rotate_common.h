@@ -71,6 +71,7 @@ constexpr int RQ_CLD = RQ_CK + 4;    // LDS pitch of a streamed chunk row
 constexpr int RQ_RING = 3;           // streamed chunks in flight (registers)
 constexpr int PP_SLICE = 512;        // columns of K per projection workgroup
 constexpr int PP_MAXJT = BWLA_MAX_RANK / 16;
+constexpr int PP_GROUPJT = 2;        // 16-column tiles of the rank per projection workgroup when they are dealt out
 constexpr size_t RQ_LDS_LIMIT = 160 * 1024 - 256;   // leaves room for the few static bytes
 
 __host__ __device__ inline int rq_pad16(int n) { return (n + 15) & ~15; }

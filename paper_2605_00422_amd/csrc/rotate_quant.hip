@@ -40,8 +40,17 @@ struct RqArgs {
     float* tmode;            // T + (PSP rank): first of the entries the layer's mode adds to a row, or NULL
     int asym, shift;         // the layer's mode: asymmetric activation codes, row shift
     int64_t rot_blocks;      // workgroups below this index rotate token blockIdx.x, the rest project
+    int JG;                  // projection workgroups per (token tile, slice): groups of rank tiles
     const uint16_t* R1p; const uint16_t* R2p;          // bf16 term planes of the factors
 };
+
+// projection workgroup pb of a launch: slice fastest, then the group of rank tiles, then the token tile
+template <bool BF16>
+__device__ __forceinline__ void psp_block_at(char* lds, const RqArgs& a, int pb, bool finish = true) {
+    const int s = pb % a.S, rest = pb / a.S;
+    psp_block<BF16>(lds, a.X, a.M, a.K, a.r, a.U, a.T, a.counters, a.partials, a.S, rest / a.JG, s, a.tp, finish,
+                    rest % a.JG, a.JG);
+}
 
 template <bool BF16>
 __global__ __launch_bounds__(RQ_THREADS) void rotate_quant_kernel(RqArgs a) {
@@ -51,8 +60,7 @@ __global__ __launch_bounds__(RQ_THREADS) void rotate_quant_kernel(RqArgs a) {
                            a.asym != 0, a.shift != 0);
     } else {
         const int pb = (int)(blockIdx.x - a.rot_blocks);
-        psp_block<BF16>(reinterpret_cast<char*>(lds), a.X, a.M, a.K, a.r, a.U, a.T, a.counters, a.partials, a.S,
-                        pb / a.S, pb % a.S, a.tp);
+        psp_block_at<BF16>(reinterpret_cast<char*>(lds), a, pb);
     }
 }
 
@@ -66,8 +74,7 @@ __global__ __launch_bounds__(THREADS) void rotate_quant3_kernel(RqArgs a) {
                            a.tp, a.qmax, a.asym != 0, a.shift != 0);
     } else {
         const int pb = (int)(blockIdx.x - a.rot_blocks);
-        psp_block<true>(reinterpret_cast<char*>(lds), a.X, a.M, a.K, a.r, a.U, a.T, a.counters, a.partials, a.S,
-                        pb / a.S, pb % a.S, a.tp);
+        psp_block_at<true>(reinterpret_cast<char*>(lds), a, pb);
     }
 }
 
@@ -81,8 +88,7 @@ __global__ __launch_bounds__(640) void rotate_split_kernel(RqArgs a) {
                            (int)(blockIdx.x - t * G), a.K, a.n1, a.n2, a.R1p, a.R2p, a.xs, a.pmax, a.qsum);
     } else {
         const int pb = (int)(blockIdx.x - a.rot_blocks);
-        psp_block<true>(reinterpret_cast<char*>(lds), a.X, a.M, a.K, a.r, a.U, a.T, a.counters, a.partials, a.S,
-                        pb / a.S, pb % a.S, a.tp, false);
+        psp_block_at<true>(reinterpret_cast<char*>(lds), a, pb, false);
     }
 }
 
@@ -188,12 +194,14 @@ bwla_psp_plan bwla_make_psp_plan(int64_t M, int64_t K, int r) {
     const int rp = (r + 15) & ~15;
     // The projection rides in the rotation launch while that launch stays within about two
     // workgroups per CU: its short workgroups then finish in the shadow of the rotation.
-    const int64_t ride = M + ((M + 15) / 16) * ((K + PP_SLICE - 1) / PP_SLICE);
+    // (ranks of more than two 16-column tiles are dealt to several workgroups per slice)
+    const int jg = rp > 16 * PP_GROUPJT ? (rp / 16 + PP_GROUPJT - 1) / PP_GROUPJT : 1;
+    const int64_t ride = M + ((M + 15) / 16) * ((K + PP_SLICE - 1) / PP_SLICE) * jg;
     if (M <= 16 || r <= 0 || ride <= 512) {
         p.token_tiles = (int)((M + 15) / 16);
         p.k_per_split = PP_SLICE;
         p.splits = r > 0 ? (int)((K + PP_SLICE - 1) / PP_SLICE) : 1;
-        p.tile_rows = 16; p.tile_cols = rp; p.col_groups = 1;
+        p.tile_rows = 16; p.tile_cols = jg > 1 ? 16 * PP_GROUPJT : rp; p.col_groups = jg;
         return p;
     }
     // many tokens: about three workgroups per CU, slices a multiple of 128 (4 wavefronts x 32)
@@ -230,11 +238,12 @@ hipError_t bwla_launch_rotate_quant(const bwla_layer_t* L, const void* dX, int x
     a.counters = (int*)dws;
     a.partials = dws ? (float*)((char*)dws + bwla_psp_counter_bytes(M)) : nullptr;
     a.S = plan.splits;
+    a.JG = plan.tile_rows == 16 ? plan.col_groups : 1;
     a.xs = nullptr; a.pmax = nullptr;
     // Few tokens: one launch holds rotation and projection workgroups (a second launch would
     // cost more than it saves).  Many tokens: the projection has a kernel of its own.
     const bool merged = ru > 0 && plan.tile_rows == 16;
-    const int64_t pblocks = merged ? (int64_t)plan.token_tiles * plan.splits : 0;
+    const int64_t pblocks = merged ? (int64_t)plan.token_tiles * plan.splits * plan.col_groups : 0;
     const size_t plds = merged ? pp_lds_bytes(ru) : 0;
     a.rot_blocks = M;
     hipError_t e;
@@ -329,7 +338,7 @@ size_t bwla_split_rotation_bytes(const bwla_layer_t* L, const bwla_psp_plan& pla
     const RsShape rs = rs_shape(s3);
     if (!rs.ok) return 0;
     const bool merged = bwla_rank_u(L) > 0 && plan.tile_rows == 16;
-    const int64_t pblocks = merged ? (int64_t)plan.token_tiles * plan.splits : 0;
+    const int64_t pblocks = merged ? (int64_t)plan.token_tiles * plan.splits * plan.col_groups : 0;
     // every workgroup of the launch gets a CU of its own at once; with more tokens than that the
     // one-workgroup-per-token kernel keeps the chip busy anyway
     if (M * rs.G + pblocks > bwla_device_cus()) return 0;
