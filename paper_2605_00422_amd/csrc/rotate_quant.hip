@@ -339,9 +339,10 @@ size_t bwla_split_rotation_bytes(const bwla_layer_t* L, const bwla_psp_plan& pla
     if (!rs.ok) return 0;
     const bool merged = bwla_rank_u(L) > 0 && plan.tile_rows == 16;
     const int64_t pblocks = merged ? (int64_t)plan.token_tiles * plan.splits * plan.col_groups : 0;
-    // every workgroup of the launch gets a CU of its own at once; with more tokens than that the
-    // one-workgroup-per-token kernel keeps the chip busy anyway
-    if (M * rs.G + pblocks > bwla_device_cus()) return 0;
+    // up to two workgroups per CU (one after the other where LDS lets only one be resident):
+    // 224 x 128 at sixteen tokens 21.6 us against 31.2 in one workgroup per token, at thirty-two
+    // 34.5 against 32.0; with more tokens the one-workgroup-per-token kernel keeps the chip busy
+    if (M * rs.G + pblocks > 2 * bwla_device_cus()) return 0;
     return (size_t)(M * L->K + 2 * M * rs.E + M) * sizeof(float);     // values, extremes, per-token code offset
 }
 

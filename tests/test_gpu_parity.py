@@ -101,6 +101,7 @@ def test_cfg4_70b_gate_m4096_sampled_rows():
     (1, 9600, 128, 75, 64, 8, "bf16"),     # resident factors, long stage: split too; odd n2 (2-byte token loads)
     (2, 25600, 160, 160, 100, 16, "bf16"), # ten strips: 640-thread workgroups, ten slices per token
     (5, 8192, 128, 64, 300, 24, "bf16"),   # resident factors, up to eight tokens: split (40 rotation workgroups + projection)
+    (20, 28672, 224, 128, 64, 40, "bf16"), # two token tiles, more workgroups than CUs (280 rotation + 336 projection)
 ])
 def test_ragged_and_degenerate_shapes(M, K, n1, n2, N, r, xd):
     from parity_util import run_case
