@@ -75,7 +75,12 @@ __device__ __forceinline__ void r3_split3(const float (&f)[8], v8bf& h1, v8bf& h
 // wavefronts match.
 constexpr int R3_FILLR = 12;         // 16-byte pieces of the R1 terms a thread keeps in flight
 constexpr int R3_LOCAL_BARRIERS = 4;
-template <int ATM, bool LOOP, bool LOCAL = false>
+// DUAL (with LOOP): the workgroup has two sets of strip wavefronts, each with token rows and
+// reduction words of its own, which work on two tokens at a time with the one copy of the R1
+// terms in LDS: where LDS lets only one workgroup be resident, a SIMD then has two independent
+// MFMA chains to interleave instead of one.  Both sets pass the same barriers; a set without a
+// token left repeats the last one and stores nothing.
+template <int ATM, bool LOOP, bool LOCAL = false, bool DUAL = false>
 __device__ __forceinline__ void rotate3_token(char* lds, const uint16_t* __restrict__ X, int64_t t_first,
                                               int64_t t_stride, int64_t M, int64_t K, int n1, int n2,
                                               const uint16_t* __restrict__ R1p,
@@ -85,8 +90,11 @@ __device__ __forceinline__ void rotate3_token(char* lds, const uint16_t* __restr
                                               int tp = 0, float qmax = 31.0f, bool asym = false,
                                               bool shift = false) {
     const R3Shape sh = r3_shape(n1, n2);
-    const int tid = threadIdx.x, lane = tid & 63;
-    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);         // = strip
+    const int tid_all = threadIdx.x;
+    const int wv = __builtin_amdgcn_readfirstlane(tid_all >> 6);
+    const int grp = DUAL ? (wv >= sh.strips ? 1 : 0) : 0;              // which of the two tokens in flight
+    const int wave = wv - grp * sh.strips;                             // = strip
+    const int tid = tid_all - grp * 64 * sh.strips, lane = tid & 63;
     // the workgroup may have more wavefronts than strips (the projection workgroups of the same
     // launch use them): those only help to fetch the R1 terms, or leave at once
     // (more than 8 tiles along n1 never fit LDS whole: no code for them)
@@ -94,14 +102,15 @@ __device__ __forceinline__ void rotate3_token(char* lds, const uint16_t* __restr
     const bool helper = wave >= sh.strips;
     if (helper && !(early && !LOCAL)) return;
     const int nthreads = 64 * sh.strips;
+    const int nth_all = DUAL ? 2 * nthreads : nthreads;
     const int nfill = (early && !LOCAL) ? (int)blockDim.x : nthreads;
     RQTRACE_DECL;
     RQTRACE(0);
     const int li = lane & 15, lg = lane >> 4;
     const int n1p16 = sh.at * 16, n1p32 = sh.ch2 * 32, n2p32 = sh.k1 * 32;
-    char* vt = lds;                                                    // token rows, later the code image
-    char* cb = lds + sh.r0bytes;                                       // chunk buffers
-    float* red = reinterpret_cast<float*>(lds + sh.r0bytes + (size_t)(sh.alias ? 1 : sh.nbuf) * sh.cbytes);
+    char* vt = lds + grp * sh.r0bytes;                                 // token rows, later the code image
+    char* cb = lds + (DUAL ? 2 : 1) * sh.r0bytes;                      // chunk buffers
+    float* red = reinterpret_cast<float*>(cb + (size_t)(sh.alias ? 1 : sh.nbuf) * sh.cbytes) + grp * 64;
 
     // ---- packed R1 terms [term][n1p16][n1p32]: chunk ch = columns [32 ch, 32 ch + 32) of every row
     const int crow_items = 3 * n1p16 * 4;                              // 16-byte pieces per chunk
@@ -165,18 +174,18 @@ __device__ __forceinline__ void rotate3_token(char* lds, const uint16_t* __restr
     if (early) rp_issue();                             // first of all: the largest request of the token
     if (sh.resident && !early) {
         // all chunks at once, eight loads in flight per thread
-        for (int base = 0; base < total; base += 8 * nthreads) {
+        for (int base = 0; base < total; base += 8 * nth_all) {
             v4i tmp[8];
 #pragma unroll
             for (int e = 0; e < 8; ++e) {
-                const int g = base + e * nthreads + tid;
+                const int g = base + e * nth_all + tid_all;
                 const int gc = g < total ? g : total - 1;
                 const int ch = gc / crow_items;
                 tmp[e] = *chunk_src(ch, gc - ch * crow_items);
             }
 #pragma unroll
             for (int e = 0; e < 8; ++e) {
-                const int g = base + e * nthreads + tid;
+                const int g = base + e * nth_all + tid_all;
                 if (g < total) {
                     const int ch = g / crow_items;
                     *chunk_dst(ch, g - ch * crow_items) = tmp[e];
@@ -187,14 +196,17 @@ __device__ __forceinline__ void rotate3_token(char* lds, const uint16_t* __restr
     // LOOP: resident factors and many tokens -- the workgroup keeps the factors and walks over
     // tokens t_first, t_first + t_stride, ...  Otherwise one token per workgroup (the body below is
     // then straight-line code).
-    int64_t t = t_first;
+    // (DUAL: workgroup b takes tokens 2 b and 2 b + 1, then 2 (b + stride), ...)
+    int64_t tp0 = DUAL ? 2 * t_first : t_first;                         // first token of the round
 #pragma nounroll
     do {
+    const bool live = tp0 + grp < M;
+    const int64_t t = live ? tp0 + grp : M - 1;
     // In a loop, lane-derived values are recomputed per token from an opaque copy of the thread
     // index: otherwise every address of the body is hoisted out of the loop and kept in registers.
     int tid_opaque = threadIdx.x;
     if constexpr (LOOP) asm volatile("" : "+v"(tid_opaque));
-    const int tid = tid_opaque, lane = tid & 63, li = lane & 15, lg = lane >> 4;
+    const int tid = tid_opaque - grp * 64 * sh.strips, lane = tid & 63, li = lane & 15, lg = lane >> 4;
     // ---- R2 terms of my strip: rows d = 16*strip + li of the packed [term][n2p16][n2p32] planes
     // (read again for every token: kept across the token loop they would not fit the register
     // budget; the opaque zero keeps the loads inside the loop)
@@ -463,7 +475,7 @@ __device__ __forceinline__ void rotate3_token(char* lds, const uint16_t* __restr
     int* redi = reinterpret_cast<int*>(red) + 16;
     if (lane == 0) redi[wave] = lsum;
     __syncthreads();
-    if (!LOCAL || store_out) {
+    if ((!LOCAL || store_out) && live) {
         {
             const uint4* src = reinterpret_cast<const uint4*>(codes);
             uint4* dst = reinterpret_cast<uint4*>(q + t * K);
@@ -481,8 +493,8 @@ __device__ __forceinline__ void rotate3_token(char* lds, const uint16_t* __restr
     }
     RQTRACE(6);
     if constexpr (LOOP) __syncthreads();               // the code image and the reduction words are free again
-    t += t_stride;
-    } while (LOOP && t < M);
+    tp0 += DUAL ? 2 * t_stride : t_stride;
+    } while (LOOP && tp0 < M);
     RQTRACE_FLUSH;
 }
 

@@ -65,11 +65,11 @@ __global__ __launch_bounds__(RQ_THREADS) void rotate_quant_kernel(RqArgs a) {
 }
 
 // rotation on bf16 MFMA (bf16 activations): 64 threads per 16-column strip of n2
-template <int ATM, int THREADS, bool LOOP>
+template <int ATM, int THREADS, bool LOOP, bool DUAL = false>
 __global__ __launch_bounds__(THREADS) void rotate_quant3_kernel(RqArgs a) {
     extern __shared__ __align__(16) float lds[];
     if ((int64_t)blockIdx.x < a.rot_blocks) {
-        rotate3_token<ATM, LOOP>(reinterpret_cast<char*>(lds), reinterpret_cast<const uint16_t*>(a.X), blockIdx.x,
+        rotate3_token<ATM, LOOP, false, DUAL>(reinterpret_cast<char*>(lds), reinterpret_cast<const uint16_t*>(a.X), blockIdx.x,
                            a.rot_blocks, a.M, a.K, a.n1, a.n2, a.R1p, a.R2p, a.q, a.scale, a.qsum, true, a.tmode,
                            a.tp, a.qmax, a.asym != 0, a.shift != 0);
     } else {
@@ -92,17 +92,22 @@ __global__ __launch_bounds__(640) void rotate_split_kernel(RqArgs a) {
     }
 }
 
-template <int ATM, int THREADS, bool LOOP>
+template <int ATM, int THREADS, bool LOOP, bool DUAL = false>
 hipError_t launch_rotate3_v(const RqArgs& a, int64_t blocks, int threads, size_t lds, hipStream_t st) {
     static bwla_lds_attr attr;
-    hipError_t e = attr.ensure((const void*)rotate_quant3_kernel<ATM, THREADS, LOOP>, lds);
+    hipError_t e = attr.ensure((const void*)rotate_quant3_kernel<ATM, THREADS, LOOP, DUAL>, lds);
     if (e != hipSuccess) return e;
-    rotate_quant3_kernel<ATM, THREADS, LOOP><<<dim3((unsigned)blocks), dim3((unsigned)threads), lds, st>>>(a);
+    rotate_quant3_kernel<ATM, THREADS, LOOP, DUAL><<<dim3((unsigned)blocks), dim3((unsigned)threads), lds, st>>>(a);
     return hipGetLastError();
 }
-// the looping variant only when a workgroup really has more than one token
+// the looping variant only when a workgroup really has more than one token; `dual`: two tokens
+// at a time (the launcher has then doubled the threads and added the second token area to lds)
 template <int ATM, int THREADS>
-hipError_t launch_rotate3(const RqArgs& a, int64_t blocks, int threads, size_t lds, hipStream_t st) {
+hipError_t launch_rotate3(const RqArgs& a, int64_t blocks, int threads, size_t lds, hipStream_t st, bool dual) {
+    if (dual) {
+        if constexpr (ATM <= 8) return launch_rotate3_v<ATM, THREADS, true, true>(a, blocks, threads, lds, st);
+        else return hipErrorInvalidValue;
+    }
     if (a.rot_blocks < a.M) return launch_rotate3_v<ATM, THREADS, true>(a, blocks, threads, lds, st);
     return launch_rotate3_v<ATM, THREADS, false>(a, blocks, threads, lds, st);
 }
@@ -287,6 +292,8 @@ hipError_t bwla_launch_rotate_quant(const bwla_layer_t* L, const void* dX, int x
         int threads = (merged && s3.strips < 8) ? 512 : 64 * s3.strips;
         const size_t pl3 = merged ? pp_lds_bytes(ru, threads / 64) : 0;
         const size_t lds3 = pl3 > s3.lds_bytes ? pl3 : s3.lds_bytes;
+        bool dual = false;
+        size_t lds_dual = 0;
         // resident factors and many tokens: as many workgroups as fit the chip at once, each
         // walking over its share of the tokens with the factors loaded once
         if (s3.resident && !merged) {
@@ -296,14 +303,23 @@ hipError_t bwla_launch_rotate_quant(const bwla_layer_t* L, const void* dX, int x
             if (per_cu < 1) per_cu = 1;
             const int64_t cap = per_cu * bwla_device_cus();
             if (M > cap) a.rot_blocks = cap;
+            // only one workgroup of at most four wavefronts per CU (large factors): two tokens at a
+            // time per workgroup, if the second token's rows still fit
+            if (per_cu == 1 && M >= 2 * cap && s3.strips <= 4 && s3.at <= 8 &&
+                s3.lds_bytes + (size_t)s3.r0bytes + 256 <= RQ_LDS_LIMIT) {
+                dual = true;
+                threads = 2 * 64 * s3.strips;
+                lds_dual = s3.lds_bytes + (size_t)s3.r0bytes + 256;
+            }
         }
         if (s3.resident && a.rot_blocks == M && s3.strips < 8) threads = 512;
         // register budget: up to 8 wavefronts may use 256 VGPRs, 9 or 10 only 168
         const int64_t grid = a.rot_blocks + pblocks;
-        if (s3.strips <= 8 && s3.at <= 4) e = launch_rotate3<4, 512>(a, grid, threads, lds3, st);
-        else if (s3.strips <= 8 && s3.at <= 8) e = launch_rotate3<8, 512>(a, grid, threads, lds3, st);
-        else if (s3.at <= 12) e = launch_rotate3<12, 640>(a, grid, threads, lds3, st);
-        else e = launch_rotate3<16, 512>(a, grid, threads, lds3, st);
+        const size_t ldsl = dual ? lds_dual : lds3;
+        if (s3.strips <= 8 && s3.at <= 4) e = launch_rotate3<4, 512>(a, grid, threads, ldsl, st, dual);
+        else if (s3.strips <= 8 && s3.at <= 8) e = launch_rotate3<8, 512>(a, grid, threads, ldsl, st, dual);
+        else if (s3.at <= 12) e = launch_rotate3<12, 640>(a, grid, threads, ldsl, st, dual);
+        else e = launch_rotate3<16, 512>(a, grid, threads, ldsl, st, dual);
         if (e != hipSuccess) return e;
         if (ru > 0 && !merged) return bwla_launch_psp_prefill(L, dX, xdtype, M, dT, dws, plan, st);
         return hipSuccess;

@@ -62,6 +62,14 @@ def test_cfg1_7b_merged_projections(which):
     print(run_case(cfg), flush=True)
 
 
+def test_looping_rotation_two_tokens_at_a_time_odd_count():
+    """Large resident factors, M >= 512: a workgroup rotates two tokens at a time; with an odd
+    number of tokens the last pair is half empty."""
+    from parity_util import run_case
+    cfg = syn.LayerConfig("dual_515", 515, 8192, 128, 64, 48, 8, "bf16", 80, 20.0, seed=13)
+    print(run_case(cfg, rows=[0, 1, 2, 3, 255, 256, 257, 510, 511, 512, 513, 514]), flush=True)
+
+
 def test_cfg4_70b_gate_m4096_sampled_rows():
     from parity_util import run_case
     cfg = {c.name.split("_")[2]: c for c in syn.block70b_configs(4096)}["gate"]
