@@ -308,8 +308,9 @@ __device__ __forceinline__ void rotate3_token(char* lds, const uint16_t* __restr
         }
     }
     RQTRACE(1);
-    // (one token per workgroup: a barrier that leaves the loads of later stages in flight)
-    if constexpr (LOOP) __syncthreads(); else bwla_lds_barrier();
+    // (a barrier that orders LDS only: loads of later stages, and in a loop the stores of the
+    // round before, stay in flight)
+    bwla_lds_barrier();
     RQTRACE(2);
 
     // ---- stage 1
@@ -431,7 +432,7 @@ __device__ __forceinline__ void rotate3_token(char* lds, const uint16_t* __restr
         mn = -mx;
     }
     if (lane == 0) { red[wave] = mx; red[32 + wave] = mn; }
-    __syncthreads();                                   // also: every wave is done with the token rows
+    bwla_lds_barrier();                                // also: every wave is done with the token rows
     float hi = red[0];
     for (int w = 1; w < sh.strips; ++w) hi = fmaxf(hi, red[w]);
     float lo = -hi;
@@ -474,7 +475,7 @@ __device__ __forceinline__ void rotate3_token(char* lds, const uint16_t* __restr
     lsum = bwla_wave_sum_i32(lsum);
     int* redi = reinterpret_cast<int*>(red) + 16;
     if (lane == 0) redi[wave] = lsum;
-    __syncthreads();
+    bwla_lds_barrier();
     if ((!LOCAL || store_out) && live) {
         {
             const uint4* src = reinterpret_cast<const uint4*>(codes);
@@ -492,7 +493,9 @@ __device__ __forceinline__ void rotate3_token(char* lds, const uint16_t* __restr
         }
     }
     RQTRACE(6);
-    if constexpr (LOOP) __syncthreads();               // the code image and the reduction words are free again
+    // the code image and the reduction words are free again (LDS only: the round's stores to
+    // global memory need not have landed)
+    if constexpr (LOOP) bwla_lds_barrier();
     tp0 += DUAL ? 2 * t_stride : t_stride;
     } while (LOOP && tp0 < M);
     RQTRACE_FLUSH;
