@@ -109,6 +109,10 @@ def test_cfg4_70b_gate_m4096_sampled_rows():
     (1, 9600, 128, 75, 64, 8, "bf16"),     # resident factors, long stage: split too; odd n2 (2-byte token loads)
     (2, 25600, 160, 160, 100, 16, "bf16"), # ten strips: 640-thread workgroups, ten slices per token
     (5, 8192, 128, 64, 300, 24, "bf16"),   # resident factors, up to eight tokens: split (40 rotation workgroups + projection)
+    # projection of more than two 16-column rank tiles: dealt to several workgroups per slice
+    (7, 1024, 32, 32, 100, 40, "f32"),     # fp32 activations, two slices, three rank tiles in two groups
+    (3, 512, 16, 32, 64, 48, "bf16"),      # a single slice: the groups write T themselves
+    (12, 4096, 64, 64, 200, 128, "bf16"),  # the largest rank: four groups of two tiles
     (20, 28672, 224, 128, 64, 40, "bf16"), # two token tiles, more workgroups than CUs (280 rotation + 336 projection)
 ])
 def test_ragged_and_degenerate_shapes(M, K, n1, n2, N, r, xd):
@@ -163,6 +167,8 @@ def test_row_shift_with_eight_bit_codes():
     (6, True, 300, 1152, 36, 32, 200, 20, "bf16"),   # prefill kernels
     (6, False, 2, 20000, 200, 100, 48, 4, "bf16"),   # split rotation
     (6, True, 3, 16896, 176, 96, 80, 0, "bf16"),     # split rotation, shift, no PSP: the three mode columns only
+    (6, True, 1, 11008, 128, 86, 64, 40, "bf16"),    # split rotation with resident factors, projection in groups
+    (6, True, 515, 8192, 128, 64, 40, 8, "bf16"),    # looping rotation, two tokens at a time, odd token count
     (4, False, 40, 1024, 32, 32, 200, 16, "bf16"),   # A4
     (7, True, 5, 2048, 32, 64, 333, 8, "bf16"),      # the widest the offset form allows
 ])
