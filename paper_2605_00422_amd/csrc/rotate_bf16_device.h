@@ -433,18 +433,26 @@ __device__ __forceinline__ void rotate3_token(char* lds, const uint16_t* __restr
     }
     if (lane == 0) { red[wave] = mx; red[32 + wave] = mn; }
     bwla_lds_barrier();                                // also: every wave is done with the token rows
-    float hi = red[0];
-    for (int w = 1; w < sh.strips; ++w) hi = fmaxf(hi, red[w]);
+    // over the strips (at most ten): one word per lane of a 16-lane row, four exchange steps
+    const int s16 = lane & 15;
+    float hi = s16 < sh.strips ? red[s16] : 0.0f;
+#pragma unroll
+    for (int off = 8; off > 0; off >>= 1) hi = fmaxf(hi, __shfl_xor(hi, off, 64));
     float lo = -hi;
     if (asym) {
-        lo = red[32];
-        for (int w = 1; w < sh.strips; ++w) lo = fminf(lo, red[32 + w]);
+        lo = s16 < sh.strips ? red[32 + s16] : 0.0f;
+#pragma unroll
+        for (int off = 8; off > 0; off >>= 1) lo = fminf(lo, __shfl_xor(lo, off, 64));
     }
     const QuantPlan qp = quant_plan(hi, lo, qmax, asym);
     RQTRACE(5);
 
     // ---- quantize: lane holds Yt[d = 16*strip + 4*lg + v][c = 16*tc + li], four consecutive d of one c
+    // (one token per workgroup and rows of whole words: the codes go straight to global memory,
+    // 16 bytes of a row per lane group; else through an image in LDS and out in 16-byte pieces)
     int8_t* codes = reinterpret_cast<int8_t*>(vt);
+    const bool direct = !LOOP && !LOCAL && (n2 & 3) == 0;
+    int8_t* qrow = q + t * K;
     int lsum = 0;
     const int d0 = wave * 16 + 4 * lg;
 #pragma unroll
@@ -457,8 +465,10 @@ __device__ __forceinline__ void rotate3_token(char* lds, const uint16_t* __restr
             if (c < n1) {
                 if ((n2 & 3) == 0) {
                     if (d0 < n2) {
-                        *reinterpret_cast<int*>(codes + c * n2 + d0) = (code[0] & 0xff) | ((code[1] & 0xff) << 8) |
-                                                                        ((code[2] & 0xff) << 16) | (code[3] << 24);
+                        const int word = (code[0] & 0xff) | ((code[1] & 0xff) << 8) | ((code[2] & 0xff) << 16) |
+                                         (code[3] << 24);
+                        if (direct) *reinterpret_cast<int*>(qrow + c * n2 + d0) = word;
+                        else *reinterpret_cast<int*>(codes + c * n2 + d0) = word;
                         lsum += code[0] + code[1] + code[2] + code[3];
                     }
                 } else {
@@ -477,19 +487,22 @@ __device__ __forceinline__ void rotate3_token(char* lds, const uint16_t* __restr
     if (lane == 0) redi[wave] = lsum;
     bwla_lds_barrier();
     if ((!LOCAL || store_out) && live) {
-        {
+        if (!direct) {
             const uint4* src = reinterpret_cast<const uint4*>(codes);
             uint4* dst = reinterpret_cast<uint4*>(q + t * K);
             const int n16 = (int)(K >> 4);
             for (int idx = tid; idx < n16; idx += nthreads) dst[idx] = src[idx];
         }
-        if (tid == 0) {
-            int tot = 0;
-            for (int w = 0; w < sh.strips; ++w) tot += redi[w];
-            qsum[t] = tot;
-            const float sc = quant_scale(hi, lo, qmax, asym);
-            scale[t] = sc;
-            quant_extras(tmode, tp, t, asym, shift, qp, sc, tot, K);
+        if (wave == 0) {
+            int tot = s16 < sh.strips ? redi[s16] : 0;
+#pragma unroll
+            for (int off = 8; off > 0; off >>= 1) tot += __shfl_xor(tot, off, 64);
+            if (lane == 0) {
+                qsum[t] = tot;
+                const float sc = quant_scale(hi, lo, qmax, asym);
+                scale[t] = sc;
+                quant_extras(tmode, tp, t, asym, shift, qp, sc, tot, K);
+            }
         }
     }
     RQTRACE(6);
