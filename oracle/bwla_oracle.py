@@ -26,6 +26,9 @@ dequantization: W_deq = delta_n Sign(W - mu_n) + mu_n, so Y = s_t (delta_n acc +
 with qsum_t the sum of the token's codes (binarize_rows_centered, dequant_output_centered,
 forward(..., centered=True)).
 
+Block chaining: swiglu_interleaved is the gate between the merged gate|up projection and the down
+projection of the MLP blocks the paper quantizes; to_bf16 the storage grid its result is kept on.
+
 Pins (tests/test_oracle_pins.py, no GPU): every function below is checked against something
 other than itself -- the dense Kronecker product, norm preservation and forward invariance,
 hand-derived worked values, the closed-form optimal scale and its residual, brute-force loops,
@@ -352,6 +355,33 @@ def forward_loops(X, R1, R2, W_rot, U, V) -> np.ndarray:
 
 
 # --------------------------------------------------------------------------- accounting
+# --------------------------------------------------------------------------- gated MLP (block chaining)
+def to_bf16(a: np.ndarray) -> np.ndarray:
+    """Round to the bfloat16 grid (nearest, ties to even) and return as fp64.  bfloat16 is the
+    upper half of an fp32 word: round the fp64 value to fp32 first only where that is exact
+    enough -- here the rounding is done on the fp64 value directly, by scaling to the 8-bit
+    significand, so that no double rounding can occur."""
+    a = np.asarray(a, dtype=np.float64)
+    out = np.zeros_like(a)
+    nz = (a != 0) & np.isfinite(a)
+    m, e = np.frexp(a[nz])                     # a = m * 2^e, 0.5 <= |m| < 1
+    out[nz] = np.ldexp(np.rint(m * 256.0), e - 8)   # 8 significant bits; np.rint rounds ties to even
+    out[~np.isfinite(a)] = a[~np.isfinite(a)]
+    return out
+
+
+def swiglu_interleaved(Y: np.ndarray) -> np.ndarray:
+    """The gate of the MLP blocks of the models the paper quantizes (their up, gate and down
+    projections: paper App., loss trajectories of the MLP blocks): h = silu(g) * u with
+    silu(g) = g / (1 + exp(-g)).  The nonlinearity is the model's, not the paper's method.
+    Y holds the outputs of a layer whose rows interleave the two projections: column 2 i is
+    gate channel i, column 2 i + 1 is up channel i.  Returns h (fp64, not rounded), [M, N / 2]."""
+    Y = np.asarray(Y, dtype=np.float64)
+    g, u = Y[:, 0::2], Y[:, 1::2]
+    with np.errstate(over="ignore"):
+        return g / (1.0 + np.exp(-g)) * u
+
+
 def effective_weight_bits(N: int, K: int, n1: int, n2: int, r: int) -> float:
     """Stored bits per weight of one packed layer: 1 sign bit, fp16 scale per row, fp16 PSP
     factors U (K,r) and V (N,r), fp32 Kronecker factors (paper Table 1 reports 1.15-1.19)."""

@@ -526,6 +526,47 @@ def test_quantized_path_tracks_the_unquantized_layer():
 
 
 # ------------------------------------------------------------------ storage accounting (paper Table 1)
+def test_swiglu_hand_values_identities_and_interleaving():
+    """silu at hand-computed points, its odd-part identity silu(x) - silu(-x) = x, its limits, the
+    order of the two operands (gate goes through silu, up does not) and the column interleaving."""
+    Y = np.array([[1.0, 1.0, 2.0, 3.0, 3.0, 2.0, 0.0, 5.0, -1.0, 4.0]])
+    h = orc.swiglu_interleaved(Y)
+    assert h.shape == (1, 5)
+    e = math.e
+    want = [1.0 / (1.0 + 1.0 / e), 2.0 / (1.0 + e ** -2) * 3.0, 3.0 / (1.0 + e ** -3) * 2.0, 0.0,
+            -1.0 / (1.0 + e) * 4.0]
+    assert np.allclose(h[0], want, rtol=1e-15, atol=0)
+    assert abs(h[0, 0] - 0.7310585786300049) < 1e-15          # silu(1), tabulated logistic value
+    assert abs(h[0, 1] - h[0, 2]) > 0.4                       # swapping gate and up changes the result
+    x = np.linspace(-30, 30, 241)
+    silu = lambda v: orc.swiglu_interleaved(np.stack([v, np.ones_like(v)], axis=1).reshape(1, -1))[0]
+    assert np.allclose(silu(x) - silu(-x), x, rtol=0, atol=1e-13)
+    assert np.allclose(silu(np.array([40.0, 700.0])), [40.0, 700.0], rtol=1e-15)
+    assert np.all(np.abs(silu(np.array([-40.0, -700.0, -800.0]))) < 1e-15)   # exp overflows to inf: -0
+    # minimum of silu: at x0 with x0 + 1 + exp(-x0)... = 0, value about -0.27846
+    assert abs(silu(x).min() - (-0.2784645)) < 1e-4
+    # linear in the up operand
+    Y2 = Y.copy(); Y2[:, 1::2] *= -2.5
+    assert np.allclose(orc.swiglu_interleaved(Y2), -2.5 * h, rtol=1e-15)
+
+
+def test_to_bf16_rounds_to_nearest_even_on_eight_bits():
+    """bfloat16 keeps 8 significant bits: spot values around 1 (spacing 2^-7), ties to even, and
+    agreement with the input generator's fp32 bit trick on fp32-representable values."""
+    u = 2.0 ** -7
+    vals = np.array([1.0, 1.0 + u, 1.0 + 0.5 * u, 1.0 + 1.5 * u, 1.0 + 0.49 * u, 1.0 + 0.51 * u, -3.0 - 2 * u, 0.0])
+    want = np.array([1.0, 1.0 + u, 1.0, 1.0 + 2 * u, 1.0, 1.0 + u, -3.0 - 2 * u, 0.0])
+    assert np.array_equal(orc.to_bf16(vals), want)
+    rng = np.random.default_rng(3)
+    x = (rng.standard_normal(5000) * np.exp(rng.uniform(-20, 20, 5000))).astype(np.float32)
+    assert np.array_equal(orc.to_bf16(x.astype(np.float64)), syn.round_to_bf16(x).astype(np.float64))
+    # a value that double rounding (fp64 -> fp32 -> bf16) would get wrong: just above a bf16 tie,
+    # by less than half an fp32 ulp
+    t = 1.0 + 0.5 * u + 2.0 ** -30
+    assert orc.to_bf16(np.array([t]))[0] == 1.0 + u
+    assert syn.round_to_bf16(np.array([t], dtype=np.float32))[0] == 1.0
+
+
 def test_effective_bits_in_paper_band():
     lo, hi = (float(v) for v in open(os.path.join(GOLDEN, "effective_bits.txt")).read().split("\n")[-2].split())
     b = orc.effective_weight_bits(11008, 4096, 64, 64, 32)
