@@ -229,6 +229,28 @@ bwla_status_t bwla_decode_forward(const bwla_layer_t* layer, const void* d_X, in
                                   void* d_ws, size_t ws_bytes, float* d_Y, int32_t* d_acc,
                                   void* stream);
 
+/*
+ * bwla_linear_forward for the merged gate|up projection of an MLP block, with the block's gate
+ * applied before anything is stored (the models the paper quantizes have up, gate and down
+ * projections in their MLP blocks: paper App., loss trajectories of the MLP blocks; the
+ * nonlinearity is the model's, not the paper's method).  The layer's rows interleave the two
+ * projections: packed row 2 i is gate channel i, row 2 i + 1 is up channel i (N even, else
+ * BWLA_ERR_SHAPE; the caller stacks W, alpha, V that way before bwla_pack_weights).  With Y as
+ * bwla_linear_forward defines it,
+ *   H[t, i] = silu(Y[t, 2 i]) * Y[t, 2 i + 1],  silu(g) = g / (1 + exp(-g)),
+ * evaluated in fp32 and rounded to bfloat16 (nearest even): the activation format that
+ * bwla_rotate_quant of the down projection reads.
+ *   d_H      out, M x N / 2 bfloat16, 16-byte aligned
+ *   d_ws     scratch of ws_bytes >= bwla_swiglu_workspace_size(layer, M): 0 for up to 16 tokens
+ *            (the decode kernel gates in its epilogue and Y never exists), else M x N fp32 for Y
+ *            (NULL allowed when 0); not kept between calls
+ * Other arguments and errors as bwla_linear_forward.
+ */
+bwla_status_t bwla_swiglu_workspace_size(const bwla_layer_t* layer, int64_t M, size_t* bytes);
+bwla_status_t bwla_linear_forward_swiglu(const bwla_layer_t* layer, const int8_t* d_q, const float* d_scale,
+                                         const int32_t* d_qsum, const float* d_T, int64_t M, void* d_H,
+                                         void* d_ws, size_t ws_bytes, void* stream);
+
 #ifdef __cplusplus
 }
 #endif

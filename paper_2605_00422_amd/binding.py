@@ -18,7 +18,8 @@ BWLA_MODE_ROW_SHIFT, BWLA_MODE_ASYM_ACT = 1, 2
 EXPORTS = ["bwla_status_string", "bwla_version", "bwla_kron_factor", "bwla_packed_size", "bwla_pack_weights",
            "bwla_unpack_signs", "bwla_psp_workspace_size", "bwla_rotate_quant", "bwla_code_sums",
            "bwla_linear_forward", "bwla_decode_forward", "bwla_packed_size_centered", "bwla_pack_weights_centered", "bwla_rotate_quant_bits",
-           "bwla_packed_size_mode", "bwla_pack_weights_mode"]
+           "bwla_packed_size_mode", "bwla_pack_weights_mode", "bwla_swiglu_workspace_size",
+           "bwla_linear_forward_swiglu"]
 
 
 class BwlaLayer(Structure):
@@ -70,6 +71,9 @@ def load() -> ctypes.CDLL:
                                         c_void_p, c_void_p, c_void_p]
     lib.bwla_decode_forward.argtypes = [POINTER(BwlaLayer), c_void_p, c_int, c_int64, c_void_p, c_void_p, c_void_p,
                                         c_void_p, c_void_p, c_size_t, c_void_p, c_void_p, c_void_p]
+    lib.bwla_swiglu_workspace_size.argtypes = [POINTER(BwlaLayer), c_int64, POINTER(c_size_t)]
+    lib.bwla_linear_forward_swiglu.argtypes = [POINTER(BwlaLayer), c_void_p, c_void_p, c_void_p, c_void_p, c_int64,
+                                               c_void_p, c_void_p, c_size_t, c_void_p]
     for name in EXPORTS:
         if name not in ("bwla_status_string", "bwla_version"):
             getattr(lib, name).restype = c_int
@@ -215,6 +219,21 @@ def decode_forward(layer: PackedLayer, X, act: Activations, Y, acc=None):
 
 def code_sums(q, qsum) -> None:
     _check(load().bwla_code_sums(_ptr(q), q.shape[0], q.shape[1], _ptr(qsum), _stream()), "bwla_code_sums")
+
+
+def swiglu_workspace_size(layer: PackedLayer, M: int) -> int:
+    out = c_size_t()
+    _check(load().bwla_swiglu_workspace_size(byref(layer.desc), M, byref(out)), "bwla_swiglu_workspace_size")
+    return out.value
+
+
+def linear_forward_swiglu(layer: PackedLayer, act: Activations, H, ws=None):
+    """H (bf16, M x N/2) = silu(gate) * up of a layer whose rows interleave gate and up channels."""
+    nbytes = 0 if ws is None else ws.numel() * ws.element_size()
+    _check(load().bwla_linear_forward_swiglu(byref(layer.desc), _ptr(act.q), _ptr(act.scale), _ptr(act.qsum),
+                                             _ptr(act.T), act.M, _ptr(H), _ptr(ws), nbytes, _stream()),
+           "bwla_linear_forward_swiglu")
+    return H
 
 
 def linear_forward(layer: PackedLayer, act: Activations, Y, acc=None):

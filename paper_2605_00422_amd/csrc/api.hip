@@ -261,4 +261,36 @@ bwla_status_t bwla_linear_forward(const bwla_layer_t* layer, const int8_t* d_q, 
     return e == hipSuccess ? BWLA_OK : BWLA_ERR_HIP;
 }
 
+bwla_status_t bwla_swiglu_workspace_size(const bwla_layer_t* layer, int64_t M, size_t* bytes) {
+    if (!bytes) return BWLA_ERR_NULL;
+    bwla_status_t s = check_layer(layer);
+    if (s != BWLA_OK) return s;
+    if (M <= 0 || M > (int64_t)1 << 24 || (layer->N & 1) != 0) return BWLA_ERR_SHAPE;
+    *bytes = bwla_gemm_decode_bs_supported(M, layer->K, layer->r)
+                 ? 0 : (size_t)bwla_align256((uint64_t)M * (uint64_t)layer->N * sizeof(float));
+    return BWLA_OK;
+}
+
+bwla_status_t bwla_linear_forward_swiglu(const bwla_layer_t* layer, const int8_t* d_q, const float* d_scale,
+                                         const int32_t* d_qsum, const float* d_T, int64_t M, void* d_H,
+                                         void* d_ws, size_t ws_bytes, void* stream) {
+    size_t need = 0;
+    bwla_status_t s = bwla_swiglu_workspace_size(layer, M, &need);
+    if (s != BWLA_OK) return s;
+    if (!d_q || !d_scale || !d_qsum || !d_H) return BWLA_ERR_NULL;
+    if (layer->r > 0 && !d_T) return BWLA_ERR_NULL;
+    if (need > 0 && !d_ws) return BWLA_ERR_NULL;
+    if (ws_bytes < need) return BWLA_ERR_BUFSIZE;
+    if (!aligned16(d_q) || !aligned16(d_H) || (d_T && !aligned16(d_T)) || (need > 0 && !aligned16(d_ws)))
+        return BWLA_ERR_ALIGN;
+    hipStream_t st = (hipStream_t)stream;
+    if (need == 0)      // the decode kernel gates in its epilogue: no M x N intermediate exists
+        return bwla_launch_gemm_decode_bs(layer, d_q, d_scale, d_qsum, d_T, M, nullptr, nullptr, st,
+                                          (uint16_t*)d_H) == hipSuccess ? BWLA_OK : BWLA_ERR_HIP;
+    s = bwla_linear_forward(layer, d_q, d_scale, d_qsum, d_T, M, (float*)d_ws, nullptr, stream);
+    if (s != BWLA_OK) return s;
+    return bwla_launch_swiglu_rows((const float*)d_ws, M, layer->N, (uint16_t*)d_H, st) == hipSuccess ? BWLA_OK
+                                                                                                    : BWLA_ERR_HIP;
+}
+
 }  // extern "C"

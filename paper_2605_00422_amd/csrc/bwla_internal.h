@@ -121,13 +121,16 @@ hipError_t bwla_launch_gemm_decode(const bwla_layer_t* L, const int8_t* dq, cons
                                    const int32_t* dqsum, const float* dT, int64_t M, float* dY,
                                    int32_t* dacc, hipStream_t st);
 bool bwla_gemm_decode_bs_supported(int64_t M, int64_t K, int r);
+// (dH not NULL: gated output h as bf16, M x N / 2, instead of Y -- see bwla_linear_forward_swiglu)
 hipError_t bwla_launch_gemm_decode_bs(const bwla_layer_t* L, const int8_t* dq, const float* dscale,
                                       const int32_t* dqsum, const float* dT, int64_t M, float* dY,
-                                      int32_t* dacc, hipStream_t st);
+                                      int32_t* dacc, hipStream_t st, uint16_t* dH = nullptr);
 // explicit launch shape (tiles per step 1/2, grid size, prefetch depth 2/4)
 hipError_t bwla_launch_gemm_decode_bs_cfg(const bwla_layer_t* L, const int8_t* dq, const float* dscale,
                                           const int32_t* dqsum, const float* dT, int64_t M, float* dY,
-                                          int32_t* dacc, hipStream_t st, int nt, int grid, int depth);
+                                          int32_t* dacc, hipStream_t st, int nt, int grid, int depth,
+                                          uint16_t* dH = nullptr);
+hipError_t bwla_launch_swiglu_rows(const float* dY, int64_t M, int64_t N, uint16_t* dH, hipStream_t st);
 hipError_t bwla_launch_gemm_prefill(const bwla_layer_t* L, const int8_t* dq, const float* dscale,
                                     const int32_t* dqsum, const float* dT, int64_t M, float* dY,
                                     int32_t* dacc, hipStream_t st);

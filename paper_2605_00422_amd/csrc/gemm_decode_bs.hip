@@ -61,7 +61,8 @@ bool bwla_gemm_decode_bs_supported(int64_t M, int64_t K, int r) {
 // explicit launch shape: nt tiles per step (1 or 2), grid size, prefetch depth (2 or 4)
 hipError_t bwla_launch_gemm_decode_bs_cfg(const bwla_layer_t* L, const int8_t* dq, const float* dscale,
                                           const int32_t* dqsum, const float* dT, int64_t M, float* dY,
-                                          int32_t* dacc, hipStream_t st, int nt, int grid, int depth) {
+                                          int32_t* dacc, hipStream_t st, int nt, int grid, int depth,
+                                          uint16_t* dH) {
     const char* blob = (const char*)L->d_blob;
     const int chunks = (int)bwla_chunks(L->K), row_tiles = (int)bwla_row_tiles(L->N);
     const int cpw = bs_cpw_for(chunks), passes = bs_passes_for(chunks);
@@ -82,7 +83,7 @@ hipError_t bwla_launch_gemm_decode_bs_cfg(const bwla_layer_t* L, const int8_t* d
     const size_t lds = bs_lds_bytes(direct ? 0 : M, chunks, rp, nt, pass_units);
     BsArgs a{(const uint4*)(blob + L->off_bits), chunks, row_tiles, dq, (int)M, (int)L->K, dscale, dqsum,
              (const __half*)(blob + L->off_alpha), (const __half*)(blob + L->off_V), dT, L->r, dY, (int)L->N,
-             dacc, KS, direct, passes};
+             dacc, KS, direct, passes, dH};
     auto launch = [&](auto kern) -> hipError_t {
         static bwla_lds_attr attr;
         hipError_t e = attr.ensure((const void*)kern, lds);
@@ -115,7 +116,7 @@ hipError_t bwla_launch_gemm_decode_bs_cfg(const bwla_layer_t* L, const int8_t* d
 
 hipError_t bwla_launch_gemm_decode_bs(const bwla_layer_t* L, const int8_t* dq, const float* dscale,
                                       const int32_t* dqsum, const float* dT, int64_t M, float* dY,
-                                      int32_t* dacc, hipStream_t st) {
+                                      int32_t* dacc, hipStream_t st, uint16_t* dH) {
     const int chunks = (int)bwla_chunks(L->K), row_tiles = (int)bwla_row_tiles(L->N);
     const int cus = bwla_device_cus();
     // Measured on MI355X: one tile per step and one workgroup per CU is the best shape for all
@@ -125,7 +126,23 @@ hipError_t bwla_launch_gemm_decode_bs(const bwla_layer_t* L, const int8_t* dq, c
     const int units = (row_tiles + nt - 1) / nt;
     const int grid = units < cus ? units : cus;
     (void)chunks;
-    return bwla_launch_gemm_decode_bs_cfg(L, dq, dscale, dqsum, dT, M, dY, dacc, st, nt, grid, 2);
+    return bwla_launch_gemm_decode_bs_cfg(L, dq, dscale, dqsum, dT, M, dY, dacc, st, nt, grid, 2, dH);
+}
+
+namespace {
+// h[t, i] = silu(Y[t, 2 i]) * Y[t, 2 i + 1] as bf16, for the GEMM kernels that do not gate in their epilogue
+__global__ void swiglu_rows_kernel(const float* __restrict__ Y, int64_t pairs, uint16_t* __restrict__ H) {
+    const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i >= pairs) return;
+    const float2 gu = reinterpret_cast<const float2*>(Y)[i];
+    H[i] = (uint16_t)bs_swiglu_bf16(gu.x, gu.y);
+}
+}  // namespace
+
+hipError_t bwla_launch_swiglu_rows(const float* dY, int64_t M, int64_t N, uint16_t* dH, hipStream_t st) {
+    const int64_t pairs = M * (N / 2);
+    swiglu_rows_kernel<<<dim3((unsigned)((pairs + 255) / 256)), dim3(256), 0, st>>>(dY, pairs, dH);
+    return hipGetLastError();
 }
 
 int bwla_device_cus() {

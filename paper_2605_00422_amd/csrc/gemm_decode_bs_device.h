@@ -37,7 +37,14 @@ struct BsArgs {
     int direct;      // stand-alone kernel: compute waves load their codes straight from global memory
                      // (else the code rows are staged in LDS first)
     int passes;      // rows longer than KS * CPW chunks are contracted in this many passes (else 1)
+    uint16_t* H;     // not NULL: the rows interleave a gate and an up projection; instead of Y the
+                     // kernel stores h[t, i] = silu(y[t, 2 i]) * y[t, 2 i + 1] as bf16, M x N / 2
 };
+// the gate of an MLP block on two neighbouring outputs (gate, up), rounded to bf16 (nearest even)
+__device__ __forceinline__ uint32_t bs_swiglu_bf16(float g, float u) {
+    const float h = g / (1.0f + __expf(-g)) * u;
+    return (uint32_t)__builtin_bit_cast(uint16_t, (__bf16)h);
+}
 
 // Fused single-launch decode (one token, r = 0): the workgroup has rotated and quantized the token
 // itself, so the codes, the scale and the code sum come from its own LDS.
@@ -445,7 +452,19 @@ __device__ __forceinline__ void epilogue_wave(const BsArgs& a, char* smem, int f
                 y[v] = st * al[v] * (float)ai[v] + (low0[v] + low1[v]) * tinv;
             }
             const int nb = tile * 16 + 4 * lg;
-            if (FAST) {
+            if (a.H != nullptr) {
+                // (N is even; a pair never straddles the end of a row)
+                if (tok_ok) {
+                    uint16_t* hrow = a.H + (int64_t)t * (N >> 1) + (nb >> 1);
+                    if (FAST) {
+                        if (nb < N)
+                            *reinterpret_cast<uint32_t*>(hrow) = bs_swiglu_bf16(y[0], y[1]) | (bs_swiglu_bf16(y[2], y[3]) << 16);
+                    } else {
+                        if (nb + 1 < N) hrow[0] = (uint16_t)bs_swiglu_bf16(y[0], y[1]);
+                        if (nb + 3 < N) hrow[1] = (uint16_t)bs_swiglu_bf16(y[2], y[3]);
+                    }
+                }
+            } else if (FAST) {
                 if (tok_ok && nb < N)
                     *reinterpret_cast<float4*>(a.Y + (int64_t)t * N + nb) = make_float4(y[0], y[1], y[2], y[3]);
             } else if (tok_ok) {

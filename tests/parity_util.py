@@ -283,3 +283,58 @@ def run_case_asym(cfg: syn.LayerConfig, centered: bool = False, act_bits: int = 
     assert out["same_codes"]["fro"] < 1e-5
     out["end_to_end"] = check_output(Y.cpu().numpy(), ref["Y"])
     return out
+
+
+def interleave_rows(a: np.ndarray, b: np.ndarray) -> np.ndarray:
+    """Rows 2 i = a[i], rows 2 i + 1 = b[i]."""
+    out = np.empty((2 * a.shape[0],) + a.shape[1:], dtype=a.dtype)
+    out[0::2], out[1::2] = a, b
+    return out
+
+
+def run_case_swiglu(cfg: syn.LayerConfig, rows=None) -> dict:
+    """bwla_linear_forward_swiglu on a layer whose rows interleave a gate and an up projection
+    (cfg.N rows in all: the synthetic layer's first half serves as gate, its second half as up),
+    against the oracle's forward followed by its swiglu_interleaved.
+    Bar: H is a bfloat16 image of fp32 values that meet criterion 3, so against the oracle's
+    unrounded h its error is that of criterion 3 plus one bfloat16 rounding (relative 2^-9 at most,
+    2^-9 / sqrt(3) in the root mean square): relative Frobenius error <= 2.5e-3, and per element
+    |error| <= 2^-8 |h| + 1e-2 max_row |h| (the rounding, and criterion 3's per-token bound)."""
+    assert cfg.N % 2 == 0
+    d = syn.make_layer(cfg)
+    half = cfg.N // 2
+    W = interleave_rows(d.W[:half], d.W[half:])
+    V = interleave_rows(d.V[:half], d.V[half:]) if cfg.r > 0 else None
+    U = d.U if cfg.r > 0 else None
+    sel = np.arange(cfg.M) if rows is None else np.asarray(rows)
+    sgn, alpha = orc.binarize_rows(W)
+    ref = orc.forward_rows(d.X, d.R1, d.R2, sgn, orc.to_fp16(alpha), U, V, sel)
+    h_ref = orc.swiglu_interleaved(ref["Y"])
+
+    layer = B.pack_weights(to_dev(W), to_dev(d.R1), to_dev(d.R2), None if U is None else to_dev(U),
+                           None if V is None else to_dev(V), cfg.n1, cfg.n2)
+    X = x_on_gpu(d)
+    act = B.Activations(layer, cfg.M)
+    B.rotate_quant(layer, X, act)
+    nws = B.swiglu_workspace_size(layer, cfg.M)
+    ws = torch.empty(nws, dtype=torch.uint8, device=DEV) if nws else None
+    H = torch.full((cfg.M, half), float("nan"), dtype=torch.bfloat16, device=DEV)
+    B.linear_forward_swiglu(layer, act, H, ws)
+    torch.cuda.synchronize()
+    Hs = H[torch.from_numpy(sel).to(DEV)].float().cpu().numpy().astype(np.float64)
+    assert np.all(np.isfinite(Hs))
+    err = Hs - h_ref
+    fro = float(np.linalg.norm(err) / max(np.linalg.norm(h_ref), 1e-300))
+    rowmax = np.maximum(np.max(np.abs(h_ref), axis=1, keepdims=True), 1e-300)
+    excess = float(np.max(np.abs(err) - (2.0 ** -8 * np.abs(h_ref) + 1e-2 * rowmax)))
+    assert fro <= 2.5e-3, f"relative Frobenius error of h {fro:.3e}"
+    assert excess <= 0.0, f"element error exceeds its bound by {excess:.3e}"
+    # the same values as the ungated output of the same codes, gated on the host in fp32: the stored
+    # bf16 may differ from that by one unit in the last place at most (exp is not the same routine)
+    Y = torch.empty((cfg.M, cfg.N), dtype=torch.float32, device=DEV)
+    B.linear_forward(layer, act, Y)
+    g, u = Y[:, 0::2], Y[:, 1::2]
+    own = (g / (1.0 + torch.exp(-g)) * u).to(torch.bfloat16)
+    ulp = (H.view(torch.int16).int() - own.view(torch.int16).int()).abs().max().item()
+    assert ulp <= 1, f"fused gate differs from the gated fp32 output by {ulp} bf16 steps"
+    return dict(cfg=cfg.name, fro=fro, ws=nws, ulp=ulp)

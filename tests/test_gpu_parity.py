@@ -180,6 +180,24 @@ def test_asymmetric_activation_codes(bits, centered, M, K, n1, n2, N, r, xd):
     print(run_case_asym(cfg, centered=centered, act_bits=bits), flush=True)
 
 
+@pytest.mark.parametrize("M,K,n1,n2,N,r,xd", [
+    (1, 4096, 64, 64, 22016, 64, "bf16"),   # 7B gate|up at one token: gated in the decode kernel's epilogue
+    (16, 5120, 64, 80, 1000, 24, "bf16"),   # sixteen tokens, N a multiple of 4
+    (3, 2048, 32, 64, 334, 8, "bf16"),      # N even but not a multiple of 4: 2-byte stores, ragged last tile
+    (2, 28672, 224, 128, 96, 0, "bf16"),    # long rows (several passes), no low-rank part
+    (40, 1024, 32, 32, 200, 16, "bf16"),    # more than sixteen tokens: GEMM into scratch, then the gate
+    (300, 1152, 36, 32, 512, 20, "bf16"),   # prefill
+])
+def test_gated_merged_projection(M, K, n1, n2, N, r, xd):
+    """bwla_linear_forward_swiglu (block chaining: the gate of the MLP block applied in the GEMM
+    that computes gate and up)."""
+    from parity_util import run_case_swiglu
+    cfg = syn.LayerConfig(f"swiglu_{M}_{K}_{N}_{r}", M, K, n1, n2, N, r, xd, max(1, K // 100), 20.0, seed=16)
+    out = run_case_swiglu(cfg)
+    assert (out["ws"] == 0) == (M <= 16)
+    print(out, flush=True)
+
+
 def test_zero_token_gives_zero_codes_and_scale():
     from parity_util import pack_on_gpu, DEV
     from paper_2605_00422_amd import binding as B

@@ -159,3 +159,14 @@ def test_packed_size_mode(lib):
     assert lib.bwla_packed_size_mode(N, K, n1, n2, 125, 3, byref(out)) == B.BWLA_OK
     assert B.packed_size(N, K, n1, n2, r, centered=True, asym=True) == \
         (lib.bwla_packed_size_mode(N, K, n1, n2, r, 3, byref(out)), out.value)[1]
+
+
+def test_swiglu_entry_points_check_arguments_first(lib):
+    desc = B.BwlaLayer()
+    fake = c_void_p(0x1000)
+    out = c_size_t()
+    assert lib.bwla_swiglu_workspace_size(None, 1, byref(out)) == B.BWLA_ERR_NULL
+    assert lib.bwla_swiglu_workspace_size(byref(desc), 1, None) == B.BWLA_ERR_NULL
+    assert lib.bwla_linear_forward_swiglu(None, fake, fake, fake, fake, 1, fake, None, 0, None) == B.BWLA_ERR_NULL
+    assert lib.bwla_linear_forward_swiglu(byref(desc), fake, fake, fake, fake, 1, fake, None, 0, None) == \
+        B.BWLA_ERR_NULL                                   # zeroed descriptor: no blob
