@@ -241,9 +241,10 @@ bwla_status_t bwla_decode_forward(const bwla_layer_t* layer, const void* d_X, in
  * evaluated in fp32 and rounded to bfloat16 (nearest even): the activation format that
  * bwla_rotate_quant of the down projection reads.
  *   d_H      out, M x N / 2 bfloat16, 16-byte aligned
- *   d_ws     scratch of ws_bytes >= bwla_swiglu_workspace_size(layer, M): 0 for up to 16 tokens
- *            (the decode kernel gates in its epilogue and Y never exists), else M x N fp32 for Y
- *            (NULL allowed when 0); not kept between calls
+ *   d_ws     scratch of ws_bytes >= bwla_swiglu_workspace_size(layer, M): 0 where the GEMM kernel
+ *            that serves the shape gates in its epilogue and Y never exists (up to 16 tokens; more
+ *            tokens when K is a multiple of 128 and N >= 32), else M x N fp32 for Y, gated by one
+ *            more launch (NULL allowed when 0); not kept between calls
  * Other arguments and errors as bwla_linear_forward.
  */
 bwla_status_t bwla_swiglu_workspace_size(const bwla_layer_t* layer, int64_t M, size_t* bytes);

@@ -261,13 +261,20 @@ bwla_status_t bwla_linear_forward(const bwla_layer_t* layer, const int8_t* d_q, 
     return e == hipSuccess ? BWLA_OK : BWLA_ERR_HIP;
 }
 
+// which GEMM serves the layer at M tokens, as bwla_linear_forward picks it, if that kernel can gate
+// in its epilogue: 1 decode kernel, 2 streaming prefill kernel, 0 neither (Y goes through scratch)
+static int swiglu_path(const bwla_layer_t* layer, int64_t M) {
+    if (bwla_gemm_decode_bs_supported(M, layer->K, layer->r)) return 1;
+    if (M <= 16 && bwla_gemm_decode_lds(M, layer->K) <= DECODE_LDS_LIMIT) return 0;
+    return bwla_gemm_prefill_streams(layer) ? 2 : 0;
+}
+
 bwla_status_t bwla_swiglu_workspace_size(const bwla_layer_t* layer, int64_t M, size_t* bytes) {
     if (!bytes) return BWLA_ERR_NULL;
     bwla_status_t s = check_layer(layer);
     if (s != BWLA_OK) return s;
     if (M <= 0 || M > (int64_t)1 << 24 || (layer->N & 1) != 0) return BWLA_ERR_SHAPE;
-    *bytes = bwla_gemm_decode_bs_supported(M, layer->K, layer->r)
-                 ? 0 : (size_t)bwla_align256((uint64_t)M * (uint64_t)layer->N * sizeof(float));
+    *bytes = swiglu_path(layer, M) != 0 ? 0 : (size_t)bwla_align256((uint64_t)M * (uint64_t)layer->N * sizeof(float));
     return BWLA_OK;
 }
 
@@ -284,9 +291,13 @@ bwla_status_t bwla_linear_forward_swiglu(const bwla_layer_t* layer, const int8_t
     if (!aligned16(d_q) || !aligned16(d_H) || (d_T && !aligned16(d_T)) || (need > 0 && !aligned16(d_ws)))
         return BWLA_ERR_ALIGN;
     hipStream_t st = (hipStream_t)stream;
-    if (need == 0)      // the decode kernel gates in its epilogue: no M x N intermediate exists
+    const int path = swiglu_path(layer, M);
+    if (path == 1)      // the kernel gates in its epilogue: no M x N intermediate exists
         return bwla_launch_gemm_decode_bs(layer, d_q, d_scale, d_qsum, d_T, M, nullptr, nullptr, st,
                                           (uint16_t*)d_H) == hipSuccess ? BWLA_OK : BWLA_ERR_HIP;
+    if (path == 2)
+        return bwla_launch_gemm_prefill(layer, d_q, d_scale, d_qsum, d_T, M, nullptr, nullptr, st,
+                                        (uint16_t*)d_H) == hipSuccess ? BWLA_OK : BWLA_ERR_HIP;
     s = bwla_linear_forward(layer, d_q, d_scale, d_qsum, d_T, M, (float*)d_ws, nullptr, stream);
     if (s != BWLA_OK) return s;
     return bwla_launch_swiglu_rows((const float*)d_ws, M, layer->N, (uint16_t*)d_H, st) == hipSuccess ? BWLA_OK

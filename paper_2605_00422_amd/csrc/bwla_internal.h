@@ -131,9 +131,11 @@ hipError_t bwla_launch_gemm_decode_bs_cfg(const bwla_layer_t* L, const int8_t* d
                                           int32_t* dacc, hipStream_t st, int nt, int grid, int depth,
                                           uint16_t* dH = nullptr);
 hipError_t bwla_launch_swiglu_rows(const float* dY, int64_t M, int64_t N, uint16_t* dH, hipStream_t st);
+bool bwla_gemm_prefill_streams(const bwla_layer_t* L);
+// (dH not NULL: gated bf16 output instead of Y; only when bwla_gemm_prefill_streams(L))
 hipError_t bwla_launch_gemm_prefill(const bwla_layer_t* L, const int8_t* dq, const float* dscale,
                                     const int32_t* dqsum, const float* dT, int64_t M, float* dY,
-                                    int32_t* dacc, hipStream_t st);
+                                    int32_t* dacc, hipStream_t st, uint16_t* dH = nullptr);
 
 // ---------------------------------------------------------------- device helpers
 #ifdef __HIPCC__

@@ -231,12 +231,15 @@ __device__ __forceinline__ v4i gd_lds_read(uint32_t addr) {
 // expcnt (6:4) and lgkmcnt (11:8) left at "no wait"
 constexpr int gd_vmcnt_imm(int n) { return (n & 15) | ((n >> 4) << 14) | (7 << 4) | (15 << 8); }
 
-template <int NTL, int WM, int WK, int NB>
+// GATED: the rows interleave a gate and an up projection, and instead of Y the kernel stores
+// h[t, i] = silu(y[t, 2 i]) * y[t, 2 i + 1] as bf16 (a compile-time variant: the plain kernel's
+// register allocation is not to change)
+template <int NTL, int WM, int WK, int NB, bool GATED = false>
 __global__ __launch_bounds__(64 * WM * WK) void gemm_prefill_direct_kernel(
     const uint4* __restrict__ bits, int chunks, int row_tiles, const int8_t* __restrict__ q, int M, int K,
     const float* __restrict__ scale, const int32_t* __restrict__ qsum, const __half* __restrict__ alpha,
     const __half* __restrict__ V, const float* __restrict__ T, int r, float* __restrict__ Y, int N,
-    int32_t* __restrict__ acc_out, int tiles_m, int tiles_n) {
+    int32_t* __restrict__ acc_out, int tiles_m, int tiles_n, uint16_t* __restrict__ H) {
     constexpr int MT = GD_MT;
     // WM wavefronts stacked along the tokens; WK wavefronts share one tile and split its slices of K
     // (small batches: more wavefronts in flight), their accumulators are added through LDS
@@ -563,7 +566,16 @@ __global__ __launch_bounds__(64 * WM * WK) void gemm_prefill_direct_kernel(
 #pragma unroll
             for (int v = 0; v < 16; ++v) {
                 const int m = mrow0 + 8 * (v >> 2) + 4 * lg + (v & 3);
-                if (m < M && n < N) {
+                if constexpr (GATED) {
+                    // lane pairs (n even, n + 1) hold (gate, up) of one token; the even lane stores
+                    const int a = 2 * acc[mt][nt][v] - qs[v];
+                    const float yv = sc[v] * al[nt] * (float)a + low[nt][v];
+                    const float up = __shfl_xor(yv, 1, 64);
+                    if (m < M && (l32 & 1) == 0 && n + 1 < N) {
+                        const float h = yv / (1.0f + __expf(-yv)) * up;
+                        H[(int64_t)m * (N >> 1) + (n >> 1)] = __builtin_bit_cast(uint16_t, (__bf16)h);
+                    }
+                } else if (m < M && n < N) {
                     const int a = 2 * acc[mt][nt][v] - qs[v];
                     Y[(int64_t)m * N + n] = sc[v] * al[nt] * (float)a + low[nt][v];
                     if (acc_out) acc_out[(int64_t)m * N + n] = a;
@@ -575,21 +587,25 @@ __global__ __launch_bounds__(64 * WM * WK) void gemm_prefill_direct_kernel(
 
 template <int NTL, int WM, int WK, int NB>
 hipError_t launch_direct(const bwla_layer_t* L, const int8_t* dq, const float* dscale, const int32_t* dqsum,
-                         const float* dT, int64_t M, float* dY, int32_t* dacc, hipStream_t st) {
+                         const float* dT, int64_t M, float* dY, int32_t* dacc, hipStream_t st, uint16_t* dH) {
     constexpr int BM = WM * GD_ROWS, BN = NTL * 32;
     const char* blob = (const char*)L->d_blob;
     const int tiles_m = (int)((M + BM - 1) / BM), tiles_n = (int)((L->N + BN - 1) / BN);
     const size_t lds = (size_t)WM * WK * NB * GD_TILE;
     static_assert((size_t)(WK - 1) * WM * GD_MT * NTL * 16 * 64 * 4 <= (size_t)WM * WK * NB * GD_TILE,
                   "the partial sums must fit into the tile rings");
-    static bwla_lds_attr attr;
-    hipError_t e = attr.ensure((const void*)gemm_prefill_direct_kernel<NTL, WM, WK, NB>, lds);
-    if (e != hipSuccess) return e;
-    gemm_prefill_direct_kernel<NTL, WM, WK, NB><<<dim3((unsigned)(tiles_m * tiles_n)), dim3(64 * WM * WK), lds, st>>>(
-        (const uint4*)(blob + L->off_bits), (int)bwla_chunks(L->K), (int)bwla_row_tiles(L->N), dq, (int)M,
-        (int)L->K, dscale, dqsum, (const __half*)(blob + L->off_alpha), (const __half*)(blob + L->off_V), dT,
-        L->r, dY, (int)L->N, dacc, tiles_m, tiles_n);
-    return hipGetLastError();
+    auto launch = [&](auto kern) -> hipError_t {
+        static bwla_lds_attr attr;
+        hipError_t e = attr.ensure((const void*)kern, lds);
+        if (e != hipSuccess) return e;
+        kern<<<dim3((unsigned)(tiles_m * tiles_n)), dim3(64 * WM * WK), lds, st>>>(
+            (const uint4*)(blob + L->off_bits), (int)bwla_chunks(L->K), (int)bwla_row_tiles(L->N), dq, (int)M,
+            (int)L->K, dscale, dqsum, (const __half*)(blob + L->off_alpha), (const __half*)(blob + L->off_V), dT,
+            L->r, dY, (int)L->N, dacc, tiles_m, tiles_n, dH);
+        return hipGetLastError();
+    };
+    if (dH != nullptr) return launch(gemm_prefill_direct_kernel<NTL, WM, WK, NB, true>);
+    return launch(gemm_prefill_direct_kernel<NTL, WM, WK, NB, false>);
 }
 
 inline int64_t tiles_for(int64_t M, int64_t N, int BM, int BN) { return ((M + BM - 1) / BM) * ((N + BN - 1) / BN); }
@@ -602,27 +618,31 @@ inline double wave_eff(int64_t tiles) {
 
 }  // namespace
 
+// the register-streaming kernel takes the layer (else the LDS-tiled one does)
+bool bwla_gemm_prefill_streams(const bwla_layer_t* L) { return L->N >= 32 && (L->K & 127) == 0; }
+
 hipError_t bwla_launch_gemm_prefill(const bwla_layer_t* L, const int8_t* dq, const float* dscale,
                                     const int32_t* dqsum, const float* dT, int64_t M, float* dY,
-                                    int32_t* dacc, hipStream_t st) {
+                                    int32_t* dacc, hipStream_t st, uint16_t* dH) {
     const int64_t N = L->N;
-    if (N >= 32 && (L->K & 127) == 0) {
+    if (bwla_gemm_prefill_streams(L)) {
         // register-streaming kernel.  Large batches: four wavefronts stacked along the tokens,
         // 256 x 160 or 256 x 128 tiles, whichever fills the chip better.  Up to 128 tokens: one or
         // two wavefronts per workgroup and narrow channel tiles, so that enough workgroups exist.
         if (M > 128) {
             const double d160 = wave_eff(tiles_for(M, N, 256, 160)), d128 = wave_eff(tiles_for(M, N, 256, 128));
-            if (d160 >= d128) return launch_direct<5, 4, 1, 4>(L, dq, dscale, dqsum, dT, M, dY, dacc, st);
-            return launch_direct<4, 4, 1, 4>(L, dq, dscale, dqsum, dT, M, dY, dacc, st);
+            if (d160 >= d128) return launch_direct<5, 4, 1, 4>(L, dq, dscale, dqsum, dT, M, dY, dacc, st, dH);
+            return launch_direct<4, 4, 1, 4>(L, dq, dscale, dqsum, dT, M, dY, dacc, st, dH);
         }
         // 64 x 32 tiles: one wavefront per workgroup when there are many tiles, else four
         // wavefronts that share a tile and split K (measured on the 70B block at 64 tokens)
         const int64_t tiles = ((M + 63) / 64) * ((N + 31) / 32);
-        if (tiles >= 768) return launch_direct<1, 1, 1, 4>(L, dq, dscale, dqsum, dT, M, dY, dacc, st);
-        return launch_direct<1, 1, 4, 4>(L, dq, dscale, dqsum, dT, M, dY, dacc, st);
+        if (tiles >= 768) return launch_direct<1, 1, 1, 4>(L, dq, dscale, dqsum, dT, M, dY, dacc, st, dH);
+        return launch_direct<1, 1, 4, 4>(L, dq, dscale, dqsum, dT, M, dY, dacc, st, dH);
     }
     // shapes the streaming kernel does not take (K not a multiple of 128, fewer than 32 channels):
-    // LDS-tiled kernel, 64 x 128 or 128 x 128 tiles
+    // LDS-tiled kernel, 64 x 128 or 128 x 128 tiles (it does not gate: the caller goes through Y)
+    if (dH != nullptr) return hipErrorInvalidValue;
     if (M <= 64) return launch_cfg<1, 2, 2, 2>(L, dq, dscale, dqsum, dT, M, dY, dacc, st);
     return launch_cfg<2, 2, 2, 2>(L, dq, dscale, dqsum, dT, M, dY, dacc, st);
 }
