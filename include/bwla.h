@@ -217,8 +217,11 @@ bwla_status_t bwla_linear_forward(const bwla_layer_t* layer, const int8_t* d_q, 
 
 /*
  * The whole forward of one layer, steps 1-5 above (paper Sec. 3.1, Sec. 4.1, Eq. 3-4, Sec. 3.2), in
- * one call: same results as bwla_rotate_quant followed by bwla_linear_forward with the same
- * buffers (d_q, d_scale, d_qsum, d_T are still written; same arguments, same errors).  For a single
+ * one call: what bwla_rotate_quant followed by bwla_linear_forward compute, with the same
+ * buffers (d_q, d_scale, d_qsum, d_T are still written; same arguments, same errors) and to the
+ * same accuracy.  Where the single-launch kernel serves the call, its rotation may add the
+ * products in another order than the kernel bwla_rotate_quant picks for the shape, so a code
+ * whose value lies on a rounding boundary can differ by one between the two.  For a single
  * bf16 token of a layer without low-rank part (r == 0) on the common decode shapes (K = 4096 with
  * n2 = 64, for one) everything runs in ONE kernel launch: every GEMM workgroup rotates and
  * quantizes the token itself while its first weights are in flight, and nothing crosses
