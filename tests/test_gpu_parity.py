@@ -275,6 +275,8 @@ def test_repeated_calls_are_deterministic():
     ("batch16", 16, 5120, 64, 80, 640, 64, False),         # projection with ten slices and its arrival counters
     ("split_rotation", 2, 20000, 200, 100, 48, 4, False),  # three launches; integer atomics on qsum
     ("prefill", 300, 1152, 36, 32, 200, 20, False),        # separate projection kernel, streaming GEMM
+    ("split_groups", 1, 11008, 128, 86, 256, 96, False),   # split rotation; projection in rank groups, summed by the quantizing launch
+    ("two_at_a_time", 600, 8192, 128, 64, 64, 8, False),   # looping rotation, two tokens at a time
 ])
 def test_hip_graph_replays_match_eager(name, M, K, n1, n2, N, r, one_call):
     """The benchmark times HIP graphs: a captured layer forward, replayed several times with other
