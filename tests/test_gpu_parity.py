@@ -206,17 +206,17 @@ def test_seeded_random_shapes_and_modes():
     at once (which rotation kernel, how the projection is dealt out, which GEMM)."""
     import random
     from paper_2605_00422_amd import binding as B
-    from parity_util import run_case, run_case_asym
+    from parity_util import run_case, run_case_asym, run_case_swiglu
     rnd = random.Random(7)
     done = 0
-    while done < 16:
+    while done < 24:
         n1 = rnd.choice([16, 32, 48, 64, 96, 112, 128, 144, 160, 176, 192, 200, 224, 256])
         n2 = rnd.choice([8, 12, 16, 24, 32, 40, 48, 64, 75, 80, 86, 96, 100, 112, 128, 144, 160])
         K = n1 * n2
-        M = rnd.choice([1, 1, 2, 3, 4, 5, 8, 9, 16, 17, 20, 33])
+        M = rnd.choice([1, 1, 2, 3, 4, 5, 8, 9, 16, 17, 20, 33, 64, 130, 300, 515])
         r = rnd.choice([0, 8, 16, 24, 32, 40, 48, 64, 96, 120])
         N = rnd.choice([32, 40, 64, 100])
-        mode = rnd.choice(["plain", "plain", "centered", "asym", "asym+centered"])
+        mode = rnd.choice(["plain", "plain", "centered", "asym", "asym+centered", "gated"])
         if K % 32 or K > 32768 or n2 > n1:
             continue
         try:
@@ -226,7 +226,9 @@ def test_seeded_random_shapes_and_modes():
         cfg = syn.LayerConfig(f"rnd_{M}_{n1}x{n2}_{N}_{r}", M, K, n1, n2, N, r, "bf16", max(1, K // 100), 20.0,
                               seed=200 + done)
         print(done, cfg.name, mode, flush=True)
-        if mode.startswith("asym"):
+        if mode == "gated":
+            run_case_swiglu(cfg)
+        elif mode.startswith("asym"):
             run_case_asym(cfg, centered=mode.endswith("centered"))
         else:
             run_case(cfg, centered=(mode == "centered"))
