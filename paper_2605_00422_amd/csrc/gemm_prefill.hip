@@ -634,11 +634,19 @@ hipError_t bwla_launch_gemm_prefill(const bwla_layer_t* L, const int8_t* dq, con
             if (d160 >= d128) return launch_direct<5, 4, 1, 4>(L, dq, dscale, dqsum, dT, M, dY, dacc, st, dH);
             return launch_direct<4, 4, 1, 4>(L, dq, dscale, dqsum, dT, M, dY, dacc, st, dH);
         }
-        // 64 x 32 tiles: one wavefront per workgroup when there are many tiles, else four
-        // wavefronts that share a tile and split K (measured on the 70B block at 64 tokens)
+        // Up to 128 tokens the kernel is bound by how often the code rows are re-read (every workgroup
+        // reads all K of its tokens) and by how many wavefronts are in flight.  With t tiles of
+        // 64 x 32: up to one per CU, four wavefronts share a tile and split K; up to two per CU,
+        // 64 x 64 tiles shared by four wavefronts (half the code traffic, one workgroup per CU);
+        // more, one wavefront per 64 x 32 tile.  Measured (us), in that order of variants:
+        // 8192 x 8192 at 64 tokens (256 tiles) 17.1 / 21.6 / 27.8, at 128 (512) 33.3 / 23.1 / 29.1;
+        // 4096 -> 11008 at 64 (344) 21.8 / 15.8 / 17.3, at 128 (688) 33.5 / 30.7 / 19.1;
+        // 8192 -> 28672 at 64 (896) 62.0 / 42.2 / 31.2.
         const int64_t tiles = ((M + 63) / 64) * ((N + 31) / 32);
-        if (tiles >= 768) return launch_direct<1, 1, 1, 4>(L, dq, dscale, dqsum, dT, M, dY, dacc, st, dH);
-        return launch_direct<1, 1, 4, 4>(L, dq, dscale, dqsum, dT, M, dY, dacc, st, dH);
+        const int64_t cus = bwla_device_cus();
+        if (tiles <= cus) return launch_direct<1, 1, 4, 4>(L, dq, dscale, dqsum, dT, M, dY, dacc, st, dH);
+        if (tiles <= 2 * cus) return launch_direct<2, 1, 4, 4>(L, dq, dscale, dqsum, dT, M, dY, dacc, st, dH);
+        return launch_direct<1, 1, 1, 4>(L, dq, dscale, dqsum, dT, M, dY, dacc, st, dH);
     }
     // shapes the streaming kernel does not take (K not a multiple of 128, fewer than 32 channels):
     // LDS-tiled kernel, 64 x 128 or 128 x 128 tiles (it does not gate: the caller goes through Y)

@@ -89,6 +89,8 @@ def test_cfg4_70b_gate_m4096_sampled_rows():
     (520, 640, 20, 32, 330, 0, "bf16"),    # streaming GEMM without a low-rank branch
     (40, 480, 20, 24, 70, 8, "bf16"),      # K not a multiple of 128: LDS-tiled GEMM, 64 x 128 tiles
     (150, 160, 16, 10, 24, 4, "f32"),      # fewer than 32 channels: LDS-tiled GEMM, 128 x 128 tiles
+    (33, 256, 16, 16, 8800, 8, "bf16"),    # streaming GEMM, 275 tiles of 64 x 32: 64 x 64 tiles shared by four wavefronts
+    (20, 256, 16, 16, 16672, 0, "bf16"),   # streaming GEMM, 521 tiles: one wavefront per tile
     # rows longer than 8192 columns at decode: four chunks per compute wavefront
     (1, 11008, 128, 86, 1000, 32, "bf16"),  # 7B down-projection shape: 22 chunks, six compute wavefronts
     (8, 12288, 128, 96, 520, 0, "bf16"),    # 24 chunks, eight tokens, no low-rank part
