@@ -12,6 +12,7 @@
 //   gemm_prefill_kernel         the remaining shapes: code tiles shared through LDS, double
 //                               buffered, one barrier per 128 columns
 #include "bwla_internal.h"
+#include <algorithm>
 
 namespace {
 
@@ -629,12 +630,16 @@ hipError_t bwla_launch_gemm_prefill(const bwla_layer_t* L, const int8_t* dq, con
         // register-streaming kernel.  Large batches: four wavefronts stacked along the tokens,
         // 256 x 160 or 256 x 128 tiles, whichever fills the chip better.  Up to 128 tokens: one or
         // two wavefronts per workgroup and narrow channel tiles, so that enough workgroups exist.
-        if (M > 128) {
+        // (the large tiles need enough workgroups: 4096 x 4096 at 512 tokens has 52 of them and takes
+        // 36.9 us against 21.0 with one wavefront per 64 x 32 tile; 8192 x 8192 at 256 tokens 63.0
+        // against 35.8; at 104 workgroups the large tiles win, 38.6 against 44.0 and 64.0 against 77.8)
+        const int64_t big = std::min(tiles_for(M, N, 256, 160), tiles_for(M, N, 256, 128));
+        if (M > 128 && big > 72) {
             const double d160 = wave_eff(tiles_for(M, N, 256, 160)), d128 = wave_eff(tiles_for(M, N, 256, 128));
             if (d160 >= d128) return launch_direct<5, 4, 1, 4>(L, dq, dscale, dqsum, dT, M, dY, dacc, st, dH);
             return launch_direct<4, 4, 1, 4>(L, dq, dscale, dqsum, dT, M, dY, dacc, st, dH);
         }
-        // Up to 128 tokens the kernel is bound by how often the code rows are re-read (every workgroup
+        // Few tokens (or few large tiles): the kernel is bound by how often the code rows are re-read (every workgroup
         // reads all K of its tokens) and by how many wavefronts are in flight.  With t tiles of
         // 64 x 32: up to one per CU, four wavefronts share a tile and split K; up to two per CU,
         // 64 x 64 tiles shared by four wavefronts (half the code traffic, one workgroup per CU);
