@@ -304,12 +304,14 @@ hipError_t bwla_launch_rotate_quant(const bwla_layer_t* L, const void* dX, int x
             const int64_t cap = per_cu * bwla_device_cus();
             if (M > cap) a.rot_blocks = cap;
             // only one workgroup of at most four wavefronts per CU (large factors): two tokens at a
-            // time per workgroup, if the second token's rows still fit
-            if (per_cu == 1 && M >= 2 * cap && s3.strips <= 4 && s3.at <= 8 &&
+            // time per workgroup, if the second token's rows still fit (128 x 64: 28 us for 272 to
+            // 448 tokens in two rounds of one token, 22 us for 512 tokens two at a time)
+            if (per_cu == 1 && M > cap && s3.strips <= 4 && s3.at <= 8 &&
                 s3.lds_bytes + (size_t)s3.r0bytes + 256 <= RQ_LDS_LIMIT) {
                 dual = true;
                 threads = 2 * 64 * s3.strips;
                 lds_dual = s3.lds_bytes + (size_t)s3.r0bytes + 256;
+                if ((M + 1) / 2 < cap) a.rot_blocks = (M + 1) / 2;
             }
         }
         if (s3.resident && a.rot_blocks == M && s3.strips < 8) threads = 512;

@@ -70,6 +70,13 @@ def test_looping_rotation_two_tokens_at_a_time_odd_count():
     print(run_case(cfg, rows=[0, 1, 2, 3, 255, 256, 257, 510, 511, 512, 513, 514]), flush=True)
 
 
+def test_looping_rotation_two_tokens_at_a_time_fewer_pairs_than_cus():
+    """Between one and two tokens per CU: fewer workgroups than CUs, one round of two tokens each."""
+    from parity_util import run_case
+    cfg = syn.LayerConfig("dual_301", 301, 8192, 128, 64, 48, 8, "bf16", 80, 20.0, seed=14)
+    print(run_case(cfg, rows=[0, 1, 2, 149, 150, 151, 298, 299, 300]), flush=True)
+
+
 def test_cfg4_70b_gate_m4096_sampled_rows():
     from parity_util import run_case
     cfg = {c.name.split("_")[2]: c for c in syn.block70b_configs(4096)}["gate"]
