@@ -298,7 +298,10 @@ hipError_t bwla_launch_rotate_quant(const bwla_layer_t* L, const void* dX, int x
         // walking over its share of the tokens with the factors loaded once
         if (s3.resident && !merged) {
             int64_t per_cu = (int64_t)(RQ_LDS_LIMIT / lds3);
-            const int64_t by_waves = 32 / (threads / 64);              // at most 32 wavefronts per CU
+            // the kernels use more than 170 registers: two wavefronts per SIMD, eight per CU (counting
+            // what LDS alone allows put 64 x 64 at 1024 tokens on one workgroup per token, 37.8 us;
+            // 512 looping workgroups take 28.5)
+            const int64_t by_waves = 8 / (threads / 64);
             if (per_cu > by_waves) per_cu = by_waves;
             if (per_cu < 1) per_cu = 1;
             const int64_t cap = per_cu * bwla_device_cus();
