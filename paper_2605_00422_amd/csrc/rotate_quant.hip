@@ -197,12 +197,14 @@ int bwla_rotate_max_tiles() { return RQ_MAXT * RQ_WAVES; }
 bwla_psp_plan bwla_make_psp_plan(int64_t M, int64_t K, int r) {
     bwla_psp_plan p;
     const int rp = (r + 15) & ~15;
-    // The projection rides in the rotation launch while that launch stays within about two
-    // workgroups per CU: its short workgroups then finish in the shadow of the rotation.
+    // The projection rides in the rotation launch while that launch stays within about three
+    // workgroups per CU: its short workgroups then finish in the shadow of the rotation, and the
+    // separate projection kernel costs about 8 us at these sizes (64 x 80, rank 64, 320 tokens:
+    // 33.4 -> 25.6 us with 720 workgroups; 128 x 64, rank 64, 320 tokens: 960 workgroups lose, 36.7 -> 38.8).
     // (ranks of more than two 16-column tiles are dealt to several workgroups per slice)
     const int jg = rp > 16 * PP_GROUPJT ? (rp / 16 + PP_GROUPJT - 1) / PP_GROUPJT : 1;
     const int64_t ride = M + ((M + 15) / 16) * ((K + PP_SLICE - 1) / PP_SLICE) * jg;
-    if (M <= 16 || r <= 0 || ride <= 512) {
+    if (M <= 16 || r <= 0 || ride <= 768) {
         p.token_tiles = (int)((M + 15) / 16);
         p.k_per_split = PP_SLICE;
         p.splits = r > 0 ? (int)((K + PP_SLICE - 1) / PP_SLICE) : 1;
