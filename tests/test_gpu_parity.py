@@ -122,7 +122,7 @@ def test_cfg4_70b_gate_m4096_sampled_rows():
     (7, 1024, 32, 32, 100, 40, "f32"),     # fp32 activations, two slices, three rank tiles in two groups
     (3, 512, 16, 32, 64, 48, "bf16"),      # a single slice: the groups write T themselves
     (12, 4096, 64, 64, 200, 128, "bf16"),  # the largest rank: four groups of two tiles
-    (20, 28672, 224, 128, 64, 40, "bf16"), # two token tiles, more workgroups than CUs (280 rotation + 336 projection)
+    (20, 28672, 224, 128, 64, 40, "bf16"), # two token tiles, more workgroups than CUs (280 rotation + 224 projection)
 ])
 def test_ragged_and_degenerate_shapes(M, K, n1, n2, N, r, xd):
     from parity_util import run_case
