@@ -102,8 +102,14 @@ __device__ __forceinline__ float bwla_load_agent(const float* p) {
 }
 // Called by every thread of the workgroup after its partial stores; true in the workgroup that
 // arrives last of `expected`.  `flag` is one int of LDS.
+// Ordering relied on: the partial stores are device-scope write-through stores; every thread waits
+// until the memory system has acknowledged its own (the explicit vmcnt(0) wait below -- a fence of
+// workgroup scope does not emit one), the barrier then collects all threads, and only after it does
+// one thread bump the device-scope counter.  A workgroup that reads the full count therefore finds
+// every partial tile at the device-coherent level, which its device-scope loads read.
 __device__ __forceinline__ bool bwla_partials_arrive(int* counter, int expected, int* flag) {
-    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");     // my stores have completed
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
+    __builtin_amdgcn_s_waitcnt(0);                             // my stores have been acknowledged
     __syncthreads();
     if (threadIdx.x == 0)
         *flag = __hip_atomic_fetch_add(counter, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) == expected - 1;

@@ -1,4 +1,5 @@
-"""Structural checks of the compiled streaming GEMM (no GPU needed).
+"""Structural checks of compiled kernels (no GPU needed): the streaming GEMM's hand-counted
+waits, and the split-K hand-over of the projection's partial sums.
 
 The kernel issues its ring loads as inline assembly and waits for them with hand-counted
 `s_waitcnt vmcnt(N)`.  That is only correct while the compiler (a) adds no vector-memory
@@ -17,7 +18,7 @@ CSRC = os.path.join(ROOT, "paper_2605_00422_amd", "csrc")
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 # (channel tiles per wavefront, wavefronts along the tokens, wavefronts along K, ring depth) of
 # every instantiation that is launched
-VARIANTS = [(1, 1, 1, 4), (1, 1, 4, 4), (4, 4, 1, 4), (5, 4, 1, 4)]
+VARIANTS = [(1, 1, 1, 4), (1, 1, 4, 4), (2, 1, 4, 4), (4, 4, 1, 4), (5, 4, 1, 4)]
 
 
 @pytest.fixture(scope="module")
@@ -85,3 +86,38 @@ def test_registers_of_loads_in_flight_stay_reserved(kernels, ntl, wm, wk, nb):
             lo = int(m.group(1))
             hi = int(m.group(2)) if m.group(2) else lo
             assert not any(r in dest for r in range(lo, hi + 1)), f"writes a register of a load in flight: {l}"
+
+
+def _device_asm(src):
+    if not os.path.exists(HIPCC):
+        pytest.skip("hipcc not available")
+    with tempfile.TemporaryDirectory() as tmp:
+        out = os.path.join(tmp, "out.s")
+        cmd = [HIPCC, "--offload-arch=gfx950", "-O3", "-std=c++17", "-w", "-Xclang", "-target-feature", "-Xclang",
+               "-packed-fp32-ops", "-I", os.path.join(ROOT, "include"), "-I", CSRC, "-S", "--cuda-device-only",
+               "-o", out, os.path.join(CSRC, src)]
+        subprocess.run(cmd, check=True, capture_output=True)
+        return [l.strip() for l in open(out).read().split("\n")]
+
+
+@pytest.mark.parametrize("src,min_sites", [("psp_prefill.hip", 1), ("rotate_quant.hip", 2)])
+def test_partial_sums_are_acknowledged_before_the_arrival_count(src, min_sites):
+    """The workgroup that arrives last at the counter reads the other workgroups' partial tiles.
+    Nothing but an explicit wait orders a workgroup's device-scope stores before its counter bump
+    (a workgroup-scope fence emits none), so between the last such store and the returning atomic
+    add there must be: a wait for all vector-memory operations, then the barrier, then the add."""
+    lines = _device_asm(src)
+    sites = 0
+    for i, l in enumerate(lines):
+        if not (l.startswith("global_atomic_add") and l.endswith("sc0")):
+            continue                                   # (adds without return value are code sums)
+        bar = next(j for j in range(i, 0, -1) if lines[j] == "s_barrier")
+        st = next((j for j in range(bar, max(bar - 400, 0), -1)
+                   if lines[j].startswith("global_store_dword") and lines[j].endswith("sc1")), None)
+        if st is None:
+            continue
+        sites += 1
+        waits = [j for j in range(st + 1, bar) if lines[j].startswith("s_waitcnt") and "vmcnt(0)" in lines[j]]
+        assert waits, f"{src}: no vmcnt(0) wait between the partial stores (line {st}) and the barrier (line {bar})"
+        assert not any(lines[j].startswith("global_store") for j in range(waits[-1], bar))
+    assert sites >= min_sites
