@@ -567,6 +567,44 @@ def test_to_bf16_rounds_to_nearest_even_on_eight_bits():
     assert syn.round_to_bf16(np.array([t], dtype=np.float32))[0] == 1.0
 
 
+def test_to_fp16_rounds_to_nearest_even_on_eleven_bits():
+    """fp16 keeps 11 significant bits (spacing 2^-10 in [1, 2)), has subnormals of 2^-24 below 2^-14
+    and overflows to infinity from 65520 on: spot values and ties, a value that double rounding
+    through fp32 gets wrong, and exact rational arithmetic on random values of every binade."""
+    from fractions import Fraction
+    u = 2.0 ** -10
+    vals = np.array([1.0, 1.0 + u, 1.0 + 0.5 * u, 1.0 + 1.5 * u, 1.0 + 0.49 * u, 1.0 + 0.51 * u, -3.0 - 2 * u, 0.0,
+                     65504.0, 65519.9, 2.0 ** -24, 0.5 * 2.0 ** -24, 1.5 * 2.0 ** -24, 2.0 ** -14 - 2.0 ** -25])
+    want = np.array([1.0, 1.0 + u, 1.0, 1.0 + 2 * u, 1.0, 1.0 + u, -3.0 - 2 * u, 0.0,
+                     65504.0, 65504.0, 2.0 ** -24, 0.0, 2.0 ** -23, 2.0 ** -14])
+    assert np.array_equal(orc.to_fp16(vals), want)
+    with np.errstate(over="ignore"):
+        assert np.isinf(orc.to_fp16(np.array([65520.0]))[0])
+    # just above a tie by less than half an fp32 ulp: fp64 -> fp32 lands on the tie, which then goes to even
+    t = 1.0 + 0.5 * u + 2.0 ** -30
+    assert orc.to_fp16(np.array([t]))[0] == 1.0 + u
+    assert np.float16(np.float32(t)) == np.float16(1.0)
+
+    def rational(x):
+        f = Fraction(x)
+        if f == 0:
+            return 0.0
+        e = math.floor(math.log2(abs(x)))
+        while Fraction(2) ** e > abs(f):
+            e -= 1
+        while Fraction(2) ** (e + 1) <= abs(f):
+            e += 1
+        quantum = Fraction(2) ** (max(e, -14) - 10)
+        return float(round(f / quantum) * quantum)      # Python rounds a Fraction half to even
+
+    rng = np.random.default_rng(11)
+    x = rng.standard_normal(4000) * np.exp2(rng.uniform(-27, 15.9, 4000))
+    # scales and factors as the layers store them: |w| ~ 0.016, U and V ~ 0.01
+    x = np.concatenate([x, rng.standard_normal(2000) * 0.01, np.abs(rng.standard_normal(2000)) * 0.02])
+    x = x[np.abs(x) < 65500.0]
+    assert np.array_equal(orc.to_fp16(x), np.array([rational(v) for v in x]))
+
+
 def test_effective_bits_in_paper_band():
     lo, hi = (float(v) for v in open(os.path.join(GOLDEN, "effective_bits.txt")).read().split("\n")[-2].split())
     b = orc.effective_weight_bits(11008, 4096, 64, 64, 32)
