@@ -16,7 +16,9 @@
  * Conventions for every call
  *   - All `d_*` pointers are DEVICE pointers on the current HIP device, owned by the caller,
  *     at least 16-byte aligned.  The library never allocates or frees device memory and keeps
- *     no global state.
+ *     nothing of a caller's between calls (what it caches per process -- the compute-unit count of
+ *     each device, the kernels whose shared-memory limit it has already raised -- is guarded and
+ *     may be used from several host threads).
  *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).  Calls enqueue
  *     work and return; they do not synchronize.
  *   - Return value is a bwla_status_t.  Arguments are validated on the host before anything is
@@ -32,6 +34,9 @@
 #ifdef __cplusplus
 extern "C" {
 #endif
+
+/* The entry points below are the only symbols the shared library exports. */
+#define BWLA_API __attribute__((visibility("default")))
 
 typedef enum {
     BWLA_OK = 0,
@@ -82,19 +87,19 @@ typedef struct bwla_layer {
     const void* d_blob;
 } bwla_layer_t;
 
-const char* bwla_status_string(int status);
+BWLA_API const char* bwla_status_string(int status);
 
 /* Library ABI version (integer, bumped on incompatible change). */
-int bwla_version(void);
+BWLA_API int bwla_version(void);
 
 /*
  * Kronecker dimension factorization, paper App. A.1 Algorithm 1: n2 is the largest divisor of
  * K not above sqrt(K), n1 = K / n2 (so n1 >= n2).  Host only.
  */
-bwla_status_t bwla_kron_factor(int64_t K, int32_t* n1, int32_t* n2);
+BWLA_API bwla_status_t bwla_kron_factor(int64_t K, int32_t* n1, int32_t* n2);
 
 /* Size in bytes of the packed blob for a layer of this shape.  Host only. */
-bwla_status_t bwla_packed_size(int64_t N, int64_t K, int32_t n1, int32_t n2, int32_t r,
+BWLA_API bwla_status_t bwla_packed_size(int64_t N, int64_t K, int32_t n1, int32_t n2, int32_t r,
                                size_t* bytes);
 
 /*
@@ -108,7 +113,7 @@ bwla_status_t bwla_packed_size(int64_t N, int64_t K, int32_t n1, int32_t n2, int
  *   out      host descriptor to fill
  * Runs as kernels on `stream`; the inputs may be released once the stream has drained.
  */
-bwla_status_t bwla_pack_weights(const float* d_W_rot, const float* d_R1, const float* d_R2,
+BWLA_API bwla_status_t bwla_pack_weights(const float* d_W_rot, const float* d_R1, const float* d_R2,
                                 const float* d_U, const float* d_V,
                                 int64_t N, int64_t K, int32_t n1, int32_t n2, int32_t r,
                                 void* d_blob, size_t blob_bytes, void* stream,
@@ -123,9 +128,9 @@ bwla_status_t bwla_pack_weights(const float* d_W_rot, const float* d_R1, const f
  * BWLA_MAX_RANK), mode = BWLA_MODE_ROW_SHIFT.  Arguments as for bwla_pack_weights / bwla_packed_size, with r
  * the PSP rank (columns of d_U and d_V).
  */
-bwla_status_t bwla_packed_size_centered(int64_t N, int64_t K, int32_t n1, int32_t n2, int32_t r,
+BWLA_API bwla_status_t bwla_packed_size_centered(int64_t N, int64_t K, int32_t n1, int32_t n2, int32_t r,
                                         size_t* bytes);
-bwla_status_t bwla_pack_weights_centered(const float* d_W_rot, const float* d_R1, const float* d_R2,
+BWLA_API bwla_status_t bwla_pack_weights_centered(const float* d_W_rot, const float* d_R1, const float* d_R2,
                                          const float* d_U, const float* d_V,
                                          int64_t N, int64_t K, int32_t n1, int32_t n2, int32_t r,
                                          void* d_blob, size_t blob_bytes, void* stream,
@@ -142,9 +147,9 @@ bwla_status_t bwla_pack_weights_centered(const float* d_W_rot, const float* d_R1
  *   Y[t,n] = scale_t * (delta_n * (acc - z rowsum_n) + mu_n * sum_k (q - z)) + sum_j T[t,j] V[n,j].
  * The layer's r becomes r + (2 if ASYM_ACT) + (1 if ROW_SHIFT), at most BWLA_MAX_RANK.
  */
-bwla_status_t bwla_packed_size_mode(int64_t N, int64_t K, int32_t n1, int32_t n2, int32_t r, int32_t mode,
+BWLA_API bwla_status_t bwla_packed_size_mode(int64_t N, int64_t K, int32_t n1, int32_t n2, int32_t r, int32_t mode,
                                     size_t* bytes);
-bwla_status_t bwla_pack_weights_mode(const float* d_W_rot, const float* d_R1, const float* d_R2,
+BWLA_API bwla_status_t bwla_pack_weights_mode(const float* d_W_rot, const float* d_R1, const float* d_R2,
                                      const float* d_U, const float* d_V,
                                      int64_t N, int64_t K, int32_t n1, int32_t n2, int32_t r, int32_t mode,
                                      void* d_blob, size_t blob_bytes, void* stream,
@@ -154,7 +159,7 @@ bwla_status_t bwla_pack_weights_mode(const float* d_W_rot, const float* d_R1, co
  * Inspection helper: expand the packed sign bits to the interchange view, an N x K int8
  * matrix of +1 / -1 (bit 1 <-> +1), and copy alpha as fp32.  d_alpha may be NULL.
  */
-bwla_status_t bwla_unpack_signs(const bwla_layer_t* layer, int8_t* d_sgn, float* d_alpha,
+BWLA_API bwla_status_t bwla_unpack_signs(const bwla_layer_t* layer, int8_t* d_sgn, float* d_alpha,
                                 void* stream);
 
 /*
@@ -166,7 +171,7 @@ bwla_status_t bwla_unpack_signs(const bwla_layer_t* layer, int8_t* d_sgn, float*
  * per 16-token tile, which every call returns to zero; everything behind them is overwritten by
  * each call.  Two calls that overlap in time must not share one scratch buffer.
  */
-bwla_status_t bwla_psp_workspace_size(const bwla_layer_t* layer, int64_t M, size_t* bytes);
+BWLA_API bwla_status_t bwla_psp_workspace_size(const bwla_layer_t* layer, int64_t M, size_t* bytes);
 
 /*
  * Steps 1, 2 and the first half of 4 of the forward:
@@ -184,7 +189,7 @@ bwla_status_t bwla_psp_workspace_size(const bwla_layer_t* layer, int64_t M, size
  * d_q holds q - 2^(b-1), d_qsum their sums, d_scale the step (hi - lo) / (2^b - 1).
  *   d_ws     scratch of ws_bytes >= bwla_psp_workspace_size(layer, M) (NULL allowed when that is 0)
  */
-bwla_status_t bwla_rotate_quant(const bwla_layer_t* layer, const void* d_X, int xdtype, int64_t M,
+BWLA_API bwla_status_t bwla_rotate_quant(const bwla_layer_t* layer, const void* d_X, int xdtype, int64_t M,
                                 int8_t* d_q, float* d_scale, int32_t* d_qsum, float* d_T,
                                 void* d_ws, size_t ws_bytes, void* stream);
 
@@ -194,12 +199,13 @@ bwla_status_t bwla_rotate_quant(const bwla_layer_t* layer, const void* d_X, int 
  * act_bits in 2..8 (else BWLA_ERR_UNSUPPORTED), still one code per int8.  bwla_rotate_quant is
  * act_bits = 6.  bwla_linear_forward takes the codes of any width; bwla_decode_forward is 6-bit.
  */
-bwla_status_t bwla_rotate_quant_bits(const bwla_layer_t* layer, const void* d_X, int xdtype, int act_bits,
+BWLA_API bwla_status_t bwla_rotate_quant_bits(const bwla_layer_t* layer, const void* d_X, int xdtype, int act_bits,
                                      int64_t M, int8_t* d_q, float* d_scale, int32_t* d_qsum, float* d_T,
                                      void* d_ws, size_t ws_bytes, void* stream);
 
-/* qsum_t = sum_k q[t,k] for codes that did not come from bwla_rotate_quant. */
-bwla_status_t bwla_code_sums(const int8_t* d_q, int64_t M, int64_t K, int32_t* d_qsum, void* stream);
+/* qsum_t = sum_k q[t,k] for codes that did not come from bwla_rotate_quant (codes in [-127, 127],
+ * see bwla_linear_forward). */
+BWLA_API bwla_status_t bwla_code_sums(const int8_t* d_q, int64_t M, int64_t K, int32_t* d_qsum, void* stream);
 
 /*
  * Steps 3, 4 (second half) and 5:
@@ -207,11 +213,14 @@ bwla_status_t bwla_code_sums(const int8_t* d_q, int64_t M, int64_t K, int32_t* d
  *              expanded in registers to 0/1-valued int8 digits b, and the +-1 product is
  *              recovered exactly as 2 * sum_k q b - qsum_t;
  *   Y[t,n]   = scale_t * alpha_n * acc[t,n] + sum_j T[t,j] V[n,j]      (paper Eq. 4; Sec. 3.2)
- *   d_q, d_scale, d_qsum, d_T  as produced by bwla_rotate_quant (d_T NULL iff r == 0)
+ *   d_q, d_scale, d_qsum, d_T  as produced by bwla_rotate_quant (d_T NULL iff r == 0).  Codes from
+ *            elsewhere (with d_qsum from bwla_code_sums) must lie in [-127, 127]: the kernels negate
+ *            the operand of the sign digit byte-wise, which has no +128, so a code of -128 would
+ *            give wrong sums without any error being reported
  *   d_Y      out, M x N fp32
  *   d_acc    optional out, M x N int32 raw accumulators (NULL to skip)
  */
-bwla_status_t bwla_linear_forward(const bwla_layer_t* layer, const int8_t* d_q, const float* d_scale,
+BWLA_API bwla_status_t bwla_linear_forward(const bwla_layer_t* layer, const int8_t* d_q, const float* d_scale,
                                   const int32_t* d_qsum, const float* d_T, int64_t M,
                                   float* d_Y, int32_t* d_acc, void* stream);
 
@@ -227,7 +236,7 @@ bwla_status_t bwla_linear_forward(const bwla_layer_t* layer, const int8_t* d_q, 
  * quantizes the token itself while its first weights are in flight, and nothing crosses
  * workgroups.  All other cases run the two launches back to back.
  */
-bwla_status_t bwla_decode_forward(const bwla_layer_t* layer, const void* d_X, int xdtype, int64_t M,
+BWLA_API bwla_status_t bwla_decode_forward(const bwla_layer_t* layer, const void* d_X, int xdtype, int64_t M,
                                   int8_t* d_q, float* d_scale, int32_t* d_qsum, float* d_T,
                                   void* d_ws, size_t ws_bytes, float* d_Y, int32_t* d_acc,
                                   void* stream);
@@ -250,8 +259,8 @@ bwla_status_t bwla_decode_forward(const bwla_layer_t* layer, const void* d_X, in
  *            more launch (NULL allowed when 0); not kept between calls
  * Other arguments and errors as bwla_linear_forward.
  */
-bwla_status_t bwla_swiglu_workspace_size(const bwla_layer_t* layer, int64_t M, size_t* bytes);
-bwla_status_t bwla_linear_forward_swiglu(const bwla_layer_t* layer, const int8_t* d_q, const float* d_scale,
+BWLA_API bwla_status_t bwla_swiglu_workspace_size(const bwla_layer_t* layer, int64_t M, size_t* bytes);
+BWLA_API bwla_status_t bwla_linear_forward_swiglu(const bwla_layer_t* layer, const int8_t* d_q, const float* d_scale,
                                          const int32_t* d_qsum, const float* d_T, int64_t M, void* d_H,
                                          void* d_ws, size_t ws_bytes, void* stream);
 

@@ -13,7 +13,7 @@ LIB_PATH = os.path.join(HERE, "libbwla.so")
 SOURCES = ["api.hip", "pack.hip", "rotate_quant.hip", "gemm_decode.hip", "gemm_decode_bs.hip", "gemm_prefill.hip", "psp_prefill.hip"]
 
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
-FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC",
+FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-fvisibility=hidden",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
          "-I", os.path.join(ROOT, "include"), "-I", CSRC]
 

@@ -2,6 +2,11 @@
 // stream.  Nothing here allocates device memory or synchronizes.
 #include <math.h>
 
+#include <atomic>
+#include <map>
+#include <mutex>
+#include <utility>
+
 #include "bwla_internal.h"
 
 size_t bwla_rotate_lds_bytes(int n1, int n2);
@@ -70,6 +75,32 @@ size_t rq_ws_bytes(const bwla_layer_t* L, const bwla_psp_plan& p, int64_t M) {
 }
 
 }  // namespace
+
+int bwla_device_cus() {
+    static std::atomic<int> cached[64];                // 0 = not asked yet
+    int dev = 0, n = 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return 256;
+    n = cached[dev].load(std::memory_order_relaxed);
+    if (n > 0) return n;
+    if (hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n <= 0) n = 256;
+    cached[dev].store(n, std::memory_order_relaxed);
+    return n;
+}
+
+hipError_t bwla_ensure_lds(const void* fn, size_t bytes) {
+    if (bytes <= 64 * 1024) return hipSuccess;          // default limit, nothing to raise
+    static std::mutex mu;
+    static std::map<std::pair<const void*, int>, size_t> granted;
+    int dev = 0;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return e;
+    std::lock_guard<std::mutex> lock(mu);
+    size_t& g = granted[std::make_pair(fn, dev)];
+    if (bytes <= g) return hipSuccess;
+    e = hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)bytes);
+    if (e == hipSuccess) g = bytes;
+    return e;
+}
 
 extern "C" {
 

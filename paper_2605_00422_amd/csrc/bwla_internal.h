@@ -23,7 +23,7 @@ static inline int64_t bwla_row_tiles(int64_t N) { return (N + BWLA_TILE_ROWS - 1
 static inline int64_t bwla_chunks(int64_t K) { return (K + BWLA_CHUNK_COLS - 1) / BWLA_CHUNK_COLS; }
 static inline uint64_t bwla_align256(uint64_t x) { return (x + 255u) & ~uint64_t(255); }
 
-// compute units of the current device (cached; 256 if the query fails)
+// compute units of the current device (cached per device; 256 if the query fails)
 int bwla_device_cus();
 
 // three bf16 term planes of an n x n factor, rows padded to 16 and columns to 32
@@ -61,22 +61,11 @@ int bwla_psp_prefill_tile_cols(int rp);
 hipError_t bwla_launch_psp_prefill(const bwla_layer_t* L, const void* dX, int xdtype, int64_t M, float* dT,
                                    void* dws, const bwla_psp_plan& plan, hipStream_t st);
 
-// Raises a kernel's dynamic-LDS limit once per process and size class (per device 0..15), so
-// that steady-state launches, also under stream capture, issue no attribute calls.
-struct bwla_lds_attr {
-    size_t granted[16] = {0};
-    hipError_t ensure(const void* fn, size_t bytes) {
-        if (bytes <= 64 * 1024) return hipSuccess;      // default limit, nothing to raise
-        int dev = 0;
-        hipError_t e = hipGetDevice(&dev);
-        if (e != hipSuccess) return e;
-        if (dev < 0 || dev >= 16) dev = 0, granted[0] = 0;
-        if (bytes <= granted[dev]) return hipSuccess;
-        e = hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)bytes);
-        if (e == hipSuccess) granted[dev] = bytes;
-        return e;
-    }
-};
+// Raises a kernel's dynamic-LDS limit, once per kernel, device and size class, so that steady-state
+// launches, also under stream capture, issue no attribute calls.  Safe to call from several host
+// threads.  (What the library remembers between calls is this table and the CU count per device:
+// facts about the process, never about a caller's data.)
+hipError_t bwla_ensure_lds(const void* fn, size_t bytes);
 
 // ---------------------------------------------------------------- launchers (one per .hip file)
 hipError_t bwla_launch_pack(const float* dW, const float* dR1, const float* dR2, const float* dU,
@@ -131,11 +120,6 @@ bool bwla_gemm_decode_bs_supported(int64_t M, int64_t K, int r);
 hipError_t bwla_launch_gemm_decode_bs(const bwla_layer_t* L, const int8_t* dq, const float* dscale,
                                       const int32_t* dqsum, const float* dT, int64_t M, float* dY,
                                       int32_t* dacc, hipStream_t st, uint16_t* dH = nullptr);
-// explicit launch shape (tiles per step 1/2, grid size, prefetch depth 2/4)
-hipError_t bwla_launch_gemm_decode_bs_cfg(const bwla_layer_t* L, const int8_t* dq, const float* dscale,
-                                          const int32_t* dqsum, const float* dT, int64_t M, float* dY,
-                                          int32_t* dacc, hipStream_t st, int nt, int grid, int depth,
-                                          uint16_t* dH = nullptr);
 hipError_t bwla_launch_swiglu_rows(const float* dY, int64_t M, int64_t N, uint16_t* dH, hipStream_t st);
 bool bwla_gemm_prefill_streams(const bwla_layer_t* L);
 // (dH not NULL: gated bf16 output instead of Y; only when bwla_gemm_prefill_streams(L))

@@ -189,8 +189,7 @@ hipError_t bwla_launch_gemm_decode(const bwla_layer_t* L, const int8_t* dq, cons
     size_t lds = (size_t)rows * chunks * BWLA_CHUNK_COLS;
     const size_t red = (size_t)waves * NT * 64 * 16;
     if (lds < red) lds = red;
-    static bwla_lds_attr attr;
-    hipError_t e = attr.ensure((const void*)gemm_decode_kernel<1>, lds);
+    hipError_t e = bwla_ensure_lds((const void*)gemm_decode_kernel<1>, lds);
     if (e != hipSuccess) return e;
     gemm_decode_kernel<1><<<dim3((unsigned)groups), dim3(64 * waves), lds, st>>>(
         (const uint4*)(blob + L->off_bits), chunks, row_tiles, dq, (int)M, (int)L->K, dscale, dqsum,

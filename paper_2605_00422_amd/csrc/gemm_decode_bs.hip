@@ -37,7 +37,6 @@ __global__ __launch_bounds__(CPW == BS_CPW ? BS_MAX_THREADS : 64 * (BS_MAXKS_LON
     const int units = (a.row_tiles + NT - 1) / NT;
     const int n_iter = (units - first + stride - 1) / stride;            // >= 1: grid <= units
     const int PV = (NT * (((a.r + 15) >> 4) * 16) + 31) >> 5;
-    TRACE(0);
     if (wave == a.KS) epilogue_wave<DEPTH, NT, JTT, FAST, false, MULTI>(a, smem, first, stride, n_iter, wave, lane);
     else if (wave <= PV) compute_wave<CPW, DEPTH, NT, true, false, MULTI>(a, smem, first, stride, n_iter, wave, lane);
     else compute_wave<CPW, DEPTH, NT, false, false, MULTI>(a, smem, first, stride, n_iter, wave, lane);
@@ -46,11 +45,6 @@ __global__ __launch_bounds__(CPW == BS_CPW ? BS_MAX_THREADS : 64 * (BS_MAXKS_LON
 
 }  // namespace
 
-#ifdef BWLA_TRACE
-extern "C" int bwla_trace_dump(long long* host, int n) {
-    return (int)hipMemcpyFromSymbol(host, HIP_SYMBOL(bwla_trace_buf), (size_t)n * sizeof(long long));
-}
-#endif
 
 bool bwla_gemm_decode_bs_supported(int64_t M, int64_t K, int r) {
     const int chunks = (int)bwla_chunks(K);
@@ -58,11 +52,14 @@ bool bwla_gemm_decode_bs_supported(int64_t M, int64_t K, int r) {
     return M <= 16 && chunks >= 2 && bs_fits(0, chunks, r, 1, bs_cpw_for(chunks), bs_passes_for(chunks) > 1 ? 64 : 0);
 }
 
-// explicit launch shape: nt tiles per step (1 or 2), grid size, prefetch depth (2 or 4)
-hipError_t bwla_launch_gemm_decode_bs_cfg(const bwla_layer_t* L, const int8_t* dq, const float* dscale,
-                                          const int32_t* dqsum, const float* dT, int64_t M, float* dY,
-                                          int32_t* dacc, hipStream_t st, int nt, int grid, int depth,
-                                          uint16_t* dH) {
+// Measured on MI355X: one 16-row tile per step, a prefetch ring of two steps and one workgroup per
+// CU is the best launch shape for all decode layers tried (two tiles per step run the steady state
+// ~30% faster but pay more at start-up, which dominates at these sizes).
+hipError_t bwla_launch_gemm_decode_bs(const bwla_layer_t* L, const int8_t* dq, const float* dscale,
+                                      const int32_t* dqsum, const float* dT, int64_t M, float* dY,
+                                      int32_t* dacc, hipStream_t st, uint16_t* dH) {
+    constexpr int nt = 1;
+    int grid = bwla_device_cus();
     const char* blob = (const char*)L->d_blob;
     const int chunks = (int)bwla_chunks(L->K), row_tiles = (int)bwla_row_tiles(L->N);
     const int cpw = bs_cpw_for(chunks), passes = bs_passes_for(chunks);
@@ -70,7 +67,7 @@ hipError_t bwla_launch_gemm_decode_bs_cfg(const bwla_layer_t* L, const int8_t* d
     if (grid > units0) grid = units0;
     // with several passes the sums of earlier passes wait in LDS, 1 KiB per tile of the workgroup's units
     const int pass_units = passes > 1 ? (units0 + grid - 1) / grid : 0;
-    if ((nt != 1 && nt != 2) || grid < 1 || chunks < 2 || M > 16 || pass_units > 64 ||
+    if (grid < 1 || chunks < 2 || M > 16 || pass_units > 64 ||
         !bs_fits(0, chunks, L->r, nt, cpw, pass_units))
         return hipErrorInvalidValue;
     // up to four tokens: code rows staged in LDS when they fit; else every wave loads its own
@@ -85,8 +82,7 @@ hipError_t bwla_launch_gemm_decode_bs_cfg(const bwla_layer_t* L, const int8_t* d
              (const __half*)(blob + L->off_alpha), (const __half*)(blob + L->off_V), dT, L->r, dY, (int)L->N,
              dacc, KS, direct, passes, dH};
     auto launch = [&](auto kern) -> hipError_t {
-        static bwla_lds_attr attr;
-        hipError_t e = attr.ensure((const void*)kern, lds);
+        hipError_t e = bwla_ensure_lds((const void*)kern, lds);
         if (e != hipSuccess) return e;
         kern<<<dim3((unsigned)grid), dim3(64 * (KS + 1)), lds, st>>>(a);
         return hipGetLastError();
@@ -100,33 +96,15 @@ hipError_t bwla_launch_gemm_decode_bs_cfg(const bwla_layer_t* L, const int8_t* d
     if (cpw == BS_CPW_LONG && jtt == J)                                                                    \
         return fast ? launch(gemm_decode_bs_kernel<BS_CPW_LONG, 2, 1, J, true, true>)                      \
                     : launch(gemm_decode_bs_kernel<BS_CPW_LONG, 2, 1, J, false, true>);
-    if (cpw == BS_CPW_LONG && nt != 1) return hipErrorInvalidValue;
     BS_LONG(0) BS_LONG(1) BS_LONG(2) BS_LONG(3) BS_LONG(4) BS_LONG(8)
 #undef BS_LONG
-#define BS_CASE(D, T, J)                                                                                   \
-    if (depth == D && nt == T && jtt == J)                                                                 \
-        return fast ? launch(gemm_decode_bs_kernel<BS_CPW, D, T, J, true>)                                 \
-                    : launch(gemm_decode_bs_kernel<BS_CPW, D, T, J, false>);
-#define BS_CASES(J) BS_CASE(2, 1, J) BS_CASE(4, 1, J) BS_CASE(2, 2, J) BS_CASE(4, 2, J)
-    BS_CASES(0) BS_CASES(1) BS_CASES(2) BS_CASES(3) BS_CASES(4) BS_CASES(8)
-#undef BS_CASES
+#define BS_CASE(J)                                                                                         \
+    if (jtt == J)                                                                                          \
+        return fast ? launch(gemm_decode_bs_kernel<BS_CPW, 2, 1, J, true>)                                 \
+                    : launch(gemm_decode_bs_kernel<BS_CPW, 2, 1, J, false>);
+    BS_CASE(0) BS_CASE(1) BS_CASE(2) BS_CASE(3) BS_CASE(4) BS_CASE(8)
 #undef BS_CASE
     return hipErrorInvalidValue;
-}
-
-hipError_t bwla_launch_gemm_decode_bs(const bwla_layer_t* L, const int8_t* dq, const float* dscale,
-                                      const int32_t* dqsum, const float* dT, int64_t M, float* dY,
-                                      int32_t* dacc, hipStream_t st, uint16_t* dH) {
-    const int chunks = (int)bwla_chunks(L->K), row_tiles = (int)bwla_row_tiles(L->N);
-    const int cus = bwla_device_cus();
-    // Measured on MI355X: one tile per step and one workgroup per CU is the best shape for all
-    // decode layers tried (two tiles per step run the steady state ~30% faster but pay more at
-    // start-up, which dominates at these sizes).
-    const int nt = 1;
-    const int units = (row_tiles + nt - 1) / nt;
-    const int grid = units < cus ? units : cus;
-    (void)chunks;
-    return bwla_launch_gemm_decode_bs_cfg(L, dq, dscale, dqsum, dT, M, dY, dacc, st, nt, grid, 2, dH);
 }
 
 namespace {
@@ -143,17 +121,4 @@ hipError_t bwla_launch_swiglu_rows(const float* dY, int64_t M, int64_t N, uint16
     const int64_t pairs = M * (N / 2);
     swiglu_rows_kernel<<<dim3((unsigned)((pairs + 255) / 256)), dim3(256), 0, st>>>(dY, pairs, dH);
     return hipGetLastError();
-}
-
-int bwla_device_cus() {
-    static int cus = 0;
-    if (cus == 0) {
-        int dev = 0, n = 0;
-        if (hipGetDevice(&dev) == hipSuccess &&
-            hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess && n > 0)
-            cus = n;
-        else
-            cus = 256;
-    }
-    return cus;
 }

@@ -9,12 +9,6 @@ namespace {
 constexpr int BS_MAX_THREADS = 576;                  // up to 8 compute waves + 1 epilogue wave
 constexpr int BS_MAXKS = BS_MAX_THREADS / 64 - 1;    // compute waves per workgroup
 
-#ifdef BWLA_TRACE
-static __device__ long long bwla_trace_buf[64 * 16 * 40];
-#define TRACE(slot) do { if (lane == 0 && (blockIdx.x & 3) == 0 && blockIdx.x < 256) bwla_trace_buf[((blockIdx.x >> 2) * 16 + wave) * 40 + (slot)] = wall_clock64(); } while (0)
-#else
-#define TRACE(slot) do { } while (0)
-#endif
 
 // byte-wise negation of four packed int8 (no value is -128 here)
 __device__ __forceinline__ int neg_bytes(int x) {
@@ -200,19 +194,15 @@ __device__ __forceinline__ void compute_wave(const BsArgs& a, char* smem, int fi
     if constexpr (FUSED) {
         // the weights are on their way; meanwhile the rotation wavefronts of this workgroup work
         // through their barriers, after the last of which the token's codes are in LDS
-        TRACE(0);
         if (wave == 0) bs_zero_fill<NT>(a, qt, red, lane);
 #pragma unroll
         for (int i = 0; i < rotation_barriers; ++i) bwla_lds_barrier();
-        TRACE(39);
         bs_local_stage_codes(a, qt, fl, wave, lane);
         __builtin_amdgcn_s_waitcnt(0);                     // this wave's copies (and first units) landed
-        TRACE(1);
         bwla_lds_barrier();
     } else if (!a.direct) {
         stage_codes(a, qt, wave, lane);
         __builtin_amdgcn_s_waitcnt(0);
-        TRACE(1);
         bwla_lds_barrier();
     }
     v4i b[CPW][8];
@@ -264,7 +254,6 @@ __device__ __forceinline__ void compute_wave(const BsArgs& a, char* smem, int fi
             b[i][7] = v4i{neg_bytes(b[i][7].x), neg_bytes(b[i][7].y), neg_bytes(b[i][7].z), neg_bytes(b[i][7].w)};
     };
     load_b(0);
-    TRACE(2);
     int cur_pass = 0;
 
     // The trip count is rounded up to a multiple of DEPTH: surplus steps redo the last step.
@@ -310,9 +299,7 @@ __device__ __forceinline__ void compute_wave(const BsArgs& a, char* smem, int fi
             for (int nt = 0; nt < NT; ++nt)
 #pragma unroll
                 for (int i = 0; i < CPW; ++i) wq[d][nt][i] = w_load(it + DEPTH, nt, i);
-            if (it < 12) TRACE(3 + 3 * it);
             bwla_lds_barrier();
-            if (it < 12) TRACE(5 + 3 * it);
             __builtin_amdgcn_sched_barrier(0);             // keep the steps in program order
         }
     }
@@ -339,7 +326,6 @@ __device__ __forceinline__ void epilogue_wave(const BsArgs& a, char* smem, int f
     if constexpr (FUSED) {
         // this wavefront comes from the rotation: the codes are in LDS, and so are the per-strip
         // maxima and sums (same expressions as where the rotation writes scale and sum out)
-        TRACE(39);
         float amax = fmaxf(fl.amax[0], -fl.amax[32]);
         int tot = fl.sums[0];
         for (int w = 1; w < fl.strips; ++w) {
@@ -350,7 +336,6 @@ __device__ __forceinline__ void epilogue_wave(const BsArgs& a, char* smem, int f
         qs = tok_ok ? tot : 0;
         bs_local_stage_codes(a, qt, fl, wave, lane);
         __builtin_amdgcn_s_waitcnt(0);
-        TRACE(1);
         bwla_lds_barrier();
         static_assert(!FUSED || JTT == 0, "the fused decode kernel has no low-rank part");
     } else {
@@ -369,12 +354,10 @@ __device__ __forceinline__ void epilogue_wave(const BsArgs& a, char* smem, int f
             }
         if (a.direct) {
             bs_zero_fill<NT>(a, qt, red, lane, false);         // (the compute waves fetch their codes themselves)
-            TRACE(1);
         } else {
             bs_zero_fill<NT>(a, qt, red, lane);
             stage_codes(a, qt, wave, lane);
             __builtin_amdgcn_s_waitcnt(0);                     // zeros written, this wave's copies landed
-            TRACE(1);
             bwla_lds_barrier();
         }
     }
@@ -398,7 +381,6 @@ __device__ __forceinline__ void epilogue_wave(const BsArgs& a, char* smem, int f
             thi[uu][e] = h;
             tlo[uu][e] = (_Float16)(x - (float)h);
         }
-    TRACE(2);
 
     // Several passes over a long row (see compute_wave): step `it` is unit it % n_iter of pass
     // it / n_iter; the sums of the earlier passes wait in LDS (this wavefront alone touches them)
@@ -409,9 +391,7 @@ __device__ __forceinline__ void epilogue_wave(const BsArgs& a, char* smem, int f
     const int n_real = n_iter * H;
     const int n_steps = (n_real + DEPTH - 1) / DEPTH * DEPTH;    // same barrier count as the compute waves
     for (int it = 0; it < n_steps; ++it) {
-        if (it < 12) TRACE(3 + 3 * it);
         bwla_lds_barrier();                                // partial tiles and side pieces of `it` are in LDS
-        if (it < 12) TRACE(4 + 3 * it);
         const char* sd = side + (it & 1) * side_bytes(rp, NT);
         const int hp = MULTI ? dni.div(it < n_real ? it : 0) : 0, ui = it - hp * n_iter;
 #pragma unroll
@@ -476,7 +456,6 @@ __device__ __forceinline__ void epilogue_wave(const BsArgs& a, char* smem, int f
                     }
             }
         }
-        if (it < 12) TRACE(5 + 3 * it);
     }
 }
 

@@ -174,8 +174,7 @@ hipError_t launch_cfg(const bwla_layer_t* L, const int8_t* dq, const float* dsca
     const int tiles_m = (int)((M + BM - 1) / BM), tiles_n = (int)((L->N + BN - 1) / BN);
     const size_t lds = 2 * (size_t)BM * GP_LDA;
     auto kern = gemm_prefill_kernel<MT, NTL, WM, WN>;
-    static bwla_lds_attr attr;
-    hipError_t e = attr.ensure((const void*)kern, lds);
+    hipError_t e = bwla_ensure_lds((const void*)kern, lds);
     if (e != hipSuccess) return e;
     kern<<<dim3((unsigned)(tiles_m * tiles_n)), dim3(64 * WM * WN), lds, st>>>(
         (const uint4*)(blob + L->off_bits), (int)bwla_chunks(L->K), (int)bwla_row_tiles(L->N), dq, (int)M,
@@ -596,8 +595,7 @@ hipError_t launch_direct(const bwla_layer_t* L, const int8_t* dq, const float* d
     static_assert((size_t)(WK - 1) * WM * GD_MT * NTL * 16 * 64 * 4 <= (size_t)WM * WK * NB * GD_TILE,
                   "the partial sums must fit into the tile rings");
     auto launch = [&](auto kern) -> hipError_t {
-        static bwla_lds_attr attr;
-        hipError_t e = attr.ensure((const void*)kern, lds);
+        hipError_t e = bwla_ensure_lds((const void*)kern, lds);
         if (e != hipSuccess) return e;
         kern<<<dim3((unsigned)(tiles_m * tiles_n)), dim3(64 * WM * WK), lds, st>>>(
             (const uint4*)(blob + L->off_bits), (int)bwla_chunks(L->K), (int)bwla_row_tiles(L->N), dq, (int)M,

@@ -258,8 +258,7 @@ __global__ __launch_bounds__(PF_THREADS) void psp_prefill_kernel(PfArgs a) {
 template <bool BF16, int NJT>
 hipError_t launch(const PfArgs& a, int blocks, hipStream_t st) {
     const size_t lds = (size_t)PF_WAVES * PF_TM * NJT * 16 * sizeof(float) + 16;
-    static bwla_lds_attr attr;
-    hipError_t e = attr.ensure((const void*)psp_prefill_kernel<BF16, NJT>, lds);
+    hipError_t e = bwla_ensure_lds((const void*)psp_prefill_kernel<BF16, NJT>, lds);
     if (e != hipSuccess) return e;
     psp_prefill_kernel<BF16, NJT><<<dim3((unsigned)blocks), dim3(PF_THREADS), lds, st>>>(a);
     return hipGetLastError();

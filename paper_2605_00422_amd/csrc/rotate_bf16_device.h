@@ -104,8 +104,6 @@ __device__ __forceinline__ void rotate3_token(char* lds, const uint16_t* __restr
     const int nthreads = 64 * sh.strips;
     const int nth_all = DUAL ? 2 * nthreads : nthreads;
     const int nfill = (early && !LOCAL) ? (int)blockDim.x : nthreads;
-    RQTRACE_DECL;
-    RQTRACE(0);
     const int li = lane & 15, lg = lane >> 4;
     const int n1p16 = sh.at * 16, n1p32 = sh.ch2 * 32, n2p32 = sh.k1 * 32;
     char* vt = lds + grp * sh.r0bytes;                                 // token rows, later the code image
@@ -307,11 +305,9 @@ __device__ __forceinline__ void rotate3_token(char* lds, const uint16_t* __restr
             if (it < crow_items) *chunk_dst(0, it) = first[e];
         }
     }
-    RQTRACE(1);
     // (a barrier that orders LDS only: loads of later stages, and in a loop the stores of the
     // round before, stay in flight)
     bwla_lds_barrier();
-    RQTRACE(2);
 
     // ---- stage 1
     v4f z[ATM];
@@ -345,11 +341,9 @@ __device__ __forceinline__ void rotate3_token(char* lds, const uint16_t* __restr
     }
 
     // ---- stage 2: chunk ch contracts a in [32 ch, 32 ch + 32) = accumulator tiles 2 ch, 2 ch + 1
-    RQTRACE(3);
     if (early) {
         rp_store();
         bwla_lds_barrier();
-        RQTRACE(7);
     }
     if (sh.alias) __syncthreads();                     // the token rows make room for a chunk buffer
     v4f y[ATM];
@@ -408,7 +402,6 @@ __device__ __forceinline__ void rotate3_token(char* lds, const uint16_t* __restr
         }
     }
 
-    RQTRACE(4);
     // ---- per-token max magnitude (padded rows and columns are exact zeros)
     // (symmetric codes need the largest magnitude only: one reduction, stored as hi = -lo)
     float mx = 0.0f, mn = 0.0f;
@@ -445,7 +438,6 @@ __device__ __forceinline__ void rotate3_token(char* lds, const uint16_t* __restr
         for (int off = 8; off > 0; off >>= 1) lo = fminf(lo, __shfl_xor(lo, off, 64));
     }
     const QuantPlan qp = quant_plan(hi, lo, qmax, asym);
-    RQTRACE(5);
 
     // ---- quantize: lane holds Yt[d = 16*strip + 4*lg + v][c = 16*tc + li], four consecutive d of one c
     // (one token per workgroup and rows of whole words: the codes go straight to global memory,
@@ -505,13 +497,11 @@ __device__ __forceinline__ void rotate3_token(char* lds, const uint16_t* __restr
             }
         }
     }
-    RQTRACE(6);
     // the code image and the reduction words are free again (LDS only: the round's stores to
     // global memory need not have landed)
     if constexpr (LOOP) bwla_lds_barrier();
     tp0 += DUAL ? 2 * t_stride : t_stride;
     } while (LOOP && tp0 < M);
-    RQTRACE_FLUSH;
 }
 
 }  // namespace

@@ -1,22 +1,10 @@
-// Shared by the rotation kernels: development trace hooks, the per-token quantizer plan
+// Shared by the rotation kernels: the per-token quantizer plan
 // (symmetric or min-max affine codes), launch constants, LDS shapes of the fp32 path, fast division.
 #pragma once
 #include "bwla_internal.h"
 
 namespace {
 
-#ifdef BWLA_TRACE
-// Development aid (off in the product build): cycle stamps are kept in registers and written
-// once at the end of the workgroup, so that taking them adds no memory waits.
-__device__ long long bwla_rq_trace_buf[16 * 8 * 16];
-#define RQTRACE_DECL long long rq_tr[10] = {0, 0, 0, 0, 0, 0, 0, 0, 0, 0}
-#define RQTRACE(slot) do { rq_tr[slot] = __builtin_readcyclecounter(); } while (0)
-#define RQTRACE_FLUSH do { if ((threadIdx.x & 63) == 0 && blockIdx.x < 16) { _Pragma("unroll") for (int i_ = 0; i_ < 10; ++i_) bwla_rq_trace_buf[(blockIdx.x * 8 + (threadIdx.x >> 6)) * 16 + i_] = rq_tr[i_]; } } while (0)
-#else
-#define RQTRACE_DECL do { } while (0)
-#define RQTRACE(slot) do { } while (0)
-#define RQTRACE_FLUSH do { } while (0)
-#endif
 
 // How a token is quantized, from its largest and smallest rotated value (hi >= 0 >= lo: the
 // reductions start at zero, which also covers the zero padding).

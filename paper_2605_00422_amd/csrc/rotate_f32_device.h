@@ -196,16 +196,12 @@ __device__ __forceinline__ void rotate_token(float* lds, const void* __restrict_
 #pragma unroll
     for (int s = 0; s < RQ_MAXT; ++s) acc[s] = v4f{0.f, 0.f, 0.f, 0.f};
 
-    RQTRACE_DECL;
-    RQTRACE(0);
     fill_lds<BF16>(X, t * K, n1, n2, R1, R2, sh, reg, fac, fac + sh.n2p * sh.ld2t);
 
     if (sh.resident) {
         const float* r2t = fac;
         const float* r1t = fac + sh.n2p * sh.ld2t;
-        RQTRACE(1);
         __syncthreads();
-        RQTRACE(2);
         // stage 1: Z[a][d] = sum_b V[a][b] R2[b][d];   tile (ti over a, tj over d)
 #pragma unroll
         for (int g = 0; g < RQ_MAXT / 2; ++g) {
@@ -225,7 +221,6 @@ __device__ __forceinline__ void rotate_token(float* lds, const void* __restrict_
                 }
             }
         }
-        RQTRACE(3);
         bwla_lds_barrier();                                        // every wave is done reading V
         // lane holds Z[a = ti*16 + 4*lg + v][d = tj*16 + li]: one 128-bit store into ZT[d][a..a+3]
 #pragma unroll
@@ -239,7 +234,6 @@ __device__ __forceinline__ void rotate_token(float* lds, const void* __restrict_
             }
         }
         bwla_lds_barrier();                                        // ZT is published
-        RQTRACE(4);
         // stage 2: Yt[d][c] = sum_a ZT[d][a] R1[a][c];   tile (ti over d, tj over c)
 #pragma unroll
         for (int g = 0; g < RQ_MAXT / 2; ++g) {
@@ -306,7 +300,6 @@ __device__ __forceinline__ void rotate_token(float* lds, const void* __restrict_
                     bwla_lds_barrier();
                 }
             }
-            if (stage == 0) RQTRACE(3); else RQTRACE(9);
             if (stage == 0) {
                 // lane holds Z[a = ti*16 + 4*lg + v][d = tj*16 + li] -> ZT[d][a..a+3]; V is dead
                 // (every wave passed the last barrier of the loop)
@@ -324,7 +317,6 @@ __device__ __forceinline__ void rotate_token(float* lds, const void* __restrict_
         }
     }
 
-    RQTRACE(5);
     // ================= per-token max magnitude
     float mx = 0.0f, mn = 0.0f;
 #pragma unroll
@@ -341,7 +333,6 @@ __device__ __forceinline__ void rotate_token(float* lds, const void* __restrict_
 #pragma unroll
     for (int w = 1; w < RQ_WAVES; ++w) { hi = fmaxf(hi, red[w]); lo = fminf(lo, red[32 + w]); }
     const QuantPlan qp = quant_plan(hi, lo, qmax, asym);
-    RQTRACE(6);
 
     // ================= quantize from registers into an LDS byte image of the token's codes:
     // lane holds Yt[d = ti*16 + 4*lg + v][c = tj*16 + li], i.e. four consecutive d of one c
@@ -385,7 +376,6 @@ __device__ __forceinline__ void rotate_token(float* lds, const void* __restrict_
         const int n16 = (int)(K >> 4);
         for (int idx = tid; idx < n16; idx += RQ_THREADS) dst[idx] = src[idx];
     }
-    RQTRACE(7);
     if (tid == 0) {
         int tot = 0;
 #pragma unroll
@@ -395,8 +385,6 @@ __device__ __forceinline__ void rotate_token(float* lds, const void* __restrict_
         scale[t] = sc;
         quant_extras(tmode, tp, t, asym, shift, qp, sc, tot, K);
     }
-    RQTRACE(8);
-    RQTRACE_FLUSH;
 #undef RQ_PAIR_SLOTS
 }
 

@@ -94,8 +94,7 @@ __global__ __launch_bounds__(640) void rotate_split_kernel(RqArgs a) {
 
 template <int ATM, int THREADS, bool LOOP, bool DUAL = false>
 hipError_t launch_rotate3_v(const RqArgs& a, int64_t blocks, int threads, size_t lds, hipStream_t st) {
-    static bwla_lds_attr attr;
-    hipError_t e = attr.ensure((const void*)rotate_quant3_kernel<ATM, THREADS, LOOP, DUAL>, lds);
+    hipError_t e = bwla_ensure_lds((const void*)rotate_quant3_kernel<ATM, THREADS, LOOP, DUAL>, lds);
     if (e != hipSuccess) return e;
     rotate_quant3_kernel<ATM, THREADS, LOOP, DUAL><<<dim3((unsigned)blocks), dim3((unsigned)threads), lds, st>>>(a);
     return hipGetLastError();
@@ -124,11 +123,6 @@ hipError_t launch_rotate3(const RqArgs& a, int64_t blocks, int threads, size_t l
 // (With r > 0 the projection T = x U would have to reach every workgroup inside the launch; the
 // arrival counting and the wait that this takes cost more than the second launch saves.)
 constexpr int FD_THREADS = 512;
-#ifdef BWLA_TRACE
-#define FDTRACE(slot) do { if ((threadIdx.x & 63) == 0 && (blockIdx.x & 3) == 0 && blockIdx.x < 256) bwla_trace_buf[((blockIdx.x >> 2) * 16 + 8 + (threadIdx.x >> 6)) * 40 + (slot)] = wall_clock64(); } while (0)
-#else
-#define FDTRACE(slot) do { } while (0)
-#endif
 template <int ATM, bool FAST>
 __global__ __launch_bounds__(FD_THREADS) void decode_fused_kernel(RqArgs ra, BsArgs ba) {
     extern __shared__ __align__(16) float lds[];
@@ -141,10 +135,8 @@ __global__ __launch_bounds__(FD_THREADS) void decode_fused_kernel(RqArgs ra, BsA
     const int first = (int)blockIdx.x, stride = (int)gridDim.x;
     const int n_iter = (ba.row_tiles - first + stride - 1) / stride;
     if (wave < sh.strips) {
-        FDTRACE(0);
         rotate3_token<ATM, false, true>(rot, reinterpret_cast<const uint16_t*>(ra.X), 0, 1, 1, ra.K, ra.n1, ra.n2,
                                         ra.R1p, ra.R2p, ra.q, ra.scale, ra.qsum, first == 0);
-        FDTRACE(1);
         if (wave != 0) return;
         epilogue_wave<2, 1, 0, FAST, true>(ba, smem, first, stride, n_iter, ba.KS, lane, fl);
     } else {
@@ -176,14 +168,6 @@ __global__ __launch_bounds__(256) void code_sums_kernel(const int8_t* __restrict
 
 }  // namespace
 
-#ifdef BWLA_TRACE
-extern "C" int bwla_fd_trace_dump(long long* host, int n) {
-    return (int)hipMemcpyFromSymbol(host, HIP_SYMBOL(bwla_trace_buf), (size_t)n * sizeof(long long));
-}
-extern "C" int bwla_rq_trace_dump(long long* host, int n) {
-    return (int)hipMemcpyFromSymbol(host, HIP_SYMBOL(bwla_rq_trace_buf), (size_t)n * sizeof(long long));
-}
-#endif
 
 size_t bwla_rotate_lds_bytes(int n1, int n2) { return rq_shape(n1, n2).lds_bytes; }
 // factors that do not fit into LDS are streamed with 16-byte loads, which needs n % 4 == 0
@@ -266,8 +250,7 @@ hipError_t bwla_launch_rotate_quant(const bwla_layer_t* L, const void* dX, int x
         const int threads3 = s3.strips > 8 ? 64 * s3.strips : 512;     // the projection wants eight wavefronts
         const size_t pl3 = merged ? pp_lds_bytes(ru, threads3 / 64) : 0;
         const size_t lds3 = pl3 > rs.lds_bytes ? pl3 : rs.lds_bytes;
-        static bwla_lds_attr attr;
-        e = attr.ensure((const void*)rotate_split_kernel, lds3);
+        e = bwla_ensure_lds((const void*)rotate_split_kernel, lds3);
         if (e != hipSuccess) return e;
         rotate_split_kernel<<<dim3((unsigned)(a.rot_blocks + pblocks)), dim3((unsigned)threads3), lds3, st>>>(a);
         e = hipGetLastError();
@@ -333,13 +316,11 @@ hipError_t bwla_launch_rotate_quant(const bwla_layer_t* L, const void* dX, int x
     }
     const size_t lds = plds > sh.lds_bytes ? plds : sh.lds_bytes;
     if (xdtype == BWLA_X_BF16) {
-        static bwla_lds_attr attr;
-        e = attr.ensure((const void*)rotate_quant_kernel<true>, lds);
+        e = bwla_ensure_lds((const void*)rotate_quant_kernel<true>, lds);
         if (e != hipSuccess) return e;
         rotate_quant_kernel<true><<<dim3((unsigned)(M + pblocks)), dim3(RQ_THREADS), lds, st>>>(a);
     } else {
-        static bwla_lds_attr attr;
-        e = attr.ensure((const void*)rotate_quant_kernel<false>, lds);
+        e = bwla_ensure_lds((const void*)rotate_quant_kernel<false>, lds);
         if (e != hipSuccess) return e;
         rotate_quant_kernel<false><<<dim3((unsigned)(M + pblocks)), dim3(RQ_THREADS), lds, st>>>(a);
     }
@@ -398,8 +379,7 @@ hipError_t bwla_launch_decode_fused(const bwla_layer_t* L, const void* dX, int x
     const int G = row_tiles < cus ? row_tiles : cus;
     const bool fast = (L->N % 4 == 0) && dacc == nullptr;
     auto launch = [&](auto kern) -> hipError_t {
-        static bwla_lds_attr attr;
-        hipError_t e = attr.ensure((const void*)kern, lds);
+        hipError_t e = bwla_ensure_lds((const void*)kern, lds);
         if (e != hipSuccess) return e;
         kern<<<dim3((unsigned)G), dim3(FD_THREADS), lds, st>>>(ra, ba);
         return hipGetLastError();

@@ -53,8 +53,6 @@ __device__ __forceinline__ void rotate_slice_block(char* lds, const uint16_t* __
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);         // = strip
     // all wavefronts of the workgroup fetch; those beyond the strips end behind the first barrier
     const bool worker = wave < sh.strips;
-    RQTRACE_DECL;
-    RQTRACE(0);
     const int nthreads = (int)blockDim.x;
     const int n1p16 = sh.at * 16, n1p32 = sh.ch2 * 32, n2p32 = sh.k1 * 32;
     char* vt = lds;                                                    // token rows V[a][b]
@@ -161,10 +159,8 @@ __device__ __forceinline__ void rotate_slice_block(char* lds, const uint16_t* __
     if ((sh.strips & 1) != 0)
         for (int i = tid; i < 3 * 16 * 2; i += nthreads)
             *reinterpret_cast<v4i*>(pl + (i >> 1) * rs.ppitch + sh.strips * 32 + (i & 1) * 16) = v4i{0, 0, 0, 0};
-    RQTRACE(1);
     bwla_lds_barrier();
     if (!worker) return;
-    RQTRACE(2);
 
     // ---- A: tile of P for my strip of b: rows of the tile are b = 16 w + 4 lg + v, columns c = li
     {
@@ -213,9 +209,7 @@ __device__ __forceinline__ void rotate_slice_block(char* lds, const uint16_t* __
         *reinterpret_cast<uint2*>(pd + 16 * rs.ppitch) = uint2{w2[0], w2[1]};
         *reinterpret_cast<uint2*>(pd + 32 * rs.ppitch) = uint2{w3[0], w3[1]};
     }
-    RQTRACE(3);
     bwla_lds_barrier();
-    RQTRACE(4);
 
     // ---- B: my strip of the result: rows c = 16 j + 4 lg + v, column d = 16 w + li
     v4f y = v4f{0.f, 0.f, 0.f, 0.f};
@@ -239,7 +233,6 @@ __device__ __forceinline__ void rotate_slice_block(char* lds, const uint16_t* __
             }
         }
     }
-    RQTRACE(5);
 
     // ---- rotated values out, and the extremes of my tile (0 included)
     float mx = 0.0f, mn = 0.0f;
@@ -262,8 +255,6 @@ __device__ __forceinline__ void rotate_slice_block(char* lds, const uint16_t* __
         pm[1] = mn;
         if (j == 0 && wave == 0) qsum[t] = 0;          // the quantizing launch adds its sums up here
     }
-    RQTRACE(6);
-    RQTRACE_FLUSH;
 }
 
 // second launch of the split rotation: RS_QB workgroups per token quantize the rotated values, each

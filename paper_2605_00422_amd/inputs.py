@@ -35,13 +35,10 @@ class LayerConfig:
     seed: int = 0
 
 
-def _near_square(n: int) -> tuple[int, int]:
-    """Largest divisor not above sqrt(n) and its cofactor, larger first (shape bookkeeping for
-    the config table only; the library has its own implementation of the paper's Alg. 1)."""
-    a = int(np.floor(np.sqrt(n)))
-    while a > 1 and n % a:
-        a -= 1
-    return n // a, a
+# Kronecker pairs (n1, n2) of the block widths used below, as the paper's Algorithm 1 gives them
+# (App. A.1): written out, so that this module holds none of the method's steps.  The tests hold
+# them against both the oracle's and the library's implementation of the algorithm.
+KRON_PAIRS = {4096: (64, 64), 8192: (128, 64), 11008: (128, 86), 28672: (224, 128)}
 
 
 def _pct(K: int, frac: float) -> int:
@@ -66,7 +63,7 @@ def block70b_configs(M: int) -> list[LayerConfig]:
     out = []
     for nm, K, N in (("q", h, h), ("k", h, kv), ("v", h, kv), ("o", h, h),
                      ("gate", h, inter), ("up", h, inter), ("down", inter, h)):
-        n1, n2 = _near_square(K)
+        n1, n2 = KRON_PAIRS[K]
         out.append(LayerConfig(f"cfg4_70b_{nm}_m{M}", M, K, n1, n2, N, 64, "bf16",
                                _pct(K, 0.01), 50.0))
     return out
@@ -82,7 +79,7 @@ def block7b_configs(M: int) -> list[LayerConfig]:
     out = []
     for nm, K, N, r in (("q", h, h, 32), ("gate", h, inter, 32), ("down", inter, h, 32),
                         ("qkv", h, 3 * h, 96), ("gateup", h, 2 * inter, 64)):
-        n1, n2 = _near_square(K)
+        n1, n2 = KRON_PAIRS[K]
         out.append(LayerConfig(f"cfg1_7b_{nm}_m{M}", M, K, n1, n2, N, r, "bf16", _pct(K, 0.01), 50.0))
     return out
 

@@ -47,11 +47,13 @@ def test_cfg3_qwen32b_down_prefill_sampled_rows():
 
 
 @pytest.mark.parametrize("M", [1, 64])
-@pytest.mark.parametrize("which", ["k", "o", "down"])
+@pytest.mark.parametrize("which", ["k", "o", "gate", "down"])
 def test_cfg4_70b_block_small_m(which, M):
+    """The block's four distinct layer shapes (q = o, v = k, up = gate) at one and at 64 tokens."""
     from parity_util import run_case
     cfg = {c.name.split("_")[2]: c for c in syn.block70b_configs(M)}[which]
-    print(run_case(cfg), flush=True)
+    rows = None if which != "gate" or M == 1 else _sample_rows(M, 16)   # (oracle time: 28672 channels)
+    print(run_case(cfg, rows=rows), flush=True)
 
 
 @pytest.mark.parametrize("which", ["qkv", "gateup"])
@@ -77,10 +79,13 @@ def test_looping_rotation_two_tokens_at_a_time_fewer_pairs_than_cus():
     print(run_case(cfg, rows=[0, 1, 2, 149, 150, 151, 298, 299, 300]), flush=True)
 
 
-def test_cfg4_70b_gate_m4096_sampled_rows():
+@pytest.mark.parametrize("which", ["q", "k", "gate", "down"])
+def test_cfg4_70b_block_m4096_sampled_rows(which):
+    """The block's four distinct shapes at 4096 tokens, full size on the GPU in the benchmarked
+    launch configuration; the oracle checks a seeded sample of token rows plus the first and last."""
     from parity_util import run_case
-    cfg = {c.name.split("_")[2]: c for c in syn.block70b_configs(4096)}["gate"]
-    print(run_case(cfg, rows=_sample_rows(cfg.M, 32)), flush=True)
+    cfg = {c.name.split("_")[2]: c for c in syn.block70b_configs(4096)}[which]
+    print(run_case(cfg, rows=_sample_rows(cfg.M, 32 if which in ("gate", "down") else 48)), flush=True)
 
 
 @pytest.mark.parametrize("M,K,n1,n2,N,r,xd", [

@@ -29,6 +29,13 @@ def test_exports_match_header(lib):
     assert declared == set(B.EXPORTS)
     for name in declared:
         assert hasattr(lib, name), name
+    # and nothing else of the library's own is visible from outside
+    import shutil
+    import subprocess
+    nm = shutil.which("nm") or "/opt/rocm/llvm/bin/llvm-nm"
+    out = subprocess.run([nm, "-D", "--defined-only", B.LIB_PATH], capture_output=True, text=True, check=True).stdout
+    exported = {l.split()[-1] for l in out.splitlines() if l.split() and " T " in l}
+    assert {n for n in exported if "bwla" in n} == declared
 
 
 def test_status_strings_and_version(lib):
@@ -51,6 +58,9 @@ def test_kron_factor_matches_hand_pairs(lib):
         assert n1 * n2 == n and n2 <= n1
         assert n2 == max(d for d in range(1, n + 1) if n % d == 0 and d * d <= n)
     a, b = c_int32(), c_int32()
+    from paper_2605_00422_amd import inputs as syn
+    for K, pair in syn.KRON_PAIRS.items():
+        assert B.kron_factor(K) == pair, K
     assert lib.bwla_kron_factor(0, byref(a), byref(b)) == B.BWLA_ERR_SHAPE
     assert lib.bwla_kron_factor(16, None, byref(b)) == B.BWLA_ERR_NULL
 

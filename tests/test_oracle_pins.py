@@ -42,6 +42,12 @@ def test_kron_factor_hand_pairs():
             assert orc.kron_factor(n) == (n1, n2), n
 
 
+def test_input_module_pairs_are_algorithm_one():
+    """The config table's literal pairs are what Algorithm 1 gives for those widths."""
+    for K, pair in syn.KRON_PAIRS.items():
+        assert orc.kron_factor(K) == pair, K
+
+
 def test_kron_factor_properties_bruteforce():
     for n in range(1, 600):
         n1, n2 = orc.kron_factor(n)
