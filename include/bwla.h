@@ -242,6 +242,26 @@ BWLA_API bwla_status_t bwla_decode_forward(const bwla_layer_t* layer, const void
                                   void* stream);
 
 /*
+ * bwla_decode_forward for callers that cannot allocate device memory or hand over a workspace: code
+ * under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same inputs,
+ * outputs, results and errors as bwla_decode_forward, but the scratch (arrival counters and partial
+ * sums of the projection, and for a few tokens of a layer with a large factor R1 the rotated values
+ * between the rotation's two launches) lives in a fixed array of BWLA_STATIC_SCRATCH_BYTES inside
+ * the library's device image, one per GPU, held until the process ends.  The call allocates
+ * nothing and calls no allocating routine; it clears the counters it needs with a small kernel.
+ *   - A call whose bwla_psp_workspace_size(layer, M) exceeds BWLA_STATIC_SCRATCH_BYTES returns
+ *     BWLA_ERR_BUFSIZE and enqueues nothing (decode batches of the common model widths fit; long
+ *     prefills do not: use bwla_decode_forward with a workspace of the caller's).
+ *   - Every call on a GPU uses that GPU's one array: calls that may overlap in time on one GPU (two
+ *     streams, two host threads) race on it and must be serialized by the caller.
+ *   - The first call on a device looks the array's address up (once per device and process).
+ */
+#define BWLA_STATIC_SCRATCH_BYTES (4u << 20)
+BWLA_API bwla_status_t bwla_decode_forward_static(const bwla_layer_t* layer, const void* d_X, int xdtype,
+                                                  int64_t M, int8_t* d_q, float* d_scale, int32_t* d_qsum,
+                                                  float* d_T, float* d_Y, int32_t* d_acc, void* stream);
+
+/*
  * bwla_linear_forward for the merged gate|up projection of an MLP block, with the block's gate
  * applied before anything is stored (the models the paper quantizes have up, gate and down
  * projections in their MLP blocks: paper App., loss trajectories of the MLP blocks; the

@@ -19,7 +19,7 @@ EXPORTS = ["bwla_status_string", "bwla_version", "bwla_kron_factor", "bwla_packe
            "bwla_unpack_signs", "bwla_psp_workspace_size", "bwla_rotate_quant", "bwla_code_sums",
            "bwla_linear_forward", "bwla_decode_forward", "bwla_packed_size_centered", "bwla_pack_weights_centered", "bwla_rotate_quant_bits",
            "bwla_packed_size_mode", "bwla_pack_weights_mode", "bwla_swiglu_workspace_size",
-           "bwla_linear_forward_swiglu"]
+           "bwla_linear_forward_swiglu", "bwla_decode_forward_static"]
 
 
 class BwlaLayer(Structure):
@@ -71,6 +71,8 @@ def load() -> ctypes.CDLL:
                                         c_void_p, c_void_p, c_void_p]
     lib.bwla_decode_forward.argtypes = [POINTER(BwlaLayer), c_void_p, c_int, c_int64, c_void_p, c_void_p, c_void_p,
                                         c_void_p, c_void_p, c_size_t, c_void_p, c_void_p, c_void_p]
+    lib.bwla_decode_forward_static.argtypes = [POINTER(BwlaLayer), c_void_p, c_int, c_int64, c_void_p, c_void_p,
+                                               c_void_p, c_void_p, c_void_p, c_void_p, c_void_p]
     lib.bwla_swiglu_workspace_size.argtypes = [POINTER(BwlaLayer), c_int64, POINTER(c_size_t)]
     lib.bwla_linear_forward_swiglu.argtypes = [POINTER(BwlaLayer), c_void_p, c_void_p, c_void_p, c_void_p, c_int64,
                                                c_void_p, c_void_p, c_size_t, c_void_p]
@@ -214,6 +216,18 @@ def decode_forward(layer: PackedLayer, X, act: Activations, Y, acc=None):
     _check(load().bwla_decode_forward(byref(layer.desc), _ptr(X), xd, X.shape[0], _ptr(act.q), _ptr(act.scale),
                                       _ptr(act.qsum), _ptr(act.T), _ptr(act.ws), act.ws_bytes, _ptr(Y), _ptr(acc),
                                       _stream()), "bwla_decode_forward")
+    return Y
+
+
+def decode_forward_static(layer: PackedLayer, X, act: Activations, Y, acc=None):
+    """bwla_decode_forward with the library's own fixed scratch (act.ws is not used)."""
+    import torch
+    if X.dtype not in (torch.bfloat16, torch.float32):
+        raise TypeError("X must be float32 or bfloat16")
+    xd = BWLA_X_BF16 if X.dtype == torch.bfloat16 else BWLA_X_F32
+    _check(load().bwla_decode_forward_static(byref(layer.desc), _ptr(X), xd, X.shape[0], _ptr(act.q), _ptr(act.scale),
+                                             _ptr(act.qsum), _ptr(act.T), _ptr(Y), _ptr(acc), _stream()),
+           "bwla_decode_forward_static")
     return Y
 
 

@@ -102,6 +102,40 @@ hipError_t bwla_ensure_lds(const void* fn, size_t bytes) {
     return e;
 }
 
+// ---------------------------------------------------------------- scratch of the allocation-free call
+// One array per GPU the library runs on, held until the process ends.  `scratch` itself is only the
+// host-side name of the symbol: the device address is asked for once per device (with that device
+// current) and that pointer is what kernels and fills get.
+static __device__ __align__(256) unsigned char scratch[BWLA_STATIC_SCRATCH_BYTES];
+
+namespace {
+
+__global__ void fill_zero_kernel(uint32_t* p, int n) {
+    const int i = (int)(blockIdx.x * blockDim.x + threadIdx.x);
+    if (i < n) p[i] = 0u;
+}
+
+hipError_t static_scratch_ptr(void** out) {
+    static std::mutex mu;
+    static void* ptrs[64] = {nullptr};
+    int dev = 0;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return e;
+    if (dev < 0 || dev >= 64) return hipErrorInvalidDevice;
+    std::lock_guard<std::mutex> lock(mu);
+    if (ptrs[dev] == nullptr) {
+        void* p = nullptr;
+        e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+        if (e != hipSuccess) return e;
+        if (p == nullptr) return hipErrorInvalidSymbol;
+        ptrs[dev] = p;
+    }
+    *out = ptrs[dev];
+    return hipSuccess;
+}
+
+}  // namespace
+
 extern "C" {
 
 const char* bwla_status_string(int status) {
@@ -261,6 +295,35 @@ bwla_status_t bwla_decode_forward(const bwla_layer_t* layer, const void* d_X, in
     s = bwla_rotate_quant(layer, d_X, xdtype, M, d_q, d_scale, d_qsum, d_T, d_ws, ws_bytes, stream);
     if (s != BWLA_OK) return s;
     return bwla_linear_forward(layer, d_q, d_scale, d_qsum, d_T, M, d_Y, d_acc, stream);
+}
+
+bwla_status_t bwla_decode_forward_static(const bwla_layer_t* layer, const void* d_X, int xdtype, int64_t M,
+                                         int8_t* d_q, float* d_scale, int32_t* d_qsum, float* d_T, float* d_Y,
+                                         int32_t* d_acc, void* stream) {
+    // everything that can be refused is refused before the scratch is touched
+    bwla_status_t s = check_layer(layer);
+    if (s != BWLA_OK) return s;
+    if (M <= 0 || M > (int64_t)1 << 24) return BWLA_ERR_SHAPE;
+    const bwla_psp_plan plan = bwla_make_psp_plan(M, layer->K, bwla_rank_u(layer));
+    const size_t need = rq_ws_bytes(layer, plan, M);
+    if (need > BWLA_STATIC_SCRATCH_BYTES) return BWLA_ERR_BUFSIZE;
+    if (!d_X || !d_q || !d_scale || !d_qsum || !d_Y) return BWLA_ERR_NULL;
+    if (layer->r > 0 && !d_T) return BWLA_ERR_NULL;
+    if (xdtype != BWLA_X_F32 && xdtype != BWLA_X_BF16) return BWLA_ERR_UNSUPPORTED;
+    if (!aligned16(d_X) || !aligned16(d_q) || !aligned16(d_Y) || (d_T && !aligned16(d_T)) ||
+        (d_acc && !aligned16(d_acc)))
+        return BWLA_ERR_ALIGN;
+    void* ws = nullptr;
+    if (static_scratch_ptr(&ws) != hipSuccess) return BWLA_ERR_HIP;
+    if (need > 0) {
+        // the arrival counters at the head of the scratch must read zero; a kernel clears them (a
+        // memset node would not replay reliably from a captured graph)
+        const int words = (int)(bwla_psp_counter_bytes(M) / sizeof(uint32_t));
+        fill_zero_kernel<<<dim3((unsigned)((words + 255) / 256)), dim3(256), 0, (hipStream_t)stream>>>((uint32_t*)ws, words);
+        if (hipGetLastError() != hipSuccess) return BWLA_ERR_HIP;
+    }
+    return bwla_decode_forward(layer, d_X, xdtype, M, d_q, d_scale, d_qsum, d_T, ws, BWLA_STATIC_SCRATCH_BYTES, d_Y,
+                               d_acc, stream);
 }
 
 bwla_status_t bwla_code_sums(const int8_t* d_q, int64_t M, int64_t K, int32_t* d_qsum, void* stream) {
