@@ -66,10 +66,15 @@ typedef enum {
  *          interchange view); 16-row tiles x 512-column chunks, 1 KiB each
  *   alpha  N fp16, alpha_n = mean_k |W_rot[n,k]|            (paper App. A.2.4)
  *   V      N x rp fp16 row-major, rp = r rounded up to a multiple of 16, zero padded
- *   U      rp x K fp16: U transposed (row j holds column j of U), rows r..rp-1 zero
+ *   U      rp * K fp16 in MFMA operand order: 1 KiB blocks [16-column tile][32-row step], inside a
+ *          block lane lg * 16 + li holds U[32 step + 8 lg + e][16 tile + li], e = 0..7; columns
+ *          r..rp-1 zero
  *   R1     n1 x n1 fp32 row-major;  R2  n2 x n2 fp32 row-major
  *   R1p, R2p  the same factors transposed and split into three bfloat16 terms each (their sum is
  *          the fp32 value exactly), zero padded: operand layout of the bf16-MFMA rotation
+ *   Rd     only for factor pairs of 32 or 64 (off_Rd = 0 otherwise): the factors once more, in the
+ *          order in which the single-launch decode kernel reads them, one contiguous KiB per MFMA
+ *          operand -- R2 as three bfloat16 terms, R1 as two fp16 terms of 256 R1 (22 bits)
  * `mode` is a set of BWLA_MODE_* bits; each adds rank-one terms of the dequantization as extra
  * columns of V (written at pack time) and T (written by bwla_rotate_quant) behind the PSP columns,
  * and r counts them: U keeps r - extra columns.
@@ -82,7 +87,7 @@ typedef enum {
 typedef struct bwla_layer {
     int64_t N, K;
     int32_t n1, n2, r, mode;
-    uint64_t off_bits, off_alpha, off_V, off_U, off_R1, off_R2, off_R1p, off_R2p;
+    uint64_t off_bits, off_alpha, off_V, off_U, off_R1, off_R2, off_R1p, off_R2p, off_Rd;
     uint64_t blob_bytes;
     const void* d_blob;
 } bwla_layer_t;
@@ -231,10 +236,12 @@ BWLA_API bwla_status_t bwla_linear_forward(const bwla_layer_t* layer, const int8
  * same accuracy.  Where the single-launch kernel serves the call, its rotation may add the
  * products in another order than the kernel bwla_rotate_quant picks for the shape, so a code
  * whose value lies on a rounding boundary can differ by one between the two.  For a single
- * bf16 token of a layer without low-rank part (r == 0) on the common decode shapes (K = 4096 with
- * n2 = 64, for one) everything runs in ONE kernel launch: every GEMM workgroup rotates and
- * quantizes the token itself while its first weights are in flight, and nothing crosses
- * workgroups.  All other cases run the two launches back to back.
+ * bf16 token of a layer whose Kronecker factors are 32 or 64 wide (K = 1024 .. 4096: the
+ * attention and up / gate projections of the 4096-wide models), with a PSP rank up to 64 and
+ * symmetric codes (with or without the row shift), everything runs in ONE kernel launch: every
+ * workgroup rotates and quantizes the token itself while its sign bits stream in, half of its
+ * wavefronts compute T = x U meanwhile, and nothing crosses workgroups.  All other cases run the
+ * two launches back to back.
  */
 BWLA_API bwla_status_t bwla_decode_forward(const bwla_layer_t* layer, const void* d_X, int xdtype, int64_t M,
                                   int8_t* d_q, float* d_scale, int32_t* d_qsum, float* d_T,

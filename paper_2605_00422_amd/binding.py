@@ -26,7 +26,7 @@ class BwlaLayer(Structure):
     _fields_ = [("N", c_int64), ("K", c_int64), ("n1", c_int32), ("n2", c_int32), ("r", c_int32),
                 ("mode", c_int32), ("off_bits", c_uint64), ("off_alpha", c_uint64), ("off_V", c_uint64),
                 ("off_U", c_uint64), ("off_R1", c_uint64), ("off_R2", c_uint64), ("off_R1p", c_uint64), ("off_R2p", c_uint64),
-                ("blob_bytes", c_uint64),
+                ("off_Rd", c_uint64), ("blob_bytes", c_uint64),
                 ("d_blob", c_void_p)]
 
 

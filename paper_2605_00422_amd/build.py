@@ -10,7 +10,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB_PATH = os.path.join(HERE, "libbwla.so")
-SOURCES = ["api.hip", "pack.hip", "rotate_quant.hip", "gemm_decode.hip", "gemm_decode_bs.hip", "gemm_prefill.hip", "psp_prefill.hip"]
+SOURCES = ["api.hip", "pack.hip", "rotate_quant.hip", "gemm_decode.hip", "gemm_decode_bs.hip", "gemm_prefill.hip", "psp_prefill.hip", "decode_layer.hip"]
 
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-fvisibility=hidden",
@@ -18,9 +18,14 @@ FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-fvisibility=hi
          "-I", os.path.join(ROOT, "include"), "-I", CSRC]
 
 
+# Per-file flags.  decode_layer.hip: the first 14 dwords of its kernels' arguments (seven pointers)
+# are preloaded into SGPRs when a wavefront starts, instead of being fetched by the kernel.
+FILE_FLAGS = {"decode_layer.hip": ["-mllvm", "-amdgpu-kernarg-preload-count=14"]}
+
+
 def _compile(src: str, extra: list[str]) -> str:
     obj = os.path.join(CSRC, src.replace(".hip", ".o"))
-    cmd = [HIPCC, *FLAGS, *extra, "-c", os.path.join(CSRC, src), "-o", obj]
+    cmd = [HIPCC, *FLAGS, *FILE_FLAGS.get(src, []), *extra, "-c", os.path.join(CSRC, src), "-o", obj]
     res = subprocess.run(cmd, capture_output=True, text=True)
     err = "\n".join(l for l in res.stderr.splitlines()
                     if "not a recognized feature for this target" not in l)

@@ -47,6 +47,8 @@ void fill_layout(bwla_layer_t* L, int64_t N, int64_t K, int32_t n1, int32_t n2, 
     L->off_R2 = off;    off = bwla_align256(off + (uint64_t)n2 * n2 * 4);
     L->off_R1p = off;   off = bwla_align256(off + bwla_factor_planes_bytes(n1));
     L->off_R2p = off;   off = bwla_align256(off + bwla_factor_planes_bytes(n2));
+    L->off_Rd = 0;
+    if (bwla_decode_planes_bytes(n1, n2) > 0) { L->off_Rd = off; off = bwla_align256(off + bwla_decode_planes_bytes(n1, n2)); }
     L->blob_bytes = off;
 }
 
@@ -61,7 +63,8 @@ bwla_status_t check_layer(const bwla_layer_t* L) {
     fill_layout(&ref, L->N, L->K, L->n1, L->n2, L->r, L->mode);
     if (ref.off_bits != L->off_bits || ref.off_alpha != L->off_alpha || ref.off_V != L->off_V ||
         ref.off_U != L->off_U || ref.off_R1 != L->off_R1 || ref.off_R2 != L->off_R2 ||
-        ref.off_R1p != L->off_R1p || ref.off_R2p != L->off_R2p || ref.blob_bytes != L->blob_bytes)
+        ref.off_R1p != L->off_R1p || ref.off_R2p != L->off_R2p || ref.off_Rd != L->off_Rd ||
+        ref.blob_bytes != L->blob_bytes)
         return BWLA_ERR_SHAPE;
     if (!aligned16(L->d_blob)) return BWLA_ERR_ALIGN;
     return BWLA_OK;
@@ -151,7 +154,7 @@ const char* bwla_status_string(int status) {
     }
 }
 
-int bwla_version(void) { return 1; }
+int bwla_version(void) { return 2; }
 
 bwla_status_t bwla_kron_factor(int64_t K, int32_t* n1, int32_t* n2) {
     if (!n1 || !n2) return BWLA_ERR_NULL;
@@ -289,7 +292,7 @@ bwla_status_t bwla_decode_forward(const bwla_layer_t* layer, const void* d_X, in
     hipStream_t st = (hipStream_t)stream;
     // one launch when the shape allows it
     bool done = false;
-    if (bwla_launch_decode_fused(layer, d_X, xdtype, M, d_q, d_scale, d_qsum, d_Y, d_acc, st, &done) != hipSuccess)
+    if (bwla_launch_decode_layer(layer, d_X, xdtype, M, d_q, d_scale, d_qsum, d_T, d_Y, d_acc, st, &done) != hipSuccess)
         return BWLA_ERR_HIP;
     if (done) return BWLA_OK;
     s = bwla_rotate_quant(layer, d_X, xdtype, M, d_q, d_scale, d_qsum, d_T, d_ws, ws_bytes, stream);

@@ -31,6 +31,18 @@ inline uint64_t bwla_factor_planes_bytes(int n) {
     return (uint64_t)3 * ((n + 15) & ~15) * ((n + 31) & ~31) * 2;
 }
 
+// factor planes of the single-launch decode kernel (0 when the pair is not one it takes): R2 in
+// three bf16 terms, (n2 / 16) strips x (n2 / 32) steps x 3 KiB; R1 in two fp16 terms, (n1 / 32)
+// steps x 2 x (n1 / 16) KiB
+inline uint64_t bwla_decode_planes_r2_bytes(int n1, int n2) {
+    const bool ok = (n1 == 32 || n1 == 64) && (n2 == 32 || n2 == 64);
+    return ok ? (uint64_t)(n2 / 16) * (n2 / 32) * 3 * 1024 : 0;
+}
+inline uint64_t bwla_decode_planes_bytes(int n1, int n2) {
+    const uint64_t r2 = bwla_decode_planes_r2_bytes(n1, n2);
+    return r2 ? r2 + (uint64_t)(n1 / 32) * 2 * (n1 / 16) * 1024 : 0;
+}
+
 // PSP projection (T = X U) launch plan: token tiles x column groups x S slices of K.  Up to 16
 // tokens the projection rides in the rotation launch (tiles of 16 tokens x rp columns); above,
 // a kernel of its own takes tiles of 64 tokens x up to 64 columns.
@@ -108,9 +120,10 @@ __device__ __forceinline__ bool bwla_partials_arrive(int* counter, int expected,
 #endif
 
 hipError_t bwla_launch_code_sums(const int8_t* dq, int64_t M, int64_t K, int32_t* dqsum, hipStream_t st);
-hipError_t bwla_launch_decode_fused(const bwla_layer_t* L, const void* dX, int xdtype, int64_t M, int8_t* dq,
-                                    float* dscale, int32_t* dqsum, float* dY, int32_t* dacc, hipStream_t st,
-                                    bool* done);
+// the whole layer in one launch for one bf16 token where the shape allows it (*done says whether)
+hipError_t bwla_launch_decode_layer(const bwla_layer_t* L, const void* dX, int xdtype, int64_t M, int8_t* dq,
+                                    float* dscale, int32_t* dqsum, float* dT, float* dY, int32_t* dacc,
+                                    hipStream_t st, bool* done);
 
 hipError_t bwla_launch_gemm_decode(const bwla_layer_t* L, const int8_t* dq, const float* dscale,
                                    const int32_t* dqsum, const float* dT, int64_t M, float* dY,

@@ -1,0 +1,641 @@
+// One launch for a whole decode layer with a single bf16 token (the memory-bound case of paper
+// Sec. 4.4): rotation (Sec. 3.1), symmetric INT6 codes (Sec. 4.1), binary GEMM (Eq. 3-4), PSP
+// branch (Sec. 3.2) and dequantization in every workgroup, with nothing crossing workgroups.
+//
+// A workgroup owns a few 16-channel tiles of the output and has eight wavefronts:
+//   wavefronts 0..3  rotate the token (one 16-column strip of the n1 x n2 reshape each) and
+//                    quantize it: the rotation of one token is about a megaflop fed from L2,
+//                    cheaper to repeat in every workgroup than to hand its result around;
+//   wavefronts 4..7  meanwhile compute T = x U for a quarter of K each on fp16 MFMA (x is scaled
+//                    by a power of two per quarter so that it fits fp16 exactly; U is stored in
+//                    B operand order and read straight from L2, 2 K r bytes per workgroup -- the
+//                    price of needing no hand-over between workgroups);
+//   all eight        then contract the codes with the workgroup's sign bits, which every wavefront
+//                    requested for its 512-column chunk before anything else, so that they stream
+//                    from HBM while the token is rotated; one wavefront finishes the outputs.
+// What the kernel is bound by at these sizes is instruction issue and latency, not bandwidth, so
+// the serial path is kept short: operands go global -> LDS asynchronously in the order in which
+// an MFMA lane reads them (no repacking, no bank conflicts), reductions run on DPP row operations,
+// codes are rounded by adding 1.5 * 2^23 (one fused multiply-add per code, round-half-even), and
+// the only workgroup barriers are: operands landed, codes ready, partial sums ready.
+#include <type_traits>
+
+#include "bwla_internal.h"
+
+namespace {
+
+typedef __attribute__((ext_vector_type(8))) __bf16 v8bf;
+typedef _Float16 v8h __attribute__((ext_vector_type(8)));
+
+constexpr int DL_THREADS = 512;      // eight wavefronts
+constexpr int DL_TPW = 3;            // channel tiles per workgroup and round
+constexpr int DL_MAXAT = 4;          // 16-row tiles along n1 (n1 <= 64)
+constexpr int DL_MAXK1 = 2;          // 32-deep steps along n2 (n2 <= 64)
+constexpr int DL_MAXJTU = 4;         // 16-column tiles of U (PSP rank <= 64)
+constexpr int DL_MAXJTV = 5;         // 16-column tiles of V (one more when the layer's mode adds a column)
+constexpr int DL_MAXROUNDS = 8;      // rounds of DL_TPW tiles per workgroup (more channels than that: two launches)
+constexpr int DL_SPIN_LIMIT = 1 << 22;
+
+// (the pointers every wavefront needs for its first requests are kernel parameters of their own:
+// the first 14 dwords of the kernel arguments are preloaded into SGPRs at wavefront launch, which
+// takes the argument fetch -- a memory round trip -- out of the path to the first request)
+struct DlArgs {
+    int8_t* q; float* scale; int32_t* qsum; float* T;      // written by workgroup 0
+    float* Y; int32_t* acc_out;
+    int N, r, ru, row_tiles, rounds, shift;
+};
+
+// ---- DPP row operations: reductions over the 64 lanes without LDS traffic
+template <int CTRL>
+__device__ __forceinline__ int dl_dpp(int v) {
+    return __builtin_amdgcn_update_dpp(0, v, CTRL, 0xf, 0xf, true);
+}
+// largest of non-negative floats over the wavefront, as a wave-uniform value
+__device__ __forceinline__ float dl_wave_max_nonneg(float v) {
+    int x = __float_as_int(v);                         // non-negative floats order like their bits
+    x = max(x, dl_dpp<0xB1>(x));                       // quad_perm [1,0,3,2]
+    x = max(x, dl_dpp<0x4E>(x));                       // quad_perm [2,3,0,1]
+    x = max(x, dl_dpp<0x141>(x));                      // row_half_mirror
+    x = max(x, dl_dpp<0x140>(x));                      // row_mirror: every lane of a row of 16 has the row's maximum
+    const int r0 = __builtin_amdgcn_readlane(x, 0), r1 = __builtin_amdgcn_readlane(x, 16);
+    const int r2 = __builtin_amdgcn_readlane(x, 32), r3 = __builtin_amdgcn_readlane(x, 48);
+    return __int_as_float(max(max(r0, r1), max(r2, r3)));
+}
+__device__ __forceinline__ int dl_wave_sum(int x) {
+    x += dl_dpp<0xB1>(x);
+    x += dl_dpp<0x4E>(x);
+    x += dl_dpp<0x141>(x);
+    x += dl_dpp<0x140>(x);
+    return __builtin_amdgcn_readlane(x, 0) + __builtin_amdgcn_readlane(x, 16) + __builtin_amdgcn_readlane(x, 32) +
+           __builtin_amdgcn_readlane(x, 48);
+}
+
+// byte-wise negation of four packed int8 (no value is -128 here)
+__device__ __forceinline__ int dl_neg_bytes(int x) {
+    const unsigned nx = ~(unsigned)x;
+    return (int)(((nx & 0x7f7f7f7fu) + 0x01010101u) ^ (nx & 0x80808080u));
+}
+
+__device__ __forceinline__ void dl_async_16(const void* src, char* dst_block) {
+    // lane l's 16 bytes land at dst_block + 16 l (the hardware's placement)
+    __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)src,
+                                     (__attribute__((address_space(3))) void*)dst_block, 16, 0, 0);
+}
+
+// swizzle of the token rows in LDS: row a keeps its 16-byte granule g at slot g ^ dl_swz(a), so that
+// the sixteen rows a lane group reads for one MFMA operand fall into sixteen different bank groups
+__device__ __forceinline__ int dl_swz(int a, int gpr) { return gpr == 8 ? (a >> 1) & 7 : (a >> 2) & 3; }
+
+// N1, N2: the Kronecker factors (compile-time: at these sizes the kernel is bound by the number of
+// instructions on its serial path, and run-time shapes cost address arithmetic and branches).
+// JTU, JTV: 16-column tiles of U and of V.
+template <int N1, int N2, int JTU, int JTV>
+__global__ __launch_bounds__(DL_THREADS) void decode_layer_kernel(const uint16_t* __restrict__ pX,
+                                                                  const uint16_t* __restrict__ pR1h,
+                                                                  const uint16_t* __restrict__ pR2d,
+                                                                  const uint4* __restrict__ pbits,
+                                                                  const __half* __restrict__ pUt,
+                                                                  const __half* __restrict__ pV,
+                                                                  const __half* __restrict__ palpha, DlArgs a) {
+    constexpr int K = N1 * N2, AT = N1 / 16, K1 = N2 / 32, CH2 = N1 / 32, STRIPS = N2 / 16, CHUNKS = K / 512;
+    constexpr int GPR = N2 / 8;                        // 16-byte granules per token row: 8 or 4
+    constexpr int S = K / 4, NKS = S / 32;             // T: columns and 32-deep steps per quarter of K
+    static_assert(STRIPS <= 4 && AT <= 4 && CHUNKS <= 8 && CHUNKS >= 2, "shape outside the kernel's wavefront roles");
+    extern __shared__ __align__(16) char lds[];
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int li = lane & 15, lg = lane >> 4;
+    const int grid = (int)gridDim.x, blk = (int)blockIdx.x;
+
+    // ---- LDS map
+    char* xt = lds;                                    // token rows, bf16, K * 2 bytes, granules swizzled
+    char* r1 = xt + 2 * K;                             // R1 terms [chunk][term][tile of c][lane * 16]: CH2 * 2 * AT KiB
+    char* codes = r1 + CH2 * 2 * AT * 1024;            // K code bytes, k order
+    char* xh = codes + K;                              // token as fp16, scaled per quarter of K: K * 2 bytes
+    float* red = reinterpret_cast<float*>(xh + 2 * K); // [0..3] strip maxima, [4..7] strip code sums, [8] arrival count
+    float* tpart = red + 16;                           // [4 quarters][16 * DL_MAXJTU] partial T
+    float* tfin = tpart + 4 * 16 * DL_MAXJTU;          // [8 wavefronts][16 * DL_MAXJTV] T as an epilogue wavefront reads it
+    int* part = reinterpret_cast<int*>(tfin + 8 * 16 * DL_MAXJTV);   // [rounds][DL_TPW][8 chunks][16 channels]
+    char* wb = reinterpret_cast<char*>(part + DL_MAXROUNDS * DL_TPW * 8 * 16);   // sign bits of the first round: [DL_TPW][CHUNKS] KiB
+
+    // arrival counts (rotation wavefronts: operands landed, maxima left, codes written; wavefronts
+    // 4..7: sign bits landed), zero before anybody bumps them: this barrier costs nothing, every
+    // wavefront would otherwise wait here for its first operands
+    int* cnt = reinterpret_cast<int*>(red) + 8;
+    if (tid < 4) cnt[tid] = 0;
+    bwla_lds_barrier();
+    // A subset of the wavefronts meets without holding up the others: each bumps the count when it
+    // is ready, and whoever needs them all waits until the count is full.  (The wait is bounded: a
+    // wavefront that gave up would compute with incomplete operands, but the kernel always ends.)
+    auto arrive = [&](int* c) {
+        if (lane == 0) __hip_atomic_fetch_add(c, 1, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_WORKGROUP);
+    };
+    auto await = [&](int* c, int n) {
+        for (int spin = 0; spin < DL_SPIN_LIMIT; ++spin) {
+            if (__hip_atomic_load(c, __ATOMIC_ACQUIRE, __HIP_MEMORY_SCOPE_WORKGROUP) >= n) break;
+            __builtin_amdgcn_s_sleep(1);
+        }
+    };
+    auto meet = [&](int* c, int n) { arrive(c); await(c, n); };
+
+    auto tile_id = [&](int rd, int t) -> int { return (rd * DL_TPW + t) * grid + blk; };
+    auto tile_of = [&](int rd, int t) -> int {
+        const int id = tile_id(rd, t);
+        return id < a.row_tiles ? id : a.row_tiles - 1;
+    };
+    // with a T part the first four wavefronts contract (two chunks each) while the others project;
+    // without, all eight contract
+    constexpr int GW = JTU > 0 ? 4 : 8, CPW = (CHUNKS + GW - 1) / GW;
+    const bool rotates = wave < STRIPS, projects = JTU > 0 && wave >= 4, contracts = wave < GW;
+
+    // Sign bits.  They are the bulk of the layer's bytes and are not needed before the codes exist,
+    // so they are requested only once the rotation's operands have landed.  With a T part, those of
+    // the first round are fetched by the T wavefronts, asynchronously into LDS: a request of a
+    // rotation wavefront would stall it behind the T wavefronts' stream in the memory pipeline.
+    // Without, and for later rounds (layers of more than DL_TPW tiles per workgroup), every
+    // contracting wavefront loads its own into registers, a round ahead.
+    constexpr bool BITS_VIA_LDS = JTU > 0;
+    v4i wq[DL_TPW][CPW];
+#pragma unroll
+    for (int t = 0; t < DL_TPW; ++t)
+#pragma unroll
+        for (int i = 0; i < CPW; ++i) wq[t][i] = v4i{0, 0, 0, 0};
+    auto request_bits = [&](int rd) {
+#pragma unroll
+        for (int t = 0; t < DL_TPW; ++t)
+#pragma unroll
+            for (int i = 0; i < CPW; ++i) {
+                const int c = wave + i * GW;
+                if (contracts && c < CHUNKS) {
+                    const uint4 x = pbits[(tile_of(rd, t) * CHUNKS + c) * 64 + lane];
+                    wq[t][i] = v4i{(int)x.x, (int)x.y, (int)x.z, (int)x.w};
+                }
+            }
+    };
+    // epilogue: wavefront e finishes round e; lane o < 16 * DL_TPW channel o & 15 of tile o >> 4
+    constexpr int VQ = 2 * JTV;                        // 16-byte pieces of a V row
+    v4i vrow[VQ > 0 ? VQ : 1];
+    uint16_t alpha_raw = 0;
+    auto fetch_first_bits = [&]() {                     // wavefronts 4..7
+#pragma unroll
+        for (int i = 0; i < (DL_TPW * CHUNKS + 3) / 4; ++i) {
+            const int idx = (wave - 4) + 4 * i;
+            if (idx < DL_TPW * CHUNKS) {
+                const int t = idx / CHUNKS, c = idx - t * CHUNKS;
+                dl_async_16(pbits + (tile_of(0, t) * CHUNKS + c) * 64 + lane, wb + idx * 1024);
+            }
+        }
+    };
+    auto epi_loads = [&](int rd) {
+        const int ti = lane >> 4;
+        if (ti < DL_TPW) {
+            int n = tile_of(rd, ti) * 16 + (lane & 15);
+            if (n >= a.N) n = a.N - 1;
+            alpha_raw = reinterpret_cast<const uint16_t*>(palpha)[n];
+#pragma unroll
+            for (int i = 0; i < VQ; ++i) vrow[i] = *reinterpret_cast<const v4i*>(pV + n * (16 * JTV) + 8 * i);
+        }
+    };
+    // ================================================================ requests, critical ones first
+    v4i bfr[K1][3];                                    // R2 terms of my strip (rotation wavefronts)
+    v4i xq[2] = {v4i{0, 0, 0, 0}, v4i{0, 0, 0, 0}};   // my quarter of the token (T wavefronts)
+    constexpr int TD = JTU <= 2 ? 16 : 8;              // T: steps in flight
+    v4i uring[TD][JTU > 0 ? JTU : 1];
+    // T: workgroups walk over U from different starting steps: the workgroups of one L2 then ask
+    // for all of U at once instead of all waiting for the same lines, one round trip after the other
+    const int ks_first = (blk >> 3) & (NKS - 1);
+    auto u_load = [&](int i, int jt) -> v4i {
+        const int ks = (ks_first + (i < NKS ? i : NKS - 1)) & (NKS - 1);
+        return *reinterpret_cast<const v4i*>(pUt + ((jt * (K / 32) + (wave - 4) * NKS + ks) * 64 + lane) * 8);
+    };
+    if (rotates) {
+        // the token, asynchronously into LDS: 1 KiB per instruction
+#pragma unroll
+        for (int i = 0; i < (2 * K / 1024 + STRIPS - 1) / STRIPS; ++i) {
+            const int blkx = wave + i * STRIPS;
+            if (blkx < 2 * K / 1024) {
+                const int row = blkx * (64 / GPR) + lane / GPR;
+                const int slot = lane & (GPR - 1);
+                dl_async_16(pX + row * N2 + ((slot ^ dl_swz(row, GPR)) << 3), xt + blkx * 1024);
+            }
+        }
+        // R2 terms of my strip and all R1 terms: stored block by block as the MFMAs read them, one
+        // contiguous KiB per wavefront-wide request
+#pragma unroll
+        for (int kb = 0; kb < K1; ++kb)
+#pragma unroll
+            for (int p = 0; p < 3; ++p)
+                bfr[kb][p] = *reinterpret_cast<const v4i*>(pR2d + (((wave * K1 + kb) * 3 + p) * 64 + lane) * 8);
+        constexpr int NB = CH2 * 2 * AT;
+#pragma unroll
+        for (int i = 0; i < (NB + STRIPS - 1) / STRIPS; ++i) {
+            const int b1 = wave + i * STRIPS;
+            if (b1 < NB) dl_async_16(pR1h + (b1 * 64 + lane) * 8, r1 + b1 * 1024);
+        }
+        if (wave < a.rounds) epi_loads(wave);
+    } else if (projects) {
+#pragma unroll
+        for (int i = 0; i < 2; ++i) {
+            const int piece = lane + 64 * i;
+            if (piece * 8 < S) xq[i] = *reinterpret_cast<const v4i*>(pX + (wave - 4) * S + piece * 8);
+        }
+        if (wave < a.rounds) epi_loads(wave);
+        fetch_first_bits();
+        __builtin_amdgcn_sched_barrier(0);             // (the counted wait further down relies on this order)
+#pragma unroll
+        for (int d = 0; d < TD; ++d)
+#pragma unroll
+            for (int jt = 0; jt < JTU; ++jt) uring[d][jt] = u_load(d, jt);
+    }
+
+    // ================================================================ T = x U, first part: the token as fp16
+    float t_unscale = 1.0f;
+    if (projects) {
+        float m = 0.0f;
+#pragma unroll
+        for (int i = 0; i < 2; ++i)
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                const uint32_t w = (uint32_t)xq[i][e];
+                m = fmaxf(m, fmaxf(fabsf(__uint_as_float(w << 16)), fabsf(__uint_as_float(w & 0xffff0000u))));
+            }
+        m = dl_wave_max_nonneg(m);
+        // power of two that puts the quarter's largest magnitude into [2^13, 2^14): bf16 values are
+        // then fp16 values exactly, unless they are 2^28 times smaller than that largest one
+        int E = (__float_as_int(m) >> 23) & 0xff;
+        E = E < 32 ? 32 : (E > 222 ? 222 : E);
+        const float sc = __int_as_float((267 - E) << 23);
+        t_unscale = __int_as_float((E - 13) << 23);
+#pragma unroll
+        for (int i = 0; i < 2; ++i) {
+            const int piece = lane + 64 * i;
+            if (piece * 8 < S) {
+                v4i o;
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    const uint32_t w = (uint32_t)xq[i][e];
+                    const auto h2 = __builtin_amdgcn_cvt_pkrtz(__uint_as_float(w << 16) * sc,
+                                                               __uint_as_float(w & 0xffff0000u) * sc);
+                    o[e] = __builtin_bit_cast(int, h2);
+                }
+                *reinterpret_cast<v4i*>(xh + ((wave - 4) * S + piece * 8) * 2) = o;
+            }
+        }
+        // the sign bits have landed once only the requests for U, which are younger, are outstanding
+        __builtin_amdgcn_sched_barrier(0);
+        __builtin_amdgcn_s_waitcnt(0x0F70 | ((TD * JTU) & 15) | (((TD * JTU) >> 4) << 14));   // vmcnt(TD * JTU)
+        arrive(cnt + 3);
+    } else if (!rotates) {
+        // a wavefront that only contracts waits until the rotation's operands are there
+        await(cnt, STRIPS);
+        if (!BITS_VIA_LDS) request_bits(0);
+        if (wave < a.rounds) epi_loads(wave);
+    }
+
+    if (rotates) {
+        // ---- operands landed: every rotation wavefront waits for its own asynchronous copies, then
+        // for the other rotation wavefronts (the T wavefronts go on by themselves)
+        __builtin_amdgcn_s_waitcnt(0);
+        meet(cnt, STRIPS);
+        if (!BITS_VIA_LDS) request_bits(0);
+        // ============================================================ rotation, stage 1: Z = V R2
+        v4f z[AT];
+#pragma unroll
+        for (int ta = 0; ta < AT; ++ta) z[ta] = v4f{0.f, 0.f, 0.f, 0.f};
+        v8bf av[K1][AT];
+#pragma unroll
+        for (int kb = 0; kb < K1; ++kb)
+#pragma unroll
+            for (int ta = 0; ta < AT; ++ta) {
+                const int row = ta * 16 + li;
+                av[kb][ta] = __builtin_bit_cast(v8bf, *reinterpret_cast<const v4i*>(
+                                 xt + row * (N2 * 2) + (((4 * kb + lg) ^ dl_swz(row, GPR)) << 4)));
+            }
+#pragma unroll
+        for (int kb = 0; kb < K1; ++kb)
+#pragma unroll
+            for (int p = 2; p >= 0; --p) {             // small terms first
+                const v8bf b = __builtin_bit_cast(v8bf, bfr[kb][p]);
+#pragma unroll
+                for (int ta = 0; ta < AT; ++ta) z[ta] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(av[kb][ta], b, z[ta], 0, 0, 0);
+            }
+        // ============================================================ stage 2: Yt = Zt R1
+        // The accumulator tiles of stage 1 are A operands as they stand: lane (li, lg) holds
+        // Z[a = 16 ta + 4 lg + v][d = li]; two stacked tiles give the eight contraction positions
+        // of a lane group in the order in which the R1 terms are stored.  Both operands as two fp16
+        // terms (22 bits): Z of this strip scaled by a power of two so that its largest magnitude is
+        // in [2^13, 2^14), R1 stored as 256 R1; of the four products the smallest (lo x lo, 2^-22 of
+        // the result) is left out.  The scale is undone in the quantization step.
+        float zm = 0.0f;
+#pragma unroll
+        for (int ta = 0; ta < AT; ++ta)
+#pragma unroll
+            for (int v = 0; v < 4; ++v) zm = fmaxf(zm, fabsf(z[ta][v]));
+        zm = dl_wave_max_nonneg(zm);
+        int Ez = (__float_as_int(zm) >> 23) & 0xff;
+        Ez = Ez < 32 ? 32 : (Ez > 222 ? 222 : Ez);
+        const float zsc = __int_as_float((267 - Ez) << 23);
+        const float yun = __int_as_float((Ez - 13 - 8) << 23);       // back from the scaled Z and the 256 R1
+        v4f y[AT];
+#pragma unroll
+        for (int tc = 0; tc < AT; ++tc) y[tc] = v4f{0.f, 0.f, 0.f, 0.f};
+        v8h ah[CH2], al[CH2];
+#pragma unroll
+        for (int ch = 0; ch < CH2; ++ch)
+#pragma unroll
+            for (int e = 0; e < 8; ++e) {
+                const float f = z[2 * ch + (e >> 2)][e & 3] * zsc;
+                const _Float16 h = (_Float16)f;
+                ah[ch][e] = h;
+                al[ch][e] = (_Float16)(f - (float)h);
+            }
+#pragma unroll
+        for (int ch = 0; ch < CH2; ++ch) {
+            const char* cb = r1 + ch * 2 * AT * 1024 + lane * 16;
+            v8h bh[AT], bl[AT];
+#pragma unroll
+            for (int tc = 0; tc < AT; ++tc) {
+                bh[tc] = __builtin_bit_cast(v8h, *reinterpret_cast<const v4i*>(cb + (0 * AT + tc) * 1024));
+                bl[tc] = __builtin_bit_cast(v8h, *reinterpret_cast<const v4i*>(cb + (1 * AT + tc) * 1024));
+            }
+            // small products first
+#pragma unroll
+            for (int tc = 0; tc < AT; ++tc) y[tc] = __builtin_amdgcn_mfma_f32_16x16x32_f16(al[ch], bh[tc], y[tc], 0, 0, 0);
+#pragma unroll
+            for (int tc = 0; tc < AT; ++tc) y[tc] = __builtin_amdgcn_mfma_f32_16x16x32_f16(ah[ch], bl[tc], y[tc], 0, 0, 0);
+#pragma unroll
+            for (int tc = 0; tc < AT; ++tc) y[tc] = __builtin_amdgcn_mfma_f32_16x16x32_f16(ah[ch], bh[tc], y[tc], 0, 0, 0);
+        }
+        // ============================================================ largest magnitude of the token
+        float mx = 0.0f;
+#pragma unroll
+        for (int tc = 0; tc < AT; ++tc)
+#pragma unroll
+            for (int v = 0; v < 4; ++v) mx = fmaxf(mx, fabsf(y[tc][v]));
+        mx = dl_wave_max_nonneg(mx) * yun;
+        // the rotation wavefronts exchange their maxima among themselves
+        if (lane == 0) red[wave] = mx;
+        meet(cnt + 1, STRIPS);
+        float amax = 0.0f;
+#pragma unroll
+        for (int w = 0; w < STRIPS; ++w) amax = fmaxf(amax, red[w]);
+        const float inv = amax > 0.0f ? 31.0f * __builtin_amdgcn_rcpf(amax) * yun : 0.0f;   // (on this strip's scaled values)
+
+        // ============================================================ codes
+        // lane holds Yt[d = 16 strip + 4 lg + v][c = 16 tc + li]: four consecutive k = c n2 + d.
+        // x * inv + 1.5 * 2^23 rounds to an integer (ties to even) whose low byte is the code.
+        int lsum = 0;
+#pragma unroll
+        for (int tc = 0; tc < AT; ++tc) {
+            uint32_t cb[4];
+#pragma unroll
+            for (int v = 0; v < 4; ++v) cb[v] = __float_as_uint(__builtin_fmaf(y[tc][v], inv, 12582912.0f));
+            const uint32_t lo = __builtin_amdgcn_perm(cb[1], cb[0], 0x0c0c0400u);      // bytes: cb0.b0, cb1.b0, 0, 0
+            const uint32_t hi = __builtin_amdgcn_perm(cb[3], cb[2], 0x04000c0cu);      // bytes: 0, 0, cb2.b0, cb3.b0
+            const uint32_t word = lo | hi;
+            *reinterpret_cast<uint32_t*>(codes + (16 * tc + li) * N2 + 16 * wave + 4 * lg) = word;
+            lsum = __builtin_amdgcn_sdot4((int)word, 0x01010101, lsum, false);
+        }
+        lsum = dl_wave_sum(lsum);
+        if (lane == 0) reinterpret_cast<int*>(red)[4 + wave] = lsum;
+        arrive(cnt + 2);                               // my codes and my code sum are in LDS
+    } else if (projects) {
+        // ============================================================ T = x U, my quarter of K
+        v4f tacc[JTU > 0 ? JTU : 1];
+#pragma unroll
+        for (int jt = 0; jt < (JTU > 0 ? JTU : 1); ++jt) tacc[jt] = v4f{0.f, 0.f, 0.f, 0.f};
+        const char* xa = xh + ((wave - 4) * S + 8 * lg) * 2;
+#pragma unroll
+        for (int i0 = 0; i0 < NKS; i0 += TD) {
+#pragma unroll
+            for (int d = 0; d < TD; ++d) {
+                const int ks = (ks_first + i0 + d) & (NKS - 1);
+                const v8h av = __builtin_bit_cast(v8h, *reinterpret_cast<const v4i*>(xa + ks * 64));
+#pragma unroll
+                for (int jt = 0; jt < JTU; ++jt) {
+                    tacc[jt] = __builtin_amdgcn_mfma_f32_16x16x32_f16(av, __builtin_bit_cast(v8h, uring[d][jt]), tacc[jt], 0, 0, 0);
+                    if (i0 + d + TD < NKS) uring[d][jt] = u_load(i0 + d + TD, jt);
+                }
+            }
+        }
+        // every row of the A operand was the token: row 0 of the result (lanes 0..15) is T's slice
+        if (lane < 16) {
+#pragma unroll
+            for (int jt = 0; jt < JTU; ++jt) tpart[(wave - 4) * 16 * DL_MAXJTU + 16 * jt + lane] = tacc[jt][0] * t_unscale;
+        }
+    }
+
+    // ================================================================ binary GEMM on the workgroup's tiles
+    if (contracts) {
+        await(cnt + 2, STRIPS);                        // the token's codes are complete
+        // operand codes of my chunks: for digit class j the 16 codes at columns 512 c + 128 lg + 16 j
+        // (every token column of the MFMA reads the one token; only column 0 is used)
+        v4i b[CPW][8];
+#pragma unroll
+        for (int i = 0; i < CPW; ++i) {
+            const int c = wave + i * GW;
+#pragma unroll
+            for (int j = 0; j < 8; ++j) {
+                b[i][j] = v4i{0, 0, 0, 0};
+                if (c < CHUNKS) b[i][j] = *reinterpret_cast<const v4i*>(codes + 512 * c + 128 * lg + 16 * j);
+            }
+            b[i][7] = v4i{dl_neg_bytes(b[i][7].x), dl_neg_bytes(b[i][7].y), dl_neg_bytes(b[i][7].z), dl_neg_bytes(b[i][7].w)};
+        }
+        if (BITS_VIA_LDS) {
+            await(cnt + 3, 4);                         // the first round's sign bits are in LDS
+#pragma unroll
+            for (int t = 0; t < DL_TPW; ++t)
+#pragma unroll
+                for (int i = 0; i < CPW; ++i) {
+                    const int c = wave + i * GW;
+                    if (c < CHUNKS) wq[t][i] = *reinterpret_cast<const v4i*>(wb + (t * CHUNKS + c) * 1024 + lane * 16);
+                }
+        }
+        for (int rd = 0; rd < a.rounds; ++rd) {
+            int* prt = part + rd * DL_TPW * 8 * 16;
+            // the round's tiles (all DL_TPW of them, except in the last round) side by side: per tile
+            // and chunk two independent chains through the accumulator (odd and even digit classes),
+            // e = S6+S4+S2+S0, o = 2 (S7+S5+S3+S1), exact arithmetic shifts in between
+            auto contract = [&](auto nt_) {
+                constexpr int NT = decltype(nt_)::value;
+                v4i acc_e[NT][CPW], acc_o[NT][CPW];
+#pragma unroll
+                for (int t = 0; t < NT; ++t)
+#pragma unroll
+                    for (int i = 0; i < CPW; ++i) acc_e[t][i] = acc_o[t][i] = v4i{0, 0, 0, 0};
+#pragma unroll
+                for (int jj = 3; jj >= 0; --jj) {
+                    const int mo = 0x01010101 << (2 * jj + 1), me = 0x01010101 << (2 * jj);
+#pragma unroll
+                    for (int t = 0; t < NT; ++t)
+#pragma unroll
+                        for (int i = 0; i < CPW; ++i) {
+                            const v4i w = wq[t][i];
+                            const v4i xo = v4i{w.x & mo, w.y & mo, w.z & mo, w.w & mo};
+                            acc_o[t][i] = __builtin_amdgcn_mfma_i32_16x16x64_i8(xo, b[i][2 * jj + 1], acc_o[t][i], 0, 0, 0);
+                            const v4i xe = v4i{w.x & me, w.y & me, w.z & me, w.w & me};
+                            acc_e[t][i] = __builtin_amdgcn_mfma_i32_16x16x64_i8(xe, b[i][2 * jj], acc_e[t][i], 0, 0, 0);
+                        }
+                    if (jj > 0) {
+#pragma unroll
+                        for (int t = 0; t < NT; ++t)
+#pragma unroll
+                            for (int i = 0; i < CPW; ++i) { acc_o[t][i] = acc_o[t][i] >> 2; acc_e[t][i] = acc_e[t][i] >> 2; }
+                    }
+                }
+                // lane (li = token column, lg) holds channels 4 lg .. 4 lg + 3: column 0 is the token
+                if (li == 0) {
+#pragma unroll
+                    for (int t = 0; t < NT; ++t) {
+                        v4i sum = acc_e[t][0] + (acc_o[t][0] >> 1);
+#pragma unroll
+                        for (int i = 1; i < CPW; ++i) sum += acc_e[t][i] + (acc_o[t][i] >> 1);
+                        *reinterpret_cast<v4i*>(prt + (t * 8 + wave) * 16 + 4 * lg) = sum;
+                    }
+                }
+            };
+            static_assert(DL_TPW == 3, "the dispatch below lists the tile counts");
+            if (tile_id(rd, 2) < a.row_tiles) contract(std::integral_constant<int, 3>{});
+            else if (tile_id(rd, 1) < a.row_tiles) contract(std::integral_constant<int, 2>{});
+            else if (tile_id(rd, 0) < a.row_tiles) contract(std::integral_constant<int, 1>{});
+            // next round's sign bits into the same registers
+            if (rd + 1 < a.rounds) request_bits(rd + 1);
+        }
+    }
+
+    // ---- partial sums of all rounds, code sums and partial T are in LDS
+    bwla_lds_barrier();
+
+    // token-wide values
+    float amax = 0.0f;
+    int qs = 0;
+#pragma unroll
+    for (int w = 0; w < STRIPS; ++w) {
+        amax = fmaxf(amax, red[w]);
+        qs += reinterpret_cast<const int*>(red)[4 + w];
+    }
+    // workgroup 0 also writes the token's codes out
+    if (blk == 0) {
+        for (int i = tid; i < (K >> 4); i += DL_THREADS)
+            reinterpret_cast<uint4*>(a.q)[i] = reinterpret_cast<const uint4*>(codes)[i];
+    }
+    // ================================================================ epilogue: wavefront e finishes round e
+    if (wave < a.rounds) {
+        const int rd = wave;
+        const float st = amax / 31.0f;
+        float* tf = tfin + wave * 16 * DL_MAXJTV;
+        // T as the epilogue reads it: the PSP columns, then the column a row shift adds
+        if (JTV > 0) {
+            for (int j = lane; j < 16 * JTV; j += 64) {
+                float tv = 0.0f;
+                if (j < a.ru) {
+#pragma unroll
+                    for (int s4 = 0; s4 < 4; ++s4) tv += tpart[s4 * 16 * DL_MAXJTU + j];
+                } else if (a.shift && j == a.ru) {
+                    tv = st * (float)qs;
+                }
+                tf[j] = tv;
+                if (blk == 0 && rd == 0 && j < a.r) a.T[j] = tv;
+            }
+        }
+        // ... and workgroup 0 the token's scale and code sum
+        if (blk == 0 && rd == 0 && lane == 0) { a.scale[0] = st; a.qsum[0] = qs; }
+        const int* prt = part + rd * DL_TPW * 8 * 16;
+        const int ti = lane >> 4, row = lane & 15;
+        if (ti < DL_TPW) {
+            const int tile = tile_id(rd, ti);
+            const int n = tile * 16 + row;
+            int tot = 0;
+#pragma unroll
+            for (int w = 0; w < GW; ++w) tot += prt[(ti * 8 + w) * 16 + row];
+            const int ai = 2 * tot - qs;
+            float low = 0.0f;
+#pragma unroll
+            for (int i = 0; i < VQ; ++i) {
+                const v4f tq0 = *reinterpret_cast<const v4f*>(tf + 8 * i);
+                const v4f tq1 = *reinterpret_cast<const v4f*>(tf + 8 * i + 4);
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    const int vw = vrow[i][e];          // (a copy: a bit cast applied to a vector element reads element 0)
+                    const __half2 h = __builtin_bit_cast(__half2, vw);
+                    const float t0 = e < 2 ? tq0[2 * e] : tq1[2 * e - 4], t1 = e < 2 ? tq0[2 * e + 1] : tq1[2 * e - 3];
+                    low = __builtin_fmaf(t0, __low2float(h), low);
+                    low = __builtin_fmaf(t1, __high2float(h), low);
+                }
+            }
+            const float yv = st * __half2float(__ushort_as_half(alpha_raw)) * (float)ai + low;
+            if (tile < a.row_tiles && n < a.N) {
+                a.Y[n] = yv;
+                if (a.acc_out) a.acc_out[n] = ai;
+            }
+        }
+    }
+}
+
+size_t dl_lds_bytes(int K, int n1, int n2, bool with_t) {
+    const int at = n1 >> 4, ch2 = n1 >> 5;
+    return (size_t)2 * K + (size_t)ch2 * 2 * at * 1024 + K + 2 * K +
+           (16 + 4 * 16 * DL_MAXJTU + 8 * 16 * DL_MAXJTV) * sizeof(float) + DL_MAXROUNDS * DL_TPW * 8 * 16 * sizeof(int) +
+           (with_t ? (size_t)DL_TPW * (K / 512) * 1024 : 0);
+}
+
+}  // namespace
+
+// Single-launch decode layer.  *done = false (and nothing launched) when the shape is outside what
+// the kernel takes: one bf16 token; Kronecker factors of 32 or 64 (K = 1024 .. 4096, which covers
+// the 4096-wide models' attention and up/gate projections); PSP rank up to 64; symmetric codes,
+// with or without the row shift.
+hipError_t bwla_launch_decode_layer(const bwla_layer_t* L, const void* dX, int xdtype, int64_t M, int8_t* dq,
+                                    float* dscale, int32_t* dqsum, float* dT, float* dY, int32_t* dacc,
+                                    hipStream_t st, bool* done) {
+    *done = false;
+    const int n1 = L->n1, n2 = L->n2;
+    if (M != 1 || xdtype != BWLA_X_BF16) return hipSuccess;
+    if ((n1 != 32 && n1 != 64) || (n2 != 32 && n2 != 64)) return hipSuccess;
+    if ((L->mode & BWLA_MODE_ASYM_ACT) != 0) return hipSuccess;
+    const int ru = bwla_rank_u(L), r = L->r;
+    const int jtu = (ru + 15) >> 4, jtv = (r + 15) >> 4;
+    if (jtu > DL_MAXJTU || jtv > DL_MAXJTV) return hipSuccess;
+    const int K = (int)L->K, chunks = (int)bwla_chunks(L->K), row_tiles = (int)bwla_row_tiles(L->N);
+    if (chunks > 8 || chunks < 2 || (K & 511) != 0) return hipSuccess;
+    const char* blob = (const char*)L->d_blob;
+    const int cus = bwla_device_cus();
+    const int grid = row_tiles < cus ? row_tiles : cus;
+    DlArgs a;
+    const uint16_t* pX = (const uint16_t*)dX;
+    if (L->off_Rd == 0) return hipSuccess;
+    const uint16_t* pR2d = (const uint16_t*)(blob + L->off_Rd);
+    const uint16_t* pR1h = (const uint16_t*)(blob + L->off_Rd + bwla_decode_planes_r2_bytes(n1, n2));
+    const uint4* pbits = (const uint4*)(blob + L->off_bits);
+    const __half* palpha = (const __half*)(blob + L->off_alpha);
+    const __half* pV = (const __half*)(blob + L->off_V);
+    const __half* pUt = (const __half*)(blob + L->off_U);
+    a.q = dq; a.scale = dscale; a.qsum = dqsum; a.T = dT; a.Y = dY; a.acc_out = dacc;
+    a.N = (int)L->N; a.r = r; a.ru = ru; a.row_tiles = row_tiles;
+    a.rounds = (row_tiles + DL_TPW * grid - 1) / (DL_TPW * grid);
+    if (a.rounds > DL_MAXROUNDS) return hipSuccess;
+    a.shift = (L->mode & BWLA_MODE_ROW_SHIFT) ? 1 : 0;
+    const size_t lds = dl_lds_bytes(K, n1, n2, jtu > 0);
+    auto launch = [&](auto kern) -> hipError_t {
+        hipError_t e = bwla_ensure_lds((const void*)kern, lds);
+        if (e != hipSuccess) return e;
+        kern<<<dim3((unsigned)grid), dim3(DL_THREADS), lds, st>>>(pX, pR1h, pR2d, pbits, pUt, pV, palpha, a);
+        return hipGetLastError();
+    };
+    hipError_t e = hipSuccess;
+    bool found = false;
+#define DL_CASE(A_, B_, U_, V_) \
+    if (n1 == A_ && n2 == B_ && jtu == U_ && jtv == V_) { found = true; e = launch(decode_layer_kernel<A_, B_, U_, V_>); }
+#define DL_RANKS(A_, B_) \
+    DL_CASE(A_, B_, 0, 0) DL_CASE(A_, B_, 0, 1) DL_CASE(A_, B_, 1, 1) DL_CASE(A_, B_, 1, 2) DL_CASE(A_, B_, 2, 2) \
+    DL_CASE(A_, B_, 2, 3) DL_CASE(A_, B_, 3, 3) DL_CASE(A_, B_, 3, 4) DL_CASE(A_, B_, 4, 4) DL_CASE(A_, B_, 4, 5)
+    DL_RANKS(64, 64)
+    // the smaller factor pairs with the ranks their widths would carry
+    DL_CASE(32, 64, 0, 0) DL_CASE(32, 64, 1, 1) DL_CASE(32, 64, 2, 2) DL_CASE(64, 32, 0, 0) DL_CASE(64, 32, 1, 1)
+    DL_CASE(64, 32, 2, 2) DL_CASE(32, 32, 0, 0) DL_CASE(32, 32, 1, 1)
+#undef DL_RANKS
+#undef DL_CASE
+    if (!found) return hipSuccess;                         // no kernel built for this pair: the caller's two launches
+    if (e == hipSuccess) *done = true;
+    return e;
+}

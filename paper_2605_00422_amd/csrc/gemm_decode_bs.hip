@@ -37,9 +37,9 @@ __global__ __launch_bounds__(CPW == BS_CPW ? BS_MAX_THREADS : 64 * (BS_MAXKS_LON
     const int units = (a.row_tiles + NT - 1) / NT;
     const int n_iter = (units - first + stride - 1) / stride;            // >= 1: grid <= units
     const int PV = (NT * (((a.r + 15) >> 4) * 16) + 31) >> 5;
-    if (wave == a.KS) epilogue_wave<DEPTH, NT, JTT, FAST, false, MULTI>(a, smem, first, stride, n_iter, wave, lane);
-    else if (wave <= PV) compute_wave<CPW, DEPTH, NT, true, false, MULTI>(a, smem, first, stride, n_iter, wave, lane);
-    else compute_wave<CPW, DEPTH, NT, false, false, MULTI>(a, smem, first, stride, n_iter, wave, lane);
+    if (wave == a.KS) epilogue_wave<DEPTH, NT, JTT, FAST, MULTI>(a, smem, first, stride, n_iter, wave, lane);
+    else if (wave <= PV) compute_wave<CPW, DEPTH, NT, true, MULTI>(a, smem, first, stride, n_iter, wave, lane);
+    else compute_wave<CPW, DEPTH, NT, false, MULTI>(a, smem, first, stride, n_iter, wave, lane);
 }
 
 

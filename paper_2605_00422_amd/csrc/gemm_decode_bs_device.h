@@ -40,21 +40,6 @@ __device__ __forceinline__ uint32_t bs_swiglu_bf16(float g, float u) {
     return (uint32_t)__builtin_bit_cast(uint16_t, (__bf16)h);
 }
 
-// Fused single-launch decode (one token, r = 0): the workgroup has rotated and quantized the token
-// itself, so the codes, the scale and the code sum come from its own LDS.
-struct FusedLocal {
-    const char* codes;       // K code bytes of the token, in k order
-    const float* amax;       // per-strip largest rotated value; 32 words further on: the smallest
-    const int* sums;         // per-strip sums of the codes
-    int strips;
-};
-// the token's code row, LDS -> LDS, into the swizzled row 0 of the code rows (row 0: identity)
-__device__ __forceinline__ void bs_local_stage_codes(const BsArgs& a, char* qt, const FusedLocal& fl, int wave,
-                                                     int lane) {
-    const int kgran = a.K >> 4;
-    for (int g = wave * 64 + lane; g < kgran; g += (a.KS + 1) * 64)
-        *reinterpret_cast<v4i*>(qt + g * 16) = *reinterpret_cast<const v4i*>(fl.codes + g * 16);
-}
 // zero what no copy fills in the code rows (from the last, possibly partial, chunk to the row end;
 // the last 512 bytes are the operand of a chunk past K; only positions whose granule lies past K:
 // the others belong to the copies, which may land at any time), and the partial-tile slots that
@@ -107,10 +92,9 @@ __device__ __forceinline__ void stage_codes(const BsArgs& a, char* qt, int wave,
 }
 
 // ------------------------------------------------------------------ compute wave
-template <int CPW, int DEPTH, int NT, bool SIDE, bool FUSED = false, bool MULTI = false>
+template <int CPW, int DEPTH, int NT, bool SIDE, bool MULTI = false>
 __device__ __forceinline__ void compute_wave(const BsArgs& a, char* smem, int first, int stride, int n_iter,
-                                             int wave, int lane, const FusedLocal& fl = FusedLocal{},
-                                             int rotation_barriers = 0) {
+                                             int wave, int lane) {
     const int li = lane & 15, lg = lane >> 4;
     const int KS = a.KS, chunks = a.chunks;
     const int JT = (a.r + 15) >> 4, rp = JT * 16;
@@ -191,16 +175,7 @@ __device__ __forceinline__ void compute_wave(const BsArgs& a, char* smem, int fi
     // stage the code rows into LDS first; granules are XOR-swizzled by row against bank conflicts.
     const int Kp = chunks * BWLA_CHUNK_COLS;
     const int brow = li < a.M ? li : a.M - 1;             // padded token columns repeat the last row; never stored
-    if constexpr (FUSED) {
-        // the weights are on their way; meanwhile the rotation wavefronts of this workgroup work
-        // through their barriers, after the last of which the token's codes are in LDS
-        if (wave == 0) bs_zero_fill<NT>(a, qt, red, lane);
-#pragma unroll
-        for (int i = 0; i < rotation_barriers; ++i) bwla_lds_barrier();
-        bs_local_stage_codes(a, qt, fl, wave, lane);
-        __builtin_amdgcn_s_waitcnt(0);                     // this wave's copies (and first units) landed
-        bwla_lds_barrier();
-    } else if (!a.direct) {
+    if (!a.direct) {
         stage_codes(a, qt, wave, lane);
         __builtin_amdgcn_s_waitcnt(0);
         bwla_lds_barrier();
@@ -209,7 +184,7 @@ __device__ __forceinline__ void compute_wave(const BsArgs& a, char* smem, int fi
     // operand codes of pass hp: chunks hp * KS * CPW + wave + i * KS
     auto load_b = [&](int hp) {
         const int cbase = hp * KS * CPW + wave;
-        if (FUSED || !a.direct) {
+        if (!a.direct) {
 #pragma unroll
             for (int i = 0; i < CPW; ++i) {
                 const int c = cbase + i * KS < chunks ? cbase + i * KS : chunks;   // chunk `chunks` is a zero patch
@@ -306,9 +281,9 @@ __device__ __forceinline__ void compute_wave(const BsArgs& a, char* smem, int fi
 }
 
 // ------------------------------------------------------------------ epilogue wave
-template <int DEPTH, int NT, int JTT, bool FAST, bool FUSED = false, bool MULTI = false>
+template <int DEPTH, int NT, int JTT, bool FAST, bool MULTI = false>
 __device__ __forceinline__ void epilogue_wave(const BsArgs& a, char* smem, int first, int stride, int n_iter,
-                                              int wave, int lane, const FusedLocal& fl = FusedLocal{}) {
+                                              int wave, int lane) {
     const int li = lane & 15, lg = lane >> 4;
     const int KS = a.KS, N = a.N;
     const int JT = (a.r + 15) >> 4, rp = JT * 16;
@@ -323,43 +298,26 @@ __device__ __forceinline__ void epilogue_wave(const BsArgs& a, char* smem, int f
     // this lane's slice of T (token li, rank entries 16*uu + 4*lg + e), zero past M and r
     float tv[JTT > 0 ? JTT : 1][4];
     float tmax = 0.0f;
-    if constexpr (FUSED) {
-        // this wavefront comes from the rotation: the codes are in LDS, and so are the per-strip
-        // maxima and sums (same expressions as where the rotation writes scale and sum out)
-        float amax = fmaxf(fl.amax[0], -fl.amax[32]);
-        int tot = fl.sums[0];
-        for (int w = 1; w < fl.strips; ++w) {
-            amax = fmaxf(amax, fmaxf(fl.amax[w], -fl.amax[32 + w]));
-            tot += fl.sums[w];
+    if (tok_ok) {
+        st = a.scale[t];
+        qs = a.qsum[t];
+    }
+#pragma unroll
+    for (int uu = 0; uu < JTT; ++uu)
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            const int j = uu * 16 + 4 * lg + e;
+            tv[uu][e] = 0.0f;
+            if (tok_ok && j < a.r) tv[uu][e] = a.T[(int64_t)t * a.r + j];
+            tmax = fmaxf(tmax, fabsf(tv[uu][e]));
         }
-        st = tok_ok ? amax / 31.0f : 0.0f;
-        qs = tok_ok ? tot : 0;
-        bs_local_stage_codes(a, qt, fl, wave, lane);
-        __builtin_amdgcn_s_waitcnt(0);
-        bwla_lds_barrier();
-        static_assert(!FUSED || JTT == 0, "the fused decode kernel has no low-rank part");
+    if (a.direct) {
+        bs_zero_fill<NT>(a, qt, red, lane, false);         // (the compute waves fetch their codes themselves)
     } else {
-        if (tok_ok) {
-            st = a.scale[t];
-            qs = a.qsum[t];
-        }
-#pragma unroll
-        for (int uu = 0; uu < JTT; ++uu)
-#pragma unroll
-            for (int e = 0; e < 4; ++e) {
-                const int j = uu * 16 + 4 * lg + e;
-                tv[uu][e] = 0.0f;
-                if (tok_ok && j < a.r) tv[uu][e] = a.T[(int64_t)t * a.r + j];
-                tmax = fmaxf(tmax, fabsf(tv[uu][e]));
-            }
-        if (a.direct) {
-            bs_zero_fill<NT>(a, qt, red, lane, false);         // (the compute waves fetch their codes themselves)
-        } else {
-            bs_zero_fill<NT>(a, qt, red, lane);
-            stage_codes(a, qt, wave, lane);
-            __builtin_amdgcn_s_waitcnt(0);                     // zeros written, this wave's copies landed
-            bwla_lds_barrier();
-        }
+        bs_zero_fill<NT>(a, qt, red, lane);
+        stage_codes(a, qt, wave, lane);
+        __builtin_amdgcn_s_waitcnt(0);                     // zeros written, this wave's copies landed
+        bwla_lds_barrier();
     }
 
     // fp16 operands of T for the f16 MFMA: T * 2^k = hi + lo (both fp16, error 2^-22), with the

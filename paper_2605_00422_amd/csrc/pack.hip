@@ -146,13 +146,19 @@ __global__ void f32_to_f16_rows_kernel(const float* __restrict__ src, int64_t ro
     dst[i] = col < r ? __float2half_rn(src[row * r + col]) : __float2half_rn(0.0f);
 }
 
-// K x r fp32 -> rp x K fp16, transposed (rows r..rp-1 zero)
-__global__ void u_transpose_f16_kernel(const float* __restrict__ U, int64_t K, int r, int rp,
-                                       __half* __restrict__ Ut) {
+// K x r fp32 -> fp16 in the order in which an MFMA (16x16x32) reads its B operand: blocks
+// [16-column tile jt][32-row step ks] of 1 KiB, inside a block lane (li, lg) = lg * 16 + li holds the
+// eight values U[32 ks + 8 lg + e][16 jt + li], e = 0..7 (columns r..rp-1 zero).  A wavefront-wide
+// 16-byte load of a block is one contiguous KiB.
+__global__ void u_pack_f16_kernel(const float* __restrict__ U, int64_t K, int r, int rp, __half* __restrict__ Up) {
     const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
     if (i >= (int64_t)rp * K) return;
-    const int64_t j = i / K, k = i - j * K;
-    Ut[i] = j < r ? __float2half_rn(U[k * r + j]) : __float2half_rn(0.0f);
+    const int e = (int)(i & 7), lane = (int)((i >> 3) & 63);
+    const int64_t blk = i >> 9, ksteps = K >> 5;
+    const int64_t jt = blk / ksteps, ks = blk - jt * ksteps;
+    const int64_t k = 32 * ks + 8 * (lane >> 4) + e;
+    const int j = (int)(16 * jt + (lane & 15));
+    Up[i] = j < r ? __float2half_rn(U[k * r + j]) : __float2half_rn(0.0f);
 }
 
 // n x n fp32 factor R -> three bf16 term planes P[term][x][k], x < np16, k < np32, of R transposed:
@@ -184,6 +190,43 @@ __global__ void factor_planes_kernel(const float* __restrict__ R, int n, int per
     P[i] = (uint16_t)(h1 >> 16);
     P[plane + i] = (uint16_t)(h2 >> 16);
     P[2 * plane + i] = (uint16_t)(h3 >> 16);
+}
+
+// Factor planes of the single-launch decode kernel (n1, n2 of 32 or 64), one 1 KiB block per MFMA
+// operand, lane (li, lg) = lg * 16 + li holding eight 16-bit values:
+//   R2 part, blocks [strip w][step kb][term p < 3]: term p (bf16; the three add up to the fp32 value)
+//            of R2[b = 32 kb + 8 lg + e][d = 16 w + li]
+//   R1 part, blocks [step ch][term t < 2][tile tc]: term t (fp16; hi = nearest, lo = remainder) of
+//            256 R1[a][c = 16 tc + li], a = 32 ch + (e < 4 ? 4 lg + e : 16 + 4 lg + e - 4): the order in
+//            which two stacked 16-row accumulator tiles present their rows to a lane group
+__global__ void decode_planes_kernel(const float* __restrict__ R1, const float* __restrict__ R2, int n1, int n2,
+                                     uint16_t* __restrict__ out) {
+    const int at = n1 / 16, k1 = n2 / 32, ch2 = n1 / 32, strips = n2 / 16;
+    const int nb2 = strips * k1 * 3, nb1 = ch2 * 2 * at;
+    const int i = blockIdx.x * blockDim.x + threadIdx.x;
+    if (i >= (nb2 + nb1) * 512) return;
+    const int blk = i >> 9, lane = (i >> 3) & 63, e = i & 7, li = lane & 15, lg = lane >> 4;
+    if (blk < nb2) {
+        const int p = blk % 3, kb = (blk / 3) % k1, w = blk / (3 * k1);
+        const float v = R2[(int64_t)(32 * kb + 8 * lg + e) * n2 + 16 * w + li];
+        auto bf = [](float f) -> uint32_t {
+            const uint32_t u = __float_as_uint(f);
+            return (u + 0x7fffu + ((u >> 16) & 1u)) & 0xffff0000u;
+        };
+        const uint32_t h1 = bf(v);
+        const float r1 = v - __uint_as_float(h1);
+        const uint32_t h2 = bf(r1);
+        const uint32_t h3 = bf(r1 - __uint_as_float(h2));
+        out[i] = (uint16_t)((p == 0 ? h1 : p == 1 ? h2 : h3) >> 16);
+    } else {
+        const int b1 = blk - nb2;
+        const int tc = b1 % at, t = (b1 / at) % 2, ch = b1 / (2 * at);
+        const int a = 32 * ch + (e < 4 ? 4 * lg + e : 16 + 4 * lg + e - 4);
+        const float v = 256.0f * R1[(int64_t)a * n1 + 16 * tc + li];
+        const __half hi = __float2half_rn(v);
+        const __half lo = __float2half_rn(v - __half2float(hi));
+        out[i] = __half_as_ushort(t == 0 ? hi : lo);
+    }
 }
 
 __global__ void copy_f32_kernel(const float* __restrict__ src, int64_t n, float* __restrict__ dst) {
@@ -222,7 +265,7 @@ hipError_t bwla_launch_pack(const float* dW, const float* dR1, const float* dR2,
     }
     if (r > 0) {
         const int64_t nu = K * rpu;
-        u_transpose_f16_kernel<<<dim3((unsigned)((nu + 255) / 256)), dim3(256), 0, st>>>(dU, K, r, rpu, (__half*)(blob + L->off_U));
+        u_pack_f16_kernel<<<dim3((unsigned)((nu + 255) / 256)), dim3(256), 0, st>>>(dU, K, r, rpu, (__half*)(blob + L->off_U));
     }
     if (L->mode != 0) {
         // columns behind the PSP ones: [asymmetric codes: 2][row shift: 1]
@@ -242,6 +285,10 @@ hipError_t bwla_launch_pack(const float* dW, const float* dR1, const float* dR2,
     const int p1 = ((n1 + 15) & ~15) * ((n1 + 31) & ~31), p2 = ((n2 + 15) & ~15) * ((n2 + 31) & ~31);
     factor_planes_kernel<<<dim3((unsigned)((p1 + 255) / 256)), dim3(256), 0, st>>>(dR1, n1, 1, (uint16_t*)(blob + L->off_R1p));
     factor_planes_kernel<<<dim3((unsigned)((p2 + 255) / 256)), dim3(256), 0, st>>>(dR2, n2, 0, (uint16_t*)(blob + L->off_R2p));
+    if (L->off_Rd != 0) {
+        const int nd = (int)(bwla_decode_planes_bytes(n1, n2) / 2);
+        decode_planes_kernel<<<dim3((unsigned)((nd + 255) / 256)), dim3(256), 0, st>>>(dR1, dR2, n1, n2, (uint16_t*)(blob + L->off_Rd));
+    }
     return hipGetLastError();
 }
 

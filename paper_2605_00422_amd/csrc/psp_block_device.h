@@ -52,7 +52,7 @@ __device__ __forceinline__ void psp_block(char* smem, const void* __restrict__ X
 
     // wave w takes columns [64w, 64w+64) of the slice in 4 groups of 16: lane (li, lg) owns
     // k = 16*g + 4*lg + e, e = 0..3 -- of token li as MFMA operand A, of column jt*16 + li of U as
-    // operand B (8 contiguous bytes of the transposed U).  All loads are issued before the first use.
+    // operand B (8 contiguous bytes of the packed U).  All loads are issued before the first use.
     int64_t trow = (int64_t)tt * 16 + li;
     if (trow > M - 1) trow = M - 1;                    // padded token rows are never stored
     v4f acc[PP_MAXJT];
@@ -77,7 +77,10 @@ __device__ __forceinline__ void psp_block(char* smem, const void* __restrict__ X
         if (!in) x[g][0] = x[g][1] = x[g][2] = x[g][3] = 0.0f;
 #pragma unroll
         for (int jt = 0; jt < PP_MAXJT; ++jt)
-            if (jt < JT) u[g][jt] = *reinterpret_cast<const uint2*>(U + (int64_t)((jt0 + jt) * 16 + li) * K + kc);
+            // (packed U: 1 KiB blocks [column tile][step of 32 rows], lane (li, k / 8 within the step), 8 values)
+            if (jt < JT)
+                u[g][jt] = *reinterpret_cast<const uint2*>(U + ((int64_t)(jt0 + jt) * (K >> 5) + (kc >> 5)) * 512 +
+                                                           ((((int)kc & 31) >> 3) * 16 + li) * 8 + ((int)kc & 7));
     }
 
 #pragma unroll

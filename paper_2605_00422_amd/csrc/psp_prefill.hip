@@ -5,8 +5,9 @@
 // once.  Both MFMA operands come straight from global memory as 16-byte vectors along K:
 //   A  activations, row-major [M][K]; bf16 inputs are used as they are, fp32 inputs are split
 //      into three bf16 terms (8 + 8 + 8 mantissa bits, exact)
-//   B  the packed U, transposed [rp][K] fp16; a fragment is split in registers into two bf16
-//      terms whose sum is the fp16 value exactly (8 + 3 mantissa bits)
+//   B  the packed U, fp16 in MFMA operand order (one contiguous KiB per 16 columns x 32 rows); a
+//      fragment is split in registers into two bf16 terms whose sum is the fp16 value exactly
+//      (8 + 3 mantissa bits)
 // so every product is exact and only the fp32 accumulation rounds.  A workgroup owns 64 tokens
 // x up to 64 columns x one slice of K; its four wavefronts split the slice, add their tiles
 // through LDS and either store T (one slice) or write a partial tile to scratch, where the
@@ -26,7 +27,7 @@ typedef __attribute__((ext_vector_type(8))) __bf16 v8bf;
 struct PfArgs {
     const void* X; int64_t M, K; int r, rp;   // r = rank of the projection (columns of U)
     int tp;                               // row pitch of T (r, or r + 1 for a layer with row shifts)
-    const __half* Ut;                     // [rp][K] fp16
+    const __half* Ut;                     // packed U: [rp / 16][K / 32][64 lanes][8] fp16
     float* T; int* counters; float* partials;
     int S, JG, kslice;
 };
@@ -50,7 +51,7 @@ __device__ __forceinline__ void pf_load(Frag<BF16, NJT>& f, const void* __restri
         }
     }
 #pragma unroll
-    for (int jt = 0; jt < NJT; ++jt) f.b[jt] = *reinterpret_cast<const uint4*>(Ut + uoff[jt] + kb);
+    for (int jt = 0; jt < NJT; ++jt) f.b[jt] = *reinterpret_cast<const uint4*>(Ut + uoff[jt] + kb * 16);
 }
 
 // eight fp16 values -> hi + lo, both bf16: hi = bf16(u) rounded to nearest, lo = u - hi (exact)
@@ -154,7 +155,7 @@ __global__ __launch_bounds__(PF_THREADS) void psp_prefill_kernel(PfArgs a) {
     for (int jt = 0; jt < NJT; ++jt) {
         int row = jg * 64 + jt * 16 + li;
         if (row > a.rp - 1) row = a.rp - 1;            // columns past rp are never stored
-        uoff[jt] = (int64_t)row * K + 8 * lg;
+        uoff[jt] = (int64_t)(row >> 4) * K * 16 + (lg * 16 + (row & 15)) * 8;   // block row of the packed U; a step of 32 is 512 values on
     }
     // every load stays inside [0, K): steps past the range re-read the last block of K and
     // are multiplied by zero

@@ -67,26 +67,20 @@ __device__ __forceinline__ void r3_split3(const float (&f)[8], v8bf& h1, v8bf& h
 // One token per workgroup with resident factors (!LOOP): everything the token needs is requested
 // in one go -- its R2 terms, the token itself, and last the R1 terms, which stay in flight (in
 // registers) through stage 1 and go to LDS just before stage 2.  Wavefronts beyond the strips, if
-// the workgroup has any (and they are not somebody else's, see LOCAL), carry their share of the R1
-// terms and end once it is in LDS.
-// LOCAL (fused single-launch decode): the codes, the per-strip maxima and the per-strip code sums
-// stay in LDS for the rest of the workgroup (see r3_local); only if `store_out` are they also
-// written out.  The body then has exactly R3_LOCAL_BARRIERS barriers, which the workgroup's other
-// wavefronts match.
+// the workgroup has any, carry their share of the R1 terms and end once it is in LDS.
 constexpr int R3_FILLR = 12;         // 16-byte pieces of the R1 terms a thread keeps in flight
-constexpr int R3_LOCAL_BARRIERS = 4;
 // DUAL (with LOOP): the workgroup has two sets of strip wavefronts, each with token rows and
 // reduction words of its own, which work on two tokens at a time with the one copy of the R1
 // terms in LDS: where LDS lets only one workgroup be resident, a SIMD then has two independent
 // MFMA chains to interleave instead of one.  Both sets pass the same barriers; a set without a
 // token left repeats the last one and stores nothing.
-template <int ATM, bool LOOP, bool LOCAL = false, bool DUAL = false>
+template <int ATM, bool LOOP, bool DUAL = false>
 __device__ __forceinline__ void rotate3_token(char* lds, const uint16_t* __restrict__ X, int64_t t_first,
                                               int64_t t_stride, int64_t M, int64_t K, int n1, int n2,
                                               const uint16_t* __restrict__ R1p,
                                               const uint16_t* __restrict__ R2p, int8_t* __restrict__ q,
                                               float* __restrict__ scale, int32_t* __restrict__ qsum,
-                                              bool store_out = true, float* __restrict__ tmode = nullptr,
+                                              float* __restrict__ tmode = nullptr,
                                               int tp = 0, float qmax = 31.0f, bool asym = false,
                                               bool shift = false) {
     const R3Shape sh = r3_shape(n1, n2);
@@ -100,10 +94,10 @@ __device__ __forceinline__ void rotate3_token(char* lds, const uint16_t* __restr
     // (more than 8 tiles along n1 never fit LDS whole: no code for them)
     const bool early = !LOOP && ATM <= 8 && sh.resident;
     const bool helper = wave >= sh.strips;
-    if (helper && !(early && !LOCAL)) return;
+    if (helper && !early) return;
     const int nthreads = 64 * sh.strips;
     const int nth_all = DUAL ? 2 * nthreads : nthreads;
-    const int nfill = (early && !LOCAL) ? (int)blockDim.x : nthreads;
+    const int nfill = early ? (int)blockDim.x : nthreads;
     const int li = lane & 15, lg = lane >> 4;
     const int n1p16 = sh.at * 16, n1p32 = sh.ch2 * 32, n2p32 = sh.k1 * 32;
     char* vt = lds + grp * sh.r0bytes;                                 // token rows, later the code image
@@ -443,7 +437,7 @@ __device__ __forceinline__ void rotate3_token(char* lds, const uint16_t* __restr
     // (one token per workgroup and rows of whole words: the codes go straight to global memory,
     // 16 bytes of a row per lane group; else through an image in LDS and out in 16-byte pieces)
     int8_t* codes = reinterpret_cast<int8_t*>(vt);
-    const bool direct = !LOOP && !LOCAL && (n2 & 3) == 0;
+    const bool direct = !LOOP && (n2 & 3) == 0;
     int8_t* qrow = q + t * K;
     int lsum = 0;
     const int d0 = wave * 16 + 4 * lg;
@@ -478,7 +472,7 @@ __device__ __forceinline__ void rotate3_token(char* lds, const uint16_t* __restr
     int* redi = reinterpret_cast<int*>(red) + 16;
     if (lane == 0) redi[wave] = lsum;
     bwla_lds_barrier();
-    if ((!LOCAL || store_out) && live) {
+    if (live) {
         if (!direct) {
             const uint4* src = reinterpret_cast<const uint4*>(codes);
             uint4* dst = reinterpret_cast<uint4*>(q + t * K);

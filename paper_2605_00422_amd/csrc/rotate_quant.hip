@@ -15,12 +15,11 @@
 //
 // PSP projection (paper Sec. 3.2), T = X U from the un-rotated, un-quantized activations, few
 // tokens: a workgroup takes 16 tokens x 512 columns of K, reads its operands (activations and
-// the transposed fp16 U) straight from global memory and multiplies on fp32 MFMA.  With several
+// the packed fp16 U) straight from global memory and multiplies on fp32 MFMA.  With several
 // slices, every workgroup writes its partial tile to scratch and the one that arrives last adds
 // them in slice order.
 
 #include "bwla_internal.h"
-#include "gemm_decode_bs_device.h"
 #include "rotate_common.h"
 #include "rotate_f32_device.h"
 #include "rotate_bf16_device.h"
@@ -69,8 +68,8 @@ template <int ATM, int THREADS, bool LOOP, bool DUAL = false>
 __global__ __launch_bounds__(THREADS) void rotate_quant3_kernel(RqArgs a) {
     extern __shared__ __align__(16) float lds[];
     if ((int64_t)blockIdx.x < a.rot_blocks) {
-        rotate3_token<ATM, LOOP, false, DUAL>(reinterpret_cast<char*>(lds), reinterpret_cast<const uint16_t*>(a.X), blockIdx.x,
-                           a.rot_blocks, a.M, a.K, a.n1, a.n2, a.R1p, a.R2p, a.q, a.scale, a.qsum, true, a.tmode,
+        rotate3_token<ATM, LOOP, DUAL>(reinterpret_cast<char*>(lds), reinterpret_cast<const uint16_t*>(a.X), blockIdx.x,
+                           a.rot_blocks, a.M, a.K, a.n1, a.n2, a.R1p, a.R2p, a.q, a.scale, a.qsum, a.tmode,
                            a.tp, a.qmax, a.asym != 0, a.shift != 0);
     } else {
         const int pb = (int)(blockIdx.x - a.rot_blocks);
@@ -109,45 +108,6 @@ hipError_t launch_rotate3(const RqArgs& a, int64_t blocks, int threads, size_t l
     }
     if (a.rot_blocks < a.M) return launch_rotate3_v<ATM, THREADS, true>(a, blocks, threads, lds, st);
     return launch_rotate3_v<ATM, THREADS, false>(a, blocks, threads, lds, st);
-}
-
-// ---------------------------------------------------------------------------------------------
-// One launch for a whole decode layer with a single token and no low-rank part (r = 0).  Every
-// workgroup is a workgroup of the activation-stationary GEMM that first rotates and quantizes the
-// token itself: the rotation of one token is a few hundred kFLOP fed from L2, cheaper to repeat
-// per workgroup than to hand its result from one workgroup to all the others through memory, and
-// nothing crosses workgroups.  Wavefronts [0, strips) rotate while wavefronts
-// [strips, strips + KS), the GEMM's compute wavefronts, already have their first weights in
-// flight; then wavefront 0 goes on as the GEMM's epilogue wavefront and the other rotation
-// wavefronts end.  The first workgroup also writes codes, scale and code sum out.
-// (With r > 0 the projection T = x U would have to reach every workgroup inside the launch; the
-// arrival counting and the wait that this takes cost more than the second launch saves.)
-constexpr int FD_THREADS = 512;
-template <int ATM, bool FAST>
-__global__ __launch_bounds__(FD_THREADS) void decode_fused_kernel(RqArgs ra, BsArgs ba) {
-    extern __shared__ __align__(16) float lds[];
-    const R3Shape sh = r3_shape(ra.n1, ra.n2);
-    char* rot = reinterpret_cast<char*>(lds);
-    char* smem = rot + ((sh.lds_bytes + 255) & ~(size_t)255);
-    const FusedLocal fl = r3_local(rot, sh);
-    const int tid = threadIdx.x, lane = tid & 63;
-    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-    const int first = (int)blockIdx.x, stride = (int)gridDim.x;
-    const int n_iter = (ba.row_tiles - first + stride - 1) / stride;
-    if (wave < sh.strips) {
-        rotate3_token<ATM, false, true>(rot, reinterpret_cast<const uint16_t*>(ra.X), 0, 1, 1, ra.K, ra.n1, ra.n2,
-                                        ra.R1p, ra.R2p, ra.q, ra.scale, ra.qsum, first == 0);
-        if (wave != 0) return;
-        epilogue_wave<2, 1, 0, FAST, true>(ba, smem, first, stride, n_iter, ba.KS, lane, fl);
-    } else {
-        const int cw = wave - sh.strips;
-        if (cw >= ba.KS) return;                                   // surplus wavefronts
-        // r = 0: only the wavefront that fetches the output scales has a side piece
-        if (cw == 0)
-            compute_wave<BS_CPW, 2, 1, true, true>(ba, smem, first, stride, n_iter, cw, lane, fl, R3_LOCAL_BARRIERS);
-        else
-            compute_wave<BS_CPW, 2, 1, false, true>(ba, smem, first, stride, n_iter, cw, lane, fl, R3_LOCAL_BARRIERS);
-    }
 }
 
 __global__ __launch_bounds__(256) void code_sums_kernel(const int8_t* __restrict__ q, int64_t K,
@@ -348,47 +308,6 @@ size_t bwla_split_rotation_bytes(const bwla_layer_t* L, const bwla_psp_plan& pla
     // 34.5 against 32.0; with more tokens the one-workgroup-per-token kernel keeps the chip busy
     if (M * rs.G + pblocks > 2 * bwla_device_cus()) return 0;
     return (size_t)(M * L->K + 2 * M * rs.E + M) * sizeof(float);     // values, extremes, per-token code offset
-}
-
-// Single-launch decode layer.  *done = false (and nothing launched) when the shape is outside what
-// the fused kernel takes: one bf16 token, r = 0, factors resident in LDS with at most 8 tiles
-// along n1, rotation strips and GEMM compute wavefronts together within the 512-thread workgroup
-// (K = 4096 with n2 = 64: 4 + 4), and LDS for both roles side by side.
-hipError_t bwla_launch_decode_fused(const bwla_layer_t* L, const void* dX, int xdtype, int64_t M, int8_t* dq,
-                                    float* dscale, int32_t* dqsum, float* dY, int32_t* dacc, hipStream_t st,
-                                    bool* done) {
-    *done = false;
-    const R3Shape s3 = r3_shape(L->n1, L->n2);
-    const int chunks = (int)bwla_chunks(L->K), row_tiles = (int)bwla_row_tiles(L->N);
-    const int KS = (chunks + BS_CPW - 1) / BS_CPW;
-    if (M != 1 || L->r != 0 || xdtype != BWLA_X_BF16 || !s3.ok || !s3.resident || s3.at > 8 || (L->K & 15) != 0)
-        return hipSuccess;
-    if (chunks < 2 || s3.strips + KS > FD_THREADS / 64 || !bs_fits(M, chunks, 0, 1)) return hipSuccess;
-    const size_t lds = ((s3.lds_bytes + 255) & ~(size_t)255) + bs_lds_bytes(M, chunks, 0, 1);
-    if (lds > 160 * 1024) return hipSuccess;
-    const char* blob = (const char*)L->d_blob;
-    RqArgs ra{};
-    ra.X = dX; ra.M = M; ra.K = L->K; ra.n1 = L->n1; ra.n2 = L->n2; ra.r = 0;
-    ra.R1p = (const uint16_t*)(blob + L->off_R1p); ra.R2p = (const uint16_t*)(blob + L->off_R2p);
-    ra.q = dq; ra.scale = dscale; ra.qsum = dqsum;
-    BsArgs ba{(const uint4*)(blob + L->off_bits), chunks, row_tiles, dq, (int)M, (int)L->K, dscale, dqsum,
-              (const __half*)(blob + L->off_alpha), (const __half*)(blob + L->off_V), nullptr, 0, dY, (int)L->N,
-              dacc, KS, 0, 1};
-    // one workgroup per CU fits (registers)
-    const int cus = bwla_device_cus();
-    const int G = row_tiles < cus ? row_tiles : cus;
-    const bool fast = (L->N % 4 == 0) && dacc == nullptr;
-    auto launch = [&](auto kern) -> hipError_t {
-        hipError_t e = bwla_ensure_lds((const void*)kern, lds);
-        if (e != hipSuccess) return e;
-        kern<<<dim3((unsigned)G), dim3(FD_THREADS), lds, st>>>(ra, ba);
-        return hipGetLastError();
-    };
-    hipError_t e;
-    if (s3.at <= 4) e = fast ? launch(decode_fused_kernel<4, true>) : launch(decode_fused_kernel<4, false>);
-    else e = fast ? launch(decode_fused_kernel<8, true>) : launch(decode_fused_kernel<8, false>);
-    if (e == hipSuccess) *done = true;
-    return e;
 }
 
 hipError_t bwla_launch_code_sums(const int8_t* dq, int64_t M, int64_t K, int32_t* dqsum, hipStream_t st) {

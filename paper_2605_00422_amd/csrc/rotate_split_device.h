@@ -346,12 +346,4 @@ __global__ void shift_column_kernel(const float* __restrict__ scale, const int32
     if (t < M) tshift[t * tp] = scale[t] * ((float)qsum[t] - (float)K * zcs[t]);
 }
 
-// where rotate3_token<.., LOCAL> leaves its results (resident shapes only)
-__device__ __forceinline__ FusedLocal r3_local(const char* lds, const R3Shape& sh) {
-    // words [0, 16) largest values, [16, 32) code sums, [32, 48) smallest values (of the 64 words
-    // behind the chunk buffers)
-    const float* red = reinterpret_cast<const float*>(lds + sh.r0bytes + (size_t)sh.nbuf * sh.cbytes);
-    return FusedLocal{lds, red, reinterpret_cast<const int*>(red) + 16, sh.strips};
-}
-
 }  // namespace
