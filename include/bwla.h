@@ -172,9 +172,13 @@ BWLA_API bwla_status_t bwla_unpack_signs(const bwla_layer_t* layer, int8_t* d_sg
  * arrival counters, and, for a few tokens of a layer with a large factor R1 (six or more 16-row
  * tiles), the rotated values in fp32 and their extremes between the two launches the rotation
  * then takes.  Returns 0 bytes when neither is used.
- * The scratch must be zero-filled once when it is allocated: it starts with one arrival counter
- * per 16-token tile, which every call returns to zero; everything behind them is overwritten by
- * each call.  Two calls that overlap in time must not share one scratch buffer.
+ * The scratch must be zero-filled once when it is allocated and then left to the library: its
+ * first 5120 bytes are the exchange area of bwla_decode_forward's single-launch kernel (an epoch
+ * that every such launch moves on, arrival counts that every launch returns to zero, partial
+ * sums tagged with their epoch), then comes one arrival counter per 16-token tile, which every
+ * call returns to zero; everything behind them is overwritten by each call.  One scratch may
+ * serve calls on different layers and token counts; two calls that overlap in time must not
+ * share one.
  */
 BWLA_API bwla_status_t bwla_psp_workspace_size(const bwla_layer_t* layer, int64_t M, size_t* bytes);
 
@@ -239,9 +243,12 @@ BWLA_API bwla_status_t bwla_linear_forward(const bwla_layer_t* layer, const int8
  * bf16 token of a layer whose Kronecker factors are 32 or 64 wide (K = 1024 .. 4096: the
  * attention and up / gate projections of the 4096-wide models), with a PSP rank up to 64 and
  * symmetric codes (with or without the row shift), everything runs in ONE kernel launch: every
- * workgroup rotates and quantizes the token itself while its sign bits stream in, half of its
- * wavefronts compute T = x U meanwhile, and nothing crosses workgroups.  All other cases run the
- * two launches back to back.
+ * workgroup rotates and quantizes the token itself while its sign bits stream in; only the
+ * projection T = x U is shared: the first 32 workgroups compute it in eight slices of K and
+ * leave the sums, tagged with a per-launch epoch, in the first bytes of d_ws, where every
+ * workgroup picks them up (bounded polling; no workgroup ever waits for one that has not been
+ * started).  That exchange is why calls that share one d_ws must not overlap.  All other cases
+ * run the two launches back to back.
  */
 BWLA_API bwla_status_t bwla_decode_forward(const bwla_layer_t* layer, const void* d_X, int xdtype, int64_t M,
                                   int8_t* d_q, float* d_scale, int32_t* d_qsum, float* d_T,

@@ -70,12 +70,15 @@ bwla_status_t check_layer(const bwla_layer_t* L) {
     return BWLA_OK;
 }
 
-// scratch of bwla_rotate_quant: the projection's part, then (256-byte aligned) the split rotation's
+// scratch of bwla_rotate_quant: the head every scratch has, the projection's part, then (256-byte
+// aligned) the split rotation's; nothing at all when neither part is needed
 size_t rq_ws_bytes(const bwla_layer_t* L, const bwla_psp_plan& p, int64_t M) {
     const size_t split = bwla_split_rotation_bytes(L, p, M);
     const size_t psp = bwla_psp_ws_bytes(p, M, bwla_rank_u(L));
-    return split ? (size_t)bwla_align256(psp) + split : psp;
+    const size_t body = split ? (size_t)bwla_align256(psp) + split : psp;
+    return body ? (size_t)BWLA_WS_HEAD + body : 0;
 }
+inline void* ws_body(void* d_ws) { return d_ws ? (char*)d_ws + BWLA_WS_HEAD : nullptr; }
 
 }  // namespace
 
@@ -113,9 +116,13 @@ static __device__ __align__(256) unsigned char scratch[BWLA_STATIC_SCRATCH_BYTES
 
 namespace {
 
-__global__ void fill_zero_kernel(uint32_t* p, int n) {
+// what must read zero when a call starts: the eight arrival counts in the scratch's head (words
+// 16, 32, .. 128; the epoch and the tagged words beside them must stay as they are) and the
+// counters behind the head
+__global__ void clear_counts_kernel(uint32_t* ws, int head_words, int n) {
     const int i = (int)(blockIdx.x * blockDim.x + threadIdx.x);
-    if (i < n) p[i] = 0u;
+    if (i < n) ws[head_words + i] = 0u;
+    if (i < 8) ws[16 * (1 + i)] = 0u;
 }
 
 hipError_t static_scratch_ptr(void** out) {
@@ -268,7 +275,7 @@ bwla_status_t bwla_rotate_quant_bits(const bwla_layer_t* layer, const void* d_X,
     const size_t need = rq_ws_bytes(layer, plan, M);
     if (need > 0 && (!d_ws || ws_bytes < need)) return d_ws ? BWLA_ERR_BUFSIZE : BWLA_ERR_NULL;
     hipStream_t st = (hipStream_t)stream;
-    if (bwla_launch_rotate_quant(layer, d_X, xdtype, M, d_q, d_scale, d_qsum, d_T, d_ws, plan, st, act_bits) !=
+    if (bwla_launch_rotate_quant(layer, d_X, xdtype, M, d_q, d_scale, d_qsum, d_T, ws_body(d_ws), plan, st, act_bits) !=
         hipSuccess)
         return BWLA_ERR_HIP;
     return BWLA_OK;
@@ -292,7 +299,8 @@ bwla_status_t bwla_decode_forward(const bwla_layer_t* layer, const void* d_X, in
     hipStream_t st = (hipStream_t)stream;
     // one launch when the shape allows it
     bool done = false;
-    if (bwla_launch_decode_layer(layer, d_X, xdtype, M, d_q, d_scale, d_qsum, d_T, d_Y, d_acc, st, &done) != hipSuccess)
+    if (bwla_launch_decode_layer(layer, d_X, xdtype, M, d_q, d_scale, d_qsum, d_T, need > 0 ? d_ws : nullptr, d_Y, d_acc, st,
+                                 &done) != hipSuccess)
         return BWLA_ERR_HIP;
     if (done) return BWLA_OK;
     s = bwla_rotate_quant(layer, d_X, xdtype, M, d_q, d_scale, d_qsum, d_T, d_ws, ws_bytes, stream);
@@ -319,10 +327,11 @@ bwla_status_t bwla_decode_forward_static(const bwla_layer_t* layer, const void* 
     void* ws = nullptr;
     if (static_scratch_ptr(&ws) != hipSuccess) return BWLA_ERR_HIP;
     if (need > 0) {
-        // the arrival counters at the head of the scratch must read zero; a kernel clears them (a
-        // memset node would not replay reliably from a captured graph)
+        // the arrival counts of the scratch must read zero; a kernel clears them (a memset node would
+        // not replay reliably from a captured graph)
         const int words = (int)(bwla_psp_counter_bytes(M) / sizeof(uint32_t));
-        fill_zero_kernel<<<dim3((unsigned)((words + 255) / 256)), dim3(256), 0, (hipStream_t)stream>>>((uint32_t*)ws, words);
+        clear_counts_kernel<<<dim3((unsigned)((words + 255) / 256)), dim3(256), 0, (hipStream_t)stream>>>(
+            (uint32_t*)ws, (int)(BWLA_WS_HEAD / sizeof(uint32_t)), words);
         if (hipGetLastError() != hipSuccess) return BWLA_ERR_HIP;
     }
     return bwla_decode_forward(layer, d_X, xdtype, M, d_q, d_scale, d_qsum, d_T, ws, BWLA_STATIC_SCRATCH_BYTES, d_Y,

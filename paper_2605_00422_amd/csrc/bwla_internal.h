@@ -55,7 +55,14 @@ struct bwla_psp_plan {
     int col_groups;    // tiles across the rank
 };
 bwla_psp_plan bwla_make_psp_plan(int64_t M, int64_t K, int r);
-// scratch starts with one arrival counter per 16 tokens (whatever the plan), padded to 256 bytes
+// Every scratch of bwla_rotate_quant starts with the exchange area of the single-launch decode
+// kernel -- an epoch word, eight arrival counts (64 bytes apart, from byte 64 on), and from byte
+// 1024 on 8 x 64 tagged partial sums of T = x U, 8 bytes each -- at the same place whatever the
+// layer and the token count, so that every
+// call on a scratch agrees on it and no other kernel writes there.  The counters and partial sums
+// of the other kernels follow behind it.
+constexpr uint64_t BWLA_WS_HEAD = 1024 + 8 * 64 * 8;
+// behind the head: one arrival counter per 16 tokens (whatever the plan), padded to 256 bytes
 inline uint64_t bwla_psp_counter_bytes(int64_t M) { return bwla_align256((uint64_t)((M + 15) / 16) * sizeof(int)); }
 // columns that a layer's mode adds to V and T behind the PSP columns
 inline int bwla_extra_cols(int mode) { return ((mode & BWLA_MODE_ASYM_ACT) ? 2 : 0) + ((mode & BWLA_MODE_ROW_SHIFT) ? 1 : 0); }
@@ -122,8 +129,8 @@ __device__ __forceinline__ bool bwla_partials_arrive(int* counter, int expected,
 hipError_t bwla_launch_code_sums(const int8_t* dq, int64_t M, int64_t K, int32_t* dqsum, hipStream_t st);
 // the whole layer in one launch for one bf16 token where the shape allows it (*done says whether)
 hipError_t bwla_launch_decode_layer(const bwla_layer_t* L, const void* dX, int xdtype, int64_t M, int8_t* dq,
-                                    float* dscale, int32_t* dqsum, float* dT, float* dY, int32_t* dacc,
-                                    hipStream_t st, bool* done);
+                                    float* dscale, int32_t* dqsum, float* dT, void* dws_head, float* dY,
+                                    int32_t* dacc, hipStream_t st, bool* done);
 
 hipError_t bwla_launch_gemm_decode(const bwla_layer_t* L, const int8_t* dq, const float* dscale,
                                    const int32_t* dqsum, const float* dT, int64_t M, float* dY,

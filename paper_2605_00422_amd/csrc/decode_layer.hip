@@ -1,23 +1,30 @@
 // One launch for a whole decode layer with a single bf16 token (the memory-bound case of paper
 // Sec. 4.4): rotation (Sec. 3.1), symmetric INT6 codes (Sec. 4.1), binary GEMM (Eq. 3-4), PSP
-// branch (Sec. 3.2) and dequantization in every workgroup, with nothing crossing workgroups.
+// branch (Sec. 3.2) and dequantization.
 //
 // A workgroup owns a few 16-channel tiles of the output and has eight wavefronts:
 //   wavefronts 0..3  rotate the token (one 16-column strip of the n1 x n2 reshape each) and
 //                    quantize it: the rotation of one token is about a megaflop fed from L2,
 //                    cheaper to repeat in every workgroup than to hand its result around;
-//   wavefronts 4..7  meanwhile compute T = x U for a quarter of K each on fp16 MFMA (x is scaled
-//                    by a power of two per quarter so that it fits fp16 exactly; U is stored in
-//                    B operand order and read straight from L2, 2 K r bytes per workgroup -- the
-//                    price of needing no hand-over between workgroups);
-//   all eight        then contract the codes with the workgroup's sign bits, which every wavefront
-//                    requested for its 512-column chunk before anything else, so that they stream
-//                    from HBM while the token is rotated; one wavefront finishes the outputs.
+//   all eight        then contract the codes with the workgroup's sign bits, one 512-column chunk
+//                    each, requested as soon as the rotation's operands have landed so that they
+//                    stream from HBM while the token is rotated; afterwards each wavefront finishes one round
+//                    of tiles (scale, alpha, PSP columns, store).
+// The PSP projection T = x U is the one thing that is shared: U is 2 K r bytes, and reading it in
+// every workgroup would cost more L2 bandwidth than the whole layer costs HBM bandwidth.  The
+// first workgroups each project one eighth of K on fp16 MFMA (x scaled by a power of two per piece
+// so that it fits fp16 exactly; U stored in B operand order) and leave their 8 x r partial sums
+// in the scratch, each value in one 8-byte word with the call's epoch as a tag; every workgroup
+// polls those words with device-scope loads while its rotation is still running, and adds the
+// eight slices in slice order.  The epoch comes from the scratch and is bumped once per launch by
+// the workgroup that is the last to have read it, so a word written by an earlier call can never
+// pass for this call's, and nothing has to be cleared.
 // What the kernel is bound by at these sizes is instruction issue and latency, not bandwidth, so
 // the serial path is kept short: operands go global -> LDS asynchronously in the order in which
 // an MFMA lane reads them (no repacking, no bank conflicts), reductions run on DPP row operations,
 // codes are rounded by adding 1.5 * 2^23 (one fused multiply-add per code, round-half-even), and
-// the only workgroup barriers are: operands landed, codes ready, partial sums ready.
+// wavefronts meet through arrival counts in LDS instead of workgroup barriers wherever only some
+// of them have to.
 #include <type_traits>
 
 #include "bwla_internal.h"
@@ -34,6 +41,8 @@ constexpr int DL_MAXK1 = 2;          // 32-deep steps along n2 (n2 <= 64)
 constexpr int DL_MAXJTU = 4;         // 16-column tiles of U (PSP rank <= 64)
 constexpr int DL_MAXJTV = 5;         // 16-column tiles of V (one more when the layer's mode adds a column)
 constexpr int DL_MAXROUNDS = 8;      // rounds of DL_TPW tiles per workgroup (more channels than that: two launches)
+constexpr int DL_SLICES = 8;         // slices of K of the shared projection
+constexpr int DL_PRODUCERS = 32;     // workgroups that project (each slice four times: the first to land serves)
 constexpr int DL_SPIN_LIMIT = 1 << 22;
 
 // (the pointers every wavefront needs for its first requests are kernel parameters of their own:
@@ -42,8 +51,10 @@ constexpr int DL_SPIN_LIMIT = 1 << 22;
 struct DlArgs {
     int8_t* q; float* scale; int32_t* qsum; float* T;      // written by workgroup 0
     float* Y; int32_t* acc_out;
+    unsigned* sync;                  // head of the scratch: [0] epoch, [16 (1 + i)] arrival count i < 8, from byte 1024 on the tagged sums
     int N, r, ru, row_tiles, rounds, shift;
 };
+
 
 // ---- DPP row operations: reductions over the 64 lanes without LDS traffic
 template <int CTRL>
@@ -99,7 +110,9 @@ __global__ __launch_bounds__(DL_THREADS) void decode_layer_kernel(const uint16_t
                                                                   const __half* __restrict__ palpha, DlArgs a) {
     constexpr int K = N1 * N2, AT = N1 / 16, K1 = N2 / 32, CH2 = N1 / 32, STRIPS = N2 / 16, CHUNKS = K / 512;
     constexpr int GPR = N2 / 8;                        // 16-byte granules per token row: 8 or 4
-    constexpr int S = K / 4, NKS = S / 32;             // T: columns and 32-deep steps per quarter of K
+    constexpr int SW = K / DL_SLICES, SWW = SW / 4;    // T: columns per slice and per wavefront of a producer
+    constexpr int NKS = SWW / 32, RPU = 16 * JTU;      // T: 32-deep steps per wavefront; columns of U
+    static_assert(JTU == 0 || NKS >= 1, "a producer wavefront has at least one step");
     static_assert(STRIPS <= 4 && AT <= 4 && CHUNKS <= 8 && CHUNKS >= 2, "shape outside the kernel's wavefront roles");
     extern __shared__ __align__(16) char lds[];
     const int tid = threadIdx.x, lane = tid & 63;
@@ -111,18 +124,18 @@ __global__ __launch_bounds__(DL_THREADS) void decode_layer_kernel(const uint16_t
     char* xt = lds;                                    // token rows, bf16, K * 2 bytes, granules swizzled
     char* r1 = xt + 2 * K;                             // R1 terms [chunk][term][tile of c][lane * 16]: CH2 * 2 * AT KiB
     char* codes = r1 + CH2 * 2 * AT * 1024;            // K code bytes, k order
-    char* xh = codes + K;                              // token as fp16, scaled per quarter of K: K * 2 bytes
-    float* red = reinterpret_cast<float*>(xh + 2 * K); // [0..3] strip maxima, [4..7] strip code sums, [8] arrival count
-    float* tpart = red + 16;                           // [4 quarters][16 * DL_MAXJTU] partial T
-    float* tfin = tpart + 4 * 16 * DL_MAXJTU;          // [8 wavefronts][16 * DL_MAXJTV] T as an epilogue wavefront reads it
+    char* xh = codes + K;                              // a producer's slice of the token as fp16: SW * 2 bytes
+    float* red = reinterpret_cast<float*>(xh + 2 * SW);// [0..3] strip maxima, [4..7] strip code sums, [8..13] arrival counts, [14] epoch
+    float* tpart = red + 16;                           // [4 wavefronts][16 * DL_MAXJTU] partial T of a producer
+    float* txl = tpart + 4 * 16 * DL_MAXJTU;           // [DL_SLICES][16 * DL_MAXJTU] the slices' sums, [DL_SLICES * ...] on: T
+    float* tfin = txl + (DL_SLICES + 1) * 16 * DL_MAXJTU;   // [8 wavefronts][16 * DL_MAXJTV] T as an epilogue wavefront reads it
     int* part = reinterpret_cast<int*>(tfin + 8 * 16 * DL_MAXJTV);   // [rounds][DL_TPW][8 chunks][16 channels]
-    char* wb = reinterpret_cast<char*>(part + DL_MAXROUNDS * DL_TPW * 8 * 16);   // sign bits of the first round: [DL_TPW][CHUNKS] KiB
 
-    // arrival counts (rotation wavefronts: operands landed, maxima left, codes written; wavefronts
-    // 4..7: sign bits landed), zero before anybody bumps them: this barrier costs nothing, every
-    // wavefront would otherwise wait here for its first operands
+    // arrival counts (rotation wavefronts: operands landed, maxima left, codes written; a producer's
+    // wavefronts: partial sums left; wavefront 7: epoch read), zero before anybody bumps them: this
+    // barrier costs nothing, every wavefront would otherwise wait here for its first operands
     int* cnt = reinterpret_cast<int*>(red) + 8;
-    if (tid < 4) cnt[tid] = 0;
+    if (tid < 5) cnt[tid] = 0;
     bwla_lds_barrier();
     // A subset of the wavefronts meets without holding up the others: each bumps the count when it
     // is ready, and whoever needs them all waits until the count is full.  (The wait is bounded: a
@@ -143,18 +156,15 @@ __global__ __launch_bounds__(DL_THREADS) void decode_layer_kernel(const uint16_t
         const int id = tile_id(rd, t);
         return id < a.row_tiles ? id : a.row_tiles - 1;
     };
-    // with a T part the first four wavefronts contract (two chunks each) while the others project;
-    // without, all eight contract
-    constexpr int GW = JTU > 0 ? 4 : 8, CPW = (CHUNKS + GW - 1) / GW;
-    const bool rotates = wave < STRIPS, projects = JTU > 0 && wave >= 4, contracts = wave < GW;
+    constexpr int GW = 8, CPW = (CHUNKS + GW - 1) / GW;
+    const bool rotates = wave < STRIPS, contracts = wave < GW;
+    const bool produces = JTU > 0 && wave >= 4 && blk < DL_PRODUCERS;     // my slice: blk & 7
+    const int slice = blk & (DL_SLICES - 1);
 
-    // Sign bits.  They are the bulk of the layer's bytes and are not needed before the codes exist,
-    // so they are requested only once the rotation's operands have landed.  With a T part, those of
-    // the first round are fetched by the T wavefronts, asynchronously into LDS: a request of a
-    // rotation wavefront would stall it behind the T wavefronts' stream in the memory pipeline.
-    // Without, and for later rounds (layers of more than DL_TPW tiles per workgroup), every
-    // contracting wavefront loads its own into registers, a round ahead.
-    constexpr bool BITS_VIA_LDS = JTU > 0;
+    // Sign bits of my chunk for a round's tiles.  They are the bulk of the layer's bytes and are not
+    // needed before the codes exist, so they are requested only once the rotation's operands have
+    // landed: the weight stream then runs in the shadow of the rotation instead of holding up the
+    // few kilobytes the rotation waits for.
     v4i wq[DL_TPW][CPW];
 #pragma unroll
     for (int t = 0; t < DL_TPW; ++t)
@@ -172,20 +182,13 @@ __global__ __launch_bounds__(DL_THREADS) void decode_layer_kernel(const uint16_t
                 }
             }
     };
-    // epilogue: wavefront e finishes round e; lane o < 16 * DL_TPW channel o & 15 of tile o >> 4
+    // epilogue: round 0 is finished by wavefront 5, then 6, 7, 4, 3 .. 0 (wavefronts 4 and 7 have
+    // errands of their own, and the rotation wavefronts' first requests are the ones everything
+    // waits for); lane o < 16 * DL_TPW channel o & 15 of tile o >> 4
+    const int my_round = wave >= 5 ? wave - 5 : (wave == 4 ? 3 : 7 - wave);
     constexpr int VQ = 2 * JTV;                        // 16-byte pieces of a V row
     v4i vrow[VQ > 0 ? VQ : 1];
     uint16_t alpha_raw = 0;
-    auto fetch_first_bits = [&]() {                     // wavefronts 4..7
-#pragma unroll
-        for (int i = 0; i < (DL_TPW * CHUNKS + 3) / 4; ++i) {
-            const int idx = (wave - 4) + 4 * i;
-            if (idx < DL_TPW * CHUNKS) {
-                const int t = idx / CHUNKS, c = idx - t * CHUNKS;
-                dl_async_16(pbits + (tile_of(0, t) * CHUNKS + c) * 64 + lane, wb + idx * 1024);
-            }
-        }
-    };
     auto epi_loads = [&](int rd) {
         const int ti = lane >> 4;
         if (ti < DL_TPW) {
@@ -198,16 +201,12 @@ __global__ __launch_bounds__(DL_THREADS) void decode_layer_kernel(const uint16_t
     };
     // ================================================================ requests, critical ones first
     v4i bfr[K1][3];                                    // R2 terms of my strip (rotation wavefronts)
-    v4i xq[2] = {v4i{0, 0, 0, 0}, v4i{0, 0, 0, 0}};   // my quarter of the token (T wavefronts)
-    constexpr int TD = JTU <= 2 ? 16 : 8;              // T: steps in flight
-    v4i uring[TD][JTU > 0 ? JTU : 1];
-    // T: workgroups walk over U from different starting steps: the workgroups of one L2 then ask
-    // for all of U at once instead of all waiting for the same lines, one round trip after the other
-    const int ks_first = (blk >> 3) & (NKS - 1);
-    auto u_load = [&](int i, int jt) -> v4i {
-        const int ks = (ks_first + (i < NKS ? i : NKS - 1)) & (NKS - 1);
-        return *reinterpret_cast<const v4i*>(pUt + ((jt * (K / 32) + (wave - 4) * NKS + ks) * 64 + lane) * 8);
-    };
+    v4i xq = v4i{0, 0, 0, 0};                          // my piece of the token (a producer's wavefronts)
+    v4i uop[NKS > 0 ? NKS : 1][JTU > 0 ? JTU : 1];
+    unsigned epoch = 0;
+    // (an ordinary load: the word was written by an earlier launch, and this launch moves it on only
+    // after every workgroup has read it)
+    if (JTU > 0 && wave == 7) epoch = *reinterpret_cast<const volatile unsigned*>(a.sync);
     if (rotates) {
         // the token, asynchronously into LDS: 1 KiB per instruction
 #pragma unroll
@@ -232,72 +231,119 @@ __global__ __launch_bounds__(DL_THREADS) void decode_layer_kernel(const uint16_t
             const int b1 = wave + i * STRIPS;
             if (b1 < NB) dl_async_16(pR1h + (b1 * 64 + lane) * 8, r1 + b1 * 1024);
         }
-        if (wave < a.rounds) epi_loads(wave);
-    } else if (projects) {
+        if (my_round < a.rounds) epi_loads(my_round);
+    } else if (produces) {
+        // my SWW columns of the token (16 bytes from each of the first lanes) and of U
+        const int col0 = slice * SW + (wave - 4) * SWW;
+        if (lane * 8 < SWW) xq = *reinterpret_cast<const v4i*>(pX + col0 + lane * 8);
 #pragma unroll
-        for (int i = 0; i < 2; ++i) {
-            const int piece = lane + 64 * i;
-            if (piece * 8 < S) xq[i] = *reinterpret_cast<const v4i*>(pX + (wave - 4) * S + piece * 8);
-        }
-        if (wave < a.rounds) epi_loads(wave);
-        fetch_first_bits();
-        __builtin_amdgcn_sched_barrier(0);             // (the counted wait further down relies on this order)
+        for (int ks = 0; ks < NKS; ++ks)
 #pragma unroll
-        for (int d = 0; d < TD; ++d)
-#pragma unroll
-            for (int jt = 0; jt < JTU; ++jt) uring[d][jt] = u_load(d, jt);
+            for (int jt = 0; jt < JTU; ++jt)
+                uop[ks][jt] = *reinterpret_cast<const v4i*>(pUt + ((jt * (K / 32) + col0 / 32 + ks) * 64 + lane) * 8);
     }
 
-    // ================================================================ T = x U, first part: the token as fp16
-    float t_unscale = 1.0f;
-    if (projects) {
+    // ================================================================ T = x U, a producer's slice
+    if (produces) {
         float m = 0.0f;
 #pragma unroll
-        for (int i = 0; i < 2; ++i)
-#pragma unroll
-            for (int e = 0; e < 4; ++e) {
-                const uint32_t w = (uint32_t)xq[i][e];
-                m = fmaxf(m, fmaxf(fabsf(__uint_as_float(w << 16)), fabsf(__uint_as_float(w & 0xffff0000u))));
-            }
+        for (int e = 0; e < 4; ++e) {
+            const uint32_t w = (uint32_t)xq[e];
+            m = fmaxf(m, fmaxf(fabsf(__uint_as_float(w << 16)), fabsf(__uint_as_float(w & 0xffff0000u))));
+        }
         m = dl_wave_max_nonneg(m);
-        // power of two that puts the quarter's largest magnitude into [2^13, 2^14): bf16 values are
+        // power of two that puts the piece's largest magnitude into [2^13, 2^14): bf16 values are
         // then fp16 values exactly, unless they are 2^28 times smaller than that largest one
         int E = (__float_as_int(m) >> 23) & 0xff;
         E = E < 32 ? 32 : (E > 222 ? 222 : E);
         const float sc = __int_as_float((267 - E) << 23);
-        t_unscale = __int_as_float((E - 13) << 23);
+        const float t_unscale = __int_as_float((E - 13) << 23);
+        if (lane * 8 < SWW) {
+            v4i o;
 #pragma unroll
-        for (int i = 0; i < 2; ++i) {
-            const int piece = lane + 64 * i;
-            if (piece * 8 < S) {
-                v4i o;
-#pragma unroll
-                for (int e = 0; e < 4; ++e) {
-                    const uint32_t w = (uint32_t)xq[i][e];
-                    const auto h2 = __builtin_amdgcn_cvt_pkrtz(__uint_as_float(w << 16) * sc,
-                                                               __uint_as_float(w & 0xffff0000u) * sc);
-                    o[e] = __builtin_bit_cast(int, h2);
-                }
-                *reinterpret_cast<v4i*>(xh + ((wave - 4) * S + piece * 8) * 2) = o;
+            for (int e = 0; e < 4; ++e) {
+                const uint32_t w = (uint32_t)xq[e];
+                const auto h2 = __builtin_amdgcn_cvt_pkrtz(__uint_as_float(w << 16) * sc, __uint_as_float(w & 0xffff0000u) * sc);
+                o[e] = __builtin_bit_cast(int, h2);
             }
+            *reinterpret_cast<v4i*>(xh + ((wave - 4) * SWW + lane * 8) * 2) = o;
         }
-        // the sign bits have landed once only the requests for U, which are younger, are outstanding
-        __builtin_amdgcn_sched_barrier(0);
-        __builtin_amdgcn_s_waitcnt(0x0F70 | ((TD * JTU) & 15) | (((TD * JTU) >> 4) << 14));   // vmcnt(TD * JTU)
+        v4f tacc[JTU > 0 ? JTU : 1];
+#pragma unroll
+        for (int jt = 0; jt < (JTU > 0 ? JTU : 1); ++jt) tacc[jt] = v4f{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int ks = 0; ks < NKS; ++ks) {
+            // every row of the A operand is the token (the LDS writes above are this wavefront's own)
+            const v8h av = __builtin_bit_cast(v8h, *reinterpret_cast<const v4i*>(xh + ((wave - 4) * SWW + 32 * ks + 8 * lg) * 2));
+#pragma unroll
+            for (int jt = 0; jt < JTU; ++jt)
+                tacc[jt] = __builtin_amdgcn_mfma_f32_16x16x32_f16(av, __builtin_bit_cast(v8h, uop[ks][jt]), tacc[jt], 0, 0, 0);
+        }
+        // row 0 of the result (lanes 0..15) is my part of the slice's sums
+        if (lane < 16) {
+#pragma unroll
+            for (int jt = 0; jt < JTU; ++jt) tpart[(wave - 4) * 16 * DL_MAXJTU + 16 * jt + lane] = tacc[jt][0] * t_unscale;
+        }
         arrive(cnt + 3);
-    } else if (!rotates) {
+    }
+    if (JTU > 0 && wave == 7) {
+        // the epoch has been read (the bump at the end of the kernel must not come before every
+        // workgroup has): hand it to wavefront 4, and count this workgroup in
+        if (lane == 0) {
+            reinterpret_cast<unsigned*>(red)[14] = epoch;
+            // (eight counts, 64 bytes apart, and nobody waits for the result: 256 arrivals at one
+            // address would take microseconds)
+            __hip_atomic_fetch_add(a.sync + 16 * (1 + (blk & 7)), 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        }
+        arrive(cnt + 4);
+    }
+    if (!rotates) {
         // a wavefront that only contracts waits until the rotation's operands are there
         await(cnt, STRIPS);
-        if (!BITS_VIA_LDS) request_bits(0);
-        if (wave < a.rounds) epi_loads(wave);
+        request_bits(0);
+        if (my_round < a.rounds) epi_loads(my_round);
     }
+    if (JTU > 0 && wave == 4) {
+        await(cnt + 4, 1);
+        const unsigned tag = reinterpret_cast<const unsigned*>(red)[14] + 1u;
+        unsigned long long* tx = reinterpret_cast<unsigned long long*>(a.sync + 256);
+        if (blk < DL_PRODUCERS) {
+            // the slice's sums: four wavefronts' parts in wavefront order; value and tag in one word
+            await(cnt + 3, 4);
+            if (lane < RPU) {
+                float v = 0.0f;
+#pragma unroll
+                for (int w = 0; w < 4; ++w) v += tpart[w * 16 * DL_MAXJTU + lane];
+                __hip_atomic_store(tx + slice * 16 * DL_MAXJTU + lane,
+                                   ((unsigned long long)tag << 32) | (unsigned long long)__float_as_uint(v), __ATOMIC_RELAXED,
+                                   __HIP_MEMORY_SCOPE_AGENT);
+            }
+        }
+    }
+    // All eight slices of this call: the words are asked for before the contraction and looked at
+    // behind it, by when they have long been written; should one not carry the call's tag yet, the
+    // wavefront polls (bounded; the producers wait for nobody).
+    constexpr int NE = (DL_SLICES * RPU + 63) / 64;
+    unsigned long long ent[NE > 0 ? NE : 1];
+    auto poll = [&](unsigned tag) -> bool {
+        const unsigned long long* tx = reinterpret_cast<const unsigned long long*>(a.sync + 256);
+        bool ok = true;
+#pragma unroll
+        for (int i = 0; i < NE; ++i) {
+            const int idx = lane + 64 * i, sl = idx / (RPU > 0 ? RPU : 1), j = idx - sl * RPU;
+            ent[i] = (unsigned long long)tag << 32;
+            if (sl < DL_SLICES) ent[i] = __hip_atomic_load(tx + sl * 16 * DL_MAXJTU + j, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            ok = ok && (unsigned)(ent[i] >> 32) == tag;
+        }
+        return __all(ok);
+    };
 
     if (rotates) {
         // ---- operands landed: every rotation wavefront waits for its own asynchronous copies, then
         // for the other rotation wavefronts (the T wavefronts go on by themselves)
         __builtin_amdgcn_s_waitcnt(0);
         meet(cnt, STRIPS);
-        if (!BITS_VIA_LDS) request_bits(0);
+        request_bits(0);
         // ============================================================ rotation, stage 1: Z = V R2
         v4f z[AT];
 #pragma unroll
@@ -399,30 +445,6 @@ __global__ __launch_bounds__(DL_THREADS) void decode_layer_kernel(const uint16_t
         lsum = dl_wave_sum(lsum);
         if (lane == 0) reinterpret_cast<int*>(red)[4 + wave] = lsum;
         arrive(cnt + 2);                               // my codes and my code sum are in LDS
-    } else if (projects) {
-        // ============================================================ T = x U, my quarter of K
-        v4f tacc[JTU > 0 ? JTU : 1];
-#pragma unroll
-        for (int jt = 0; jt < (JTU > 0 ? JTU : 1); ++jt) tacc[jt] = v4f{0.f, 0.f, 0.f, 0.f};
-        const char* xa = xh + ((wave - 4) * S + 8 * lg) * 2;
-#pragma unroll
-        for (int i0 = 0; i0 < NKS; i0 += TD) {
-#pragma unroll
-            for (int d = 0; d < TD; ++d) {
-                const int ks = (ks_first + i0 + d) & (NKS - 1);
-                const v8h av = __builtin_bit_cast(v8h, *reinterpret_cast<const v4i*>(xa + ks * 64));
-#pragma unroll
-                for (int jt = 0; jt < JTU; ++jt) {
-                    tacc[jt] = __builtin_amdgcn_mfma_f32_16x16x32_f16(av, __builtin_bit_cast(v8h, uring[d][jt]), tacc[jt], 0, 0, 0);
-                    if (i0 + d + TD < NKS) uring[d][jt] = u_load(i0 + d + TD, jt);
-                }
-            }
-        }
-        // every row of the A operand was the token: row 0 of the result (lanes 0..15) is T's slice
-        if (lane < 16) {
-#pragma unroll
-            for (int jt = 0; jt < JTU; ++jt) tpart[(wave - 4) * 16 * DL_MAXJTU + 16 * jt + lane] = tacc[jt][0] * t_unscale;
-        }
     }
 
     // ================================================================ binary GEMM on the workgroup's tiles
@@ -441,16 +463,17 @@ __global__ __launch_bounds__(DL_THREADS) void decode_layer_kernel(const uint16_t
             }
             b[i][7] = v4i{dl_neg_bytes(b[i][7].x), dl_neg_bytes(b[i][7].y), dl_neg_bytes(b[i][7].z), dl_neg_bytes(b[i][7].w)};
         }
-        if (BITS_VIA_LDS) {
-            await(cnt + 3, 4);                         // the first round's sign bits are in LDS
-#pragma unroll
-            for (int t = 0; t < DL_TPW; ++t)
-#pragma unroll
-                for (int i = 0; i < CPW; ++i) {
-                    const int c = wave + i * GW;
-                    if (c < CHUNKS) wq[t][i] = *reinterpret_cast<const v4i*>(wb + (t * CHUNKS + c) * 1024 + lane * 16);
-                }
-        }
+        bool t_here = false;
+        const unsigned tag = JTU > 0 && wave == 4 ? reinterpret_cast<const unsigned*>(red)[14] + 1u : 0u;
+        if (JTU > 0 && wave == 4) t_here = poll(tag);
+        // workgroup 0 moves the epoch on once every workgroup has read it: its last wavefront asks
+        // for the eight arrival counts here and looks at them behind the contraction
+        const bool bumps = JTU > 0 && wave == 7 && blk == 0;
+        unsigned seen = 0;
+        auto count_arrivals = [&]() {
+            seen = lane < 8 ? __hip_atomic_load(a.sync + 16 * (1 + lane), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) : 0u;
+        };
+        if (bumps) count_arrivals();
         for (int rd = 0; rd < a.rounds; ++rd) {
             int* prt = part + rd * DL_TPW * 8 * 16;
             // the round's tiles (all DL_TPW of them, except in the last round) side by side: per tile
@@ -501,6 +524,35 @@ __global__ __launch_bounds__(DL_THREADS) void decode_layer_kernel(const uint16_t
             // next round's sign bits into the same registers
             if (rd + 1 < a.rounds) request_bits(rd + 1);
         }
+        if (bumps) {
+            for (int spin = 0; spin < DL_SPIN_LIMIT; ++spin) {
+                if ((unsigned)dl_wave_sum((int)seen) == (unsigned)grid) break;
+                __builtin_amdgcn_s_sleep(8);
+                count_arrivals();
+            }
+            // (all have read it: the counts go back to zero, the epoch moves on; the next launch
+            // sees both, being ordered behind this one)
+            if (lane < 8) __hip_atomic_store(a.sync + 16 * (1 + lane), 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            if (lane == 0) __hip_atomic_store(a.sync, epoch + 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        }
+        if (JTU > 0 && wave == 4) {
+            for (int spin = 0; !t_here && spin < DL_SPIN_LIMIT; ++spin) {
+                __builtin_amdgcn_s_sleep(8);
+                t_here = poll(tag);
+            }
+#pragma unroll
+            for (int i = 0; i < NE; ++i) {
+                const int idx = lane + 64 * i;
+                if (idx < DL_SLICES * RPU) txl[idx] = __uint_as_float((unsigned)ent[i]);
+            }
+            // T: the slices in slice order
+            if (lane < RPU) {
+                float v = 0.0f;
+#pragma unroll
+                for (int sl = 0; sl < DL_SLICES; ++sl) v += txl[sl * RPU + lane];
+                txl[DL_SLICES * 16 * DL_MAXJTU + lane] = v;
+            }
+        }
     }
 
     // ---- partial sums of all rounds, code sums and partial T are in LDS
@@ -519,9 +571,9 @@ __global__ __launch_bounds__(DL_THREADS) void decode_layer_kernel(const uint16_t
         for (int i = tid; i < (K >> 4); i += DL_THREADS)
             reinterpret_cast<uint4*>(a.q)[i] = reinterpret_cast<const uint4*>(codes)[i];
     }
-    // ================================================================ epilogue: wavefront e finishes round e
-    if (wave < a.rounds) {
-        const int rd = wave;
+    // ================================================================ epilogue: every wavefront its round
+    if (my_round < a.rounds) {
+        const int rd = my_round;
         const float st = amax / 31.0f;
         float* tf = tfin + wave * 16 * DL_MAXJTV;
         // T as the epilogue reads it: the PSP columns, then the column a row shift adds
@@ -529,8 +581,7 @@ __global__ __launch_bounds__(DL_THREADS) void decode_layer_kernel(const uint16_t
             for (int j = lane; j < 16 * JTV; j += 64) {
                 float tv = 0.0f;
                 if (j < a.ru) {
-#pragma unroll
-                    for (int s4 = 0; s4 < 4; ++s4) tv += tpart[s4 * 16 * DL_MAXJTU + j];
+                    tv = txl[DL_SLICES * 16 * DL_MAXJTU + j];
                 } else if (a.shift && j == a.ru) {
                     tv = st * (float)qs;
                 }
@@ -574,20 +625,23 @@ __global__ __launch_bounds__(DL_THREADS) void decode_layer_kernel(const uint16_t
 
 size_t dl_lds_bytes(int K, int n1, int n2, bool with_t) {
     const int at = n1 >> 4, ch2 = n1 >> 5;
-    return (size_t)2 * K + (size_t)ch2 * 2 * at * 1024 + K + 2 * K +
-           (16 + 4 * 16 * DL_MAXJTU + 8 * 16 * DL_MAXJTV) * sizeof(float) + DL_MAXROUNDS * DL_TPW * 8 * 16 * sizeof(int) +
-           (with_t ? (size_t)DL_TPW * (K / 512) * 1024 : 0);
+    (void)with_t;
+    return (size_t)2 * K + (size_t)ch2 * 2 * at * 1024 + K + 2 * (K / DL_SLICES) +
+           (16 + 4 * 16 * DL_MAXJTU + (DL_SLICES + 1) * 16 * DL_MAXJTU + 8 * 16 * DL_MAXJTV) * sizeof(float) +
+           DL_MAXROUNDS * DL_TPW * 8 * 16 * sizeof(int);
 }
 
 }  // namespace
 
+
 // Single-launch decode layer.  *done = false (and nothing launched) when the shape is outside what
 // the kernel takes: one bf16 token; Kronecker factors of 32 or 64 (K = 1024 .. 4096, which covers
-// the 4096-wide models' attention and up/gate projections); PSP rank up to 64; symmetric codes,
-// with or without the row shift.
+// the 4096-wide models' attention and up/gate projections); PSP rank up to 64 (and then at least
+// 512 output channels, so that the projection has its 32 producers); symmetric codes, with or
+// without the row shift.  dws_head: the first BWLA_WS_HEAD bytes of the caller's scratch.
 hipError_t bwla_launch_decode_layer(const bwla_layer_t* L, const void* dX, int xdtype, int64_t M, int8_t* dq,
-                                    float* dscale, int32_t* dqsum, float* dT, float* dY, int32_t* dacc,
-                                    hipStream_t st, bool* done) {
+                                    float* dscale, int32_t* dqsum, float* dT, void* dws_head, float* dY,
+                                    int32_t* dacc, hipStream_t st, bool* done) {
     *done = false;
     const int n1 = L->n1, n2 = L->n2;
     if (M != 1 || xdtype != BWLA_X_BF16) return hipSuccess;
@@ -614,6 +668,10 @@ hipError_t bwla_launch_decode_layer(const bwla_layer_t* L, const void* dX, int x
     a.N = (int)L->N; a.r = r; a.ru = ru; a.row_tiles = row_tiles;
     a.rounds = (row_tiles + DL_TPW * grid - 1) / (DL_TPW * grid);
     if (a.rounds > DL_MAXROUNDS) return hipSuccess;
+    // the shared projection needs its producers (the first DL_PRODUCERS workgroups) and the exchange
+    // area at the head of the scratch
+    if (jtu > 0 && (grid < DL_PRODUCERS || dws_head == nullptr)) return hipSuccess;
+    a.sync = (unsigned*)dws_head;
     a.shift = (L->mode & BWLA_MODE_ROW_SHIFT) ? 1 : 0;
     const size_t lds = dl_lds_bytes(K, n1, n2, jtu > 0);
     auto launch = [&](auto kern) -> hipError_t {

@@ -19,6 +19,7 @@ from paper_2605_00422_amd import binding as B
 from paper_2605_00422_amd import inputs as syn
 
 DEV = "cuda:0"
+WS_HEAD = 1024 + 8 * 64 * 8     # exchange area of the single-launch decode kernel at the head of every scratch
 
 
 def to_dev(a, dtype=None):
@@ -111,7 +112,7 @@ def run_case(cfg: syn.LayerConfig, rows=None, centered: bool = False, act_bits: 
     torch.cuda.synchronize()
     # the scratch starts with the projection's arrival counters (if there is a projection)
     ncnt = (((cfg.M + 15) // 16) * 4 + 255) // 256 * 256 if cfg.r > 0 else 0   # (cfg.r: the projection's rank)
-    assert int(torch.count_nonzero(act.ws[:ncnt])) == 0, "arrival counters not restored to zero"
+    assert int(torch.count_nonzero(act.ws[WS_HEAD:WS_HEAD + ncnt])) == 0, "arrival counters not restored to zero"
 
     # the one-call entry point (a single launch for one bf16 token without low-rank part, else the
     # two calls).  It may rotate with another kernel than bwla_rotate_quant picks for the shape,
@@ -127,7 +128,8 @@ def run_case(cfg: syn.LayerConfig, rows=None, centered: bool = False, act_bits: 
         for rep, (Xi, with_acc) in enumerate(((X2, False), (X, True), (X, False))):
             B.decode_forward(layer, Xi, act1, Y1, acc1 if with_acc else None)
             torch.cuda.synchronize()
-            assert int(torch.count_nonzero(act1.ws[:ncnt])) == 0, f"call {rep}: counters not restored to zero"
+            assert int(torch.count_nonzero(act1.ws[WS_HEAD:WS_HEAD + ncnt])) == 0, f"call {rep}: counters not restored to zero"
+            assert int(torch.count_nonzero(act1.ws[64:1024])) == 0, f"call {rep}: arrival counts of the exchange area not restored"
             if rep == 1:
                 kept = (act1.q.clone(), act1.scale.clone(), act1.qsum.clone(), Y1.clone())
         assert torch.equal(act1.q, kept[0]) and torch.equal(act1.scale, kept[1]) and torch.equal(act1.qsum, kept[2])
