@@ -4,9 +4,12 @@
     python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload NAME] [--no-extra]
 
 A step is one pass of the whole hot path over one batch of synthetic activations: one
-bwla_rotate_quant call and one bwla_linear_forward call.  Successive steps use different
-packed copies of the layer (enough copies to exceed the 256 MB last-level cache), as the layers
-of a model are all distinct, so the sign bits always stream from HBM.  Prints one JSON line.
+bwla_decode_forward call (rotation, codes, binary GEMM, PSP branch, dequantization: one kernel
+launch where the library has a single-launch kernel for the shape, else the launches of
+bwla_rotate_quant and bwla_linear_forward back to back).  Successive steps use different packed
+copies of the layer, 512 MB of them, as the layers of a model are all distinct; and every timed
+region starts behind a pass over a 768 MB buffer, so whatever the number of steps the sign bits
+stream from HBM, not from the 256 MB last-level cache.  Prints one JSON line.
 """
 from __future__ import annotations
 
@@ -25,15 +28,26 @@ if ROOT not in sys.path:
 HBM_PEAK_GBPS = 8000.0        # MI355X HBM3E
 INT8_PEAK_TOPS = 5000.0       # dense INT8 MFMA
 CACHE_DEFEAT_BYTES = 512 << 20
+FLUSH_BYTES = 768 << 20
+TRAFFIC_FILE = os.path.join(ROOT, "profiles", "pmc_hbm_traffic.txt")
 
-# HBM bytes per bwla_linear_forward launch measured with rocprofv3 --pmc (FETCH_SIZE and
-# WRITE_SIZE in separate runs, each scaled by what the same counter reads for a plain device
-# copy of known size in the same run); the runs and their figures are summarised in
-# profiles/pmc_hbm_traffic_linear_forward.txt.  None = not measured for that workload.
-MEASURED_TRAFFIC_BYTES = {
-    "cfg1_decode7b": 6729055,                 # fetch 6.69 MB + write 0.04 MB (algorithmic 6.41 MB)
-    "cfg3_qwen32b_down_m2048": 231902860,     # fetch 190.0 MB (8 XCDs x bits + codes) + write 41.9 MB
-}
+
+def measured_traffic():
+    """HBM bytes per launch measured with rocprofv3 --pmc (FETCH_SIZE and WRITE_SIZE in separate
+    runs, each scaled by what the same counter reads for a plain device copy of known size in the
+    same run), read from the tracked summary of those runs: its lines
+        traffic <workload> <kernel> <fetch bytes> <write bytes>
+    Returns {(workload, kernel): bytes}; empty when the summary is missing."""
+    out = {}
+    try:
+        with open(TRAFFIC_FILE) as f:
+            for ln in f:
+                p = ln.split()
+                if len(p) == 5 and p[0] == "traffic":
+                    out[(p[1], p[2])] = int(p[3]) + int(p[4])
+    except OSError:
+        pass
+    return out
 
 
 def linear_forward_bytes(cfg) -> int:
@@ -51,8 +65,25 @@ def rotate_quant_bytes(cfg) -> int:
         + 8 * cfg.M + 4 * cfg.M * cfg.r
 
 
+def layer_bytes(cfg) -> int:
+    """Algorithmic bytes of the whole layer: everything either call reads or writes once."""
+    return linear_forward_bytes(cfg) + rotate_quant_bytes(cfg)
+
+
 def gemm_ops(cfg) -> int:
     return 2 * cfg.M * cfg.N * cfg.K
+
+
+_flush_buf = None
+
+
+def flush_caches(torch):
+    """One read-modify-write pass over 768 MB on the current stream: afterwards neither the L2s
+    nor the 256 MB last-level cache hold anything of the layers."""
+    global _flush_buf
+    if _flush_buf is None:
+        _flush_buf = torch.zeros(FLUSH_BYTES // 4, dtype=torch.int32, device="cuda:0")
+    _flush_buf.add_(1)
 
 
 class Workload:
@@ -77,7 +108,7 @@ class Workload:
         torch.cuda.synchronize()
         nbytes = first.blob.numel()
         if copies is None:
-            copies = max(2, min(96, math.ceil(CACHE_DEFEAT_BYTES / nbytes)))
+            copies = max(2, math.ceil(CACHE_DEFEAT_BYTES / nbytes))
         self.layers = [first]
         for _ in range(copies - 1):
             blob = first.blob.clone()
@@ -88,12 +119,18 @@ class Workload:
         self.X = X.to(torch.bfloat16) if cfg.x_dtype == "bf16" else X
         self.act = B.Activations(first, cfg.M)
         self.Y = torch.empty((cfg.M, cfg.N), dtype=torch.float32, device=dev)
+        # 1 where bwla_decode_forward has a single-launch kernel for the shape (6-bit codes only:
+        # the call takes no code width)
+        self.launches = B.decode_forward_launches(first, cfg.M, cfg.x_dtype == "bf16") if act_bits == 6 else 2
         torch.cuda.synchronize()
 
     def step(self, i):
         L = self.layers[i % len(self.layers)]
-        self.B.rotate_quant(L, self.X, self.act, self.act_bits)
-        self.B.linear_forward(L, self.act, self.Y)
+        if self.act_bits == 6:
+            self.B.decode_forward(L, self.X, self.act, self.Y)
+        else:
+            self.B.rotate_quant(L, self.X, self.act, self.act_bits)
+            self.B.linear_forward(L, self.act, self.Y)
 
     def only_rotate(self, i):
         self.B.rotate_quant(self.layers[i % len(self.layers)], self.X, self.act, self.act_bits)
@@ -114,6 +151,7 @@ class Workload:
         torch = self.torch
         for i in range(warmup):
             fn(i)
+        flush_caches(torch)
         torch.cuda.synchronize()
         e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
         e0.record()
@@ -123,9 +161,10 @@ class Workload:
         torch.cuda.synchronize()
         return e0.elapsed_time(e1) / steps
 
-    def time_graph(self, fn, steps, warmup):
+    def time_graph(self, fn, steps, warmup, replays=5):
         """The same K calls captured once into a HIP graph and replayed: per-call milliseconds
-        without host launch overhead (how a decode loop would be deployed)."""
+        without host launch overhead (how a decode loop would be deployed).  `replays` timed
+        replays, each behind a cache flush; returns (median, minimum)."""
         torch = self.torch
         for i in range(max(warmup, 3)):
             fn(i)
@@ -139,12 +178,17 @@ class Workload:
         torch.cuda.synchronize()
         g.replay()
         torch.cuda.synchronize()
-        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-        e0.record()
-        g.replay()
-        e1.record()
-        torch.cuda.synchronize()
-        return e0.elapsed_time(e1) / steps
+        ms = []
+        for _ in range(replays):
+            flush_caches(torch)
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            g.replay()
+            e1.record()
+            torch.cuda.synchronize()
+            ms.append(e0.elapsed_time(e1) / steps)
+        ms.sort()
+        return ms[len(ms) // 2], ms[0]
 
 
 def measure(cfg, steps, warmup, use_graph=True, centered=False, act_bits=6, asym=False):
@@ -152,7 +196,7 @@ def measure(cfg, steps, warmup, use_graph=True, centered=False, act_bits=6, asym
     out = {"workload": cfg.name + ("+row_shift" if centered else "") + (f"+a{act_bits}" if act_bits != 6 else "")
            + ("+asym" if asym else ""),
            "M": cfg.M, "K": cfg.K, "N": cfg.N, "r": cfg.r,
-           "kron": f"{cfg.n1}x{cfg.n2}", "layer_copies": len(w.layers)}
+           "kron": f"{cfg.n1}x{cfg.n2}", "layer_copies": len(w.layers), "launches_per_layer": w.launches}
     ms_step = w.time_loop(w.step, steps, warmup)
     ms_fwd = w.time_loop(w.only_forward, steps, warmup)
     ms_rot = w.time_loop(w.only_rotate, steps, warmup)
@@ -160,31 +204,117 @@ def measure(cfg, steps, warmup, use_graph=True, centered=False, act_bits=6, asym
                      "us_rotate_quant": ms_rot * 1e3}
     if use_graph:
         try:
-            gs = w.time_graph(w.step, steps, warmup)
-            gf = w.time_graph(w.only_forward, steps, warmup)
-            gr = w.time_graph(w.only_rotate, steps, warmup)
-            out["graph"] = {"us_per_layer": gs * 1e3, "us_linear_forward": gf * 1e3, "us_rotate_quant": gr * 1e3}
+            gs, gs_min = w.time_graph(w.step, steps, warmup)
+            gf, _ = w.time_graph(w.only_forward, steps, warmup)
+            gr, _ = w.time_graph(w.only_rotate, steps, warmup)
+            out["graph"] = {"us_per_layer": gs * 1e3, "us_per_layer_min": gs_min * 1e3,
+                            "us_linear_forward": gf * 1e3, "us_rotate_quant": gr * 1e3}
             if cfg.name.startswith("cfg1_7b_gateup") and cfg.M <= 16:
-                out["graph"]["us_linear_forward_gated"] = w.time_graph(w.only_forward_gated, steps, warmup) * 1e3
+                out["graph"]["us_linear_forward_gated"] = w.time_graph(w.only_forward_gated, steps, warmup)[0] * 1e3
         except Exception as ex:  # graph capture is an optimisation of the launch path only
             out["graph"] = {"error": repr(ex)[:200]}
     return w, out
 
 
-def roofline_for(cfg, us_forward):
-    """Roofline of the dominant kernel (the binary GEMM inside bwla_linear_forward)."""
-    hbm_t = linear_forward_bytes(cfg) / (HBM_PEAK_GBPS * 1e9)
-    mfma_t = gemm_ops(cfg) / (INT8_PEAK_TOPS * 1e12)
-    t = us_forward * 1e-6
-    if hbm_t >= mfma_t:
-        a = linear_forward_bytes(cfg) / t / 1e9
-        return {"bound": "hbm", "achieved": a, "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": a / HBM_PEAK_GBPS,
-                "traffic": MEASURED_TRAFFIC_BYTES.get(cfg.name), "kernel": "bwla_linear_forward",
-                "bytes_per_launch": linear_forward_bytes(cfg), "us_per_launch": us_forward}
+def best_of(res):
+    """The faster of the stream loop and the graph replay (median) of the whole layer."""
+    best, mode = res["stream"], "stream"
+    if "graph" in res and "us_per_layer" in res["graph"] and res["graph"]["us_per_layer"] < best["us_per_layer"]:
+        best, mode = res["graph"], "graph"
+    return best, mode
+
+
+class Peaks:
+    """What this GPU reaches on a pure streaming read of a given size and on a loop of INT8 MFMAs
+    only (the library's two measurement kernels), timed like the workloads: events on the
+    launch stream around a graph replay, every read launch on a window of a 768 MB buffer that the launches before it
+    did not touch."""
+
+    def __init__(self, torch, B):
+        self.torch, self.B = torch, B
+        flush_caches(torch)
+        self.sink = torch.zeros(16384, dtype=torch.int32, device="cuda:0")
+        self._read = {}
+        self._mfma = None
+
+    def hbm_read_gbps(self, nbytes, launches=40):
+        nbytes = max(4096, min(int(nbytes), FLUSH_BYTES // 3) // 4096 * 4096)
+        if nbytes in self._read:
+            return self._read[nbytes]
+        torch = self.torch
+        buf = _flush_buf.view(torch.uint8)
+        nwin = FLUSH_BYTES // nbytes
+        launches = max(1, min(launches, nwin - 1))      # the buffer's tail is what the flush wrote last
+        wins = [buf[i * nbytes:(i + 1) * nbytes] for i in range(launches)]
+        self.B.probe_hbm_read(wins[0], self.sink)
+        torch.cuda.synchronize()
+        # replayed from a graph like the workloads, so that host launch overhead is not in the figure
+        g = torch.cuda.CUDAGraph()
+        st = torch.cuda.Stream()
+        with torch.cuda.stream(st):
+            with torch.cuda.graph(g, stream=st):
+                for wv in wins:
+                    self.B.probe_hbm_read(wv, self.sink)
+        torch.cuda.synchronize()
+        best = 0.0
+        for _ in range(3):
+            flush_caches(torch)
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            g.replay()
+            e1.record()
+            torch.cuda.synchronize()
+            best = max(best, nbytes * launches / (e0.elapsed_time(e1) * 1e-3) / 1e9)
+        self._read[nbytes] = best
+        return best
+
+    def mfma_int8_tops(self):
+        if self._mfma is None:
+            torch = self.torch
+            self.B.probe_mfma_int8(1000, self.sink)
+            torch.cuda.synchronize()
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            ops = self.B.probe_mfma_int8(20000, self.sink)
+            e1.record()
+            torch.cuda.synchronize()
+            self._mfma = ops / (e0.elapsed_time(e1) * 1e-3) / 1e12
+        return self._mfma
+
+
+def roofline_for(cfg, launches, us_layer, us_forward, peaks, traffic, workload=None):
+    """Roofline of the dominant kernel: the single-launch decode kernel where it serves the layer
+    (then the kernel is the layer), else the binary GEMM inside bwla_linear_forward; with the
+    whole layer (all launches, all bytes or operations) against the same peak beside it."""
+    workload = workload or cfg.name
+    hbm_bound = layer_bytes(cfg) / (HBM_PEAK_GBPS * 1e9) >= gemm_ops(cfg) / (INT8_PEAK_TOPS * 1e12)
+    if launches == 1:
+        kernel, t, nbytes = "decode_layer_kernel", us_layer * 1e-6, layer_bytes(cfg)
+    else:
+        kernel = "gemm_decode_bs_kernel" if cfg.M <= 16 else "gemm_prefill_direct_kernel"
+        t, nbytes = us_forward * 1e-6, linear_forward_bytes(cfg)
+    tl = us_layer * 1e-6
+    if hbm_bound:
+        a = nbytes / t / 1e9
+        pm = peaks.hbm_read_gbps(nbytes) if peaks else None
+        r = {"bound": "hbm", "achieved": a, "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": a / HBM_PEAK_GBPS,
+             "traffic": traffic.get((workload, kernel)), "kernel": kernel, "bytes_per_launch": nbytes,
+             "us_per_launch": t * 1e6,
+             "peak_measured": pm, "frac_of_measured": (a / pm if pm else None),
+             "peak_measured_what": "one streaming-read launch of the same number of bytes, cold",
+             "peak_measured_large": (peaks.hbm_read_gbps(FLUSH_BYTES // 3) if peaks else None),
+             "layer": {"achieved": layer_bytes(cfg) / tl / 1e9, "frac": layer_bytes(cfg) / tl / 1e9 / HBM_PEAK_GBPS,
+                       "bytes": layer_bytes(cfg), "us": us_layer, "launches": launches}}
+        return r
     a = gemm_ops(cfg) / t / 1e12
+    pm = peaks.mfma_int8_tops() if peaks else None
     return {"bound": "mfma", "achieved": a, "peak": INT8_PEAK_TOPS, "unit": "TOP/s", "frac": a / INT8_PEAK_TOPS,
-            "traffic": MEASURED_TRAFFIC_BYTES.get(cfg.name), "kernel": "bwla_linear_forward",
-            "ops_per_launch": gemm_ops(cfg), "us_per_launch": us_forward}
+            "traffic": traffic.get((workload, kernel)), "kernel": kernel, "ops_per_launch": gemm_ops(cfg),
+            "us_per_launch": t * 1e6,
+            "peak_measured": pm, "frac_of_measured": (a / pm if pm else None),
+            "peak_measured_what": "a launch of INT8 16x16x64 MFMAs on register operands only",
+            "layer": {"achieved": gemm_ops(cfg) / tl / 1e12, "frac": gemm_ops(cfg) / tl / 1e12 / INT8_PEAK_TOPS,
+                      "ops": gemm_ops(cfg), "us": us_layer, "launches": launches}}
 
 
 def side_kernel_report(cfg, us_rotate):
@@ -240,6 +370,7 @@ def main():
     ap.add_argument("--no-extra", action="store_true", help="skip the other configurations")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle baseline")
     ap.add_argument("--no-graph", action="store_true")
+    ap.add_argument("--no-peaks", action="store_true", help="skip the measured-ceiling launches")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run three plain 256 MiB device copies (counter calibration under rocprofv3 --pmc)")
     args = ap.parse_args()
@@ -273,27 +404,27 @@ def main():
         del src, dst
         torch.cuda.empty_cache()
 
+    traffic = measured_traffic()
+    peaks = None if args.no_peaks else Peaks(torch, B)
     w, res = measure(cfg, args.steps, args.warmup, not args.no_graph)
-    best = res["stream"]
-    mode = "stream"
-    if "graph" in res and "us_per_layer" in res["graph"] and res["graph"]["us_per_layer"] < best["us_per_layer"]:
-        best, mode = res["graph"], "graph"
+    best, mode = best_of(res)
     us_layer = best["us_per_layer"]
     us_fwd = best["us_linear_forward"]
-    roof = roofline_for(cfg, us_fwd)
+    roof = roofline_for(cfg, w.launches, us_layer, us_fwd, peaks, traffic)
     line = {
         "metric": "us/layer, W1A6 linear forward (rotate+quant, binary GEMM + PSP + dequant)",
         "value": us_layer, "unit": "us/layer", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": us_layer / 1e3, "higher_is_better": False, "scaling": "weak", "vs_baseline": None,
         "dtype": "int8",
-        "dtype_detail": "int8 codes x 1-bit weights -> int32 on INT8 MFMA; fp32 rotation, bf16/fp16-split MFMA side products, fp32 epilogue",
+        "dtype_detail": "int8 codes x 1-bit weights -> int32 on INT8 MFMA; rotation on bf16/fp16-split MFMA with fp32 accumulation, fp32 epilogue",
         "data": "synthetic",
         "config": {"workload": cfg.name, "M": cfg.M, "K": cfg.K, "N": cfg.N, "r": cfg.r,
                    "kron": f"{cfg.n1}x{cfg.n2}", "x_dtype": cfg.x_dtype, "launch_mode": mode,
-                   "layer_copies": res["layer_copies"]},
+                   "launches_per_layer": w.launches, "layer_copies": res["layer_copies"],
+                   "cache_flush_bytes": FLUSH_BYTES},
         "effective_tops": gemm_ops(cfg) / (us_layer * 1e-6) / 1e12,
-        "hbm_gbps_layer": (linear_forward_bytes(cfg) + rotate_quant_bytes(cfg)) / (us_layer * 1e-6) / 1e9,
-        "us_linear_forward": us_fwd, "us_rotate_quant": best["us_rotate_quant"],
+        "hbm_gbps_layer": layer_bytes(cfg) / (us_layer * 1e-6) / 1e9,
+        "us_two_calls": {"us_linear_forward": us_fwd, "us_rotate_quant": best["us_rotate_quant"]},
         "timings": {k: res[k] for k in ("stream", "graph") if k in res},
         "roofline": roof,
         "side_kernels": [side_kernel_report(cfg, best["us_rotate_quant"])],
@@ -305,8 +436,10 @@ def main():
 
     if not args.no_extra:
         extra = []
-        names = ["cfg1_7b_q_m1", "cfg1_7b_down_m1", "cfg1_7b_qkv_m1", "cfg1_7b_gateup_m1", "cfg2_qwen32b_up_m16", "cfg3_qwen32b_down_m2048",
-                 "cfg4_70b_gate_m1", "cfg4_70b_down_m1", "cfg4_70b_q_m64", "cfg4_70b_q_m4096"]
+        names = ["cfg1_7b_q_m1", "cfg1_7b_down_m1", "cfg1_7b_qkv_m1", "cfg1_7b_gateup_m1", "cfg2_qwen32b_up_m16",
+                 "cfg3_qwen32b_down_m2048", "cfg4_70b_gate_m1", "cfg4_70b_down_m1", "cfg4_70b_q_m64",
+                 "cfg4_70b_gate_m64", "cfg4_70b_down_m64", "cfg4_70b_q_m4096", "cfg4_70b_gate_m4096",
+                 "cfg4_70b_down_m4096"]
         # (name, layer binarized with the row shift: the shift term rides as one more low-rank column)
         # and 8-bit activation codes, the width of the paper's speed run: same kernels, same bytes)
         # and per-token asymmetric codes with the row shift, the paper's own setting: three more columns)
@@ -317,26 +450,28 @@ def main():
             if nm == cfg.name and not shift and bits == 6 and not asym:
                 continue
             c = all_cfgs[nm]
-            st = max(20, min(args.steps, 200 if c.M <= 64 else 20))
+            st = max(10, min(args.steps, 200 if c.M <= 64 else (20 if c.M <= 2048 else 10)))
             ww, r = measure(c, st, max(3, min(args.warmup, st // 4)), not args.no_graph, centered=shift,
                             act_bits=bits, asym=asym)
             if shift or asym:
                 c = dataclasses.replace(c, r=c.r + int(shift) + 2 * int(asym))   # bytes of the extra columns of V and T
-            b = r["stream"]
-            if "graph" in r and "us_per_layer" in r["graph"] and r["graph"]["us_per_layer"] < b["us_per_layer"]:
-                b = r["graph"]
-            r["roofline"] = roofline_for(c, b["us_linear_forward"])
+            b, _ = best_of(r)
+            r["roofline"] = roofline_for(c, ww.launches, b["us_per_layer"], b["us_linear_forward"], peaks, traffic,
+                                         workload=r["workload"])
             r["side_kernels"] = [side_kernel_report(c, b["us_rotate_quant"])]
             r["effective_tops"] = gemm_ops(c) / (b["us_per_layer"] * 1e-6) / 1e12
             extra.append(r)
             del ww
             torch.cuda.empty_cache()
         line["other_workloads"] = extra
+        # the prefill shape's roofline (INT8 MFMA bound) beside the headline's (HBM bound)
+        pre = [e for e in extra if e["workload"] == "cfg3_qwen32b_down_m2048"]
+        if pre:
+            line["roofline_prefill"] = dict(pre[0]["roofline"], workload=pre[0]["workload"])
         # the seven linear layers of a 7B decoder block at one token: called one by one (q, k, v, o,
         # gate, up, down), and with the projections that read the same activations packed as one
         # layer (qkv, o, gate|up, down)
-        us = {e["workload"]: min(e[k]["us_per_layer"] for k in ("stream", "graph") if k in e and "us_per_layer" in e[k])
-              for e in extra}
+        us = {e["workload"]: best_of(e)[0]["us_per_layer"] for e in extra}
         us[cfg.name] = us_layer
         need = ("cfg1_7b_q_m1", "cfg1_decode7b", "cfg1_7b_down_m1", "cfg1_7b_qkv_m1", "cfg1_7b_gateup_m1")
         if all(k in us for k in need):

@@ -256,6 +256,13 @@ BWLA_API bwla_status_t bwla_decode_forward(const bwla_layer_t* layer, const void
                                   void* stream);
 
 /*
+ * Whether bwla_decode_forward serves (layer, xdtype, M) with its single-launch kernel: *launches
+ * (host) = 1, else 2 (bwla_rotate_quant's and bwla_linear_forward's launches back to back; the
+ * rotation of a long prefill may itself take more than one).  Launches nothing.
+ */
+BWLA_API bwla_status_t bwla_decode_forward_launches(const bwla_layer_t* layer, int xdtype, int64_t M, int* launches);
+
+/*
  * bwla_decode_forward for callers that cannot allocate device memory or hand over a workspace: code
  * under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same inputs,
  * outputs, results and errors as bwla_decode_forward, but the scratch (arrival counters and partial
@@ -297,6 +304,23 @@ BWLA_API bwla_status_t bwla_swiglu_workspace_size(const bwla_layer_t* layer, int
 BWLA_API bwla_status_t bwla_linear_forward_swiglu(const bwla_layer_t* layer, const int8_t* d_q, const float* d_scale,
                                          const int32_t* d_qsum, const float* d_T, int64_t M, void* d_H,
                                          void* d_ws, size_t ws_bytes, void* stream);
+
+/*
+ * Measurement aids for benchmarks, not steps of the method: the ceilings this GPU actually reaches,
+ * to quote the forward's kernels against next to the published peaks.
+ *   bwla_probe_hbm_read   one launch that reads `bytes` (a multiple of 16) from d_src (device,
+ *                         16-byte aligned) with coalesced 16-byte loads and writes a checksum per
+ *                         workgroup to d_sink (device, sink_bytes >= 32 KiB is always enough, else
+ *                         BWLA_ERR_BUFSIZE).  Bytes / launch duration is the read bandwidth a kernel of
+ *                         that size can reach.
+ *   bwla_probe_mfma_int8  one launch in which every wavefront issues 4 * iters independent 16x16x64
+ *                         INT8 MFMAs (1 <= iters <= 2^20) on register operands; *ops_out (host) gets
+ *                         the launch's operation count (2 per multiply-add), d_sink (device,
+ *                         >= 16 KiB) a checksum.
+ * Both enqueue on `stream`, own no memory, and return the usual codes.
+ */
+BWLA_API bwla_status_t bwla_probe_hbm_read(const void* d_src, size_t bytes, void* d_sink, size_t sink_bytes, void* stream);
+BWLA_API bwla_status_t bwla_probe_mfma_int8(int iters, void* d_sink, size_t sink_bytes, int64_t* ops_out, void* stream);
 
 #ifdef __cplusplus
 }

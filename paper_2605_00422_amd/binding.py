@@ -19,7 +19,8 @@ EXPORTS = ["bwla_status_string", "bwla_version", "bwla_kron_factor", "bwla_packe
            "bwla_unpack_signs", "bwla_psp_workspace_size", "bwla_rotate_quant", "bwla_code_sums",
            "bwla_linear_forward", "bwla_decode_forward", "bwla_packed_size_centered", "bwla_pack_weights_centered", "bwla_rotate_quant_bits",
            "bwla_packed_size_mode", "bwla_pack_weights_mode", "bwla_swiglu_workspace_size",
-           "bwla_linear_forward_swiglu", "bwla_decode_forward_static"]
+           "bwla_linear_forward_swiglu", "bwla_decode_forward_static", "bwla_probe_hbm_read",
+           "bwla_probe_mfma_int8", "bwla_decode_forward_launches"]
 
 
 class BwlaLayer(Structure):
@@ -73,6 +74,9 @@ def load() -> ctypes.CDLL:
                                         c_void_p, c_void_p, c_size_t, c_void_p, c_void_p, c_void_p]
     lib.bwla_decode_forward_static.argtypes = [POINTER(BwlaLayer), c_void_p, c_int, c_int64, c_void_p, c_void_p,
                                                c_void_p, c_void_p, c_void_p, c_void_p, c_void_p]
+    lib.bwla_decode_forward_launches.argtypes = [POINTER(BwlaLayer), c_int, c_int64, POINTER(c_int)]
+    lib.bwla_probe_hbm_read.argtypes = [c_void_p, c_size_t, c_void_p, c_size_t, c_void_p]
+    lib.bwla_probe_mfma_int8.argtypes = [c_int, c_void_p, c_size_t, POINTER(ctypes.c_int64), c_void_p]
     lib.bwla_swiglu_workspace_size.argtypes = [POINTER(BwlaLayer), c_int64, POINTER(c_size_t)]
     lib.bwla_linear_forward_swiglu.argtypes = [POINTER(BwlaLayer), c_void_p, c_void_p, c_void_p, c_void_p, c_int64,
                                                c_void_p, c_void_p, c_size_t, c_void_p]
@@ -219,6 +223,13 @@ def decode_forward(layer: PackedLayer, X, act: Activations, Y, acc=None):
     return Y
 
 
+def decode_forward_launches(layer: PackedLayer, M: int, bf16: bool = True) -> int:
+    n = c_int()
+    _check(load().bwla_decode_forward_launches(byref(layer.desc), BWLA_X_BF16 if bf16 else BWLA_X_F32, M, byref(n)),
+           "bwla_decode_forward_launches")
+    return n.value
+
+
 def decode_forward_static(layer: PackedLayer, X, act: Activations, Y, acc=None):
     """bwla_decode_forward with the library's own fixed scratch (act.ws is not used)."""
     import torch
@@ -229,6 +240,20 @@ def decode_forward_static(layer: PackedLayer, X, act: Activations, Y, acc=None):
                                              _ptr(act.qsum), _ptr(act.T), _ptr(Y), _ptr(acc), _stream()),
            "bwla_decode_forward_static")
     return Y
+
+
+def probe_hbm_read(src, sink) -> None:
+    """One streaming read of the whole tensor `src` (measurement aid)."""
+    _check(load().bwla_probe_hbm_read(_ptr(src), src.numel() * src.element_size(), _ptr(sink),
+                                      sink.numel() * sink.element_size(), _stream()), "bwla_probe_hbm_read")
+
+
+def probe_mfma_int8(iters: int, sink) -> int:
+    """One launch of back-to-back INT8 MFMAs (measurement aid); returns its operation count."""
+    ops = ctypes.c_int64()
+    _check(load().bwla_probe_mfma_int8(int(iters), _ptr(sink), sink.numel() * sink.element_size(), byref(ops),
+                                       _stream()), "bwla_probe_mfma_int8")
+    return ops.value
 
 
 def code_sums(q, qsum) -> None:

@@ -308,6 +308,21 @@ bwla_status_t bwla_decode_forward(const bwla_layer_t* layer, const void* d_X, in
     return bwla_linear_forward(layer, d_q, d_scale, d_qsum, d_T, M, d_Y, d_acc, stream);
 }
 
+bwla_status_t bwla_decode_forward_launches(const bwla_layer_t* layer, int xdtype, int64_t M, int* launches) {
+    bwla_status_t s = check_layer(layer);
+    if (s != BWLA_OK) return s;
+    if (!launches) return BWLA_ERR_NULL;
+    if (M <= 0 || M > (int64_t)1 << 24) return BWLA_ERR_SHAPE;
+    if (xdtype != BWLA_X_F32 && xdtype != BWLA_X_BF16) return BWLA_ERR_UNSUPPORTED;
+    bool one = false;
+    // (a scratch pointer that is not NULL, as a caller that sized it by bwla_psp_workspace_size passes)
+    if (bwla_launch_decode_layer(layer, layer->d_blob, xdtype, M, nullptr, nullptr, nullptr, nullptr, const_cast<void*>(layer->d_blob), nullptr,
+                                 nullptr, nullptr, &one, true) != hipSuccess)
+        return BWLA_ERR_HIP;
+    *launches = one ? 1 : 2;
+    return BWLA_OK;
+}
+
 bwla_status_t bwla_decode_forward_static(const bwla_layer_t* layer, const void* d_X, int xdtype, int64_t M,
                                          int8_t* d_q, float* d_scale, int32_t* d_qsum, float* d_T, float* d_Y,
                                          int32_t* d_acc, void* stream) {

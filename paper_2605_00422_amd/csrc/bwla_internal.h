@@ -130,7 +130,7 @@ hipError_t bwla_launch_code_sums(const int8_t* dq, int64_t M, int64_t K, int32_t
 // the whole layer in one launch for one bf16 token where the shape allows it (*done says whether)
 hipError_t bwla_launch_decode_layer(const bwla_layer_t* L, const void* dX, int xdtype, int64_t M, int8_t* dq,
                                     float* dscale, int32_t* dqsum, float* dT, void* dws_head, float* dY,
-                                    int32_t* dacc, hipStream_t st, bool* done);
+                                    int32_t* dacc, hipStream_t st, bool* done, bool dry_run = false);
 
 hipError_t bwla_launch_gemm_decode(const bwla_layer_t* L, const int8_t* dq, const float* dscale,
                                    const int32_t* dqsum, const float* dT, int64_t M, float* dY,

@@ -638,10 +638,11 @@ size_t dl_lds_bytes(int K, int n1, int n2, bool with_t) {
 // the kernel takes: one bf16 token; Kronecker factors of 32 or 64 (K = 1024 .. 4096, which covers
 // the 4096-wide models' attention and up/gate projections); PSP rank up to 64 (and then at least
 // 512 output channels, so that the projection has its 32 producers); symmetric codes, with or
-// without the row shift.  dws_head: the first BWLA_WS_HEAD bytes of the caller's scratch.
+// without the row shift.  dws_head: the first BWLA_WS_HEAD bytes of the caller's scratch.  With
+// dry_run nothing is launched and *done only says whether the kernel would serve the call.
 hipError_t bwla_launch_decode_layer(const bwla_layer_t* L, const void* dX, int xdtype, int64_t M, int8_t* dq,
                                     float* dscale, int32_t* dqsum, float* dT, void* dws_head, float* dY,
-                                    int32_t* dacc, hipStream_t st, bool* done) {
+                                    int32_t* dacc, hipStream_t st, bool* done, bool dry_run) {
     *done = false;
     const int n1 = L->n1, n2 = L->n2;
     if (M != 1 || xdtype != BWLA_X_BF16) return hipSuccess;
@@ -675,6 +676,7 @@ hipError_t bwla_launch_decode_layer(const bwla_layer_t* L, const void* dX, int x
     a.shift = (L->mode & BWLA_MODE_ROW_SHIFT) ? 1 : 0;
     const size_t lds = dl_lds_bytes(K, n1, n2, jtu > 0);
     auto launch = [&](auto kern) -> hipError_t {
+        if (dry_run) return hipSuccess;                    // the caller only asks whether the shape is served
         hipError_t e = bwla_ensure_lds((const void*)kern, lds);
         if (e != hipSuccess) return e;
         kern<<<dim3((unsigned)grid), dim3(DL_THREADS), lds, st>>>(pX, pR1h, pR2d, pbits, pUt, pV, palpha, a);

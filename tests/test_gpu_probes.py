@@ -1,0 +1,58 @@
+"""The library's measurement aids and the launch-count query on the GPU (run with -m gpu): the
+probes run, refuse what their header says they refuse, and the query names the single-launch
+kernel exactly for the shapes bwla_decode_forward's description lists."""
+import dataclasses
+
+import numpy as np
+import pytest
+
+torch = pytest.importorskip("torch")
+
+from paper_2605_00422_amd import inputs as syn  # noqa: E402
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module", autouse=True)
+def _need_gpu():
+    if not torch.cuda.is_available():
+        pytest.skip("no GPU")
+    from paper_2605_00422_amd import binding as B
+    B.load()
+
+
+def test_probes_run_and_refuse():
+    from paper_2605_00422_amd import binding as B
+    sink = torch.zeros(16384, dtype=torch.int32, device="cuda:0")
+    src = torch.arange(1 << 20, dtype=torch.int32, device="cuda:0")
+    B.probe_hbm_read(src, sink)
+    torch.cuda.synchronize()
+    # the xor of all words of the buffer, folded over the workgroups' checksums
+    got = 0
+    for w in sink.cpu().numpy().tolist():
+        got ^= w & 0xFFFFFFFF
+    x = src.cpu().numpy()
+    want = int(np.bitwise_xor.reduce(x.view(np.uint32)))
+    assert got == want
+    ops = B.probe_mfma_int8(100, sink)
+    torch.cuda.synchronize()
+    assert ops > 0 and ops % (2 * 16 * 16 * 64 * 4 * 100) == 0
+    with pytest.raises(B.BwlaError):
+        B.probe_hbm_read(src[:3], sink)            # 12 bytes: not a multiple of 16
+    with pytest.raises(B.BwlaError):
+        B.probe_mfma_int8(0, sink)
+    with pytest.raises(B.BwlaError):
+        B.probe_mfma_int8(10, sink[:16])           # sink too small
+
+
+def test_launch_count_query():
+    from paper_2605_00422_amd import binding as B
+    from parity_util import pack_on_gpu
+    small = dataclasses.replace(syn.CONFIGS["cfg1_decode7b"], N=1024)
+    layer = pack_on_gpu(syn.make_layer(small, with_activations=False))
+    assert B.decode_forward_launches(layer, 1, bf16=True) == 1
+    assert B.decode_forward_launches(layer, 1, bf16=False) == 2      # fp32 activations
+    assert B.decode_forward_launches(layer, 2, bf16=True) == 2       # more than one token
+    c0 = syn.CONFIGS["cfg0_tiny"]                                     # 16 x 32 factors
+    l0 = pack_on_gpu(syn.make_layer(c0, with_activations=False))
+    assert B.decode_forward_launches(l0, 1, bf16=True) == 2
