@@ -31,16 +31,24 @@ inline uint64_t bwla_factor_planes_bytes(int n) {
     return (uint64_t)3 * ((n + 15) & ~15) * ((n + 31) & ~31) * 2;
 }
 
-// factor planes of the single-launch decode kernel (0 when the pair is not one it takes): R2 in
-// three bf16 terms, (n2 / 16) strips x (n2 / 32) steps x 3 KiB; R1 in two fp16 terms, (n1 / 32)
-// steps x 2 x (n1 / 16) KiB
+// Factor planes in MFMA operand order (one contiguous KiB per operand), stored for factor pairs
+// that are multiples of 32 up to 160 (0 bytes otherwise), three parts:
+//   R2d  three bf16 terms of R2, (n2 / 16) strips x (n2 / 32) steps x 3 KiB: only for pairs of 32 or
+//        64, the single-launch decode kernel's
+//   R1h  two fp16 terms of 256 R1, (n1 / 32) steps x 2 x (n1 / 16) KiB
+//   R2h  two fp16 terms of 256 R2, (n2 / 16) strips x (n2 / 32) steps x 2 KiB
+inline bool bwla_planes_shape_ok(int n1, int n2) {
+    return n1 >= 32 && n2 >= 32 && n1 <= 160 && n2 <= 160 && (n1 & 31) == 0 && (n2 & 31) == 0;
+}
 inline uint64_t bwla_decode_planes_r2_bytes(int n1, int n2) {
     const bool ok = (n1 == 32 || n1 == 64) && (n2 == 32 || n2 == 64);
     return ok ? (uint64_t)(n2 / 16) * (n2 / 32) * 3 * 1024 : 0;
 }
+inline uint64_t bwla_planes_r1h_bytes(int n1) { return (uint64_t)(n1 / 32) * 2 * (n1 / 16) * 1024; }
+inline uint64_t bwla_planes_r2h_bytes(int n2) { return (uint64_t)(n2 / 16) * (n2 / 32) * 2 * 1024; }
 inline uint64_t bwla_decode_planes_bytes(int n1, int n2) {
-    const uint64_t r2 = bwla_decode_planes_r2_bytes(n1, n2);
-    return r2 ? r2 + (uint64_t)(n1 / 32) * 2 * (n1 / 16) * 1024 : 0;
+    if (!bwla_planes_shape_ok(n1, n2)) return 0;
+    return bwla_decode_planes_r2_bytes(n1, n2) + bwla_planes_r1h_bytes(n1) + bwla_planes_r2h_bytes(n2);
 }
 
 // PSP projection (T = X U) launch plan: token tiles x column groups x S slices of K.  Up to 16
@@ -128,6 +136,9 @@ __device__ __forceinline__ bool bwla_partials_arrive(int* counter, int expected,
 
 hipError_t bwla_launch_code_sums(const int8_t* dq, int64_t M, int64_t K, int32_t* dqsum, hipStream_t st);
 // the whole layer in one launch for one bf16 token where the shape allows it (*done says whether)
+hipError_t bwla_launch_rotate_planes(const bwla_layer_t* L, const void* dX, int xdtype, int64_t M, int8_t* dq,
+                                     float* dscale, int32_t* dqsum, float* dT, int act_bits, hipStream_t st,
+                                     bool* done);
 hipError_t bwla_launch_decode_layer(const bwla_layer_t* L, const void* dX, int xdtype, int64_t M, int8_t* dq,
                                     float* dscale, int32_t* dqsum, float* dT, void* dws_head, float* dY,
                                     int32_t* dacc, hipStream_t st, bool* done, bool dry_run = false);

@@ -192,19 +192,20 @@ __global__ void factor_planes_kernel(const float* __restrict__ R, int n, int per
     P[2 * plane + i] = (uint16_t)(h3 >> 16);
 }
 
-// Factor planes of the single-launch decode kernel (n1, n2 of 32 or 64), one 1 KiB block per MFMA
-// operand, lane (li, lg) = lg * 16 + li holding eight 16-bit values:
-//   R2 part, blocks [strip w][step kb][term p < 3]: term p (bf16; the three add up to the fp32 value)
-//            of R2[b = 32 kb + 8 lg + e][d = 16 w + li]
-//   R1 part, blocks [step ch][term t < 2][tile tc]: term t (fp16; hi = nearest, lo = remainder) of
+// Factor planes in MFMA operand order (factor pairs that are multiples of 32 up to 160), one 1 KiB
+// block per MFMA operand, lane (li, lg) = lg * 16 + li holding eight 16-bit values:
+//   R2d part (pairs of 32 or 64 only), blocks [strip w][step kb][term p < 3]: term p (bf16; the
+//            three add up to the fp32 value) of R2[b = 32 kb + 8 lg + e][d = 16 w + li]
+//   R1h part, blocks [step ch][term t < 2][tile tc]: term t (fp16; hi = nearest, lo = remainder) of
 //            256 R1[a][c = 16 tc + li], a = 32 ch + (e < 4 ? 4 lg + e : 16 + 4 lg + e - 4): the order in
 //            which two stacked 16-row accumulator tiles present their rows to a lane group
+//   R2h part, blocks [strip w][step kb][term t < 2]: the same two fp16 terms of 256 R2[b][d]
 __global__ void decode_planes_kernel(const float* __restrict__ R1, const float* __restrict__ R2, int n1, int n2,
-                                     uint16_t* __restrict__ out) {
+                                     int with_r2d, uint16_t* __restrict__ out) {
     const int at = n1 / 16, k1 = n2 / 32, ch2 = n1 / 32, strips = n2 / 16;
-    const int nb2 = strips * k1 * 3, nb1 = ch2 * 2 * at;
+    const int nb2 = with_r2d ? strips * k1 * 3 : 0, nb1 = ch2 * 2 * at, nb2h = strips * k1 * 2;
     const int i = blockIdx.x * blockDim.x + threadIdx.x;
-    if (i >= (nb2 + nb1) * 512) return;
+    if (i >= (nb2 + nb1 + nb2h) * 512) return;
     const int blk = i >> 9, lane = (i >> 3) & 63, e = i & 7, li = lane & 15, lg = lane >> 4;
     if (blk < nb2) {
         const int p = blk % 3, kb = (blk / 3) % k1, w = blk / (3 * k1);
@@ -218,11 +219,19 @@ __global__ void decode_planes_kernel(const float* __restrict__ R1, const float* 
         const uint32_t h2 = bf(r1);
         const uint32_t h3 = bf(r1 - __uint_as_float(h2));
         out[i] = (uint16_t)((p == 0 ? h1 : p == 1 ? h2 : h3) >> 16);
-    } else {
+    } else if (blk < nb2 + nb1) {
         const int b1 = blk - nb2;
         const int tc = b1 % at, t = (b1 / at) % 2, ch = b1 / (2 * at);
         const int a = 32 * ch + (e < 4 ? 4 * lg + e : 16 + 4 * lg + e - 4);
         const float v = 256.0f * R1[(int64_t)a * n1 + 16 * tc + li];
+        const __half hi = __float2half_rn(v);
+        const __half lo = __float2half_rn(v - __half2float(hi));
+        out[i] = __half_as_ushort(t == 0 ? hi : lo);
+    } else {
+        // R2h, blocks [strip w][step kb][term t < 2]: 256 R2[b = 32 kb + 8 lg + e][d = 16 w + li]
+        const int b2 = blk - nb2 - nb1;
+        const int t = b2 % 2, kb = (b2 / 2) % k1, w = b2 / (2 * k1);
+        const float v = 256.0f * R2[(int64_t)(32 * kb + 8 * lg + e) * n2 + 16 * w + li];
         const __half hi = __float2half_rn(v);
         const __half lo = __float2half_rn(v - __half2float(hi));
         out[i] = __half_as_ushort(t == 0 ? hi : lo);
@@ -287,7 +296,8 @@ hipError_t bwla_launch_pack(const float* dW, const float* dR1, const float* dR2,
     factor_planes_kernel<<<dim3((unsigned)((p2 + 255) / 256)), dim3(256), 0, st>>>(dR2, n2, 0, (uint16_t*)(blob + L->off_R2p));
     if (L->off_Rd != 0) {
         const int nd = (int)(bwla_decode_planes_bytes(n1, n2) / 2);
-        decode_planes_kernel<<<dim3((unsigned)((nd + 255) / 256)), dim3(256), 0, st>>>(dR1, dR2, n1, n2, (uint16_t*)(blob + L->off_Rd));
+        decode_planes_kernel<<<dim3((unsigned)((nd + 255) / 256)), dim3(256), 0, st>>>(
+            dR1, dR2, n1, n2, bwla_decode_planes_r2_bytes(n1, n2) > 0 ? 1 : 0, (uint16_t*)(blob + L->off_Rd));
     }
     return hipGetLastError();
 }

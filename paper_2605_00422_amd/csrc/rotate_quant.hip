@@ -198,6 +198,14 @@ hipError_t bwla_launch_rotate_quant(const bwla_layer_t* L, const void* dX, int x
     const size_t plds = merged ? pp_lds_bytes(ru) : 0;
     a.rot_blocks = M;
     hipError_t e;
+    if (!merged) {
+        // many bf16 tokens and factors whose operand-order planes fit LDS: the looping kernel with
+        // resident factors
+        bool done = false;
+        e = bwla_launch_rotate_planes(L, dX, xdtype, M, dq, dscale, dqsum, dT, act_bits, st, &done);
+        if (e != hipSuccess) return e;
+        if (done) return ru > 0 ? bwla_launch_psp_prefill(L, dX, xdtype, M, dT, dws, plan, st) : hipSuccess;
+    }
     const R3Shape s3 = r3_shape(L->n1, L->n2);
     const size_t split_bytes = xdtype == BWLA_X_BF16 ? bwla_split_rotation_bytes(L, plan, M) : 0;
     if (split_bytes > 0 && dws != nullptr) {

@@ -79,6 +79,22 @@ def test_looping_rotation_two_tokens_at_a_time_fewer_pairs_than_cus():
     print(run_case(cfg, rows=[0, 1, 2, 149, 150, 151, 298, 299, 300]), flush=True)
 
 
+@pytest.mark.parametrize("M,K,n1,n2,N,r,bits,centered", [
+    (2085, 4096, 64, 64, 48, 8, 6, False),     # four tokens at a time per workgroup, three rounds, the last one ragged
+    (520, 25600, 160, 160, 64, 16, 6, False),  # ten strips, one token at a time, third round with eight workgroups
+    (600, 4096, 64, 64, 40, 8, 8, False),      # 8-bit codes
+    (515, 8192, 128, 64, 40, 8, 6, True),      # row shift: the shift entry of T from the looping kernel
+    (512, 2048, 32, 64, 40, 0, 6, False),      # exactly two tokens per CU, no low-rank part: no kernel built, the older path
+])
+def test_resident_factor_rotation_many_tokens(M, K, n1, n2, N, r, bits, centered):
+    """At least two bf16 tokens per CU and factors whose operand-order planes fit LDS: the looping
+    rotation kernel with resident factors (two-term fp16 operands)."""
+    from parity_util import run_case
+    cfg = syn.LayerConfig(f"planes_{M}_{K}_{bits}", M, K, n1, n2, N, r, "bf16", max(1, K // 100), 20.0, seed=21)
+    rows = sorted(set(_sample_rows(M, 40, seed=3).tolist()) | {M - 2, M // 2})
+    print(run_case(cfg, rows=rows, centered=centered, act_bits=bits), flush=True)
+
+
 @pytest.mark.parametrize("which", ["q", "k", "gate", "down"])
 def test_cfg4_70b_block_m4096_sampled_rows(which):
     """The block's four distinct shapes at 4096 tokens, full size on the GPU in the benchmarked
