@@ -149,18 +149,28 @@ __global__ __launch_bounds__((N2 / 16) * 64 * G) void rotate_planes_kernel(RpArg
         const int64_t t = t0 + (int64_t)j * tstep;
         const bool live = t < a.M;
         // ================================================================ the two stages, step by step
+        // Every LDS operand is requested one step before the MFMAs that use it (a step: the four
+        // MFMAs of one 32-deep piece of stage 1, or the three of one output tile of stage 2), so
+        // that a wavefront does not stand still for an LDS round trip at every step.
         v4f y[AT];
 #pragma unroll
         for (int tc = 0; tc < AT; ++tc) y[tc] = v4f{0.f, 0.f, 0.f, 0.f};
+        auto ld_a = [&](int ch, int kb, int half) -> v4i {
+            return *reinterpret_cast<const v4i*>(xt + (32 * ch + 16 * half + li) * PITCH + lg * 16 + kb * 64);
+        };
+        auto ld_b = [&](int ch, int term, int tc) -> v4i {
+            return *reinterpret_cast<const v4i*>(r1 + ((ch * 2 + term) * AT + tc) * 1024 + lane * 16);
+        };
+        v4i na0 = ld_a(0, 0, 0), na1 = ld_a(0, 0, 1);
 #pragma unroll
         for (int ch = 0; ch < CH2; ++ch) {
             v4f z0 = v4f{0.f, 0.f, 0.f, 0.f}, z1 = z0;
-            const char* a0p = xt + (32 * ch + li) * PITCH + lg * 16;
-            const char* a1p = a0p + 16 * PITCH;
+            v4i nbh = v4i{0, 0, 0, 0}, nbl = nbh;
 #pragma unroll
             for (int kb = 0; kb < K1; ++kb) {
-                const v8h_r a0 = __builtin_bit_cast(v8h_r, *reinterpret_cast<const v4i*>(a0p + kb * 64));
-                const v8h_r a1 = __builtin_bit_cast(v8h_r, *reinterpret_cast<const v4i*>(a1p + kb * 64));
+                const v8h_r a0 = __builtin_bit_cast(v8h_r, na0), a1 = __builtin_bit_cast(v8h_r, na1);
+                if (kb + 1 < K1) { na0 = ld_a(ch, kb + 1, 0); na1 = ld_a(ch, kb + 1, 1); }
+                else { nbh = ld_b(ch, 0, 0); nbl = ld_b(ch, 1, 0); }
                 z0 = __builtin_amdgcn_mfma_f32_16x16x32_f16(a0, bl[kb], z0, 0, 0, 0);      // small term first
                 z1 = __builtin_amdgcn_mfma_f32_16x16x32_f16(a1, bl[kb], z1, 0, 0, 0);
                 z0 = __builtin_amdgcn_mfma_f32_16x16x32_f16(a0, bh[kb], z0, 0, 0, 0);
@@ -176,11 +186,11 @@ __global__ __launch_bounds__((N2 / 16) * 64 * G) void rotate_planes_kernel(RpArg
                 ah[e] = h;
                 al[e] = (_Float16)__builtin_fmaf((float)h, -1.0f, f);
             }
-            const char* cb = r1 + ch * 2 * AT * 1024 + lane * 16;
 #pragma unroll
             for (int tc = 0; tc < AT; ++tc) {
-                const v8h_r ch_ = __builtin_bit_cast(v8h_r, *reinterpret_cast<const v4i*>(cb + (0 * AT + tc) * 1024));
-                const v8h_r cl_ = __builtin_bit_cast(v8h_r, *reinterpret_cast<const v4i*>(cb + (1 * AT + tc) * 1024));
+                const v8h_r ch_ = __builtin_bit_cast(v8h_r, nbh), cl_ = __builtin_bit_cast(v8h_r, nbl);
+                if (tc + 1 < AT) { nbh = ld_b(ch, 0, tc + 1); nbl = ld_b(ch, 1, tc + 1); }
+                else if (ch + 1 < CH2) { na0 = ld_a(ch + 1, 0, 0); na1 = ld_a(ch + 1, 0, 1); }
                 y[tc] = __builtin_amdgcn_mfma_f32_16x16x32_f16(al, ch_, y[tc], 0, 0, 0);
                 y[tc] = __builtin_amdgcn_mfma_f32_16x16x32_f16(ah, cl_, y[tc], 0, 0, 0);
                 y[tc] = __builtin_amdgcn_mfma_f32_16x16x32_f16(ah, ch_, y[tc], 0, 0, 0);

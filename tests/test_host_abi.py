@@ -67,15 +67,17 @@ def test_kron_factor_matches_hand_pairs(lib):
 
 def test_packed_size_accounting(lib):
     """Blob = 1 bit per weight in 16 x 512 tiles + fp16 alpha + fp16 U, V (rows padded to 16)
-    + fp32 factors + operand-ordered copies of the two small factors (bf16 term planes; for factors of
-    32 or 64 also the planes of the single-launch decode kernel).  The layer's parameters are ~1.18
+    + fp32 factors + operand-ordered copies of the two small factors (bf16 term planes; for factors that
+    are multiples of 32 up to 160 also fp16 two-term planes of both, and for 32 or 64 the bf16 planes of
+    the single-launch decode kernel).  The layer's parameters are ~1.18
     bits per weight at the 7B-like shape, inside the band the paper reports (Table 1: 1.15-1.19); the
     copies of the factors add 0.015 on top."""
     N, K, n1, n2, r = 11008, 4096, 64, 64, 32
     size = B.packed_size(N, K, n1, n2, r)
     pad = lambda n, m: (n + m - 1) // m * m
     planes = lambda n: 3 * pad(n, 16) * pad(n, 32) * 2        # three bf16 terms of a factor, padded
-    decode_planes = (n2 // 16) * (n2 // 32) * 3 * 1024 + (n1 // 32) * 2 * (n1 // 16) * 1024
+    decode_planes = ((n2 // 16) * (n2 // 32) * 3 * 1024 + (n1 // 32) * 2 * (n1 // 16) * 1024
+                     + (n2 // 16) * (n2 // 32) * 2 * 1024)
     params = N * K // 8 + 2 * N + 2 * r * (N + K) + 4 * (n1 * n1 + n2 * n2)
     exact = params + planes(n1) + planes(n2) + decode_planes
     assert exact <= size <= exact + 9 * 256
