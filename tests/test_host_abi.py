@@ -71,7 +71,7 @@ def test_packed_size_accounting(lib):
     are multiples of 32 up to 160 also fp16 two-term planes of both, and for 32 or 64 the bf16 planes of
     the single-launch decode kernel).  The layer's parameters are ~1.18
     bits per weight at the 7B-like shape, inside the band the paper reports (Table 1: 1.15-1.19); the
-    copies of the factors add 0.015 on top."""
+    copies of the factors add 0.02 on top."""
     N, K, n1, n2, r = 11008, 4096, 64, 64, 32
     size = B.packed_size(N, K, n1, n2, r)
     pad = lambda n, m: (n + m - 1) // m * m
@@ -82,7 +82,7 @@ def test_packed_size_accounting(lib):
     exact = params + planes(n1) + planes(n2) + decode_planes
     assert exact <= size <= exact + 9 * 256
     assert 1.15 <= 8 * params / (N * K) <= 1.19
-    assert 8 * size / (N * K) <= 1.20
+    assert 8 * size / (N * K) <= 1.21
     # factor pairs the decode kernel does not take carry no such planes
     assert B.packed_size(N, 4096 * 2, 128, 64, r) - B.packed_size(N, 4096 * 2, 128, 64, 0) <= 2 * r * (N + 8192) + 512
     # ragged shapes pad rows to 16 and columns to 512
