@@ -37,7 +37,7 @@ typedef _Float16 v8h __attribute__((ext_vector_type(8)));
 
 constexpr int DL_THREADS = 512;      // eight wavefronts
 constexpr int DL_TPW = 3;            // channel tiles per workgroup and round
-constexpr int DL_MAXAT = 4;          // 16-row tiles along n1 (n1 <= 64)
+constexpr int DL_MAXAT = 8;          // 16-row tiles along n1 (n1 <= 128)
 constexpr int DL_MAXK1 = 2;          // 32-deep steps along n2 (n2 <= 64)
 constexpr int DL_MAXJTU = 4;         // 16-column tiles of U (PSP rank <= 64)
 constexpr int DL_MAXJTV = 5;         // 16-column tiles of V (one more when the layer's mode adds a column)
@@ -62,6 +62,9 @@ __device__ __forceinline__ int dl_neg_bytes(int x) {
     const unsigned nx = ~(unsigned)x;
     return (int)(((nx & 0x7f7f7f7fu) + 0x01010101u) ^ (nx & 0x80808080u));
 }
+
+// s_waitcnt immediate: at most n vector memory operations still outstanding (other counters not waited for)
+constexpr int dl_vmcnt_imm(int n) { return (n & 15) | ((n >> 4) << 14) | (7 << 4) | (15 << 8); }
 
 __device__ __forceinline__ void dl_async_16(const void* src, char* dst_block) {
     // lane l's 16 bytes land at dst_block + 16 l (the hardware's placement)
@@ -88,8 +91,9 @@ __global__ __launch_bounds__(DL_THREADS) void decode_layer_kernel(const uint16_t
     constexpr int GPR = N2 / 8;                        // 16-byte granules per token row: 8 or 4
     constexpr int SW = K / DL_SLICES, SWW = SW / 4;    // T: columns per slice and per wavefront of a producer
     constexpr int NKS = SWW / 32, RPU = 16 * JTU;      // T: 32-deep steps per wavefront; columns of U
+    constexpr int NB1 = CH2 * 2 * AT;                  // 1 KiB blocks of the R1 terms
     static_assert(JTU == 0 || NKS >= 1, "a producer wavefront has at least one step");
-    static_assert(STRIPS <= 4 && AT <= 4 && CHUNKS <= 8 && CHUNKS >= 2, "shape outside the kernel's wavefront roles");
+    static_assert(STRIPS <= 4 && AT <= DL_MAXAT && CHUNKS <= 16 && CHUNKS >= 2, "shape outside the kernel's wavefront roles");
     extern __shared__ __align__(16) char lds[];
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -101,17 +105,17 @@ __global__ __launch_bounds__(DL_THREADS) void decode_layer_kernel(const uint16_t
     char* r1 = xt + 2 * K;                             // R1 terms [chunk][term][tile of c][lane * 16]: CH2 * 2 * AT KiB
     char* codes = r1 + CH2 * 2 * AT * 1024;            // K code bytes, k order
     char* xh = codes + K;                              // a producer's slice of the token as fp16: SW * 2 bytes
-    float* red = reinterpret_cast<float*>(xh + 2 * SW);// [0..3] strip maxima, [4..7] strip code sums, [8..13] arrival counts, [14] epoch
+    float* red = reinterpret_cast<float*>(xh + 2 * SW);// [0..3] strip maxima, [4..7] strip code sums, [8..13] six arrival counts, [14] epoch
     float* tpart = red + 16;                           // [4 wavefronts][16 * DL_MAXJTU] partial T of a producer
     float* txl = tpart + 4 * 16 * DL_MAXJTU;           // [DL_SLICES][16 * DL_MAXJTU] the slices' sums, [DL_SLICES * ...] on: T
     float* tfin = txl + (DL_SLICES + 1) * 16 * DL_MAXJTU;   // [8 wavefronts][16 * DL_MAXJTV] T as an epilogue wavefront reads it
     int* part = reinterpret_cast<int*>(tfin + 8 * 16 * DL_MAXJTV);   // [rounds][DL_TPW][8 chunks][16 channels]
 
-    // arrival counts (rotation wavefronts: operands landed, maxima left, codes written; a producer's
-    // wavefronts: partial sums left; wavefront 7: epoch read), zero before anybody bumps them: this
+    // arrival counts (rotation wavefronts: token and R2 landed, maxima left, codes written; a producer's
+    // wavefronts: partial sums left; wavefront 7: epoch read; rotation wavefronts again: R1 landed), zero before anybody bumps them: this
     // barrier costs nothing, every wavefront would otherwise wait here for its first operands
     int* cnt = reinterpret_cast<int*>(red) + 8;
-    if (tid < 5) cnt[tid] = 0;
+    if (tid < 6) cnt[tid] = 0;
     bwla_lds_barrier();
     // A subset of the wavefronts meets without holding up the others: each bumps the count when it
     // is ready, and whoever needs them all waits until the count is full.  (The wait is bounded: a
@@ -201,13 +205,13 @@ __global__ __launch_bounds__(DL_THREADS) void decode_layer_kernel(const uint16_t
 #pragma unroll
             for (int p = 0; p < 3; ++p)
                 bfr[kb][p] = *reinterpret_cast<const v4i*>(pR2d + (((wave * K1 + kb) * 3 + p) * 64 + lane) * 8);
-        constexpr int NB = CH2 * 2 * AT;
+        // (last, and the same number for every rotation wavefront: stage 1 does not wait for them)
+        static_assert(NB1 % STRIPS == 0, "every rotation wavefront requests the same number of R1 blocks");
 #pragma unroll
-        for (int i = 0; i < (NB + STRIPS - 1) / STRIPS; ++i) {
+        for (int i = 0; i < NB1 / STRIPS; ++i) {
             const int b1 = wave + i * STRIPS;
-            if (b1 < NB) dl_async_16(pR1h + (b1 * 64 + lane) * 8, r1 + b1 * 1024);
+            dl_async_16(pR1h + (b1 * 64 + lane) * 8, r1 + b1 * 1024);
         }
-        if (my_round < a.rounds) epi_loads(my_round);
     } else if (produces) {
         // my SWW columns of the token (16 bytes from each of the first lanes) and of U
         const int col0 = slice * SW + (wave - 4) * SWW;
@@ -275,7 +279,7 @@ __global__ __launch_bounds__(DL_THREADS) void decode_layer_kernel(const uint16_t
     }
     if (!rotates) {
         // a wavefront that only contracts waits until the rotation's operands are there
-        await(cnt, STRIPS);
+        await(cnt + 5, STRIPS);
         request_bits(0);
         if (my_round < a.rounds) epi_loads(my_round);
     }
@@ -317,9 +321,9 @@ __global__ __launch_bounds__(DL_THREADS) void decode_layer_kernel(const uint16_t
     if (rotates) {
         // ---- operands landed: every rotation wavefront waits for its own asynchronous copies, then
         // for the other rotation wavefronts (the T wavefronts go on by themselves)
-        __builtin_amdgcn_s_waitcnt(0);
+        // (loads return in the order of their requests: all but the R1 blocks, which came last)
+        __builtin_amdgcn_s_waitcnt(dl_vmcnt_imm(NB1 / STRIPS));
         meet(cnt, STRIPS);
-        request_bits(0);
         // ============================================================ rotation, stage 1: Z = V R2
         v4f z[AT];
 #pragma unroll
@@ -341,6 +345,11 @@ __global__ __launch_bounds__(DL_THREADS) void decode_layer_kernel(const uint16_t
 #pragma unroll
                 for (int ta = 0; ta < AT; ++ta) z[ta] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(av[kb][ta], b, z[ta], 0, 0, 0);
             }
+        // ---- the R1 terms have landed, everybody's; from here on the weight stream may have the memory pipes
+        __builtin_amdgcn_s_waitcnt(dl_vmcnt_imm(0));
+        meet(cnt + 5, STRIPS);
+        request_bits(0);
+        if (my_round < a.rounds) epi_loads(my_round);
         // ============================================================ stage 2: Yt = Zt R1
         // The accumulator tiles of stage 1 are A operands as they stand: lane (li, lg) holds
         // Z[a = 16 ta + 4 lg + v][d = li]; two stacked tiles give the eight contraction positions
@@ -452,6 +461,7 @@ __global__ __launch_bounds__(DL_THREADS) void decode_layer_kernel(const uint16_t
         if (bumps) count_arrivals();
         for (int rd = 0; rd < a.rounds; ++rd) {
             int* prt = part + rd * DL_TPW * 8 * 16;
+
             // the round's tiles (all DL_TPW of them, except in the last round) side by side: per tile
             // and chunk two independent chains through the accumulator (odd and even digit classes),
             // e = S6+S4+S2+S0, o = 2 (S7+S5+S3+S1), exact arithmetic shifts in between
@@ -611,8 +621,8 @@ size_t dl_lds_bytes(int K, int n1, int n2, bool with_t) {
 
 
 // Single-launch decode layer.  *done = false (and nothing launched) when the shape is outside what
-// the kernel takes: one bf16 token; Kronecker factors of 32 or 64 (K = 1024 .. 4096, which covers
-// the 4096-wide models' attention and up/gate projections); PSP rank up to 64 (and then at least
+// the kernel takes: one bf16 token; Kronecker factors of 32 or 64, or 128 x 64 (K = 1024 .. 8192, which
+// covers the 4096- and 8192-wide models' attention and up/gate projections); PSP rank up to 64 (and then at least
 // 512 output channels, so that the projection has its 32 producers); symmetric codes, with or
 // without the row shift.  dws_head: the first BWLA_WS_HEAD bytes of the caller's scratch.  With
 // dry_run nothing is launched and *done only says whether the kernel would serve the call.
@@ -622,13 +632,13 @@ hipError_t bwla_launch_decode_layer(const bwla_layer_t* L, const void* dX, int x
     *done = false;
     const int n1 = L->n1, n2 = L->n2;
     if (M != 1 || xdtype != BWLA_X_BF16) return hipSuccess;
-    if ((n1 != 32 && n1 != 64) || (n2 != 32 && n2 != 64)) return hipSuccess;
+    if ((n1 != 32 && n1 != 64 && n1 != 128) || (n2 != 32 && n2 != 64)) return hipSuccess;
     if ((L->mode & BWLA_MODE_ASYM_ACT) != 0) return hipSuccess;
     const int ru = bwla_rank_u(L), r = L->r;
     const int jtu = (ru + 15) >> 4, jtv = (r + 15) >> 4;
     if (jtu > DL_MAXJTU || jtv > DL_MAXJTV) return hipSuccess;
     const int K = (int)L->K, chunks = (int)bwla_chunks(L->K), row_tiles = (int)bwla_row_tiles(L->N);
-    if (chunks > 8 || chunks < 2 || (K & 511) != 0) return hipSuccess;
+    if (chunks > 16 || chunks < 2 || (K & 511) != 0) return hipSuccess;
     const char* blob = (const char*)L->d_blob;
     const int cus = bwla_device_cus();
     const int grid = row_tiles < cus ? row_tiles : cus;
@@ -669,6 +679,8 @@ hipError_t bwla_launch_decode_layer(const bwla_layer_t* L, const void* dX, int x
     // the smaller factor pairs with the ranks their widths would carry
     DL_CASE(32, 64, 0, 0) DL_CASE(32, 64, 1, 1) DL_CASE(32, 64, 2, 2) DL_CASE(64, 32, 0, 0) DL_CASE(64, 32, 1, 1)
     DL_CASE(64, 32, 2, 2) DL_CASE(32, 32, 0, 0) DL_CASE(32, 32, 1, 1)
+    // 8192 columns (128 x 64: the 8192-wide models' attention and up / gate projections)
+    DL_CASE(128, 64, 0, 0) DL_CASE(128, 64, 2, 2) DL_CASE(128, 64, 4, 4) DL_CASE(128, 64, 4, 5)
 #undef DL_RANKS
 #undef DL_CASE
     if (!found) return hipSuccess;                         // no kernel built for this pair: the caller's two launches
