@@ -119,18 +119,13 @@ class Workload:
         self.X = X.to(torch.bfloat16) if cfg.x_dtype == "bf16" else X
         self.act = B.Activations(first, cfg.M)
         self.Y = torch.empty((cfg.M, cfg.N), dtype=torch.float32, device=dev)
-        # 1 where bwla_decode_forward has a single-launch kernel for the shape (6-bit codes only:
-        # the call takes no code width)
-        self.launches = B.decode_forward_launches(first, cfg.M, cfg.x_dtype == "bf16") if act_bits == 6 else 2
+        # 1 where bwla_decode_forward has a single-launch kernel for the shape (at any code width)
+        self.launches = B.decode_forward_launches(first, cfg.M, cfg.x_dtype == "bf16")
         torch.cuda.synchronize()
 
     def step(self, i):
         L = self.layers[i % len(self.layers)]
-        if self.act_bits == 6:
-            self.B.decode_forward(L, self.X, self.act, self.Y)
-        else:
-            self.B.rotate_quant(L, self.X, self.act, self.act_bits)
-            self.B.linear_forward(L, self.act, self.Y)
+        self.B.decode_forward(L, self.X, self.act, self.Y, act_bits=self.act_bits)
 
     def only_rotate(self, i):
         self.B.rotate_quant(self.layers[i % len(self.layers)], self.X, self.act, self.act_bits)

@@ -255,6 +255,13 @@ BWLA_API bwla_status_t bwla_decode_forward(const bwla_layer_t* layer, const void
                                   int8_t* d_q, float* d_scale, int32_t* d_qsum, float* d_T,
                                   void* d_ws, size_t ws_bytes, float* d_Y, int32_t* d_acc,
                                   void* stream);
+/* bwla_decode_forward at another width of the activation codes: act_bits as in bwla_rotate_quant_bits
+ * (2..8, else BWLA_ERR_UNSUPPORTED; 8 is the width of the paper's speed run, Sec. 4.4).  The
+ * single-launch kernel serves every width. */
+BWLA_API bwla_status_t bwla_decode_forward_bits(const bwla_layer_t* layer, const void* d_X, int xdtype, int act_bits,
+                                                int64_t M, int8_t* d_q, float* d_scale, int32_t* d_qsum, float* d_T,
+                                                void* d_ws, size_t ws_bytes, float* d_Y, int32_t* d_acc,
+                                                void* stream);
 
 /*
  * Whether bwla_decode_forward serves (layer, xdtype, M) with its single-launch kernel: *launches

@@ -20,7 +20,7 @@ EXPORTS = ["bwla_status_string", "bwla_version", "bwla_kron_factor", "bwla_packe
            "bwla_linear_forward", "bwla_decode_forward", "bwla_packed_size_centered", "bwla_pack_weights_centered", "bwla_rotate_quant_bits",
            "bwla_packed_size_mode", "bwla_pack_weights_mode", "bwla_swiglu_workspace_size",
            "bwla_linear_forward_swiglu", "bwla_decode_forward_static", "bwla_probe_hbm_read",
-           "bwla_probe_mfma_int8", "bwla_decode_forward_launches"]
+           "bwla_probe_mfma_int8", "bwla_decode_forward_launches", "bwla_decode_forward_bits"]
 
 
 class BwlaLayer(Structure):
@@ -74,6 +74,8 @@ def load() -> ctypes.CDLL:
                                         c_void_p, c_void_p, c_size_t, c_void_p, c_void_p, c_void_p]
     lib.bwla_decode_forward_static.argtypes = [POINTER(BwlaLayer), c_void_p, c_int, c_int64, c_void_p, c_void_p,
                                                c_void_p, c_void_p, c_void_p, c_void_p, c_void_p]
+    lib.bwla_decode_forward_bits.argtypes = [POINTER(BwlaLayer), c_void_p, c_int, c_int, c_int64, c_void_p, c_void_p, c_void_p,
+                                             c_void_p, c_void_p, c_size_t, c_void_p, c_void_p, c_void_p]
     lib.bwla_decode_forward_launches.argtypes = [POINTER(BwlaLayer), c_int, c_int64, POINTER(c_int)]
     lib.bwla_probe_hbm_read.argtypes = [c_void_p, c_size_t, c_void_p, c_size_t, c_void_p]
     lib.bwla_probe_mfma_int8.argtypes = [c_int, c_void_p, c_size_t, POINTER(ctypes.c_int64), c_void_p]
@@ -211,15 +213,20 @@ def rotate_quant(layer: PackedLayer, X, act: Activations, act_bits: int = 6) -> 
     return act
 
 
-def decode_forward(layer: PackedLayer, X, act: Activations, Y, acc=None):
+def decode_forward(layer: PackedLayer, X, act: Activations, Y, acc=None, act_bits: int = 6):
     """bwla_rotate_quant + bwla_linear_forward in one call (one kernel launch where possible)."""
     import torch
     if X.dtype not in (torch.bfloat16, torch.float32):
         raise TypeError("X must be float32 or bfloat16")
     xd = BWLA_X_BF16 if X.dtype == torch.bfloat16 else BWLA_X_F32
-    _check(load().bwla_decode_forward(byref(layer.desc), _ptr(X), xd, X.shape[0], _ptr(act.q), _ptr(act.scale),
-                                      _ptr(act.qsum), _ptr(act.T), _ptr(act.ws), act.ws_bytes, _ptr(Y), _ptr(acc),
-                                      _stream()), "bwla_decode_forward")
+    if act_bits == 6:
+        _check(load().bwla_decode_forward(byref(layer.desc), _ptr(X), xd, X.shape[0], _ptr(act.q), _ptr(act.scale),
+                                          _ptr(act.qsum), _ptr(act.T), _ptr(act.ws), act.ws_bytes, _ptr(Y), _ptr(acc),
+                                          _stream()), "bwla_decode_forward")
+    else:
+        _check(load().bwla_decode_forward_bits(byref(layer.desc), _ptr(X), xd, int(act_bits), X.shape[0], _ptr(act.q),
+                                               _ptr(act.scale), _ptr(act.qsum), _ptr(act.T), _ptr(act.ws), act.ws_bytes,
+                                               _ptr(Y), _ptr(acc), _stream()), "bwla_decode_forward_bits")
     return Y
 
 

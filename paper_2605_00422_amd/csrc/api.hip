@@ -281,11 +281,13 @@ bwla_status_t bwla_rotate_quant_bits(const bwla_layer_t* layer, const void* d_X,
     return BWLA_OK;
 }
 
-bwla_status_t bwla_decode_forward(const bwla_layer_t* layer, const void* d_X, int xdtype, int64_t M,
+bwla_status_t bwla_decode_forward_bits(const bwla_layer_t* layer, const void* d_X, int xdtype, int act_bits, int64_t M,
                                   int8_t* d_q, float* d_scale, int32_t* d_qsum, float* d_T, void* d_ws,
                                   size_t ws_bytes, float* d_Y, int32_t* d_acc, void* stream) {
+    if (act_bits < 2 || act_bits > 8) return BWLA_ERR_UNSUPPORTED;
     bwla_status_t s = check_layer(layer);
     if (s != BWLA_OK) return s;
+    if ((layer->mode & BWLA_MODE_ASYM_ACT) && act_bits > 7) return BWLA_ERR_UNSUPPORTED;
     if (!d_X || !d_q || !d_scale || !d_qsum || !d_Y) return BWLA_ERR_NULL;
     if (layer->r > 0 && !d_T) return BWLA_ERR_NULL;
     if (M <= 0 || M > (int64_t)1 << 24) return BWLA_ERR_SHAPE;
@@ -300,12 +302,18 @@ bwla_status_t bwla_decode_forward(const bwla_layer_t* layer, const void* d_X, in
     // one launch when the shape allows it
     bool done = false;
     if (bwla_launch_decode_layer(layer, d_X, xdtype, M, d_q, d_scale, d_qsum, d_T, need > 0 ? d_ws : nullptr, d_Y, d_acc, st,
-                                 &done) != hipSuccess)
+                                 &done, false, act_bits) != hipSuccess)
         return BWLA_ERR_HIP;
     if (done) return BWLA_OK;
-    s = bwla_rotate_quant(layer, d_X, xdtype, M, d_q, d_scale, d_qsum, d_T, d_ws, ws_bytes, stream);
+    s = bwla_rotate_quant_bits(layer, d_X, xdtype, act_bits, M, d_q, d_scale, d_qsum, d_T, d_ws, ws_bytes, stream);
     if (s != BWLA_OK) return s;
     return bwla_linear_forward(layer, d_q, d_scale, d_qsum, d_T, M, d_Y, d_acc, stream);
+}
+
+bwla_status_t bwla_decode_forward(const bwla_layer_t* layer, const void* d_X, int xdtype, int64_t M,
+                                  int8_t* d_q, float* d_scale, int32_t* d_qsum, float* d_T, void* d_ws,
+                                  size_t ws_bytes, float* d_Y, int32_t* d_acc, void* stream) {
+    return bwla_decode_forward_bits(layer, d_X, xdtype, 6, M, d_q, d_scale, d_qsum, d_T, d_ws, ws_bytes, d_Y, d_acc, stream);
 }
 
 bwla_status_t bwla_decode_forward_launches(const bwla_layer_t* layer, int xdtype, int64_t M, int* launches) {

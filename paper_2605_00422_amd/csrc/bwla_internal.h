@@ -141,7 +141,7 @@ hipError_t bwla_launch_rotate_planes(const bwla_layer_t* L, const void* dX, int 
                                      bool* done);
 hipError_t bwla_launch_decode_layer(const bwla_layer_t* L, const void* dX, int xdtype, int64_t M, int8_t* dq,
                                     float* dscale, int32_t* dqsum, float* dT, void* dws_head, float* dY,
-                                    int32_t* dacc, hipStream_t st, bool* done, bool dry_run = false);
+                                    int32_t* dacc, hipStream_t st, bool* done, bool dry_run = false, int act_bits = 6);
 
 hipError_t bwla_launch_gemm_decode(const bwla_layer_t* L, const int8_t* dq, const float* dscale,
                                    const int32_t* dqsum, const float* dT, int64_t M, float* dY,

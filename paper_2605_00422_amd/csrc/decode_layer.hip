@@ -54,6 +54,7 @@ struct DlArgs {
     float* Y; int32_t* acc_out;
     unsigned* sync;                  // head of the scratch: [0] epoch, [16 (1 + i)] arrival count i < 8, from byte 1024 on the tagged sums
     int N, r, ru, row_tiles, rounds, shift;
+    float qmax;                      // largest code, 2^(bits-1) - 1
 };
 
 
@@ -410,7 +411,7 @@ __global__ __launch_bounds__(DL_THREADS) void decode_layer_kernel(const uint16_t
         float amax = 0.0f;
 #pragma unroll
         for (int w = 0; w < STRIPS; ++w) amax = fmaxf(amax, red[w]);
-        const float inv = amax > 0.0f ? 31.0f * __builtin_amdgcn_rcpf(amax) * yun : 0.0f;   // (on this strip's scaled values)
+        const float inv = amax > 0.0f ? a.qmax * __builtin_amdgcn_rcpf(amax) * yun : 0.0f;   // (on this strip's scaled values)
 
         // ============================================================ codes
         // lane holds Yt[d = 16 strip + 4 lg + v][c = 16 tc + li]: four consecutive k = c n2 + d.
@@ -560,7 +561,7 @@ __global__ __launch_bounds__(DL_THREADS) void decode_layer_kernel(const uint16_t
     // ================================================================ epilogue: every wavefront its round
     if (my_round < a.rounds) {
         const int rd = my_round;
-        const float st = amax / 31.0f;
+        const float st = amax / a.qmax;
         float* tf = tfin + wave * 16 * DL_MAXJTV;
         // T as the epilogue reads it: the PSP columns, then the column a row shift adds
         if (JTV > 0) {
@@ -628,7 +629,7 @@ size_t dl_lds_bytes(int K, int n1, int n2, bool with_t) {
 // dry_run nothing is launched and *done only says whether the kernel would serve the call.
 hipError_t bwla_launch_decode_layer(const bwla_layer_t* L, const void* dX, int xdtype, int64_t M, int8_t* dq,
                                     float* dscale, int32_t* dqsum, float* dT, void* dws_head, float* dY,
-                                    int32_t* dacc, hipStream_t st, bool* done, bool dry_run) {
+                                    int32_t* dacc, hipStream_t st, bool* done, bool dry_run, int act_bits) {
     *done = false;
     const int n1 = L->n1, n2 = L->n2;
     if (M != 1 || xdtype != BWLA_X_BF16) return hipSuccess;
@@ -660,6 +661,7 @@ hipError_t bwla_launch_decode_layer(const bwla_layer_t* L, const void* dX, int x
     if (jtu > 0 && (grid < DL_PRODUCERS || dws_head == nullptr)) return hipSuccess;
     a.sync = (unsigned*)dws_head;
     a.shift = (L->mode & BWLA_MODE_ROW_SHIFT) ? 1 : 0;
+    a.qmax = (float)((1 << (act_bits - 1)) - 1);
     const size_t lds = dl_lds_bytes(K, n1, n2, jtu > 0);
     auto launch = [&](auto kern) -> hipError_t {
         if (dry_run) return hipSuccess;                    // the caller only asks whether the shape is served
