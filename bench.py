@@ -89,13 +89,14 @@ def flush_caches(torch):
 class Workload:
     """One layer on the GPU with `copies` packed replicas and preallocated outputs."""
 
-    def __init__(self, cfg, copies=None, centered=False, act_bits=6, asym=False):
+    def __init__(self, cfg, copies=None, centered=False, act_bits=6, asym=False, nibble=False):
         import numpy as np
         import torch
         from paper_2605_00422_amd import binding as B
         from paper_2605_00422_amd import inputs as syn
         self.cfg, self.B, self.torch = cfg, B, torch
         self.act_bits = act_bits
+        self.nibble = nibble          # 4-bit codes packed two to a byte between the two calls
         dev = "cuda:0"
         d = syn.make_layer(cfg)
         self.data = d
@@ -121,16 +122,27 @@ class Workload:
         self.Y = torch.empty((cfg.M, cfg.N), dtype=torch.float32, device=dev)
         # 1 where bwla_decode_forward has a single-launch kernel for the shape (at any code width)
         self.launches = B.decode_forward_launches(first, cfg.M, cfg.x_dtype == "bf16")
+        if nibble:
+            self.q4 = torch.empty((cfg.M, cfg.K // 2), dtype=torch.uint8, device=dev)
+            self.launches = 2
         torch.cuda.synchronize()
 
     def step(self, i):
         L = self.layers[i % len(self.layers)]
+        if self.nibble:
+            self.B.rotate_quant(L, self.X, self.act, self.act_bits)
+            self.B.pack_codes_a4(self.act.q, self.q4)
+            self.B.linear_forward_a4(L, self.q4, self.act, self.Y)
+            return
         self.B.decode_forward(L, self.X, self.act, self.Y, act_bits=self.act_bits)
 
     def only_rotate(self, i):
         self.B.rotate_quant(self.layers[i % len(self.layers)], self.X, self.act, self.act_bits)
 
     def only_forward(self, i):
+        if self.nibble:
+            self.B.linear_forward_a4(self.layers[i % len(self.layers)], self.q4, self.act, self.Y)
+            return
         self.B.linear_forward(self.layers[i % len(self.layers)], self.act, self.Y)
 
     def only_forward_gated(self, i):
@@ -186,12 +198,14 @@ class Workload:
         return ms[len(ms) // 2], ms[0]
 
 
-def measure(cfg, steps, warmup, use_graph=True, centered=False, act_bits=6, asym=False):
-    w = Workload(cfg, centered=centered, act_bits=act_bits, asym=asym)
+def measure(cfg, steps, warmup, use_graph=True, centered=False, act_bits=6, asym=False, nibble=False):
+    w = Workload(cfg, centered=centered, act_bits=act_bits, asym=asym, nibble=nibble)
     out = {"workload": cfg.name + ("+row_shift" if centered else "") + (f"+a{act_bits}" if act_bits != 6 else "")
-           + ("+asym" if asym else ""),
+           + ("+asym" if asym else "") + ("+nibbles" if nibble else ""),
            "M": cfg.M, "K": cfg.K, "N": cfg.N, "r": cfg.r,
            "kron": f"{cfg.n1}x{cfg.n2}", "layer_copies": len(w.layers), "launches_per_layer": w.launches}
+    if nibble:
+        w.step(0)            # the packed codes exist before the GEMM is timed on its own
     ms_step = w.time_loop(w.step, steps, warmup)
     ms_fwd = w.time_loop(w.only_forward, steps, warmup)
     ms_rot = w.time_loop(w.only_rotate, steps, warmup)
@@ -438,21 +452,28 @@ def main():
         # (name, layer binarized with the row shift: the shift term rides as one more low-rank column)
         # and 8-bit activation codes, the width of the paper's speed run: same kernels, same bytes)
         # and per-token asymmetric codes with the row shift, the paper's own setting: three more columns)
-        variants = [(n, False, 6, False) for n in names] + [("cfg1_decode7b", True, 6, False),
-                                                            ("cfg1_decode7b", False, 8, False),
-                                                            ("cfg1_decode7b", True, 6, True)]
-        for nm, shift, bits, asym in variants:
+        # and 4-bit codes (paper Table 3) at the prefill shape: one per byte, and two per byte)
+        variants = [(n, False, 6, False, False) for n in names] + [("cfg1_decode7b", True, 6, False, False),
+                                                                   ("cfg1_decode7b", False, 8, False, False),
+                                                                   ("cfg1_decode7b", True, 6, True, False),
+                                                                   ("cfg3_qwen32b_down_m2048", False, 4, False, False),
+                                                                   ("cfg3_qwen32b_down_m2048", False, 4, False, True)]
+        for nm, shift, bits, asym, nibble in variants:
             if nm == cfg.name and not shift and bits == 6 and not asym:
                 continue
             c = all_cfgs[nm]
             st = max(10, min(args.steps, 200 if c.M <= 64 else (20 if c.M <= 2048 else 10)))
             ww, r = measure(c, st, max(3, min(args.warmup, st // 4)), not args.no_graph, centered=shift,
-                            act_bits=bits, asym=asym)
+                            act_bits=bits, asym=asym, nibble=nibble)
+            if nibble:
+                r["code_bytes_per_launch"] = c.M * c.K // 2
             if shift or asym:
                 c = dataclasses.replace(c, r=c.r + int(shift) + 2 * int(asym))   # bytes of the extra columns of V and T
             b, _ = best_of(r)
             r["roofline"] = roofline_for(c, ww.launches, b["us_per_layer"], b["us_linear_forward"], peaks, traffic,
                                          workload=r["workload"])
+            if not nibble and bits == 4:
+                r["code_bytes_per_launch"] = c.M * c.K
             r["side_kernels"] = [side_kernel_report(c, b["us_rotate_quant"])]
             r["effective_tops"] = gemm_ops(c) / (b["us_per_layer"] * 1e-6) / 1e12
             extra.append(r)

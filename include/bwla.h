@@ -314,6 +314,24 @@ BWLA_API bwla_status_t bwla_linear_forward_swiglu(const bwla_layer_t* layer, con
                                          void* d_ws, size_t ws_bytes, void* stream);
 
 /*
+ * 4-bit activation codes two to a byte (paper Table 3 reports W1A4: codes in [-7, 7]), which halves the
+ * bytes the prefill GEMM reads per token.
+ *   bwla_pack_codes_a4      d_q (M x K int8, every code in [-8, 7], as bwla_rotate_quant_bits writes them
+ *                           with act_bits = 4) -> d_q4 (M x K / 2 bytes, 16-byte aligned).  Layout: K is cut
+ *                           into runs of 32 codes; byte b (0..15) of run j holds code 32 j + b in its low
+ *                           nibble and code 32 j + 16 + b in its high nibble, two's complement.  K must be a
+ *                           multiple of 32 (else BWLA_ERR_UNSUPPORTED).
+ *   bwla_linear_forward_a4  bwla_linear_forward on such codes; every other argument, the results (bit for bit,
+ *                           accumulators included) and the errors as there.  The nibbles are unpacked in the
+ *                           operand path of the streaming prefill kernel; shapes that kernel does not take
+ *                           (M <= 16, K not a multiple of 128, N < 32) return BWLA_ERR_UNSUPPORTED.
+ */
+BWLA_API bwla_status_t bwla_pack_codes_a4(const int8_t* d_q, int64_t M, int64_t K, uint8_t* d_q4, void* stream);
+BWLA_API bwla_status_t bwla_linear_forward_a4(const bwla_layer_t* layer, const uint8_t* d_q4, const float* d_scale,
+                                              const int32_t* d_qsum, const float* d_T, int64_t M, float* d_Y,
+                                              int32_t* d_acc, void* stream);
+
+/*
  * Measurement aids for benchmarks, not steps of the method: the ceilings this GPU actually reaches,
  * to quote the forward's kernels against next to the published peaks.
  *   bwla_probe_hbm_read   one launch that reads `bytes` (a multiple of 16) from d_src (device,

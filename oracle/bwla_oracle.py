@@ -382,6 +382,28 @@ def swiglu_interleaved(Y: np.ndarray) -> np.ndarray:
         return g / (1.0 + np.exp(-g)) * u
 
 
+def pack_nibbles(q: np.ndarray) -> np.ndarray:
+    """4-bit codes two to a byte (paper Table 3, W1A4; the storage layout is this build's): K is cut
+    into runs of 32 codes, and byte b (0..15) of run j holds code 32 j + b in its low nibble and code
+    32 j + 16 + b in its high nibble, both in two's complement.  q: (M, K) integers in [-8, 7]."""
+    q = np.asarray(q, dtype=np.int64)
+    M, K = q.shape
+    if K % 32 != 0 or q.min() < -8 or q.max() > 7:
+        raise ValueError("need K % 32 == 0 and codes in [-8, 7]")
+    runs = q.reshape(M, K // 32, 2, 16)
+    return ((runs[:, :, 0, :] & 0xF) | ((runs[:, :, 1, :] & 0xF) << 4)).reshape(M, K // 2).astype(np.uint8)
+
+
+def unpack_nibbles(p: np.ndarray) -> np.ndarray:
+    """Inverse of pack_nibbles: (M, K / 2) bytes -> (M, K) codes."""
+    p = np.asarray(p, dtype=np.int64)
+    M, KB = p.shape
+    runs = p.reshape(M, KB // 16, 16)
+    sext = lambda n: np.where(n >= 8, n - 16, n)
+    out = np.stack([sext(runs & 0xF), sext((runs >> 4) & 0xF)], axis=2)
+    return out.reshape(M, 2 * KB)
+
+
 def effective_weight_bits(N: int, K: int, n1: int, n2: int, r: int) -> float:
     """Stored bits per weight of one packed layer: 1 sign bit, fp16 scale per row, fp16 PSP
     factors U (K,r) and V (N,r), fp32 Kronecker factors (paper Table 1 reports 1.15-1.19)."""

@@ -20,7 +20,8 @@ EXPORTS = ["bwla_status_string", "bwla_version", "bwla_kron_factor", "bwla_packe
            "bwla_linear_forward", "bwla_decode_forward", "bwla_packed_size_centered", "bwla_pack_weights_centered", "bwla_rotate_quant_bits",
            "bwla_packed_size_mode", "bwla_pack_weights_mode", "bwla_swiglu_workspace_size",
            "bwla_linear_forward_swiglu", "bwla_decode_forward_static", "bwla_probe_hbm_read",
-           "bwla_probe_mfma_int8", "bwla_decode_forward_launches", "bwla_decode_forward_bits"]
+           "bwla_probe_mfma_int8", "bwla_decode_forward_launches", "bwla_decode_forward_bits", "bwla_pack_codes_a4",
+           "bwla_linear_forward_a4"]
 
 
 class BwlaLayer(Structure):
@@ -76,6 +77,9 @@ def load() -> ctypes.CDLL:
                                                c_void_p, c_void_p, c_void_p, c_void_p, c_void_p]
     lib.bwla_decode_forward_bits.argtypes = [POINTER(BwlaLayer), c_void_p, c_int, c_int, c_int64, c_void_p, c_void_p, c_void_p,
                                              c_void_p, c_void_p, c_size_t, c_void_p, c_void_p, c_void_p]
+    lib.bwla_pack_codes_a4.argtypes = [c_void_p, c_int64, c_int64, c_void_p, c_void_p]
+    lib.bwla_linear_forward_a4.argtypes = [POINTER(BwlaLayer), c_void_p, c_void_p, c_void_p, c_void_p, c_int64,
+                                           c_void_p, c_void_p, c_void_p]
     lib.bwla_decode_forward_launches.argtypes = [POINTER(BwlaLayer), c_int, c_int64, POINTER(c_int)]
     lib.bwla_probe_hbm_read.argtypes = [c_void_p, c_size_t, c_void_p, c_size_t, c_void_p]
     lib.bwla_probe_mfma_int8.argtypes = [c_int, c_void_p, c_size_t, POINTER(ctypes.c_int64), c_void_p]
@@ -261,6 +265,22 @@ def probe_mfma_int8(iters: int, sink) -> int:
     _check(load().bwla_probe_mfma_int8(int(iters), _ptr(sink), sink.numel() * sink.element_size(), byref(ops),
                                        _stream()), "bwla_probe_mfma_int8")
     return ops.value
+
+
+def pack_codes_a4(q, q4=None):
+    """int8 codes in [-8, 7] (M x K) -> nibble-packed codes (M x K / 2 bytes)."""
+    import torch
+    if q4 is None:
+        q4 = torch.empty((q.shape[0], q.shape[1] // 2), dtype=torch.uint8, device=q.device)
+    _check(load().bwla_pack_codes_a4(_ptr(q), q.shape[0], q.shape[1], _ptr(q4), _stream()), "bwla_pack_codes_a4")
+    return q4
+
+
+def linear_forward_a4(layer: PackedLayer, q4, act: Activations, Y, acc=None):
+    """bwla_linear_forward on nibble-packed 4-bit codes (scale, code sums and T from `act`)."""
+    _check(load().bwla_linear_forward_a4(byref(layer.desc), _ptr(q4), _ptr(act.scale), _ptr(act.qsum), _ptr(act.T),
+                                         act.M, _ptr(Y), _ptr(acc), _stream()), "bwla_linear_forward_a4")
+    return Y
 
 
 def code_sums(q, qsum) -> None:

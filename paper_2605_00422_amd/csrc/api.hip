@@ -390,6 +390,31 @@ bwla_status_t bwla_linear_forward(const bwla_layer_t* layer, const int8_t* d_q, 
     return e == hipSuccess ? BWLA_OK : BWLA_ERR_HIP;
 }
 
+bwla_status_t bwla_pack_codes_a4(const int8_t* d_q, int64_t M, int64_t K, uint8_t* d_q4, void* stream) {
+    if (!d_q || !d_q4) return BWLA_ERR_NULL;
+    if (M <= 0 || K <= 0 || M > (int64_t)1 << 24) return BWLA_ERR_SHAPE;
+    if ((K & 31) != 0 || K > BWLA_MAX_K) return BWLA_ERR_UNSUPPORTED;
+    if (!aligned16(d_q) || !aligned16(d_q4)) return BWLA_ERR_ALIGN;
+    return bwla_launch_pack_codes_a4(d_q, M, K, d_q4, (hipStream_t)stream) == hipSuccess ? BWLA_OK : BWLA_ERR_HIP;
+}
+
+bwla_status_t bwla_linear_forward_a4(const bwla_layer_t* layer, const uint8_t* d_q4, const float* d_scale,
+                                     const int32_t* d_qsum, const float* d_T, int64_t M, float* d_Y,
+                                     int32_t* d_acc, void* stream) {
+    bwla_status_t s = check_layer(layer);
+    if (s != BWLA_OK) return s;
+    if (!d_q4 || !d_scale || !d_qsum || !d_Y) return BWLA_ERR_NULL;
+    if (layer->r > 0 && !d_T) return BWLA_ERR_NULL;
+    if (M <= 0 || M > (int64_t)1 << 24) return BWLA_ERR_SHAPE;
+    if (!aligned16(d_q4) || !aligned16(d_Y) || (d_T && !aligned16(d_T)) || (d_acc && !aligned16(d_acc)))
+        return BWLA_ERR_ALIGN;
+    // the streaming prefill kernel is the one that unpacks nibbles in its operand path
+    if (M <= 16 || !bwla_gemm_prefill_streams(layer)) return BWLA_ERR_UNSUPPORTED;
+    const hipError_t e = bwla_launch_gemm_prefill(layer, reinterpret_cast<const int8_t*>(d_q4), d_scale, d_qsum, d_T, M,
+                                                  d_Y, d_acc, (hipStream_t)stream, nullptr, true);
+    return e == hipSuccess ? BWLA_OK : BWLA_ERR_HIP;
+}
+
 // which GEMM serves the layer at M tokens, as bwla_linear_forward picks it, if that kernel can gate
 // in its epilogue: 1 decode kernel, 2 streaming prefill kernel, 0 neither (Y goes through scratch)
 static int swiglu_path(const bwla_layer_t* layer, int64_t M) {

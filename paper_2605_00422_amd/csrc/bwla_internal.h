@@ -156,7 +156,9 @@ bool bwla_gemm_prefill_streams(const bwla_layer_t* L);
 // (dH not NULL: gated bf16 output instead of Y; only when bwla_gemm_prefill_streams(L))
 hipError_t bwla_launch_gemm_prefill(const bwla_layer_t* L, const int8_t* dq, const float* dscale,
                                     const int32_t* dqsum, const float* dT, int64_t M, float* dY,
-                                    int32_t* dacc, hipStream_t st, uint16_t* dH = nullptr);
+                                    int32_t* dacc, hipStream_t st, uint16_t* dH = nullptr, bool a4 = false);
+// (a4: dq holds nibble-packed codes, K / 2 bytes per token; only when bwla_gemm_prefill_streams(L), no gating)
+hipError_t bwla_launch_pack_codes_a4(const int8_t* dq, int64_t M, int64_t K, uint8_t* dq4, hipStream_t st);
 
 // ---------------------------------------------------------------- device helpers
 #ifdef __HIPCC__

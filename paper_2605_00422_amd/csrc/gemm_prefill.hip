@@ -221,6 +221,8 @@ __device__ __forceinline__ void gd_split3(float x, __bf16& h1, __bf16& h2, __bf1
 // 16-byte position of piece `c16` of row `row` inside its 128-byte LDS row; the XOR key makes
 // the column-wise operand reads conflict free
 __device__ __forceinline__ int gd_key(int row) { return (row ^ (row >> 3)) & 7; }
+// 64-byte rows (nibble-packed codes): rows r, r + 4, r + 8, r + 12 share a bank group, the key separates them
+__device__ __forceinline__ int gd_key4(int row) { return (row >> 2) & 3; }
 
 __device__ __forceinline__ v4i gd_lds_read(uint32_t addr) {
     v4i r;
@@ -234,7 +236,12 @@ constexpr int gd_vmcnt_imm(int n) { return (n & 15) | ((n >> 4) << 14) | (7 << 4
 // GATED: the rows interleave a gate and an up projection, and instead of Y the kernel stores
 // h[t, i] = silu(y[t, 2 i]) * y[t, 2 i + 1] as bf16 (a compile-time variant: the plain kernel's
 // register allocation is not to change)
-template <int NTL, int WM, int WK, int NB, bool GATED = false>
+// A4: the codes arrive nibble-packed (two 4-bit codes per byte, 16-code pieces interleaved in pairs:
+// byte b of packed piece P holds code b of piece 2P in its low and of piece 2P + 1 in its high nibble).
+// A row of a slice is then 64 bytes; a lane reads one packed piece for two contraction steps and
+// moves each nibble to the top of its byte, (x << 4) & 0xf0.. and x & 0xf0..: int8 operands worth 16
+// times the code, so the accumulators are exact multiples of 16 and are shifted down once at the end.
+template <int NTL, int WM, int WK, int NB, bool GATED = false, bool A4 = false>
 __global__ __launch_bounds__(64 * WM * WK) void gemm_prefill_direct_kernel(
     const uint4* __restrict__ bits, int chunks, int row_tiles, const int8_t* __restrict__ q, int M, int K,
     const float* __restrict__ scale, const int32_t* __restrict__ qsum, const __half* __restrict__ alpha,
@@ -248,7 +255,8 @@ __global__ __launch_bounds__(64 * WM * WK) void gemm_prefill_direct_kernel(
     // when slice j + 1 is needed, the operations of slices j + 2 and j + 3 may still be in flight
     // (NB = ring depth, 4 or 2: code tiles in LDS and weight slots in registers)
     static_assert(NB == 4 || NB == 2, "ring depth");
-    constexpr int GD_PER_SLICE = NTL + 8;
+    constexpr int NCOPY = A4 ? 4 : 8;                            // code copies per slice
+    constexpr int GD_PER_SLICE = NTL + NCOPY;
     constexpr int GD_YOUNGER = (NB - 2) * GD_PER_SLICE;
     extern __shared__ __align__(16) char smem[];
     const int tid = threadIdx.x, lane = tid & 63;
@@ -281,23 +289,27 @@ __global__ __launch_bounds__(64 * WM * WK) void gemm_prefill_direct_kernel(
     // its last row (their results are not stored).  Addresses are a wave-uniform base plus a
     // 32-bit lane offset (at most 64 rows apart).
     const int m_first = m_base < M ? m_base : M - 1;
-    const int8_t* abase = q + (int64_t)m_first * K;
-    int avofs[8];
+    const int KB = A4 ? K >> 1 : K;                              // bytes of a code row
+    const int8_t* abase = q + (int64_t)m_first * KB;
+    int avofs[NCOPY];
 #pragma unroll
-    for (int j = 0; j < 8; ++j) {
-        const int row = 8 * j + (lane >> 3);
+    for (int j = 0; j < NCOPY; ++j) {
+        // (nibbles: instruction j moves rows 16j .. 16j+15 of 64 bytes, lane i row i/4, position i%4)
+        const int row = A4 ? 16 * j + (lane >> 2) : 8 * j + (lane >> 3);
         int m = m_base + row;
         if (m > M - 1) m = M - 1;
-        avofs[j] = (m - m_first) * K + (((lane & 7) ^ gd_key(row)) << 4);
+        avofs[j] = A4 ? (m - m_first) * KB + (((lane & 3) ^ gd_key4(row)) << 4)
+                      : (m - m_first) * KB + (((lane & 7) ^ gd_key(row)) << 4);
     }
-    // operand reads: row mt*32 + l32, piece 4*lg + s
+    // operand reads: row mt*32 + l32, piece 4*lg + s (nibbles: packed piece 2*lg + s, s < 2)
     uint32_t rofs[MT][4];
 #pragma unroll
     for (int mt = 0; mt < MT; ++mt)
 #pragma unroll
         for (int s = 0; s < 4; ++s) {
             const int row = mt * 32 + l32;
-            rofs[mt][s] = mytile_lds + row * 128 + ((((4 * lg + s) ^ gd_key(row)) & 7) << 4);
+            rofs[mt][s] = A4 ? mytile_lds + row * 64 + ((((2 * lg + (s & 1)) ^ gd_key4(row)) & 3) << 4)
+                             : mytile_lds + row * 128 + ((((4 * lg + s) ^ gd_key(row)) & 7) << 4);
         }
     // weight rows nt*32 + l32 of this workgroup's columns: 16-row tile, row inside it (tiles past
     // the matrix re-read its last tile); offsets in 16-byte units from a uniform base
@@ -318,9 +330,9 @@ __global__ __launch_bounds__(64 * WM * WK) void gemm_prefill_direct_kernel(
         const int kc = slice_of(ks);
         char* dst = mytile + (ks & (NB - 1)) * GD_TILE;
 #pragma unroll
-        for (int j = 0; j < 8; ++j)
+        for (int j = 0; j < NCOPY; ++j)
             __builtin_amdgcn_global_load_lds(
-                (const __attribute__((address_space(1))) void*)(abase + (int64_t)kc * 128 + avofs[j]),
+                (const __attribute__((address_space(1))) void*)(abase + (int64_t)kc * (A4 ? 64 : 128) + avofs[j]),
                 (__attribute__((address_space(3))) void*)(dst + j * 1024), 16, 0, 0);
     };
     struct Wslot { v4i w[NTL]; };                                // vector values: they stay in registers
@@ -350,18 +362,37 @@ __global__ __launch_bounds__(64 * WM * WK) void gemm_prefill_direct_kernel(
     // Operands of one contraction step: code rows from LDS (asynchronous read, to be followed
     // by settle()), expanded weight bits.
     struct Ops { v4i av[MT]; v4i b[NTL]; };
+    v4i raw[MT];                                                 // nibbles: the packed piece of steps 2h, 2h + 1
     auto prepare = [&](Ops& o, const Wslot& sl, int ks, int s) {
         const uint32_t bo = (uint32_t)((ks & (NB - 1)) * GD_TILE);
+        if constexpr (A4) {
+            if ((s & 1) == 0) {
 #pragma unroll
-        for (int mt = 0; mt < MT; ++mt) o.av[mt] = gd_lds_read(rofs[mt][s] + bo);
+                for (int mt = 0; mt < MT; ++mt) raw[mt] = gd_lds_read(rofs[mt][s >> 1] + bo);
+            }
+        } else {
+#pragma unroll
+            for (int mt = 0; mt < MT; ++mt) o.av[mt] = gd_lds_read(rofs[mt][s] + bo);
+        }
         // slices past the end (the trip count is padded to a multiple of three) contract zeros
         const int mask = ks < nslices ? 0x01010101 : 0;
 #pragma unroll
         for (int nt = 0; nt < NTL; ++nt) o.b[nt] = (sl.w[nt] >> (shamt + s)) & mask;
     };
-    auto settle = [&](Ops& o) {
+    auto settle = [&](Ops& o, int s) {
         static_assert(MT == 2, "operand list of the wait below");
-        asm volatile("s_waitcnt lgkmcnt(0)" : "+v"(o.av[0]), "+v"(o.av[1]));
+        if constexpr (A4) {
+            if ((s & 1) == 0) {
+                asm volatile("s_waitcnt lgkmcnt(0)" : "+v"(raw[0]), "+v"(raw[1]));
+#pragma unroll
+                for (int mt = 0; mt < MT; ++mt) o.av[mt] = (raw[mt] << 4) & 0xf0f0f0f0;
+            } else {
+#pragma unroll
+                for (int mt = 0; mt < MT; ++mt) o.av[mt] = raw[mt] & 0xf0f0f0f0;
+            }
+        } else {
+            asm volatile("s_waitcnt lgkmcnt(0)" : "+v"(o.av[0]), "+v"(o.av[1]));
+        }
     };
     auto contract = [&](const Ops& o) {
 #pragma unroll
@@ -395,7 +426,7 @@ __global__ __launch_bounds__(64 * WM * WK) void gemm_prefill_direct_kernel(
             }
             contract(ops);
             __builtin_amdgcn_sched_barrier(0);
-            settle(following);
+            settle(following, s + 1);                            // (s + 1 = 4: step 0 of the next slice)
             ops = following;
         }
         fetch_w(cur, ks + NB);
@@ -412,7 +443,7 @@ __global__ __launch_bounds__(64 * WM * WK) void gemm_prefill_direct_kernel(
     __builtin_amdgcn_s_waitcnt(gd_vmcnt_imm((NB - 1) * GD_PER_SLICE));  // slice 0 has landed
     landed(w0);
     prepare(ops, w0, 0, 0);
-    settle(ops);
+    settle(ops, 0);
     if constexpr (NB == 4) {
         for (int ks0 = 0; ks0 < nslices; ks0 += 4) {
             step(w0, w1, ks0);
@@ -471,6 +502,12 @@ __global__ __launch_bounds__(64 * WM * WK) void gemm_prefill_direct_kernel(
                         acc[mt][nt][v] += red[((w - 1) * WM + wm) * PER_WAVE + ((mt * NTL + nt) * 16 + v) * 64 + lane];
     }
 
+    if constexpr (A4) {
+#pragma unroll
+        for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+            for (int nt = 0; nt < NTL; ++nt) acc[mt][nt] = acc[mt][nt] >> 4;    // exact: every operand was 16 x code
+    }
     // ---- epilogue.  Accumulator element v of lane (l32, lg): row 8*(v/4) + 4*lg + v%4, column l32.
     // Low-rank term on bf16 MFMA 32x32x16 with exact operand splits (T: three terms, V: two):
     // per 16 ranks one T fragment and NTL V fragments are loaded one step ahead of their use.
@@ -587,7 +624,8 @@ __global__ __launch_bounds__(64 * WM * WK) void gemm_prefill_direct_kernel(
 
 template <int NTL, int WM, int WK, int NB>
 hipError_t launch_direct(const bwla_layer_t* L, const int8_t* dq, const float* dscale, const int32_t* dqsum,
-                         const float* dT, int64_t M, float* dY, int32_t* dacc, hipStream_t st, uint16_t* dH) {
+                         const float* dT, int64_t M, float* dY, int32_t* dacc, hipStream_t st, uint16_t* dH,
+                         bool a4 = false) {
     constexpr int BM = WM * GD_ROWS, BN = NTL * 32;
     const char* blob = (const char*)L->d_blob;
     const int tiles_m = (int)((M + BM - 1) / BM), tiles_n = (int)((L->N + BN - 1) / BN);
@@ -603,6 +641,7 @@ hipError_t launch_direct(const bwla_layer_t* L, const int8_t* dq, const float* d
             L->r, dY, (int)L->N, dacc, tiles_m, tiles_n, dH);
         return hipGetLastError();
     };
+    if (a4) return dH != nullptr ? hipErrorInvalidValue : launch(gemm_prefill_direct_kernel<NTL, WM, WK, NB, false, true>);
     if (dH != nullptr) return launch(gemm_prefill_direct_kernel<NTL, WM, WK, NB, true>);
     return launch(gemm_prefill_direct_kernel<NTL, WM, WK, NB, false>);
 }
@@ -622,7 +661,7 @@ bool bwla_gemm_prefill_streams(const bwla_layer_t* L) { return L->N >= 32 && (L-
 
 hipError_t bwla_launch_gemm_prefill(const bwla_layer_t* L, const int8_t* dq, const float* dscale,
                                     const int32_t* dqsum, const float* dT, int64_t M, float* dY,
-                                    int32_t* dacc, hipStream_t st, uint16_t* dH) {
+                                    int32_t* dacc, hipStream_t st, uint16_t* dH, bool a4) {
     const int64_t N = L->N;
     if (bwla_gemm_prefill_streams(L)) {
         // register-streaming kernel.  Large batches: four wavefronts stacked along the tokens,
@@ -634,8 +673,8 @@ hipError_t bwla_launch_gemm_prefill(const bwla_layer_t* L, const int8_t* dq, con
         const int64_t big = std::min(tiles_for(M, N, 256, 160), tiles_for(M, N, 256, 128));
         if (M > 128 && big > 72) {
             const double d160 = wave_eff(tiles_for(M, N, 256, 160)), d128 = wave_eff(tiles_for(M, N, 256, 128));
-            if (d160 >= d128) return launch_direct<5, 4, 1, 4>(L, dq, dscale, dqsum, dT, M, dY, dacc, st, dH);
-            return launch_direct<4, 4, 1, 4>(L, dq, dscale, dqsum, dT, M, dY, dacc, st, dH);
+            if (d160 >= d128) return launch_direct<5, 4, 1, 4>(L, dq, dscale, dqsum, dT, M, dY, dacc, st, dH, a4);
+            return launch_direct<4, 4, 1, 4>(L, dq, dscale, dqsum, dT, M, dY, dacc, st, dH, a4);
         }
         // Few tokens (or few large tiles): the kernel is bound by how often the code rows are re-read (every workgroup
         // reads all K of its tokens) and by how many wavefronts are in flight.  With t tiles of
@@ -647,13 +686,13 @@ hipError_t bwla_launch_gemm_prefill(const bwla_layer_t* L, const int8_t* dq, con
         // 8192 -> 28672 at 64 (896) 62.0 / 42.2 / 31.2.
         const int64_t tiles = ((M + 63) / 64) * ((N + 31) / 32);
         const int64_t cus = bwla_device_cus();
-        if (tiles <= cus) return launch_direct<1, 1, 4, 4>(L, dq, dscale, dqsum, dT, M, dY, dacc, st, dH);
-        if (tiles <= 2 * cus) return launch_direct<2, 1, 4, 4>(L, dq, dscale, dqsum, dT, M, dY, dacc, st, dH);
-        return launch_direct<1, 1, 1, 4>(L, dq, dscale, dqsum, dT, M, dY, dacc, st, dH);
+        if (tiles <= cus) return launch_direct<1, 1, 4, 4>(L, dq, dscale, dqsum, dT, M, dY, dacc, st, dH, a4);
+        if (tiles <= 2 * cus) return launch_direct<2, 1, 4, 4>(L, dq, dscale, dqsum, dT, M, dY, dacc, st, dH, a4);
+        return launch_direct<1, 1, 1, 4>(L, dq, dscale, dqsum, dT, M, dY, dacc, st, dH, a4);
     }
     // shapes the streaming kernel does not take (K not a multiple of 128, fewer than 32 channels):
     // LDS-tiled kernel, 64 x 128 or 128 x 128 tiles (it does not gate: the caller goes through Y)
-    if (dH != nullptr) return hipErrorInvalidValue;
+    if (dH != nullptr || a4) return hipErrorInvalidValue;
     if (M <= 64) return launch_cfg<1, 2, 2, 2>(L, dq, dscale, dqsum, dT, M, dY, dacc, st);
     return launch_cfg<2, 2, 2, 2>(L, dq, dscale, dqsum, dT, M, dY, dacc, st);
 }

@@ -126,6 +126,23 @@ __global__ __launch_bounds__(256) void code_sums_kernel(const int8_t* __restrict
     if (threadIdx.x == 0) qsum[t] = red[0] + red[1] + red[2] + red[3];
 }
 
+// Nibble packing of 4-bit codes: 32 codes (two 16-code pieces) become 16 bytes, byte b holding code b
+// of the first piece in its low and code b of the second piece in its high nibble.  One thread per
+// 16 output bytes.
+__global__ __launch_bounds__(256) void pack_codes_a4_kernel(const int8_t* __restrict__ q, int64_t pieces,
+                                                            uint8_t* __restrict__ q4) {
+    const int64_t p = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (p >= pieces) return;
+    const uint4 lo = *reinterpret_cast<const uint4*>(q + p * 32);
+    const uint4 hi = *reinterpret_cast<const uint4*>(q + p * 32 + 16);
+    uint4 o;
+    o.x = (lo.x & 0x0f0f0f0fu) | ((hi.x << 4) & 0xf0f0f0f0u);
+    o.y = (lo.y & 0x0f0f0f0fu) | ((hi.y << 4) & 0xf0f0f0f0u);
+    o.z = (lo.z & 0x0f0f0f0fu) | ((hi.z << 4) & 0xf0f0f0f0u);
+    o.w = (lo.w & 0x0f0f0f0fu) | ((hi.w << 4) & 0xf0f0f0f0u);
+    *reinterpret_cast<uint4*>(q4 + p * 16) = o;
+}
+
 }  // namespace
 
 
@@ -316,6 +333,12 @@ size_t bwla_split_rotation_bytes(const bwla_layer_t* L, const bwla_psp_plan& pla
     // 34.5 against 32.0; with more tokens the one-workgroup-per-token kernel keeps the chip busy
     if (M * rs.G + pblocks > 2 * bwla_device_cus()) return 0;
     return (size_t)(M * L->K + 2 * M * rs.E + M) * sizeof(float);     // values, extremes, per-token code offset
+}
+
+hipError_t bwla_launch_pack_codes_a4(const int8_t* dq, int64_t M, int64_t K, uint8_t* dq4, hipStream_t st) {
+    const int64_t pieces = M * (K / 32);
+    pack_codes_a4_kernel<<<dim3((unsigned)((pieces + 255) / 256)), dim3(256), 0, st>>>(dq, pieces, dq4);
+    return hipGetLastError();
 }
 
 hipError_t bwla_launch_code_sums(const int8_t* dq, int64_t M, int64_t K, int32_t* dqsum, hipStream_t st) {

@@ -184,6 +184,61 @@ def test_other_activation_widths(bits, M, K, n1, n2, N, r, xd):
     print(run_case(cfg, act_bits=bits), flush=True)
 
 
+@pytest.mark.parametrize("M,K,n1,n2,N,r", [
+    (2048, 25600, 160, 160, 5120, 64),   # the prefill configuration's shape: 256 x 160 tiles
+    (300, 1152, 36, 32, 200, 20),        # ragged token and channel tiles, 9 slices, one wavefront per tile
+    (64, 8192, 128, 64, 8192, 64),       # four wavefronts share a tile and split K
+    (130, 4096, 64, 64, 2500, 0),        # no low-rank part
+])
+def test_nibble_packed_a4_codes(M, K, n1, n2, N, r):
+    """W1A4 with two codes per byte (paper Table 3): the packing kernel against the oracle's layout,
+    bit for bit, and the GEMM on packed codes against the GEMM on the same codes in int8 -- accumulators
+    and outputs identical -- which the oracle's rows then check by the usual criteria."""
+    from parity_util import pack_on_gpu, x_on_gpu, check_output, DEV
+    from oracle import bwla_oracle as orc
+    from paper_2605_00422_amd import binding as B
+    cfg = syn.LayerConfig(f"a4n_{M}_{K}_{N}", M, K, n1, n2, N, r, "bf16", max(1, K // 100), 20.0, seed=31)
+    d = syn.make_layer(cfg)
+    layer = pack_on_gpu(d)
+    X = x_on_gpu(d)
+    act = B.Activations(layer, M)
+    B.rotate_quant(layer, X, act, 4)
+    Y8 = torch.empty((M, N), dtype=torch.float32, device=DEV)
+    a8 = torch.empty((M, N), dtype=torch.int32, device=DEV)
+    B.linear_forward(layer, act, Y8, a8)
+    q4 = B.pack_codes_a4(act.q)
+    Y4 = torch.full((M, N), float("nan"), dtype=torch.float32, device=DEV)
+    a4 = torch.full((M, N), -1, dtype=torch.int32, device=DEV)
+    B.linear_forward_a4(layer, q4, act, Y4, a4)
+    torch.cuda.synchronize()
+    q = act.q.cpu().numpy()
+    assert q.min() >= -7 and q.max() <= 7
+    assert np.array_equal(q4.cpu().numpy(), orc.pack_nibbles(q)), "packed layout differs from the oracle's"
+    assert torch.equal(a4, a8), "accumulators on packed codes differ"
+    assert torch.equal(Y4, Y8), "outputs on packed codes differ"
+    # the oracle on a sample of rows, from the GPU's own codes: exact accumulators, output by criterion 3
+    rows = _sample_rows(M, 16, seed=5)
+    sgn, alpha = orc.binarize_rows(d.W)
+    assert np.array_equal(a4[torch.from_numpy(rows).to(DEV)].cpu().numpy().astype(np.int64), orc.binary_gemm(q[rows], sgn))
+    ref = orc.forward_rows(d.X, d.R1, d.R2, sgn, orc.to_fp16(alpha), d.U if r else None, d.V if r else None, rows, act_bits=4)
+    check_output(Y4[torch.from_numpy(rows).to(DEV)].cpu().numpy(), ref["Y"])
+
+
+def test_nibble_packed_a4_refusals():
+    from parity_util import pack_on_gpu, DEV
+    from paper_2605_00422_amd import binding as B
+    cfg = syn.LayerConfig("a4n_refuse", 8, 1024, 32, 32, 64, 0, "bf16", 4, 20.0, seed=32)
+    layer = pack_on_gpu(syn.make_layer(cfg))
+    act = B.Activations(layer, 8)
+    q4 = torch.zeros((8, 512), dtype=torch.uint8, device=DEV)
+    Y = torch.empty((8, 64), dtype=torch.float32, device=DEV)
+    with pytest.raises(B.BwlaError) as e:
+        B.linear_forward_a4(layer, q4, act, Y)          # decode batch: the decode kernels take bytes
+    assert e.value.status == 5
+    with pytest.raises(B.BwlaError):
+        B.pack_codes_a4(torch.zeros((2, 48), dtype=torch.int8, device=DEV))     # K not a multiple of 32
+
+
 def test_row_shift_with_eight_bit_codes():
     from parity_util import run_case
     cfg = syn.LayerConfig("shift_a8", 3, 2048, 32, 64, 300, 16, "bf16", 20, 20.0, seed=14)

@@ -638,3 +638,24 @@ def test_inputs_are_on_their_storage_grids():
     f = syn.make_layer(cfg)
     assert np.array_equal(e.X, f.X) and np.array_equal(e.W, f.W)
     assert len(e.outlier_idx) == 2
+
+
+def test_nibble_packing_layout_by_hand_and_round_trip():
+    """Two 4-bit codes per byte: byte b of a run of 32 codes = code b (low nibble), code 16 + b (high
+    nibble), two's complement -- written out for one run by hand, then the inverse on random codes."""
+    q = np.zeros((1, 32), dtype=np.int64)
+    q[0, 0], q[0, 16] = 1, 2          # byte 0 = 0x21
+    q[0, 1], q[0, 17] = -1, 7         # byte 1 = 0x7f
+    q[0, 15], q[0, 31] = -8, -7       # byte 15 = 0x98
+    p = orc.pack_nibbles(q)
+    assert p.shape == (1, 16) and p.dtype == np.uint8
+    assert p[0, 0] == 0x21 and p[0, 1] == 0x7F and p[0, 15] == 0x98 and not np.any(p[0, 2:15])
+    rng = np.random.default_rng(5)
+    q = rng.integers(-7, 8, size=(5, 96))
+    p = orc.pack_nibbles(q)
+    assert p.shape == (5, 48) and np.array_equal(orc.unpack_nibbles(p), q)
+    # the second run starts at byte 16 and pairs codes 32.. with 48..
+    assert p[2, 16] == ((q[2, 32] & 0xF) | ((q[2, 48] & 0xF) << 4))
+    for bad in (np.full((1, 32), 8), np.zeros((1, 48), dtype=np.int64)):
+        with pytest.raises(ValueError):
+            orc.pack_nibbles(bad)
