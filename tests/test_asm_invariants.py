@@ -18,7 +18,9 @@ CSRC = os.path.join(ROOT, "paper_2605_00422_amd", "csrc")
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 # (channel tiles per wavefront, wavefronts along the tokens, wavefronts along K, ring depth) of
 # every instantiation that is launched
-VARIANTS = [(1, 1, 1, 4), (1, 1, 4, 4), (2, 1, 4, 4), (4, 4, 1, 4), (5, 4, 1, 4)]
+# every instantiation that is launched; the last entry: codes nibble-packed (4 code copies per slice instead of 8)
+SHAPES = [(1, 1, 1, 4), (1, 1, 4, 4), (2, 1, 4, 4), (4, 4, 1, 4), (5, 4, 1, 4)]
+VARIANTS = [(*v, a4) for a4 in (0, 1) for v in SHAPES]
 
 
 @pytest.fixture(scope="module")
@@ -33,11 +35,12 @@ def kernels():
         subprocess.run(cmd, check=True, capture_output=True)
         text = open(out).read().split("\n")
     found = {}
-    for ntl, wm, wk, nb in VARIANTS:
-        pat = re.compile(rf"^_ZN.*gemm_prefill_direct_kernelILi{ntl}ELi{wm}ELi{wk}ELi{nb}E.*:")
+    for ntl, wm, wk, nb, a4 in VARIANTS:
+        # (the two trailing template arguments: not gated, nibble-packed or not)
+        pat = re.compile(rf"^_ZN.*gemm_prefill_direct_kernelILi{ntl}ELi{wm}ELi{wk}ELi{nb}ELb0ELb{a4}E.*:")
         start = next(i for i, l in enumerate(text) if pat.match(l))
         end = next(i for i in range(start, len(text)) if "s_endpgm" in text[i])
-        found[(ntl, wm, wk, nb)] = text[start:end + 1]
+        found[(ntl, wm, wk, nb, a4)] = text[start:end + 1]
     return found
 
 
@@ -48,27 +51,28 @@ def _main_loop(lines):
     return start, end
 
 
-@pytest.mark.parametrize("ntl,wm,wk,nb", VARIANTS)
-def test_streaming_gemm_loop_structure(kernels, ntl, wm, wk, nb):
-    lines = kernels[(ntl, wm, wk, nb)]
+@pytest.mark.parametrize("ntl,wm,wk,nb,a4", VARIANTS)
+def test_streaming_gemm_loop_structure(kernels, ntl, wm, wk, nb, a4):
+    lines = kernels[(ntl, wm, wk, nb, a4)]
+    copies = 4 if a4 else 8
     start, end = _main_loop(lines)
     loop = lines[start:end + 1]
     code = [l.strip() for l in loop if l.strip() and not l.strip().startswith((";", "."))]
     # nb slices per trip: nb x (NTL weight loads + 8 asynchronous code copies), nb x 4 x 2 NTL MFMAs
-    assert sum(l.startswith("global_load_lds_dwordx4") for l in code) == 8 * nb
+    assert sum(l.startswith("global_load_lds_dwordx4") for l in code) == copies * nb
     assert sum(l.startswith("global_load_dwordx4") for l in code) == nb * ntl
     assert sum(l.startswith("v_mfma_i32_32x32x32_i8") for l in code) == nb * 4 * 2 * ntl
     # the only vector-memory waits are the hand-counted ones, with the documented count
     waits = [l for l in code if l.startswith("s_waitcnt") and "vmcnt" in l]
-    assert waits == [f"s_waitcnt vmcnt({(nb - 2) * (ntl + 8)})"] * nb
+    assert waits == [f"s_waitcnt vmcnt({(nb - 2) * (ntl + copies)})"] * nb
     # no other memory traffic and no register shuffling of ring or accumulator registers
     assert not any(l.startswith(("scratch_", "global_store", "buffer_", "flat_")) for l in code)
     assert not any(l.startswith(("v_mov_b32", "v_accvgpr")) for l in code)
 
 
-@pytest.mark.parametrize("ntl,wm,wk,nb", VARIANTS)
-def test_registers_of_loads_in_flight_stay_reserved(kernels, ntl, wm, wk, nb):
-    lines = kernels[(ntl, wm, wk, nb)]
+@pytest.mark.parametrize("ntl,wm,wk,nb,a4", VARIANTS)
+def test_registers_of_loads_in_flight_stay_reserved(kernels, ntl, wm, wk, nb, a4):
+    lines = kernels[(ntl, wm, wk, nb, a4)]
     start, end = _main_loop(lines)
     dest = set()
     for l in lines[start:end]:
