@@ -306,16 +306,21 @@ __global__ __launch_bounds__(DL_THREADS) void decode_layer_kernel(const uint16_t
     // wavefront polls (bounded; the producers wait for nobody).
     constexpr int NE = (DL_SLICES * RPU + 63) / 64;
     unsigned long long ent[NE > 0 ? NE : 1];
-    auto poll = [&](unsigned tag) -> bool {
+    // (two halves: the request, and -- behind the contraction -- the look at what came back, so that
+    // the device-scope round trip is not waited for before the contraction starts)
+    auto poll_request = [&](unsigned tag) {
         const unsigned long long* tx = reinterpret_cast<const unsigned long long*>(a.sync + 256);
-        bool ok = true;
 #pragma unroll
         for (int i = 0; i < NE; ++i) {
             const int idx = lane + 64 * i, sl = idx / (RPU > 0 ? RPU : 1), j = idx - sl * RPU;
             ent[i] = (unsigned long long)tag << 32;
             if (sl < DL_SLICES) ent[i] = __hip_atomic_load(tx + sl * 16 * DL_MAXJTU + j, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-            ok = ok && (unsigned)(ent[i] >> 32) == tag;
         }
+    };
+    auto poll_check = [&](unsigned tag) -> bool {
+        bool ok = true;
+#pragma unroll
+        for (int i = 0; i < NE; ++i) ok = ok && (unsigned)(ent[i] >> 32) == tag;
         return __all(ok);
     };
 
@@ -451,7 +456,7 @@ __global__ __launch_bounds__(DL_THREADS) void decode_layer_kernel(const uint16_t
         }
         bool t_here = false;
         const unsigned tag = JTU > 0 && wave == 4 ? reinterpret_cast<const unsigned*>(red)[14] + 1u : 0u;
-        if (JTU > 0 && wave == 4) t_here = poll(tag);
+        if (JTU > 0 && wave == 4) poll_request(tag);
         // workgroup 0 moves the epoch on once every workgroup has read it: its last wavefront asks
         // for the eight arrival counts here and looks at them behind the contraction
         const bool bumps = JTU > 0 && wave == 7 && blk == 0;
@@ -523,9 +528,11 @@ __global__ __launch_bounds__(DL_THREADS) void decode_layer_kernel(const uint16_t
             if (lane == 0) __hip_atomic_store(a.sync, epoch + 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         }
         if (JTU > 0 && wave == 4) {
+            t_here = poll_check(tag);                  // what the request before the contraction brought
             for (int spin = 0; !t_here && spin < DL_SPIN_LIMIT; ++spin) {
                 __builtin_amdgcn_s_sleep(8);
-                t_here = poll(tag);
+                poll_request(tag);
+                t_here = poll_check(tag);
             }
 #pragma unroll
             for (int i = 0; i < NE; ++i) {
