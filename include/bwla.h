@@ -72,7 +72,8 @@ typedef enum {
  *   R1     n1 x n1 fp32 row-major;  R2  n2 x n2 fp32 row-major
  *   R1p, R2p  the same factors transposed and split into three bfloat16 terms each (their sum is
  *          the fp32 value exactly), zero padded: operand layout of the bf16-MFMA rotation
- *   Rd     only for factor pairs that are multiples of 32 up to 160 (off_Rd = 0 otherwise): the
+ *   Rd     only for factor pairs that are multiples of 32, n1 up to 256 and n2 up to 160 (off_Rd = 0
+ *          otherwise): the
  *          factors once more, in the order in which the kernels with resident factors read them, one
  *          contiguous KiB per MFMA operand -- for pairs of 32 or 64 R2 as three bfloat16 terms (the
  *          single-launch decode kernel's), then R1 and R2 as two fp16 terms of 256 R (22 bits)

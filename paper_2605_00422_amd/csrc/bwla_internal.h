@@ -32,13 +32,13 @@ inline uint64_t bwla_factor_planes_bytes(int n) {
 }
 
 // Factor planes in MFMA operand order (one contiguous KiB per operand), stored for factor pairs
-// that are multiples of 32 up to 160 (0 bytes otherwise), three parts:
+// that are multiples of 32, n1 up to 256 and n2 up to 160 (0 bytes otherwise), three parts:
 //   R2d  three bf16 terms of R2, (n2 / 16) strips x (n2 / 32) steps x 3 KiB: only for the pairs the
 //        single-launch decode kernel takes (n1 of 32, 64 or 128, n2 of 32 or 64)
 //   R1h  two fp16 terms of 256 R1, (n1 / 32) steps x 2 x (n1 / 16) KiB
 //   R2h  two fp16 terms of 256 R2, (n2 / 16) strips x (n2 / 32) steps x 2 KiB
 inline bool bwla_planes_shape_ok(int n1, int n2) {
-    return n1 >= 32 && n2 >= 32 && n1 <= 160 && n2 <= 160 && (n1 & 31) == 0 && (n2 & 31) == 0;
+    return n1 >= 32 && n2 >= 32 && n1 <= 256 && n2 <= 160 && (n1 & 31) == 0 && (n2 & 31) == 0;
 }
 inline uint64_t bwla_decode_planes_r2_bytes(int n1, int n2) {
     const bool ok = (n1 == 32 || n1 == 64 || n1 == 128) && (n2 == 32 || n2 == 64);

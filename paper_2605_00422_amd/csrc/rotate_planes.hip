@@ -37,7 +37,7 @@ struct RpArgs {
     float* tmode; int tp; float qmax; int asym, shift;
 };
 
-template <int N1, int N2, int G>
+template <int N1, int N2, int G, bool STREAM = false>
 struct RpShape {
     static constexpr int K = N1 * N2, AT = N1 / 16, K1 = N2 / 32, CH2 = N1 / 32, STRIPS = N2 / 16;
     static constexpr int GPR = N2 / 8;                  // 16-byte granules (8 values) per token row
@@ -46,15 +46,17 @@ struct RpShape {
     static constexpr int THREADS = TG * G;
     static constexpr int ITEMS = N1 * GPR;              // granules per token
     static constexpr int NI = (ITEMS + TG - 1) / TG;    // granules per thread
-    static constexpr int R1_BYTES = CH2 * 2 * AT * 1024;
+    static constexpr int CHUNK_BYTES = 2 * AT * 1024;   // both terms of one 32-deep step of R1
+    static constexpr int R1_BYTES = STREAM ? 2 * CHUNK_BYTES : CH2 * CHUNK_BYTES;
     static constexpr int XT_BYTES = N1 * PITCH;
     static constexpr int RED_WORDS = 64;                // per group: [0,16) maxima, [16,32) minima, [32,48) token maxima, [48,64) code sums
     static constexpr size_t LDS = (size_t)R1_BYTES + (size_t)G * XT_BYTES + (size_t)G * RED_WORDS * 4;
 };
 
-template <int N1, int N2, int G>
+template <int N1, int N2, int G, bool STREAM = false>
 __global__ __launch_bounds__((N2 / 16) * 64 * G) void rotate_planes_kernel(RpArgs a) {
-    using S = RpShape<N1, N2, G>;
+    using S = RpShape<N1, N2, G, STREAM>;
+    static_assert(!STREAM || G == 1, "streamed R1 terms: one token group");
     constexpr int K = S::K, AT = S::AT, K1 = S::K1, CH2 = S::CH2, STRIPS = S::STRIPS, GPR = S::GPR, PITCH = S::PITCH;
     constexpr int TG = S::TG, NI = S::NI, ITEMS = S::ITEMS;
     extern __shared__ __align__(16) char lds[];
@@ -66,11 +68,25 @@ __global__ __launch_bounds__((N2 / 16) * 64 * G) void rotate_planes_kernel(RpArg
     float* red = reinterpret_cast<float*>(lds + S::R1_BYTES + G * S::XT_BYTES) + grp * S::RED_WORDS;
     int* redi = reinterpret_cast<int*>(red) + 48;
 
-    // ---- R1 terms: global -> LDS asynchronously, one KiB per wavefront-wide request
+    // ---- R1 terms: global -> LDS asynchronously, one KiB per wavefront-wide request.  Resident: all
+    // of them, once.  STREAM (R1 too large for LDS): the 2 AT blocks of one 32-deep step at a time into
+    // one of two buffers, step g = (token round) * CH2 + ch into buffer g & 1, requested while the
+    // step before it is worked on.
     constexpr int NB1 = CH2 * 2 * AT, NW = STRIPS * G;
-    for (int b = wv; b < NB1; b += NW)
-        __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(a.R1h + (b * 64 + lane) * 8),
-                                         (__attribute__((address_space(3))) void*)(r1 + b * 1024), 16, 0, 0);
+    auto request_chunk = [&](int g) {
+        const int ch = g % CH2;
+        for (int b = wv; b < 2 * AT; b += NW)
+            __builtin_amdgcn_global_load_lds(
+                (const __attribute__((address_space(1))) void*)(a.R1h + ((ch * 2 * AT + b) * 64 + lane) * 8),
+                (__attribute__((address_space(3))) void*)(r1 + (g & 1) * S::CHUNK_BYTES + b * 1024), 16, 0, 0);
+    };
+    if constexpr (STREAM) {
+        request_chunk(0);
+    } else {
+        for (int b = wv; b < NB1; b += NW)
+            __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(a.R1h + (b * 64 + lane) * 8),
+                                             (__attribute__((address_space(3))) void*)(r1 + b * 1024), 16, 0, 0);
+    }
     // ---- R2 terms of my strip, kept in registers over all tokens
     v8h_r bh[K1], bl[K1];
 #pragma unroll
@@ -159,7 +175,10 @@ __global__ __launch_bounds__((N2 / 16) * 64 * G) void rotate_planes_kernel(RpArg
             return *reinterpret_cast<const v4i*>(xt + (32 * ch + 16 * half + li) * PITCH + lg * 16 + kb * 64);
         };
         auto ld_b = [&](int ch, int term, int tc) -> v4i {
-            return *reinterpret_cast<const v4i*>(r1 + ((ch * 2 + term) * AT + tc) * 1024 + lane * 16);
+            if constexpr (STREAM)
+                return *reinterpret_cast<const v4i*>(r1 + ((j * CH2 + ch) & 1) * S::CHUNK_BYTES + (term * AT + tc) * 1024 + lane * 16);
+            else
+                return *reinterpret_cast<const v4i*>(r1 + ((ch * 2 + term) * AT + tc) * 1024 + lane * 16);
         };
         v4i na0 = ld_a(0, 0, 0), na1 = ld_a(0, 0, 1);
 #pragma unroll
@@ -170,7 +189,7 @@ __global__ __launch_bounds__((N2 / 16) * 64 * G) void rotate_planes_kernel(RpArg
             for (int kb = 0; kb < K1; ++kb) {
                 const v8h_r a0 = __builtin_bit_cast(v8h_r, na0), a1 = __builtin_bit_cast(v8h_r, na1);
                 if (kb + 1 < K1) { na0 = ld_a(ch, kb + 1, 0); na1 = ld_a(ch, kb + 1, 1); }
-                else { nbh = ld_b(ch, 0, 0); nbl = ld_b(ch, 1, 0); }
+                else if (!STREAM) { nbh = ld_b(ch, 0, 0); nbl = ld_b(ch, 1, 0); }
                 z0 = __builtin_amdgcn_mfma_f32_16x16x32_f16(a0, bl[kb], z0, 0, 0, 0);      // small term first
                 z1 = __builtin_amdgcn_mfma_f32_16x16x32_f16(a1, bl[kb], z1, 0, 0, 0);
                 z0 = __builtin_amdgcn_mfma_f32_16x16x32_f16(a0, bh[kb], z0, 0, 0, 0);
@@ -178,6 +197,14 @@ __global__ __launch_bounds__((N2 / 16) * 64 * G) void rotate_planes_kernel(RpArg
             }
             // lane (li, lg) holds Z[a = 32 ch + 4 lg + v (z0), 32 ch + 16 + 4 lg + v (z1)][d = li]: the eight
             // contraction positions of an A operand, in the order the R1 terms were stored in.
+            if constexpr (STREAM) {
+                // this step's R1 terms have landed, everybody's share; the other buffer is free (all are
+                // past the step before): the next step's terms go there while this one is worked on
+                __builtin_amdgcn_s_waitcnt(0);
+                bwla_lds_barrier();
+                if (j + 1 < rounds || ch + 1 < CH2) request_chunk(j * CH2 + ch + 1);
+                nbh = ld_b(ch, 0, 0); nbl = ld_b(ch, 1, 0);
+            }
             v8h_r ah, al;
 #pragma unroll
             for (int e = 0; e < 8; ++e) {
@@ -268,16 +295,16 @@ __global__ __launch_bounds__((N2 / 16) * 64 * G) void rotate_planes_kernel(RpArg
     }
 }
 
-template <int N1, int N2, int G>
+template <int N1, int N2, int G, bool STREAM = false>
 hipError_t launch_planes(const RpArgs& a, int cus, hipStream_t st) {
-    using S = RpShape<N1, N2, G>;
+    using S = RpShape<N1, N2, G, STREAM>;
     static_assert(S::LDS <= RQ_LDS_LIMIT, "the factors and the token rows have to fit LDS");
     static_assert(S::STRIPS <= 16 && N1 % 32 == 0 && N2 % 32 == 0, "shape outside the kernel's layout");
-    hipError_t e = bwla_ensure_lds((const void*)rotate_planes_kernel<N1, N2, G>, S::LDS);
+    hipError_t e = bwla_ensure_lds((const void*)rotate_planes_kernel<N1, N2, G, STREAM>, S::LDS);
     if (e != hipSuccess) return e;
     int64_t grid = (a.M + G - 1) / G;
     if (grid > cus) grid = cus;
-    rotate_planes_kernel<N1, N2, G><<<dim3((unsigned)grid), dim3(S::THREADS), S::LDS, st>>>(a);
+    rotate_planes_kernel<N1, N2, G, STREAM><<<dim3((unsigned)grid), dim3(S::THREADS), S::LDS, st>>>(a);
     return hipGetLastError();
 }
 
@@ -307,6 +334,7 @@ hipError_t bwla_launch_rotate_planes(const bwla_layer_t* L, const void* dX, int 
     if (n1 == 160 && n2 == 160) e = launch_planes<160, 160, 1>(a, cus, st);
     else if (n1 == 128 && n2 == 64) e = launch_planes<128, 64, 4>(a, cus, st);
     else if (n1 == 64 && n2 == 64) e = launch_planes<64, 64, 4>(a, cus, st);
+    else if (n1 == 224 && n2 == 128) e = launch_planes<224, 128, 1, true>(a, cus, st);     // R1 terms: 196 KB, streamed
     else return hipSuccess;
     if (e == hipSuccess) *done = true;
     return e;

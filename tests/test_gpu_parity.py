@@ -85,6 +85,7 @@ def test_looping_rotation_two_tokens_at_a_time_fewer_pairs_than_cus():
     (600, 4096, 64, 64, 40, 8, 8, False),      # 8-bit codes
     (515, 8192, 128, 64, 40, 8, 6, True),      # row shift: the shift entry of T from the looping kernel
     (512, 2048, 32, 64, 40, 0, 6, False),      # exactly two tokens per CU, no low-rank part: no kernel built, the older path
+    (530, 28672, 224, 128, 40, 8, 6, False),   # R1 too large for LDS: its terms streamed step by step, seven steps (odd: buffers swap roles per token)
 ])
 def test_resident_factor_rotation_many_tokens(M, K, n1, n2, N, r, bits, centered):
     """At least two bf16 tokens per CU and factors whose operand-order planes fit LDS: the looping
