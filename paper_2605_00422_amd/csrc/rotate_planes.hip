@@ -310,7 +310,7 @@ hipError_t launch_planes(const RpArgs& a, int cus, hipStream_t st) {
 
 }  // namespace
 
-// *done = false (nothing launched) when the shape has no kernel here: bf16 tokens, at least two
+// *done = false (nothing launched) when the shape has no kernel here: bf16 tokens, at least one
 // per CU, a factor pair for which the operand-order planes exist and a kernel was built.
 hipError_t bwla_launch_rotate_planes(const bwla_layer_t* L, const void* dX, int xdtype, int64_t M, int8_t* dq,
                                      float* dscale, int32_t* dqsum, float* dT, int act_bits, hipStream_t st,
@@ -319,7 +319,7 @@ hipError_t bwla_launch_rotate_planes(const bwla_layer_t* L, const void* dX, int 
     const int n1 = L->n1, n2 = L->n2;
     if (xdtype != BWLA_X_BF16 || L->off_Rd == 0) return hipSuccess;
     const int cus = bwla_device_cus();
-    if (M < 2 * (int64_t)cus) return hipSuccess;
+    if (M < (int64_t)cus) return hipSuccess;
     const char* blob = (const char*)L->d_blob;
     RpArgs a;
     a.X = (const uint16_t*)dX; a.M = M;
