@@ -11,7 +11,8 @@ ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB_PATH = os.path.join(HERE, "libbwla.so")
 SOURCES = ["api.hip", "pack.hip", "rotate_quant.hip", "gemm_decode.hip", "gemm_decode_bs.hip", "gemm_prefill.hip", "psp_prefill.hip", "decode_layer.hip",
-           "probe.hip", "rotate_planes.hip"]
+           "probe.hip", "rotate_planes.hip",
+           "quantizer_api.hip", "quantizer_gemm.hip", "quantizer_rows.hip", "quantizer_jacobi.hip"]
 
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-fvisibility=hidden",

@@ -23,10 +23,15 @@ def lib():
 
 
 def test_exports_match_header(lib):
-    text = open(os.path.join(ROOT, "include", "bwla.h")).read()
-    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
-    declared = set(re.findall(r"\b(bwla_[a-z_0-9]+)\s*\(", text))
-    assert declared == set(B.EXPORTS)
+    from paper_2605_00422_amd import quantizer_binding as QB
+    QB.load()
+    declared = set()
+    for header, names in (("bwla.h", B.EXPORTS), ("bwla_quantizer.h", QB.EXPORTS)):
+        text = open(os.path.join(ROOT, "include", header)).read()
+        text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+        here = set(re.findall(r"\b(bwla_[a-z_0-9]+)\s*\(", text))
+        assert here == set(names), header
+        declared |= here
     for name in declared:
         assert hasattr(lib, name), name
     # and nothing else of the library's own is visible from outside
@@ -189,3 +194,40 @@ def test_swiglu_entry_points_check_arguments_first(lib):
     assert lib.bwla_linear_forward_swiglu(None, fake, fake, fake, fake, 1, fake, None, 0, None) == B.BWLA_ERR_NULL
     assert lib.bwla_linear_forward_swiglu(byref(desc), fake, fake, fake, fake, 1, fake, None, 0, None) == \
         B.BWLA_ERR_NULL                                   # zeroed descriptor: no blob
+
+
+def test_quantizer_entry_points_check_arguments_first(lib):
+    """Offline quantizer (include/bwla_quantizer.h): shapes, limits, null pointers, alignment and the
+    scratch size are checked on the host; the scratch holds at least the five n x m fp64 arrays."""
+    from paper_2605_00422_amd import quantizer_binding as QB
+    QB.load()
+    out = c_size_t()
+    assert lib.bwla_quantizer_workspace_size(100, 512, 16, 32, 8, byref(out)) == B.BWLA_OK
+    assert out.value >= 5 * 100 * 512 * 8
+    assert QB.workspace_size(100, 512, 16, 32, 8) == out.value
+    assert lib.bwla_quantizer_workspace_size(100, 512, 16, 32, 8, None) == B.BWLA_ERR_NULL
+    assert lib.bwla_quantizer_workspace_size(100, 512, 16, 16, 8, byref(out)) == B.BWLA_ERR_SHAPE      # n1 n2 != m
+    assert lib.bwla_quantizer_workspace_size(4, 512, 16, 32, 8, byref(out)) == B.BWLA_ERR_SHAPE        # k > n
+    assert lib.bwla_quantizer_workspace_size(100, 512, 16, 32, -1, byref(out)) == B.BWLA_ERR_SHAPE
+    assert lib.bwla_quantizer_workspace_size(1000, 512 * 512, 512, 512, 8, byref(out)) == B.BWLA_ERR_UNSUPPORTED
+    assert lib.bwla_quantizer_workspace_size(1000, 512, 16, 32, 129, byref(out)) == B.BWLA_ERR_UNSUPPORTED
+    assert lib.bwla_quantizer_workspace_size(70000, 512, 16, 32, 8, byref(out)) == B.BWLA_ERR_UNSUPPORTED
+    fake, odd = c_void_p(0x1000), c_void_p(0x1008)
+    big = 1 << 40
+    assert lib.bwla_q_okt_rows(None, fake, fake, 8, fake, fake, 100, 512, 16, 32, fake, None, fake, big, None) == B.BWLA_ERR_NULL
+    assert lib.bwla_q_okt_rows(fake, None, fake, 8, fake, fake, 100, 512, 16, 32, fake, None, fake, big, None) == B.BWLA_ERR_NULL
+    assert lib.bwla_q_okt_rows(fake, fake, fake, 8, fake, fake, 100, 512, 16, 32, odd, None, fake, big, None) == B.BWLA_ERR_ALIGN
+    assert lib.bwla_q_okt_rows(fake, fake, fake, 8, fake, fake, 100, 512, 16, 32, fake, None, fake, 1024, None) == B.BWLA_ERR_BUFSIZE
+    assert lib.bwla_q_okt_rows(fake, fake, fake, 8, fake, fake, 100, 512, 16, 31, fake, None, fake, big, None) == B.BWLA_ERR_SHAPE
+    assert lib.bwla_q_init_theta(None, 10, 10, 1e-8, fake, fake, None) == B.BWLA_ERR_NULL
+    assert lib.bwla_q_em_step(fake, 0, 10, 1e-8, fake, fake, None) == B.BWLA_ERR_SHAPE
+    assert lib.bwla_q_gmm_nll(fake, 10, 10, fake, fake, fake, fake, 8, None) == B.BWLA_ERR_BUFSIZE
+    assert lib.bwla_q_procrustes(3, fake, fake, fake, fake, fake, 100, 512, 16, 32, fake, fake, big, None) == B.BWLA_ERR_SHAPE
+    assert lib.bwla_q_svd_square(fake, 257, fake, fake, fake, fake, big, None) == B.BWLA_ERR_UNSUPPORTED
+    assert lib.bwla_q_svd_square(fake, 16, fake, fake, fake, fake, 64, None) == B.BWLA_ERR_BUFSIZE
+    assert lib.bwla_q_truncate_rank(fake, 100, 512, 0, 10, 1e-9, fake, fake, None, fake, big, None) == B.BWLA_ERR_SHAPE
+    assert lib.bwla_q_psp_step(fake, fake, fake, 8, fake, fake, fake, None, 100, 512, 16, 32, 0.0, 10, 1e-9, fake, big, None) == B.BWLA_ERR_NULL
+    assert lib.bwla_quantize_layer(fake, 100, 512, 16, 32, 8, 2, 0.0, 1e-8, 10, 1e-9, 1, fake, fake, fake, None, fake,
+                                   None, None, None, fake, big, None) == B.BWLA_ERR_NULL               # k > 0 needs U
+    assert lib.bwla_quantize_layer(fake, 100, 512, 16, 32, 8, 2, 0.0, 0.0, 10, 1e-9, 1, fake, fake, fake, fake, fake,
+                                   None, None, None, fake, big, None) == B.BWLA_ERR_SHAPE              # s2_min must be > 0
