@@ -5,29 +5,56 @@
 //
 // The columns of G are kept as contiguous rows of a work array (column j = row j), V likewise.
 // A sweep visits every pair of columns once, in the round-robin order of a tournament: n / 2
-// disjoint pairs per round, n - 1 rounds, the pairs of a round dealt to the 16 wavefronts.  A
-// wavefront holds both columns of its pair in registers (up to four elements per lane), takes the
-// three inner products by butterflies, and applies the plane rotation that makes the two columns
-// orthogonal to them and to the matching columns of V.  Sweeps end when one passes without a
-// rotation (every pair orthogonal to 1e-15 relative) or after 60.  At the end the column norms are
-// the singular values, the normalized columns U, and V holds the right singular vectors.
+// disjoint pairs per round, n - 1 rounds.  A pair belongs to a group of lanes that holds both columns
+// in registers (up to four elements per lane), takes the three inner products, and applies the plane
+// rotation that makes the two columns orthogonal to them and to the matching columns of V.  Up to
+// n = 64 a group is one row of 16 lanes -- four pairs per wavefront, all pairs of a round at once,
+// the inner products summed on DPP row operations alone; larger matrices give a pair a whole
+// wavefront (row sums on DPP, the four rows added through lane reads).  Sweeps end when one passes
+// without a rotation (every pair orthogonal to 1e-15 relative) or after 60.  At the end the column
+// norms are the singular values, the normalized columns U, and V holds the right singular vectors.
+// Up to n = 96 both arrays (2 n^2 doubles, at most 144 KiB) live in LDS, where a round costs an LDS
+// round trip instead of an L2 one; larger matrices work in the caller's scratch (L2-resident).
+#include "bwla_internal.h"
 #include "quantizer_internal.h"
 
 namespace {
 
-constexpr int JT = 1024, JW = JT / 64, JMAX = 256;
+constexpr int JT = 1024, JW = JT / 64, JMAX = 256, JLDS = 96;
 
-__device__ __forceinline__ double jwave_sum(double v) {
-#pragma unroll
-    for (int off = 32; off > 0; off >>= 1) v += __shfl_xor(v, off, 64);
+template <int CTRL>
+__device__ __forceinline__ double jdpp(double v) {
+    const int lo = __builtin_amdgcn_update_dpp(0, __double2loint(v), CTRL, 0xf, 0xf, true);
+    const int hi = __builtin_amdgcn_update_dpp(0, __double2hiint(v), CTRL, 0xf, 0xf, true);
+    return __hiloint2double(hi, lo);
+}
+// sum over a row of 16 lanes, the same value in each of them
+__device__ __forceinline__ double jrow_sum(double v) {
+    v += jdpp<0xB1>(v);      // quad_perm [1,0,3,2]
+    v += jdpp<0x4E>(v);      // quad_perm [2,3,0,1]
+    v += jdpp<0x141>(v);     // row_half_mirror
+    v += jdpp<0x140>(v);     // row_mirror
+    return v;
+}
+__device__ __forceinline__ double jread(double v, int lane) {
+    return __hiloint2double(__builtin_amdgcn_readlane(__double2hiint(v), lane),
+                            __builtin_amdgcn_readlane(__double2loint(v), lane));
+}
+template <int GW>
+__device__ __forceinline__ double jgroup_sum(double v) {
+    v = jrow_sum(v);
+    if (GW == 64) v = (jread(v, 0) + jread(v, 16)) + (jread(v, 32) + jread(v, 48));
     return v;
 }
 
+// GW: lanes per pair (16 for n <= 64, else 64); LDS: the work arrays live in dynamic LDS
+template <int GW, bool LDS>
 __global__ __launch_bounds__(JT) void jacobi_kernel(QJacobi a) {
     if (a.skip && *a.skip) return;
     const int n = a.n, t = threadIdx.x, lane = t & 63, w = t >> 6;
-    double* Wc = a.work;
-    double* Vc = a.work + (size_t)n * n;
+    extern __shared__ double jlds[];
+    double* Wc = LDS ? jlds : a.work;
+    double* Vc = Wc + (size_t)n * n;
     __shared__ int pos[2][JMAX + 2];
     __shared__ int rotated;
     __shared__ double sg[JMAX];
@@ -40,32 +67,41 @@ __global__ __launch_bounds__(JT) void jacobi_kernel(QJacobi a) {
     const int np = (n + 1) & ~1;
     for (int i = t; i < np; i += JT) pos[0][i] = i;
     int cur = 0;
+    constexpr int GROUPS = JT / GW;
+    const int gid = t / GW, sl = t % GW;
     __syncthreads();
     for (int sweep = 0; sweep < 60; ++sweep) {
         if (t == 0) rotated = 0;
         __syncthreads();
         for (int round = 0; round < np - 1; ++round) {
-            for (int pr = w; pr < np / 2; pr += JW) {
-                int p = pos[cur][pr], q = pos[cur][np - 1 - pr];
-                if (p >= n || q >= n) continue;            // the bye of an odd n
-                if (p > q) { const int s = p; p = q; q = s; }
+            for (int base = 0; base < np / 2; base += GROUPS) {        // the same trip count in every lane
+                const int pr = base + gid;
+                int p = 0, q = 0;
+                bool live = pr < np / 2;
+                if (live) {
+                    p = pos[cur][pr];
+                    q = pos[cur][np - 1 - pr];
+                    live = p < n && q < n;                              // else the bye of an odd n
+                    if (p > q) { const int s = p; p = q; q = s; }
+                }
                 double* xp = Wc + (size_t)p * n;
                 double* yp = Wc + (size_t)q * n;
                 double x[4], y[4];
                 double al = 0.0, be = 0.0, ga = 0.0;
 #pragma unroll
                 for (int u = 0; u < 4; ++u) {
-                    const int e = lane + 64 * u;
-                    x[u] = e < n ? xp[e] : 0.0;
-                    y[u] = e < n ? yp[e] : 0.0;
+                    const int e = sl + GW * u;
+                    const bool in = live && e < n;
+                    x[u] = in ? xp[e] : 0.0;
+                    y[u] = in ? yp[e] : 0.0;
                     al += x[u] * x[u];
                     be += y[u] * y[u];
                     ga += x[u] * y[u];
                 }
-                al = jwave_sum(al);
-                be = jwave_sum(be);
-                ga = jwave_sum(ga);
-                if (al > 0.0 && be > 0.0 && fabs(ga) > 1.0e-15 * sqrt(al * be)) {
+                al = jgroup_sum<GW>(al);
+                be = jgroup_sum<GW>(be);
+                ga = jgroup_sum<GW>(ga);
+                if (live && al > 0.0 && be > 0.0 && fabs(ga) > 1.0e-15 * sqrt(al * be)) {
                     const double zeta = (be - al) / (2.0 * ga);
                     const double tt = copysign(1.0, zeta) / (fabs(zeta) + sqrt(1.0 + zeta * zeta));
                     const double cs = 1.0 / sqrt(1.0 + tt * tt), sn = cs * tt;
@@ -73,7 +109,7 @@ __global__ __launch_bounds__(JT) void jacobi_kernel(QJacobi a) {
                     double* vq = Vc + (size_t)q * n;
 #pragma unroll
                     for (int u = 0; u < 4; ++u) {
-                        const int e = lane + 64 * u;
+                        const int e = sl + GW * u;
                         if (e < n) {
                             xp[e] = cs * x[u] - sn * y[u];
                             yp[e] = sn * x[u] + cs * y[u];
@@ -82,7 +118,7 @@ __global__ __launch_bounds__(JT) void jacobi_kernel(QJacobi a) {
                             vq[e] = sn * vx + cs * vy;
                         }
                     }
-                    if (lane == 0) rotated = 1;
+                    if (sl == 0) rotated = 1;
                 }
             }
             // next round of the tournament: position 0 stays, the others move on by one
@@ -96,7 +132,7 @@ __global__ __launch_bounds__(JT) void jacobi_kernel(QJacobi a) {
     for (int j = w; j < n; j += JW) {
         double s = 0.0;
         for (int e = lane; e < n; e += 64) s += Wc[(size_t)j * n + e] * Wc[(size_t)j * n + e];
-        s = jwave_sum(s);
+        s = jgroup_sum<64>(s);
         if (lane == 0) sg[j] = sqrt(s);
     }
     __syncthreads();
@@ -135,6 +171,16 @@ __global__ __launch_bounds__(JT) void jacobi_kernel(QJacobi a) {
 
 hipError_t bwla_q_launch_jacobi(const QJacobi& j, hipStream_t st) {
     if (j.n < 1 || j.n > JMAX) return hipErrorInvalidValue;
-    hipLaunchKernelGGL(jacobi_kernel, dim3(1), dim3(JT), 0, st, j);
-    return hipGetLastError();
+    const size_t lds = j.n <= JLDS ? (size_t)2 * j.n * j.n * sizeof(double) : 0;
+    auto launch = [&](auto kern) {
+        if (lds > 48 * 1024) {
+            const hipError_t e = bwla_ensure_lds((const void*)kern, lds);
+            if (e != hipSuccess) return e;
+        }
+        hipLaunchKernelGGL(kern, dim3(1), dim3(JT), lds, st, j);
+        return hipGetLastError();
+    };
+    if (j.n <= 64) return launch(jacobi_kernel<16, true>);
+    if (j.n <= JLDS) return launch(jacobi_kernel<64, true>);
+    return launch(jacobi_kernel<64, false>);
 }
