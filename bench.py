@@ -337,6 +337,50 @@ def side_kernel_report(cfg, us_rotate):
             "flops_per_launch": flops, "tflops": flops / t / 1e12}
 
 
+def quantizer_report(torch, rounds=2, svd_iters=20):
+    """The offline quantizer (paper App. A.1 Algorithm 2) on a synthetic Gaussian matrix of the default
+    workload's shape: time per round of {EM, PSP, two Procrustes updates}, the loss after every
+    sub-step, and how the OKT transform of all rows (three fp64 GEMMs and the centering, each a pass
+    over the n x m array) sits against HBM."""
+    from paper_2605_00422_amd import quantizer_binding as qb
+    n, n1, n2, k = 11008, 64, 64, 32
+    m = n1 * n2
+    g = torch.Generator(device="cuda")
+    g.manual_seed(0)
+    W = torch.randn(n, m, device="cuda", dtype=torch.float32, generator=g) * 0.02
+    ws = torch.zeros(qb.workspace_size(n, m, n1, n2, k), dtype=torch.uint8, device="cuda")
+    f32 = lambda *s: torch.empty(*s, dtype=torch.float32, device="cuda")
+    f64 = lambda *s: torch.empty(*s, dtype=torch.float64, device="cuda")
+    R1, R2, Wrot, U, V, c, s2 = f32(n1, n1), f32(n2, n2), f32(n, m), f32(m, k), f32(n, k), f64(n), f64(n)
+    hist = f64(1 + 3 * rounds)
+
+    def timed(fn, reps):
+        fn()
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(reps):
+            fn()
+        e1.record()
+        torch.cuda.synchronize()
+        return e0.elapsed_time(e1) / reps
+
+    ms = timed(lambda: qb.quantize_layer(W, n1, n2, k, rounds, R1, R2, Wrot, U, V, c, s2, hist, ws,
+                                         svd_iters=svd_iters, svd_tol=0.0), 2)
+    W64, X, A, Bt = W.double(), f64(n, m), torch.zeros(n, k, dtype=torch.float64, device="cuda"), \
+        torch.zeros(m, k, dtype=torch.float64, device="cuda")
+    r1, r2 = R1.double(), R2.double()
+    ms_okt = timed(lambda: qb.okt_rows(W64, A, Bt, r1, r2, X, None, ws), 5)
+    passes = 8 * n * m * 8            # W - M, two GEMM stages, centering: each reads and writes n x m fp64
+    return {"workload": f"Gaussian {n} x {m} (Kronecker {n1} x {n2}), rank {k}", "dtype": "f64",
+            "rounds": rounds, "svd_iters_per_round": svd_iters, "ms_total": ms, "ms_per_round": ms / rounds,
+            "loss_history": [float(v) for v in hist.cpu()],
+            "okt_rows": {"ms": ms_okt, "bound": "hbm", "bytes_moved": passes,
+                         "achieved": passes / (ms_okt * 1e-3) / 1e9, "peak": 8000.0, "unit": "GB/s",
+                         "frac": passes / (ms_okt * 1e-3) / 1e9 / 8000.0,
+                         "flops": 2 * n * m * (n1 + n2 + k)}}
+
+
 def cpu_baseline(w, budget_s=12.0):
     """The CPU oracle (as it stands) on the same workload: online path only (the binarized
     matrix is prepared once, like the packed layer on the GPU)."""
@@ -501,6 +545,7 @@ def main():
                 # GEMM as bf16, ready for the down projection's rotation
                 line["block7b_m1"]["us_gateup_forward"] = gu[0]["graph"]["us_linear_forward"]
                 line["block7b_m1"]["us_gateup_forward_gated"] = gu[0]["graph"]["us_linear_forward_gated"]
+        line["quantizer"] = quantizer_report(torch)
     print(json.dumps(line))
 
 

@@ -270,3 +270,34 @@ def test_quantize_layer_history_and_outputs(n, n1, n2, k, t):
         sgn, alpha = B.unpack_signs(layer)
         so, ao, _ = fwd.binarize_rows_centered(wr)
         assert np.mean(sgn.cpu().numpy() != so) < 1e-3
+
+
+def test_quantize_layer_at_the_7b_shape():
+    """11008 x 4096 (64 x 64), rank 32 -- the shape the benchmark times.  At this size the oracle checks
+    what it can compute in seconds: the loss never increases over the sub-steps, the last entry is
+    L_GMM of the returned W_rot under the returned mixtures, the factors are orthogonal, and sampled
+    rows of W_rot equal (W - V U^T)_i (R1 (x) R2)."""
+    qb = _qb()
+    n, n1, n2, k, t = 11008, 64, 64, 32, 2
+    m = n1 * n2
+    rng = np.random.default_rng(7)
+    W = (rng.standard_normal((n, m)) * 0.02 + rng.standard_normal((n, 1)) * 0.004).astype(np.float32)
+    f32 = lambda *s: torch.empty(*s, dtype=torch.float32, device="cuda")
+    R1, R2, Wrot, U, V = f32(n1, n1), f32(n2, n2), f32(n, m), f32(m, k), f32(n, k)
+    c = torch.empty(n, dtype=torch.float64, device="cuda")
+    s2 = torch.empty(n, dtype=torch.float64, device="cuda")
+    hist = torch.empty(1 + 3 * t, dtype=torch.float64, device="cuda")
+    qb.quantize_layer(_dev(W, torch.float32), n1, n2, k, t, R1, R2, Wrot, U, V, c, s2, hist, _ws(n, m, n1, n2, k),
+                      svd_iters=20, svd_tol=0.0)
+    h = hist.cpu().numpy()
+    assert np.all(np.isfinite(h)) and np.all(np.diff(h) <= 1e-12), h
+    assert h[-1] < h[0] - 1e-3
+    r1, r2 = R1.double().cpu().numpy(), R2.double().cpu().numpy()
+    assert np.max(np.abs(r1.T @ r1 - np.eye(n1))) < 1e-5 and np.max(np.abs(r2.T @ r2 - np.eye(n2))) < 1e-5
+    wr = Wrot.double().cpu().numpy()
+    assert abs(Q.gmm_nll(Q.center_rows(wr), c.cpu().numpy(), s2.cpu().numpy()) - h[-1]) < 1e-6
+    rows = np.concatenate([[0, n - 1], rng.choice(n, 62, replace=False)])
+    Vh, Uh = V.double().cpu().numpy(), U.double().cpu().numpy()
+    want = fwd.kron_rotate(W[rows].astype(np.float64) - Vh[rows] @ Uh.T, r1, r2)
+    assert _rel(wr[rows], want) < 1e-5
+    assert np.linalg.matrix_rank(Vh, tol=1e-9) == k
