@@ -242,7 +242,7 @@ constexpr int gd_vmcnt_imm(int n) { return (n & 15) | ((n >> 4) << 14) | (7 << 4
 // moves each nibble to the top of its byte, (x << 4) & 0xf0.. and x & 0xf0..: int8 operands worth 16
 // times the code, so the accumulators are exact multiples of 16 and are shifted down once at the end.
 template <int NTL, int WM, int WK, int NB, bool GATED = false, bool A4 = false>
-__global__ __launch_bounds__(64 * WM * WK) void gemm_prefill_direct_kernel(
+__global__ __launch_bounds__(64 * WM * WK, NB == 2 ? 2 : 1) void gemm_prefill_direct_kernel(
     const uint4* __restrict__ bits, int chunks, int row_tiles, const int8_t* __restrict__ q, int M, int K,
     const float* __restrict__ scale, const int32_t* __restrict__ qsum, const __half* __restrict__ alpha,
     const __half* __restrict__ V, const float* __restrict__ T, int r, float* __restrict__ Y, int N,
@@ -460,20 +460,14 @@ __global__ __launch_bounds__(64 * WM * WK) void gemm_prefill_direct_kernel(
     // Drain the loads nobody reads.  Their destination registers must stay reserved until they
     // have landed, so the wait names all four slots as operands: without that the code behind
     // the loop may reuse a register that a load still in flight is about to overwrite.
-    static_assert(NTL == 1 || NTL == 2 || NTL == 4 || NTL == 5, "operand lists of the drain below");
     asm volatile("s_waitcnt vmcnt(0)" : "+v"(w0.w[0]), "+v"(w1.w[0]));
     // the remaining slot registers are used after the wait, hence reserved across it
-    if constexpr (NB == 4) asm volatile("" : "+v"(w2.w[0]), "+v"(w3.w[0]));
-    if constexpr (NTL >= 2) {
-        asm volatile("" : "+v"(w0.w[1]), "+v"(w1.w[1]));
-        if constexpr (NB == 4) asm volatile("" : "+v"(w2.w[1]), "+v"(w3.w[1]));
+#pragma unroll
+    for (int nt = 1; nt < NTL; ++nt) asm volatile("" : "+v"(w0.w[nt]), "+v"(w1.w[nt]));
+    if constexpr (NB == 4) {
+#pragma unroll
+        for (int nt = 0; nt < NTL; ++nt) asm volatile("" : "+v"(w2.w[nt]), "+v"(w3.w[nt]));
     }
-    if constexpr (NTL >= 4) {
-        static_assert(NTL < 4 || NB == 4, "wide tiles use the deep ring");
-        asm volatile("" : "+v"(w0.w[2]), "+v"(w1.w[2]), "+v"(w2.w[2]), "+v"(w3.w[2]),
-                          "+v"(w0.w[3]), "+v"(w1.w[3]), "+v"(w2.w[3]), "+v"(w3.w[3]));
-    }
-    if constexpr (NTL == 5) asm volatile("" : "+v"(w0.w[4]), "+v"(w1.w[4]), "+v"(w2.w[4]), "+v"(w3.w[4]));
 
     if constexpr (WK > 1) {
         // every wavefront has drained its copies: the tiles are dead, LDS carries the partial sums
@@ -509,8 +503,11 @@ __global__ __launch_bounds__(64 * WM * WK) void gemm_prefill_direct_kernel(
             for (int nt = 0; nt < NTL; ++nt) acc[mt][nt] = acc[mt][nt] >> 4;    // exact: every operand was 16 x code
     }
     // ---- epilogue.  Accumulator element v of lane (l32, lg): row 8*(v/4) + 4*lg + v%4, column l32.
-    // Low-rank term on bf16 MFMA 32x32x16 with exact operand splits (T: three terms, V: two):
-    // per 16 ranks one T fragment and NTL V fragments are loaded one step ahead of their use.
+    // Low-rank term on fp16 MFMA 32x32x16: V is stored in fp16 and is an operand as it stands; a token's
+    // row of T is scaled by a power of two (largest entry near 2^13) and split into two fp16 terms,
+    // T 2^k = hi + lo to 2^-22, so a 16-rank step costs two products per channel tile; the scale is
+    // undone per result row.  T and V fragments are loaded one step ahead of their use.
+    typedef _Float16 v8h __attribute__((ext_vector_type(8)));
     const int JT = (r + 15) >> 4, rp = JT * 16;
     int ncol[NTL];
     float al[NTL];
@@ -520,72 +517,85 @@ __global__ __launch_bounds__(64 * WM * WK) void gemm_prefill_direct_kernel(
         ncol[nt] = n < N ? n : N - 1;
         al[nt] = __half2float(alpha[ncol[nt]]);
     }
-    struct Raw { float4 t[2]; uint4 v[NTL]; };
 #pragma unroll
     for (int mt = 0; mt < MT; ++mt) {
         const int mrow0 = m_base + mt * 32;
         if (mrow0 >= M) continue;
         int tmr = mrow0 + l32;
         if (tmr > M - 1) tmr = M - 1;
-        auto load_raw = [&](Raw& rw, int kk) {
-            const int j0 = kk * 16 + 8 * lg;
-            const float* tp = T + (int64_t)tmr * r + j0;
-            if ((r & 3) == 0) {
-                // whole groups of four are inside or outside the row; clamp the address, zero the value
-                const float4 z = make_float4(0.f, 0.f, 0.f, 0.f);
-                const float4 t0 = *reinterpret_cast<const float4*>(j0 < r ? tp : T);
-                const float4 t1 = *reinterpret_cast<const float4*>(j0 + 4 < r ? tp + 4 : T);
-                rw.t[0] = j0 < r ? t0 : z;
-                rw.t[1] = j0 + 4 < r ? t1 : z;
-            } else {
-                float e[8];
-#pragma unroll
-                for (int i = 0; i < 8; ++i) e[i] = j0 + i < r ? tp[i] : 0.0f;
-                rw.t[0] = make_float4(e[0], e[1], e[2], e[3]);
-                rw.t[1] = make_float4(e[4], e[5], e[6], e[7]);
-            }
-#pragma unroll
-            for (int nt = 0; nt < NTL; ++nt)
-                rw.v[nt] = *reinterpret_cast<const uint4*>(V + (int64_t)ncol[nt] * rp + j0);
-        };
         v16f low[NTL];
 #pragma unroll
         for (int nt = 0; nt < NTL; ++nt)
 #pragma unroll
             for (int v = 0; v < 16; ++v) low[nt][v] = 0.0f;
-        if (JT > 0) {
-            Raw cur, nxt;
-            load_raw(cur, 0);
-            for (int kk = 0; kk < JT; ++kk) {
-                load_raw(nxt, kk + 1 < JT ? kk + 1 : JT - 1);
-                const float tv[8] = {cur.t[0].x, cur.t[0].y, cur.t[0].z, cur.t[0].w,
-                                     cur.t[1].x, cur.t[1].y, cur.t[1].z, cur.t[1].w};
-                v8bf t1, t2, t3;
+        float tun[16];                                           // 2^-k of the result rows
 #pragma unroll
-                for (int e = 0; e < 8; ++e) {
-                    __bf16 h1, h2, h3;
-                    gd_split3(tv[e], h1, h2, h3);
-                    t1[e] = h1; t2[e] = h2; t3[e] = h3;
+        for (int v = 0; v < 16; ++v) tun[v] = 0.0f;
+        if (JT > 0) {
+            // my token's entries 16 kk + 8 lg .. + 7 of T
+            auto load_t = [&](float (&tv)[8], int kk) {
+                const int j0 = kk * 16 + 8 * lg;
+                const float* tp = T + (int64_t)tmr * r + j0;
+                if ((r & 3) == 0) {
+                    // whole groups of four are inside or outside the row; clamp the address, zero the value
+                    const float4 z = make_float4(0.f, 0.f, 0.f, 0.f);
+                    const float4 t0 = *reinterpret_cast<const float4*>(j0 < r ? tp : T);
+                    const float4 t1 = *reinterpret_cast<const float4*>(j0 + 4 < r ? tp + 4 : T);
+                    const float4 u0 = j0 < r ? t0 : z, u1 = j0 + 4 < r ? t1 : z;
+                    tv[0] = u0.x; tv[1] = u0.y; tv[2] = u0.z; tv[3] = u0.w;
+                    tv[4] = u1.x; tv[5] = u1.y; tv[6] = u1.z; tv[7] = u1.w;
+                } else {
+#pragma unroll
+                    for (int i = 0; i < 8; ++i) tv[i] = j0 + i < r ? tp[i] : 0.0f;
+                }
+            };
+            // first pass: the row's largest magnitude (the row is read again below, from the caches)
+            float tmax = 0.0f;
+            for (int kk = 0; kk < JT; ++kk) {
+                float tv[8];
+                load_t(tv, kk);
+#pragma unroll
+                for (int i = 0; i < 8; ++i) tmax = fmaxf(tmax, fabsf(tv[i]));
+            }
+            tmax = fmaxf(tmax, __shfl_xor(tmax, 32, 64));        // the other half of my token's row
+            int kexp = 0;
+            if (tmax > 0.0f && tmax < 3.0e38f) kexp = 13 - ilogbf(tmax);
+            kexp = kexp > 100 ? 100 : (kexp < -100 ? -100 : kexp);
+            const float tinv = ldexpf(1.0f, -kexp);
+            // result row 8 (v / 4) + 4 lg + v % 4 of the tile belongs to the token of lane (that row, any lg)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) tun[v] = __shfl(tinv, 8 * (v >> 2) + 4 * lg + (v & 3), 64);
+            uint4 vcur[NTL], vnxt[NTL];
+            float tcur[8], tnxt[8];
+            auto load_v = [&](uint4 (&dst)[NTL], int kk) {
+#pragma unroll
+                for (int nt = 0; nt < NTL; ++nt)
+                    dst[nt] = *reinterpret_cast<const uint4*>(V + (int64_t)ncol[nt] * rp + kk * 16 + 8 * lg);
+            };
+            load_v(vcur, 0);
+            load_t(tcur, 0);
+            for (int kk = 0; kk < JT; ++kk) {
+                const int kn = kk + 1 < JT ? kk + 1 : JT - 1;
+                load_v(vnxt, kn);
+                load_t(tnxt, kn);
+                v8h thi, tlo;
+#pragma unroll
+                for (int i = 0; i < 8; ++i) {
+                    const float x = ldexpf(tcur[i], kexp);
+                    const _Float16 h = (_Float16)x;
+                    thi[i] = h;
+                    tlo[i] = (_Float16)(x - (float)h);
                 }
 #pragma unroll
                 for (int nt = 0; nt < NTL; ++nt) {
-                    v8bf vh, vl;
-                    const __half2* h2p = reinterpret_cast<const __half2*>(&cur.v[nt]);
-#pragma unroll
-                    for (int e = 0; e < 4; ++e) {
-                        const float2 f = __half22float2(h2p[e]);
-                        const __bf16 a0 = (__bf16)f.x, a1 = (__bf16)f.y;
-                        vh[2 * e] = a0; vh[2 * e + 1] = a1;
-                        vl[2 * e] = (__bf16)(f.x - (float)a0); vl[2 * e + 1] = (__bf16)(f.y - (float)a1);
-                    }
-                    low[nt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(t3, vl, low[nt], 0, 0, 0);
-                    low[nt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(t2, vl, low[nt], 0, 0, 0);
-                    low[nt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(t3, vh, low[nt], 0, 0, 0);
-                    low[nt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(t1, vl, low[nt], 0, 0, 0);
-                    low[nt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(t2, vh, low[nt], 0, 0, 0);
-                    low[nt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(t1, vh, low[nt], 0, 0, 0);
+                    const v8h vb = __builtin_bit_cast(v8h, vcur[nt]);
+                    low[nt] = __builtin_amdgcn_mfma_f32_32x32x16_f16(tlo, vb, low[nt], 0, 0, 0);
+                    low[nt] = __builtin_amdgcn_mfma_f32_32x32x16_f16(thi, vb, low[nt], 0, 0, 0);
                 }
-                cur = nxt;
+#pragma unroll
+                for (int nt = 0; nt < NTL; ++nt) vcur[nt] = vnxt[nt];
+#pragma unroll
+                for (int i = 0; i < 8; ++i) tcur[i] = tnxt[i];
             }
         }
         float sc[16];
@@ -606,7 +616,7 @@ __global__ __launch_bounds__(64 * WM * WK) void gemm_prefill_direct_kernel(
                 if constexpr (GATED) {
                     // lane pairs (n even, n + 1) hold (gate, up) of one token; the even lane stores
                     const int a = 2 * acc[mt][nt][v] - qs[v];
-                    const float yv = sc[v] * al[nt] * (float)a + low[nt][v];
+                    const float yv = sc[v] * al[nt] * (float)a + low[nt][v] * tun[v];
                     const float up = __shfl_xor(yv, 1, 64);
                     if (m < M && (l32 & 1) == 0 && n + 1 < N) {
                         const float h = yv / (1.0f + __expf(-yv)) * up;
@@ -614,7 +624,7 @@ __global__ __launch_bounds__(64 * WM * WK) void gemm_prefill_direct_kernel(
                     }
                 } else if (m < M && n < N) {
                     const int a = 2 * acc[mt][nt][v] - qs[v];
-                    Y[(int64_t)m * N + n] = sc[v] * al[nt] * (float)a + low[nt][v];
+                    Y[(int64_t)m * N + n] = sc[v] * al[nt] * (float)a + low[nt][v] * tun[v];
                     if (acc_out) acc_out[(int64_t)m * N + n] = a;
                 }
             }
@@ -672,6 +682,15 @@ hipError_t bwla_launch_gemm_prefill(const bwla_layer_t* L, const int8_t* dq, con
         // against 35.8; at 104 workgroups the large tiles win, 38.6 against 44.0 and 64.0 against 77.8)
         const int64_t big = std::min(tiles_for(M, N, 256, 160), tiles_for(M, N, 256, 128));
         if (M > 128 && big > 72) {
+            const int64_t cus_big = bwla_device_cus();
+            // Output-heavy shapes (short rows of K, many channels: every round of tiles ends in a burst of
+            // stores) with an even number of 256 x 128 tiles per CU: two workgroups per CU, each with a
+            // ring of two slices (64 KiB of LDS, at most 256 registers), so that one workgroup's epilogue
+            // and first loads run under the other's contraction.  Measured against the one-workgroup
+            // variants at 4096 tokens: 8192 -> 8192 -3 .. -8 %, 8192 -> 28672 -5 .. -8 %, 28672 -> 8192 -1.5 %.
+            const int64_t t128 = tiles_for(M, N, 256, 128);
+            if (t128 >= 4 * cus_big && t128 % (2 * cus_big) == 0)
+                return launch_direct<4, 4, 1, 2>(L, dq, dscale, dqsum, dT, M, dY, dacc, st, dH, a4);
             const double d160 = wave_eff(tiles_for(M, N, 256, 160)), d128 = wave_eff(tiles_for(M, N, 256, 128));
             if (d160 >= d128) return launch_direct<5, 4, 1, 4>(L, dq, dscale, dqsum, dT, M, dY, dacc, st, dH, a4);
             return launch_direct<4, 4, 1, 4>(L, dq, dscale, dqsum, dT, M, dY, dacc, st, dH, a4);
