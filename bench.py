@@ -291,6 +291,46 @@ class Peaks:
         return self._mfma
 
 
+def microbench(torch, B):
+    """Latencies the decode path lives with, measured with the library's probe launches: the period
+    of back-to-back launches of a kernel that does nothing (from a graph, like the workloads), and the
+    latency of one dependent load that misses every cache / that hits the L2."""
+    n = 400
+    g = torch.cuda.CUDAGraph()
+    st = torch.cuda.Stream()
+    with torch.cuda.stream(st):
+        B.probe_empty_launch()
+        torch.cuda.synchronize()
+        with torch.cuda.graph(g, stream=st):
+            for _ in range(n):
+                B.probe_empty_launch()
+    torch.cuda.synchronize()
+    period = 1e9
+    for _ in range(3):
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        g.replay()
+        e1.record()
+        torch.cuda.synchronize()
+        period = min(period, e0.elapsed_time(e1) * 1e3 / n)
+    out = torch.zeros(2, dtype=torch.int64, device="cuda:0")
+    flush_caches(torch)
+    buf = _flush_buf.view(torch.uint8)
+    iters = 2000
+    # cold: a new 4 KiB page region every load (stride 1 MiB + 4 KiB over the flushed buffer's head)
+    B.probe_load_latency(buf[:FLUSH_BYTES // 2], (1 << 20) + 4096, 300, out)
+    torch.cuda.synchronize()
+    miss = out[0].item() * 10.0 / 300
+    small = buf[:1 << 20]
+    B.probe_load_latency(small, 128, (1 << 20) // 128, out)       # first walk brings the MiB into the L2
+    B.probe_load_latency(small, 128, iters, out)
+    torch.cuda.synchronize()
+    l2 = out[0].item() * 10.0 / iters
+    return {"empty_launch_period_us": period, "dependent_load_ns": {"miss": miss, "l2_hit": l2},
+            "what": "graph of 400 launches of an empty kernel (256 x 512 threads); one lane's dependent 4-byte loads, "
+                    "1 MiB + 4 KiB apart over a flushed 384 MiB buffer / 128 bytes apart over 1 MiB read just before"}
+
+
 def roofline_for(cfg, launches, us_layer, us_forward, peaks, traffic, workload=None):
     """Roofline of the dominant kernel: the single-launch decode kernel where it serves the layer
     (then the kernel is the layer), else the binary GEMM inside bwla_linear_forward; with the
@@ -546,6 +586,8 @@ def main():
                 line["block7b_m1"]["us_gateup_forward"] = gu[0]["graph"]["us_linear_forward"]
                 line["block7b_m1"]["us_gateup_forward_gated"] = gu[0]["graph"]["us_linear_forward_gated"]
         line["quantizer"] = quantizer_report(torch)
+    if peaks is not None:
+        line["microbench"] = microbench(torch, B)
     print(json.dumps(line))
 
 

@@ -334,7 +334,7 @@ BWLA_API bwla_status_t bwla_linear_forward_a4(const bwla_layer_t* layer, const u
 
 /*
  * Measurement aids for benchmarks, not steps of the method: the ceilings this GPU actually reaches,
- * to quote the forward's kernels against next to the published peaks.
+ * to quote the forward's kernels against next to the published peaks, and two latencies.
  *   bwla_probe_hbm_read   one launch that reads `bytes` (a multiple of 16) from d_src (device,
  *                         16-byte aligned) with coalesced 16-byte loads and writes a checksum per
  *                         workgroup to d_sink (device, sink_bytes >= 32 KiB is always enough, else
@@ -344,10 +344,25 @@ BWLA_API bwla_status_t bwla_linear_forward_a4(const bwla_layer_t* layer, const u
  *                         INT8 MFMAs (1 <= iters <= 2^20) on register operands; *ops_out (host) gets
  *                         the launch's operation count (2 per multiply-add), d_sink (device,
  *                         >= 16 KiB) a checksum.
- * Both enqueue on `stream`, own no memory, and return the usual codes.
+ *   bwla_probe_empty_launch  one launch of a kernel that does nothing, in the launch shape of the decode
+ *                         kernels (one workgroup of 512 threads per CU): timed back to back from a graph
+ *                         it gives the period at which dependent launches can follow one another.
+ *   bwla_probe_load_latency  one lane issues `iters` (1 .. 2^24) loads of four bytes from d_buf (device,
+ *                         `bytes` long, a multiple of 4), each at an index that depends on the value the
+ *                         one before returned: the index moves on by stride_bytes (a multiple of 4,
+ *                         0 < stride_bytes <= bytes - 4; plus one word when the loaded word is odd) and wraps
+ *                         at the end.  d_out (device, 16 bytes, 8-byte aligned) gets the duration of the
+ *                         walk in ticks of the GPU's constant 100 MHz counter (10 ns each) and the last
+ *                         index.  Ticks * 10 / iters is the latency of one dependent load in nanoseconds: of
+ *                         a miss everywhere when the walk never comes back to a line, of the L2 when the
+ *                         buffer was read just before and fits it.
+ * All enqueue on `stream`, own no memory, and return the usual codes.
  */
 BWLA_API bwla_status_t bwla_probe_hbm_read(const void* d_src, size_t bytes, void* d_sink, size_t sink_bytes, void* stream);
 BWLA_API bwla_status_t bwla_probe_mfma_int8(int iters, void* d_sink, size_t sink_bytes, int64_t* ops_out, void* stream);
+BWLA_API bwla_status_t bwla_probe_empty_launch(void* stream);
+BWLA_API bwla_status_t bwla_probe_load_latency(const void* d_buf, size_t bytes, size_t stride_bytes, int iters,
+                                               void* d_out, void* stream);
 
 #ifdef __cplusplus
 }

@@ -21,7 +21,7 @@ EXPORTS = ["bwla_status_string", "bwla_version", "bwla_kron_factor", "bwla_packe
            "bwla_packed_size_mode", "bwla_pack_weights_mode", "bwla_swiglu_workspace_size",
            "bwla_linear_forward_swiglu", "bwla_decode_forward_static", "bwla_probe_hbm_read",
            "bwla_probe_mfma_int8", "bwla_decode_forward_launches", "bwla_decode_forward_bits", "bwla_pack_codes_a4",
-           "bwla_linear_forward_a4"]
+           "bwla_linear_forward_a4", "bwla_probe_empty_launch", "bwla_probe_load_latency"]
 
 
 class BwlaLayer(Structure):
@@ -83,6 +83,8 @@ def load() -> ctypes.CDLL:
     lib.bwla_decode_forward_launches.argtypes = [POINTER(BwlaLayer), c_int, c_int64, POINTER(c_int)]
     lib.bwla_probe_hbm_read.argtypes = [c_void_p, c_size_t, c_void_p, c_size_t, c_void_p]
     lib.bwla_probe_mfma_int8.argtypes = [c_int, c_void_p, c_size_t, POINTER(ctypes.c_int64), c_void_p]
+    lib.bwla_probe_empty_launch.argtypes = [c_void_p]
+    lib.bwla_probe_load_latency.argtypes = [c_void_p, c_size_t, c_size_t, c_int, c_void_p, c_void_p]
     lib.bwla_swiglu_workspace_size.argtypes = [POINTER(BwlaLayer), c_int64, POINTER(c_size_t)]
     lib.bwla_linear_forward_swiglu.argtypes = [POINTER(BwlaLayer), c_void_p, c_void_p, c_void_p, c_void_p, c_int64,
                                                c_void_p, c_void_p, c_size_t, c_void_p]
@@ -265,6 +267,16 @@ def probe_mfma_int8(iters: int, sink) -> int:
     _check(load().bwla_probe_mfma_int8(int(iters), _ptr(sink), sink.numel() * sink.element_size(), byref(ops),
                                        _stream()), "bwla_probe_mfma_int8")
     return ops.value
+
+
+def probe_empty_launch() -> None:
+    _check(load().bwla_probe_empty_launch(_stream()), "bwla_probe_empty_launch")
+
+
+def probe_load_latency(buf, stride_bytes: int, iters: int, out) -> None:
+    """out: int64 CUDA tensor of two elements (ticks of 10 ns, last index)."""
+    _check(load().bwla_probe_load_latency(_ptr(buf), buf.numel() * buf.element_size(), stride_bytes, iters, _ptr(out),
+                                          _stream()), "bwla_probe_load_latency")
 
 
 def pack_codes_a4(q, q4=None):

@@ -1,6 +1,7 @@
-// Two measurement aids, not steps of the method: what this GPU reaches on a pure streaming read of
-// a given size and on a loop of nothing but INT8 MFMAs.  The benchmark quotes the forward's
-// kernels against these measured ceilings next to the published peaks (8 TB/s, 5.0 POP/s).
+// Measurement aids, not steps of the method: what this GPU reaches on a pure streaming read of a
+// given size and on a loop of nothing but INT8 MFMAs (the benchmark quotes the forward's kernels
+// against these measured ceilings next to the published peaks, 8 TB/s and 5.0 POP/s), what a kernel
+// launch costs when the kernel does nothing, and how long a dependent load takes.
 #include "bwla_internal.h"
 
 namespace {
@@ -46,9 +47,47 @@ __global__ __launch_bounds__(256) void probe_mfma_i8_kernel(int iters, int32_t* 
     sink[(blockIdx.x * 256 + threadIdx.x) & 4095] = s.x ^ s.y ^ s.z ^ s.w;
 }
 
+// a launch of the decode kernels' shape (one workgroup of 512 threads per CU) that does nothing
+__global__ __launch_bounds__(512) void probe_empty_kernel() {}
+
+// One lane walks through the buffer: the index of every load depends on the value the load before it
+// returned ((v & 1) is unknown to the compiler), so the loads cannot overlap.  Ticks of the constant
+// 100 MHz counter around the walk go to out[0], the last index to out[1] (keeps the chain alive).
+__global__ void probe_chase_kernel(const uint32_t* __restrict__ buf, uint64_t n, uint64_t stride, int iters,
+                                   uint64_t* __restrict__ out) {
+    if (threadIdx.x != 0) return;
+    uint64_t idx = 0;
+    const uint64_t t0 = wall_clock64();
+    for (int i = 0; i < iters; ++i) {
+        const uint32_t v = __builtin_nontemporal_load(buf + idx);
+        idx += stride + (v & 1u);
+        if (idx >= n) idx -= n;
+    }
+    const uint64_t t1 = wall_clock64();
+    out[0] = t1 - t0;
+    out[1] = idx;
+}
+
 }  // namespace
 
 extern "C" {
+
+BWLA_API bwla_status_t bwla_probe_empty_launch(void* stream) {
+    hipLaunchKernelGGL(probe_empty_kernel, dim3(bwla_device_cus()), dim3(512), 0, (hipStream_t)stream);
+    return hipGetLastError() == hipSuccess ? BWLA_OK : BWLA_ERR_HIP;
+}
+
+BWLA_API bwla_status_t bwla_probe_load_latency(const void* d_buf, size_t bytes, size_t stride_bytes, int iters,
+                                               void* d_out, void* stream) {
+    if (!d_buf || !d_out) return BWLA_ERR_NULL;
+    if (bytes < 8 || (bytes & 3) || (stride_bytes & 3) || stride_bytes == 0 || stride_bytes + 4 > bytes ||
+        iters < 1 || iters > (1 << 24))
+        return BWLA_ERR_SHAPE;
+    if (((uintptr_t)d_buf & 3) || ((uintptr_t)d_out & 7)) return BWLA_ERR_ALIGN;
+    hipLaunchKernelGGL(probe_chase_kernel, dim3(1), dim3(64), 0, (hipStream_t)stream, (const uint32_t*)d_buf,
+                       (uint64_t)(bytes / 4), (uint64_t)(stride_bytes / 4), iters, (uint64_t*)d_out);
+    return hipGetLastError() == hipSuccess ? BWLA_OK : BWLA_ERR_HIP;
+}
 
 BWLA_API bwla_status_t bwla_probe_hbm_read(const void* d_src, size_t bytes, void* d_sink, size_t sink_bytes, void* stream) {
     if (!d_src || !d_sink) return BWLA_ERR_NULL;

@@ -45,6 +45,28 @@ def test_probes_run_and_refuse():
         B.probe_mfma_int8(10, sink[:16])           # sink too small
 
 
+def test_latency_probes_run_and_refuse():
+    from paper_2605_00422_amd import binding as B
+    B.probe_empty_launch()
+    buf = torch.zeros(1 << 18, dtype=torch.int32, device="cuda:0")          # 1 MiB of even words: stride exact
+    out = torch.zeros(2, dtype=torch.int64, device="cuda:0")
+    B.probe_load_latency(buf, 128, 1000, out)
+    torch.cuda.synchronize()
+    ticks, idx = out.cpu().numpy().tolist()
+    assert idx == (1000 * 32) % (1 << 18)                                    # 1000 steps of 32 words
+    assert 1000 * 5 <= ticks * 10 <= 1000 * 20000                            # 5 ns .. 20 us per load
+    odd = torch.ones(1 << 10, dtype=torch.int32, device="cuda:0")           # odd words: one word further each time
+    B.probe_load_latency(odd, 64, 10, out)
+    torch.cuda.synchronize()
+    assert out[1].item() == (10 * 17) % (1 << 10)
+    with pytest.raises(B.BwlaError):
+        B.probe_load_latency(buf, 0, 10, out)
+    with pytest.raises(B.BwlaError):
+        B.probe_load_latency(buf, 4 << 20, 10, out)                          # stride beyond the buffer
+    with pytest.raises(B.BwlaError):
+        B.probe_load_latency(buf, 128, 0, out)
+
+
 def test_launch_count_query():
     from paper_2605_00422_amd import binding as B
     from parity_util import pack_on_gpu
