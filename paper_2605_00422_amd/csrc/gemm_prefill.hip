@@ -504,10 +504,16 @@ __global__ __launch_bounds__(64 * WM * WK, NB == 2 ? 2 : 1) void gemm_prefill_di
     }
     // ---- epilogue.  Accumulator element v of lane (l32, lg): row 8*(v/4) + 4*lg + v%4, column l32.
     // Low-rank term on fp16 MFMA 32x32x16: V is stored in fp16 and is an operand as it stands; a token's
-    // row of T is scaled by a power of two (largest entry near 2^13) and split into two fp16 terms,
-    // T 2^k = hi + lo to 2^-22, so a 16-rank step costs two products per channel tile; the scale is
-    // undone per result row.  T and V fragments are loaded one step ahead of their use.
+    // row of T is scaled by a power of two 2^k (largest entry near 2^13) and split into two fp16 terms,
+    // T 2^k = hi + lo to 2^-22: two products per 16 ranks and channel tile.  The main term
+    // scale_t alpha_n (2 acc - qsum_t) is formed first, times 2^k of its row, in the accumulator's
+    // registers, the MFMAs add the low-rank products onto it, and 2^-k is applied at the store (powers of
+    // two: exact).  What the epilogue waits for is memory, not arithmetic: all its loads -- scales and code
+    // sums of the rows, the tokens' rows of T, the channels' rows of V, up to 64 ranks at a time -- are
+    // requested in one go before the first use (they were ten dependent round trips per tile when T and V
+    // were fetched step by step: 12 % of the launch at 8192 x 8192 and 4096 tokens).
     typedef _Float16 v8h __attribute__((ext_vector_type(8)));
+    constexpr int JC = (NB == 2 || NTL == 5) ? 2 : 4;                          // 16-rank steps per chunk (fewer where registers are short)
     const int JT = (r + 15) >> 4, rp = JT * 16;
     int ncol[NTL];
     float al[NTL];
@@ -517,87 +523,57 @@ __global__ __launch_bounds__(64 * WM * WK, NB == 2 ? 2 : 1) void gemm_prefill_di
         ncol[nt] = n < N ? n : N - 1;
         al[nt] = __half2float(alpha[ncol[nt]]);
     }
+    // my token's entries 16 kk + 8 lg .. + 7 of T (zero past the rank)
+    auto load_t = [&](float (&tv)[8], int tmr, int kk) {
+        const int j0 = kk * 16 + 8 * lg;
+        const float* tp = T + (int64_t)tmr * r + j0;
+        if ((r & 3) == 0) {
+            // whole groups of four are inside or outside the row; clamp the address, zero the value
+            const float4 z = make_float4(0.f, 0.f, 0.f, 0.f);
+            const float4 t0 = *reinterpret_cast<const float4*>(j0 < r ? tp : T);
+            const float4 t1 = *reinterpret_cast<const float4*>(j0 + 4 < r ? tp + 4 : T);
+            const float4 u0 = j0 < r ? t0 : z, u1 = j0 + 4 < r ? t1 : z;
+            tv[0] = u0.x; tv[1] = u0.y; tv[2] = u0.z; tv[3] = u0.w;
+            tv[4] = u1.x; tv[5] = u1.y; tv[6] = u1.z; tv[7] = u1.w;
+        } else {
+#pragma unroll
+            for (int i = 0; i < 8; ++i) tv[i] = j0 + i < r ? tp[i] : 0.0f;
+        }
+    };
+    uint4 vfr[JC][NTL];                                          // V fragments of the current chunk of ranks
+    auto load_v = [&](int c0) {
+#pragma unroll
+        for (int j = 0; j < JC; ++j) {
+            const int kk = c0 + j < JT ? c0 + j : (JT > 0 ? JT - 1 : 0);
+#pragma unroll
+            for (int nt = 0; nt < NTL; ++nt)
+                vfr[j][nt] = JT > 0 ? *reinterpret_cast<const uint4*>(V + (int64_t)ncol[nt] * rp + kk * 16 + 8 * lg)
+                                    : make_uint4(0, 0, 0, 0);
+        }
+    };
+    load_v(0);
+    const bool one_chunk = JT <= JC;                             // then V stays in registers for both row tiles
 #pragma unroll
     for (int mt = 0; mt < MT; ++mt) {
         const int mrow0 = m_base + mt * 32;
         if (mrow0 >= M) continue;
         int tmr = mrow0 + l32;
         if (tmr > M - 1) tmr = M - 1;
-        v16f low[NTL];
+        // the row's largest magnitude, over all of its ranks
+        float tmax = 0.0f;
+        for (int c0 = 0; c0 < JT; c0 += JC) {
+            float tv[JC][8];
 #pragma unroll
-        for (int nt = 0; nt < NTL; ++nt)
+            for (int j = 0; j < JC; ++j) load_t(tv[j], tmr, c0 + j < JT ? c0 + j : JT - 1);
 #pragma unroll
-            for (int v = 0; v < 16; ++v) low[nt][v] = 0.0f;
-        float tun[16];                                           // 2^-k of the result rows
+            for (int j = 0; j < JC; ++j)
 #pragma unroll
-        for (int v = 0; v < 16; ++v) tun[v] = 0.0f;
-        if (JT > 0) {
-            // my token's entries 16 kk + 8 lg .. + 7 of T
-            auto load_t = [&](float (&tv)[8], int kk) {
-                const int j0 = kk * 16 + 8 * lg;
-                const float* tp = T + (int64_t)tmr * r + j0;
-                if ((r & 3) == 0) {
-                    // whole groups of four are inside or outside the row; clamp the address, zero the value
-                    const float4 z = make_float4(0.f, 0.f, 0.f, 0.f);
-                    const float4 t0 = *reinterpret_cast<const float4*>(j0 < r ? tp : T);
-                    const float4 t1 = *reinterpret_cast<const float4*>(j0 + 4 < r ? tp + 4 : T);
-                    const float4 u0 = j0 < r ? t0 : z, u1 = j0 + 4 < r ? t1 : z;
-                    tv[0] = u0.x; tv[1] = u0.y; tv[2] = u0.z; tv[3] = u0.w;
-                    tv[4] = u1.x; tv[5] = u1.y; tv[6] = u1.z; tv[7] = u1.w;
-                } else {
-#pragma unroll
-                    for (int i = 0; i < 8; ++i) tv[i] = j0 + i < r ? tp[i] : 0.0f;
-                }
-            };
-            // first pass: the row's largest magnitude (the row is read again below, from the caches)
-            float tmax = 0.0f;
-            for (int kk = 0; kk < JT; ++kk) {
-                float tv[8];
-                load_t(tv, kk);
-#pragma unroll
-                for (int i = 0; i < 8; ++i) tmax = fmaxf(tmax, fabsf(tv[i]));
-            }
-            tmax = fmaxf(tmax, __shfl_xor(tmax, 32, 64));        // the other half of my token's row
-            int kexp = 0;
-            if (tmax > 0.0f && tmax < 3.0e38f) kexp = 13 - ilogbf(tmax);
-            kexp = kexp > 100 ? 100 : (kexp < -100 ? -100 : kexp);
-            const float tinv = ldexpf(1.0f, -kexp);
-            // result row 8 (v / 4) + 4 lg + v % 4 of the tile belongs to the token of lane (that row, any lg)
-#pragma unroll
-            for (int v = 0; v < 16; ++v) tun[v] = __shfl(tinv, 8 * (v >> 2) + 4 * lg + (v & 3), 64);
-            uint4 vcur[NTL], vnxt[NTL];
-            float tcur[8], tnxt[8];
-            auto load_v = [&](uint4 (&dst)[NTL], int kk) {
-#pragma unroll
-                for (int nt = 0; nt < NTL; ++nt)
-                    dst[nt] = *reinterpret_cast<const uint4*>(V + (int64_t)ncol[nt] * rp + kk * 16 + 8 * lg);
-            };
-            load_v(vcur, 0);
-            load_t(tcur, 0);
-            for (int kk = 0; kk < JT; ++kk) {
-                const int kn = kk + 1 < JT ? kk + 1 : JT - 1;
-                load_v(vnxt, kn);
-                load_t(tnxt, kn);
-                v8h thi, tlo;
-#pragma unroll
-                for (int i = 0; i < 8; ++i) {
-                    const float x = ldexpf(tcur[i], kexp);
-                    const _Float16 h = (_Float16)x;
-                    thi[i] = h;
-                    tlo[i] = (_Float16)(x - (float)h);
-                }
-#pragma unroll
-                for (int nt = 0; nt < NTL; ++nt) {
-                    const v8h vb = __builtin_bit_cast(v8h, vcur[nt]);
-                    low[nt] = __builtin_amdgcn_mfma_f32_32x32x16_f16(tlo, vb, low[nt], 0, 0, 0);
-                    low[nt] = __builtin_amdgcn_mfma_f32_32x32x16_f16(thi, vb, low[nt], 0, 0, 0);
-                }
-#pragma unroll
-                for (int nt = 0; nt < NTL; ++nt) vcur[nt] = vnxt[nt];
-#pragma unroll
-                for (int i = 0; i < 8; ++i) tcur[i] = tnxt[i];
-            }
+                for (int i = 0; i < 8; ++i) tmax = fmaxf(tmax, fabsf(tv[j][i]));
         }
+        tmax = fmaxf(tmax, __shfl_xor(tmax, 32, 64));            // the other half of my token's row
+        int kexp = 0;
+        if (tmax > 0.0f && tmax < 3.0e38f) kexp = 13 - ilogbf(tmax);
+        kexp = kexp > 60 ? 60 : (kexp < -60 ? -60 : kexp);
         float sc[16];
         int qs[16];
 #pragma unroll
@@ -607,25 +583,68 @@ __global__ __launch_bounds__(64 * WM * WK, NB == 2 ? 2 : 1) void gemm_prefill_di
             sc[v] = scale[m];
             qs[v] = qsum[m];
         }
+        // the main term replaces acc in place (as float bits), times 2^k of its row:
+        // result row 8 (v / 4) + 4 lg + v % 4 belongs to the token of lane (that row, any lg)
+        int krow[16];
 #pragma unroll
-        for (int nt = 0; nt < NTL; ++nt) {
-            const int n = n_base + nt * 32 + l32;
+        for (int v = 0; v < 16; ++v) {
+            krow[v] = __shfl(kexp, 8 * (v >> 2) + 4 * lg + (v & 3), 64);
+            const float up = __int_as_float((127 + krow[v]) << 23);
+            const int m = mrow0 + 8 * (v >> 2) + 4 * lg + (v & 3);
 #pragma unroll
-            for (int v = 0; v < 16; ++v) {
-                const int m = mrow0 + 8 * (v >> 2) + 4 * lg + (v & 3);
+            for (int nt = 0; nt < NTL; ++nt) {
+                const int a = 2 * acc[mt][nt][v] - qs[v];
+                if constexpr (!GATED) {
+                    const int n = n_base + nt * 32 + l32;
+                    if (acc_out && m < M && n < N) acc_out[(int64_t)m * N + n] = a;
+                }
+                acc[mt][nt][v] = __float_as_int(sc[v] * al[nt] * (float)a * up);
+            }
+        }
+        for (int c0 = 0; c0 < JT; c0 += JC) {
+            if (c0 > 0 || (mt > 0 && !one_chunk)) load_v(c0);
+            float tv[JC][8];
+#pragma unroll
+            for (int j = 0; j < JC; ++j) load_t(tv[j], tmr, c0 + j < JT ? c0 + j : JT - 1);   // (from the caches)
+#pragma unroll
+            for (int j = 0; j < JC; ++j) {
+                if (c0 + j < JT) {
+                    v8h thi, tlo;
+#pragma unroll
+                    for (int i = 0; i < 8; ++i) {
+                        const float x = ldexpf(tv[j][i], kexp);
+                        const _Float16 h = (_Float16)x;
+                        thi[i] = h;
+                        tlo[i] = (_Float16)(x - (float)h);
+                    }
+#pragma unroll
+                    for (int nt = 0; nt < NTL; ++nt) {
+                        const v8h vb = __builtin_bit_cast(v8h, vfr[j][nt]);
+                        v16f y = __builtin_bit_cast(v16f, acc[mt][nt]);
+                        y = __builtin_amdgcn_mfma_f32_32x32x16_f16(tlo, vb, y, 0, 0, 0);
+                        y = __builtin_amdgcn_mfma_f32_32x32x16_f16(thi, vb, y, 0, 0, 0);
+                        acc[mt][nt] = __builtin_bit_cast(v16i, y);
+                    }
+                }
+            }
+        }
+#pragma unroll
+        for (int v = 0; v < 16; ++v) {
+            const float down = __int_as_float((127 - krow[v]) << 23);
+            const int m = mrow0 + 8 * (v >> 2) + 4 * lg + (v & 3);
+#pragma unroll
+            for (int nt = 0; nt < NTL; ++nt) {
+                const int n = n_base + nt * 32 + l32;
+                const float yv = __int_as_float(acc[mt][nt][v]) * down;
                 if constexpr (GATED) {
                     // lane pairs (n even, n + 1) hold (gate, up) of one token; the even lane stores
-                    const int a = 2 * acc[mt][nt][v] - qs[v];
-                    const float yv = sc[v] * al[nt] * (float)a + low[nt][v] * tun[v];
                     const float up = __shfl_xor(yv, 1, 64);
                     if (m < M && (l32 & 1) == 0 && n + 1 < N) {
                         const float h = yv / (1.0f + __expf(-yv)) * up;
                         H[(int64_t)m * (N >> 1) + (n >> 1)] = __builtin_bit_cast(uint16_t, (__bf16)h);
                     }
                 } else if (m < M && n < N) {
-                    const int a = 2 * acc[mt][nt][v] - qs[v];
-                    Y[(int64_t)m * N + n] = sc[v] * al[nt] * (float)a + low[nt][v] * tun[v];
-                    if (acc_out) acc_out[(int64_t)m * N + n] = a;
+                    Y[(int64_t)m * N + n] = yv;
                 }
             }
         }
