@@ -726,6 +726,9 @@ hipError_t bwla_launch_gemm_prefill(const bwla_layer_t* L, const int8_t* dq, con
         const int64_t cus = bwla_device_cus();
         if (tiles <= cus) return launch_direct<1, 1, 4, 4>(L, dq, dscale, dqsum, dT, M, dY, dacc, st, dH, a4);
         if (tiles <= 2 * cus) return launch_direct<2, 1, 4, 4>(L, dq, dscale, dqsum, dT, M, dY, dacc, st, dH, a4);
+        // beyond three per CU the wavefronts' re-reads of the code rows load the L2 -> CU paths: 64 x 64
+        // tiles shared by two wavefronts halve them (8192 -> 28672 at 64 tokens, 896 tiles: 37.2 -> 32.2 us)
+        if (tiles > 3 * cus) return launch_direct<2, 1, 2, 4>(L, dq, dscale, dqsum, dT, M, dY, dacc, st, dH, a4);
         return launch_direct<1, 1, 1, 4>(L, dq, dscale, dqsum, dT, M, dY, dacc, st, dH, a4);
     }
     // shapes the streaming kernel does not take (K not a multiple of 128, fewer than 32 channels):
