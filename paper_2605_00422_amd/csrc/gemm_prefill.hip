@@ -241,8 +241,8 @@ constexpr int gd_vmcnt_imm(int n) { return (n & 15) | ((n >> 4) << 14) | (7 << 4
 // A row of a slice is then 64 bytes; a lane reads one packed piece for two contraction steps and
 // moves each nibble to the top of its byte, (x << 4) & 0xf0.. and x & 0xf0..: int8 operands worth 16
 // times the code, so the accumulators are exact multiples of 16 and are shifted down once at the end.
-template <int NTL, int WM, int WK, int NB, bool GATED = false, bool A4 = false>
-__global__ __launch_bounds__(64 * WM * WK, NB == 2 ? 2 : 1) void gemm_prefill_direct_kernel(
+template <int NTL, int WM, int WK, int NB, bool GATED = false, bool A4 = false, int WN = 1>
+__global__ __launch_bounds__(64 * WM * WK * WN, NB == 2 ? 2 : 1) void gemm_prefill_direct_kernel(
     const uint4* __restrict__ bits, int chunks, int row_tiles, const int8_t* __restrict__ q, int M, int K,
     const float* __restrict__ scale, const int32_t* __restrict__ qsum, const __half* __restrict__ alpha,
     const __half* __restrict__ V, const float* __restrict__ T, int r, float* __restrict__ Y, int N,
@@ -250,7 +250,10 @@ __global__ __launch_bounds__(64 * WM * WK, NB == 2 ? 2 : 1) void gemm_prefill_di
     constexpr int MT = GD_MT;
     // WM wavefronts stacked along the tokens; WK wavefronts share one tile and split its slices of K
     // (small batches: more wavefronts in flight), their accumulators are added through LDS
-    constexpr int BM = WM * GD_ROWS, BN = NTL * 32;
+    // WN wavefronts side by side along the channels (wavefronts with the same token rows then ask for the
+    // same code rows at about the same time: the second request is served by the CU's L1)
+    static_assert(WN == 1 || WK == 1, "channel-wise stacking is for unsplit K");
+    constexpr int BM = WM * GD_ROWS, BN = WN * NTL * 32;
     // vector-memory operations per slice and wavefront: NTL weight loads, then 8 code copies;
     // when slice j + 1 is needed, the operations of slices j + 2 and j + 3 may still be in flight
     // (NB = ring depth, 4 or 2: code tiles in LDS and weight slots in registers)
@@ -261,7 +264,7 @@ __global__ __launch_bounds__(64 * WM * WK, NB == 2 ? 2 : 1) void gemm_prefill_di
     extern __shared__ __align__(16) char smem[];
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-    const int wm = wave % WM, wk = wave / WM;
+    const int wm = wave % WM, wk = WK == 1 ? 0 : wave / WM, wn = WK == 1 ? wave / WM : 0;
     const int l32 = lane & 31, lg = lane >> 5;
     char* mytile = smem + wave * (NB * GD_TILE);
     const uint32_t mytile_lds = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) char*)mytile;
@@ -272,7 +275,7 @@ __global__ __launch_bounds__(64 * WM * WK, NB == 2 ? 2 : 1) void gemm_prefill_di
     const int nblocks = gridDim.x;
     if ((nblocks & 7) == 0) pid = (pid & 7) * (nblocks >> 3) + (pid >> 3);
     const int tm = pid / tiles_n, tn = pid - tm * tiles_n;
-    const int m_base = tm * BM + wm * GD_ROWS, n_base = tn * BN;
+    const int m_base = tm * BM + wm * GD_ROWS, n_base = tn * BN + wn * (NTL * 32);
     // my slices of K: [s_begin, s_begin + nslices) of K / 128 (K % 128 == 0, checked by the launcher)
     const int ns_all = K >> 7;
     const int ns_per = (ns_all + WK - 1) / WK;
@@ -651,28 +654,28 @@ __global__ __launch_bounds__(64 * WM * WK, NB == 2 ? 2 : 1) void gemm_prefill_di
     }
 }
 
-template <int NTL, int WM, int WK, int NB>
+template <int NTL, int WM, int WK, int NB, int WN = 1>
 hipError_t launch_direct(const bwla_layer_t* L, const int8_t* dq, const float* dscale, const int32_t* dqsum,
                          const float* dT, int64_t M, float* dY, int32_t* dacc, hipStream_t st, uint16_t* dH,
                          bool a4 = false) {
-    constexpr int BM = WM * GD_ROWS, BN = NTL * 32;
+    constexpr int BM = WM * GD_ROWS, BN = WN * NTL * 32;
     const char* blob = (const char*)L->d_blob;
     const int tiles_m = (int)((M + BM - 1) / BM), tiles_n = (int)((L->N + BN - 1) / BN);
-    const size_t lds = (size_t)WM * WK * NB * GD_TILE;
+    const size_t lds = (size_t)WM * WK * WN * NB * GD_TILE;
     static_assert((size_t)(WK - 1) * WM * GD_MT * NTL * 16 * 64 * 4 <= (size_t)WM * WK * NB * GD_TILE,
                   "the partial sums must fit into the tile rings");
     auto launch = [&](auto kern) -> hipError_t {
         hipError_t e = bwla_ensure_lds((const void*)kern, lds);
         if (e != hipSuccess) return e;
-        kern<<<dim3((unsigned)(tiles_m * tiles_n)), dim3(64 * WM * WK), lds, st>>>(
+        kern<<<dim3((unsigned)(tiles_m * tiles_n)), dim3(64 * WM * WK * WN), lds, st>>>(
             (const uint4*)(blob + L->off_bits), (int)bwla_chunks(L->K), (int)bwla_row_tiles(L->N), dq, (int)M,
             (int)L->K, dscale, dqsum, (const __half*)(blob + L->off_alpha), (const __half*)(blob + L->off_V), dT,
             L->r, dY, (int)L->N, dacc, tiles_m, tiles_n, dH);
         return hipGetLastError();
     };
-    if (a4) return dH != nullptr ? hipErrorInvalidValue : launch(gemm_prefill_direct_kernel<NTL, WM, WK, NB, false, true>);
-    if (dH != nullptr) return launch(gemm_prefill_direct_kernel<NTL, WM, WK, NB, true>);
-    return launch(gemm_prefill_direct_kernel<NTL, WM, WK, NB, false>);
+    if (a4) return dH != nullptr ? hipErrorInvalidValue : launch(gemm_prefill_direct_kernel<NTL, WM, WK, NB, false, true, WN>);
+    if (dH != nullptr) return launch(gemm_prefill_direct_kernel<NTL, WM, WK, NB, true, false, WN>);
+    return launch(gemm_prefill_direct_kernel<NTL, WM, WK, NB, false, false, WN>);
 }
 
 inline int64_t tiles_for(int64_t M, int64_t N, int BM, int BN) { return ((M + BM - 1) / BM) * ((N + BN - 1) / BN); }
@@ -702,6 +705,12 @@ hipError_t bwla_launch_gemm_prefill(const bwla_layer_t* L, const int8_t* dq, con
         const int64_t big = std::min(tiles_for(M, N, 256, 160), tiles_for(M, N, 256, 128));
         if (M > 128 && big > 72) {
             const int64_t cus_big = bwla_device_cus();
+            // Four wavefronts side by side on the same 64 token rows (64 x 640 tiles) where such tiles come to
+            // whole rounds over the CUs: the code rows are then fetched once per CU and slice instead of four
+            // times (2048 x 25600 -> 5120: 217 -> 209 us against the 256 x 160 tiles).
+            const int64_t t640 = tiles_for(M, N, 64, 640);
+            if (N % 640 == 0 && t640 % cus_big == 0)
+                return launch_direct<5, 1, 1, 4, 4>(L, dq, dscale, dqsum, dT, M, dY, dacc, st, dH, a4);
             // Output-heavy shapes (short rows of K, many channels: every round of tiles ends in a burst of
             // stores) with an even number of 256 x 128 tiles per CU: two workgroups per CU, each with a
             // ring of two slices (64 KiB of LDS, at most 256 registers), so that one workgroup's epilogue

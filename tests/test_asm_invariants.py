@@ -19,7 +19,7 @@ HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 # (channel tiles per wavefront, wavefronts along the tokens, wavefronts along K, ring depth) of
 # every instantiation that is launched
 # every instantiation that is launched; the last entry: codes nibble-packed (4 code copies per slice instead of 8)
-SHAPES = [(1, 1, 1, 4), (1, 1, 4, 4), (2, 1, 4, 4), (4, 4, 1, 4), (5, 4, 1, 4), (4, 4, 1, 2), (2, 1, 2, 4)]
+SHAPES = [(1, 1, 1, 4), (1, 1, 4, 4), (2, 1, 4, 4), (4, 4, 1, 4), (5, 4, 1, 4), (4, 4, 1, 2), (2, 1, 2, 4), (5, 1, 1, 4)]
 VARIANTS = [(*v, a4) for a4 in (0, 1) for v in SHAPES]
 
 
