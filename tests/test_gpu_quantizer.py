@@ -51,7 +51,8 @@ def _rel(a, b):
     return float(np.max(np.abs(a - b)) / max(np.max(np.abs(b)), 1e-300))
 
 
-SHAPES = [(24, 4, 6, 2), (150, 16, 32, 8), (200, 12, 10, 5), (333, 64, 64, 8), (70, 80, 64, 4)]
+SHAPES = [(24, 4, 6, 2), (150, 16, 32, 8), (200, 12, 10, 5), (333, 64, 64, 8), (70, 80, 64, 4), (6, 112, 128, 3),
+          (10, 86, 64, 3)]
 
 
 @pytest.mark.parametrize("n,n1,n2,k", SHAPES)
