@@ -35,8 +35,9 @@ extern "C" {
 #endif
 
 /* Bytes of scratch that every call below accepts for a problem of this size (five n x m fp64
- * arrays, the subspace-iteration blocks, Jacobi work space, split-contraction partial sums).
- * Host only. */
+ * arrays, the subspace-iteration blocks, Jacobi work space, split-contraction partial sums): the d_ws
+ * of a call must hold at least as many, except where a call states a smaller need.  n1 = n2 = 1 with
+ * m > 1 sizes the scratch of the calls that take no factors (bwla_q_truncate_rank).  Host only. */
 BWLA_API bwla_status_t bwla_quantizer_workspace_size(int64_t n, int64_t m, int32_t n1, int32_t n2, int32_t k,
                                                      size_t* bytes);
 
@@ -62,7 +63,7 @@ BWLA_API bwla_status_t bwla_q_em_step(const double* d_X, int64_t n, int64_t m, d
                                       double* d_s2, void* stream);
 
 /* L_GMM (App. A.2.2): -1 / (n m) sum_ij log[ 1/2 phi(x_ij; c_i, s_i^2) + 1/2 phi(x_ij; -c_i, s_i^2) ]
- * to d_out[0]. */
+ * to d_out[0].  d_ws: n fp64 values are enough. */
 BWLA_API bwla_status_t bwla_q_gmm_nll(const double* d_X, int64_t n, int64_t m, const double* d_c,
                                       const double* d_s2, double* d_out, void* d_ws, size_t ws_bytes,
                                       void* stream);
@@ -83,7 +84,7 @@ BWLA_API bwla_status_t bwla_q_procrustes(int32_t which, const double* d_Wres, co
 /*
  * SVD of a square matrix, nn <= 256, by one-sided Jacobi rotations: d_sig (nn, descending),
  * d_Ut (row j = left singular vector j times sigma_j), d_Vt (row j = right singular vector j).
- * Any of the three outputs may be NULL.
+ * Any of the three outputs may be NULL.  d_ws: 2 nn^2 fp64 values are enough.
  */
 BWLA_API bwla_status_t bwla_q_svd_square(const double* d_G, int32_t nn, double* d_sig, double* d_Ut, double* d_Vt,
                                          void* d_ws, size_t ws_bytes, void* stream);
@@ -99,6 +100,7 @@ BWLA_API bwla_status_t bwla_q_svd_square(const double* d_G, int32_t nn, double* 
  * `tol` (relative) in one iteration: the remaining launches then return at once.  The captured
  * energy converges like (sigma_{p+1} / sigma_k)^(4 iterations); a spectrum without a gap behind
  * sigma_k needs many iterations for the singular vectors themselves.
+ * d_ws: bwla_quantizer_workspace_size(n, m, 1, 1, k) bytes.
  */
 BWLA_API bwla_status_t bwla_q_truncate_rank(const double* d_Y, int64_t n, int64_t m, int32_t k, int32_t iters,
                                             double tol, double* d_A, double* d_Bt, double* d_sig, void* d_ws,
