@@ -17,7 +17,7 @@
  * calls enqueue on `stream` and do not synchronize, allocate nothing, and validate their arguments
  * on the host before anything is enqueued (status codes of bwla.h).  The Kronecker convention is
  * the forward path's: a row times R1 (x) R2 is R1^T V R2 on the row reshaped row-major to n1 x n2.
- * Limits (BWLA_ERR_UNSUPPORTED): n1, n2 <= 256; k <= 128; n, m < 2^31 / 256.
+ * Limits (BWLA_ERR_UNSUPPORTED): n1, n2 <= 256; k <= 128; n <= 65535; m <= 65536.
  *
  * Readings of the paper taken here (the same as the test oracle's, each derived in its header):
  * the MM targets of a row are the centered targets plus the row's current mean (this makes every
