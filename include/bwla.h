@@ -175,7 +175,7 @@ BWLA_API bwla_status_t bwla_unpack_signs(const bwla_layer_t* layer, int8_t* d_sg
  * tiles), the rotated values in fp32 and their extremes between the two launches the rotation
  * then takes.  Returns 0 bytes when neither is used.
  * The scratch must be zero-filled once when it is allocated and then left to the library: its
- * first 5120 bytes are the exchange area of bwla_decode_forward's single-launch kernel (an epoch
+ * first 7168 bytes are the exchange area of bwla_decode_forward's single-launch kernel (an epoch
  * that every such launch moves on, arrival counts that every launch returns to zero, partial
  * sums tagged with their epoch), then comes one arrival counter per 16-token tile, which every
  * call returns to zero; everything behind them is overwritten by each call.  One scratch may
@@ -243,7 +243,7 @@ BWLA_API bwla_status_t bwla_linear_forward(const bwla_layer_t* layer, const int8
  * products in another order than the kernel bwla_rotate_quant picks for the shape, so a code
  * whose value lies on a rounding boundary can differ by one between the two.  For a single
  * bf16 token of a layer whose Kronecker factors are 32 or 64 wide (K = 1024 .. 4096: the
- * attention and up / gate projections of the 4096-wide models), with a PSP rank up to 64 and
+ * attention and up / gate projections of the 4096-wide models), with a PSP rank up to 96 and
  * symmetric codes (with or without the row shift), everything runs in ONE kernel launch: every
  * workgroup rotates and quantizes the token itself while its sign bits stream in; only the
  * projection T = x U is shared: the first 32 workgroups compute it in eight slices of K and

@@ -65,11 +65,11 @@ struct bwla_psp_plan {
 bwla_psp_plan bwla_make_psp_plan(int64_t M, int64_t K, int r);
 // Every scratch of bwla_rotate_quant starts with the exchange area of the single-launch decode
 // kernel -- an epoch word, eight arrival counts (64 bytes apart, from byte 64 on), and from byte
-// 1024 on 8 x 64 tagged partial sums of T = x U, 8 bytes each -- at the same place whatever the
+// 1024 on 8 x 96 tagged partial sums of T = x U, 8 bytes each -- at the same place whatever the
 // layer and the token count, so that every
 // call on a scratch agrees on it and no other kernel writes there.  The counters and partial sums
 // of the other kernels follow behind it.
-constexpr uint64_t BWLA_WS_HEAD = 1024 + 8 * 64 * 8;
+constexpr uint64_t BWLA_WS_HEAD = 1024 + 8 * 96 * 8;
 // behind the head: one arrival counter per 16 tokens (whatever the plan), padded to 256 bytes
 inline uint64_t bwla_psp_counter_bytes(int64_t M) { return bwla_align256((uint64_t)((M + 15) / 16) * sizeof(int)); }
 // columns that a layer's mode adds to V and T behind the PSP columns

@@ -39,10 +39,11 @@ constexpr int DL_THREADS = 512;      // eight wavefronts
 constexpr int DL_TPW = 3;            // channel tiles per workgroup and round
 constexpr int DL_MAXAT = 8;          // 16-row tiles along n1 (n1 <= 128)
 constexpr int DL_MAXK1 = 2;          // 32-deep steps along n2 (n2 <= 64)
-constexpr int DL_MAXJTU = 4;         // 16-column tiles of U (PSP rank <= 64)
-constexpr int DL_MAXJTV = 5;         // 16-column tiles of V (one more when the layer's mode adds a column)
+constexpr int DL_MAXJTU = 6;         // 16-column tiles of U (PSP rank <= 96)
+constexpr int DL_MAXJTV = 7;         // 16-column tiles of V (one more when the layer's mode adds a column)
 constexpr int DL_MAXROUNDS = 8;      // rounds of DL_TPW tiles per workgroup (more channels than that: two launches)
 constexpr int DL_SLICES = 8;         // slices of K of the shared projection
+static_assert(BWLA_WS_HEAD == 1024 + (uint64_t)DL_SLICES * 16 * DL_MAXJTU * 8, "the exchange area is the scratch's head");
 constexpr int DL_PRODUCERS = 32;     // workgroups that project (each slice four times: the first to land serves)
 constexpr int DL_SPIN_LIMIT = 1 << 22;
 
@@ -291,11 +292,12 @@ __global__ __launch_bounds__(DL_THREADS) void decode_layer_kernel(const uint16_t
         if (blk < DL_PRODUCERS) {
             // the slice's sums: four wavefronts' parts in wavefront order; value and tag in one word
             await(cnt + 3, 4);
-            if (lane < RPU) {
+#pragma unroll
+            for (int j = lane; j < RPU; j += 64) {
                 float v = 0.0f;
 #pragma unroll
-                for (int w = 0; w < 4; ++w) v += tpart[w * 16 * DL_MAXJTU + lane];
-                __hip_atomic_store(tx + slice * 16 * DL_MAXJTU + lane,
+                for (int w = 0; w < 4; ++w) v += tpart[w * 16 * DL_MAXJTU + j];
+                __hip_atomic_store(tx + slice * 16 * DL_MAXJTU + j,
                                    ((unsigned long long)tag << 32) | (unsigned long long)__float_as_uint(v), __ATOMIC_RELAXED,
                                    __HIP_MEMORY_SCOPE_AGENT);
             }
@@ -540,11 +542,12 @@ __global__ __launch_bounds__(DL_THREADS) void decode_layer_kernel(const uint16_t
                 if (idx < DL_SLICES * RPU) txl[idx] = __uint_as_float((unsigned)ent[i]);
             }
             // T: the slices in slice order
-            if (lane < RPU) {
+#pragma unroll
+            for (int j = lane; j < RPU; j += 64) {
                 float v = 0.0f;
 #pragma unroll
-                for (int sl = 0; sl < DL_SLICES; ++sl) v += txl[sl * RPU + lane];
-                txl[DL_SLICES * 16 * DL_MAXJTU + lane] = v;
+                for (int sl = 0; sl < DL_SLICES; ++sl) v += txl[sl * RPU + j];
+                txl[DL_SLICES * 16 * DL_MAXJTU + j] = v;
             }
         }
     }
@@ -685,6 +688,8 @@ hipError_t bwla_launch_decode_layer(const bwla_layer_t* L, const void* dX, int x
     DL_CASE(A_, B_, 0, 0) DL_CASE(A_, B_, 0, 1) DL_CASE(A_, B_, 1, 1) DL_CASE(A_, B_, 1, 2) DL_CASE(A_, B_, 2, 2) \
     DL_CASE(A_, B_, 2, 3) DL_CASE(A_, B_, 3, 3) DL_CASE(A_, B_, 3, 4) DL_CASE(A_, B_, 4, 4) DL_CASE(A_, B_, 4, 5)
     DL_RANKS(64, 64)
+    // (ranks up to 96: the merged q|k|v projection of a 4096-wide block)
+    DL_CASE(64, 64, 5, 5) DL_CASE(64, 64, 5, 6) DL_CASE(64, 64, 6, 6) DL_CASE(64, 64, 6, 7)
     // the smaller factor pairs with the ranks their widths would carry
     DL_CASE(32, 64, 0, 0) DL_CASE(32, 64, 1, 1) DL_CASE(32, 64, 2, 2) DL_CASE(64, 32, 0, 0) DL_CASE(64, 32, 1, 1)
     DL_CASE(64, 32, 2, 2) DL_CASE(32, 32, 0, 0) DL_CASE(32, 32, 1, 1)

@@ -19,7 +19,7 @@ from paper_2605_00422_amd import binding as B
 from paper_2605_00422_amd import inputs as syn
 
 DEV = "cuda:0"
-WS_HEAD = 1024 + 8 * 64 * 8     # exchange area of the single-launch decode kernel at the head of every scratch
+WS_HEAD = 1024 + 8 * 96 * 8     # exchange area of the single-launch decode kernel at the head of every scratch
 
 
 def to_dev(a, dtype=None):

@@ -134,6 +134,8 @@ def test_cfg4_70b_block_m4096_sampled_rows(which):
     (1, 2048, 32, 64, 333, 0, "bf16"),     # ragged N (scalar stores), two compute wavefronts
     (1, 1536, 48, 32, 1000, 0, "bf16"),    # two rotation strips, odd chunk count, last tile ragged
     (1, 4096, 128, 32, 520, 0, "bf16"),    # eight tiles along n1
+    (1, 4096, 64, 64, 1040, 96, "bf16"),   # single-launch kernel at its largest rank (six 16-column tiles of U)
+    (1, 4096, 64, 64, 2000, 70, "bf16"),   # five rank tiles, the last partly filled
     # few tokens, R1 too large for LDS: rotation split over several workgroups + quantizing launch
     (3, 16896, 176, 96, 80, 8, "bf16"),    # odd number of tiles along n1: the last slice has one tile
     (2, 20000, 200, 100, 48, 0, "bf16"),   # ragged n1 and n2 (strips and tiles partly filled), r = 0
@@ -156,6 +158,7 @@ def test_ragged_and_degenerate_shapes(M, K, n1, n2, N, r, xd):
     (16, 512, 16, 32, 512, 8, "f32"),        # fp32 activations (old rotation kernel), decode GEMM
     (1, 4096, 64, 64, 1000, 32, "bf16"),     # one token: merged projection, shift entry from the bf16 rotation
     (1, 4096, 64, 64, 528, 0, "bf16"),       # no PSP at all: the shift is the only column of T and V
+    (1, 4096, 64, 64, 1536, 96, "bf16"),     # single-launch kernel, rank 96 + the shift column: seven tiles of V
     (16, 5120, 64, 80, 640, 15, "bf16"),     # r + 1 = 16 fills the padded rank exactly
     (40, 1024, 32, 32, 200, 16, "bf16"),     # r + 1 = 17 crosses into the next 16-column group; streaming GEMM, 4 waves split K
     (300, 1152, 36, 32, 200, 20, "bf16"),    # prefill: separate projection kernel writes T with the wider pitch
