@@ -633,7 +633,7 @@ size_t dl_lds_bytes(int K, int n1, int n2, bool with_t) {
 
 // Single-launch decode layer.  *done = false (and nothing launched) when the shape is outside what
 // the kernel takes: one bf16 token; Kronecker factors of 32 or 64, or 128 x 64 (K = 1024 .. 8192, which
-// covers the 4096- and 8192-wide models' attention and up/gate projections); PSP rank up to 64 (and then at least
+// covers the 4096- and 8192-wide models' attention and up/gate projections); PSP rank up to 96 (and then at least
 // 512 output channels, so that the projection has its 32 producers); symmetric codes, with or
 // without the row shift.  dws_head: the first BWLA_WS_HEAD bytes of the caller's scratch.  With
 // dry_run nothing is launched and *done only says whether the kernel would serve the call.
