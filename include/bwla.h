@@ -242,9 +242,9 @@ BWLA_API bwla_status_t bwla_linear_forward(const bwla_layer_t* layer, const int8
  * same accuracy.  Where the single-launch kernel serves the call, its rotation may add the
  * products in another order than the kernel bwla_rotate_quant picks for the shape, so a code
  * whose value lies on a rounding boundary can differ by one between the two.  For a single
- * bf16 token of a layer whose Kronecker factors are 32 or 64 wide (K = 1024 .. 4096: the
- * attention and up / gate projections of the 4096-wide models), with a PSP rank up to 96 and
- * symmetric codes (with or without the row shift), everything runs in ONE kernel launch: every
+ * bf16 token of a layer whose Kronecker factors are 32 or 64 wide, or 128 x 64 (K = 1024 .. 8192: the
+ * attention and up / gate projections of the 4096- and 8192-wide models), with a PSP rank up to 96,
+ * symmetric or asymmetric codes and with or without the row shift, everything runs in ONE kernel launch: every
  * workgroup rotates and quantizes the token itself while its sign bits stream in; only the
  * projection T = x U is shared: the first 32 workgroups compute it in eight slices of K and
  * leave the sums, tagged with a per-launch epoch, in the first bytes of d_ws, where every
@@ -258,7 +258,7 @@ BWLA_API bwla_status_t bwla_decode_forward(const bwla_layer_t* layer, const void
                                   void* stream);
 /* bwla_decode_forward at another width of the activation codes: act_bits as in bwla_rotate_quant_bits
  * (2..8, else BWLA_ERR_UNSUPPORTED; 8 is the width of the paper's speed run, Sec. 4.4).  The
- * single-launch kernel serves every width. */
+ * single-launch kernel serves every width of the symmetric codes and every width the asymmetric ones allow. */
 BWLA_API bwla_status_t bwla_decode_forward_bits(const bwla_layer_t* layer, const void* d_X, int xdtype, int act_bits,
                                                 int64_t M, int8_t* d_q, float* d_scale, int32_t* d_qsum, float* d_T,
                                                 void* d_ws, size_t ws_bytes, float* d_Y, int32_t* d_acc,

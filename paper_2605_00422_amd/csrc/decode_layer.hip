@@ -1,5 +1,5 @@
 // One launch for a whole decode layer with a single bf16 token (the memory-bound case of paper
-// Sec. 4.4): rotation (Sec. 3.1), symmetric INT6 codes (Sec. 4.1), binary GEMM (Eq. 3-4), PSP
+// Sec. 4.4): rotation (Sec. 3.1), INT6 codes, symmetric or asymmetric (Sec. 4.1), binary GEMM (Eq. 3-4), PSP
 // branch (Sec. 3.2) and dequantization.
 //
 // A workgroup owns a few 16-channel tiles of the output and has eight wavefronts:
@@ -28,6 +28,7 @@
 #include <type_traits>
 
 #include "bwla_internal.h"
+#include "rotate_common.h"
 #include "wave_dpp.h"
 
 namespace {
@@ -80,8 +81,9 @@ __device__ __forceinline__ int dl_swz(int a, int gpr) { return gpr == 8 ? (a >> 
 
 // N1, N2: the Kronecker factors (compile-time: at these sizes the kernel is bound by the number of
 // instructions on its serial path, and run-time shapes cost address arithmetic and branches).
-// JTU, JTV: 16-column tiles of U and of V.
-template <int N1, int N2, int JTU, int JTV>
+// JTU, JTV: 16-column tiles of U and of V.  ASYM: asymmetric codes (their own instantiations, so that the
+// symmetric path carries none of their instructions).
+template <int N1, int N2, int JTU, int JTV, bool ASYM>
 __global__ __launch_bounds__(DL_THREADS) void decode_layer_kernel(const uint16_t* __restrict__ pX,
                                                                   const uint16_t* __restrict__ pR1h,
                                                                   const uint16_t* __restrict__ pR2d,
@@ -107,8 +109,8 @@ __global__ __launch_bounds__(DL_THREADS) void decode_layer_kernel(const uint16_t
     char* r1 = xt + 2 * K;                             // R1 terms [chunk][term][tile of c][lane * 16]: CH2 * 2 * AT KiB
     char* codes = r1 + CH2 * 2 * AT * 1024;            // K code bytes, k order
     char* xh = codes + K;                              // a producer's slice of the token as fp16: SW * 2 bytes
-    float* red = reinterpret_cast<float*>(xh + 2 * SW);// [0..3] strip maxima, [4..7] strip code sums, [8..13] six arrival counts, [14] epoch
-    float* tpart = red + 16;                           // [4 wavefronts][16 * DL_MAXJTU] partial T of a producer
+    float* red = reinterpret_cast<float*>(xh + 2 * SW);// [0..3] strip maxima, [4..7] strip code sums, [8..13] six arrival counts, [14] epoch, [16..19] strip minima
+    float* tpart = red + 32;                           // [4 wavefronts][16 * DL_MAXJTU] partial T of a producer
     float* txl = tpart + 4 * 16 * DL_MAXJTU;           // [DL_SLICES][16 * DL_MAXJTU] the slices' sums, [DL_SLICES * ...] on: T
     float* tfin = txl + (DL_SLICES + 1) * 16 * DL_MAXJTU;   // [8 wavefronts][16 * DL_MAXJTV] T as an epilogue wavefront reads it
     int* part = reinterpret_cast<int*>(tfin + 8 * 16 * DL_MAXJTV);   // [rounds][DL_TPW][8 chunks][16 channels]
@@ -405,30 +407,59 @@ __global__ __launch_bounds__(DL_THREADS) void decode_layer_kernel(const uint16_t
 #pragma unroll
             for (int tc = 0; tc < AT; ++tc) y[tc] = __builtin_amdgcn_mfma_f32_16x16x32_f16(ah[ch], bh[tc], y[tc], 0, 0, 0);
         }
-        // ============================================================ largest magnitude of the token
-        float mx = 0.0f;
+        // ============================================================ range of the token
+        // symmetric codes: the largest magnitude; asymmetric codes (Sec. 4.1): the largest and the smallest
+        // value, zero included
+        float mx = 0.0f, mn = 0.0f;
+        if constexpr (ASYM) {
 #pragma unroll
-        for (int tc = 0; tc < AT; ++tc)
+            for (int tc = 0; tc < AT; ++tc)
 #pragma unroll
-            for (int v = 0; v < 4; ++v) mx = fmaxf(mx, fabsf(y[tc][v]));
-        mx = dl_wave_max_nonneg(mx) * yun;
-        // the rotation wavefronts exchange their maxima among themselves
-        if (lane == 0) red[wave] = mx;
+                for (int v = 0; v < 4; ++v) { mx = fmaxf(mx, y[tc][v]); mn = fminf(mn, y[tc][v]); }
+            mx = dl_wave_max_nonneg(mx) * yun;
+            mn = -dl_wave_max_nonneg(-mn) * yun;
+        } else {
+#pragma unroll
+            for (int tc = 0; tc < AT; ++tc)
+#pragma unroll
+                for (int v = 0; v < 4; ++v) mx = fmaxf(mx, fabsf(y[tc][v]));
+            mx = dl_wave_max_nonneg(mx) * yun;
+        }
+        // the rotation wavefronts exchange their extremes among themselves
+        if (lane == 0) {
+            red[wave] = mx;
+            if constexpr (ASYM) red[16 + wave] = mn;
+        }
         meet(cnt + 1, STRIPS);
-        float amax = 0.0f;
+        float amax = 0.0f, amin = 0.0f;
 #pragma unroll
-        for (int w = 0; w < STRIPS; ++w) amax = fmaxf(amax, red[w]);
-        const float inv = amax > 0.0f ? a.qmax * __builtin_amdgcn_rcpf(amax) * yun : 0.0f;   // (on this strip's scaled values)
+        for (int w = 0; w < STRIPS; ++w) {
+            amax = fmaxf(amax, red[w]);
+            if constexpr (ASYM) amin = fminf(amin, red[16 + w]);
+        }
+        // (factor on this strip's scaled values; the constant that rounds carries the zero point)
+        float inv = amax > 0.0f ? a.qmax * __builtin_amdgcn_rcpf(amax) * yun : 0.0f, addc = 12582912.0f;
+        if constexpr (ASYM) {
+            const QuantPlan qp = quant_plan(amax, amin, a.qmax, true);
+            inv = qp.inv * yun;
+            addc = 12582912.0f + qp.zc;
+        }
+        const float cmin = 12582912.0f - (a.qmax + 1.0f), cmax = 12582912.0f + a.qmax;
 
         // ============================================================ codes
         // lane holds Yt[d = 16 strip + 4 lg + v][c = 16 tc + li]: four consecutive k = c n2 + d.
-        // x * inv + 1.5 * 2^23 rounds to an integer (ties to even) whose low byte is the code.
+        // x * inv + 1.5 * 2^23 (+ zero point) rounds to an integer (ties to even) whose low byte is the
+        // code; only asymmetric codes can leave their range (by one, at the top) and are clamped.
         int lsum = 0;
 #pragma unroll
         for (int tc = 0; tc < AT; ++tc) {
             uint32_t cb[4];
 #pragma unroll
-            for (int v = 0; v < 4; ++v) cb[v] = __float_as_uint(__builtin_fmaf(y[tc][v], inv, 12582912.0f));
+            for (int v = 0; v < 4; ++v) {
+                float f = __builtin_fmaf(y[tc][v], inv, addc);
+                if constexpr (ASYM) f = __builtin_amdgcn_fmed3f(f, cmin, cmax);
+                cb[v] = __float_as_uint(f);
+            }
             const uint32_t lo = __builtin_amdgcn_perm(cb[1], cb[0], 0x0c0c0400u);      // bytes: cb0.b0, cb1.b0, 0, 0
             const uint32_t hi = __builtin_amdgcn_perm(cb[3], cb[2], 0x04000c0cu);      // bytes: 0, 0, cb2.b0, cb3.b0
             const uint32_t word = lo | hi;
@@ -556,11 +587,12 @@ __global__ __launch_bounds__(DL_THREADS) void decode_layer_kernel(const uint16_t
     bwla_lds_barrier();
 
     // token-wide values
-    float amax = 0.0f;
+    float amax = 0.0f, amin = 0.0f;
     int qs = 0;
 #pragma unroll
     for (int w = 0; w < STRIPS; ++w) {
         amax = fmaxf(amax, red[w]);
+        if constexpr (ASYM) amin = fminf(amin, red[16 + w]);
         qs += reinterpret_cast<const int*>(red)[4 + w];
     }
     // workgroup 0 also writes the token's codes out
@@ -571,16 +603,21 @@ __global__ __launch_bounds__(DL_THREADS) void decode_layer_kernel(const uint16_t
     // ================================================================ epilogue: every wavefront its round
     if (my_round < a.rounds) {
         const int rd = my_round;
-        const float st = amax / a.qmax;
+        const float st = ASYM ? quant_scale(amax, amin, a.qmax, true) : amax / a.qmax;
+        const float zc = ASYM ? quant_plan(amax, amin, a.qmax, true).zc : 0.0f;
+        const int jshift = a.ru + (ASYM ? 2 : 0);
         float* tf = tfin + wave * 16 * DL_MAXJTV;
-        // T as the epilogue reads it: the PSP columns, then the column a row shift adds
+        // T as the epilogue reads it: the PSP columns, then the columns the layer's mode adds
+        // (asymmetric codes: -scale * zero point, twice; row shift: scale * sum of (code - zero point))
         if (JTV > 0) {
             for (int j = lane; j < 16 * JTV; j += 64) {
                 float tv = 0.0f;
                 if (j < a.ru) {
                     tv = txl[DL_SLICES * 16 * DL_MAXJTU + j];
-                } else if (a.shift && j == a.ru) {
-                    tv = st * (float)qs;
+                } else if (j < jshift) {
+                    tv = -(st * zc);
+                } else if (a.shift && j == jshift) {
+                    tv = st * ((float)qs - (float)K * zc);
                 }
                 tf[j] = tv;
                 if (blk == 0 && rd == 0 && j < a.r) a.T[j] = tv;
@@ -620,11 +657,22 @@ __global__ __launch_bounds__(DL_THREADS) void decode_layer_kernel(const uint16_t
     }
 }
 
+using DlKernel = void (*)(const uint16_t*, const uint16_t*, const uint16_t*, const uint4*, const __half*, const __half*,
+                          const __half*, DlArgs);
+// (asymmetric codes bring at least their two columns of V)
+template <int N1, int N2, int JTU, int JTV>
+DlKernel dl_kernel_for(bool asym) {
+    if constexpr (JTV >= 1) {
+        if (asym) return decode_layer_kernel<N1, N2, JTU, JTV, true>;
+    }
+    return decode_layer_kernel<N1, N2, JTU, JTV, false>;
+}
+
 size_t dl_lds_bytes(int K, int n1, int n2, bool with_t) {
     const int at = n1 >> 4, ch2 = n1 >> 5;
     (void)with_t;
     return (size_t)2 * K + (size_t)ch2 * 2 * at * 1024 + K + 2 * (K / DL_SLICES) +
-           (16 + 4 * 16 * DL_MAXJTU + (DL_SLICES + 1) * 16 * DL_MAXJTU + 8 * 16 * DL_MAXJTV) * sizeof(float) +
+           (32 + 4 * 16 * DL_MAXJTU + (DL_SLICES + 1) * 16 * DL_MAXJTU + 8 * 16 * DL_MAXJTV) * sizeof(float) +
            DL_MAXROUNDS * DL_TPW * 8 * 16 * sizeof(int);
 }
 
@@ -634,8 +682,8 @@ size_t dl_lds_bytes(int K, int n1, int n2, bool with_t) {
 // Single-launch decode layer.  *done = false (and nothing launched) when the shape is outside what
 // the kernel takes: one bf16 token; Kronecker factors of 32 or 64, or 128 x 64 (K = 1024 .. 8192, which
 // covers the 4096- and 8192-wide models' attention and up/gate projections); PSP rank up to 96 (and then at least
-// 512 output channels, so that the projection has its 32 producers); symmetric codes, with or
-// without the row shift.  dws_head: the first BWLA_WS_HEAD bytes of the caller's scratch.  With
+// 512 output channels, so that the projection has its 32 producers); symmetric or asymmetric codes (the
+// latter up to 7 bits), with or without the row shift.  dws_head: the first BWLA_WS_HEAD bytes of the caller's scratch.  With
 // dry_run nothing is launched and *done only says whether the kernel would serve the call.
 hipError_t bwla_launch_decode_layer(const bwla_layer_t* L, const void* dX, int xdtype, int64_t M, int8_t* dq,
                                     float* dscale, int32_t* dqsum, float* dT, void* dws_head, float* dY,
@@ -644,10 +692,12 @@ hipError_t bwla_launch_decode_layer(const bwla_layer_t* L, const void* dX, int x
     const int n1 = L->n1, n2 = L->n2;
     if (M != 1 || xdtype != BWLA_X_BF16) return hipSuccess;
     if ((n1 != 32 && n1 != 64 && n1 != 128) || (n2 != 32 && n2 != 64)) return hipSuccess;
-    if ((L->mode & BWLA_MODE_ASYM_ACT) != 0) return hipSuccess;
+    const bool asym = (L->mode & BWLA_MODE_ASYM_ACT) != 0;
+    if (asym && act_bits > 7) return hipSuccess;          // (the stored code -128 has no negated byte)
     const int ru = bwla_rank_u(L), r = L->r;
     const int jtu = (ru + 15) >> 4, jtv = (r + 15) >> 4;
     if (jtu > DL_MAXJTU || jtv > DL_MAXJTV) return hipSuccess;
+    if (asym && jtv < 1) return hipSuccess;               // (cannot be: the mode brings two columns)
     const int K = (int)L->K, chunks = (int)bwla_chunks(L->K), row_tiles = (int)bwla_row_tiles(L->N);
     if (chunks > 16 || chunks < 2 || (K & 511) != 0) return hipSuccess;
     const char* blob = (const char*)L->d_blob;
@@ -683,7 +733,7 @@ hipError_t bwla_launch_decode_layer(const bwla_layer_t* L, const void* dX, int x
     hipError_t e = hipSuccess;
     bool found = false;
 #define DL_CASE(A_, B_, U_, V_) \
-    if (n1 == A_ && n2 == B_ && jtu == U_ && jtv == V_) { found = true; e = launch(decode_layer_kernel<A_, B_, U_, V_>); }
+    if (n1 == A_ && n2 == B_ && jtu == U_ && jtv == V_) { found = true; e = launch(dl_kernel_for<A_, B_, U_, V_>(asym)); }
 #define DL_RANKS(A_, B_) \
     DL_CASE(A_, B_, 0, 0) DL_CASE(A_, B_, 0, 1) DL_CASE(A_, B_, 1, 1) DL_CASE(A_, B_, 1, 2) DL_CASE(A_, B_, 2, 2) \
     DL_CASE(A_, B_, 2, 3) DL_CASE(A_, B_, 3, 3) DL_CASE(A_, B_, 3, 4) DL_CASE(A_, B_, 4, 4) DL_CASE(A_, B_, 4, 5)

@@ -260,6 +260,12 @@ def test_row_shift_with_eight_bit_codes():
     (6, True, 515, 8192, 128, 64, 40, 8, "bf16"),    # looping rotation, two tokens at a time, odd token count
     (4, False, 40, 1024, 32, 32, 200, 16, "bf16"),   # A4
     (7, True, 5, 2048, 32, 64, 333, 8, "bf16"),      # the widest the offset form allows
+    # one token, one launch: the paper's own setting (asymmetric codes, row shift) on the 7B shapes
+    (6, True, 1, 4096, 64, 64, 4096, 64, "bf16"),    # 64 + 2 + 1 columns: five tiles of V
+    (6, True, 1, 4096, 64, 64, 1029, 0, "bf16"),     # the three mode columns only, ragged channels
+    (6, True, 1, 8192, 128, 64, 1024, 61, "bf16"),   # 8192 columns, 64 columns of V in all
+    (7, False, 1, 4096, 64, 64, 520, 0, "bf16"),     # 7-bit codes: the two zero-point columns only
+    (4, True, 1, 2048, 64, 32, 600, 13, "bf16"),     # 4-bit codes, 13 + 3 = 16 columns
 ])
 def test_asymmetric_activation_codes(bits, centered, M, K, n1, n2, N, r, xd):
     """Layers packed with BWLA_MODE_ASYM_ACT (paper Sec. 4.1: per-token asymmetric activation
@@ -267,6 +273,27 @@ def test_asymmetric_activation_codes(bits, centered, M, K, n1, n2, N, r, xd):
     from parity_util import run_case_asym
     cfg = syn.LayerConfig(f"asym{bits}_{M}_{K}_{N}_{r}", M, K, n1, n2, N, r, xd, max(1, K // 100), 20.0, seed=15)
     print(run_case_asym(cfg, centered=centered, act_bits=bits), flush=True)
+
+
+def test_asymmetric_codes_single_launch_shapes_and_zero_token():
+    """One bf16 token on a layer with asymmetric codes is served by a single launch (shapes of the decode
+    kernel); a token of zeros gives step 0, every stored code at the bottom of its range (q = z = 0),
+    zero mode columns and a zero output."""
+    from parity_util import to_dev, DEV
+    from paper_2605_00422_amd import binding as B
+    cfg = syn.LayerConfig("asym_zero_tok", 1, 4096, 64, 64, 777, 32, "bf16", 0, 1.0, seed=21)
+    d = syn.make_layer(cfg)
+    layer = B.pack_weights(to_dev(syn.shifted_weights(d)), to_dev(d.R1), to_dev(d.R2), to_dev(d.U), to_dev(d.V), cfg.n1,
+                           cfg.n2, centered=True, asym=True)
+    assert B.decode_forward_launches(layer, 1) == 1
+    X = torch.zeros((1, cfg.K), dtype=torch.bfloat16, device=DEV)
+    act = B.Activations(layer, 1)
+    Y = torch.full((1, cfg.N), float("nan"), dtype=torch.float32, device=DEV)
+    B.decode_forward(layer, X, act, Y)
+    torch.cuda.synchronize()
+    assert float(act.scale[0]) == 0.0
+    assert torch.all(act.q == -32) and int(act.qsum[0]) == -32 * cfg.K
+    assert torch.count_nonzero(act.T) == 0 and torch.count_nonzero(Y) == 0
 
 
 @pytest.mark.parametrize("M,K,n1,n2,N,r,xd", [
