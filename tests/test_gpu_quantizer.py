@@ -302,3 +302,43 @@ def test_quantize_layer_at_the_7b_shape():
     want = fwd.kron_rotate(W[rows].astype(np.float64) - Vh[rows] @ Uh.T, r1, r2)
     assert _rel(wr[rows], want) < 1e-5
     assert np.linalg.matrix_rank(Vh, tol=1e-9) == k
+
+
+def test_quantized_layer_through_the_online_path():
+    """Algorithm 2's result handed to the online path (Sec. 3.2: Y = Q(X R) B'^T + (X U) V^T): the factors,
+    W_rot and the balanced U, V are packed by the forward path's own call and one decode call runs a few
+    tokens through them.  The output equals the oracle's forward on the same factors (criterion of
+    the parity tests), and against the dense product X W^T it is closer than the layer binarized as it
+    stands (identity rotations, no low-rank branch): the planted low-rank part, which dominates the
+    binarization error of the raw matrix, now travels through the PSP branch in fp16."""
+    from paper_2605_00422_amd import binding as B
+    from parity_util import check_output
+    qb = _qb()
+    n, n1, n2, k, t, M = 512, 32, 32, 8, 3, 8
+    m = n1 * n2
+    rng, W, _, _, _, _ = _problem(11, n, n1, n2, k, planted=0.05)
+    W = W.astype(np.float32).astype(np.float64)
+    f32 = lambda *s: torch.empty(*s, dtype=torch.float32, device="cuda")
+    R1, R2, Wrot, U, V = f32(n1, n1), f32(n2, n2), f32(n, m), f32(m, k), f32(n, k)
+    qb.quantize_layer(_dev(W, torch.float32), n1, n2, k, t, R1, R2, Wrot, U, V, None, None, None, _ws(n, m, n1, n2, k),
+                      svd_iters=100, svd_tol=1e-12)
+    X = fwd.to_bf16(rng.standard_normal((M, m)))
+    Xg = _dev(X, torch.bfloat16)
+    dense = X @ W.T
+
+    def run(layer):
+        act = B.Activations(layer, M)
+        Y = torch.empty((M, n), dtype=torch.float32, device="cuda")
+        B.decode_forward(layer, Xg, act, Y)
+        torch.cuda.synchronize()
+        return Y.double().cpu().numpy()
+
+    Yq = run(B.pack_weights(Wrot, R1, R2, U, V, n1, n2, centered=True))
+    ref = fwd.forward(X, R1.double().cpu().numpy(), R2.double().cpu().numpy(), Wrot.double().cpu().numpy(),
+                      U.double().cpu().numpy(), V.double().cpu().numpy(), centered=True)
+    check_output(Yq, ref["Y"])
+    eye = lambda s: torch.eye(s, dtype=torch.float32, device="cuda")
+    Y0 = run(B.pack_weights(_dev(W, torch.float32), eye(n1), eye(n2), None, None, n1, n2, centered=True))
+    err = lambda Y: float(np.linalg.norm(Y - dense) / np.linalg.norm(dense))
+    print(dict(quantized=err(Yq), as_it_stands=err(Y0)), flush=True)
+    assert err(Yq) < 0.85 * err(Y0)
