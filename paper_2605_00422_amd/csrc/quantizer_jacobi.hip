@@ -20,7 +20,9 @@
 
 namespace {
 
-constexpr int JT = 1024, JW = JT / 64, JMAX = 256, JLDS = 96;
+constexpr int JMAX = 256, JLDS = 96;
+// threads of the workgroup: a row of 16 lanes per pair serves 32 pairs (n <= 64) with 512 threads
+constexpr int jacobi_threads(int gw) { return gw == 16 ? 512 : 1024; }
 
 template <int CTRL>
 __device__ __forceinline__ double jdpp(double v) {
@@ -49,8 +51,9 @@ __device__ __forceinline__ double jgroup_sum(double v) {
 
 // GW: lanes per pair (16 for n <= 64, else 64); LDS: the work arrays live in dynamic LDS
 template <int GW, bool LDS>
-__global__ __launch_bounds__(JT) void jacobi_kernel(QJacobi a) {
+__global__ __launch_bounds__(jacobi_threads(GW)) void jacobi_kernel(QJacobi a) {
     if (a.skip && *a.skip) return;
+    constexpr int JT = jacobi_threads(GW), JW = JT / 64;
     const int n = a.n, t = threadIdx.x, lane = t & 63, w = t >> 6;
     extern __shared__ double jlds[];
     double* Wc = LDS ? jlds : a.work;
@@ -101,10 +104,12 @@ __global__ __launch_bounds__(JT) void jacobi_kernel(QJacobi a) {
                 al = jgroup_sum<GW>(al);
                 be = jgroup_sum<GW>(be);
                 ga = jgroup_sum<GW>(ga);
-                if (live && al > 0.0 && be > 0.0 && fabs(ga) > 1.0e-15 * sqrt(al * be)) {
+                // (|ga| > 1e-15 sqrt(al be), without the root; four special-function calls a rotation instead
+                // of six: their dependent chain is most of what a round costs)
+                if (live && al > 0.0 && be > 0.0 && ga * ga > 1.0e-30 * (al * be)) {
                     const double zeta = (be - al) / (2.0 * ga);
                     const double tt = copysign(1.0, zeta) / (fabs(zeta) + sqrt(1.0 + zeta * zeta));
-                    const double cs = 1.0 / sqrt(1.0 + tt * tt), sn = cs * tt;
+                    const double cs = rsqrt(1.0 + tt * tt), sn = cs * tt;
                     double* vp = Vc + (size_t)p * n;
                     double* vq = Vc + (size_t)q * n;
 #pragma unroll
@@ -172,15 +177,15 @@ __global__ __launch_bounds__(JT) void jacobi_kernel(QJacobi a) {
 hipError_t bwla_q_launch_jacobi(const QJacobi& j, hipStream_t st) {
     if (j.n < 1 || j.n > JMAX) return hipErrorInvalidValue;
     const size_t lds = j.n <= JLDS ? (size_t)2 * j.n * j.n * sizeof(double) : 0;
-    auto launch = [&](auto kern) {
+    auto launch = [&](auto kern, int threads) {
         if (lds > 48 * 1024) {
             const hipError_t e = bwla_ensure_lds((const void*)kern, lds);
             if (e != hipSuccess) return e;
         }
-        hipLaunchKernelGGL(kern, dim3(1), dim3(JT), lds, st, j);
+        hipLaunchKernelGGL(kern, dim3(1), dim3(threads), lds, st, j);
         return hipGetLastError();
     };
-    if (j.n <= 64) return launch(jacobi_kernel<16, true>);
-    if (j.n <= JLDS) return launch(jacobi_kernel<64, true>);
-    return launch(jacobi_kernel<64, false>);
+    if (j.n <= 64) return launch(jacobi_kernel<16, true>, jacobi_threads(16));
+    if (j.n <= JLDS) return launch(jacobi_kernel<64, true>, jacobi_threads(64));
+    return launch(jacobi_kernel<64, false>, jacobi_threads(64));
 }
