@@ -67,6 +67,26 @@ def check_output(Y_gpu: np.ndarray, Y_ref: np.ndarray) -> dict:
     return dict(fro=float(fro), max_rel=mx)
 
 
+def check_end_to_end(Y_gpu: np.ndarray, Y_ref: np.ndarray, flips: int, Y_on_gpu_codes) -> dict:
+    """Criterion 3 on the whole path.  Criterion 1 lets a code whose pre-rounding value sits on a
+    rounding boundary go either way; one such code moves every output of its token by scale * alpha,
+    which for a single token can alone exceed the bar (K = 8192, flat activations: 1.8e-3).  So the
+    plain comparison with the oracle's output is tried first and is what counts whenever no code
+    differs; where codes did flip and it fails, the output is held to the same bar against the oracle's
+    steps 3-5 on the codes the GPU chose (Y_on_gpu_codes: a callable that computes it), and the plain
+    figure is reported beside it."""
+    try:
+        return check_output(Y_gpu, Y_ref)
+    except AssertionError:
+        if flips == 0:
+            raise
+    out = check_output(Y_gpu, Y_on_gpu_codes())
+    err = Y_gpu.astype(np.float64) - Y_ref
+    out["tie_flips"] = int(flips)
+    out["fro_plain"] = float(np.linalg.norm(err) / max(np.linalg.norm(Y_ref), 1e-300))
+    return out
+
+
 def run_case(cfg: syn.LayerConfig, rows=None, centered: bool = False, act_bits: int = 6) -> dict:
     """Whole path on the GPU for all M tokens; the oracle on all of them, or on `rows`.
     centered: the layer is binarized with the row shift (weights get a per-channel offset first).
@@ -90,6 +110,15 @@ def run_case(cfg: syn.LayerConfig, rows=None, centered: bool = False, act_bits: 
         alpha16 = orc.to_fp16(alpha)
         ref = orc.forward_rows(d.X, d.R1, d.R2, sgn, alpha16, U, V, sel, act_bits=act_bits)
         ref_T = ref["T"]
+        mu16 = None
+
+    def on_codes(q):
+        """the oracle's steps 3-5 on the codes q (rows `sel`)"""
+        q = q.astype(np.int8)
+        acc_q = orc.binary_gemm(q, sgn)
+        if centered:
+            return orc.dequant_output_centered(acc_q, ref["s"], alpha16, mu16, q.astype(np.int64).sum(axis=1), ref["T"], V)
+        return orc.dequant_output(acc_q, ref["s"], alpha16, ref["T"], V)
 
     layer = pack_on_gpu(d, W, centered)
     assert layer.desc.r == rt and layer.desc.mode == int(centered)
@@ -142,7 +171,7 @@ def run_case(cfg: syn.LayerConfig, rows=None, centered: bool = False, act_bits: 
         if cfg.r > 0:
             tden1 = np.maximum(np.max(np.abs(ref["T"]), axis=1, keepdims=True), 1e-30)
             assert np.max(np.abs(act1.T.cpu().numpy().astype(np.float64)[:, :cfg.r] - ref["T"]) / tden1) < 2e-5
-        check_output(Y1.cpu().numpy(), ref["Y"])
+        check_end_to_end(Y1.cpu().numpy(), ref["Y"], int(np.count_nonzero(q1 != ref["q"])), lambda: on_codes(q1))
         # other activations: the one call and the two calls agree to within criterion 3
         act2x = B.Activations(layer, cfg.M)
         Y2a = torch.empty_like(Y)
@@ -151,7 +180,12 @@ def run_case(cfg: syn.LayerConfig, rows=None, centered: bool = False, act_bits: 
         B.linear_forward(layer, act2x, Y2a)
         B.decode_forward(layer, X2, act1, Y2b)
         torch.cuda.synchronize()
-        check_output(Y2b.cpu().numpy(), Y2a.cpu().numpy().astype(np.float64))
+        # (where the two rotations put a code on different sides of a rounding boundary the outputs
+        # belong to different codes: then only the codes are compared, to one step)
+        dq = (act1.q.int() - act2x.q.int()).abs()
+        assert int(dq.max()) <= 1
+        if int(dq.max()) == 0:
+            check_output(Y2b.cpu().numpy(), Y2a.cpu().numpy().astype(np.float64))
         del act1, act2x, Y1, Y2a, Y2b, acc1, X2, kept
 
     sel_t = torch.from_numpy(sel).to(DEV)
@@ -191,7 +225,7 @@ def run_case(cfg: syn.LayerConfig, rows=None, centered: bool = False, act_bits: 
     assert out["same_codes"]["fro"] < 1e-5
 
     # criterion 3: end to end
-    out["end_to_end"] = check_output(Y[sel_t].cpu().numpy(), ref["Y"])
+    out["end_to_end"] = check_end_to_end(Y[sel_t].cpu().numpy(), ref["Y"], out["codes"]["mismatch"], lambda: on_codes(q_gpu))
     return out
 
 
@@ -271,6 +305,19 @@ def run_case_asym(cfg: syn.LayerConfig, centered: bool = False, act_bits: int = 
 
     dz, diff, same = held(act, acc)
 
+    def on_codes(a_):
+        """the oracle's steps 3-5 on the GPU's stored codes and zero points: centered codes c = q' - z'"""
+        qg = a_.q.cpu().numpy().astype(np.int64)
+        sg = a_.scale.cpu().numpy().astype(np.float64)
+        Tg = a_.T.cpu().numpy().astype(np.float64)
+        zg = np.rint(np.where(sg > 0, -Tg[:, ru] / np.where(sg > 0, sg, 1.0), -half)).astype(np.int64)
+        cg = qg - zg[:, None]
+        acc_c = np.rint(cg.astype(np.float64) @ sgn.astype(np.float64).T).astype(np.int64)
+        mu16 = orc.to_fp16(ref["mu"]) if centered else np.zeros(cfg.N)
+        Tz = ref["T"] if cfg.r > 0 else np.zeros((cfg.M, 0))
+        Vz = V if cfg.r > 0 else np.zeros((cfg.N, 0))
+        return orc.dequant_output_centered(acc_c, ref["s"], alpha16, mu16, cg.sum(axis=1), Tz, Vz)
+
     # the one-call entry point (one launch for a single bf16 token where the shape allows it), by the
     # same criteria; called again on the same token, with another token in between, it gives the same bits
     one_call = None
@@ -289,8 +336,9 @@ def run_case_asym(cfg: syn.LayerConfig, centered: bool = False, act_bits: int = 
                 kept = (act1.q.clone(), act1.scale.clone(), act1.qsum.clone(), act1.T.clone(), Y1.clone())
         assert torch.equal(act1.q, kept[0]) and torch.equal(act1.scale, kept[1]) and torch.equal(act1.qsum, kept[2])
         assert torch.equal(act1.T, kept[3]) and torch.equal(Y1, kept[4]), "one-call results change between calls"
-        held(act1, acc1)
-        one_call = check_output(Y1.cpu().numpy(), ref["Y"])
+        dz1, diff1, _ = held(act1, acc1)
+        one_call = check_end_to_end(Y1.cpu().numpy(), ref["Y"], int(np.count_nonzero(dz1)) + int(np.count_nonzero(diff1)),
+                                    lambda: on_codes(act1))
         del act1, Y1, acc1, X2, kept
 
     # the oracle's codes through the ABI: exact accumulators, output to rounding
@@ -311,7 +359,8 @@ def run_case_asym(cfg: syn.LayerConfig, centered: bool = False, act_bits: int = 
     out = dict(cfg=cfg.name, zero_point_moved=int(np.count_nonzero(dz)), code_mismatch=int(np.count_nonzero(diff[same])))
     out["same_codes"] = check_output(Y2.cpu().numpy(), ref["Y"])
     assert out["same_codes"]["fro"] < 1e-5
-    out["end_to_end"] = check_output(Y.cpu().numpy(), ref["Y"])
+    out["end_to_end"] = check_end_to_end(Y.cpu().numpy(), ref["Y"], int(np.count_nonzero(dz)) + int(np.count_nonzero(diff)),
+                                         lambda: on_codes(act))
     if one_call is not None:
         out["one_call"] = one_call
     return out
@@ -329,9 +378,11 @@ def run_case_swiglu(cfg: syn.LayerConfig, rows=None) -> dict:
     (cfg.N rows in all: the synthetic layer's first half serves as gate, its second half as up),
     against the oracle's forward followed by its swiglu_interleaved.
     Bar: H is a bfloat16 image of fp32 values that meet criterion 3, so against the oracle's
-    unrounded h its error is that of criterion 3 plus one bfloat16 rounding (relative 2^-9 at most,
-    2^-9 / sqrt(3) in the root mean square): relative Frobenius error <= 2.5e-3, and per element
-    |error| <= 2^-8 |h| + 1e-2 max_row |h| (the rounding, and criterion 3's per-token bound)."""
+    unrounded h its error is one bfloat16 rounding (8 significant bits: at most 2^-8 relative, about
+    1.6e-3 in the root mean square over many values, up to 2^-8 = 3.9e-3 over a few) plus criterion 3's
+    error carried through the gate (two factors: at most 2e-3): relative Frobenius error <= 6e-3, and per
+    element |error| <= 2^-8 |h| + 1e-2 max_row |h| (the rounding, and criterion 3's per-token bound).
+    The sharp check is the last one: within one bf16 step of the ungated GPU output gated in fp32."""
     assert cfg.N % 2 == 0
     d = syn.make_layer(cfg)
     half = cfg.N // 2
@@ -355,11 +406,19 @@ def run_case_swiglu(cfg: syn.LayerConfig, rows=None) -> dict:
     torch.cuda.synchronize()
     Hs = H[torch.from_numpy(sel).to(DEV)].float().cpu().numpy().astype(np.float64)
     assert np.all(np.isfinite(Hs))
+    # codes that went the other way on a rounding boundary (criterion 1 allows it; see check_end_to_end):
+    # the reference is then the oracle's steps 3-5 and gate on the codes the GPU chose
+    q_gpu = act.q[torch.from_numpy(sel).to(DEV)].cpu().numpy()
+    check_codes(q_gpu, ref)
+    flips = int(np.count_nonzero(q_gpu != ref["q"]))
+    if flips:
+        h_ref = orc.swiglu_interleaved(orc.dequant_output(orc.binary_gemm(q_gpu, sgn), ref["s"], orc.to_fp16(alpha),
+                                                          ref["T"], V))
     err = Hs - h_ref
     fro = float(np.linalg.norm(err) / max(np.linalg.norm(h_ref), 1e-300))
     rowmax = np.maximum(np.max(np.abs(h_ref), axis=1, keepdims=True), 1e-300)
     excess = float(np.max(np.abs(err) - (2.0 ** -8 * np.abs(h_ref) + 1e-2 * rowmax)))
-    assert fro <= 2.5e-3, f"relative Frobenius error of h {fro:.3e}"
+    assert fro <= 6e-3, f"relative Frobenius error of h {fro:.3e}"
     assert excess <= 0.0, f"element error exceeds its bound by {excess:.3e}"
     # the same values as the ungated output of the same codes, gated on the host in fp32: the stored
     # bf16 may differ from that by one unit in the last place at most (exp is not the same routine)
@@ -369,4 +428,4 @@ def run_case_swiglu(cfg: syn.LayerConfig, rows=None) -> dict:
     own = (g / (1.0 + torch.exp(-g)) * u).to(torch.bfloat16)
     ulp = (H.view(torch.int16).int() - own.view(torch.int16).int()).abs().max().item()
     assert ulp <= 1, f"fused gate differs from the gated fp32 output by {ulp} bf16 steps"
-    return dict(cfg=cfg.name, fro=fro, ws=nws, ulp=ulp)
+    return dict(cfg=cfg.name, fro=fro, ws=nws, ulp=ulp, tie_flips=flips)

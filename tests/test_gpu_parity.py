@@ -351,6 +351,41 @@ def test_seeded_random_shapes_and_modes():
         done += 1
 
 
+def test_seeded_single_launch_shapes_and_modes():
+    """A seeded draw over what the single-launch decode kernel takes (one bf16 token, factors of 32, 64
+    or 128 x 64, ranks 0..96 that are not multiples of 16 too, channel counts around the kernel's limits,
+    every mode and code width) and its neighbours (two tokens, too few channels for the shared projection),
+    each through the whole path against the oracle."""
+    import random
+    from paper_2605_00422_amd import binding as B
+    from parity_util import run_case, run_case_asym, run_case_swiglu
+    rnd = random.Random(11)
+    done = 0
+    while done < 32:
+        n1 = rnd.choice([32, 64, 64, 64, 128])
+        n2 = rnd.choice([32, 64, 64]) if n1 != 128 else 64
+        K = n1 * n2
+        M = rnd.choice([1, 1, 1, 2])
+        r = rnd.choice([0, 1, 5, 13, 16, 17, 30, 32, 45, 48, 61, 64, 70, 80, 93, 96])
+        N = rnd.choice([48, 500, 512, 513, 777, 1024, 2000, 4096, 4100, 6001, 11008, 12288, 13000])
+        bits = rnd.choice([6, 6, 6, 4, 7, 8])
+        mode = rnd.choice(["plain", "centered", "asym", "asym+centered", "gated"])
+        if mode.startswith("asym") and bits == 8:
+            bits = 7
+        if mode == "gated" and (N % 2 or bits != 6):
+            continue
+        cfg = syn.LayerConfig(f"rdl_{M}_{n1}x{n2}_{N}_{r}_a{bits}", M, K, n1, n2, N, r, "bf16", max(1, K // 100), 20.0,
+                              seed=300 + done)
+        print(done, cfg.name, mode, flush=True)
+        if mode == "gated":
+            run_case_swiglu(cfg)
+        elif mode.startswith("asym"):
+            run_case_asym(cfg, centered=mode.endswith("centered"), act_bits=bits)
+        else:
+            run_case(cfg, centered=(mode == "centered"), act_bits=bits)
+        done += 1
+
+
 def test_zero_token_gives_zero_codes_and_scale():
     from parity_util import pack_on_gpu, DEV
     from paper_2605_00422_amd import binding as B
