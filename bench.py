@@ -412,13 +412,28 @@ def quantizer_report(torch, rounds=2, svd_iters=20):
     r1, r2 = R1.double(), R2.double()
     ms_okt = timed(lambda: qb.okt_rows(W64, A, Bt, r1, r2, X, None, ws), 5)
     passes = 8 * n * m * 8            # W - M, two GEMM stages, centering: each reads and writes n x m fp64
+    # the down projection of the same block (128 x 86 factors: the polar factors of the Procrustes
+    # updates come from the Newton-Schulz iteration there, not from the Jacobi SVD)
+    del W64, X, A, Bt, Wrot, U, V
+    dn, d1, d2 = 4096, 128, 86
+    dm = d1 * d2
+    Wd = torch.randn(dn, dm, device="cuda", dtype=torch.float32, generator=g) * 0.02
+    wsd = ws[:qb.workspace_size(dn, dm, d1, d2, k)] if qb.workspace_size(dn, dm, d1, d2, k) <= ws.numel() else \
+        torch.zeros(qb.workspace_size(dn, dm, d1, d2, k), dtype=torch.uint8, device="cuda")
+    dR1, dR2, dWrot, dU, dV, dc, ds2 = f32(d1, d1), f32(d2, d2), f32(dn, dm), f32(dm, k), f32(dn, k), f64(dn), f64(dn)
+    dhist = f64(1 + 3 * rounds)
+    ms_down = timed(lambda: qb.quantize_layer(Wd, d1, d2, k, rounds, dR1, dR2, dWrot, dU, dV, dc, ds2, dhist, wsd,
+                                              svd_iters=svd_iters, svd_tol=0.0), 2)
+    down = {"workload": f"Gaussian {dn} x {dm} (Kronecker {d1} x {d2}), rank {k}", "ms_per_round": ms_down / rounds,
+            "loss_history": [float(v) for v in dhist.cpu()]}
     return {"workload": f"Gaussian {n} x {m} (Kronecker {n1} x {n2}), rank {k}", "dtype": "f64",
             "rounds": rounds, "svd_iters_per_round": svd_iters, "ms_total": ms, "ms_per_round": ms / rounds,
             "loss_history": [float(v) for v in hist.cpu()],
             "okt_rows": {"ms": ms_okt, "bound": "hbm", "bytes_moved": passes,
                          "achieved": passes / (ms_okt * 1e-3) / 1e9, "peak": 8000.0, "unit": "GB/s",
                          "frac": passes / (ms_okt * 1e-3) / 1e9 / 8000.0,
-                         "flops": 2 * n * m * (n1 + n2 + k)}}
+                         "flops": 2 * n * m * (n1 + n2 + k)},
+            "down_projection": down}
 
 
 def cpu_baseline(w, budget_s=12.0):

@@ -74,7 +74,9 @@ BWLA_API bwla_status_t bwla_q_gmm_nll(const double* d_X, int64_t n, int64_t m, c
  * sum_i lambda_i || R1^T V_i R2 - T_i ||_F^2 (polar factor of C1 = sum_i lambda_i V_i R2 T_i^T),
  * which = 2 the minimizer over R2 (C2 = sum_i lambda_i V_i^T R1 T_i); V_i is row i of d_Wres = W - M
  * reshaped, T_i its target.  d_Rnew out, n1 x n1 or n2 x n2.  The polar factor comes from a one-sided
- * Jacobi SVD; a singular C has no unique one and gives an undefined (finite) result.
+ * Jacobi SVD for factors up to 64 and from the Newton-Schulz iteration X <- X (3 I - X^T X) / 2 on
+ * C / ||C||_F above (the same matrix, from small GEMMs instead of a single workgroup); a singular C
+ * has no unique one and gives an undefined (finite) result.
  */
 BWLA_API bwla_status_t bwla_q_procrustes(int32_t which, const double* d_Wres, const double* d_R1,
                                          const double* d_R2, const double* d_c, const double* d_s2, int64_t n,

@@ -115,9 +115,46 @@ const double* okt(Ctx& x, const double* W, const double* A, const double* Bt, co
     return Wres;
 }
 
+// Above this size the polar factor comes from the Newton-Schulz iteration (a few dozen small GEMMs on
+// the matrix cores) instead of the one-workgroup Jacobi SVD, whose time grows with the cube of the size
+// (86: 4 ms, 128: 11 ms, 256: 81 ms).
+constexpr int POLAR_JACOBI_MAX = 64;
+constexpr int POLAR_NS_PAIRS = 32;
+
 // polar factor of the jn-sized scratch matrix C (nn x nn) into R
 void polar(Ctx& x, int nn, double* R) {
     const QPlan& P = x.P;
+    if (nn > POLAR_JACOBI_MAX) {
+        // X <- X (3 I - X^T X) / 2 from X = C / ||C||_F: singular values in (0, 1] rise to 1 (by 3/2 per
+        // step while small, then quadratically), the singular vectors stay: X -> U V^T.  Steps come in
+        // pairs so that X is back in the same buffer after each; before a pair X^T X is compared with I,
+        // and once it is within 1e-13 the remaining launches return at once.  A singular C never gets
+        // there and leaves a finite matrix that is not orthogonal.
+        double *Xa = x.d(P.Ws), *Xb = x.d(P.Vs), *G = x.d(P.G);
+        int* done = x.done();
+        x.ck(bwla_q_launch_set_int(done, 0, x.st));
+        x.ck(bwla_q_launch_scale_inv_frob(x.d(P.C), nn * nn, Xa, x.st));
+        auto step = [&](const double* src, double* dst) {
+            QGemm g = qgemm_plain(src, src, G, nn, nn, nn);       // G = src^T src
+            g.rsA = 1; g.klA = nn;
+            gemm(x, g, done);
+            QGemm u = qgemm_plain(src, G, dst, nn, nn, nn);       // dst = 1.5 src - 0.5 src G
+            u.C0 = src; u.alpha = -0.5; u.beta = 1.5;
+            gemm(x, u, done);
+        };
+        for (int it = 0; it < POLAR_NS_PAIRS; ++it) {
+            if (it > 0) {
+                QGemm g = qgemm_plain(Xa, Xa, G, nn, nn, nn);
+                g.rsA = 1; g.klA = nn;
+                gemm(x, g, done);
+                x.ck(bwla_q_launch_near_identity(G, nn, 1.0e-13, done, x.st));
+            }
+            step(Xa, Xb);
+            step(Xb, Xa);
+        }
+        x.ck(hipMemcpyAsync(R, Xa, (size_t)nn * nn * sizeof(double), hipMemcpyDeviceToDevice, x.st));
+        return;
+    }
     QJacobi j{};
     j.G = x.d(P.C); j.n = nn; j.pw = -1.0; j.sig = x.d(P.sig); j.Ws = x.d(P.Ws); j.Vs = x.d(P.Vs); j.work = x.d(P.jwork);
     x.ck(bwla_q_launch_jacobi(j, x.st));

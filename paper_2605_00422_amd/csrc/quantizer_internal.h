@@ -62,6 +62,10 @@ hipError_t bwla_q_launch_gradx(const double* X, const double* c, const double* s
 // Q[i] = uniform in [-1, 1) from a counter-based hash of (seed, i)
 hipError_t bwla_q_launch_fill_hash(double* Q, size_t count, uint32_t seed, hipStream_t st);
 hipError_t bwla_q_launch_fill_identity(double* R, int n, hipStream_t st);
+// X = C / ||C||_F (count values, one workgroup; a zero matrix stays zero)
+hipError_t bwla_q_launch_scale_inv_frob(const double* C, int count, double* X, hipStream_t st);
+// *done = 1 once max |G - I| <= tol (G nn x nn); never cleared
+hipError_t bwla_q_launch_near_identity(const double* G, int nn, double tol, int* done, hipStream_t st);
 hipError_t bwla_q_launch_set_int(int* p, int v, hipStream_t st);
 hipError_t bwla_q_launch_fill_value(double* p, size_t count, double v, hipStream_t st);
 // dst[e] = src[e]^pw (0 where src <= 0)

@@ -167,6 +167,39 @@ __global__ void fill_hash_kernel(double* Q, size_t count, uint32_t seed) {
 __global__ void fill_identity_kernel(double* R, int n) {
     for (int e = blockIdx.x * RT + threadIdx.x; e < n * n; e += gridDim.x * RT) R[e] = (e / n == e % n) ? 1.0 : 0.0;
 }
+// X = C / ||C||_F, one workgroup (the start of the Newton-Schulz iteration for the polar factor:
+// every singular value of X is at most 1); a zero matrix stays zero
+__global__ __launch_bounds__(RT) void scale_inv_frob_kernel(const double* C, int count, double* X) {
+    __shared__ double sh[4];
+    double s = 0.0;
+    for (int e = threadIdx.x; e < count; e += RT) s += C[e] * C[e];
+    const double tot = block_sum(s, sh);
+    const double inv = tot > 0.0 ? 1.0 / sqrt(tot) : 0.0;
+    for (int e = threadIdx.x; e < count; e += RT) X[e] = C[e] * inv;
+}
+// *done = 1 once max |G - I| <= tol (G nn x nn, one workgroup); never cleared here
+__global__ __launch_bounds__(RT) void near_identity_kernel(const double* G, int nn, double tol, int* done) {
+    __shared__ double sh[4];
+    double worst = 0.0;
+    for (int e = threadIdx.x; e < nn * nn; e += RT) {
+        const double d = fabs(G[e] - (e / nn == e % nn ? 1.0 : 0.0));
+        worst = d > worst || d != d ? d : worst;            // (a NaN stays)
+    }
+    // (the largest by way of the sum helper's layout: per wavefront, then over the four)
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) {
+        const double o = __shfl_xor(worst, off, 64);
+        worst = o > worst || o != o ? o : worst;
+    }
+    __syncthreads();
+    if ((threadIdx.x & 63) == 0) sh[threadIdx.x >> 6] = worst;
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        double w = sh[0];
+        for (int i = 1; i < 4; ++i) w = sh[i] > w || sh[i] != sh[i] ? sh[i] : w;
+        if (w <= tol) *done = 1;
+    }
+}
 __global__ void set_int_kernel(int* p, int v) { *p = v; }
 __global__ void fill_value_kernel(double* p, size_t count, double v) {
     for (size_t e = (size_t)blockIdx.x * RT + threadIdx.x; e < count; e += (size_t)gridDim.x * RT) p[e] = v;
@@ -253,6 +286,14 @@ hipError_t bwla_q_launch_fill_hash(double* Q, size_t count, uint32_t seed, hipSt
 }
 hipError_t bwla_q_launch_fill_identity(double* R, int n, hipStream_t st) {
     hipLaunchKernelGGL(fill_identity_kernel, dim3(flat_blocks((size_t)n * n)), dim3(RT), 0, st, R, n);
+    return hipGetLastError();
+}
+hipError_t bwla_q_launch_scale_inv_frob(const double* C, int count, double* X, hipStream_t st) {
+    hipLaunchKernelGGL(scale_inv_frob_kernel, dim3(1), dim3(RT), 0, st, C, count, X);
+    return hipGetLastError();
+}
+hipError_t bwla_q_launch_near_identity(const double* G, int nn, double tol, int* done, hipStream_t st) {
+    hipLaunchKernelGGL(near_identity_kernel, dim3(1), dim3(RT), 0, st, G, nn, tol, done);
     return hipGetLastError();
 }
 hipError_t bwla_q_launch_set_int(int* p, int v, hipStream_t st) {
