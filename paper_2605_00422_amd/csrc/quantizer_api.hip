@@ -214,6 +214,7 @@ void truncate(Ctx& x, const double* Y, int iters, double tol, double* A2, double
         j.G = G; j.n = p; j.pw = pw; j.sig = x.d(P.sig); j.Vs = Vs; j.Ws = nullptr; j.work = x.d(P.jwork);
         if (track) { j.prev_sig = x.d(P.prev); j.lead = k; j.tol = tol; j.done = done; }
         j.skip = skip;
+        j.sym = true;                                       // a Gram matrix
         x.ck(bwla_q_launch_jacobi(j, x.st));
     };
     auto times_vs = [&](const double* B, int rows, int cols, double* out, const int* skip) {   // out = B Vs^T[:, :cols]
@@ -242,6 +243,7 @@ void truncate(Ctx& x, const double* Y, int iters, double tol, double* A2, double
     {
         QJacobi j{};
         j.G = G; j.n = p; j.pw = 0.0; j.sig = lam; j.Vs = Vs; j.work = x.d(P.jwork);
+        j.sym = true;
         x.ck(bwla_q_launch_jacobi(j, x.st));
     }
     times_vs(Zs, n, k, A2, nullptr);

@@ -86,9 +86,12 @@ hipError_t bwla_q_launch_row_stats(const double* Y, int n, int m, double* mean, 
 // iteration -- when prev_sig is given, done is set once the leading `lead` singular values moved by
 // at most tol relative to the previous call, and prev_sig is replaced.  The launch returns
 // immediately when *skip != 0.
+// sym: G is symmetric positive semidefinite (a Gram matrix): the rotations are not accumulated, v_j is
+// the normalized column j of G V (equal to u_j there), and matrices up to 136 wide stay in LDS.
 struct QJacobi {
     const double* G; int n; double pw;
     double* sig; double* Ws; double* Vs; double* work;
     double* prev_sig; int lead; double tol; int* done; const int* skip;
+    bool sym;
 };
 hipError_t bwla_q_launch_jacobi(const QJacobi& j, hipStream_t st);

@@ -20,7 +20,7 @@
 
 namespace {
 
-constexpr int JMAX = 256, JLDS = 96;
+constexpr int JMAX = 256, JLDS = 96, JLDS_SYM = 136;    // largest n with both arrays / with one array in LDS
 // threads of the workgroup: a row of 16 lanes per pair serves 32 pairs (n <= 64) with 512 threads
 constexpr int jacobi_threads(int gw) { return gw == 16 ? 512 : 1024; }
 
@@ -45,12 +45,17 @@ __device__ __forceinline__ double jread(double v, int lane) {
 template <int GW>
 __device__ __forceinline__ double jgroup_sum(double v) {
     v = jrow_sum(v);
+    if (GW == 32) v += __shfl_xor(v, 16, 64);          // the other row of the pair's two
     if (GW == 64) v = (jread(v, 0) + jread(v, 16)) + (jread(v, 32) + jread(v, 48));
     return v;
 }
 
-// GW: lanes per pair (16 for n <= 64, else 64); LDS: the work arrays live in dynamic LDS
-template <int GW, bool LDS>
+// GW: lanes per pair (16 for n <= 64, 32 for n <= 128, else 64); LDS: the work arrays live in dynamic LDS.
+// ACCV: the rotations are accumulated into V.  Without it (a symmetric positive semidefinite G, whose
+// left and right singular vectors coincide) the right singular vectors are the normalized columns of
+// the rotated G themselves -- orthogonal to the tolerance of the sweeps, and as accurate as eigenvectors
+// as the accumulated ones (both diagonalize G up to eps ||G||) -- at half the work and half the memory.
+template <int GW, bool LDS, bool ACCV>
 __global__ __launch_bounds__(jacobi_threads(GW)) void jacobi_kernel(QJacobi a) {
     if (a.skip && *a.skip) return;
     constexpr int JT = jacobi_threads(GW), JW = JT / 64;
@@ -65,7 +70,7 @@ __global__ __launch_bounds__(jacobi_threads(GW)) void jacobi_kernel(QJacobi a) {
     for (int e = t; e < n * n; e += JT) {
         const int j = e / n, i = e - j * n;
         Wc[e] = a.G[(size_t)i * n + j];
-        Vc[e] = i == j ? 1.0 : 0.0;
+        if (ACCV) Vc[e] = i == j ? 1.0 : 0.0;
     }
     const int np = (n + 1) & ~1;
     for (int i = t; i < np; i += JT) pos[0][i] = i;
@@ -118,9 +123,11 @@ __global__ __launch_bounds__(jacobi_threads(GW)) void jacobi_kernel(QJacobi a) {
                         if (e < n) {
                             xp[e] = cs * x[u] - sn * y[u];
                             yp[e] = sn * x[u] + cs * y[u];
-                            const double vx = vp[e], vy = vq[e];
-                            vp[e] = cs * vx - sn * vy;
-                            vq[e] = sn * vx + cs * vy;
+                            if (ACCV) {
+                                const double vx = vp[e], vy = vq[e];
+                                vp[e] = cs * vx - sn * vy;
+                                vq[e] = sn * vx + cs * vy;
+                            }
                         }
                     }
                     if (sl == 0) rotated = 1;
@@ -150,10 +157,11 @@ __global__ __launch_bounds__(jacobi_threads(GW)) void jacobi_kernel(QJacobi a) {
     for (int jj = w; jj < n; jj += JW) {
         const int j = ord[jj];
         const double s = sg[j];
-        const double scale = s > 0.0 ? (a.pw == 0.0 ? 1.0 : pow(s, a.pw)) : 0.0;
+        double scale = s > 0.0 ? (a.pw == 0.0 ? 1.0 : pow(s, a.pw)) : 0.0;
+        if (!ACCV && s > 0.0) scale /= s;                   // v_j = the column of the rotated G over its norm
         for (int e = lane; e < n; e += 64) {
             if (a.Ws) a.Ws[(size_t)jj * n + e] = Wc[(size_t)j * n + e];
-            if (a.Vs) a.Vs[(size_t)jj * n + e] = scale * Vc[(size_t)j * n + e];
+            if (a.Vs) a.Vs[(size_t)jj * n + e] = scale * (ACCV ? Vc[(size_t)j * n + e] : Wc[(size_t)j * n + e]);
         }
     }
     if (t == 0 && a.prev_sig && a.done) {
@@ -176,7 +184,8 @@ __global__ __launch_bounds__(jacobi_threads(GW)) void jacobi_kernel(QJacobi a) {
 
 hipError_t bwla_q_launch_jacobi(const QJacobi& j, hipStream_t st) {
     if (j.n < 1 || j.n > JMAX) return hipErrorInvalidValue;
-    const size_t lds = j.n <= JLDS ? (size_t)2 * j.n * j.n * sizeof(double) : 0;
+    const bool in_lds = j.n <= (j.sym ? JLDS_SYM : JLDS);
+    const size_t lds = in_lds ? (size_t)(j.sym ? 1 : 2) * j.n * j.n * sizeof(double) : 0;
     auto launch = [&](auto kern, int threads) {
         if (lds > 48 * 1024) {
             const hipError_t e = bwla_ensure_lds((const void*)kern, lds);
@@ -185,7 +194,13 @@ hipError_t bwla_q_launch_jacobi(const QJacobi& j, hipStream_t st) {
         hipLaunchKernelGGL(kern, dim3(1), dim3(threads), lds, st, j);
         return hipGetLastError();
     };
-    if (j.n <= 64) return launch(jacobi_kernel<16, true>, jacobi_threads(16));
-    if (j.n <= JLDS) return launch(jacobi_kernel<64, true>, jacobi_threads(64));
-    return launch(jacobi_kernel<64, false>, jacobi_threads(64));
+    if (j.sym) {
+        if (j.n <= 64) return launch(jacobi_kernel<16, true, false>, jacobi_threads(16));
+        if (j.n <= 128) return launch(jacobi_kernel<32, true, false>, jacobi_threads(32));
+        if (in_lds) return launch(jacobi_kernel<64, true, false>, jacobi_threads(64));
+        return launch(jacobi_kernel<64, false, false>, jacobi_threads(64));
+    }
+    if (j.n <= 64) return launch(jacobi_kernel<16, true, true>, jacobi_threads(16));
+    if (in_lds) return launch(jacobi_kernel<64, true, true>, jacobi_threads(64));
+    return launch(jacobi_kernel<64, false, true>, jacobi_threads(64));
 }
