@@ -9,12 +9,15 @@
 // in registers (up to four elements per lane), takes the three inner products, and applies the plane
 // rotation that makes the two columns orthogonal to them and to the matching columns of V.  Up to
 // n = 64 a group is one row of 16 lanes -- four pairs per wavefront, all pairs of a round at once,
-// the inner products summed on DPP row operations alone; larger matrices give a pair a whole
-// wavefront (row sums on DPP, the four rows added through lane reads).  Sweeps end when one passes
+// the inner products summed on DPP row operations alone; larger matrices give a pair two rows (one
+// lane exchange more) or a whole wavefront (row sums on DPP, the four rows added through lane reads).  Sweeps end when one passes
 // without a rotation (every pair orthogonal to 1e-15 relative) or after 60.  At the end the column
 // norms are the singular values, the normalized columns U, and V holds the right singular vectors.
 // Up to n = 96 both arrays (2 n^2 doubles, at most 144 KiB) live in LDS, where a round costs an LDS
 // round trip instead of an L2 one; larger matrices work in the caller's scratch (L2-resident).
+// For a symmetric positive semidefinite matrix (the Gram matrices of the subspace iteration) V is not
+// kept at all -- its columns are the normalized columns of the rotated matrix -- so that matrices up
+// to 136 wide fit LDS; there a pair takes two rows of lanes up to n = 128.
 #include "bwla_internal.h"
 #include "quantizer_internal.h"
 
