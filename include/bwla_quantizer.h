@@ -99,7 +99,9 @@ BWLA_API bwla_status_t bwla_q_svd_square(const double* d_G, int32_t nn, double* 
  * min(n, m, max(2 k, k + 16)) vectors from a fixed pseudo-random start, re-orthonormalized every
  * iteration through the eigendecomposition of its Gram matrix, and a final Rayleigh-Ritz step.  It
  * stops after `iters` iterations, or earlier once the k leading Ritz values have moved by at most
- * `tol` (relative) in one iteration: the remaining launches then return at once.  The captured
+ * `tol` (relative) in one iteration: the remaining launches then return at once.  (Blocks of more than
+ * 136 vectors, i.e. k > 68, are orthonormalized by the Newton-Schulz iteration instead, have no Ritz
+ * values along the way and always run all `iters` iterations.)  The captured
  * energy converges like (sigma_{p+1} / sigma_k)^(4 iterations); a spectrum without a gap behind
  * sigma_k needs many iterations for the singular vectors themselves.
  * d_ws: bwla_quantizer_workspace_size(n, m, 1, 1, k) bytes.

@@ -222,6 +222,50 @@ void truncate(Ctx& x, const double* Y, int iters, double tol, double* A2, double
         g.csB = p; g.klB = 1;
         gemm(x, g, skip);
     };
+    if (p > BWLA_Q_JACOBI_SYM_LDS) {
+        // Blocks too wide for the one-workgroup eigensolver to hold in LDS (ranks above 68): the block is
+        // orthonormalized by the Newton-Schulz iteration X <- X (3 I - X^T X) / 2 instead (tall GEMMs; it
+        // converges to the orthogonal polar factor of the block, a basis of the same subspace), there are
+        // no Ritz values along the way, so every one of the `iters` iterations runs, and the eigensolver is
+        // called once, for the Rayleigh-Ritz step.
+        auto ns_ortho = [&](double* src, double* dst) {                 // src is overwritten; result in dst
+            x.ck(bwla_q_launch_set_int(done, 0, x.st));
+            gram(src, m, nullptr);
+            x.ck(bwla_q_launch_gram_inv_norm(G, p, x.d(P.scal), x.st));
+            x.ck(bwla_q_launch_scale_by(src, (size_t)m * p, x.d(P.scal), x.st));
+            auto step = [&](const double* a, double* b, const int* skip) {
+                gram(a, m, skip);
+                QGemm u = qgemm_plain(a, G, b, m, p, p);                  // b = 1.5 a - 0.5 a G
+                u.C0 = a; u.alpha = -0.5; u.beta = 1.5;
+                gemm(x, u, skip);
+            };
+            step(src, dst, nullptr);
+            for (int pair = 0; pair < POLAR_NS_PAIRS; ++pair) {
+                gram(dst, m, done);
+                x.ck(bwla_q_launch_near_identity(G, p, 1.0e-13, done, x.st));
+                step(dst, src, done);
+                step(src, dst, done);
+            }
+        };
+        ns_ortho(Q, Q2);
+        double* cur = Q2; double* oth = Q;
+        for (int it = 0; it < iters; ++it) {
+            gemm(x, qgemm_plain(Y, cur, Zs, n, p, m));                   // Zs = Y Q
+            QGemm t = qgemm_plain(Y, Zs, oth, m, p, n);                  // oth = Y^T Zs
+            t.rsA = 1; t.klA = m;
+            gemm(x, t);
+            ns_ortho(oth, cur);
+        }
+        gemm(x, qgemm_plain(Y, cur, Zs, n, p, m));
+        gram(Zs, n, nullptr);
+        QJacobi j{};
+        j.G = G; j.n = p; j.pw = 0.0; j.sig = lam; j.Vs = Vs; j.work = x.d(P.jwork);
+        j.sym = true;
+        x.ck(bwla_q_launch_jacobi(j, x.st));
+        times_vs(Zs, n, k, A2, nullptr);
+        times_vs(cur, m, k, Bt2, nullptr);
+        return;
+    }
     // the start, orthonormalized
     gram(Q, m, nullptr); jac(-0.5, false, nullptr); times_vs(Q, m, p, Q2, nullptr);
     double* cur = Q2; double* oth = Q;

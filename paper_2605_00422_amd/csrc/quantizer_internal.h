@@ -64,6 +64,11 @@ hipError_t bwla_q_launch_fill_hash(double* Q, size_t count, uint32_t seed, hipSt
 hipError_t bwla_q_launch_fill_identity(double* R, int n, hipStream_t st);
 // X = C / ||C||_F (count values, one workgroup; a zero matrix stays zero)
 hipError_t bwla_q_launch_scale_inv_frob(const double* C, int count, double* X, hipStream_t st);
+// out[0] = 1 / sqrt(max_j sum_i |G_ij|) for a Gram matrix G = X^T X (nn x nn): a bound on 1 / sigma_max(X)
+// (0 for a zero matrix); one workgroup
+hipError_t bwla_q_launch_gram_inv_norm(const double* G, int nn, double* out, hipStream_t st);
+// X[e] *= s[0]
+hipError_t bwla_q_launch_scale_by(double* X, size_t count, const double* s, hipStream_t st);
 // *done = 1 once max |G - I| <= tol (G nn x nn); never cleared
 hipError_t bwla_q_launch_near_identity(const double* G, int nn, double tol, int* done, hipStream_t st);
 hipError_t bwla_q_launch_set_int(int* p, int v, hipStream_t st);
@@ -95,3 +100,5 @@ struct QJacobi {
     bool sym;
 };
 hipError_t bwla_q_launch_jacobi(const QJacobi& j, hipStream_t st);
+constexpr int BWLA_Q_JACOBI_LDS = 96;        // largest matrix whose two work arrays fit LDS
+constexpr int BWLA_Q_JACOBI_SYM_LDS = 136;   // ... whose one array does (sym)

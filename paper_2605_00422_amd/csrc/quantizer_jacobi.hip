@@ -23,7 +23,7 @@
 
 namespace {
 
-constexpr int JMAX = 256, JLDS = 96, JLDS_SYM = 136;    // largest n with both arrays / with one array in LDS
+constexpr int JMAX = 256, JLDS = BWLA_Q_JACOBI_LDS, JLDS_SYM = BWLA_Q_JACOBI_SYM_LDS;
 // threads of the workgroup: a row of 16 lanes per pair serves 32 pairs (n <= 64) with 512 threads
 constexpr int jacobi_threads(int gw) { return gw == 16 ? 512 : 1024; }
 

@@ -177,6 +177,27 @@ __global__ __launch_bounds__(RT) void scale_inv_frob_kernel(const double* C, int
     const double inv = tot > 0.0 ? 1.0 / sqrt(tot) : 0.0;
     for (int e = threadIdx.x; e < count; e += RT) X[e] = C[e] * inv;
 }
+// out[0] = 1 / sqrt(largest absolute column sum of G): for G = X^T X that sum bounds sigma_max(X)^2
+__global__ __launch_bounds__(RT) void gram_inv_norm_kernel(const double* G, int nn, double* out) {
+    __shared__ double sh[RT];
+    double worst = 0.0;
+    for (int j = threadIdx.x; j < nn; j += RT) {
+        double s = 0.0;
+        for (int i = 0; i < nn; ++i) s += fabs(G[(size_t)i * nn + j]);
+        worst = s > worst ? s : worst;
+    }
+    sh[threadIdx.x] = worst;
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        double w = 0.0;
+        for (int i = 0; i < RT; ++i) w = sh[i] > w ? sh[i] : w;
+        out[0] = w > 0.0 ? 1.0 / sqrt(w) : 0.0;
+    }
+}
+__global__ void scale_by_kernel(double* X, size_t count, const double* s) {
+    const double f = s[0];
+    for (size_t e = (size_t)blockIdx.x * RT + threadIdx.x; e < count; e += (size_t)gridDim.x * RT) X[e] *= f;
+}
 // *done = 1 once max |G - I| <= tol (G nn x nn, one workgroup); never cleared here
 __global__ __launch_bounds__(RT) void near_identity_kernel(const double* G, int nn, double tol, int* done) {
     __shared__ double sh[4];
@@ -290,6 +311,14 @@ hipError_t bwla_q_launch_fill_identity(double* R, int n, hipStream_t st) {
 }
 hipError_t bwla_q_launch_scale_inv_frob(const double* C, int count, double* X, hipStream_t st) {
     hipLaunchKernelGGL(scale_inv_frob_kernel, dim3(1), dim3(RT), 0, st, C, count, X);
+    return hipGetLastError();
+}
+hipError_t bwla_q_launch_gram_inv_norm(const double* G, int nn, double* out, hipStream_t st) {
+    hipLaunchKernelGGL(gram_inv_norm_kernel, dim3(1), dim3(RT), 0, st, G, nn, out);
+    return hipGetLastError();
+}
+hipError_t bwla_q_launch_scale_by(double* X, size_t count, const double* s, hipStream_t st) {
+    hipLaunchKernelGGL(scale_by_kernel, dim3(flat_blocks(count)), dim3(RT), 0, st, X, count, s);
     return hipGetLastError();
 }
 hipError_t bwla_q_launch_near_identity(const double* G, int nn, double tol, int* done, hipStream_t st) {

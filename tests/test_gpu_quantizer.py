@@ -154,10 +154,11 @@ def test_procrustes_updates(n, n1, n2, k):
         assert after <= before * (1 + 1e-12)
 
 
-# (the last four: blocks of 80, 128, 132 and 160 vectors -- the Gram matrix's eigenproblem in a row pair of
-# lanes per column pair, in a wavefront per pair with the matrix in LDS, and in scratch)
+# (the last five: blocks of 80, 128, 132, 160 and 256 vectors -- the Gram matrix's eigenproblem in a row pair of
+# lanes per column pair and in a wavefront per pair with the matrix in LDS; above 136 vectors the block is
+# orthonormalized by the Newton-Schulz iteration and the eigenproblem is solved once, in scratch)
 @pytest.mark.parametrize("n,m,k", [(40, 30, 3), (300, 128, 8), (96, 512, 16), (513, 200, 5), (300, 256, 40),
-                                   (400, 300, 64), (300, 280, 66), (400, 320, 80)])
+                                   (400, 300, 64), (300, 280, 66), (400, 320, 80), (500, 300, 128)])
 def test_truncate_rank_with_a_gap(n, m, k):
     """Planted rank-k part above a noise floor: the truncation itself is determined, and matches."""
     qb = _qb()
