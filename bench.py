@@ -75,15 +75,21 @@ def gemm_ops(cfg) -> int:
 
 
 _flush_buf = None
+_flush_sink = None
 
 
 def flush_caches(torch):
-    """One read-modify-write pass over 768 MB on the current stream: afterwards neither the L2s
-    nor the 256 MB last-level cache hold anything of the layers."""
-    global _flush_buf
+    """One streaming read of 768 MB on the current stream: afterwards neither the L2s nor the 256 MB
+    last-level cache hold anything of the layers.  (A read, not a read-modify-write: the dirty lines a
+    writing pass leaves behind drain to HBM during the next few hundred microseconds and slowed the
+    first forty or so layer launches behind it by 1 us each -- which a timed region of 20 steps carried
+    in full and one of 400 steps hardly at all.)"""
+    global _flush_buf, _flush_sink
+    from paper_2605_00422_amd import binding as B
     if _flush_buf is None:
         _flush_buf = torch.zeros(FLUSH_BYTES // 4, dtype=torch.int32, device="cuda:0")
-    _flush_buf.add_(1)
+        _flush_sink = torch.zeros(1 << 16, dtype=torch.int32, device="cuda:0")
+    B.probe_hbm_read(_flush_buf, _flush_sink)
 
 
 class Workload:
@@ -171,21 +177,31 @@ class Workload:
     def time_graph(self, fn, steps, warmup, replays=5):
         """The same K calls captured once into a HIP graph and replayed: per-call milliseconds
         without host launch overhead (how a decode loop would be deployed).  `replays` timed
-        replays, each behind a cache flush; returns (median, minimum)."""
+        replays, each behind a cache flush; returns (median, minimum).  The span of the K calls is
+        read off the GPU's constant 100 MHz counter by two one-wavefront launches captured in front
+        of and behind them (the gap to the first call and from the last count as the gaps between
+        calls do); events around the replay measure the same span plus the replay's own start on the
+        GPU -- some 25 us, which K = 400 calls do not notice and K = 20 would carry as 1 us each; that
+        figure is kept as last_graph_events_ms and reported beside the other."""
         torch = self.torch
         for i in range(max(warmup, 3)):
             fn(i)
         torch.cuda.synchronize()
+        B = self.B
         g = torch.cuda.CUDAGraph()
         s = torch.cuda.Stream()
+        t0 = torch.zeros(1, dtype=torch.int64, device="cuda:0")
+        t1 = torch.zeros(1, dtype=torch.int64, device="cuda:0")
         with torch.cuda.stream(s):
             with torch.cuda.graph(g, stream=s):
+                B.probe_clock(t0)
                 for i in range(steps):
                     fn(warmup + i)
+                B.probe_clock(t1)
         torch.cuda.synchronize()
         g.replay()
         torch.cuda.synchronize()
-        ms = []
+        ms, ms_ev = [], []
         for _ in range(replays):
             flush_caches(torch)
             e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
@@ -193,8 +209,11 @@ class Workload:
             g.replay()
             e1.record()
             torch.cuda.synchronize()
-            ms.append(e0.elapsed_time(e1) / steps)
+            ms_ev.append(e0.elapsed_time(e1) / steps)
+            ms.append((t1.item() - t0.item()) * 1e-5 / steps)          # ticks of 10 ns -> ms
         ms.sort()
+        ms_ev.sort()
+        self.last_graph_events_ms = ms_ev[len(ms_ev) // 2]
         return ms[len(ms) // 2], ms[0]
 
 
@@ -214,9 +233,11 @@ def measure(cfg, steps, warmup, use_graph=True, centered=False, act_bits=6, asym
     if use_graph:
         try:
             gs, gs_min = w.time_graph(w.step, steps, warmup)
+            gs_events = w.last_graph_events_ms
             gf, _ = w.time_graph(w.only_forward, steps, warmup)
             gr, _ = w.time_graph(w.only_rotate, steps, warmup)
             out["graph"] = {"us_per_layer": gs * 1e3, "us_per_layer_min": gs_min * 1e3,
+                            "us_per_layer_events": gs_events * 1e3,
                             "us_linear_forward": gf * 1e3, "us_rotate_quant": gr * 1e3}
             if cfg.name.startswith("cfg1_7b_gateup") and cfg.M <= 16:
                 out["graph"]["us_linear_forward_gated"] = w.time_graph(w.only_forward_gated, steps, warmup)[0] * 1e3

@@ -356,11 +356,16 @@ BWLA_API bwla_status_t bwla_linear_forward_a4(const bwla_layer_t* layer, const u
  *                         index.  Ticks * 10 / iters is the latency of one dependent load in nanoseconds: of
  *                         a miss everywhere when the walk never comes back to a line, of the L2 when the
  *                         buffer was read just before and fits it.
+ *   bwla_probe_clock      one launch of one wavefront that writes the GPU's constant 100 MHz counter (ticks
+ *                         of 10 ns) to d_out (device, 8 bytes, 8-byte aligned).  Two of them around a
+ *                         sequence of launches -- also inside a captured graph -- give the time the GPU
+ *                         spent on the sequence without the host's part of getting it started.
  * All enqueue on `stream`, own no memory, and return the usual codes.
  */
 BWLA_API bwla_status_t bwla_probe_hbm_read(const void* d_src, size_t bytes, void* d_sink, size_t sink_bytes, void* stream);
 BWLA_API bwla_status_t bwla_probe_mfma_int8(int iters, void* d_sink, size_t sink_bytes, int64_t* ops_out, void* stream);
 BWLA_API bwla_status_t bwla_probe_empty_launch(void* stream);
+BWLA_API bwla_status_t bwla_probe_clock(void* d_out, void* stream);
 BWLA_API bwla_status_t bwla_probe_load_latency(const void* d_buf, size_t bytes, size_t stride_bytes, int iters,
                                                void* d_out, void* stream);
 

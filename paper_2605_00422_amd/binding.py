@@ -21,7 +21,7 @@ EXPORTS = ["bwla_status_string", "bwla_version", "bwla_kron_factor", "bwla_packe
            "bwla_packed_size_mode", "bwla_pack_weights_mode", "bwla_swiglu_workspace_size",
            "bwla_linear_forward_swiglu", "bwla_decode_forward_static", "bwla_probe_hbm_read",
            "bwla_probe_mfma_int8", "bwla_decode_forward_launches", "bwla_decode_forward_bits", "bwla_pack_codes_a4",
-           "bwla_linear_forward_a4", "bwla_probe_empty_launch", "bwla_probe_load_latency"]
+           "bwla_linear_forward_a4", "bwla_probe_empty_launch", "bwla_probe_load_latency", "bwla_probe_clock"]
 
 
 class BwlaLayer(Structure):
@@ -84,6 +84,7 @@ def load() -> ctypes.CDLL:
     lib.bwla_probe_hbm_read.argtypes = [c_void_p, c_size_t, c_void_p, c_size_t, c_void_p]
     lib.bwla_probe_mfma_int8.argtypes = [c_int, c_void_p, c_size_t, POINTER(ctypes.c_int64), c_void_p]
     lib.bwla_probe_empty_launch.argtypes = [c_void_p]
+    lib.bwla_probe_clock.argtypes = [c_void_p, c_void_p]
     lib.bwla_probe_load_latency.argtypes = [c_void_p, c_size_t, c_size_t, c_int, c_void_p, c_void_p]
     lib.bwla_swiglu_workspace_size.argtypes = [POINTER(BwlaLayer), c_int64, POINTER(c_size_t)]
     lib.bwla_linear_forward_swiglu.argtypes = [POINTER(BwlaLayer), c_void_p, c_void_p, c_void_p, c_void_p, c_int64,
@@ -271,6 +272,11 @@ def probe_mfma_int8(iters: int, sink) -> int:
 
 def probe_empty_launch() -> None:
     _check(load().bwla_probe_empty_launch(_stream()), "bwla_probe_empty_launch")
+
+
+def probe_clock(out) -> None:
+    """out: int64 CUDA tensor of one element; gets the GPU's 100 MHz counter when the launch runs."""
+    _check(load().bwla_probe_clock(_ptr(out), _stream()), "bwla_probe_clock")
 
 
 def probe_load_latency(buf, stride_bytes: int, iters: int, out) -> None:

@@ -68,9 +68,21 @@ __global__ void probe_chase_kernel(const uint32_t* __restrict__ buf, uint64_t n,
     out[1] = idx;
 }
 
+// the constant 100 MHz counter at the moment the kernel runs
+__global__ void probe_clock_kernel(uint64_t* __restrict__ out) {
+    if (threadIdx.x == 0) out[0] = wall_clock64();
+}
+
 }  // namespace
 
 extern "C" {
+
+BWLA_API bwla_status_t bwla_probe_clock(void* d_out, void* stream) {
+    if (!d_out) return BWLA_ERR_NULL;
+    if ((uintptr_t)d_out & 7) return BWLA_ERR_ALIGN;
+    hipLaunchKernelGGL(probe_clock_kernel, dim3(1), dim3(64), 0, (hipStream_t)stream, (uint64_t*)d_out);
+    return hipGetLastError() == hipSuccess ? BWLA_OK : BWLA_ERR_HIP;
+}
 
 BWLA_API bwla_status_t bwla_probe_empty_launch(void* stream) {
     hipLaunchKernelGGL(probe_empty_kernel, dim3(bwla_device_cus()), dim3(512), 0, (hipStream_t)stream);

@@ -67,6 +67,45 @@ def test_latency_probes_run_and_refuse():
         B.probe_load_latency(buf, 128, 0, out)
 
 
+def test_clock_probe_brackets_work_on_the_stream():
+    """Two clock launches around a known amount of GPU work: the counter advances, at 100 MHz, by about
+    what events measure for the same span; also from a captured graph, on every replay."""
+    from paper_2605_00422_amd import binding as B
+    t0 = torch.zeros(1, dtype=torch.int64, device="cuda:0")
+    t1 = torch.zeros(1, dtype=torch.int64, device="cuda:0")
+    big = torch.zeros(64 << 20, dtype=torch.int32, device="cuda:0")
+
+    def span():
+        B.probe_clock(t0)
+        big.add_(1)                                  # 512 MB of traffic: some tens of microseconds at least
+        B.probe_clock(t1)
+
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    span()
+    torch.cuda.synchronize()
+    e0.record()
+    span()
+    e1.record()
+    torch.cuda.synchronize()
+    us_clock = (t1.item() - t0.item()) / 100.0
+    us_events = e0.elapsed_time(e1) * 1e3
+    assert 20.0 < us_clock <= us_events * 1.05 + 5.0, (us_clock, us_events)
+    assert us_clock > 0.5 * us_events - 20.0, (us_clock, us_events)
+    g = torch.cuda.CUDAGraph()
+    s = torch.cuda.Stream()
+    with torch.cuda.stream(s):
+        with torch.cuda.graph(g, stream=s):
+            span()
+    seen = []
+    for _ in range(3):
+        g.replay()
+        torch.cuda.synchronize()
+        seen.append((t0.item(), t1.item()))
+    assert all(b > a for a, b in seen) and seen[0][1] < seen[1][0] < seen[1][1] < seen[2][0]
+    with pytest.raises(B.BwlaError):
+        B.probe_clock(None)
+
+
 def test_launch_count_query():
     from paper_2605_00422_amd import binding as B
     from parity_util import pack_on_gpu
