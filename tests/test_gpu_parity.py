@@ -425,6 +425,8 @@ def test_repeated_calls_are_deterministic():
 @pytest.mark.parametrize("name,M,K,n1,n2,N,r,one_call", [
     ("decode", 1, 4096, 64, 64, 1024, 32, False),          # two launches per layer (the bench's default workload shape)
     ("single_launch", 1, 4096, 64, 64, 1024, 0, True),     # bwla_decode_forward's single-launch kernel
+    ("single_launch_psp", 1, 4096, 64, 64, 1024, 32, True),     # ... with the shared projection: epoch and tagged sums move on with every replay
+    ("single_launch_asym", 1, 4096, 64, 64, 1024, 32, True),    # ... on a layer with asymmetric codes and the row shift
     ("batch16", 16, 5120, 64, 80, 640, 64, False),         # projection with ten slices and its arrival counters
     ("split_rotation", 2, 20000, 200, 100, 48, 4, False),  # three launches; integer atomics on qsum
     ("prefill", 300, 1152, 36, 32, 200, 20, False),        # separate projection kernel, streaming GEMM
@@ -439,7 +441,14 @@ def test_hip_graph_replays_match_eager(name, M, K, n1, n2, N, r, one_call):
     from paper_2605_00422_amd import binding as B
     cfg = syn.LayerConfig(f"graph_{name}", M, K, n1, n2, N, r, "bf16", max(1, K // 100), 20.0, seed=16)
     d = syn.make_layer(cfg)
-    layer = pack_on_gpu(d)
+    if name.endswith("asym"):
+        from parity_util import to_dev
+        layer = B.pack_weights(to_dev(syn.shifted_weights(d)), to_dev(d.R1), to_dev(d.R2), to_dev(d.U), to_dev(d.V), n1, n2,
+                               centered=True, asym=True)
+    else:
+        layer = pack_on_gpu(d)
+    if name.startswith("single_launch"):
+        assert B.decode_forward_launches(layer, M) == 1
     X1 = x_on_gpu(d)
     X2 = (X1.float() * 0.75 + torch.roll(X1.float(), 3, dims=1)).to(X1.dtype)
 
@@ -456,7 +465,7 @@ def test_hip_graph_replays_match_eager(name, M, K, n1, n2, N, r, one_call):
         Y = torch.empty((M, N), dtype=torch.float32, device=DEV)
         forward(X, act, Y)
         torch.cuda.synchronize()
-        eager[key] = (Y.clone(), act.q.clone(), act.scale.clone(), act.qsum.clone())
+        eager[key] = (Y.clone(), act.q.clone(), act.scale.clone(), act.qsum.clone()) + ((act.T.clone(),) if r > 0 else ())
 
     Xg = X1.clone()
     actg = B.Activations(layer, M)
@@ -475,5 +484,5 @@ def test_hip_graph_replays_match_eager(name, M, K, n1, n2, N, r, one_call):
         torch.cuda.synchronize()
         g.replay()
         torch.cuda.synchronize()
-        got = (Yg, actg.q, actg.scale, actg.qsum)
+        got = (Yg, actg.q, actg.scale, actg.qsum) + ((actg.T,) if r > 0 else ())
         assert all(torch.equal(a, b) for a, b in zip(got, eager[key])), f"replay {rep} ({key}) differs from eager"
